@@ -1,0 +1,22 @@
+"""fp64 CPU oracle for the Rodimus DDTS recurrence -- TEST INFRASTRUCTURE ONLY.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.  The product path (the HIP library and its
+Python binding) never does, and shares no code with it.
+
+Contents
+--------
+``rodimus_oracle.c``  the sequential recurrence in plain C, IEEE double
+                      (paper Sec. 3.1.3, state recurrence of the Rodimus block).
+``sequential.py``     ctypes loader for it: ``scan`` and ``step``.
+``chunkwise.py``      the same result computed by the chunkwise form of the
+                      appendix "Chunkwise Parallel Representation of the Rodimus
+                      Block", in numpy fp64 -- used to check the chunk algebra
+                      and the chunk-size invariance of the result.
+``build.py``          compiles the C file with gcc into ``librodimus_oracle.so``.
+
+Pins (tests/test_oracle_pins.py): reduction to plain causal linear attention,
+alpha = 0, the unrolled O(T^2) weighted sum, geometric-series closed form,
+a hand-worked rational example, split-sequence and chunk-size invariance.
+"""
+from .sequential import scan, step, threads  # noqa: F401

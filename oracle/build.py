@@ -1,0 +1,24 @@
+"""Compile the C oracle into ``oracle/librodimus_oracle.so`` (gcc, no fast-math).
+
+Building the checker is not using it: the product build may call this so the
+tests find the library, but nothing in the product path loads the result.
+"""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "rodimus_oracle.c")
+LIB = os.path.join(HERE, "librodimus_oracle.so")
+
+
+def build(force: bool = True) -> str:
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+        return LIB
+    cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fno-fast-math", "-ffp-contract=off",
+           "-Wall", "-Wextra", "-shared", "-fPIC", SRC, "-o", LIB, "-lm"]
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build())

@@ -1,0 +1,148 @@
+/*
+ * Rodimus DDTS recurrence -- fp64 CPU oracle.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct statement
+ * of what the GPU library must compute.  Nothing in the product path may call,
+ * link or import it; only tests/, the smoke check and the benchmark's
+ * "cpu_baseline" leg do.  It shares no code with the HIP kernels.
+ *
+ * What it computes (paper, Sec. 3.1.3 "The Overall Rodimus Block", the state
+ * recurrence of the block, with the general gated transition of Sec. 3.1.1 in
+ * its second, factored form and the value-side transition gate fixed to one):
+ *
+ *     S_t = diag(alpha_t) S_{t-1} + (k_t)^T (beta_t .* v_t),   o_t = q_t S_t
+ *
+ * per (batch b, head h) independently, t = 1..T, S_0 given (or zero), with
+ * alpha_t = exp(log_alpha_t) a 1 x dk row acting on the rows of the dk x dv
+ * state, beta_t a 1 x dv input gate on the value, and the key-side input gate
+ * (g^tau in the paper) already folded into k_t by the caller.  The output uses
+ * the state AFTER the update, exactly as the recurrence is printed.  The
+ * feed-through term of the block output (d_t .* x'_t) is outside this function.
+ *
+ * All arithmetic is IEEE double.  Inputs arrive as float: every bf16 and fp32
+ * value the GPU receives is exactly representable in float, so the oracle sees
+ * the same numbers the GPU sees and input rounding is not counted as error.
+ *
+ * Layouts (innermost index contiguous):
+ *     q, k, log_alpha : [B, T, H, dk]      v, beta, o : [B, T, H, dv]
+ *     S0, S_T         : [B, H, dk, dv]
+ * The decode step uses the same layouts with T dropped ([N, H, ...]).
+ *
+ * There is no blocking, fusion or reordering: the loops below are the
+ * recurrence as written.  OpenMP only distributes the independent (b, h)
+ * recurrences over host threads.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdlib.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int rodimus_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* One time step of one (b, h) recurrence, in place on S (dk x dv, row-major). */
+static void ddts_update(double *S, const float *q, const float *k, const float *v,
+                        const float *log_alpha, const float *beta, double *o,
+                        int dk, int dv, double *gated_v)
+{
+    /* gated value: beta_t .* v_t   (beta == NULL means the all-ones gate) */
+    for (int j = 0; j < dv; ++j)
+        gated_v[j] = (beta ? (double)beta[j] : 1.0) * (double)v[j];
+
+    /* S_t = diag(alpha_t) S_{t-1} + k_t^T (beta_t .* v_t) */
+    for (int r = 0; r < dk; ++r) {
+        const double alpha = exp((double)log_alpha[r]);   /* exp(-inf) == 0 */
+        const double kr = (double)k[r];
+        double *Srow = S + (size_t)r * dv;
+        for (int j = 0; j < dv; ++j)
+            Srow[j] = alpha * Srow[j] + kr * gated_v[j];
+    }
+
+    /* o_t = q_t S_t  (the updated state) */
+    for (int j = 0; j < dv; ++j) {
+        double acc = 0.0;
+        for (int r = 0; r < dk; ++r)
+            acc += (double)q[r] * S[(size_t)r * dv + j];
+        o[j] = acc;
+    }
+}
+
+/*
+ * Sequential scan over T tokens.
+ *   beta may be NULL (all ones); S0 may be NULL (zero state); S_T may be NULL.
+ * Returns 0 on success, 1 on bad arguments, 2 on allocation failure.
+ */
+int rodimus_oracle_scan(const float *q, const float *k, const float *v,
+                        const float *log_alpha, const float *beta,
+                        const double *S0, double *o, double *S_T,
+                        int B, int T, int H, int dk, int dv)
+{
+    if (!q || !k || !v || !log_alpha || !o) return 1;
+    if (B < 0 || T < 0 || H < 0 || dk <= 0 || dv <= 0) return 1;
+    int failed = 0;
+
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < H; ++h) {
+            double *S = (double *)malloc(sizeof(double) * (size_t)dk * dv);
+            double *gv = (double *)malloc(sizeof(double) * (size_t)dv);
+            if (!S || !gv) {
+                free(S); free(gv);
+#pragma omp atomic write
+                failed = 1;
+                continue;
+            }
+            const size_t state_off = ((size_t)b * H + h) * (size_t)dk * dv;
+            for (size_t e = 0; e < (size_t)dk * dv; ++e)
+                S[e] = S0 ? S0[state_off + e] : 0.0;
+
+            for (int t = 0; t < T; ++t) {
+                const size_t row = ((size_t)b * T + t) * H + h;
+                ddts_update(S, q + row * dk, k + row * dk, v + row * dv,
+                            log_alpha + row * dk, beta ? beta + row * dv : NULL,
+                            o + row * dv, dk, dv, gv);
+            }
+            if (S_T)
+                for (size_t e = 0; e < (size_t)dk * dv; ++e)
+                    S_T[state_off + e] = S[e];
+            free(S); free(gv);
+        }
+    }
+    return failed ? 2 : 0;
+}
+
+/*
+ * One recurrent decode step for N independent sequences: S is updated in place
+ * to S' and o = q S'.   Layouts [N, H, dk], [N, H, dv], S [N, H, dk, dv].
+ */
+int rodimus_oracle_step(const float *q, const float *k, const float *v,
+                        const float *log_alpha, const float *beta,
+                        double *S, double *o, int N, int H, int dk, int dv)
+{
+    if (!q || !k || !v || !log_alpha || !S || !o) return 1;
+    if (N < 0 || H < 0 || dk <= 0 || dv <= 0) return 1;
+    int failed = 0;
+
+#pragma omp parallel for schedule(static)
+    for (long s = 0; s < (long)N * H; ++s) {
+        double *gv = (double *)malloc(sizeof(double) * (size_t)dv);
+        if (!gv) {
+#pragma omp atomic write
+            failed = 1;
+            continue;
+        }
+        ddts_update(S + (size_t)s * dk * dv, q + (size_t)s * dk, k + (size_t)s * dk,
+                    v + (size_t)s * dv, log_alpha + (size_t)s * dk,
+                    beta ? beta + (size_t)s * dv : NULL, o + (size_t)s * dv, dk, dv, gv);
+        free(gv);
+    }
+    return failed ? 2 : 0;
+}

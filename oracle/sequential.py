@@ -1,0 +1,112 @@
+"""ctypes front-end of the C oracle (``rodimus_oracle.c``) -- test infrastructure only.
+
+``scan``  : S_t = diag(exp(log_alpha_t)) S_{t-1} + k_t^T (beta_t .* v_t), o_t = q_t S_t
+            for t = 1..T (paper Sec. 3.1.3, recurrence of the Rodimus block).
+``step``  : one iteration of that recurrence for N independent sequences.
+
+Inputs may be numpy arrays or torch CPU tensors of any float dtype (bf16 included);
+they are widened to float32 bit-exactly, the C code widens to double.  Outputs are
+numpy float64.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        lib = ctypes.CDLL(path)
+        f32p = ctypes.POINTER(ctypes.c_float)
+        f64p = ctypes.POINTER(ctypes.c_double)
+        lib.rodimus_oracle_scan.argtypes = [f32p, f32p, f32p, f32p, f32p, f64p, f64p, f64p] + [ctypes.c_int] * 5
+        lib.rodimus_oracle_scan.restype = ctypes.c_int
+        lib.rodimus_oracle_step.argtypes = [f32p, f32p, f32p, f32p, f32p, f64p, f64p] + [ctypes.c_int] * 4
+        lib.rodimus_oracle_step.restype = ctypes.c_int
+        lib.rodimus_oracle_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _f32(x):
+    """Exact float32 view of a bf16/fp16/fp32 array or tensor (None passes through)."""
+    if x is None:
+        return None
+    if hasattr(x, "detach"):                      # torch tensor, possibly bf16
+        x = x.detach().cpu().float().numpy()
+    x = np.asarray(x)
+    if x.dtype == np.float64:
+        y = x.astype(np.float32)
+        if not np.array_equal(y.astype(np.float64), x, equal_nan=True):
+            raise ValueError("oracle inputs must be exactly representable in float32")
+        x = y
+    return np.ascontiguousarray(x, dtype=np.float32)
+
+
+def _f64(x):
+    if x is None:
+        return None
+    if hasattr(x, "detach"):
+        x = x.detach().cpu().double().numpy()
+    return np.ascontiguousarray(np.asarray(x), dtype=np.float64)
+
+
+def _ptr(a, ctype):
+    return a.ctypes.data_as(ctypes.POINTER(ctype)) if a is not None else None
+
+
+def threads() -> int:
+    """Number of host threads the C oracle will use (OpenMP)."""
+    return int(_load().rodimus_oracle_threads())
+
+
+def scan(q, k, v, log_alpha, beta=None, S0=None, want_state=True):
+    """Sequential oracle.  q,k,log_alpha [B,T,H,dk]; v,beta [B,T,H,dv]; S0 [B,H,dk,dv].
+
+    Returns (o [B,T,H,dv] float64, S_T [B,H,dk,dv] float64 or None).
+    """
+    lib = _load()
+    q, k, v, la, beta = _f32(q), _f32(k), _f32(v), _f32(log_alpha), _f32(beta)
+    S0 = _f64(S0)
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    assert k.shape == (B, T, H, dk) and la.shape == (B, T, H, dk), (k.shape, la.shape)
+    assert v.shape == (B, T, H, dv), v.shape
+    assert beta is None or beta.shape == (B, T, H, dv), beta.shape
+    assert S0 is None or S0.shape == (B, H, dk, dv), S0.shape
+    o = np.empty((B, T, H, dv), dtype=np.float64)
+    S_T = np.empty((B, H, dk, dv), dtype=np.float64) if want_state else None
+    rc = lib.rodimus_oracle_scan(_ptr(q, ctypes.c_float), _ptr(k, ctypes.c_float), _ptr(v, ctypes.c_float),
+                                 _ptr(la, ctypes.c_float), _ptr(beta, ctypes.c_float), _ptr(S0, ctypes.c_double),
+                                 _ptr(o, ctypes.c_double), _ptr(S_T, ctypes.c_double), B, T, H, dk, dv)
+    if rc != 0:
+        raise RuntimeError(f"rodimus_oracle_scan failed with code {rc}")
+    return o, S_T
+
+
+def step(q, k, v, log_alpha, beta, S):
+    """One decode step.  q,k,log_alpha [N,H,dk]; v,beta [N,H,dv]; S [N,H,dk,dv] float64.
+
+    Returns (o [N,H,dv] float64, S' float64).  ``S`` itself is not modified.
+    """
+    lib = _load()
+    q, k, v, la, beta = _f32(q), _f32(k), _f32(v), _f32(log_alpha), _f32(beta)
+    S = _f64(S).copy()
+    N, H, dk = q.shape
+    dv = v.shape[-1]
+    assert k.shape == (N, H, dk) and la.shape == (N, H, dk)
+    assert v.shape == (N, H, dv) and (beta is None or beta.shape == (N, H, dv))
+    assert S.shape == (N, H, dk, dv), S.shape
+    o = np.empty((N, H, dv), dtype=np.float64)
+    rc = lib.rodimus_oracle_step(_ptr(q, ctypes.c_float), _ptr(k, ctypes.c_float), _ptr(v, ctypes.c_float),
+                                 _ptr(la, ctypes.c_float), _ptr(beta, ctypes.c_float),
+                                 _ptr(S, ctypes.c_double), _ptr(o, ctypes.c_double), N, H, dk, dv)
+    if rc != 0:
+        raise RuntimeError(f"rodimus_oracle_step failed with code {rc}")
+    return o, S
