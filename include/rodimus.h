@@ -1,0 +1,126 @@
+/*
+ * rodimus.h -- C ABI of the MI355X (gfx950) library for the Rodimus DDTS
+ * gated linear-attention recurrence.
+ *
+ * The operation (paper Sec. 3.1.3, state recurrence of the Rodimus block, with the
+ * general gated transition of Sec. 3.1.1 in its factored form and the value-side
+ * transition gate fixed to one), for every (batch, head) pair independently:
+ *
+ *     S_t = diag(exp(log_alpha_t)) S_{t-1} + k_t^T (beta_t .* v_t),    o_t = q_t S_t
+ *
+ * S is dk x dv.  log_alpha_t (1 x dk) is the log of the decay gate
+ * alpha_t = exp(-g_t .* tau_t) of Sec. 3.1.2, i.e. log_alpha = -g .* tau <= 0.
+ * beta_t (1 x dv) is the input gate on the value.  The key-side input gate
+ * g_t^tau_t, the normalisation of k and the 1/sqrt(dk) on q are folded into k and
+ * q by the caller (second form of the transition in Sec. 3.1.1); the library
+ * applies no scaling.  The output uses the state AFTER the update.  The block's
+ * feed-through term is added by the caller.
+ *
+ * General conventions
+ *   - Every pointer is a DEVICE pointer owned by the caller.  The library never
+ *     allocates or frees device memory, never synchronises and keeps no global
+ *     state; all work is enqueued on `stream` (a hipStream_t, NULL = default).
+ *   - Innermost index contiguous, no strides:
+ *         q, k, log_alpha : [B, T, H, dk]     v, beta, o : [B, T, H, dv]
+ *         S0, S_T, S      : [B, H, dk, dv]    (decode: B -> N, T dropped)
+ *   - q, k, v, o have element type `io_dtype` (RODIMUS_F32 or RODIMUS_BF16,
+ *     bf16 = upper 16 bits of an IEEE float, round-to-nearest-even on output).
+ *     log_alpha, beta and every state are fp32; all accumulation is fp32.
+ *   - Base pointers must be 16-byte aligned.
+ *   - Every function validates its arguments on the host BEFORE any launch and
+ *     returns a rodimus_status; nothing is written on error.  No exceptions,
+ *     no aborts.
+ *   - log_alpha = -inf (alpha = 0) is legal.  log_alpha > 0 is not rejected but
+ *     products of gates may then overflow.
+ */
+#ifndef RODIMUS_H
+#define RODIMUS_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RODIMUS_OK = 0,
+    RODIMUS_ERR_NULL = 1,        /* a required pointer is NULL                           */
+    RODIMUS_ERR_SHAPE = 2,       /* a size is negative/zero or out of the supported range */
+    RODIMUS_ERR_DTYPE = 3,       /* io_dtype is not a rodimus_dtype                       */
+    RODIMUS_ERR_ALIGN = 4,       /* a base pointer is not 16-byte aligned                 */
+    RODIMUS_ERR_WORKSPACE = 5,   /* workspace missing or smaller than required            */
+    RODIMUS_ERR_LAUNCH = 6,      /* the HIP runtime refused the launch                    */
+    RODIMUS_ERR_ALIAS = 7        /* an output overlaps an input it must not overlap       */
+} rodimus_status;
+
+typedef enum { RODIMUS_F32 = 0, RODIMUS_BF16 = 1 } rodimus_dtype;
+
+/* Which kernel family a chunk-scan call of this shape runs (for tests and reports). */
+typedef enum {
+    RODIMUS_PATH_NONE = 0,       /* shape not supported                                  */
+    RODIMUS_PATH_GENERIC = 1,    /* fp32 ALU chunkwise kernel, any supported shape        */
+    RODIMUS_PATH_MFMA = 2        /* bf16 MFMA chunkwise kernel (dk = 64, chunk = 64, ...) */
+} rodimus_path;
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *rodimus_status_string(int status);
+
+/*
+ * Chunkwise-parallel forward scan over T tokens (prefill / training forward).
+ * Appendix "Chunkwise Parallel Representation of the Rodimus Block": inside each chunk the
+ * masked, decayed scores (Q .* A)(K / A)^T and their product with beta .* V give the
+ * intra-chunk output; the state entering the chunk gives the inter-chunk output; the
+ * state is carried from chunk to chunk in fp32.  The result does not depend on `chunk`
+ * beyond rounding.
+ *
+ *   q, k        [B,T,H,dk] io_dtype      in
+ *   v           [B,T,H,dv] io_dtype      in
+ *   log_alpha   [B,T,H,dk] fp32          in
+ *   beta        [B,T,H,dv] fp32          in, or NULL = all ones
+ *   S0          [B,H,dk,dv] fp32         in, or NULL = zero state
+ *   o           [B,T,H,dv] io_dtype      out; must not overlap any input
+ *   S_T         [B,H,dk,dv] fp32         out, or NULL if not wanted; MAY be the same buffer as S0
+ *   chunk       1..64.  T need not be a multiple of it (the last chunk is shorter).
+ *   workspace   device scratch of at least rodimus_chunk_scan_workspace_bytes(...) bytes,
+ *               16-byte aligned; may be NULL when that size is 0.  Contents are undefined
+ *               afterwards; concurrent calls need distinct workspaces.
+ *
+ * Supported shapes: 1 <= dk <= 128, dv >= 1, dv % 4 == 0, chunk * dk <= 4096 (generic path);
+ * the MFMA path is taken for io_dtype = BF16, dk = 64, chunk = 64, dv % 64 == 0.
+ * B, T or H equal to 0 is a successful no-op.
+ */
+int rodimus_chunk_scan_fwd(const void *q, const void *k, const void *v,
+                           const float *log_alpha, const float *beta, const float *S0,
+                           void *o, float *S_T,
+                           int B, int T, int H, int dk, int dv, int chunk, int io_dtype,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/* Scratch bytes the call above needs for this shape (0 if none, or if the shape is invalid). */
+size_t rodimus_chunk_scan_workspace_bytes(int B, int T, int H, int dk, int dv, int chunk, int io_dtype);
+
+/* Kernel family (rodimus_path) the call above would run for this shape. */
+int rodimus_chunk_scan_path(int B, int T, int H, int dk, int dv, int chunk, int io_dtype);
+
+/*
+ * One recurrent decode step for N independent sequences (paper Sec. 3.1.3: at inference the
+ * block keeps only the fixed-size state, O(1) work per token):
+ *     S' = diag(exp(log_alpha)) S + k^T (beta .* v),   o = q S'
+ *
+ *   q, k        [N,H,dk] io_dtype        in
+ *   v           [N,H,dv] io_dtype        in
+ *   log_alpha   [N,H,dk] fp32            in
+ *   beta        [N,H,dv] fp32            in, or NULL = all ones
+ *   S           [N,H,dk,dv] fp32         in/out, updated IN PLACE to S'
+ *   o           [N,H,dv] io_dtype        out
+ *
+ * Supported shapes: 1 <= dk <= 256, dv >= 4, dv % 4 == 0.  N or H equal to 0 is a no-op.
+ */
+int rodimus_decode_step(const void *q, const void *k, const void *v,
+                        const float *log_alpha, const float *beta,
+                        float *S, void *o,
+                        int N, int H, int dk, int dv, int io_dtype, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RODIMUS_H */

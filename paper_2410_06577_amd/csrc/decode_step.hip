@@ -1,0 +1,117 @@
+// Recurrent decode step of the Rodimus block (paper Sec. 3.1.3): for every sequence and head
+//     S' = diag(exp(log_alpha)) S + k^T (beta .* v),    o = q S'
+// with S (dk x dv, fp32) updated in place.
+//
+// The step does 4 flop per state element and moves 8 bytes for it, so it is bound by HBM
+// bandwidth: the kernel is a streaming read-modify-write of S.  One workgroup of four
+// wavefronts owns one state (one sequence, one head) and a tile of 256 value columns:
+// lane l holds columns 4l..4l+3 as one 16-byte vector, so a wavefront touches one
+// contiguous 1 KB row segment per instruction; wavefront w takes rows w, w+4, w+8, ...
+// All row loads of a batch are issued before the first is used.  The q.S' products are
+// accumulated per lane and reduced over the four wavefronts through LDS.
+#include "internal.h"
+
+namespace rodimus {
+
+namespace {
+
+constexpr int kDecodeThreads = 256;
+constexpr int kDecodeWaves = 4;
+constexpr int kDecodeCols = 256;   // value columns per workgroup (64 lanes x 4)
+constexpr int kDecodeMaxDk = 256;
+constexpr int kRowBatch = 8;       // rows in flight per wavefront
+
+template <typename IO>
+__global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(
+    const IO *__restrict__ q, const IO *__restrict__ k, const IO *__restrict__ v,
+    const float *__restrict__ log_alpha, const float *__restrict__ beta,
+    float *__restrict__ S, IO *__restrict__ o, int dk, int dv)
+{
+    __shared__ float s_q[kDecodeMaxDk];
+    __shared__ float s_k[kDecodeMaxDk];
+    __shared__ float s_a[kDecodeMaxDk];
+    __shared__ floatx4_t s_red[kDecodeWaves][64];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const size_t state = blockIdx.x;                     // index over (sequence, head)
+    const int col = blockIdx.y * kDecodeCols + 4 * lane;
+    const bool active = col < dv;
+
+    for (int r = tid; r < dk; r += kDecodeThreads) {
+        s_q[r] = load_as_float(q + state * dk + r);
+        s_k[r] = load_as_float(k + state * dk + r);
+        s_a[r] = expf(log_alpha[state * dk + r]);        // exp(-inf) = 0
+    }
+
+    floatx4_t gv = {0.f, 0.f, 0.f, 0.f};                 // beta .* v for this lane's columns
+    if (active) {
+        gv = load4_as_float(v + state * dv + col);
+        if (beta) gv *= *reinterpret_cast<const floatx4_t *>(beta + state * dv + col);
+    }
+    __syncthreads();
+
+    float *Sp = S + state * (size_t)dk * dv + col;
+    floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
+
+    if (active) {
+        for (int r0 = wave; r0 < dk; r0 += kDecodeWaves * kRowBatch) {
+            floatx4_t s[kRowBatch];
+#pragma unroll
+            for (int u = 0; u < kRowBatch; ++u) {
+                const int r = r0 + u * kDecodeWaves;
+                if (r < dk) s[u] = __builtin_nontemporal_load(reinterpret_cast<const floatx4_t *>(Sp + (size_t)r * dv));
+            }
+#pragma unroll
+            for (int u = 0; u < kRowBatch; ++u) {
+                const int r = r0 + u * kDecodeWaves;
+                if (r < dk) {
+                    const float a = s_a[r], kr = s_k[r], qr = s_q[r];
+                    floatx4_t n;
+                    n[0] = fmaf(a, s[u][0], kr * gv[0]);
+                    n[1] = fmaf(a, s[u][1], kr * gv[1]);
+                    n[2] = fmaf(a, s[u][2], kr * gv[2]);
+                    n[3] = fmaf(a, s[u][3], kr * gv[3]);
+                    __builtin_nontemporal_store(n, reinterpret_cast<floatx4_t *>(Sp + (size_t)r * dv));
+                    acc[0] = fmaf(qr, n[0], acc[0]);
+                    acc[1] = fmaf(qr, n[1], acc[1]);
+                    acc[2] = fmaf(qr, n[2], acc[2]);
+                    acc[3] = fmaf(qr, n[3], acc[3]);
+                }
+            }
+        }
+    }
+
+    s_red[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0 && active) {
+        floatx4_t t = s_red[0][lane];
+#pragma unroll
+        for (int w = 1; w < kDecodeWaves; ++w) t += s_red[w][lane];
+        store4_from_float(o + state * dv + col, t);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_decode_step(const DecodeArgs &a)
+{
+    const long long states = (long long)a.N * a.H;
+    if (states == 0) return hipSuccess;
+    const unsigned col_tiles = (unsigned)((a.dv + kDecodeCols - 1) / kDecodeCols);
+    // grid.x is limited to 2^31-1 workgroups; the C-ABI layer has checked N*H against it.
+    dim3 grid((unsigned)states, col_tiles), block(kDecodeThreads);
+    if (a.io_dtype == RODIMUS_BF16) {
+        hipLaunchKernelGGL(decode_step_kernel<bf16_t>, grid, block, 0, a.stream,
+                           (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta,
+                           a.S, (bf16_t *)a.o, a.dk, a.dv);
+    } else {
+        hipLaunchKernelGGL(decode_step_kernel<float>, grid, block, 0, a.stream,
+                           (const float *)a.q, (const float *)a.k, (const float *)a.v, a.log_alpha, a.beta,
+                           a.S, (float *)a.o, a.dk, a.dv);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace rodimus

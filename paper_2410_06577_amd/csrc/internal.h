@@ -1,0 +1,93 @@
+// Internal declarations shared by the HIP translation units of librodimus_hip (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/rodimus.h"
+
+namespace rodimus {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx2_t __attribute__((ext_vector_type(2)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+typedef float floatx16_t __attribute__((ext_vector_type(16)));
+
+// bf16 is the upper half of an IEEE float: widening is a shift.
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+
+// Two floats -> packed bf16 pair, round-to-nearest-even in hardware (v_cvt_pk_bf16_f32); `a` in the low half.
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
+{
+    floatx2_t f = {a, b};
+    bf16x2_t h = __builtin_convertvector(f, bf16x2_t);
+    return *reinterpret_cast<uint32_t *>(&h);
+}
+
+// Element loads/stores templated on the I/O element type (float or bf16_t).
+template <typename T> __device__ __forceinline__ float load_as_float(const T *p);
+template <> __device__ __forceinline__ float load_as_float<float>(const float *p) { return *p; }
+template <> __device__ __forceinline__ float load_as_float<bf16_t>(const bf16_t *p)
+{
+    return bf16_bits_to_float(*reinterpret_cast<const uint16_t *>(p));
+}
+template <typename T> __device__ __forceinline__ void store_from_float(T *p, float x);
+template <> __device__ __forceinline__ void store_from_float<float>(float *p, float x) { *p = x; }
+template <> __device__ __forceinline__ void store_from_float<bf16_t>(bf16_t *p, float x) { *p = (bf16_t)x; }
+
+// Four consecutive elements (pointer must be aligned to 4 elements).
+template <typename T> __device__ __forceinline__ floatx4_t load4_as_float(const T *p);
+template <> __device__ __forceinline__ floatx4_t load4_as_float<float>(const float *p)
+{
+    return *reinterpret_cast<const floatx4_t *>(p);
+}
+template <> __device__ __forceinline__ floatx4_t load4_as_float<bf16_t>(const bf16_t *p)
+{
+    uint2 u = *reinterpret_cast<const uint2 *>(p);
+    floatx4_t r = {bf16_lo(u.x), bf16_hi(u.x), bf16_lo(u.y), bf16_hi(u.y)};
+    return r;
+}
+template <typename T> __device__ __forceinline__ void store4_from_float(T *p, floatx4_t x);
+template <> __device__ __forceinline__ void store4_from_float<float>(float *p, floatx4_t x)
+{
+    *reinterpret_cast<floatx4_t *>(p) = x;
+}
+template <> __device__ __forceinline__ void store4_from_float<bf16_t>(bf16_t *p, floatx4_t x)
+{
+    uint2 u = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3])};
+    *reinterpret_cast<uint2 *>(p) = u;
+}
+
+// ---- launchers (host).  Arguments are already validated by the C-ABI layer. -------------------------
+struct ScanArgs {
+    const void *q, *k, *v;
+    const float *log_alpha, *beta, *S0;
+    void *o;
+    float *S_T;
+    int B, T, H, dk, dv, chunk;
+    int io_dtype;
+    void *workspace;
+    size_t workspace_bytes;
+    hipStream_t stream;
+};
+
+struct DecodeArgs {
+    const void *q, *k, *v;
+    const float *log_alpha, *beta;
+    float *S;
+    void *o;
+    int N, H, dk, dv;
+    int io_dtype;
+    hipStream_t stream;
+};
+
+hipError_t launch_decode_step(const DecodeArgs &a);
+hipError_t launch_scan_generic(const ScanArgs &a);
+size_t scan_generic_lds_bytes(int dk, int chunk);
+
+}  // namespace rodimus

@@ -1,0 +1,131 @@
+// C-ABI entry points of librodimus_hip: argument validation on the host, then dispatch to a kernel
+// family.  Nothing here allocates, synchronises or keeps state.  See include/rodimus.h for the contract.
+#include "internal.h"
+
+namespace {
+
+using namespace rodimus;
+
+inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+inline bool overlaps(const void *a, size_t a_bytes, const void *b, size_t b_bytes)
+{
+    if (a == nullptr || b == nullptr || a_bytes == 0 || b_bytes == 0) return false;
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + b_bytes && b0 < a0 + a_bytes;
+}
+
+inline size_t elem_bytes(int io_dtype) { return io_dtype == RODIMUS_BF16 ? 2 : 4; }
+
+constexpr int kMaxScanDk = 128;
+constexpr int kMaxChunk = 64;
+constexpr int kMaxChunkTimesDk = 4096;
+constexpr int kMaxDecodeDk = 256;
+constexpr long long kMaxGridX = 2147483647LL;
+
+// Shape rules shared by the scan entry point and its two query functions.
+int scan_shape_status(int B, int T, int H, int dk, int dv, int chunk, int io_dtype)
+{
+    if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
+    if (B < 0 || T < 0 || H < 0) return RODIMUS_ERR_SHAPE;
+    if (dk < 1 || dk > kMaxScanDk || dv < 1) return RODIMUS_ERR_SHAPE;
+    if (chunk < 1 || chunk > kMaxChunk || chunk * dk > kMaxChunkTimesDk) return RODIMUS_ERR_SHAPE;
+    if ((long long)B * H > kMaxGridX || (dv + 63) / 64 > 65535) return RODIMUS_ERR_SHAPE;
+    return RODIMUS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *rodimus_status_string(int status)
+{
+    switch (status) {
+    case RODIMUS_OK: return "ok";
+    case RODIMUS_ERR_NULL: return "a required pointer is NULL";
+    case RODIMUS_ERR_SHAPE: return "a size is invalid or outside the supported range";
+    case RODIMUS_ERR_DTYPE: return "io_dtype is not RODIMUS_F32 or RODIMUS_BF16";
+    case RODIMUS_ERR_ALIGN: return "a base pointer is not 16-byte aligned";
+    case RODIMUS_ERR_WORKSPACE: return "workspace is missing or too small";
+    case RODIMUS_ERR_LAUNCH: return "the HIP runtime refused the launch";
+    case RODIMUS_ERR_ALIAS: return "an output overlaps an input it must not overlap";
+    default: return "unknown status";
+    }
+}
+
+int rodimus_chunk_scan_path(int B, int T, int H, int dk, int dv, int chunk, int io_dtype)
+{
+    if (scan_shape_status(B, T, H, dk, dv, chunk, io_dtype) != RODIMUS_OK) return RODIMUS_PATH_NONE;
+    return RODIMUS_PATH_GENERIC;
+}
+
+size_t rodimus_chunk_scan_workspace_bytes(int B, int T, int H, int dk, int dv, int chunk, int io_dtype)
+{
+    if (scan_shape_status(B, T, H, dk, dv, chunk, io_dtype) != RODIMUS_OK) return 0;
+    return 0;
+}
+
+int rodimus_chunk_scan_fwd(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta,
+                           const float *S0, void *o, float *S_T, int B, int T, int H, int dk, int dv, int chunk,
+                           int io_dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    const int shape = scan_shape_status(B, T, H, dk, dv, chunk, io_dtype);
+    if (shape != RODIMUS_OK) return shape;
+    const size_t tokens = (size_t)B * T * H;
+    if (tokens > 0 && (!q || !k || !v || !log_alpha || !o)) return RODIMUS_ERR_NULL;   // empty tensors may be NULL
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(log_alpha) || misaligned(beta) ||
+        misaligned(S0) || misaligned(o) || misaligned(S_T) || misaligned(workspace))
+        return RODIMUS_ERR_ALIGN;
+
+    const size_t eb = elem_bytes(io_dtype);
+    const size_t qk_bytes = tokens * dk * eb, v_bytes = tokens * dv * eb;
+    const size_t la_bytes = tokens * dk * 4, beta_bytes = tokens * dv * 4;
+    const size_t state_bytes = (size_t)B * H * dk * dv * 4;
+    if (overlaps(o, v_bytes, q, qk_bytes) || overlaps(o, v_bytes, k, qk_bytes) || overlaps(o, v_bytes, v, v_bytes) ||
+        overlaps(o, v_bytes, log_alpha, la_bytes) || overlaps(o, v_bytes, beta, beta_bytes) ||
+        overlaps(o, v_bytes, S0, state_bytes) || overlaps(o, v_bytes, S_T, state_bytes))
+        return RODIMUS_ERR_ALIAS;
+    if (S_T != nullptr && S_T != S0 && overlaps(S_T, state_bytes, S0, state_bytes)) return RODIMUS_ERR_ALIAS;
+    if (overlaps(S_T, state_bytes, q, qk_bytes) || overlaps(S_T, state_bytes, k, qk_bytes) ||
+        overlaps(S_T, state_bytes, v, v_bytes) || overlaps(S_T, state_bytes, log_alpha, la_bytes) ||
+        overlaps(S_T, state_bytes, beta, beta_bytes))
+        return RODIMUS_ERR_ALIAS;
+
+    const size_t need = rodimus_chunk_scan_workspace_bytes(B, T, H, dk, dv, chunk, io_dtype);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return RODIMUS_ERR_WORKSPACE;
+
+    ScanArgs a{q, k, v, log_alpha, beta, S0, o, S_T, B, T, H, dk, dv, chunk, io_dtype,
+               workspace, workspace_bytes, static_cast<hipStream_t>(stream)};
+    const hipError_t err = launch_scan_generic(a);
+    return err == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
+}
+
+int rodimus_decode_step(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta,
+                        float *S, void *o, int N, int H, int dk, int dv, int io_dtype, void *stream)
+{
+    if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
+    if (N < 0 || H < 0 || dk < 1 || dk > kMaxDecodeDk || dv < 4 || (dv & 3) != 0) return RODIMUS_ERR_SHAPE;
+    if ((long long)N * H > kMaxGridX || (dv + 255) / 256 > 65535) return RODIMUS_ERR_SHAPE;
+    const size_t states = (size_t)N * H;
+    if (states > 0 && (!q || !k || !v || !log_alpha || !S || !o)) return RODIMUS_ERR_NULL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(log_alpha) || misaligned(beta) ||
+        misaligned(S) || misaligned(o))
+        return RODIMUS_ERR_ALIGN;
+
+    const size_t eb = elem_bytes(io_dtype);
+    const size_t o_bytes = states * dv * eb, s_bytes = states * dk * dv * 4;
+    if (overlaps(o, o_bytes, q, states * dk * eb) || overlaps(o, o_bytes, k, states * dk * eb) ||
+        overlaps(o, o_bytes, v, o_bytes) || overlaps(o, o_bytes, log_alpha, states * dk * 4) ||
+        overlaps(o, o_bytes, beta, states * dv * 4) || overlaps(o, o_bytes, S, s_bytes))
+        return RODIMUS_ERR_ALIAS;
+    if (overlaps(S, s_bytes, q, states * dk * eb) || overlaps(S, s_bytes, k, states * dk * eb) ||
+        overlaps(S, s_bytes, v, o_bytes) || overlaps(S, s_bytes, log_alpha, states * dk * 4) ||
+        overlaps(S, s_bytes, beta, states * dv * 4))
+        return RODIMUS_ERR_ALIAS;
+
+    DecodeArgs a{q, k, v, log_alpha, beta, S, o, N, H, dk, dv, io_dtype, static_cast<hipStream_t>(stream)};
+    const hipError_t err = launch_decode_step(a);
+    return err == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
+}
+
+}  // extern "C"

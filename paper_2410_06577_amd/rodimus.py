@@ -1,0 +1,153 @@
+"""ctypes binding of ``librodimus_hip.so`` -- argument marshalling only.
+
+Every step of the path runs in the HIP kernels; this module checks tensor
+shapes/dtypes/devices, hands raw device pointers and the current HIP stream to the
+C ABI declared in ``include/rodimus.h`` and turns a non-zero status into an
+exception.  torch is used for device memory and streams, nothing else.  There is no
+CPU fallback: if the library has not been built, loading raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librodimus_hip.so")
+
+F32, BF16 = 0, 1
+PATH_NONE, PATH_GENERIC, PATH_MFMA = 0, 1, 2
+_DTYPES = {torch.float32: F32, torch.bfloat16: BF16}
+
+_lib = None
+
+
+class RodimusError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"rodimus status {status}: {message}")
+        self.status = status
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2410_06577_amd.build` "
+                "(there is no fallback implementation)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        L.rodimus_status_string.argtypes = [i]
+        L.rodimus_status_string.restype = ctypes.c_char_p
+        L.rodimus_chunk_scan_fwd.argtypes = [vp] * 8 + [i] * 7 + [vp, sz, vp]
+        L.rodimus_chunk_scan_fwd.restype = i
+        L.rodimus_chunk_scan_workspace_bytes.argtypes = [i] * 7
+        L.rodimus_chunk_scan_workspace_bytes.restype = sz
+        L.rodimus_chunk_scan_path.argtypes = [i] * 7
+        L.rodimus_chunk_scan_path.restype = i
+        L.rodimus_decode_step.argtypes = [vp] * 7 + [i] * 5 + [vp]
+        L.rodimus_decode_step.restype = i
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().rodimus_status_string(int(status)).decode()
+
+
+def _check(status: int):
+    if status != 0:
+        raise RodimusError(status, status_string(status))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _require(t, name, shape, dtype, device):
+    if t is None:
+        return
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: shape {tuple(t.shape)} != expected {tuple(shape)}")
+    if t.dtype != dtype:
+        raise ValueError(f"{name}: dtype {t.dtype} != expected {dtype}")
+    if t.device != device:
+        raise ValueError(f"{name}: device {t.device} != {device}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+
+
+def _stream(device):
+    return ctypes.c_void_p(torch.cuda.current_stream(device).cuda_stream)
+
+
+def rodimus_chunk_scan_workspace_bytes(B, T, H, dk, dv, chunk, io_dtype) -> int:
+    return int(lib().rodimus_chunk_scan_workspace_bytes(B, T, H, dk, dv, chunk, _DTYPES[io_dtype]))
+
+
+def rodimus_chunk_scan_path(B, T, H, dk, dv, chunk, io_dtype) -> int:
+    return int(lib().rodimus_chunk_scan_path(B, T, H, dk, dv, chunk, _DTYPES[io_dtype]))
+
+
+def rodimus_chunk_scan_fwd(q, k, v, log_alpha, beta=None, S0=None, *, chunk=64, o=None, S_T=None,
+                           want_state=True, workspace=None):
+    """Chunkwise forward scan.  q,k,log_alpha [B,T,H,dk]; v,beta [B,T,H,dv]; S0 [B,H,dk,dv] fp32.
+
+    Returns (o, S_T); S_T is None when ``want_state`` is False.  Output and workspace
+    tensors are allocated with torch unless passed in.
+    """
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_chunk_scan_fwd needs device tensors (no CPU path exists)")
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    dev, io = q.device, q.dtype
+    _require(q, "q", (B, T, H, dk), io, dev)
+    _require(k, "k", (B, T, H, dk), io, dev)
+    _require(v, "v", (B, T, H, dv), io, dev)
+    _require(log_alpha, "log_alpha", (B, T, H, dk), torch.float32, dev)
+    _require(beta, "beta", (B, T, H, dv), torch.float32, dev)
+    _require(S0, "S0", (B, H, dk, dv), torch.float32, dev)
+    if o is None:
+        o = torch.empty((B, T, H, dv), dtype=io, device=dev)
+    _require(o, "o", (B, T, H, dv), io, dev)
+    if S_T is None and want_state:
+        S_T = torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev)
+    _require(S_T, "S_T", (B, H, dk, dv), torch.float32, dev)
+    need = rodimus_chunk_scan_workspace_bytes(B, T, H, dk, dv, chunk, io)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_chunk_scan_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(S0),
+                                            _ptr(o), _ptr(S_T), B, T, H, dk, dv, int(chunk), _DTYPES[io],
+                                            _ptr(workspace), ws_bytes, _stream(dev)))
+    return o, S_T
+
+
+def rodimus_decode_step(q, k, v, log_alpha, beta, S, *, o=None):
+    """One recurrent step.  q,k,log_alpha [N,H,dk]; v,beta [N,H,dv]; S [N,H,dk,dv] fp32, updated in place.
+
+    Returns o [N,H,dv].
+    """
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_decode_step needs device tensors (no CPU path exists)")
+    N, H, dk = q.shape
+    dv = v.shape[-1]
+    dev, io = q.device, q.dtype
+    _require(q, "q", (N, H, dk), io, dev)
+    _require(k, "k", (N, H, dk), io, dev)
+    _require(v, "v", (N, H, dv), io, dev)
+    _require(log_alpha, "log_alpha", (N, H, dk), torch.float32, dev)
+    _require(beta, "beta", (N, H, dv), torch.float32, dev)
+    _require(S, "S", (N, H, dk, dv), torch.float32, dev)
+    if o is None:
+        o = torch.empty((N, H, dv), dtype=io, device=dev)
+    _require(o, "o", (N, H, dv), io, dev)
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_decode_step(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(S), _ptr(o),
+                                         N, H, dk, dv, _DTYPES[io], _stream(dev)))
+    return o

@@ -1,0 +1,53 @@
+"""Helpers of the GPU parity tests: run the HIP library and the CPU oracle on the same seeded inputs."""
+import numpy as np
+import torch
+
+import oracle
+from paper_2410_06577_amd import rodimus
+
+TOL_F32 = 1e-4      # max|err| / max|ref|, fp32 inputs, fp32 state
+TOL_BF16 = 2e-2     # bf16 inputs and outputs, fp32 state
+
+
+def tol_for(dtype):
+    return TOL_BF16 if dtype == torch.bfloat16 else TOL_F32
+
+
+def rel_err(got, ref):
+    """max|got - ref| / max|ref| over the whole tensor (the bar of the build's baseline file)."""
+    got = got.detach().cpu().double().numpy() if hasattr(got, "detach") else np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    if ref.size == 0:
+        return 0.0
+    if not np.isfinite(got).all():
+        return float("inf")
+    scale = float(np.abs(ref).max())
+    return float(np.abs(got - ref).max()) / (scale if scale > 0 else 1.0)
+
+
+def to_dev(d, device="cuda:0"):
+    return {key: (None if val is None else val.to(device)) for key, val in d.items()}
+
+
+def gpu_scan(inp, chunk, **kw):
+    """inp: dict of CPU tensors (q,k,v,log_alpha,beta,S0).  Returns (o, S_T) device tensors."""
+    g = to_dev(inp)
+    o, S_T = rodimus.rodimus_chunk_scan_fwd(g["q"], g["k"], g["v"], g["log_alpha"], g.get("beta"), g.get("S0"),
+                                            chunk=chunk, **kw)
+    torch.cuda.synchronize()
+    return o, S_T
+
+
+def oracle_scan(inp):
+    return oracle.scan(inp["q"], inp["k"], inp["v"], inp["log_alpha"], inp.get("beta"), inp.get("S0"))
+
+
+def check_scan(inp, chunk, label=""):
+    o, S_T = gpu_scan(inp, chunk)
+    o_ref, S_ref = oracle_scan(inp)
+    tol = tol_for(inp["q"].dtype)
+    eo, es = rel_err(o, o_ref), rel_err(S_T, S_ref)
+    assert eo <= tol, f"{label}: o rel err {eo:.3e} > {tol}"
+    assert es <= tol, f"{label}: S_T rel err {es:.3e} > {tol}"
+    return eo, es

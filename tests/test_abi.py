@@ -1,0 +1,100 @@
+"""The C-ABI boundary on a machine without a GPU: the library loads, exports every symbol the header
+declares, and turns every invalid argument into a status code before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2410_06577_amd import rodimus
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_WS, E_LAUNCH, E_ALIAS = range(8)
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(rodimus.LIB_PATH):
+        from paper_2410_06577_amd import build
+        build.build()
+    return rodimus.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    header = open(os.path.join(ROOT, "include", "rodimus.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(rodimus_[a-z_]+)\s*\(", header))
+    assert {"rodimus_chunk_scan_fwd", "rodimus_decode_step", "rodimus_status_string",
+            "rodimus_chunk_scan_workspace_bytes", "rodimus_chunk_scan_path"} <= declared
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_status_strings(L):
+    seen = {rodimus.status_string(s) for s in range(8)}
+    assert len(seen) == 8 and "ok" in seen
+    assert rodimus.status_string(1234) == "unknown status"
+
+
+def _scan(L, *, q=0x10000, k=0x20000, v=0x30000, la=0x40000, beta=0x50000, S0=0x60000, o=0x70000, S_T=0x80000,
+          B=1, T=4, H=1, dk=16, dv=32, chunk=4, io=rodimus.F32, ws=None, ws_bytes=0):
+    p = lambda x: None if x is None else ctypes.c_void_p(x)
+    return L.rodimus_chunk_scan_fwd(p(q), p(k), p(v), p(la), p(beta), p(S0), p(o), p(S_T),
+                                    B, T, H, dk, dv, chunk, io, p(ws), ws_bytes, None)
+
+
+def _decode(L, *, q=0x10000, k=0x20000, v=0x30000, la=0x40000, beta=0x50000, S=0x100000, o=0x70000,
+            N=2, H=2, dk=16, dv=32, io=rodimus.BF16):
+    p = lambda x: None if x is None else ctypes.c_void_p(x)
+    return L.rodimus_decode_step(p(q), p(k), p(v), p(la), p(beta), p(S), p(o), N, H, dk, dv, io, None)
+
+
+def test_scan_rejects_bad_arguments_before_any_launch(L):
+    assert _scan(L, io=7) == E_DTYPE
+    for bad in (dict(B=-1), dict(T=-1), dict(H=-2), dict(dk=0), dict(dk=129), dict(dv=0),
+                dict(chunk=0), dict(chunk=65), dict(dk=128, chunk=64)):
+        assert _scan(L, **bad) == E_SHAPE, bad
+    for name in ("q", "k", "v", "la", "o"):
+        assert _scan(L, **{name: None}) == E_NULL, name
+    for name in ("q", "k", "v", "la", "beta", "S0", "o", "S_T"):
+        assert _scan(L, **{name: 0x10008 + 0x100000}) == E_ALIGN, name
+    # the output may not overlap an input; S_T may be S0 itself but not a shifted view of it
+    assert _scan(L, o=0x30000) == E_ALIAS                   # o == v
+    assert _scan(L, o=0x10010) == E_ALIAS                   # o inside q
+    assert _scan(L, S_T=0x60010) == E_ALIAS                 # S_T partially over S0
+    assert _scan(L, S_T=0x10000) == E_ALIAS                 # S_T over q
+
+
+def test_decode_rejects_bad_arguments_before_any_launch(L):
+    assert _decode(L, io=-1) == E_DTYPE
+    for bad in (dict(N=-1), dict(H=-1), dict(dk=0), dict(dk=257), dict(dv=0), dict(dv=30)):
+        assert _decode(L, **bad) == E_SHAPE, bad
+    for name in ("q", "k", "v", "la", "S", "o"):
+        assert _decode(L, **{name: None}) == E_NULL, name
+    for name in ("q", "k", "v", "la", "beta", "S", "o"):
+        assert _decode(L, **{name: 0x900008}) == E_ALIGN, name
+    assert _decode(L, o=0x100000) == E_ALIAS                # o over the state
+    assert _decode(L, S=0x30000) == E_ALIAS                 # state over v
+
+
+def test_empty_problems_are_successful_noops(L):
+    assert _scan(L, B=0) == OK
+    assert _scan(L, H=0) == OK
+    assert _scan(L, T=0, S_T=None) == OK
+    assert _decode(L, N=0) == OK
+    assert _decode(L, H=0) == OK
+
+
+def test_queries(L):
+    assert L.rodimus_chunk_scan_path(1, 64, 1, 16, 32, 16, rodimus.F32) == rodimus.PATH_GENERIC
+    assert L.rodimus_chunk_scan_path(1, 64, 1, 0, 32, 16, rodimus.F32) == rodimus.PATH_NONE
+    assert L.rodimus_chunk_scan_workspace_bytes(1, 64, 1, 16, 32, 16, rodimus.F32) == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(1, 4, 1, 16)
+    with pytest.raises(ValueError, match="device tensors"):
+        rodimus.rodimus_chunk_scan_fwd(x, x, x, x)
+    with pytest.raises(ValueError, match="device tensors"):
+        rodimus.rodimus_decode_step(x[0], x[0], x[0], x[0], None, torch.zeros(4, 1, 16, 16))
