@@ -89,5 +89,7 @@ struct DecodeArgs {
 hipError_t launch_decode_step(const DecodeArgs &a);
 hipError_t launch_scan_generic(const ScanArgs &a);
 size_t scan_generic_lds_bytes(int dk, int chunk);
+hipError_t launch_scan_mfma(const ScanArgs &a);
+bool scan_mfma_supports(int dk, int dv, int chunk, int io_dtype);
 
 }  // namespace rodimus

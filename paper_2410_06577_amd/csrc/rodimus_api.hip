@@ -56,7 +56,7 @@ const char *rodimus_status_string(int status)
 int rodimus_chunk_scan_path(int B, int T, int H, int dk, int dv, int chunk, int io_dtype)
 {
     if (scan_shape_status(B, T, H, dk, dv, chunk, io_dtype) != RODIMUS_OK) return RODIMUS_PATH_NONE;
-    return RODIMUS_PATH_GENERIC;
+    return scan_mfma_supports(dk, dv, chunk, io_dtype) ? RODIMUS_PATH_MFMA : RODIMUS_PATH_GENERIC;
 }
 
 size_t rodimus_chunk_scan_workspace_bytes(int B, int T, int H, int dk, int dv, int chunk, int io_dtype)
@@ -96,7 +96,7 @@ int rodimus_chunk_scan_fwd(const void *q, const void *k, const void *v, const fl
 
     ScanArgs a{q, k, v, log_alpha, beta, S0, o, S_T, B, T, H, dk, dv, chunk, io_dtype,
                workspace, workspace_bytes, static_cast<hipStream_t>(stream)};
-    const hipError_t err = launch_scan_generic(a);
+    const hipError_t err = scan_mfma_supports(dk, dv, chunk, io_dtype) ? launch_scan_mfma(a) : launch_scan_generic(a);
     return err == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
 }
 
