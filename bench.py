@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the Rodimus DDTS hot path on one MI355X.  Prints ONE JSON line.
+
+A "step" is one forward chunk scan (rodimus_chunk_scan_fwd) over the 1.6B-class layer batch
+(B=8, T=4096, H=16, dk=64, dv=256, chunk=64; bf16 q/k/v/o, fp32 gates and state, non-zero S0,
+S_T returned), inputs resident in HBM.  `value` is tokens/s of that scan (tokens = B*T positions,
+all heads).  The decode leg then times 1000 chained rodimus_decode_step launches over 256
+sequences x 16 heads of 64x256 fp32 states and is reported in the `decode` object of the same
+line, with its own roofline.  `cpu_baseline` is the fp64 CPU oracle timed on this machine's host
+cores on the same scan workload (it finishes in seconds; it also serves as a parity check of the
+whole GPU result).
+
+Roofline figures: `achieved` = algorithmic bytes per launch / mean launch duration from HIP events
+on the launch stream.  Algorithmic bytes per (token, head): q 2dk + k 2dk + log_alpha 4dk + v 2dv +
+beta 4dv + o 2dv = 2560 B at dk=64, dv=256, plus S0 read and S_T written once per (batch, head).
+Decode: S read + S written (2*4*dk*dv B per state) plus the token vectors and o.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (scaled by a plain copy kernel);
+# filled in from the summaries under profiles/ once measured, None until then.
+MEASURED_TRAFFIC_BYTES = {"scan_layer_1p6b": None, "decode_256x16": None}
+
+
+def _events(n):
+    return [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+
+
+def bench_scan(w, steps, warmup, rodimus, wl, dev):
+    inp = wl.make_scan_inputs(w)
+    g = {k: (None if v is None else v.to(dev)) for k, v in inp.items()}
+    o = torch.empty((w.B, w.T, w.H, w.dv), dtype=torch.bfloat16, device=dev)
+    S_T = torch.empty((w.B, w.H, w.dk, w.dv), dtype=torch.float32, device=dev)
+    need = rodimus.rodimus_chunk_scan_workspace_bytes(w.B, w.T, w.H, w.dk, w.dv, w.chunk, torch.bfloat16)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+
+    def step():
+        rodimus.rodimus_chunk_scan_fwd(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], g["S0"],
+                                       chunk=w.chunk, o=o, S_T=S_T, workspace=ws)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = _events(steps)
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    launch_ms = sum(a.elapsed_time(b) for a, b in ev) / steps
+
+    th = w.token_heads
+    state_bytes = w.B * w.H * w.dk * w.dv * 4
+    algo_bytes = th * (8 * w.dk + 8 * w.dv) + state_bytes * ((1 if g["S0"] is not None else 0) + 1)
+    flops_causal = th * 2 * (2 * w.dk * w.dv + w.chunk * (w.dk + w.dv) // 2)
+    flops_dense = th * 2 * (2 * w.dk * w.dv + w.chunk * (w.dk + w.dv))
+    res = {
+        "wall_s": wall, "ms_per_step": wall / steps * 1e3, "launch_ms": launch_ms,
+        "tokens_per_s": w.tokens * steps / wall,
+        "algo_bytes": algo_bytes, "gbs": algo_bytes / (launch_ms * 1e-3) / 1e9,
+        "tflops_causal": flops_causal / (launch_ms * 1e-3) / 1e12,
+        "tflops_dense_tiles": flops_dense / (launch_ms * 1e-3) / 1e12,
+        "path": rodimus.rodimus_chunk_scan_path(w.B, w.T, w.H, w.dk, w.dv, w.chunk, torch.bfloat16),
+    }
+    return res, inp, o, S_T
+
+
+def bench_decode(w, rodimus, wl, dev, warmup=20):
+    d = wl.make_decode_inputs(w)
+    S = d["S"].to(dev)
+    ring = [{k: v.to(dev) for k, v in tok.items()} for tok in d["ring"]]
+    o = torch.empty((w.N, w.H, w.dv), dtype=torch.bfloat16, device=dev)
+
+    def step(i):
+        t = ring[i % len(ring)]
+        rodimus.rodimus_decode_step(t["q"], t["k"], t["v"], t["log_alpha"], t["beta"], S, o=o)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    a.record()
+    for i in range(w.steps):
+        step(i)
+    b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    launch_ms = a.elapsed_time(b) / w.steps
+    states = w.N * w.H
+    algo_bytes = states * (2 * 4 * w.dk * w.dv + 2 * (2 * w.dk) + 4 * w.dk + 2 * w.dv + 4 * w.dv + 2 * w.dv)
+    finite = bool(torch.isfinite(S).all().item())
+    return {"wall_s": wall, "launch_ms": launch_ms, "algo_bytes": algo_bytes,
+            "gbs": algo_bytes / (launch_ms * 1e-3) / 1e9, "steps_per_s": w.steps / wall, "finite": finite}
+
+
+def cpu_baseline(w, inp, o_gpu, S_gpu):
+    """fp64 oracle on the scan workload, timed on the host cores; also the parity check of the GPU result."""
+    import numpy as np
+    import oracle
+    t0 = time.perf_counter()
+    o_ref, S_ref = oracle.scan(inp["q"], inp["k"], inp["v"], inp["log_alpha"], inp["beta"], inp["S0"])
+    dt = time.perf_counter() - t0
+
+    def rel(got, ref):
+        got = got.detach().cpu().double().numpy()
+        return float(np.abs(got - ref).max() / np.abs(ref).max())
+
+    return {
+        "value": w.tokens / dt, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+        "sample": f"the whole scan workload once (B={w.B}, T={w.T}, H={w.H}, dk={w.dk}, dv={w.dv}), fp64 sequential "
+                  f"recurrence, OpenMP over (batch, head), {dt:.2f} s",
+        "seconds": dt,
+    }, {"o_rel_err": rel(o_gpu, o_ref), "S_T_rel_err": rel(S_gpu, S_ref), "tolerance": 2e-2}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--skip-decode", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (reference dispatch for rocprofv3 --pmc runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+
+    from paper_2410_06577_amd import rodimus, workloads as wl
+    rodimus.lib()                       # fail loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    w = wl.LAYER_1P6B
+    scan, inp, o, S_T = bench_scan(w, args.steps, args.warmup, rodimus, wl, dev)
+    out = {
+        "metric": "chunk_scan_tokens_per_s", "value": scan["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": scan["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: chunk-scan forward B={w.B} T={w.T} H={w.H} dk={w.dk} dv={w.dv} "
+                               f"chunk={w.chunk}, bf16 q/k/v/o, fp32 gates and state, S0 ~ N(0,0.1), S_T returned",
+                   "global_batch": w.B, "seq_len": w.T, "parallelism": "single-gpu",
+                   "kernel_path": {1: "generic", 2: "mfma"}.get(scan["path"], "none")},
+        "roofline": {"bound": "hbm", "achieved": scan["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": scan["gbs"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES["scan_layer_1p6b"],
+                     "kernel": "scan_mfma_kernel", "launch_ms": scan["launch_ms"], "algorithmic_bytes": scan["algo_bytes"]},
+        "mfma": {"achieved_causal": scan["tflops_causal"], "achieved_dense_tiles": scan["tflops_dense_tiles"],
+                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": scan["tflops_causal"] / MFMA_BF16_PEAK_TFLOPS,
+                 "note": "41.6 flop/B at dk=64: a single-pass scan is HBM-bound and cannot exceed ~13% of MFMA peak"},
+    }
+    if not args.skip_decode:
+        dw = wl.DECODE
+        dec = bench_decode(dw, rodimus, wl, dev)
+        out["decode"] = {
+            "metric": "decode_step_GB_per_s", "value": dec["gbs"], "unit": "GB/s", "ms_per_step": dec["launch_ms"],
+            "steps": dw.steps, "state_finite": dec["finite"],
+            "workload": f"{dw.name}: {dw.N} sequences x H={dw.H} x ({dw.dk}x{dw.dv}) fp32 states, bf16 q/k/v/o, "
+                        f"{dw.steps} chained steps",
+            "roofline": {"bound": "hbm", "achieved": dec["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": dec["gbs"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES["decode_256x16"],
+                         "kernel": "decode_step_kernel", "algorithmic_bytes": dec["algo_bytes"]},
+        }
+    if not args.skip_cpu_baseline:
+        base, parity = cpu_baseline(w, inp, o, S_T)
+        out["cpu_baseline"] = base
+        out["parity_vs_oracle"] = parity
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
