@@ -1,129 +1,302 @@
 // Chunkwise forward scan of the Rodimus recurrence on the matrix cores (bf16 MFMA, fp32 accumulate).
-// Shape: dk = 64, chunk = 64, value columns in tiles of 128.  gfx950 only.
+// Shape: dk = 64, value columns in tiles of 128, bf16 q/k/v/o.  gfx950 only.
 //
-// Per (batch, head), with A_t the product of the decay gates from the chunk start through row t and G_i
-// the product over the rows after i to the chunk end (paper appendix "Chunkwise Parallel Representation
-// of the Rodimus Block"):
+// The chunkwise form of the paper's appendix ("Chunkwise Parallel Representation of the Rodimus Block") is
+// applied with the state carried every 16 tokens (one MFMA tile); 64 tokens are processed per workgroup
+// barrier.  For a tile of rows t = 1..16 with S_prev the state entering it, A_t the product of the decay
+// gates from the tile start through row t and G_i the product over the rows after i to the tile end:
 //     o_t   = (q_t .* A_t) S_prev + sum_{i<=t} P[t,i] (beta_i .* v_i)
 //     P[t,i]= sum_n q_t[n] k_i[n] prod_{j=i+1..t} alpha_j[n]
-//     S_new = diag(A_C) S_prev + sum_i (k_i .* G_i)^T (beta_i .* v_i)
-// The appendix's quotient A_t / A_i is never formed: the pairwise decay is built from products of gates
-// by binary splitting of the chunk (see the comment on build_versions), so alpha = 0 and decays beyond
-// the fp32 range are exact.
+//     S_new = diag(A_16) S_prev + sum_i (k_i .* G_i)^T (beta_i .* v_i)
+// The appendix's quotient A_t / A_i is never formed.  The pairwise decay is built from PRODUCTS of gates by
+// binary splitting of the tile: for a power of two h, a row t with bit h set pairs with the rows i of the first
+// half of its aligned 2h-block and
+//     prod_{j=i+1..t} alpha_j = (prod over t's h-block from its start through t) * (prod over the rows after i
+//                               to the end of i's h-block).
+// Every pair i < t belongs to exactly one h, all factors are <= 1 for log_alpha <= 0 and exactly 0 after
+// alpha = 0, so hard resets and decays beyond the fp32 range are exact.
 //
-// One workgroup of 8 wavefronts owns one (batch, head), one tile of 128 value columns and walks the
-// chunks of its token range in order.  The fp32 state tile (64 x 128) lives in MFMA accumulators for the
-// whole walk: wavefront (rh, cs) holds rows 32rh..32rh+31, columns 32cs..32cs+31.  Per chunk:
-//   A  the prefetched q, k, log_alpha tiles go to LDS; beta .* v goes to LDS transposed (token-contiguous)
-//   B  every thread owns 4 consecutive rows x 2 key channels: gate products inside the thread, a 16-lane
-//      segmented scan across threads, then the decayed copies of q and k ("versions") are written as bf16
-//   C  o += (q .* A) S_prev on MFMA; the score tiles on MFMA (Gram matrices of the version arrays, masked)
-//   D  o += P (beta .* v), store o;  S = diag(A_C) S + (k .* G)^T (beta .* v);  bf16 copy of S for step C
-// The next chunk's global loads are issued in step A and land in registers while B-D run.
-//
-// LDS arrays holding bf16 rows of 128 bytes are stored unpadded with the 16-byte unit index XOR-swizzled by
-// the row, which keeps both the MFMA operand reads (16 B per lane, consecutive rows) and the scan threads'
-// 4-byte accesses (rows 4 apart) spread over all banks.
+// One workgroup (8 wavefronts) owns one (batch, head) and 128 value columns and walks its tokens in order.
+// The wavefronts are specialised and work one chunk apart through double-buffered LDS, with ONE barrier per
+// 64 tokens:
+//   wavefronts 0-3 ("gate" wavefronts), one 16-row tile each: lane = (row, 16 key channels).  exp of the
+//       log-gates, the prefix/suffix products of every split level by DPP across the 16 lanes of a row group,
+//       the decayed copies of q and k as bf16 MFMA operands straight from registers, the level scores as
+//       masked Gram matrices (MFMA), and for the other half: q .* A, (k .* G)^T, A_16 and P into LDS.
+//   wavefronts 4-7 ("state" wavefronts), 32 value columns each: the fp32 state slab (64 x 32) lives in MFMA
+//       accumulators for the whole walk; per tile o^T = S^T (q .* A)^T + (beta .* v)^T P^T, the bf16 store of
+//       o, S = diag(A_16) S + (k .* G)^T (beta .* v), and the bf16 copy of S that feeds the next tile.
+// Global loads are issued one chunk ahead into registers by the wavefront that consumes them.
 #include "internal.h"
 
 namespace rodimus {
 
 namespace {
 
-constexpr int kC = 64;          // chunk length
-constexpr int kK = 64;          // key width
-constexpr int kColTile = 128;   // value columns per workgroup
+constexpr int kK = 64;           // key width
+constexpr int kTile = 16;        // rows per state update
+constexpr int kChunk = 64;       // tokens per barrier (4 tiles)
+constexpr int kColTile = 128;    // value columns per workgroup
 constexpr int kThreads = 512;
 
-// ---- LDS map (bytes) ------------------------------------------------------------------------------------
-constexpr int kRowBytes = 128;                        // 64 bf16
-constexpr int kTile64 = 64 * kRowBytes;               // a [64][64] bf16 array
-constexpr int kOffX = 0;                              // 6 version arrays, one per split level h = 1..32
-constexpr int kOffQraw = kOffX + 6 * kTile64;
-constexpr int kOffKraw = kOffQraw + kTile64;
-constexpr int kOffQin = kOffKraw + kTile64;           // q .* A          [t][n]
-constexpr int kOffKstT = kOffQin + kTile64;           // (k .* G)^T      [n][token]
-constexpr int kOffGVt = kOffKstT + kTile64;           // (beta .* v)^T   [column][token], 128 rows
-constexpr int kOffSt = kOffGVt + 2 * kTile64;         // bf16 state^T    [column][n],     128 rows
-constexpr int kOffPm = kOffSt + 2 * kTile64;          // scores [t][i]; the same bytes stage log_alpha (fp32) in step A
-constexpr int kOffGam = kOffPm + 2 * kTile64;         // A_C, 64 floats
-constexpr int kLdsBytes = kOffGam + 64 * 4;
+// ---- LDS map (bytes).  Two buffers (chunk parity) of what the gate wavefronts hand to the state wavefronts.
+constexpr int kQnTile = kTile * 128;                 // q .* A,      [16 rows][64 ch] bf16, 16-byte units swizzled by row
+constexpr int kKtTile = kK * 32;                     // (k .* G)^T,  [64 ch (permuted)][16 tokens] bf16
+constexpr int kPdTile = kTile * 32;                  // P,           [16 t][16 i] bf16
+constexpr int kGmTile = kK * 4;                      // A_16,        [64] fp32
+constexpr int kOffQn = 0;
+constexpr int kOffKt = kOffQn + 4 * kQnTile;
+constexpr int kOffPd = kOffKt + 4 * kKtTile;
+constexpr int kOffGm = kOffPd + 4 * kPdTile;
+constexpr int kBufBytes = kOffGm + 4 * kGmTile;      // 19456
+constexpr int kOffVt = 2 * kBufBytes;                // (beta .* v)^T, private to each state wavefront: 4 tiles x [32 col][16 tok] bf16
+constexpr int kVtWave = 4 * 32 * 32;
+constexpr int kLdsBytes = kOffVt + 4 * kVtWave;      // 55296
 
-__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
-// byte offset of 16-byte unit `unit` (0..7) of row `row` in a bf16 array with 128-byte rows
-__device__ __forceinline__ int boff(int row, int unit) { return row * kRowBytes + ((unit ^ swz(row)) << 4); }
-// same for the fp32 log_alpha staging tile (256-byte rows, 16 units)
-__device__ __forceinline__ int loff(int row, int unit) { return row * 256 + ((unit ^ ((row >> 2) & 15)) << 4); }
-
-__device__ __forceinline__ bf16x8_t lds_operand(const unsigned char *base, int row, int unit)
-{
-    return *reinterpret_cast<const bf16x8_t *>(base + boff(row, unit));
-}
-
-__device__ __forceinline__ floatx16_t mfma32(bf16x8_t a, bf16x8_t b, floatx16_t c)
-{
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
-__device__ __forceinline__ floatx4_t mfma16(bf16x8_t a, bf16x8_t b, floatx4_t c)
+__device__ __forceinline__ floatx4_t mfma_k32(bf16x8_t a, bf16x8_t b, floatx4_t c)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
+// Contraction over the 16 tokens of a tile: each lane supplies 4 of them, the other 4 operand slots are zero.
+// (The 16x16x32 form is used on purpose: with the 16x16x16 bf16 instruction this compiler consumed MFMA results
+// before they were written.)
+__device__ __forceinline__ floatx4_t mfma_k16(uint2 a, uint2 b, floatx4_t c)
+{
+    const uint4 a8 = {a.x, a.y, 0u, 0u}, b8 = {b.x, b.y, 0u, 0u};
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a8), __builtin_bit_cast(bf16x8_t, b8), c, 0, 0, 0);
+}
 
-struct Prefetch {          // one chunk's global data for this thread, in flight while the previous chunk computes
-    uint4 q, k;            // 8 bf16 of one row
-    floatx4_t la[2];       // 4 log_alpha of two rows
-    uint4 v[2];            // 8 bf16 of two rows
-    floatx4_t beta[2][2];  // the matching 8 gate values
-};
+// DPP lane moves inside a row of 16 lanes.  Lanes without a source, or disabled by bank_mask (one bit per
+// group of 4 lanes), receive `old`.
+template <int kCtrl, int kBankMask>
+__device__ __forceinline__ float dpp(float old, float src)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(src), kCtrl, 0xf, kBankMask, false));
+}
+constexpr int QP(int a, int b, int c, int d) { return a | (b << 2) | (c << 4) | (d << 6); }
+constexpr int kRowShl = 0x100, kRowShr = 0x110;
 
 struct Geometry {
     const bf16_t *q, *k, *v;
     const float *la, *beta;
+    bf16_t *o;
     int T, H, dv;
-    int b, h, j0;          // batch, head, first value column of this workgroup
+    int b, h, j0;
 };
 
-// Issue the global loads of the chunk starting at token s.  Rows at or beyond T read as q = k = v = 0,
-// log_alpha = 0 (alpha = 1): a padded row changes neither the state nor any stored output.
-__device__ __forceinline__ void prefetch_chunk(const Geometry &g, int s, int tid, Prefetch &p)
+// =========================================================================================================
+// Gate wavefronts
+// =========================================================================================================
+struct GateLoads {          // one row, 16 channels: 8g..8g+7 and 32+8g..32+8g+7
+    uint4 q[2], k[2];
+    floatx4_t la[4];
+};
+
+__device__ __forceinline__ void gate_prefetch(const Geometry &g, int t, int grp, GateLoads &p)
 {
-    const uint4 zero4 = {0u, 0u, 0u, 0u};
-    const floatx4_t zerof = {0.f, 0.f, 0.f, 0.f};
-    {
-        const int row = tid >> 3, unit = tid & 7;
-        const bool ok = s + row < g.T;
-        const size_t off = (((size_t)g.b * g.T + s + row) * g.H + g.h) * kK + unit * 8;
-        p.q = ok ? *reinterpret_cast<const uint4 *>(g.q + off) : zero4;
-        p.k = ok ? *reinterpret_cast<const uint4 *>(g.k + off) : zero4;
+    if (t < g.T) {
+        const size_t tok = ((size_t)g.b * g.T + t) * g.H + g.h;
+        const bf16_t *qp = g.q + tok * kK + 8 * grp;
+        const bf16_t *kp = g.k + tok * kK + 8 * grp;
+        const float *lp = g.la + tok * kK + 8 * grp;
+        p.q[0] = *reinterpret_cast<const uint4 *>(qp);
+        p.q[1] = *reinterpret_cast<const uint4 *>(qp + 32);
+        p.k[0] = *reinterpret_cast<const uint4 *>(kp);
+        p.k[1] = *reinterpret_cast<const uint4 *>(kp + 32);
+        p.la[0] = *reinterpret_cast<const floatx4_t *>(lp);
+        p.la[1] = *reinterpret_cast<const floatx4_t *>(lp + 4);
+        p.la[2] = *reinterpret_cast<const floatx4_t *>(lp + 32);
+        p.la[3] = *reinterpret_cast<const floatx4_t *>(lp + 36);
+    } else {                 // padded row: q = k = 0, alpha = 1
+        const uint4 z = {0u, 0u, 0u, 0u};
+        const floatx4_t zf = {0.f, 0.f, 0.f, 0.f};
+        p.q[0] = p.q[1] = p.k[0] = p.k[1] = z;
+        p.la[0] = p.la[1] = p.la[2] = p.la[3] = zf;
     }
+}
+
+__device__ __forceinline__ bf16x8_t pack8(const float *x)
+{
+    uint4 w = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7])};
+    return __builtin_bit_cast(bf16x8_t, w);
+}
+
+// scores of one split level: entries (key row m = 4*grp + r, query row n = row) of (k .* suffix)(q .* prefix)^T
+// that belong to the level
+template <int kLevel>
+__device__ __forceinline__ void level_scores(const float (&q)[16], const float (&k)[16], const float (&pre)[16],
+                                             const float (&suf)[16], int row, int grp, floatx4_t &acc)
+{
+    float xq[16], xk[16];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        const int row = (tid >> 4) + 32 * u, unit = tid & 15;
-        const bool ok = s + row < g.T;
-        const size_t tok = ((size_t)g.b * g.T + s + row) * g.H + g.h;
-        p.la[u] = ok ? *reinterpret_cast<const floatx4_t *>(g.la + tok * kK + unit * 4) : zerof;
-        const size_t voff = tok * g.dv + g.j0 + unit * 8;
-        p.v[u] = ok ? *reinterpret_cast<const uint4 *>(g.v + voff) : zero4;
-        if (g.beta != nullptr) {
-            p.beta[u][0] = ok ? *reinterpret_cast<const floatx4_t *>(g.beta + voff) : zerof;
-            p.beta[u][1] = ok ? *reinterpret_cast<const floatx4_t *>(g.beta + voff + 4) : zerof;
+    for (int c = 0; c < 16; ++c) {
+        xq[c] = q[c] * pre[c];
+        xk[c] = k[c] * suf[c];
+    }
+    floatx4_t d = {0.f, 0.f, 0.f, 0.f};
+    d = mfma_k32(pack8(xk), pack8(xq), d);
+    d = mfma_k32(pack8(xk + 8), pack8(xq + 8), d);
+    constexpr int h = 1 << kLevel;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int m = 4 * grp + r;
+        const bool keep = (row & h) && !(m & h) && ((row >> (kLevel + 1)) == (m >> (kLevel + 1)));
+        acc[r] += keep ? d[r] : 0.f;
+    }
+}
+
+// One 16-row tile: everything the state wavefronts need for it, written to the chunk buffer `buf`.
+__device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row, int grp, const GateLoads &in)
+{
+    float q[16], k[16], a[16];
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        const uint32_t qw[4] = {in.q[m].x, in.q[m].y, in.q[m].z, in.q[m].w};
+        const uint32_t kw[4] = {in.k[m].x, in.k[m].y, in.k[m].z, in.k[m].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            q[8 * m + 2 * j] = bf16_lo(qw[j]);
+            q[8 * m + 2 * j + 1] = bf16_hi(qw[j]);
+            k[8 * m + 2 * j] = bf16_lo(kw[j]);
+            k[8 * m + 2 * j + 1] = bf16_hi(kw[j]);
+            a[8 * m + j] = __expf(in.la[2 * m][j]);           // exp(-inf) = 0
+            a[8 * m + 4 + j] = __expf(in.la[2 * m + 1][j]);
+        }
+    }
+    const bool b0 = row & 1, b1 = row & 2;
+
+    floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
+    // undecayed diagonal: a token sees its own write with weight one
+    {
+        floatx4_t d = {0.f, 0.f, 0.f, 0.f};
+        d = mfma_k32(__builtin_bit_cast(bf16x8_t, in.k[0]), __builtin_bit_cast(bf16x8_t, in.q[0]), d);
+        d = mfma_k32(__builtin_bit_cast(bf16x8_t, in.k[1]), __builtin_bit_cast(bf16x8_t, in.q[1]), d);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[r] += (4 * grp + r == row) ? d[r] : 0.f;
+    }
+
+    float pre[16], suf[16];       // prefix / suffix products of the current level's blocks
+    // h = 1: blocks of one row
+#pragma unroll
+    for (int c = 0; c < 16; ++c) { pre[c] = a[c]; suf[c] = 1.f; }
+    level_scores<0>(q, k, pre, suf, row, grp, acc);
+    // h = 2: blocks of two rows
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+        const float below = dpp<QP(0, 0, 2, 2), 0xf>(1.f, a[c]);     // alpha of the row before (odd rows)
+        const float above = dpp<QP(1, 1, 3, 3), 0xf>(1.f, a[c]);     // alpha of the row after (even rows)
+        pre[c] = b0 ? a[c] * below : a[c];
+        suf[c] = b0 ? 1.f : above;
+    }
+    level_scores<1>(q, k, pre, suf, row, grp, acc);
+    // h = 4: blocks of four rows
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+        const float first_pair = dpp<QP(1, 1, 1, 1), 0xf>(1.f, pre[c]);   // product of rows 0,1 of the quad
+        const float last_pair = dpp<QP(3, 3, 3, 3), 0xf>(1.f, pre[c]);    // product of rows 2,3 of the quad
+        pre[c] = b1 ? pre[c] * first_pair : pre[c];
+        suf[c] = b1 ? suf[c] : suf[c] * last_pair;
+    }
+    level_scores<2>(q, k, pre, suf, row, grp, acc);
+    // h = 8: blocks of eight rows (quads 0,1 and quads 2,3 of the row group)
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+        const float shr = dpp<kRowShr + 1, 0xf>(1.f, pre[c]);                  // lane 4 <- lane 3, lane 12 <- lane 11
+        const float lower = dpp<QP(0, 0, 0, 0), 0xa>(1.f, shr);                // quads 1,3: whole quad before; else 1
+        const float shl = dpp<kRowShl + 4, 0xf>(1.f, pre[c]);                  // quad 0 <- quad 1, quad 2 <- quad 3
+        const float upper = dpp<QP(3, 3, 3, 3), 0x5>(1.f, shl);                // quads 0,2: whole quad after; else 1
+        pre[c] *= lower;
+        suf[c] *= upper;
+    }
+    level_scores<3>(q, k, pre, suf, row, grp, acc);
+    // h = 16: the whole tile: A_t and G_i
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+        const float shr = dpp<kRowShr + 1, 0xf>(1.f, pre[c]);                  // lane 8 <- lane 7
+        const float q2 = dpp<QP(0, 0, 0, 0), 0x4>(1.f, shr);                   // quad 2: product of rows 0..7; else 1
+        const float lower = dpp<kRowShr + 4, 0x8>(q2, q2);                     // quad 3 <- quad 2
+        const float shl = dpp<kRowShl + 8, 0xf>(1.f, pre[c]);                  // lanes 0..7 <- lanes 8..15
+        const float q1 = dpp<QP(3, 3, 3, 3), 0x2>(1.f, shl);                   // quad 1: product of rows 8..15; else 1
+        const float upper = dpp<kRowShl + 4, 0x1>(q1, q1);                     // quad 0 <- quad 1
+        pre[c] *= lower;
+        suf[c] *= upper;
+    }
+
+    // ---- hand-over to the state wavefronts
+    {
+        float x[16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) x[c] = q[c] * pre[c];                     // q .* A
+        unsigned char *qn = buf + kOffQn + tile * kQnTile + row * 128;
+        *reinterpret_cast<bf16x8_t *>(qn + (((0 + grp) ^ (row & 7)) << 4)) = pack8(x);
+        *reinterpret_cast<bf16x8_t *>(qn + (((4 + grp) ^ (row & 7)) << 4)) = pack8(x + 8);
+    }
+    {
+        // (k .* G)^T: channel n = 32m + 8grp + e goes to LDS row 16(2m + e/4) + 4(e%4) + grp, token `row` inside it
+        unsigned char *kt = buf + kOffKt + tile * kKtTile + grp * 32 + row * 2;
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            const int m = c >> 3, e = c & 7;
+            const int lrow = 16 * (2 * m + (e >> 2)) + 4 * (e & 3);
+            *reinterpret_cast<bf16_t *>(kt + lrow * 32) = (bf16_t)(k[c] * suf[c]);
+        }
+    }
+    if (row == 15) {              // decay of the whole tile
+        float *gm = reinterpret_cast<float *>(buf + kOffGm + tile * kGmTile);
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            floatx4_t lo = {pre[8 * m], pre[8 * m + 1], pre[8 * m + 2], pre[8 * m + 3]};
+            floatx4_t hi = {pre[8 * m + 4], pre[8 * m + 5], pre[8 * m + 6], pre[8 * m + 7]};
+            *reinterpret_cast<floatx4_t *>(gm + 32 * m + 8 * grp) = lo;
+            *reinterpret_cast<floatx4_t *>(gm + 32 * m + 8 * grp + 4) = hi;
+        }
+    }
+    {
+        // P[t = row][i = 4grp .. 4grp+3]
+        uint2 w = {pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3])};
+        *reinterpret_cast<uint2 *>(buf + kOffPd + tile * kPdTile + row * 32 + grp * 8) = w;
+    }
+}
+
+// =========================================================================================================
+// State wavefronts
+// =========================================================================================================
+struct StateLoads {         // 4 tiles: one token row (lane / 4), 8 value columns (8 * (lane % 4)) each
+    uint4 v[4];
+    floatx4_t beta[4][2];
+};
+
+__device__ __forceinline__ void state_prefetch(const Geometry &g, int s, int slab, int lane, bool has_beta, StateLoads &p)
+{
+    const int trow = lane >> 2, piece = lane & 3;
+#pragma unroll
+    for (int tile = 0; tile < 4; ++tile) {
+        const int t = s + 16 * tile + trow;
+        if (t < g.T) {
+            const size_t off = (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 32 * slab + 8 * piece;
+            p.v[tile] = *reinterpret_cast<const uint4 *>(g.v + off);
+            if (has_beta) {
+                p.beta[tile][0] = *reinterpret_cast<const floatx4_t *>(g.beta + off);
+                p.beta[tile][1] = *reinterpret_cast<const floatx4_t *>(g.beta + off + 4);
+            }
+        } else {
+            const uint4 z = {0u, 0u, 0u, 0u};
+            const floatx4_t zf = {0.f, 0.f, 0.f, 0.f};
+            p.v[tile] = z;
+            p.beta[tile][0] = p.beta[tile][1] = zf;
         }
     }
 }
 
-// Step A: registers -> LDS.  beta .* v is rounded to bf16 and stored transposed (one column per LDS row).
-__device__ __forceinline__ void stage_chunk(unsigned char *lds, int tid, const Prefetch &p, bool has_beta)
+// beta .* v of one chunk, rounded to bf16 and transposed into this wavefront's private LDS area.
+// Column j = 8*piece + jj of the slab is column index n = 4*piece + jj%4 of column tile ct = jj/4 and is stored
+// in LDS row 16ct + 4(n%4) + n/4 (32 bytes = 16 tokens), which spreads the 2-byte writes over all banks.
+__device__ __forceinline__ void stage_values(unsigned char *vt, int lane, bool has_beta, const StateLoads &p)
 {
-    {
-        const int row = tid >> 3, unit = tid & 7;
-        *reinterpret_cast<uint4 *>(lds + kOffQraw + boff(row, unit)) = p.q;
-        *reinterpret_cast<uint4 *>(lds + kOffKraw + boff(row, unit)) = p.k;
-    }
+    const int trow = lane >> 2, piece = lane & 3;
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        const int row = (tid >> 4) + 32 * u, unit = tid & 15;
-        *reinterpret_cast<floatx4_t *>(lds + kOffPm + loff(row, unit)) = p.la[u];
-        const uint32_t w[4] = {p.v[u].x, p.v[u].y, p.v[u].z, p.v[u].w};
+    for (int tile = 0; tile < 4; ++tile) {
+        const uint32_t w[4] = {p.v[tile].x, p.v[tile].y, p.v[tile].z, p.v[tile].w};
         float gv[8];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -133,180 +306,90 @@ __device__ __forceinline__ void stage_chunk(unsigned char *lds, int tid, const P
         if (has_beta) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                gv[j] *= p.beta[u][0][j];
-                gv[4 + j] *= p.beta[u][1][j];
+                gv[j] *= p.beta[tile][0][j];
+                gv[4 + j] *= p.beta[tile][1][j];
             }
         }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int col = unit * 8 + j;
-            *reinterpret_cast<bf16_t *>(lds + kOffGVt + boff(col, row >> 3) + 2 * (row & 7)) = (bf16_t)gv[j];
+        for (int jj = 0; jj < 8; ++jj) {
+            const int lrow = 16 * (jj >> 2) + 4 * (jj & 3) + piece;
+            *reinterpret_cast<bf16_t *>(vt + tile * 1024 + lrow * 32 + trow * 2) = (bf16_t)gv[jj];
         }
     }
 }
 
-// Step B.  Binary splitting of the pairwise decay: for a power of two h, a row t with bit h set pairs with the
-// rows i of the first half of its aligned 2h-block, and
-//     prod_{j=i+1..t} alpha_j = (prod of alpha over t's h-block from its start through t)
-//                             * (prod of alpha over the rows after i to the end of i's h-block).
-// Version array X_h holds q .* (that prefix product) in rows with bit h set and k .* (that suffix product) in
-// the others, so the level-h scores are entries of the Gram matrix X_h X_h^T.  This thread owns rows
-// 4rg..4rg+3 and channels n0, n0+1: levels 1 and 2 stay inside the thread; for h >= 4 the in-thread products
-// are extended by E (product of the whole threads before it in its aligned group) and F (threads after it),
-// obtained by a segmented scan over the 16 lanes that share the channels.  After the last level the prefix is
-// A_t and the suffix is G_i.
-__device__ __forceinline__ void build_versions(unsigned char *lds, int lane, int wave)
+struct StateSlab {
+    floatx4_t S[4][2];      // [row tile kt][column tile ct]: lane (n, grp) holds rows 4grp..4grp+3 of the tile, column n
+    bf16x8_t Sa[2][2];      // bf16 copy as MFMA operand: [ct][k half]
+};
+// Row (kt, mu) of the slab is key channel 32(kt/2) + 8(mu/4) + 4(kt%2) + mu%4, so that the 8 operand slots of a
+// lane (rows 4grp..4grp+3 of tiles 2m and 2m+1) are the 8 consecutive channels 32m + 8grp .. +7: the same
+// channels a 16-byte read of a row of q .* A delivers.
+__device__ __forceinline__ int slab_channel(int kt, int mu) { return 32 * (kt >> 1) + 8 * (mu >> 2) + 4 * (kt & 1) + (mu & 3); }
+// Column index n of column tile ct is value column 8(n/4) + 4ct + n%4 of the slab: a lane's 2 x 4 outputs are 8
+// consecutive columns, one 16-byte store.
+__device__ __forceinline__ int slab_column(int ct, int n) { return 8 * (n >> 2) + 4 * ct + (n & 3); }
+
+__device__ __forceinline__ void refresh_operands(StateSlab &st)
 {
-    const int rg = lane & 15, cpl = lane >> 4;
-    const int n0 = 2 * (4 * wave + cpl);              // first of this thread's two key channels
-    const int unit = n0 >> 3, inunit = (n0 & 7) * 2;  // 16-byte unit and byte offset inside it
-    const int lane_base = lane & ~15;
-
-    float a[4][2], q[4][2], k[4][2];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int row = 4 * rg + r;
-        const floatx2_t la = *reinterpret_cast<const floatx2_t *>(lds + kOffPm + loff(row, n0 >> 2) + (n0 & 3) * 4);
-        a[r][0] = __expf(la[0]);
-        a[r][1] = __expf(la[1]);
-        const uint32_t qw = *reinterpret_cast<const uint32_t *>(lds + kOffQraw + boff(row, unit) + inunit);
-        const uint32_t kw = *reinterpret_cast<const uint32_t *>(lds + kOffKraw + boff(row, unit) + inunit);
-        q[r][0] = bf16_lo(qw); q[r][1] = bf16_hi(qw);
-        k[r][0] = bf16_lo(kw); k[r][1] = bf16_hi(kw);
-    }
-
-    float qp[4][2], ks[4][2];     // q .* (prefix inside the thread's 4 rows), k .* (suffix inside them)
-    float p2[4][2], s2[4][2];
-    float E[5][2], F[5][2];
+    for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-        const float a01 = a[0][c] * a[1][c], a23 = a[2][c] * a[3][c];
-        p2[0][c] = a[0][c]; p2[1][c] = a01; p2[2][c] = a[2][c]; p2[3][c] = a23;
-        s2[0][c] = a[1][c]; s2[1][c] = 1.f; s2[2][c] = a[3][c]; s2[3][c] = 1.f;
-        const float p4[4] = {a[0][c], a01, a[2][c] * a01, a23 * a01};
-        const float s4[4] = {a[1][c] * a23, a23, a[3][c], 1.f};
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            qp[r][c] = q[r][c] * p4[r];
-            ks[r][c] = k[r][c] * s4[r];
+        for (int m = 0; m < 2; ++m) {
+            const floatx4_t lo = st.S[2 * m][ct], hi = st.S[2 * m + 1][ct];
+            uint4 w = {pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]), pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3])};
+            st.Sa[ct][m] = __builtin_bit_cast(bf16x8_t, w);
         }
-        const float total = p4[3];            // product over this thread's 4 rows
-        E[0][c] = 1.f; F[0][c] = 1.f;
-        float incl_pre = total, incl_suf = total;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int m = 1 << j;
-            const int last_first = (rg & ~(2 * m - 1)) + m - 1;      // last thread of the first half of the group
-            const float first_half = __shfl(incl_pre, lane_base + last_first);
-            const float second_half = __shfl(incl_suf, lane_base + last_first + 1);
-            const bool upper = (rg & m) != 0;
-            E[j + 1][c] = upper ? E[j][c] * first_half : E[j][c];
-            F[j + 1][c] = upper ? F[j][c] : F[j][c] * second_half;
-            incl_pre = E[j + 1][c] * total;
-            incl_suf = F[j + 1][c] * total;
-        }
-    }
-
-    unsigned char *X = lds + kOffX;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int row = 4 * rg + r;
-        const int off = boff(row, unit) + inunit;
-        float x0, x1;
-        // h = 1 and h = 2: the split bit is a bit of r
-        x0 = (r & 1) ? q[r][0] * a[r][0] : k[r][0];
-        x1 = (r & 1) ? q[r][1] * a[r][1] : k[r][1];
-        *reinterpret_cast<uint32_t *>(X + 0 * kTile64 + off) = pack_bf16x2(x0, x1);
-        x0 = (r & 2) ? q[r][0] * p2[r][0] : k[r][0] * s2[r][0];
-        x1 = (r & 2) ? q[r][1] * p2[r][1] : k[r][1] * s2[r][1];
-        *reinterpret_cast<uint32_t *>(X + 1 * kTile64 + off) = pack_bf16x2(x0, x1);
-        // h = 4, 8, 16, 32: the split bit is bit j of rg
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bool upper = (rg & (1 << j)) != 0;
-            x0 = upper ? qp[r][0] * E[j][0] : ks[r][0] * F[j][0];
-            x1 = upper ? qp[r][1] * E[j][1] : ks[r][1] * F[j][1];
-            *reinterpret_cast<uint32_t *>(X + (2 + j) * kTile64 + off) = pack_bf16x2(x0, x1);
-        }
-        *reinterpret_cast<uint32_t *>(lds + kOffQin + off) = pack_bf16x2(qp[r][0] * E[4][0], qp[r][1] * E[4][1]);
-    }
-    // (k .* G)^T: four consecutive tokens of one channel are 8 contiguous bytes
-#pragma unroll
-    for (int c = 0; c < 2; ++c) {
-        uint2 w;
-        w.x = pack_bf16x2(ks[0][c] * F[4][c], ks[1][c] * F[4][c]);
-        w.y = pack_bf16x2(ks[2][c] * F[4][c], ks[3][c] * F[4][c]);
-        *reinterpret_cast<uint2 *>(lds + kOffKstT + boff(n0 + c, rg >> 1) + 8 * (rg & 1)) = w;
-    }
-    if (rg == 15) {               // decay of the whole chunk, A_C
-        float *gam = reinterpret_cast<float *>(lds + kOffGam);
-        gam[n0] = a[0][0] * a[1][0] * a[2][0] * a[3][0] * E[4][0];
-        gam[n0 + 1] = a[0][1] * a[1][1] * a[2][1] * a[3][1] * E[4][1];
-    }
 }
 
-__device__ __forceinline__ void store_score_quad(unsigned char *lds, int t, int i0, float x0, float x1, float x2, float x3)
+// One chunk (4 tiles) of the state recurrence and the outputs for this wavefront's 32 columns.
+__device__ __forceinline__ void state_chunk(const Geometry &g, const unsigned char *buf, const unsigned char *vt,
+                                            int s, int slab, int n, int grp, StateSlab &st)
 {
-    uint2 w = {pack_bf16x2(x0, x1), pack_bf16x2(x2, x3)};
-    *reinterpret_cast<uint2 *>(lds + kOffPm + boff(t, i0 >> 3) + (i0 & 7) * 2) = w;
-}
+    const int lrow_v = 4 * (n & 3) + (n >> 2);        // LDS row of column index n inside a column tile / key tile
+#pragma unroll
+    for (int tile = 0; tile < 4; ++tile) {
+        const unsigned char *qn = buf + kOffQn + tile * kQnTile + n * 128;
+        const bf16x8_t qb0 = *reinterpret_cast<const bf16x8_t *>(qn + (((0 + grp) ^ (n & 7)) << 4));
+        const bf16x8_t qb1 = *reinterpret_cast<const bf16x8_t *>(qn + (((4 + grp) ^ (n & 7)) << 4));
+        const uint2 pb = *reinterpret_cast<const uint2 *>(buf + kOffPd + tile * kPdTile + n * 32 + grp * 8);
+        uint2 va[2], ka[4];
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+            va[ct] = *reinterpret_cast<const uint2 *>(vt + tile * 1024 + (16 * ct + lrow_v) * 32 + grp * 8);
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+            ka[kt] = *reinterpret_cast<const uint2 *>(buf + kOffKt + tile * kKtTile + (16 * kt + lrow_v) * 32 + grp * 8);
 
-// Step C, score tiles.  D[m][n] = sum_n' Arow_m . Brow_n with m the key row i and n the query row t, so a lane
-// ends up with four consecutive i for one t: 8 contiguous bytes of the row-major score matrix.
-__device__ __forceinline__ void score_tiles(unsigned char *lds, int lane, int wave)
-{
-    const unsigned char *X = lds + kOffX;
-    if (wave == 0) {
-        // h = 32: queries 32..63 against keys 0..31, one 32x32 tile
-        floatx16_t d = {0.f};
-        const int n = lane & 31, half = lane >> 5;
+        // o^T[column][t] = S^T (q .* A)^T + (beta .* v)^T P^T
+        floatx4_t O[2];
 #pragma unroll
-        for (int step = 0; step < 4; ++step)
-            d = mfma32(lds_operand(X + 5 * kTile64, n, 2 * step + half),
-                       lds_operand(X + 5 * kTile64, 32 + n, 2 * step + half), d);
+        for (int ct = 0; ct < 2; ++ct) {
+            floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
+            acc = mfma_k32(st.Sa[ct][0], qb0, acc);
+            acc = mfma_k32(st.Sa[ct][1], qb1, acc);
+            O[ct] = mfma_k16(va[ct], pb, acc);
+        }
+        const int t = s + 16 * tile + n;
+        if (t < g.T) {
+            uint4 w = {pack_bf16x2(O[0][0], O[0][1]), pack_bf16x2(O[0][2], O[0][3]),
+                       pack_bf16x2(O[1][0], O[1][1]), pack_bf16x2(O[1][2], O[1][3])};
+            *reinterpret_cast<uint4 *>(g.o + (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 32 * slab + 8 * grp) = w;
+        }
+
+        // S = diag(A_16) S + (k .* G)^T (beta .* v)
+        const float *gm = reinterpret_cast<const float *>(buf + kOffGm + tile * kGmTile);
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
-            store_score_quad(lds, 32 + n, 8 * g + 4 * half, d[4 * g], d[4 * g + 1], d[4 * g + 2], d[4 * g + 3]);
-    } else if (wave == 1 || wave == 2) {
-        // h = 16: tile (queries 16..31, keys 0..15) or (queries 48..63, keys 32..47); plus one all-zero tile
-        // above the diagonal that the 32-row operand reads of step D cover
-        const int i0 = (wave == 1) ? 0 : 32, t0 = i0 + 16;
-        const int n = lane & 15, g = lane >> 4;
-        floatx4_t d = {0.f, 0.f, 0.f, 0.f};
+        for (int kt = 0; kt < 4; ++kt) {
+            const floatx4_t dec = *reinterpret_cast<const floatx4_t *>(gm + slab_channel(kt, 4 * grp));
 #pragma unroll
-        for (int kh = 0; kh < 2; ++kh)
-            d = mfma16(lds_operand(X + 4 * kTile64, i0 + n, 4 * kh + g),
-                       lds_operand(X + 4 * kTile64, t0 + n, 4 * kh + g), d);
-        store_score_quad(lds, t0 + n, i0 + 4 * g, d[0], d[1], d[2], d[3]);
-        store_score_quad(lds, i0 + n, t0 + 4 * g, 0.f, 0.f, 0.f, 0.f);
-    } else if (wave >= 4) {
-        // diagonal 16x16 tile: levels h = 1, 2, 4, 8 as masked Gram matrices, plus the undecayed diagonal
-        const int t0 = 16 * (wave - 4);
-        const int n = lane & 15, g = lane >> 4;
-        floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int lvl = 0; lvl < 4; ++lvl) {
-            const int h = 1 << lvl;
-            floatx4_t d = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kh = 0; kh < 2; ++kh) {
-                const bf16x8_t x = lds_operand(X + lvl * kTile64, t0 + n, 4 * kh + g);
-                d = mfma16(x, x, d);
-            }
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int m = 4 * g + r;      // key row inside the tile
-                const bool keep = (n & h) && !(m & h) && ((n >> (lvl + 1)) == (m >> (lvl + 1)));
-                acc[r] += keep ? d[r] : 0.f;
+            for (int ct = 0; ct < 2; ++ct) {
+                floatx4_t x = st.S[kt][ct];
+                x[0] *= dec[0]; x[1] *= dec[1]; x[2] *= dec[2]; x[3] *= dec[3];
+                st.S[kt][ct] = mfma_k16(ka[kt], va[ct], x);
             }
         }
-        floatx4_t d = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kh = 0; kh < 2; ++kh)
-            d = mfma16(lds_operand(lds + kOffKraw, t0 + n, 4 * kh + g), lds_operand(lds + kOffQraw, t0 + n, 4 * kh + g), d);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc[r] += (4 * g + r == n) ? d[r] : 0.f;
-        store_score_quad(lds, t0 + n, t0 + 4 * g, acc[0], acc[1], acc[2], acc[3]);
+        refresh_operands(st);
     }
 }
 
@@ -317,88 +400,66 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
 {
     extern __shared__ __align__(16) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int rh = wave >> 2, cs = wave & 3;          // this wavefront's 32-row half and 32-column slab
-    const int n = lane & 31, half = lane >> 5;
+    const int n = lane & 15, grp = lane >> 4;
     const int bh = blockIdx.x;
-
-    Geometry g;
-    g.q = q; g.k = k; g.v = v; g.la = log_alpha; g.beta = beta;
-    g.T = T; g.H = H; g.dv = dv;
-    g.b = bh / H; g.h = bh % H; g.j0 = blockIdx.y * kColTile;
     const bool has_beta = beta != nullptr;
 
-    // state tile in accumulators: register r holds row 32rh + 8(r/4) + 4half + r%4, column 32cs + n
-    const size_t state_base = (size_t)bh * kK * dv + g.j0 + 32 * cs + n;
-    floatx16_t S;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int row = 32 * rh + 8 * (r >> 2) + 4 * half + (r & 3);
-        S[r] = (S0 != nullptr) ? S0[state_base + (size_t)row * dv] : 0.f;
-    }
-    auto publish_state = [&]() {      // bf16 copy of the state, transposed, for the next chunk's step C
-#pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-            const int n0 = 32 * rh + 8 * gq + 4 * half;
-            uint2 w = {pack_bf16x2(S[4 * gq], S[4 * gq + 1]), pack_bf16x2(S[4 * gq + 2], S[4 * gq + 3])};
-            *reinterpret_cast<uint2 *>(lds + kOffSt + boff(32 * cs + n, n0 >> 3) + (n0 & 7) * 2) = w;
+    Geometry g;
+    g.q = q; g.k = k; g.v = v; g.la = log_alpha; g.beta = beta; g.o = o;
+    g.T = T; g.H = H; g.dv = dv;
+    g.b = bh / H; g.h = bh % H; g.j0 = blockIdx.y * kColTile;
+
+    const int nchunks = (T + kChunk - 1) / kChunk;
+
+    if (wave < 4) {
+        // ------------------------------------------------------------------ gate wavefront, tile = wave
+        GateLoads cur, nxt;
+        gate_prefetch(g, 16 * wave + n, grp, cur);
+        for (int it = 0; it <= nchunks; ++it) {
+            if (it < nchunks) {
+                if (it + 1 < nchunks) gate_prefetch(g, (it + 1) * kChunk + 16 * wave + n, grp, nxt);
+                gate_tile(lds + (it & 1) * kBufBytes, wave, n, grp, cur);
+                cur = nxt;
+            }
+            __syncthreads();
         }
-    };
-    publish_state();
-
-    Prefetch pf;
-    if (T > 0) prefetch_chunk(g, 0, tid, pf);
-
-    for (int s = 0; s < T; s += kC) {
-        // ---- A
-        stage_chunk(lds, tid, pf, has_beta);
-        if (s + kC < T) prefetch_chunk(g, s + kC, tid, pf);
-        __syncthreads();
-
-        // ---- B
-        build_versions(lds, lane, wave);
-        __syncthreads();
-
-        // ---- C
-        floatx16_t O = {0.f};
+    } else {
+        // ------------------------------------------------------------------ state wavefront, slab = wave - 4
+        const int slab = wave - 4;
+        unsigned char *vt = lds + kOffVt + slab * kVtWave;
+        StateSlab st;
+        const size_t state_base = (size_t)bh * kK * dv + g.j0 + 32 * slab;
 #pragma unroll
-        for (int step = 0; step < 4; ++step)
-            O = mfma32(lds_operand(lds + kOffQin, 32 * rh + n, 2 * step + half),
-                       lds_operand(lds + kOffSt, 32 * cs + n, 2 * step + half), O);
-        score_tiles(lds, lane, wave);
-        __syncthreads();
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    st.S[kt][ct][r] = (S0 != nullptr)
+                                          ? S0[state_base + (size_t)slab_channel(kt, 4 * grp + r) * dv + slab_column(ct, n)]
+                                          : 0.f;
+        refresh_operands(st);
 
-        // ---- D
-        bf16x8_t gv[4];
-#pragma unroll
-        for (int step = 0; step < 4; ++step) gv[step] = lds_operand(lds + kOffGVt, 32 * cs + n, 2 * step + half);
-#pragma unroll
-        for (int step = 0; step < 4; ++step)
-            if (step < 2 * (rh + 1))          // causal: rows 0..31 only see keys 0..31
-                O = mfma32(lds_operand(lds + kOffPm, 32 * rh + n, 2 * step + half), gv[step], O);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int t = s + 32 * rh + 8 * (r >> 2) + 4 * half + (r & 3);
-            if (t < T) o[(((size_t)g.b * T + t) * H + g.h) * dv + g.j0 + 32 * cs + n] = (bf16_t)O[r];
+        StateLoads pf;
+        if (nchunks > 0) state_prefetch(g, 0, slab, lane, has_beta, pf);
+        for (int it = 0; it <= nchunks; ++it) {
+            if (it >= 1) {
+                // values of chunk it-1 are in `pf`: transpose them, then fetch the next chunk's while computing
+                stage_values(vt, lane, has_beta, pf);
+                if (it < nchunks) state_prefetch(g, it * kChunk, slab, lane, has_beta, pf);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // this wavefront's transposed values are in LDS
+                state_chunk(g, lds + ((it - 1) & 1) * kBufBytes, vt, (it - 1) * kChunk, slab, n, grp, st);
+            }
+            __syncthreads();
         }
-        const float *gam = reinterpret_cast<const float *>(lds + kOffGam);
+        if (S_T != nullptr) {
 #pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-            const floatx4_t dec = *reinterpret_cast<const floatx4_t *>(gam + 32 * rh + 8 * gq + 4 * half);
+            for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) S[4 * gq + e] *= dec[e];
-        }
+                for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
-        for (int step = 0; step < 4; ++step)
-            S = mfma32(lds_operand(lds + kOffKstT, 32 * rh + n, 2 * step + half), gv[step], S);
-        publish_state();
-        __syncthreads();
-    }
-
-    if (S_T != nullptr) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = 32 * rh + 8 * (r >> 2) + 4 * half + (r & 3);
-            S_T[state_base + (size_t)row * dv] = S[r];
+                    for (int r = 0; r < 4; ++r)
+                        S_T[state_base + (size_t)slab_channel(kt, 4 * grp + r) * dv + slab_column(ct, n)] = st.S[kt][ct][r];
         }
     }
 }
@@ -407,16 +468,13 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
 
 bool scan_mfma_supports(int dk, int dv, int chunk, int io_dtype)
 {
-    return io_dtype == RODIMUS_BF16 && dk == kK && chunk == kC && dv >= kColTile && dv % kColTile == 0;
+    return io_dtype == RODIMUS_BF16 && dk == kK && chunk == kChunk && dv >= kColTile && dv % kColTile == 0;
 }
 
 hipError_t launch_scan_mfma(const ScanArgs &a)
 {
     if ((long long)a.B * a.H == 0) return hipSuccess;
     if (a.T == 0 && (a.S_T == nullptr || a.S_T == a.S0)) return hipSuccess;
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (err != hipSuccess) return err;
     dim3 grid((unsigned)(a.B * a.H), (unsigned)(a.dv / kColTile)), block(kThreads);
     hipLaunchKernelGGL(scan_mfma_kernel, grid, block, kLdsBytes, a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k,
                        (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0, (bf16_t *)a.o, a.S_T, a.T, a.H, a.dv);
