@@ -29,6 +29,21 @@
 // Global loads are issued one chunk ahead into registers by the wavefront that consumes them.
 #include "internal.h"
 
+#ifdef RODIMUS_PROF
+__device__ unsigned long long g_prof[64];
+#define PROF_T() clock64()
+#define PROF_ADD(slot, t0) do { if (blockIdx.x == 0 && blockIdx.y == 0 && lane == 0) g_prof[slot] += clock64() - (t0); } while (0)
+extern "C" int rodimus_debug_read_prof(unsigned long long *out, int reset)
+{
+    hipError_t e = hipMemcpyFromSymbol(out, HIP_SYMBOL(g_prof), sizeof(unsigned long long) * 64);
+    if (reset) { unsigned long long z[64] = {0}; hipMemcpyToSymbol(HIP_SYMBOL(g_prof), z, sizeof(z)); }
+    return (int)e;
+}
+#else
+#define PROF_T() 0ull
+#define PROF_ADD(slot, t0) do { (void)(t0); } while (0)
+#endif
+
 namespace rodimus {
 
 namespace {
@@ -66,15 +81,20 @@ __device__ __forceinline__ floatx4_t mfma_k16(uint2 a, uint2 b, floatx4_t c)
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a8), __builtin_bit_cast(bf16x8_t, b8), c, 0, 0, 0);
 }
 
-// DPP lane moves inside a row of 16 lanes.  Lanes without a source, or disabled by bank_mask (one bit per
-// group of 4 lanes), receive `old`.
-template <int kCtrl, int kBankMask>
-__device__ __forceinline__ float dpp(float old, float src)
+// Cross-lane reads inside a row group of 16 lanes (one lane per tile row).
+// dpp_any: plain DPP move (quad permute or row shift); lanes without a source read 0, which callers discard.
+template <int kCtrl>
+__device__ __forceinline__ float dpp_any(float src)
 {
-    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(src), kCtrl, 0xf, kBankMask, false));
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(src), __float_as_int(src), kCtrl, 0xf, 0xf, true));
+}
+// swizzle_lane: every lane reads lane ((lane & kAnd) | kOr) of its 32-lane half
+template <int kAnd, int kOr>
+__device__ __forceinline__ float swizzle_lane(float src)
+{
+    return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(src), kAnd | (kOr << 5)));
 }
 constexpr int QP(int a, int b, int c, int d) { return a | (b << 2) | (c << 4) | (d << 6); }
-constexpr int kRowShl = 0x100, kRowShr = 0x110;
 
 struct Geometry {
     const bf16_t *q, *k, *v;
@@ -92,22 +112,27 @@ struct GateLoads {          // one row, 16 channels: 8g..8g+7 and 32+8g..32+8g+7
     floatx4_t la[4];
 };
 
+// Loads are unconditional (the row index is clamped to the last valid token) so that they stay in flight across
+// the barrier; rows at or beyond T are neutralised when consumed (gate_tile: q = k = 0, alpha = 1).
 __device__ __forceinline__ void gate_prefetch(const Geometry &g, int t, int grp, GateLoads &p)
 {
-    if (t < g.T) {
-        const size_t tok = ((size_t)g.b * g.T + t) * g.H + g.h;
-        const bf16_t *qp = g.q + tok * kK + 8 * grp;
-        const bf16_t *kp = g.k + tok * kK + 8 * grp;
-        const float *lp = g.la + tok * kK + 8 * grp;
-        p.q[0] = *reinterpret_cast<const uint4 *>(qp);
-        p.q[1] = *reinterpret_cast<const uint4 *>(qp + 32);
-        p.k[0] = *reinterpret_cast<const uint4 *>(kp);
-        p.k[1] = *reinterpret_cast<const uint4 *>(kp + 32);
-        p.la[0] = *reinterpret_cast<const floatx4_t *>(lp);
-        p.la[1] = *reinterpret_cast<const floatx4_t *>(lp + 4);
-        p.la[2] = *reinterpret_cast<const floatx4_t *>(lp + 32);
-        p.la[3] = *reinterpret_cast<const floatx4_t *>(lp + 36);
-    } else {                 // padded row: q = k = 0, alpha = 1
+    const size_t tok = ((size_t)g.b * g.T + min(t, g.T - 1)) * g.H + g.h;
+    const bf16_t *qp = g.q + tok * kK + 8 * grp;
+    const bf16_t *kp = g.k + tok * kK + 8 * grp;
+    const float *lp = g.la + tok * kK + 8 * grp;
+    p.q[0] = *reinterpret_cast<const uint4 *>(qp);
+    p.q[1] = *reinterpret_cast<const uint4 *>(qp + 32);
+    p.k[0] = *reinterpret_cast<const uint4 *>(kp);
+    p.k[1] = *reinterpret_cast<const uint4 *>(kp + 32);
+    p.la[0] = *reinterpret_cast<const floatx4_t *>(lp);
+    p.la[1] = *reinterpret_cast<const floatx4_t *>(lp + 4);
+    p.la[2] = *reinterpret_cast<const floatx4_t *>(lp + 32);
+    p.la[3] = *reinterpret_cast<const floatx4_t *>(lp + 36);
+}
+
+__device__ __forceinline__ void gate_mask_padding(bool valid, GateLoads &p)
+{
+    if (!valid) {
         const uint4 z = {0u, 0u, 0u, 0u};
         const floatx4_t zf = {0.f, 0.f, 0.f, 0.f};
         p.q[0] = p.q[1] = p.k[0] = p.k[1] = z;
@@ -146,8 +171,9 @@ __device__ __forceinline__ void level_scores(const float (&q)[16], const float (
 }
 
 // One 16-row tile: everything the state wavefronts need for it, written to the chunk buffer `buf`.
-__device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row, int grp, const GateLoads &in)
+__device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row, int grp, GateLoads &in, bool valid)
 {
+    gate_mask_padding(valid, in);
     float q[16], k[16], a[16];
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
@@ -163,7 +189,7 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
             a[8 * m + 4 + j] = __expf(in.la[2 * m + 1][j]);
         }
     }
-    const bool b0 = row & 1, b1 = row & 2;
+    const bool b0 = row & 1, b1 = row & 2, b2 = row & 4, b3 = row & 8;
 
     floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
     // undecayed diagonal: a token sees its own write with weight one
@@ -176,15 +202,25 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
     }
 
     float pre[16], suf[16];       // prefix / suffix products of the current level's blocks
-    // h = 1: blocks of one row
+    // h = 1: blocks of one row (suffix = 1, so the key operand is k itself)
+    {
+        float xq[16];
 #pragma unroll
-    for (int c = 0; c < 16; ++c) { pre[c] = a[c]; suf[c] = 1.f; }
-    level_scores<0>(q, k, pre, suf, row, grp, acc);
+        for (int c = 0; c < 16; ++c) xq[c] = q[c] * a[c];
+        floatx4_t d = {0.f, 0.f, 0.f, 0.f};
+        d = mfma_k32(__builtin_bit_cast(bf16x8_t, in.k[0]), pack8(xq), d);
+        d = mfma_k32(__builtin_bit_cast(bf16x8_t, in.k[1]), pack8(xq + 8), d);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int m = 4 * grp + r;
+            acc[r] += ((row & 1) && !(m & 1) && ((row >> 1) == (m >> 1))) ? d[r] : 0.f;
+        }
+    }
     // h = 2: blocks of two rows
 #pragma unroll
     for (int c = 0; c < 16; ++c) {
-        const float below = dpp<QP(0, 0, 2, 2), 0xf>(1.f, a[c]);     // alpha of the row before (odd rows)
-        const float above = dpp<QP(1, 1, 3, 3), 0xf>(1.f, a[c]);     // alpha of the row after (even rows)
+        const float below = dpp_any<QP(0, 0, 2, 2)>(a[c]);     // odd rows: alpha of the row before
+        const float above = dpp_any<QP(1, 1, 3, 3)>(a[c]);     // even rows: alpha of the row after
         pre[c] = b0 ? a[c] * below : a[c];
         suf[c] = b0 ? 1.f : above;
     }
@@ -192,34 +228,28 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
     // h = 4: blocks of four rows
 #pragma unroll
     for (int c = 0; c < 16; ++c) {
-        const float first_pair = dpp<QP(1, 1, 1, 1), 0xf>(1.f, pre[c]);   // product of rows 0,1 of the quad
-        const float last_pair = dpp<QP(3, 3, 3, 3), 0xf>(1.f, pre[c]);    // product of rows 2,3 of the quad
+        const float first_pair = dpp_any<QP(1, 1, 1, 1)>(pre[c]);   // product of rows 0,1 of the quad
+        const float last_pair = dpp_any<QP(3, 3, 3, 3)>(pre[c]);    // product of rows 2,3 of the quad
         pre[c] = b1 ? pre[c] * first_pair : pre[c];
         suf[c] = b1 ? suf[c] : suf[c] * last_pair;
     }
     level_scores<2>(q, k, pre, suf, row, grp, acc);
-    // h = 8: blocks of eight rows (quads 0,1 and quads 2,3 of the row group)
+    // h = 8: blocks of eight rows
 #pragma unroll
     for (int c = 0; c < 16; ++c) {
-        const float shr = dpp<kRowShr + 1, 0xf>(1.f, pre[c]);                  // lane 4 <- lane 3, lane 12 <- lane 11
-        const float lower = dpp<QP(0, 0, 0, 0), 0xa>(1.f, shr);                // quads 1,3: whole quad before; else 1
-        const float shl = dpp<kRowShl + 4, 0xf>(1.f, pre[c]);                  // quad 0 <- quad 1, quad 2 <- quad 3
-        const float upper = dpp<QP(3, 3, 3, 3), 0x5>(1.f, shl);                // quads 0,2: whole quad after; else 1
-        pre[c] *= lower;
-        suf[c] *= upper;
+        const float first_quad = swizzle_lane<0x18, 0x03>(pre[c]);  // product of rows 0..3 of the 8-block
+        const float last_quad = swizzle_lane<0x18, 0x07>(pre[c]);   // product of rows 4..7 of the 8-block
+        pre[c] = b2 ? pre[c] * first_quad : pre[c];
+        suf[c] = b2 ? suf[c] : suf[c] * last_quad;
     }
     level_scores<3>(q, k, pre, suf, row, grp, acc);
     // h = 16: the whole tile: A_t and G_i
 #pragma unroll
     for (int c = 0; c < 16; ++c) {
-        const float shr = dpp<kRowShr + 1, 0xf>(1.f, pre[c]);                  // lane 8 <- lane 7
-        const float q2 = dpp<QP(0, 0, 0, 0), 0x4>(1.f, shr);                   // quad 2: product of rows 0..7; else 1
-        const float lower = dpp<kRowShr + 4, 0x8>(q2, q2);                     // quad 3 <- quad 2
-        const float shl = dpp<kRowShl + 8, 0xf>(1.f, pre[c]);                  // lanes 0..7 <- lanes 8..15
-        const float q1 = dpp<QP(3, 3, 3, 3), 0x2>(1.f, shl);                   // quad 1: product of rows 8..15; else 1
-        const float upper = dpp<kRowShl + 4, 0x1>(q1, q1);                     // quad 0 <- quad 1
-        pre[c] *= lower;
-        suf[c] *= upper;
+        const float first_half = swizzle_lane<0x10, 0x07>(pre[c]);  // product of rows 0..7
+        const float last_half = swizzle_lane<0x10, 0x0f>(pre[c]);   // product of rows 8..15
+        pre[c] = b3 ? pre[c] * first_half : pre[c];
+        suf[c] = b3 ? suf[c] : suf[c] * last_half;
     }
 
     // ---- hand-over to the state wavefronts
@@ -235,10 +265,12 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
         // (k .* G)^T: channel n = 32m + 8grp + e goes to LDS row 16(2m + e/4) + 4(e%4) + grp, token `row` inside it
         unsigned char *kt = buf + kOffKt + tile * kKtTile + grp * 32 + row * 2;
 #pragma unroll
-        for (int c = 0; c < 16; ++c) {
+        for (int c = 0; c < 16; c += 2) {
             const int m = c >> 3, e = c & 7;
             const int lrow = 16 * (2 * m + (e >> 2)) + 4 * (e & 3);
-            *reinterpret_cast<bf16_t *>(kt + lrow * 32) = (bf16_t)(k[c] * suf[c]);
+            const uint32_t w = pack_bf16x2(k[c] * suf[c], k[c + 1] * suf[c + 1]);
+            *reinterpret_cast<uint16_t *>(kt + lrow * 32) = (uint16_t)(w & 0xffffu);
+            *reinterpret_cast<uint16_t *>(kt + (lrow + 4) * 32) = (uint16_t)(w >> 16);
         }
     }
     if (row == 15) {              // decay of the whole tile
@@ -271,19 +303,12 @@ __device__ __forceinline__ void state_prefetch(const Geometry &g, int s, int sla
     const int trow = lane >> 2, piece = lane & 3;
 #pragma unroll
     for (int tile = 0; tile < 4; ++tile) {
-        const int t = s + 16 * tile + trow;
-        if (t < g.T) {
-            const size_t off = (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 32 * slab + 8 * piece;
-            p.v[tile] = *reinterpret_cast<const uint4 *>(g.v + off);
-            if (has_beta) {
-                p.beta[tile][0] = *reinterpret_cast<const floatx4_t *>(g.beta + off);
-                p.beta[tile][1] = *reinterpret_cast<const floatx4_t *>(g.beta + off + 4);
-            }
-        } else {
-            const uint4 z = {0u, 0u, 0u, 0u};
-            const floatx4_t zf = {0.f, 0.f, 0.f, 0.f};
-            p.v[tile] = z;
-            p.beta[tile][0] = p.beta[tile][1] = zf;
+        const int t = min(s + 16 * tile + trow, g.T - 1);       // clamped: padded rows are zeroed in stage_values
+        const size_t off = (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 32 * slab + 8 * piece;
+        p.v[tile] = *reinterpret_cast<const uint4 *>(g.v + off);
+        if (has_beta) {
+            p.beta[tile][0] = *reinterpret_cast<const floatx4_t *>(g.beta + off);
+            p.beta[tile][1] = *reinterpret_cast<const floatx4_t *>(g.beta + off + 4);
         }
     }
 }
@@ -291,12 +316,13 @@ __device__ __forceinline__ void state_prefetch(const Geometry &g, int s, int sla
 // beta .* v of one chunk, rounded to bf16 and transposed into this wavefront's private LDS area.
 // Column j = 8*piece + jj of the slab is column index n = 4*piece + jj%4 of column tile ct = jj/4 and is stored
 // in LDS row 16ct + 4(n%4) + n/4 (32 bytes = 16 tokens), which spreads the 2-byte writes over all banks.
-__device__ __forceinline__ void stage_values(unsigned char *vt, int lane, bool has_beta, const StateLoads &p)
+__device__ __forceinline__ void stage_values(unsigned char *vt, int lane, bool has_beta, const StateLoads &p, int s, int T)
 {
     const int trow = lane >> 2, piece = lane & 3;
 #pragma unroll
     for (int tile = 0; tile < 4; ++tile) {
-        const uint32_t w[4] = {p.v[tile].x, p.v[tile].y, p.v[tile].z, p.v[tile].w};
+        const bool valid = s + 16 * tile + trow < T;
+        const uint32_t w[4] = {valid ? p.v[tile].x : 0u, valid ? p.v[tile].y : 0u, valid ? p.v[tile].z : 0u, valid ? p.v[tile].w : 0u};
         float gv[8];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -413,15 +439,29 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
 
     if (wave < 4) {
         // ------------------------------------------------------------------ gate wavefront, tile = wave
-        GateLoads cur, nxt;
-        gate_prefetch(g, 16 * wave + n, grp, cur);
-        for (int it = 0; it <= nchunks; ++it) {
+        GateLoads even, odd;      // loads of even / odd chunks: no register copies between iterations
+        if (nchunks > 0) gate_prefetch(g, 16 * wave + n, grp, even);
+        for (int it = 0;;) {
+            unsigned long long t0 = PROF_T();
             if (it < nchunks) {
-                if (it + 1 < nchunks) gate_prefetch(g, (it + 1) * kChunk + 16 * wave + n, grp, nxt);
-                gate_tile(lds + (it & 1) * kBufBytes, wave, n, grp, cur);
-                cur = nxt;
+                gate_prefetch(g, (it + 1) * kChunk + 16 * wave + n, grp, odd);     // unconditional (clamped): keeps the wait counts exact
+                gate_tile(lds, wave, n, grp, even, it * kChunk + 16 * wave + n < T);
             }
+            PROF_ADD(wave * 2, t0);
+            t0 = PROF_T();
             __syncthreads();
+            PROF_ADD(wave * 2 + 1, t0);
+            if (++it > nchunks) break;
+            t0 = PROF_T();
+            if (it < nchunks) {
+                gate_prefetch(g, (it + 1) * kChunk + 16 * wave + n, grp, even);
+                gate_tile(lds + kBufBytes, wave, n, grp, odd, it * kChunk + 16 * wave + n < T);
+            }
+            PROF_ADD(wave * 2, t0);
+            t0 = PROF_T();
+            __syncthreads();
+            PROF_ADD(wave * 2 + 1, t0);
+            if (++it > nchunks) break;
         }
     } else {
         // ------------------------------------------------------------------ state wavefront, slab = wave - 4
@@ -443,14 +483,21 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
         StateLoads pf;
         if (nchunks > 0) state_prefetch(g, 0, slab, lane, has_beta, pf);
         for (int it = 0; it <= nchunks; ++it) {
-            if (it >= 1) {
-                // values of chunk it-1 are in `pf`: transpose them, then fetch the next chunk's while computing
-                stage_values(vt, lane, has_beta, pf);
-                if (it < nchunks) state_prefetch(g, it * kChunk, slab, lane, has_beta, pf);
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // this wavefront's transposed values are in LDS
+            unsigned long long t0 = PROF_T();
+            if (it >= 1)       // chunk it-1: its values were transposed at the end of the previous iteration
                 state_chunk(g, lds + ((it - 1) & 1) * kBufBytes, vt, (it - 1) * kChunk, slab, n, grp, st);
+            PROF_ADD(16 + slab * 3 + 1, t0);
+            t0 = PROF_T();
+            if (it < nchunks) {
+                // values of chunk `it` (requested one iteration ago) -> LDS, then request the next chunk's
+                stage_values(vt, lane, has_beta, pf, it * kChunk, T);
+                state_prefetch(g, (it + 1) * kChunk, slab, lane, has_beta, pf);   // unconditional (clamped), see gate_prefetch
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // this wavefront's transposed values are in LDS
             }
+            PROF_ADD(16 + slab * 3, t0);
+            t0 = PROF_T();
             __syncthreads();
+            PROF_ADD(16 + slab * 3 + 2, t0);
         }
         if (S_T != nullptr) {
 #pragma unroll
