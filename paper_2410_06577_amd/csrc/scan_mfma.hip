@@ -233,23 +233,32 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
         pre[c] = b1 ? pre[c] * first_pair : pre[c];
         suf[c] = b1 ? suf[c] : suf[c] * last_pair;
     }
+    // The cross-lane reads of the next level are issued before the score work of the current one, which hides
+    // their latency.
+    float lo[16], hi[16];
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+        lo[c] = swizzle_lane<0x18, 0x03>(pre[c]);       // product of rows 0..3 of the 8-block
+        hi[c] = swizzle_lane<0x18, 0x07>(pre[c]);       // product of rows 4..7 of the 8-block
+    }
     level_scores<2>(q, k, pre, suf, row, grp, acc);
     // h = 8: blocks of eight rows
 #pragma unroll
     for (int c = 0; c < 16; ++c) {
-        const float first_quad = swizzle_lane<0x18, 0x03>(pre[c]);  // product of rows 0..3 of the 8-block
-        const float last_quad = swizzle_lane<0x18, 0x07>(pre[c]);   // product of rows 4..7 of the 8-block
-        pre[c] = b2 ? pre[c] * first_quad : pre[c];
-        suf[c] = b2 ? suf[c] : suf[c] * last_quad;
+        pre[c] = b2 ? pre[c] * lo[c] : pre[c];
+        suf[c] = b2 ? suf[c] : suf[c] * hi[c];
+    }
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+        lo[c] = swizzle_lane<0x10, 0x07>(pre[c]);       // product of rows 0..7
+        hi[c] = swizzle_lane<0x10, 0x0f>(pre[c]);       // product of rows 8..15
     }
     level_scores<3>(q, k, pre, suf, row, grp, acc);
     // h = 16: the whole tile: A_t and G_i
 #pragma unroll
     for (int c = 0; c < 16; ++c) {
-        const float first_half = swizzle_lane<0x10, 0x07>(pre[c]);  // product of rows 0..7
-        const float last_half = swizzle_lane<0x10, 0x0f>(pre[c]);   // product of rows 8..15
-        pre[c] = b3 ? pre[c] * first_half : pre[c];
-        suf[c] = b3 ? suf[c] : suf[c] * last_half;
+        pre[c] = b3 ? pre[c] * lo[c] : pre[c];
+        suf[c] = b3 ? suf[c] : suf[c] * hi[c];
     }
 
     // ---- hand-over to the state wavefronts
@@ -368,52 +377,68 @@ __device__ __forceinline__ void refresh_operands(StateSlab &st)
         }
 }
 
-// One chunk (4 tiles) of the state recurrence and the outputs for this wavefront's 32 columns.
+struct TileOperands {       // what one tile of the state recurrence reads from LDS
+    bf16x8_t qb[2];         // rows of q .* A
+    uint2 pb;               // row of P
+    uint2 va[2], ka[4];     // (beta .* v)^T and (k .* G)^T
+    floatx4_t dec[4];       // A_16 for this lane's state rows
+};
+
+__device__ __forceinline__ void load_tile_operands(const unsigned char *buf, const unsigned char *vt, int tile, int n, int grp,
+                                                   TileOperands &op)
+{
+    const int lrow_v = 4 * (n & 3) + (n >> 2);        // LDS row of column index n inside a column tile / key tile
+    const unsigned char *qn = buf + kOffQn + tile * kQnTile + n * 128;
+    op.qb[0] = *reinterpret_cast<const bf16x8_t *>(qn + (((0 + grp) ^ (n & 7)) << 4));
+    op.qb[1] = *reinterpret_cast<const bf16x8_t *>(qn + (((4 + grp) ^ (n & 7)) << 4));
+    op.pb = *reinterpret_cast<const uint2 *>(buf + kOffPd + tile * kPdTile + n * 32 + grp * 8);
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+        op.va[ct] = *reinterpret_cast<const uint2 *>(vt + tile * 1024 + (16 * ct + lrow_v) * 32 + grp * 8);
+    const float *gm = reinterpret_cast<const float *>(buf + kOffGm + tile * kGmTile);
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {
+        op.ka[kt] = *reinterpret_cast<const uint2 *>(buf + kOffKt + tile * kKtTile + (16 * kt + lrow_v) * 32 + grp * 8);
+        op.dec[kt] = *reinterpret_cast<const floatx4_t *>(gm + slab_channel(kt, 4 * grp));
+    }
+}
+
+// One chunk (4 tiles) of the state recurrence and the outputs for this wavefront's 32 columns.  The LDS operands
+// of tile i+1 are requested before tile i is computed.
 __device__ __forceinline__ void state_chunk(const Geometry &g, const unsigned char *buf, const unsigned char *vt,
                                             int s, int slab, int n, int grp, StateSlab &st)
 {
-    const int lrow_v = 4 * (n & 3) + (n >> 2);        // LDS row of column index n inside a column tile / key tile
+    TileOperands ops[2];
+    load_tile_operands(buf, vt, 0, n, grp, ops[0]);
 #pragma unroll
     for (int tile = 0; tile < 4; ++tile) {
-        const unsigned char *qn = buf + kOffQn + tile * kQnTile + n * 128;
-        const bf16x8_t qb0 = *reinterpret_cast<const bf16x8_t *>(qn + (((0 + grp) ^ (n & 7)) << 4));
-        const bf16x8_t qb1 = *reinterpret_cast<const bf16x8_t *>(qn + (((4 + grp) ^ (n & 7)) << 4));
-        const uint2 pb = *reinterpret_cast<const uint2 *>(buf + kOffPd + tile * kPdTile + n * 32 + grp * 8);
-        uint2 va[2], ka[4];
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
-            va[ct] = *reinterpret_cast<const uint2 *>(vt + tile * 1024 + (16 * ct + lrow_v) * 32 + grp * 8);
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
-            ka[kt] = *reinterpret_cast<const uint2 *>(buf + kOffKt + tile * kKtTile + (16 * kt + lrow_v) * 32 + grp * 8);
+        if (tile + 1 < 4) load_tile_operands(buf, vt, tile + 1, n, grp, ops[(tile + 1) & 1]);
+        const TileOperands &op = ops[tile & 1];
 
         // o^T[column][t] = S^T (q .* A)^T + (beta .* v)^T P^T
         floatx4_t O[2];
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct) {
             floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
-            acc = mfma_k32(st.Sa[ct][0], qb0, acc);
-            acc = mfma_k32(st.Sa[ct][1], qb1, acc);
-            O[ct] = mfma_k16(va[ct], pb, acc);
+            acc = mfma_k32(st.Sa[ct][0], op.qb[0], acc);
+            acc = mfma_k32(st.Sa[ct][1], op.qb[1], acc);
+            O[ct] = mfma_k16(op.va[ct], op.pb, acc);
+        }
+        // S = diag(A_16) S + (k .* G)^T (beta .* v)
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt) {
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct) {
+                floatx4_t x = st.S[kt][ct];
+                x[0] *= op.dec[kt][0]; x[1] *= op.dec[kt][1]; x[2] *= op.dec[kt][2]; x[3] *= op.dec[kt][3];
+                st.S[kt][ct] = mfma_k16(op.ka[kt], op.va[ct], x);
+            }
         }
         const int t = s + 16 * tile + n;
         if (t < g.T) {
             uint4 w = {pack_bf16x2(O[0][0], O[0][1]), pack_bf16x2(O[0][2], O[0][3]),
                        pack_bf16x2(O[1][0], O[1][1]), pack_bf16x2(O[1][2], O[1][3])};
             *reinterpret_cast<uint4 *>(g.o + (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 32 * slab + 8 * grp) = w;
-        }
-
-        // S = diag(A_16) S + (k .* G)^T (beta .* v)
-        const float *gm = reinterpret_cast<const float *>(buf + kOffGm + tile * kGmTile);
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt) {
-            const floatx4_t dec = *reinterpret_cast<const floatx4_t *>(gm + slab_channel(kt, 4 * grp));
-#pragma unroll
-            for (int ct = 0; ct < 2; ++ct) {
-                floatx4_t x = st.S[kt][ct];
-                x[0] *= dec[0]; x[1] *= dec[1]; x[2] *= dec[2]; x[3] *= dec[3];
-                st.S[kt][ct] = mfma_k16(ka[kt], va[ct], x);
-            }
         }
         refresh_operands(st);
     }
