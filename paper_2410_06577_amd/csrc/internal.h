@@ -91,5 +91,6 @@ hipError_t launch_scan_generic(const ScanArgs &a);
 size_t scan_generic_lds_bytes(int dk, int chunk);
 hipError_t launch_scan_mfma(const ScanArgs &a);
 bool scan_mfma_supports(int dk, int dv, int chunk, int io_dtype);
+size_t scan_mfma_workspace_bytes(int B, int T, int H, int dv);
 
 }  // namespace rodimus

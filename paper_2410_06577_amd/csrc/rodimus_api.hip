@@ -62,7 +62,7 @@ int rodimus_chunk_scan_path(int B, int T, int H, int dk, int dv, int chunk, int 
 size_t rodimus_chunk_scan_workspace_bytes(int B, int T, int H, int dk, int dv, int chunk, int io_dtype)
 {
     if (scan_shape_status(B, T, H, dk, dv, chunk, io_dtype) != RODIMUS_OK) return 0;
-    return 0;
+    return scan_mfma_supports(dk, dv, chunk, io_dtype) ? scan_mfma_workspace_bytes(B, T, H, dv) : 0;
 }
 
 int rodimus_chunk_scan_fwd(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta,

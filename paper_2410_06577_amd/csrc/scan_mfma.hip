@@ -102,6 +102,7 @@ struct Geometry {
     bf16_t *o;
     int T, H, dv;
     int b, h, j0;
+    int t_end;              // one past the last token this workgroup processes (its segment end, <= T)
 };
 
 // =========================================================================================================
@@ -114,14 +115,17 @@ struct GateLoads {          // one row, 16 channels: 8g..8g+7 and 32+8g..32+8g+7
 
 // Loads are unconditional (the row index is clamped to the last valid token) so that they stay in flight across
 // the barrier; rows at or beyond T are neutralised when consumed (gate_tile: q = k = 0, alpha = 1).
+template <bool kSummary>
 __device__ __forceinline__ void gate_prefetch(const Geometry &g, int t, int grp, GateLoads &p)
 {
-    const size_t tok = ((size_t)g.b * g.T + min(t, g.T - 1)) * g.H + g.h;
+    const size_t tok = ((size_t)g.b * g.T + min(t, g.t_end - 1)) * g.H + g.h;
     const bf16_t *qp = g.q + tok * kK + 8 * grp;
     const bf16_t *kp = g.k + tok * kK + 8 * grp;
     const float *lp = g.la + tok * kK + 8 * grp;
-    p.q[0] = *reinterpret_cast<const uint4 *>(qp);
-    p.q[1] = *reinterpret_cast<const uint4 *>(qp + 32);
+    if (!kSummary) {
+        p.q[0] = *reinterpret_cast<const uint4 *>(qp);
+        p.q[1] = *reinterpret_cast<const uint4 *>(qp + 32);
+    }
     p.k[0] = *reinterpret_cast<const uint4 *>(kp);
     p.k[1] = *reinterpret_cast<const uint4 *>(kp + 32);
     p.la[0] = *reinterpret_cast<const floatx4_t *>(lp);
@@ -171,8 +175,10 @@ __device__ __forceinline__ void level_scores(const float (&q)[16], const float (
 }
 
 // One 16-row tile: everything the state wavefronts need for it, written to the chunk buffer `buf`.
+template <bool kSummary>
 __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row, int grp, GateLoads &in, bool valid)
 {
+    if (kSummary) { const uint4 z = {0u, 0u, 0u, 0u}; in.q[0] = in.q[1] = z; }
     gate_mask_padding(valid, in);
     float q[16], k[16], a[16];
 #pragma unroll
@@ -195,15 +201,17 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
     // undecayed diagonal: a token sees its own write with weight one
     {
         floatx4_t d = {0.f, 0.f, 0.f, 0.f};
-        d = mfma_k32(__builtin_bit_cast(bf16x8_t, in.k[0]), __builtin_bit_cast(bf16x8_t, in.q[0]), d);
-        d = mfma_k32(__builtin_bit_cast(bf16x8_t, in.k[1]), __builtin_bit_cast(bf16x8_t, in.q[1]), d);
+        if (!kSummary) {
+            d = mfma_k32(__builtin_bit_cast(bf16x8_t, in.k[0]), __builtin_bit_cast(bf16x8_t, in.q[0]), d);
+            d = mfma_k32(__builtin_bit_cast(bf16x8_t, in.k[1]), __builtin_bit_cast(bf16x8_t, in.q[1]), d);
+        }
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc[r] += (4 * grp + r == row) ? d[r] : 0.f;
     }
 
     float pre[16], suf[16];       // prefix / suffix products of the current level's blocks
     // h = 1: blocks of one row (suffix = 1, so the key operand is k itself)
-    {
+    if (!kSummary) {
         float xq[16];
 #pragma unroll
         for (int c = 0; c < 16; ++c) xq[c] = q[c] * a[c];
@@ -224,7 +232,7 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
         pre[c] = b0 ? a[c] * below : a[c];
         suf[c] = b0 ? 1.f : above;
     }
-    level_scores<1>(q, k, pre, suf, row, grp, acc);
+    if (!kSummary) level_scores<1>(q, k, pre, suf, row, grp, acc);
     // h = 4: blocks of four rows
 #pragma unroll
     for (int c = 0; c < 16; ++c) {
@@ -241,7 +249,7 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
         lo[c] = swizzle_lane<0x18, 0x03>(pre[c]);       // product of rows 0..3 of the 8-block
         hi[c] = swizzle_lane<0x18, 0x07>(pre[c]);       // product of rows 4..7 of the 8-block
     }
-    level_scores<2>(q, k, pre, suf, row, grp, acc);
+    if (!kSummary) level_scores<2>(q, k, pre, suf, row, grp, acc);
     // h = 8: blocks of eight rows
 #pragma unroll
     for (int c = 0; c < 16; ++c) {
@@ -253,7 +261,7 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
         lo[c] = swizzle_lane<0x10, 0x07>(pre[c]);       // product of rows 0..7
         hi[c] = swizzle_lane<0x10, 0x0f>(pre[c]);       // product of rows 8..15
     }
-    level_scores<3>(q, k, pre, suf, row, grp, acc);
+    if (!kSummary) level_scores<3>(q, k, pre, suf, row, grp, acc);
     // h = 16: the whole tile: A_t and G_i
 #pragma unroll
     for (int c = 0; c < 16; ++c) {
@@ -262,7 +270,7 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
     }
 
     // ---- hand-over to the state wavefronts
-    {
+    if (!kSummary) {
         float x[16];
 #pragma unroll
         for (int c = 0; c < 16; ++c) x[c] = q[c] * pre[c];                     // q .* A
@@ -292,7 +300,7 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
             *reinterpret_cast<floatx4_t *>(gm + 32 * m + 8 * grp + 4) = hi;
         }
     }
-    {
+    if (!kSummary) {
         // P[t = row][i = 4grp .. 4grp+3]
         uint2 w = {pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3])};
         *reinterpret_cast<uint2 *>(buf + kOffPd + tile * kPdTile + row * 32 + grp * 8) = w;
@@ -312,7 +320,7 @@ __device__ __forceinline__ void state_prefetch(const Geometry &g, int s, int sla
     const int trow = lane >> 2, piece = lane & 3;
 #pragma unroll
     for (int tile = 0; tile < 4; ++tile) {
-        const int t = min(s + 16 * tile + trow, g.T - 1);       // clamped: padded rows are zeroed in stage_values
+        const int t = min(s + 16 * tile + trow, g.t_end - 1);   // clamped: padded rows are zeroed in stage_values
         const size_t off = (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 32 * slab + 8 * piece;
         p.v[tile] = *reinterpret_cast<const uint4 *>(g.v + off);
         if (has_beta) {
@@ -384,14 +392,17 @@ struct TileOperands {       // what one tile of the state recurrence reads from 
     floatx4_t dec[4];       // A_16 for this lane's state rows
 };
 
+template <bool kSummary>
 __device__ __forceinline__ void load_tile_operands(const unsigned char *buf, const unsigned char *vt, int tile, int n, int grp,
                                                    TileOperands &op)
 {
     const int lrow_v = 4 * (n & 3) + (n >> 2);        // LDS row of column index n inside a column tile / key tile
-    const unsigned char *qn = buf + kOffQn + tile * kQnTile + n * 128;
-    op.qb[0] = *reinterpret_cast<const bf16x8_t *>(qn + (((0 + grp) ^ (n & 7)) << 4));
-    op.qb[1] = *reinterpret_cast<const bf16x8_t *>(qn + (((4 + grp) ^ (n & 7)) << 4));
-    op.pb = *reinterpret_cast<const uint2 *>(buf + kOffPd + tile * kPdTile + n * 32 + grp * 8);
+    if (!kSummary) {
+        const unsigned char *qn = buf + kOffQn + tile * kQnTile + n * 128;
+        op.qb[0] = *reinterpret_cast<const bf16x8_t *>(qn + (((0 + grp) ^ (n & 7)) << 4));
+        op.qb[1] = *reinterpret_cast<const bf16x8_t *>(qn + (((4 + grp) ^ (n & 7)) << 4));
+        op.pb = *reinterpret_cast<const uint2 *>(buf + kOffPd + tile * kPdTile + n * 32 + grp * 8);
+    }
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct)
         op.va[ct] = *reinterpret_cast<const uint2 *>(vt + tile * 1024 + (16 * ct + lrow_v) * 32 + grp * 8);
@@ -405,24 +416,31 @@ __device__ __forceinline__ void load_tile_operands(const unsigned char *buf, con
 
 // One chunk (4 tiles) of the state recurrence and the outputs for this wavefront's 32 columns.  The LDS operands
 // of tile i+1 are requested before tile i is computed.
+template <bool kSummary>
 __device__ __forceinline__ void state_chunk(const Geometry &g, const unsigned char *buf, const unsigned char *vt,
-                                            int s, int slab, int n, int grp, StateSlab &st)
+                                            int s, int slab, int n, int grp, StateSlab &st, floatx4_t (&decay)[4])
 {
     TileOperands ops[2];
-    load_tile_operands(buf, vt, 0, n, grp, ops[0]);
+    load_tile_operands<kSummary>(buf, vt, 0, n, grp, ops[0]);
 #pragma unroll
     for (int tile = 0; tile < 4; ++tile) {
-        if (tile + 1 < 4) load_tile_operands(buf, vt, tile + 1, n, grp, ops[(tile + 1) & 1]);
+        if (tile + 1 < 4) load_tile_operands<kSummary>(buf, vt, tile + 1, n, grp, ops[(tile + 1) & 1]);
         const TileOperands &op = ops[tile & 1];
 
         // o^T[column][t] = S^T (q .* A)^T + (beta .* v)^T P^T
         floatx4_t O[2];
+        if (!kSummary) {
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct) {
-            floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
-            acc = mfma_k32(st.Sa[ct][0], op.qb[0], acc);
-            acc = mfma_k32(st.Sa[ct][1], op.qb[1], acc);
-            O[ct] = mfma_k16(op.va[ct], op.pb, acc);
+            for (int ct = 0; ct < 2; ++ct) {
+                floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
+                acc = mfma_k32(st.Sa[ct][0], op.qb[0], acc);
+                acc = mfma_k32(st.Sa[ct][1], op.qb[1], acc);
+                O[ct] = mfma_k16(op.va[ct], op.pb, acc);
+            }
+        } else {
+            // summary pass: only the segment's decay and state increment are wanted
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt) decay[kt] *= op.dec[kt];
         }
         // S = diag(A_16) S + (k .* G)^T (beta .* v)
 #pragma unroll
@@ -434,43 +452,64 @@ __device__ __forceinline__ void state_chunk(const Geometry &g, const unsigned ch
                 st.S[kt][ct] = mfma_k16(op.ka[kt], op.va[ct], x);
             }
         }
-        const int t = s + 16 * tile + n;
-        if (t < g.T) {
-            uint4 w = {pack_bf16x2(O[0][0], O[0][1]), pack_bf16x2(O[0][2], O[0][3]),
-                       pack_bf16x2(O[1][0], O[1][1]), pack_bf16x2(O[1][2], O[1][3])};
-            *reinterpret_cast<uint4 *>(g.o + (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 32 * slab + 8 * grp) = w;
+        if (!kSummary) {
+            const int t = s + 16 * tile + n;
+            if (t < g.t_end) {
+                uint4 w = {pack_bf16x2(O[0][0], O[0][1]), pack_bf16x2(O[0][2], O[0][3]),
+                           pack_bf16x2(O[1][0], O[1][1]), pack_bf16x2(O[1][2], O[1][3])};
+                *reinterpret_cast<uint4 *>(g.o + (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 32 * slab + 8 * grp) = w;
+            }
+            refresh_operands(st);
         }
-        refresh_operands(st);
     }
 }
 
+// Workspace of a sequence-split call: `nseg` state slots [seg][B*H][64][dv] fp32 followed by the segment decays
+// [nseg-1][B*H][64] fp32.  Slot 0 receives the initial state, slot s > 0 first the state increment of segment s-1
+// (summary pass), then the state entering segment s (segment_state_scan_kernel), which the main pass reads.
+struct SegmentPlan {
+    int nseg;              // 1: no split, no workspace
+    int seg_tokens;        // tokens per segment, a multiple of 64
+    float *slots;
+    float *gamma;
+};
+
+// kSummary = false: the scan proper over this workgroup's segment (blockIdx.z), reading its entering state.
+// kSummary = true : same walk from a zero state without q, scores or outputs; leaves the segment's state
+//                   increment in slot seg+1 and the segment's total decay in gamma[seg].
+template <bool kSummary>
 __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const float *__restrict__ log_alpha, const float *__restrict__ beta, const float *S0,
-    bf16_t *__restrict__ o, float *S_T, int T, int H, int dv)
+    bf16_t *__restrict__ o, float *S_T, int T, int H, int dv, SegmentPlan plan)
 {
     extern __shared__ __align__(16) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, grp = lane >> 4;
-    const int bh = blockIdx.x;
+    const int bh = blockIdx.x, seg = blockIdx.z;
+    const int BH = gridDim.x;
     const bool has_beta = beta != nullptr;
 
     Geometry g;
     g.q = q; g.k = k; g.v = v; g.la = log_alpha; g.beta = beta; g.o = o;
     g.T = T; g.H = H; g.dv = dv;
     g.b = bh / H; g.h = bh % H; g.j0 = blockIdx.y * kColTile;
+    const int t_begin = seg * plan.seg_tokens;
+    g.t_end = min(T, t_begin + plan.seg_tokens);
 
-    const int nchunks = (T + kChunk - 1) / kChunk;
+    const int nchunks = (g.t_end - t_begin + kChunk - 1) / kChunk;
+    const size_t slot_elems = (size_t)BH * kK * dv;
 
     if (wave < 4) {
         // ------------------------------------------------------------------ gate wavefront, tile = wave
         GateLoads even, odd;      // loads of even / odd chunks: no register copies between iterations
-        if (nchunks > 0) gate_prefetch(g, 16 * wave + n, grp, even);
+        const int row0 = t_begin + 16 * wave + n;
+        if (nchunks > 0) gate_prefetch<kSummary>(g, row0, grp, even);
         for (int it = 0;;) {
             unsigned long long t0 = PROF_T();
             if (it < nchunks) {
-                gate_prefetch(g, (it + 1) * kChunk + 16 * wave + n, grp, odd);     // unconditional (clamped): keeps the wait counts exact
-                gate_tile(lds, wave, n, grp, even, it * kChunk + 16 * wave + n < T);
+                gate_prefetch<kSummary>(g, row0 + (it + 1) * kChunk, grp, odd);   // unconditional (clamped): keeps the wait counts exact
+                gate_tile<kSummary>(lds, wave, n, grp, even, row0 + it * kChunk < g.t_end);
             }
             PROF_ADD(wave * 2, t0);
             t0 = PROF_T();
@@ -479,8 +518,8 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
             if (++it > nchunks) break;
             t0 = PROF_T();
             if (it < nchunks) {
-                gate_prefetch(g, (it + 1) * kChunk + 16 * wave + n, grp, even);
-                gate_tile(lds + kBufBytes, wave, n, grp, odd, it * kChunk + 16 * wave + n < T);
+                gate_prefetch<kSummary>(g, row0 + (it + 1) * kChunk, grp, even);
+                gate_tile<kSummary>(lds + kBufBytes, wave, n, grp, odd, row0 + it * kChunk < g.t_end);
             }
             PROF_ADD(wave * 2, t0);
             t0 = PROF_T();
@@ -494,29 +533,34 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
         unsigned char *vt = lds + kOffVt + slab * kVtWave;
         StateSlab st;
         const size_t state_base = (size_t)bh * kK * dv + g.j0 + 32 * slab;
+        // entering state: zero (summary), the caller's S0 (no split), or this segment's workspace slot
+        const float *S_in = kSummary ? nullptr : (plan.nseg > 1 ? plan.slots + seg * slot_elems : S0);
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    st.S[kt][ct][r] = (S0 != nullptr)
-                                          ? S0[state_base + (size_t)slab_channel(kt, 4 * grp + r) * dv + slab_column(ct, n)]
+                    st.S[kt][ct][r] = (S_in != nullptr)
+                                          ? S_in[state_base + (size_t)slab_channel(kt, 4 * grp + r) * dv + slab_column(ct, n)]
                                           : 0.f;
         refresh_operands(st);
+        floatx4_t decay[4];       // summary pass: product of the tile decays for this lane's state rows
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt) decay[kt] = floatx4_t{1.f, 1.f, 1.f, 1.f};
 
         StateLoads pf;
-        if (nchunks > 0) state_prefetch(g, 0, slab, lane, has_beta, pf);
+        if (nchunks > 0) state_prefetch(g, t_begin, slab, lane, has_beta, pf);
         for (int it = 0; it <= nchunks; ++it) {
             unsigned long long t0 = PROF_T();
             if (it >= 1)       // chunk it-1: its values were transposed at the end of the previous iteration
-                state_chunk(g, lds + ((it - 1) & 1) * kBufBytes, vt, (it - 1) * kChunk, slab, n, grp, st);
+                state_chunk<kSummary>(g, lds + ((it - 1) & 1) * kBufBytes, vt, t_begin + (it - 1) * kChunk, slab, n, grp, st, decay);
             PROF_ADD(16 + slab * 3 + 1, t0);
             t0 = PROF_T();
             if (it < nchunks) {
                 // values of chunk `it` (requested one iteration ago) -> LDS, then request the next chunk's
-                stage_values(vt, lane, has_beta, pf, it * kChunk, T);
-                state_prefetch(g, (it + 1) * kChunk, slab, lane, has_beta, pf);   // unconditional (clamped), see gate_prefetch
+                stage_values(vt, lane, has_beta, pf, t_begin + it * kChunk, g.t_end);
+                state_prefetch(g, t_begin + (it + 1) * kChunk, slab, lane, has_beta, pf);   // unconditional (clamped), see gate_prefetch
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // this wavefront's transposed values are in LDS
             }
             PROF_ADD(16 + slab * 3, t0);
@@ -524,16 +568,66 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
             __syncthreads();
             PROF_ADD(16 + slab * 3 + 2, t0);
         }
-        if (S_T != nullptr) {
+
+        float *S_out = kSummary ? plan.slots + (size_t)(seg + 1) * slot_elems : (seg == plan.nseg - 1 ? S_T : nullptr);
+        if (S_out != nullptr) {
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
                 for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
-                        S_T[state_base + (size_t)slab_channel(kt, 4 * grp + r) * dv + slab_column(ct, n)] = st.S[kt][ct][r];
+                        S_out[state_base + (size_t)slab_channel(kt, 4 * grp + r) * dv + slab_column(ct, n)] = st.S[kt][ct][r];
+        }
+        if (kSummary && blockIdx.y == 0 && slab == 0 && n == 0) {
+            float *gam = plan.gamma + ((size_t)seg * BH + bh) * kK;
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt) *reinterpret_cast<floatx4_t *>(gam + slab_channel(kt, 4 * grp)) = decay[kt];
         }
     }
+}
+
+// Entering state of every segment from the summary pass: slot 0 = S0 (or zero), and for s >= 1
+// slot s <- gamma[s-1] .* slot[s-1] + slot[s] (the increment left there by the summary pass).  One thread per
+// four adjacent state elements; the segments are walked in order.
+__global__ __launch_bounds__(256) void segment_state_scan_kernel(const float *S0, SegmentPlan plan, int dv, size_t quads_per_slot)
+{
+    const size_t e4 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e4 >= quads_per_slot) return;
+    const size_t elem = e4 * 4;                           // element index inside a slot: ((bh * 64) + n) * dv + column
+    const size_t row = elem / dv;                         // bh * 64 + n
+    floatx4_t s = (S0 != nullptr) ? *reinterpret_cast<const floatx4_t *>(S0 + elem) : floatx4_t{0.f, 0.f, 0.f, 0.f};
+    const size_t slot_elems = quads_per_slot * 4;
+    *reinterpret_cast<floatx4_t *>(plan.slots + elem) = s;
+    for (int sg = 1; sg < plan.nseg; ++sg) {
+        const float gmm = plan.gamma[(size_t)(sg - 1) * (slot_elems / dv) + row];
+        floatx4_t *p = reinterpret_cast<floatx4_t *>(plan.slots + (size_t)sg * slot_elems + elem);
+        const floatx4_t inc = *p;
+        s[0] = fmaf(gmm, s[0], inc[0]); s[1] = fmaf(gmm, s[1], inc[1]);
+        s[2] = fmaf(gmm, s[2], inc[2]); s[3] = fmaf(gmm, s[3], inc[3]);
+        *p = s;
+    }
+}
+
+// How a call is cut into sequence segments.  A single pass runs one workgroup per (batch, head, 128 columns); when
+// that leaves most of the 256 compute units idle the sequence is cut so that about 256 workgroups exist, each
+// segment keeping at least four 64-token chunks.
+struct SplitShape { int nseg, seg_tokens; };
+SplitShape choose_split(int B, int T, int H, int dv)
+{
+    const long long wgs = (long long)B * H * (dv / kColTile);
+    const int nchunks = (T + kChunk - 1) / kChunk;
+    SplitShape sp{1, nchunks * kChunk};
+    if (wgs == 0 || wgs >= 192 || nchunks < 8) return sp;
+    long long want = (256 + wgs - 1) / wgs;
+    if (want > nchunks / 4) want = nchunks / 4;
+    if (want > 64) want = 64;
+    if (want < 2) return sp;
+    const int seg_chunks = (int)((nchunks + want - 1) / want);
+    sp.nseg = (nchunks + seg_chunks - 1) / seg_chunks;
+    sp.seg_tokens = seg_chunks * kChunk;
+    if (sp.nseg < 2) sp = SplitShape{1, nchunks * kChunk};
+    return sp;
 }
 
 }  // namespace
@@ -543,13 +637,36 @@ bool scan_mfma_supports(int dk, int dv, int chunk, int io_dtype)
     return io_dtype == RODIMUS_BF16 && dk == kK && chunk == kChunk && dv >= kColTile && dv % kColTile == 0;
 }
 
+size_t scan_mfma_workspace_bytes(int B, int T, int H, int dv)
+{
+    const SplitShape sp = choose_split(B, T, H, dv);
+    if (sp.nseg <= 1) return 0;
+    const size_t bh = (size_t)B * H;
+    return ((size_t)sp.nseg * bh * kK * dv + (size_t)(sp.nseg - 1) * bh * kK) * sizeof(float);
+}
+
 hipError_t launch_scan_mfma(const ScanArgs &a)
 {
     if ((long long)a.B * a.H == 0) return hipSuccess;
     if (a.T == 0 && (a.S_T == nullptr || a.S_T == a.S0)) return hipSuccess;
-    dim3 grid((unsigned)(a.B * a.H), (unsigned)(a.dv / kColTile)), block(kThreads);
-    hipLaunchKernelGGL(scan_mfma_kernel, grid, block, kLdsBytes, a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k,
-                       (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0, (bf16_t *)a.o, a.S_T, a.T, a.H, a.dv);
+    const SplitShape sp = choose_split(a.B, a.T, a.H, a.dv);
+    const size_t bh = (size_t)a.B * a.H;
+    SegmentPlan plan{sp.nseg, sp.seg_tokens, nullptr, nullptr};
+    const dim3 block(kThreads);
+    const unsigned col_tiles = (unsigned)(a.dv / kColTile);
+    if (sp.nseg > 1) {
+        plan.slots = static_cast<float *>(a.workspace);
+        plan.gamma = plan.slots + (size_t)sp.nseg * bh * kK * a.dv;
+        hipLaunchKernelGGL(scan_mfma_kernel<true>, dim3((unsigned)bh, col_tiles, (unsigned)(sp.nseg - 1)), block, kLdsBytes,
+                           a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta,
+                           (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, a.T, a.H, a.dv, plan);
+        const size_t quads = bh * kK * a.dv / 4;
+        hipLaunchKernelGGL(segment_state_scan_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, a.stream, a.S0,
+                           plan, a.dv, quads);
+    }
+    hipLaunchKernelGGL(scan_mfma_kernel<false>, dim3((unsigned)bh, col_tiles, (unsigned)sp.nseg), block, kLdsBytes, a.stream,
+                       (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0,
+                       (bf16_t *)a.o, a.S_T, a.T, a.H, a.dv, plan);
     return hipGetLastError();
 }
 

@@ -40,6 +40,40 @@ def test_small_shapes(B, T, H, dv, s0):
     print(f"   o {eo:.2e}  S_T {es:.2e}", flush=True)
 
 
+@pytest.mark.parametrize("B,T,H,dv,s0", [
+    (1, 640, 2, 384, True),      # 10 chunks -> 2 segments of 5
+    (1, 581, 1, 128, True),      # ragged last segment
+    (2, 1100, 1, 256, False),    # 18 chunks -> 4 segments (5,5,5,3), ragged tail, zero initial state
+    (1, 4096, 2, 128, True),     # 64 chunks -> 16 segments
+])
+def test_sequence_split_path(B, T, H, dv, s0):
+    """Few (batch, head, column tile) triples: the call is cut into sequence segments (summary pass, segment scan,
+    main pass) and must still match the oracle; the final state may be written over the initial one."""
+    need = rodimus.rodimus_chunk_scan_workspace_bytes(B, T, H, 64, dv, 64, torch.bfloat16)
+    assert need > 0, "shape chosen to take the split path"
+    print(f"split B{B} T{T} H{H} dv{dv}: workspace {need} B", flush=True)
+    inp = _case(B, T, H, dv, s0, seed=T)
+    eo, es = check_scan(inp, 64, f"split B{B}T{T}H{H}dv{dv}")
+    print(f"   o {eo:.2e}  S_T {es:.2e}", flush=True)
+    if s0:
+        g = to_dev(inp)
+        state = g["S0"].clone()
+        o, _ = rodimus.rodimus_chunk_scan_fwd(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], state, chunk=64, S_T=state)
+        torch.cuda.synchronize()
+        o_ref, S_ref = oracle_scan(inp)
+        assert rel_err(o, o_ref) <= TOL_BF16 and rel_err(state, S_ref) <= TOL_BF16
+
+
+def test_split_path_rejects_small_workspace():
+    inp = _case(1, 640, 2, 384, seed=3)
+    g = to_dev(inp)
+    need = rodimus.rodimus_chunk_scan_workspace_bytes(1, 640, 2, 64, 384, 64, torch.bfloat16)
+    small = torch.empty(need - 16, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(rodimus.RodimusError) as e:
+        rodimus.rodimus_chunk_scan_fwd(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], g["S0"], chunk=64, workspace=small)
+    assert e.value.status == 5
+
+
 def test_beta_none_alpha_one_is_causal_linear_attention():
     inp = _case(1, 192, 2, 128, s0=False, seed=4)
     inp["beta"] = None
