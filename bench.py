@@ -79,7 +79,15 @@ def bench_scan(w, steps, warmup, rodimus, wl, dev):
     return res, inp, o, S_T
 
 
-def bench_decode(w, rodimus, wl, dev, warmup=20):
+def bench_scan_outputs(w, inp, rodimus, dev):
+    """One untimed scan of the given CPU inputs; returns (o, S_T) for the parity check."""
+    g = {k: (None if v is None else v.to(dev)) for k, v in inp.items()}
+    o, S_T = rodimus.rodimus_chunk_scan_fwd(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], g["S0"], chunk=w.chunk)
+    torch.cuda.synchronize()
+    return o, S_T
+
+
+def bench_decode(w, rodimus, wl, dev, warmup=100):
     d = wl.make_decode_inputs(w)
     S = d["S"].to(dev)
     ring = [{k: v.to(dev) for k, v in tok.items()} for tok in d["ring"]]
@@ -131,10 +139,11 @@ def cpu_baseline(w, inp, o_gpu, S_gpu):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--skip-decode", action="store_true")
+    ap.add_argument("--skip-other-configs", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (reference dispatch for rocprofv3 --pmc runs)")
     args = ap.parse_args()
@@ -187,6 +196,16 @@ def main():
                          "frac": dec["gbs"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES["decode_256x16"],
                          "kernel": "decode_step_kernel", "algorithmic_bytes": dec["algo_bytes"]},
         }
+    if not args.skip_other_configs:
+        del o, S_T
+        others = {}
+        for ow in (wl.MID, wl.LONG_CONTEXT):
+            r, _, _, _ = bench_scan(ow, args.steps, args.warmup, rodimus, wl, dev)
+            others[ow.name] = {"workload": f"B={ow.B} T={ow.T} H={ow.H} dk={ow.dk} dv={ow.dv} chunk={ow.chunk}",
+                               "tokens_per_s": r["tokens_per_s"], "ms_per_step": r["launch_ms"], "GB_per_s": r["gbs"],
+                               "hbm_frac": r["gbs"] / HBM_PEAK_GBS, "kernel_path": {1: "generic", 2: "mfma"}.get(r["path"])}
+        out["other_scan_configs"] = others
+        scan2, inp, o, S_T = None, inp, *bench_scan_outputs(w, inp, rodimus, dev)
     if not args.skip_cpu_baseline:
         base, parity = cpu_baseline(w, inp, o, S_T)
         out["cpu_baseline"] = base
