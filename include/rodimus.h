@@ -85,9 +85,10 @@ const char *rodimus_status_string(int status);
  *               16-byte aligned; may be NULL when that size is 0.  Contents are undefined
  *               afterwards; concurrent calls need distinct workspaces.
  *
- * Supported shapes: 1 <= dk <= 128, dv >= 1, dv % 4 == 0, chunk * dk <= 4096 (generic path);
- * the MFMA path is taken for io_dtype = BF16, dk = 64, chunk = 64, dv % 64 == 0.
- * B, T or H equal to 0 is a successful no-op.
+ * Supported shapes: 1 <= dk <= 128, dv >= 1, 1 <= chunk <= 64, chunk * dk <= 4096 (generic fp32-ALU path);
+ * the MFMA path is taken for io_dtype = BF16, dk = 64, chunk = 64, dv % 128 == 0 (it carries the state every
+ * 16 tokens internally and, when B * H * dv / 128 < 192, cuts the sequence into segments that run concurrently;
+ * only then is a workspace needed).  B, T or H equal to 0 is a successful no-op (T = 0 copies S0 to S_T).
  */
 int rodimus_chunk_scan_fwd(const void *q, const void *k, const void *v,
                            const float *log_alpha, const float *beta, const float *S0,
