@@ -153,6 +153,22 @@ def test_decode_step(N, H, dk, dv, io):
     assert rel_err(S, S_ref) <= (1e-6 if io == "f32" else tol)      # the state itself stays fp32
 
 
+def test_decode_streaming_variant_beyond_the_last_level_cache():
+    """More than 256 MiB of state switches the kernel to non-temporal accesses; results must not change."""
+    N, H = 264, 16                              # 264 * 16 * 64 KiB = 264 MiB of state
+    d = _decode_case(N, H, 64, 256, "bf16", seed=31)
+    tok = d["ring"][0]
+    g = to_dev(tok)
+    S = d["S"].to("cuda:0")
+    o = rodimus.rodimus_decode_step(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], S)
+    torch.cuda.synchronize()
+    sub = [0, 1, 131, 262, 263]
+    o_ref, S_ref = oracle.step(tok["q"][sub], tok["k"][sub], tok["v"][sub], tok["log_alpha"][sub], tok["beta"][sub],
+                               d["S"][sub])
+    assert rel_err(o[sub], o_ref) <= TOL_BF16
+    assert rel_err(S[sub], S_ref) <= 1e-6
+
+
 def test_decode_beta_none_and_alpha_zero():
     d = _decode_case(2, 2, 16, 32, "f32", seed=2)
     tok = d["ring"][0]
