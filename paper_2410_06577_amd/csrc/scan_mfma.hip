@@ -64,9 +64,11 @@ constexpr int kOffKt = kOffQn + 4 * kQnTile;
 constexpr int kOffPd = kOffKt + 4 * kKtTile;
 constexpr int kOffGm = kOffPd + 4 * kPdTile;
 constexpr int kBufBytes = kOffGm + 4 * kGmTile;      // 19456
-constexpr int kOffVt = 2 * kBufBytes;                // (beta .* v)^T, private to each state wavefront: 4 tiles x [32 col][16 tok] bf16
-constexpr int kVtWave = 4 * 32 * 32;
-constexpr int kLdsBytes = kOffVt + 4 * kVtWave;      // 55296
+constexpr int kOffVt = 2 * kBufBytes;                // (beta .* v)^T, two chunk buffers of [tile 4][slab 4][32 col][16 tok] bf16
+constexpr int kVtBuf = 4 * 4 * 1024;
+constexpr int kOffOb = kOffVt + 2 * kVtBuf;          // outputs, two chunk buffers of [64 t][128 col] bf16, 16-byte units swizzled by row
+constexpr int kObBuf = kChunk * 256;
+constexpr int kLdsBytes = kOffOb + 2 * kObBuf;       // 104448
 
 __device__ __forceinline__ floatx4_t mfma_k32(bf16x8_t a, bf16x8_t b, floatx4_t c)
 {
@@ -310,36 +312,42 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
 // =========================================================================================================
 // State wavefronts
 // =========================================================================================================
-struct StateLoads {         // 4 tiles: one token row (lane / 4), 8 value columns (8 * (lane % 4)) each
+// State wavefront `w` fetches tile w of every chunk for ALL 128 columns of the workgroup (whole 256-byte rows of v,
+// 512-byte rows of beta: long contiguous pieces are what HBM delivers at full rate) and transposes beta .* v for
+// the four state wavefronts.  Lane = (row 4u + lane/16 for u = 0..3, columns 8(lane%16) .. +7).
+struct StateLoads {
     uint4 v[4];
     floatx4_t beta[4][2];
 };
 
-__device__ __forceinline__ void state_prefetch(const Geometry &g, int s, int slab, int lane, bool has_beta, StateLoads &p)
+__device__ __forceinline__ void state_prefetch(const Geometry &g, int s, int tile, int lane, bool has_beta, StateLoads &p)
 {
-    const int trow = lane >> 2, piece = lane & 3;
+    const int rsub = lane >> 4, piece = lane & 15;
 #pragma unroll
-    for (int tile = 0; tile < 4; ++tile) {
-        const int t = min(s + 16 * tile + trow, g.t_end - 1);   // clamped: padded rows are zeroed in stage_values
-        const size_t off = (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 32 * slab + 8 * piece;
-        p.v[tile] = *reinterpret_cast<const uint4 *>(g.v + off);
+    for (int u = 0; u < 4; ++u) {
+        const int t = min(s + 16 * tile + 4 * u + rsub, g.t_end - 1);   // clamped: padded rows are zeroed in stage_values
+        const size_t off = (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 8 * piece;
+        p.v[u] = *reinterpret_cast<const uint4 *>(g.v + off);
         if (has_beta) {
-            p.beta[tile][0] = *reinterpret_cast<const floatx4_t *>(g.beta + off);
-            p.beta[tile][1] = *reinterpret_cast<const floatx4_t *>(g.beta + off + 4);
+            p.beta[u][0] = *reinterpret_cast<const floatx4_t *>(g.beta + off);
+            p.beta[u][1] = *reinterpret_cast<const floatx4_t *>(g.beta + off + 4);
         }
     }
 }
 
-// beta .* v of one chunk, rounded to bf16 and transposed into this wavefront's private LDS area.
-// Column j = 8*piece + jj of the slab is column index n = 4*piece + jj%4 of column tile ct = jj/4 and is stored
-// in LDS row 16ct + 4(n%4) + n/4 (32 bytes = 16 tokens), which spreads the 2-byte writes over all banks.
-__device__ __forceinline__ void stage_values(unsigned char *vt, int lane, bool has_beta, const StateLoads &p, int s, int T)
+// beta .* v of one tile, rounded to bf16 and transposed into the chunk buffer `vt`.  Column c = 8*piece + jj of the
+// workgroup belongs to slab c/32; inside the slab it is column index n = 4(piece%4) + jj%4 of column tile ct = jj/4
+// and lives in LDS row 16ct + 4(n%4) + n/4 (32 bytes = 16 tokens).  The 8-byte token groups of a row are XOR-ed with
+// the slab number; together with the row order this spreads the 2-byte writes over all banks.
+__device__ __forceinline__ void stage_values(unsigned char *vt, int tile, int lane, bool has_beta, const StateLoads &p, int s, int t_end)
 {
-    const int trow = lane >> 2, piece = lane & 3;
+    const int rsub = lane >> 4, piece = lane & 15;
+    const int slab = piece >> 2;
 #pragma unroll
-    for (int tile = 0; tile < 4; ++tile) {
-        const bool valid = s + 16 * tile + trow < T;
-        const uint32_t w[4] = {valid ? p.v[tile].x : 0u, valid ? p.v[tile].y : 0u, valid ? p.v[tile].z : 0u, valid ? p.v[tile].w : 0u};
+    for (int u = 0; u < 4; ++u) {
+        const int tok = 4 * u + rsub;
+        const bool valid = s + 16 * tile + tok < t_end;
+        const uint32_t w[4] = {valid ? p.v[u].x : 0u, valid ? p.v[u].y : 0u, valid ? p.v[u].z : 0u, valid ? p.v[u].w : 0u};
         float gv[8];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -349,15 +357,31 @@ __device__ __forceinline__ void stage_values(unsigned char *vt, int lane, bool h
         if (has_beta) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                gv[j] *= p.beta[tile][0][j];
-                gv[4 + j] *= p.beta[tile][1][j];
+                gv[j] *= p.beta[u][0][j];
+                gv[4 + j] *= p.beta[u][1][j];
             }
         }
+        unsigned char *dst = vt + tile * 4096 + slab * 1024 + (((tok >> 2) ^ slab) << 3) + (tok & 3) * 2;
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj) {
-            const int lrow = 16 * (jj >> 2) + 4 * (jj & 3) + piece;
-            *reinterpret_cast<bf16_t *>(vt + tile * 1024 + lrow * 32 + trow * 2) = (bf16_t)gv[jj];
+            const int lrow = 16 * (jj >> 2) + 4 * (jj & 3) + (piece & 3);
+            *reinterpret_cast<bf16_t *>(dst + lrow * 32) = (bf16_t)gv[jj];
         }
+    }
+}
+
+// Outputs of a finished chunk: LDS -> global, whole 256-byte rows.  Done by the gate wavefronts (they have slack),
+// wavefront w taking rows 16w .. 16w+15.
+__device__ __forceinline__ void store_outputs(const Geometry &g, const unsigned char *ob, int s, int wave, int lane)
+{
+    const int rsub = lane >> 4, unit = lane & 15;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int row = 16 * wave + 4 * u + rsub;
+        const uint4 w = *reinterpret_cast<const uint4 *>(ob + row * 256 + ((unit ^ (row & 15)) << 4));
+        const int t = s + row;
+        if (t < g.t_end)
+            *reinterpret_cast<uint4 *>(g.o + (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 8 * unit) = w;
     }
 }
 
@@ -393,8 +417,8 @@ struct TileOperands {       // what one tile of the state recurrence reads from 
 };
 
 template <bool kSummary>
-__device__ __forceinline__ void load_tile_operands(const unsigned char *buf, const unsigned char *vt, int tile, int n, int grp,
-                                                   TileOperands &op)
+__device__ __forceinline__ void load_tile_operands(const unsigned char *buf, const unsigned char *vt, int tile, int slab, int n,
+                                                   int grp, TileOperands &op)
 {
     const int lrow_v = 4 * (n & 3) + (n >> 2);        // LDS row of column index n inside a column tile / key tile
     if (!kSummary) {
@@ -405,7 +429,7 @@ __device__ __forceinline__ void load_tile_operands(const unsigned char *buf, con
     }
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct)
-        op.va[ct] = *reinterpret_cast<const uint2 *>(vt + tile * 1024 + (16 * ct + lrow_v) * 32 + grp * 8);
+        op.va[ct] = *reinterpret_cast<const uint2 *>(vt + tile * 4096 + slab * 1024 + (16 * ct + lrow_v) * 32 + ((grp ^ slab) << 3));
     const float *gm = reinterpret_cast<const float *>(buf + kOffGm + tile * kGmTile);
 #pragma unroll
     for (int kt = 0; kt < 4; ++kt) {
@@ -417,14 +441,14 @@ __device__ __forceinline__ void load_tile_operands(const unsigned char *buf, con
 // One chunk (4 tiles) of the state recurrence and the outputs for this wavefront's 32 columns.  The LDS operands
 // of tile i+1 are requested before tile i is computed.
 template <bool kSummary>
-__device__ __forceinline__ void state_chunk(const Geometry &g, const unsigned char *buf, const unsigned char *vt,
-                                            int s, int slab, int n, int grp, StateSlab &st, floatx4_t (&decay)[4])
+__device__ __forceinline__ void state_chunk(const unsigned char *buf, const unsigned char *vt, unsigned char *ob,
+                                            int slab, int n, int grp, StateSlab &st, floatx4_t (&decay)[4])
 {
     TileOperands ops[2];
-    load_tile_operands<kSummary>(buf, vt, 0, n, grp, ops[0]);
+    load_tile_operands<kSummary>(buf, vt, 0, slab, n, grp, ops[0]);
 #pragma unroll
     for (int tile = 0; tile < 4; ++tile) {
-        if (tile + 1 < 4) load_tile_operands<kSummary>(buf, vt, tile + 1, n, grp, ops[(tile + 1) & 1]);
+        if (tile + 1 < 4) load_tile_operands<kSummary>(buf, vt, tile + 1, slab, n, grp, ops[(tile + 1) & 1]);
         const TileOperands &op = ops[tile & 1];
 
         // o^T[column][t] = S^T (q .* A)^T + (beta .* v)^T P^T
@@ -453,12 +477,10 @@ __device__ __forceinline__ void state_chunk(const Geometry &g, const unsigned ch
             }
         }
         if (!kSummary) {
-            const int t = s + 16 * tile + n;
-            if (t < g.t_end) {
-                uint4 w = {pack_bf16x2(O[0][0], O[0][1]), pack_bf16x2(O[0][2], O[0][3]),
-                           pack_bf16x2(O[1][0], O[1][1]), pack_bf16x2(O[1][2], O[1][3])};
-                *reinterpret_cast<uint4 *>(g.o + (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 32 * slab + 8 * grp) = w;
-            }
+            // row 16tile + n of the chunk's output buffer, columns 32slab + 8grp .. +7 (16-byte unit 4slab + grp)
+            uint4 w = {pack_bf16x2(O[0][0], O[0][1]), pack_bf16x2(O[0][2], O[0][3]),
+                       pack_bf16x2(O[1][0], O[1][1]), pack_bf16x2(O[1][2], O[1][3])};
+            *reinterpret_cast<uint4 *>(ob + (16 * tile + n) * 256 + (((4 * slab + grp) ^ n) << 4)) = w;
             refresh_operands(st);
         }
     }
@@ -505,8 +527,11 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
         GateLoads even, odd;      // loads of even / odd chunks: no register copies between iterations
         const int row0 = t_begin + 16 * wave + n;
         if (nchunks > 0) gate_prefetch<kSummary>(g, row0, grp, even);
+        // Iteration `it`: store the outputs of chunk it-2 (finished by the state wavefronts in iteration it-1), then
+        // build chunk it.  nchunks + 2 iterations, one barrier each, for both kinds of wavefront.
         for (int it = 0;;) {
             unsigned long long t0 = PROF_T();
+            if (!kSummary && it >= 2) store_outputs(g, lds + kOffOb, t_begin + (it - 2) * kChunk, wave, lane);
             if (it < nchunks) {
                 gate_prefetch<kSummary>(g, row0 + (it + 1) * kChunk, grp, odd);   // unconditional (clamped): keeps the wait counts exact
                 gate_tile<kSummary>(lds, wave, n, grp, even, row0 + it * kChunk < g.t_end);
@@ -515,8 +540,9 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
             t0 = PROF_T();
             __syncthreads();
             PROF_ADD(wave * 2 + 1, t0);
-            if (++it > nchunks) break;
+            if (++it > nchunks + 1) break;
             t0 = PROF_T();
+            if (!kSummary && it >= 2) store_outputs(g, lds + kOffOb + kObBuf, t_begin + (it - 2) * kChunk, wave, lane);
             if (it < nchunks) {
                 gate_prefetch<kSummary>(g, row0 + (it + 1) * kChunk, grp, even);
                 gate_tile<kSummary>(lds + kBufBytes, wave, n, grp, odd, row0 + it * kChunk < g.t_end);
@@ -525,12 +551,11 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
             t0 = PROF_T();
             __syncthreads();
             PROF_ADD(wave * 2 + 1, t0);
-            if (++it > nchunks) break;
+            if (++it > nchunks + 1) break;
         }
     } else {
         // ------------------------------------------------------------------ state wavefront, slab = wave - 4
         const int slab = wave - 4;
-        unsigned char *vt = lds + kOffVt + slab * kVtWave;
         StateSlab st;
         const size_t state_base = (size_t)bh * kK * dv + g.j0 + 32 * slab;
         // entering state: zero (summary), the caller's S0 (no split), or this segment's workspace slot
@@ -549,19 +574,19 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt) decay[kt] = floatx4_t{1.f, 1.f, 1.f, 1.f};
 
-        StateLoads pf;
+        StateLoads pf;            // tile `slab` of the next chunk to stage, all 128 columns
         if (nchunks > 0) state_prefetch(g, t_begin, slab, lane, has_beta, pf);
-        for (int it = 0; it <= nchunks; ++it) {
+        for (int it = 0; it <= nchunks + 1; ++it) {
             unsigned long long t0 = PROF_T();
-            if (it >= 1)       // chunk it-1: its values were transposed at the end of the previous iteration
-                state_chunk<kSummary>(g, lds + ((it - 1) & 1) * kBufBytes, vt, t_begin + (it - 1) * kChunk, slab, n, grp, st, decay);
+            if (it >= 1 && it <= nchunks)      // chunk it-1: its values were staged at the end of the previous iteration
+                state_chunk<kSummary>(lds + ((it - 1) & 1) * kBufBytes, lds + kOffVt + ((it - 1) & 1) * kVtBuf,
+                                      lds + kOffOb + ((it - 1) & 1) * kObBuf, slab, n, grp, st, decay);
             PROF_ADD(16 + slab * 3 + 1, t0);
             t0 = PROF_T();
             if (it < nchunks) {
                 // values of chunk `it` (requested one iteration ago) -> LDS, then request the next chunk's
-                stage_values(vt, lane, has_beta, pf, t_begin + it * kChunk, g.t_end);
+                stage_values(lds + kOffVt + (it & 1) * kVtBuf, slab, lane, has_beta, pf, t_begin + it * kChunk, g.t_end);
                 state_prefetch(g, t_begin + (it + 1) * kChunk, slab, lane, has_beta, pf);   // unconditional (clamped), see gate_prefetch
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // this wavefront's transposed values are in LDS
             }
             PROF_ADD(16 + slab * 3, t0);
             t0 = PROF_T();
@@ -652,6 +677,12 @@ hipError_t launch_scan_mfma(const ScanArgs &a)
     const SplitShape sp = choose_split(a.B, a.T, a.H, a.dv);
     const size_t bh = (size_t)a.B * a.H;
     SegmentPlan plan{sp.nseg, sp.seg_tokens, nullptr, nullptr};
+    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel<false>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (attr == hipSuccess)
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel<true>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (attr != hipSuccess) return attr;
     const dim3 block(kThreads);
     const unsigned col_tiles = (unsigned)(a.dv / kColTile);
     if (sp.nseg > 1) {
