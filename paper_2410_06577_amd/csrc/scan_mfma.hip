@@ -152,21 +152,24 @@ __device__ __forceinline__ bf16x8_t pack8(const float *x)
     return __builtin_bit_cast(bf16x8_t, w);
 }
 
-// scores of one split level: entries (key row m = 4*grp + r, query row n = row) of (k .* suffix)(q .* prefix)^T
-// that belong to the level
+// ---- product-only construction of one tile (every split level).  Exact for any gates, including alpha = 0.
+// It works on one half of the lane's channels at a time (8 channels = the 8 operand slots of one MFMA), which
+// keeps its register footprint small; the two halves add into the same score accumulator.
+
+// scores of one split level from 8 channels: entries (key row m = 4*grp + r, query row n = row) of
+// (k .* suffix)(q .* prefix)^T that belong to the level
 template <int kLevel>
-__device__ __forceinline__ void level_scores(const float (&q)[16], const float (&k)[16], const float (&pre)[16],
-                                             const float (&suf)[16], int row, int grp, floatx4_t &acc)
+__device__ __forceinline__ void level_scores(const float (&q)[8], const float (&k)[8], const float (&pre)[8],
+                                             const float (&suf)[8], int row, int grp, floatx4_t &acc)
 {
-    float xq[16], xk[16];
+    float xq[8], xk[8];
 #pragma unroll
-    for (int c = 0; c < 16; ++c) {
+    for (int c = 0; c < 8; ++c) {
         xq[c] = q[c] * pre[c];
         xk[c] = k[c] * suf[c];
     }
-    floatx4_t d = {0.f, 0.f, 0.f, 0.f};
-    d = mfma_k32(pack8(xk), pack8(xq), d);
-    d = mfma_k32(pack8(xk + 8), pack8(xq + 8), d);
+    const floatx4_t zero = {0.f, 0.f, 0.f, 0.f};
+    const floatx4_t d = mfma_k32(pack8(xk), pack8(xq), zero);
     constexpr int h = 1 << kLevel;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -176,59 +179,41 @@ __device__ __forceinline__ void level_scores(const float (&q)[16], const float (
     }
 }
 
-// One 16-row tile: everything the state wavefronts need for it, written to the chunk buffer `buf`.
-template <bool kSummary>
-__device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row, int grp, GateLoads &in, bool valid)
+// Channels 32*kHalf + 8grp .. +7 of one tile.
+template <bool kSummary, int kHalf>
+__device__ __forceinline__ void gate_half_products(unsigned char *buf, int tile, int row, int grp, const GateLoads &in,
+                                                   floatx4_t &acc)
 {
-    if (kSummary) { const uint4 z = {0u, 0u, 0u, 0u}; in.q[0] = in.q[1] = z; }
-    gate_mask_padding(valid, in);
-    float q[16], k[16], a[16];
-#pragma unroll
-    for (int m = 0; m < 2; ++m) {
-        const uint32_t qw[4] = {in.q[m].x, in.q[m].y, in.q[m].z, in.q[m].w};
-        const uint32_t kw[4] = {in.k[m].x, in.k[m].y, in.k[m].z, in.k[m].w};
+    float q[8], k[8], a[8];
+    {
+        const uint32_t qw[4] = {in.q[kHalf].x, in.q[kHalf].y, in.q[kHalf].z, in.q[kHalf].w};
+        const uint32_t kw[4] = {in.k[kHalf].x, in.k[kHalf].y, in.k[kHalf].z, in.k[kHalf].w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            q[8 * m + 2 * j] = bf16_lo(qw[j]);
-            q[8 * m + 2 * j + 1] = bf16_hi(qw[j]);
-            k[8 * m + 2 * j] = bf16_lo(kw[j]);
-            k[8 * m + 2 * j + 1] = bf16_hi(kw[j]);
-            a[8 * m + j] = __expf(in.la[2 * m][j]);           // exp(-inf) = 0
-            a[8 * m + 4 + j] = __expf(in.la[2 * m + 1][j]);
+            q[2 * j] = bf16_lo(qw[j]);
+            q[2 * j + 1] = bf16_hi(qw[j]);
+            k[2 * j] = bf16_lo(kw[j]);
+            k[2 * j + 1] = bf16_hi(kw[j]);
+            a[j] = __expf(in.la[2 * kHalf][j]);           // exp(-inf) = 0
+            a[4 + j] = __expf(in.la[2 * kHalf + 1][j]);
         }
     }
     const bool b0 = row & 1, b1 = row & 2, b2 = row & 4, b3 = row & 8;
-
-    floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
-    // undecayed diagonal: a token sees its own write with weight one
-    {
-        floatx4_t d = {0.f, 0.f, 0.f, 0.f};
-        if (!kSummary) {
-            d = mfma_k32(__builtin_bit_cast(bf16x8_t, in.k[0]), __builtin_bit_cast(bf16x8_t, in.q[0]), d);
-            d = mfma_k32(__builtin_bit_cast(bf16x8_t, in.k[1]), __builtin_bit_cast(bf16x8_t, in.q[1]), d);
-        }
+    const floatx4_t zero = {0.f, 0.f, 0.f, 0.f};
+    if (!kSummary) {
+        // undecayed diagonal: a token sees its own write with weight one
+        const floatx4_t d = mfma_k32(__builtin_bit_cast(bf16x8_t, in.k[kHalf]), __builtin_bit_cast(bf16x8_t, in.q[kHalf]), zero);
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc[r] += (4 * grp + r == row) ? d[r] : 0.f;
     }
-
-    float pre[16], suf[16];       // prefix / suffix products of the current level's blocks
-    // h = 1: blocks of one row (suffix = 1, so the key operand is k itself)
-    if (!kSummary) {
-        float xq[16];
+    float pre[8], suf[8];         // prefix / suffix products of the current level's blocks
+    // h = 1: blocks of one row
 #pragma unroll
-        for (int c = 0; c < 16; ++c) xq[c] = q[c] * a[c];
-        floatx4_t d = {0.f, 0.f, 0.f, 0.f};
-        d = mfma_k32(__builtin_bit_cast(bf16x8_t, in.k[0]), pack8(xq), d);
-        d = mfma_k32(__builtin_bit_cast(bf16x8_t, in.k[1]), pack8(xq + 8), d);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int m = 4 * grp + r;
-            acc[r] += ((row & 1) && !(m & 1) && ((row >> 1) == (m >> 1))) ? d[r] : 0.f;
-        }
-    }
+    for (int c = 0; c < 8; ++c) { pre[c] = a[c]; suf[c] = 1.f; }
+    if (!kSummary) level_scores<0>(q, k, pre, suf, row, grp, acc);
     // h = 2: blocks of two rows
 #pragma unroll
-    for (int c = 0; c < 16; ++c) {
+    for (int c = 0; c < 8; ++c) {
         const float below = dpp_any<QP(0, 0, 2, 2)>(a[c]);     // odd rows: alpha of the row before
         const float above = dpp_any<QP(1, 1, 3, 3)>(a[c]);     // even rows: alpha of the row after
         pre[c] = b0 ? a[c] * below : a[c];
@@ -237,57 +222,169 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
     if (!kSummary) level_scores<1>(q, k, pre, suf, row, grp, acc);
     // h = 4: blocks of four rows
 #pragma unroll
-    for (int c = 0; c < 16; ++c) {
+    for (int c = 0; c < 8; ++c) {
         const float first_pair = dpp_any<QP(1, 1, 1, 1)>(pre[c]);   // product of rows 0,1 of the quad
         const float last_pair = dpp_any<QP(3, 3, 3, 3)>(pre[c]);    // product of rows 2,3 of the quad
         pre[c] = b1 ? pre[c] * first_pair : pre[c];
         suf[c] = b1 ? suf[c] : suf[c] * last_pair;
     }
-    // The cross-lane reads of the next level are issued before the score work of the current one, which hides
-    // their latency.
-    float lo[16], hi[16];
-#pragma unroll
-    for (int c = 0; c < 16; ++c) {
-        lo[c] = swizzle_lane<0x18, 0x03>(pre[c]);       // product of rows 0..3 of the 8-block
-        hi[c] = swizzle_lane<0x18, 0x07>(pre[c]);       // product of rows 4..7 of the 8-block
-    }
     if (!kSummary) level_scores<2>(q, k, pre, suf, row, grp, acc);
     // h = 8: blocks of eight rows
 #pragma unroll
-    for (int c = 0; c < 16; ++c) {
-        pre[c] = b2 ? pre[c] * lo[c] : pre[c];
-        suf[c] = b2 ? suf[c] : suf[c] * hi[c];
-    }
-#pragma unroll
-    for (int c = 0; c < 16; ++c) {
-        lo[c] = swizzle_lane<0x10, 0x07>(pre[c]);       // product of rows 0..7
-        hi[c] = swizzle_lane<0x10, 0x0f>(pre[c]);       // product of rows 8..15
+    for (int c = 0; c < 8; ++c) {
+        const float first_quad = swizzle_lane<0x18, 0x03>(pre[c]);  // product of rows 0..3 of the 8-block
+        const float last_quad = swizzle_lane<0x18, 0x07>(pre[c]);   // product of rows 4..7 of the 8-block
+        pre[c] = b2 ? pre[c] * first_quad : pre[c];
+        suf[c] = b2 ? suf[c] : suf[c] * last_quad;
     }
     if (!kSummary) level_scores<3>(q, k, pre, suf, row, grp, acc);
     // h = 16: the whole tile: A_t and G_i
 #pragma unroll
-    for (int c = 0; c < 16; ++c) {
-        pre[c] = b3 ? pre[c] * lo[c] : pre[c];
-        suf[c] = b3 ? suf[c] : suf[c] * hi[c];
+    for (int c = 0; c < 8; ++c) {
+        const float first_half = swizzle_lane<0x10, 0x07>(pre[c]);  // product of rows 0..7
+        const float last_half = swizzle_lane<0x10, 0x0f>(pre[c]);   // product of rows 8..15
+        pre[c] = b3 ? pre[c] * first_half : pre[c];
+        suf[c] = b3 ? suf[c] : suf[c] * last_half;
     }
 
     // ---- hand-over to the state wavefronts
     if (!kSummary) {
-        float x[16];
+        float x[8];
 #pragma unroll
-        for (int c = 0; c < 16; ++c) x[c] = q[c] * pre[c];                     // q .* A
+        for (int c = 0; c < 8; ++c) x[c] = q[c] * pre[c];                      // q .* A
         unsigned char *qn = buf + kOffQn + tile * kQnTile + row * 128;
-        *reinterpret_cast<bf16x8_t *>(qn + (((0 + grp) ^ (row & 7)) << 4)) = pack8(x);
-        *reinterpret_cast<bf16x8_t *>(qn + (((4 + grp) ^ (row & 7)) << 4)) = pack8(x + 8);
+        *reinterpret_cast<bf16x8_t *>(qn + (((4 * kHalf + grp) ^ (row & 7)) << 4)) = pack8(x);
     }
     {
-        // (k .* G)^T: channel n = 32m + 8grp + e goes to LDS row 16(2m + e/4) + 4(e%4) + grp, token `row` inside it
+        // (k .* G)^T: channel n = 32*kHalf + 8grp + e goes to LDS row 16(2*kHalf + e/4) + 4(e%4) + grp, token `row`
+        unsigned char *kt = buf + kOffKt + tile * kKtTile + grp * 32 + row * 2;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const int lrow = 16 * (2 * kHalf + (e >> 2)) + 4 * (e & 3);
+            const uint32_t w = pack_bf16x2(k[e] * suf[e], k[e + 1] * suf[e + 1]);
+            *reinterpret_cast<uint16_t *>(kt + lrow * 32) = (uint16_t)(w & 0xffffu);
+            *reinterpret_cast<uint16_t *>(kt + (lrow + 4) * 32) = (uint16_t)(w >> 16);
+        }
+    }
+    if (row == 15) {              // decay of the whole tile
+        float *gm = reinterpret_cast<float *>(buf + kOffGm + tile * kGmTile);
+        floatx4_t lo = {pre[0], pre[1], pre[2], pre[3]};
+        floatx4_t hi = {pre[4], pre[5], pre[6], pre[7]};
+        *reinterpret_cast<floatx4_t *>(gm + 32 * kHalf + 8 * grp) = lo;
+        *reinterpret_cast<floatx4_t *>(gm + 32 * kHalf + 8 * grp + 4) = hi;
+    }
+}
+
+template <bool kSummary>
+__device__ __forceinline__ void gate_tile_products(unsigned char *buf, int tile, int row, int grp, const GateLoads &in)
+{
+    floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
+    gate_half_products<kSummary, 0>(buf, tile, row, grp, in, acc);
+    gate_half_products<kSummary, 1>(buf, tile, row, grp, in, acc);
+    if (!kSummary) {
+        // P[t = row][i = 4grp .. 4grp+3]
+        uint2 w = {pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3])};
+        *reinterpret_cast<uint2 *>(buf + kOffPd + tile * kPdTile + row * 32 + grp * 8) = w;
+    }
+}
+
+// One 16-row tile.  The prefix products A_t of the gates are needed in any case.  When the tile's total decay A_16
+// is far from underflow in every channel (the common case), the pairwise decay inside the tile is taken as the
+// quotient A_t / A_i of the appendix's parallel form: one version of q (q .* A, which is also the inter-tile
+// operand) and one of k (k ./ A), a single masked Gram matrix, and G_i = A_16 / A_i.  Otherwise (a hard reset or
+// a very strong decay inside the tile, where 1 / A_i would overflow or divide by zero) the tile falls back to the
+// product-only construction above.  The choice is per tile and wavefront-uniform.
+constexpr float kSafeTileDecay = 8.2718061e-25f;     // 2^-80: 1 / A_i stays below 2^80, far inside bf16 and fp32 range
+
+template <bool kSummary>
+__device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row, int grp, GateLoads &in, bool valid)
+{
+    if (kSummary) { const uint4 z = {0u, 0u, 0u, 0u}; in.q[0] = in.q[1] = z; }
+    gate_mask_padding(valid, in);
+
+    float pre[16];
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            pre[8 * m + j] = __expf(in.la[2 * m][j]);           // exp(-inf) = 0
+            pre[8 * m + 4 + j] = __expf(in.la[2 * m + 1][j]);
+        }
+    const bool b0 = row & 1, b1 = row & 2, b2 = row & 4, b3 = row & 8;
+    // prefix products inside blocks of 2, 4, 8, 16 rows
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+        const float x = pre[c] * dpp_any<QP(0, 0, 2, 2)>(pre[c]);
+        pre[c] = b0 ? x : pre[c];
+    }
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+        const float x = pre[c] * dpp_any<QP(1, 1, 1, 1)>(pre[c]);
+        pre[c] = b1 ? x : pre[c];
+    }
+    float t[16];
+#pragma unroll
+    for (int c = 0; c < 16; ++c) t[c] = swizzle_lane<0x18, 0x03>(pre[c]);
+#pragma unroll
+    for (int c = 0; c < 16; ++c) pre[c] = b2 ? pre[c] * t[c] : pre[c];
+#pragma unroll
+    for (int c = 0; c < 16; ++c) t[c] = swizzle_lane<0x10, 0x07>(pre[c]);
+#pragma unroll
+    for (int c = 0; c < 16; ++c) pre[c] = b3 ? pre[c] * t[c] : pre[c];      // A_t
+    float total[16];
+#pragma unroll
+    for (int c = 0; c < 16; ++c) total[c] = swizzle_lane<0x10, 0x0f>(pre[c]);    // A_16 (row 15 of the tile)
+
+    bool weak = true;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) weak = weak && (total[c] >= kSafeTileDecay);     // false for 0 and NaN as well
+    if (__any(!weak)) {
+        gate_tile_products<kSummary>(buf, tile, row, grp, in);
+        return;
+    }
+
+    float k[16];
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        const uint32_t kw[4] = {in.k[m].x, in.k[m].y, in.k[m].z, in.k[m].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            k[8 * m + 2 * j] = bf16_lo(kw[j]) * __builtin_amdgcn_rcpf(pre[8 * m + 2 * j]);           // k ./ A
+            k[8 * m + 2 * j + 1] = bf16_hi(kw[j]) * __builtin_amdgcn_rcpf(pre[8 * m + 2 * j + 1]);
+        }
+    }
+    if (!kSummary) {
+        float q[16];
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const uint32_t qw[4] = {in.q[m].x, in.q[m].y, in.q[m].z, in.q[m].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                q[8 * m + 2 * j] = bf16_lo(qw[j]) * pre[8 * m + 2 * j];                               // q .* A
+                q[8 * m + 2 * j + 1] = bf16_hi(qw[j]) * pre[8 * m + 2 * j + 1];
+            }
+        }
+        const bf16x8_t qa0 = pack8(q), qa1 = pack8(q + 8);
+        floatx4_t d = {0.f, 0.f, 0.f, 0.f};
+        d = mfma_k32(pack8(k), qa0, d);
+        d = mfma_k32(pack8(k + 8), qa1, d);
+        unsigned char *qn = buf + kOffQn + tile * kQnTile + row * 128;
+        *reinterpret_cast<bf16x8_t *>(qn + (((0 + grp) ^ (row & 7)) << 4)) = qa0;
+        *reinterpret_cast<bf16x8_t *>(qn + (((4 + grp) ^ (row & 7)) << 4)) = qa1;
+        // P[t = row][i = 4grp .. 4grp+3], keys up to and including the query row
+        const int i0 = 4 * grp;
+        uint2 w = {pack_bf16x2(i0 <= row ? d[0] : 0.f, i0 + 1 <= row ? d[1] : 0.f),
+                   pack_bf16x2(i0 + 2 <= row ? d[2] : 0.f, i0 + 3 <= row ? d[3] : 0.f)};
+        *reinterpret_cast<uint2 *>(buf + kOffPd + tile * kPdTile + row * 32 + grp * 8) = w;
+    }
+    {
+        // (k .* G)^T with G_i = A_16 / A_i; same LDS placement as in gate_tile_products
         unsigned char *kt = buf + kOffKt + tile * kKtTile + grp * 32 + row * 2;
 #pragma unroll
         for (int c = 0; c < 16; c += 2) {
             const int m = c >> 3, e = c & 7;
             const int lrow = 16 * (2 * m + (e >> 2)) + 4 * (e & 3);
-            const uint32_t w = pack_bf16x2(k[c] * suf[c], k[c + 1] * suf[c + 1]);
+            const uint32_t w = pack_bf16x2(k[c] * total[c], k[c + 1] * total[c + 1]);
             *reinterpret_cast<uint16_t *>(kt + lrow * 32) = (uint16_t)(w & 0xffffu);
             *reinterpret_cast<uint16_t *>(kt + (lrow + 4) * 32) = (uint16_t)(w >> 16);
         }
@@ -301,11 +398,6 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
             *reinterpret_cast<floatx4_t *>(gm + 32 * m + 8 * grp) = lo;
             *reinterpret_cast<floatx4_t *>(gm + 32 * m + 8 * grp + 4) = hi;
         }
-    }
-    if (!kSummary) {
-        // P[t = row][i = 4grp .. 4grp+3]
-        uint2 w = {pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3])};
-        *reinterpret_cast<uint2 *>(buf + kOffPd + tile * kPdTile + row * 32 + grp * 8) = w;
     }
 }
 

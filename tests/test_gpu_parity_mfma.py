@@ -96,6 +96,17 @@ def test_hard_resets_and_extreme_decay():
     assert rel_err(o, o_ref) <= TOL_BF16 and rel_err(S_T, S_ref) <= TOL_BF16
 
 
+@pytest.mark.parametrize("la_value", [-3.3, -3.4, -3.5, -3.6, -8.0])
+def test_both_tile_constructions_around_the_switch(la_value):
+    """A 16-row tile uses the quotient form of the pairwise decay while its total decay stays above 2^-80 and the
+    product-only form below.  Constant log_alpha of -3.4 / -3.5 per step puts the tile total just above / below
+    that switch (exp(-16*3.4) = 2^-78.5, exp(-16*3.5) = 2^-80.8); both sides must agree with the oracle."""
+    inp = _case(1, 192, 2, 128, seed=12)
+    inp["log_alpha"][..., ::2] = la_value          # every other channel strongly decayed, the rest as drawn
+    eo, es = check_scan(inp, 64, f"la={la_value}")
+    print(f"la {la_value}: o {eo:.2e} S_T {es:.2e}", flush=True)
+
+
 def test_alpha_zero_everywhere():
     inp = _case(1, 128, 1, 128, seed=2)
     inp["log_alpha"].fill_(-float("inf"))
