@@ -34,10 +34,6 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
 MEASURED_TRAFFIC_BYTES = {"scan_layer_1p6b": 1359.3e6, "decode_256x16": 547.4e6}   # profiles/*.md
 
 
-def _events(n):
-    return [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
-
-
 def bench_scan(w, steps, warmup, rodimus, wl, dev):
     inp = wl.make_scan_inputs(w)
     g = {k: (None if v is None else v.to(dev)) for k, v in inp.items()}
@@ -53,15 +49,15 @@ def bench_scan(w, steps, warmup, rodimus, wl, dev):
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    ev = _events(steps)
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
-    for a, b in ev:
-        a.record()
+    start.record()
+    for _ in range(steps):
         step()
-        b.record()
+    stop.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    launch_ms = sum(a.elapsed_time(b) for a, b in ev) / steps
+    launch_ms = start.elapsed_time(stop) / steps      # HIP events on the launch stream around the K back-to-back launches
 
     th = w.token_heads
     state_bytes = w.B * w.H * w.dk * w.dv * 4
