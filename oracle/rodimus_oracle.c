@@ -146,3 +146,51 @@ int rodimus_oracle_step(const float *q, const float *k, const float *v,
     }
     return failed ? 2 : 0;
 }
+
+/*
+ * DDTS gate front-end (paper Sec. 3.1.2 "Design of alpha, alpha-hat and beta-hat", and the pre-processing of
+ * Sec. 3.1.3), row by row.  A row is one (token, head).  From the pre-activations z_g, z_tau (1 x dk) and z_beta
+ * (1 x dv) and the raw q, k (1 x dk):
+ *
+ *     g         = softplus(z_g)                      selection gate
+ *     tau       = sigmoid(z_tau)                     temperature gate
+ *     log_alpha = -g .* tau                          (alpha = exp(-g .* tau), the decay gate)
+ *     alpha_hat = g ^ tau                            input gate on the key side
+ *     k_out     = alpha_hat .* k / max(||k||_2, eps) k normalised (L2 over the row, eps = 1e-12), gate folded in
+ *     q_out     = q / sqrt(dk)
+ *     beta      = sigmoid(z_beta)                    input gate on the value side
+ *
+ * These are exactly the arguments the recurrence above takes (second, factored form of the transition in Sec. 3.1.1).
+ * The paper says k is "normalized" without naming the norm; L2 with the usual epsilon guard is the reading taken.
+ * z_beta / beta may be NULL together.  Everything in double; no reordering.
+ */
+static double softplus_d(double z) { return z > 0.0 ? z + log1p(exp(-z)) : log1p(exp(z)); }
+static double sigmoid_d(double z) { return z >= 0.0 ? 1.0 / (1.0 + exp(-z)) : exp(z) / (1.0 + exp(z)); }
+
+int rodimus_oracle_ddts_gates(const float *z_g, const float *z_tau, const float *z_beta,
+                              const float *q, const float *k,
+                              double *log_alpha, double *beta, double *q_out, double *k_out,
+                              long M, int dk, int dv)
+{
+    if (!z_g || !z_tau || !q || !k || !log_alpha || !q_out || !k_out) return 1;
+    if ((z_beta == NULL) != (beta == NULL)) return 1;
+    if (M < 0 || dk <= 0 || dv < 0) return 1;
+#pragma omp parallel for schedule(static)
+    for (long r = 0; r < M; ++r) {
+        const size_t o = (size_t)r * dk;
+        double norm2 = 0.0;
+        for (int n = 0; n < dk; ++n) norm2 += (double)k[o + n] * (double)k[o + n];
+        const double norm = sqrt(norm2);
+        const double inv = 1.0 / (norm > 1e-12 ? norm : 1e-12);
+        for (int n = 0; n < dk; ++n) {
+            const double g = softplus_d((double)z_g[o + n]);
+            const double tau = sigmoid_d((double)z_tau[o + n]);
+            log_alpha[o + n] = -g * tau;
+            k_out[o + n] = pow(g, tau) * (double)k[o + n] * inv;
+            q_out[o + n] = (double)q[o + n] / sqrt((double)dk);
+        }
+        if (z_beta)
+            for (int j = 0; j < dv; ++j) beta[(size_t)r * dv + j] = sigmoid_d((double)z_beta[(size_t)r * dv + j]);
+    }
+    return 0;
+}

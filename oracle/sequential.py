@@ -30,6 +30,8 @@ def _load():
         lib.rodimus_oracle_step.argtypes = [f32p, f32p, f32p, f32p, f32p, f64p, f64p] + [ctypes.c_int] * 4
         lib.rodimus_oracle_step.restype = ctypes.c_int
         lib.rodimus_oracle_threads.restype = ctypes.c_int
+        lib.rodimus_oracle_ddts_gates.argtypes = [f32p] * 5 + [f64p] * 4 + [ctypes.c_long, ctypes.c_int, ctypes.c_int]
+        lib.rodimus_oracle_ddts_gates.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -110,3 +112,30 @@ def step(q, k, v, log_alpha, beta, S):
     if rc != 0:
         raise RuntimeError(f"rodimus_oracle_step failed with code {rc}")
     return o, S
+
+
+def ddts_gates(z_g, z_tau, z_beta, q, k):
+    """DDTS gate front-end (paper Sec. 3.1.2 and the pre-processing of Sec. 3.1.3), any leading shape [..., dk] / [..., dv].
+
+    Returns float64 arrays (log_alpha, beta or None, q_out, k_out):
+    log_alpha = -softplus(z_g) * sigmoid(z_tau), beta = sigmoid(z_beta), q_out = q / sqrt(dk),
+    k_out = softplus(z_g)**sigmoid(z_tau) * k / max(||k||_2, 1e-12).
+    """
+    lib = _load()
+    z_g, z_tau, z_beta, q, k = _f32(z_g), _f32(z_tau), _f32(z_beta), _f32(q), _f32(k)
+    dk = q.shape[-1]
+    M = q.size // dk
+    dv = 0 if z_beta is None else z_beta.shape[-1]
+    assert z_g.shape == q.shape == k.shape == z_tau.shape
+    assert z_beta is None or z_beta.size == M * dv
+    la = np.empty(q.shape, np.float64)
+    qo = np.empty(q.shape, np.float64)
+    ko = np.empty(q.shape, np.float64)
+    beta = None if z_beta is None else np.empty(z_beta.shape, np.float64)
+    rc = lib.rodimus_oracle_ddts_gates(_ptr(z_g, ctypes.c_float), _ptr(z_tau, ctypes.c_float), _ptr(z_beta, ctypes.c_float),
+                                       _ptr(q, ctypes.c_float), _ptr(k, ctypes.c_float), _ptr(la, ctypes.c_double),
+                                       _ptr(beta, ctypes.c_double), _ptr(qo, ctypes.c_double), _ptr(ko, ctypes.c_double),
+                                       M, dk, dv)
+    if rc != 0:
+        raise RuntimeError(f"rodimus_oracle_ddts_gates failed with code {rc}")
+    return la, beta, qo, ko

@@ -1,0 +1,110 @@
+"""Pins for the oracle's DDTS gate front-end (CPU only): closed forms, the identities the paper states, the
+selection property of Proposition 1, and the role of the temperature."""
+import os
+
+import numpy as np
+
+import oracle
+
+
+def _gates(z_g, z_tau, k=None, q=None, z_beta=None):
+    z_g = np.atleast_2d(np.asarray(z_g, np.float32))
+    z_tau = np.atleast_2d(np.asarray(z_tau, np.float32))
+    k = np.ones_like(z_g) if k is None else np.atleast_2d(np.asarray(k, np.float32))
+    q = np.ones_like(z_g) if q is None else np.atleast_2d(np.asarray(q, np.float32))
+    return oracle.ddts_gates(z_g, z_tau, z_beta, q, k)
+
+
+def _alpha_hat(k_out, k):
+    """alpha_hat recovered from k_out = alpha_hat .* k / ||k||."""
+    k = np.atleast_2d(np.asarray(k, np.float64))
+    return k_out * np.linalg.norm(k, axis=-1, keepdims=True) / k
+
+
+def test_closed_form_values(golden_dir):
+    rows = [list(map(float, l.split())) for l in open(os.path.join(golden_dir, "ddts_gates_closed_forms.txt"))
+            if l.strip() and not l.startswith("#")]
+    for z_g, z_tau, alpha, alpha_hat in rows:
+        la, _, _, ko = _gates([[z_g]], [[z_tau]])
+        # the inputs pass through float32, so compare at float32 resolution
+        np.testing.assert_allclose(np.exp(la[0, 0]), alpha, rtol=3e-7)
+        np.testing.assert_allclose(ko[0, 0], alpha_hat, rtol=3e-7)      # k = 1, ||k|| = 1
+
+
+def test_decay_identity_and_ranges():
+    """exp(-softplus(z)) = 1 - sigmoid(z) (stated under the gate definition), hence alpha in [0, 1] at tau = 1;
+    alpha_hat >= 0 and exceeds 1 where g > 1."""
+    z = np.linspace(-30, 30, 241).astype(np.float32)[None]
+    la, _, _, ko = _gates(z, np.full_like(z, 60.0))            # tau = 1
+    one_minus_sig = 1 / (1 + np.exp(z.astype(np.float64)))     # 1 - sigmoid(z) = sigmoid(-z), without cancellation
+    np.testing.assert_allclose(np.exp(la), one_minus_sig, rtol=1e-12)
+    np.testing.assert_allclose(np.exp(la)[np.abs(z) < 5], (1 - 1 / (1 + np.exp(-z.astype(np.float64))))[np.abs(z) < 5], rtol=1e-12)
+    z_tau = np.random.default_rng(0).standard_normal(z.shape).astype(np.float32)
+    la, _, _, ko = _gates(z, z_tau)
+    assert (la <= 0).all() and (np.exp(la) <= 1).all()
+    ah = _alpha_hat(ko, np.ones_like(z))
+    assert (ah >= 0).all() and (ah[z > 2] > 1).all() and (ah[z < -2] < 1).all()
+
+
+def test_selection_property():
+    """Proposition 1: the decay of the old state and the gate on the new input move in opposite directions with the
+    selection pre-activation (d alpha / d z_g < 0 < d alpha_hat / d z_g), for any temperature."""
+    rng = np.random.default_rng(1)
+    z_g = rng.uniform(-4, 4, (1, 64)).astype(np.float32)
+    z_tau = rng.uniform(-3, 3, (1, 64)).astype(np.float32)
+    h = np.float32(1e-2)
+    la0, _, _, k0 = _gates(z_g, z_tau)
+    la1, _, _, k1 = _gates(z_g + h, z_tau)
+    assert (np.exp(la1) < np.exp(la0)).all()
+    assert (k1 > k0).all()
+
+
+def test_temperature_controls_sharpness():
+    """A smaller tau makes alpha change more slowly with g (Sec. 3.1.2, temperature gate)."""
+    z_g = np.array([[-1.0, 0.0, 0.3]], np.float32)              # g < 1
+    h = np.float32(1e-2)
+    slopes = []
+    for z_tau in (-2.0, 0.0, 2.0):
+        zt = np.full_like(z_g, z_tau)
+        a0 = np.exp(_gates(z_g, zt)[0])
+        a1 = np.exp(_gates(z_g + h, zt)[0])
+        slopes.append(np.abs(a1 - a0))
+    assert (slopes[0] < slopes[1]).all() and (slopes[1] < slopes[2]).all()
+
+
+def test_key_normalisation_query_scale_and_value_gate():
+    rng = np.random.default_rng(2)
+    M, dk, dv = 7, 16, 12
+    z_g, z_tau, q, k = (rng.standard_normal((M, dk)).astype(np.float32) for _ in range(4))
+    z_beta = rng.standard_normal((M, dv)).astype(np.float32)
+    la, beta, qo, ko = oracle.ddts_gates(z_g, z_tau, z_beta, q, k)
+    g = np.log1p(np.exp(z_g.astype(np.float64)))
+    tau = 1 / (1 + np.exp(-z_tau.astype(np.float64)))
+    np.testing.assert_allclose(la, -g * tau, rtol=1e-12)
+    np.testing.assert_allclose(np.linalg.norm(ko / g ** tau, axis=-1), 1.0, rtol=1e-12)      # unit keys before the gate
+    np.testing.assert_allclose(ko / g ** tau * np.linalg.norm(k.astype(np.float64), axis=-1, keepdims=True), k, rtol=1e-12)
+    np.testing.assert_allclose(qo, q / 4.0, rtol=1e-15)                                      # 1 / sqrt(16)
+    np.testing.assert_allclose(beta, 1 / (1 + np.exp(-z_beta.astype(np.float64))), rtol=1e-12)
+    np.testing.assert_allclose(beta + oracle.ddts_gates(z_g, z_tau, -z_beta, q, k)[1], 1.0, rtol=1e-12)
+    # a zero key stays zero instead of dividing by zero
+    k[3] = 0
+    assert np.all(oracle.ddts_gates(z_g, z_tau, None, q, k)[3][3] == 0)
+
+
+def test_gates_feed_the_recurrence():
+    """End to end on the CPU: gates -> recurrence equals the block recurrence written with alpha and alpha_hat
+    explicitly (first form of the transition in Sec. 3.1.1)."""
+    rng = np.random.default_rng(3)
+    T, dk, dv = 9, 4, 3
+    z_g, z_tau, q, k = (rng.standard_normal((1, T, 1, dk)).astype(np.float32) for _ in range(4))
+    z_beta = rng.standard_normal((1, T, 1, dv)).astype(np.float32)
+    v = rng.standard_normal((1, T, 1, dv)).astype(np.float32)
+    la, beta, qo, ko = oracle.ddts_gates(z_g, z_tau, z_beta, q, k)
+    f32 = lambda x: x.astype(np.float32)
+    o, _ = oracle.scan(f32(qo), f32(ko), v, f32(la), f32(beta))
+    # explicit form with the same float32-rounded gate values
+    a, kk, qq, bb = np.exp(f32(la).astype(np.float64)), f32(ko).astype(np.float64), f32(qo).astype(np.float64), f32(beta).astype(np.float64)
+    S = np.zeros((dk, dv))
+    for t in range(T):
+        S = a[0, t, 0][:, None] * S + np.outer(kk[0, t, 0], bb[0, t, 0] * v[0, t, 0])
+        np.testing.assert_allclose(o[0, t, 0], qq[0, t, 0] @ S, rtol=1e-12, atol=1e-14)
