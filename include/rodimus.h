@@ -121,6 +121,31 @@ int rodimus_decode_step(const void *q, const void *k, const void *v,
                         float *S, void *o,
                         int N, int H, int dk, int dv, int io_dtype, void *stream);
 
+/*
+ * DDTS gate front-end (paper Sec. 3.1.2 "Design of alpha, alpha-hat and beta-hat"; pre-processing of q and k in
+ * Sec. 3.1.3): turns the pre-activations of the gates and the raw q, k into the arguments of the two calls above.
+ * A row is one token of one head (rows = B*T*H for a scan, N*H for a decode step).
+ *     g = softplus(z_g), tau = sigmoid(z_tau)
+ *     log_alpha = -g .* tau                               (alpha = exp(-g .* tau))
+ *     k_out     = g^tau .* k / max(||k||_2, 1e-12)        (alpha-hat folded into the L2-normalised key)
+ *     q_out     = q / sqrt(dk)
+ *     beta      = sigmoid(z_beta)
+ *
+ *   z_g, z_tau  [rows, dk] io_dtype      in
+ *   z_beta      [rows, dv] io_dtype      in, or NULL (then beta must be NULL too and dv is ignored)
+ *   q, k        [rows, dk] io_dtype      in
+ *   log_alpha   [rows, dk] fp32          out
+ *   beta        [rows, dv] fp32          out
+ *   q_out,k_out [rows, dk] io_dtype      out; q_out may be the same buffer as q, k_out the same buffer as k;
+ *                                        no other overlap between an output and any other argument is allowed
+ *
+ * Supported shapes: dk a power of two in 8..512, dv % 8 == 0.  rows = 0 is a no-op.
+ */
+int rodimus_ddts_gates(const void *z_g, const void *z_tau, const void *z_beta,
+                       const void *q, const void *k,
+                       float *log_alpha, float *beta, void *q_out, void *k_out,
+                       long long rows, int dk, int dv, int io_dtype, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -1,0 +1,137 @@
+// DDTS gate front-end (paper Sec. 3.1.2, and the pre-processing of q and k in Sec. 3.1.3): from the
+// pre-activations of the selection gate, the temperature gate and the value gate, and the raw q and k, produce
+// the arguments of the recurrence:
+//     g = softplus(z_g), tau = sigmoid(z_tau)
+//     log_alpha = -g .* tau                                   (alpha = exp(-g .* tau))
+//     k_out     = g^tau .* k / max(||k||_2, 1e-12)            (input gate alpha-hat folded into the normalised key)
+//     q_out     = q / sqrt(dk)
+//     beta      = sigmoid(z_beta)
+// Elementwise apart from the key norm, hence bound by HBM bandwidth: one thread owns 8 consecutive channels of a
+// row (a row = one token of one head), the dk/8 lanes of a row reduce the squared norm by butterfly shuffles.
+// All arithmetic in fp32 with the accurate library functions.
+#include "internal.h"
+
+namespace rodimus {
+
+namespace {
+
+constexpr int kGateThreads = 256;
+
+template <typename IO> struct Vec8;
+template <> struct Vec8<float> {
+    static __device__ __forceinline__ void load(const float *p, float (&x)[8])
+    {
+        const floatx4_t a = *reinterpret_cast<const floatx4_t *>(p), b = *reinterpret_cast<const floatx4_t *>(p + 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { x[i] = a[i]; x[4 + i] = b[i]; }
+    }
+    static __device__ __forceinline__ void store(float *p, const float (&x)[8])
+    {
+        *reinterpret_cast<floatx4_t *>(p) = floatx4_t{x[0], x[1], x[2], x[3]};
+        *reinterpret_cast<floatx4_t *>(p + 4) = floatx4_t{x[4], x[5], x[6], x[7]};
+    }
+};
+template <> struct Vec8<bf16_t> {
+    static __device__ __forceinline__ void load(const bf16_t *p, float (&x)[8])
+    {
+        const uint4 w = *reinterpret_cast<const uint4 *>(p);
+        x[0] = bf16_lo(w.x); x[1] = bf16_hi(w.x); x[2] = bf16_lo(w.y); x[3] = bf16_hi(w.y);
+        x[4] = bf16_lo(w.z); x[5] = bf16_hi(w.z); x[6] = bf16_lo(w.w); x[7] = bf16_hi(w.w);
+    }
+    static __device__ __forceinline__ void store(bf16_t *p, const float (&x)[8])
+    {
+        uint4 w = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7])};
+        *reinterpret_cast<uint4 *>(p) = w;
+    }
+};
+
+__device__ __forceinline__ float sigmoid_f(float z)
+{
+    const float e = expf(-fabsf(z));                 // in (0, 1]: no overflow
+    return z >= 0.f ? 1.f / (1.f + e) : e / (1.f + e);
+}
+
+// key side: log_alpha, q_out, k_out.  lanes_per_row = dk / 8 is a power of two <= 64.
+template <typename IO>
+__global__ __launch_bounds__(kGateThreads) void ddts_key_gates_kernel(
+    const IO *__restrict__ z_g, const IO *__restrict__ z_tau, const IO *q, const IO *k,
+    float *__restrict__ log_alpha, IO *q_out, IO *k_out, long long rows, int dk, int lanes_per_row)
+{
+    const long long tid = (long long)blockIdx.x * kGateThreads + threadIdx.x;
+    const long long row = tid / lanes_per_row;
+    const int piece = (int)(tid % lanes_per_row);
+    const bool active = row < rows;                  // inactive lanes still take part in the shuffles
+    const size_t off = (size_t)(active ? row : 0) * dk + piece * 8;
+
+    float zg[8], zt[8], qv[8], kv[8];
+    Vec8<IO>::load(z_g + off, zg);
+    Vec8<IO>::load(z_tau + off, zt);
+    Vec8<IO>::load(q + off, qv);
+    Vec8<IO>::load(k + off, kv);
+
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ss = fmaf(kv[i], kv[i], ss);
+    for (int m = lanes_per_row >> 1; m > 0; m >>= 1) ss += __shfl_xor(ss, m);     // rows are aligned lane groups
+    const float inv_norm = 1.f / fmaxf(sqrtf(ss), 1e-12f);
+    const float q_scale = 1.f / sqrtf((float)dk);
+
+    float la[8], qo[8], ko[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float z = zg[i];
+        const float e = expf(-fabsf(z));
+        const float g = fmaxf(z, 0.f) + log1pf(e);                 // softplus
+        // log g: for very negative z, g = e^z (1 - e^z / 2 + ...) underflows before its logarithm does
+        const float log_g = z < -15.f ? z - 0.5f * e : logf(g);
+        const float tau = sigmoid_f(zt[i]);
+        la[i] = -g * tau;
+        ko[i] = expf(tau * log_g) * kv[i] * inv_norm;              // g^tau .* k / ||k||
+        qo[i] = qv[i] * q_scale;
+    }
+    if (active) {
+        *reinterpret_cast<floatx4_t *>(log_alpha + off) = floatx4_t{la[0], la[1], la[2], la[3]};
+        *reinterpret_cast<floatx4_t *>(log_alpha + off + 4) = floatx4_t{la[4], la[5], la[6], la[7]};
+        Vec8<IO>::store(q_out + off, qo);
+        Vec8<IO>::store(k_out + off, ko);
+    }
+}
+
+// value side: beta = sigmoid(z_beta), 8 elements per thread
+template <typename IO>
+__global__ __launch_bounds__(kGateThreads) void ddts_value_gate_kernel(const IO *__restrict__ z_beta, float *__restrict__ beta,
+                                                                       size_t n8)
+{
+    const size_t i = (size_t)blockIdx.x * kGateThreads + threadIdx.x;
+    if (i >= n8) return;
+    float z[8];
+    Vec8<IO>::load(z_beta + i * 8, z);
+    *reinterpret_cast<floatx4_t *>(beta + i * 8) = floatx4_t{sigmoid_f(z[0]), sigmoid_f(z[1]), sigmoid_f(z[2]), sigmoid_f(z[3])};
+    *reinterpret_cast<floatx4_t *>(beta + i * 8 + 4) = floatx4_t{sigmoid_f(z[4]), sigmoid_f(z[5]), sigmoid_f(z[6]), sigmoid_f(z[7])};
+}
+
+template <typename IO>
+hipError_t launch_typed(const GateArgs &a)
+{
+    if (a.rows == 0) return hipSuccess;
+    const int lanes_per_row = a.dk / 8;
+    const long long threads = a.rows * lanes_per_row;
+    hipLaunchKernelGGL(ddts_key_gates_kernel<IO>, dim3((unsigned)((threads + kGateThreads - 1) / kGateThreads)), dim3(kGateThreads),
+                       0, a.stream, (const IO *)a.z_g, (const IO *)a.z_tau, (const IO *)a.q, (const IO *)a.k, a.log_alpha,
+                       (IO *)a.q_out, (IO *)a.k_out, a.rows, a.dk, lanes_per_row);
+    if (a.z_beta != nullptr) {
+        const size_t n8 = (size_t)a.rows * a.dv / 8;
+        hipLaunchKernelGGL(ddts_value_gate_kernel<IO>, dim3((unsigned)((n8 + kGateThreads - 1) / kGateThreads)), dim3(kGateThreads), 0,
+                           a.stream, (const IO *)a.z_beta, a.beta, n8);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_ddts_gates(const GateArgs &a)
+{
+    return a.io_dtype == RODIMUS_BF16 ? launch_typed<bf16_t>(a) : launch_typed<float>(a);
+}
+
+}  // namespace rodimus

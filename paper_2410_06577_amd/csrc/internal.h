@@ -86,7 +86,17 @@ struct DecodeArgs {
     hipStream_t stream;
 };
 
+struct GateArgs {
+    const void *z_g, *z_tau, *z_beta, *q, *k;
+    float *log_alpha, *beta;
+    void *q_out, *k_out;
+    long long rows;
+    int dk, dv, io_dtype;
+    hipStream_t stream;
+};
+
 hipError_t launch_decode_step(const DecodeArgs &a);
+hipError_t launch_ddts_gates(const GateArgs &a);
 hipError_t launch_scan_generic(const ScanArgs &a);
 size_t scan_generic_lds_bytes(int dk, int chunk);
 hipError_t launch_scan_mfma(const ScanArgs &a);

@@ -128,4 +128,40 @@ int rodimus_decode_step(const void *q, const void *k, const void *v, const float
     return err == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
 }
 
+int rodimus_ddts_gates(const void *z_g, const void *z_tau, const void *z_beta, const void *q, const void *k,
+                       float *log_alpha, float *beta, void *q_out, void *k_out, long long rows, int dk, int dv,
+                       int io_dtype, void *stream)
+{
+    if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
+    if (rows < 0 || dk < 8 || dk > 512 || (dk & (dk - 1)) != 0) return RODIMUS_ERR_SHAPE;
+    if ((z_beta == nullptr) != (beta == nullptr)) return RODIMUS_ERR_NULL;
+    if (z_beta != nullptr && (dv < 8 || (dv & 7) != 0)) return RODIMUS_ERR_SHAPE;
+    if (rows * (dk / 8) / 256 >= kMaxGridX || (z_beta && (unsigned long long)rows * dv / 8 / 256 >= (unsigned long long)kMaxGridX))
+        return RODIMUS_ERR_SHAPE;
+    if (rows > 0 && (!z_g || !z_tau || !q || !k || !log_alpha || !q_out || !k_out)) return RODIMUS_ERR_NULL;
+    if (misaligned(z_g) || misaligned(z_tau) || misaligned(z_beta) || misaligned(q) || misaligned(k) ||
+        misaligned(log_alpha) || misaligned(beta) || misaligned(q_out) || misaligned(k_out))
+        return RODIMUS_ERR_ALIGN;
+
+    const size_t eb = elem_bytes(io_dtype);
+    const size_t key_bytes = (size_t)rows * dk * eb, la_bytes = (size_t)rows * dk * 4;
+    const size_t zb_bytes = (size_t)rows * (z_beta ? dv : 0) * eb, beta_bytes = (size_t)rows * (z_beta ? dv : 0) * 4;
+    // q_out may be q and k_out may be k (same buffer); every other overlap between an output and anything else is refused
+    const void *ins[5] = {z_g, z_tau, z_beta, q, k};
+    const size_t in_bytes[5] = {key_bytes, key_bytes, zb_bytes, key_bytes, key_bytes};
+    const void *outs[4] = {log_alpha, beta, q_out, k_out};
+    const size_t out_bytes[4] = {la_bytes, beta_bytes, key_bytes, key_bytes};
+    for (int o = 0; o < 4; ++o) {
+        for (int i = 0; i < 5; ++i) {
+            if ((o == 2 && i == 3 && q_out == q) || (o == 3 && i == 4 && k_out == k)) continue;
+            if (overlaps(outs[o], out_bytes[o], ins[i], in_bytes[i])) return RODIMUS_ERR_ALIAS;
+        }
+        for (int p = o + 1; p < 4; ++p)
+            if (overlaps(outs[o], out_bytes[o], outs[p], out_bytes[p])) return RODIMUS_ERR_ALIAS;
+    }
+
+    GateArgs a{z_g, z_tau, z_beta, q, k, log_alpha, beta, q_out, k_out, rows, dk, dv, io_dtype, static_cast<hipStream_t>(stream)};
+    return launch_ddts_gates(a) == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
+}
+
 }  // extern "C"

@@ -47,6 +47,8 @@ def lib() -> ctypes.CDLL:
         L.rodimus_chunk_scan_path.restype = i
         L.rodimus_decode_step.argtypes = [vp] * 7 + [i] * 5 + [vp]
         L.rodimus_decode_step.restype = i
+        L.rodimus_ddts_gates.argtypes = [vp] * 9 + [ctypes.c_longlong, i, i, i, vp]
+        L.rodimus_ddts_gates.restype = i
         _lib = L
     return _lib
 
@@ -151,3 +153,41 @@ def rodimus_decode_step(q, k, v, log_alpha, beta, S, *, o=None):
         _check(lib().rodimus_decode_step(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(S), _ptr(o),
                                          N, H, dk, dv, _DTYPES[io], _stream(dev)))
     return o
+
+
+def rodimus_ddts_gates(z_g, z_tau, z_beta, q, k, *, log_alpha=None, beta=None, q_out=None, k_out=None):
+    """DDTS gate front-end.  z_g, z_tau, q, k [..., dk]; z_beta [..., dv] or None (same leading shape).
+
+    Returns (log_alpha fp32, beta fp32 or None, q_out, k_out); q_out / k_out may be passed as q / k for in-place use.
+    """
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_ddts_gates needs device tensors (no CPU path exists)")
+    dev, io = q.device, q.dtype
+    lead, dk = tuple(q.shape[:-1]), q.shape[-1]
+    rows = 1
+    for d in lead:
+        rows *= d
+    for name, t in (("z_g", z_g), ("z_tau", z_tau), ("q", q), ("k", k)):
+        _require(t, name, lead + (dk,), io, dev)
+    dv = 0
+    if z_beta is not None:
+        dv = z_beta.shape[-1]
+        _require(z_beta, "z_beta", lead + (dv,), io, dev)
+        if beta is None:
+            beta = torch.empty(lead + (dv,), dtype=torch.float32, device=dev)
+        _require(beta, "beta", lead + (dv,), torch.float32, dev)
+    if log_alpha is None:
+        log_alpha = torch.empty(lead + (dk,), dtype=torch.float32, device=dev)
+    if q_out is None:
+        q_out = torch.empty_like(q)
+    if k_out is None:
+        k_out = torch.empty_like(k)
+    _require(log_alpha, "log_alpha", lead + (dk,), torch.float32, dev)
+    _require(q_out, "q_out", lead + (dk,), io, dev)
+    _require(k_out, "k_out", lead + (dk,), io, dev)
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_ddts_gates(_ptr(z_g), _ptr(z_tau), _ptr(z_beta), _ptr(q), _ptr(k), _ptr(log_alpha), _ptr(beta),
+                                        _ptr(q_out), _ptr(k_out), rows, dk, dv, _DTYPES[io], _stream(dev)))
+    return log_alpha, beta, q_out, k_out

@@ -138,3 +138,22 @@ def make_decode_inputs(w: DecodeWorkload) -> dict:
     ring = [_draw_token_inputs(rng, (w.N, w.H), w.dk, w.dv, 0.0, (0.5, 1.0), w.io_dtype)
             for _ in range(w.ring)]
     return {"S": torch.from_numpy(S), "ring": ring}
+
+
+def make_ddts_preactivations(lead: tuple, dk: int, dv: int, io_dtype: str = "bf16", seed: int = 7) -> dict:
+    """Inputs of the DDTS gate front-end: pre-activations z_g, z_tau [lead, dk], z_beta [lead, dv] and raw q, k.
+
+    Drawn so that the resulting gates have the distribution of the scan recipe above: z_g ~ N(0, 1),
+    z_tau = logit(U(0.5, 1)) (so that sigmoid(z_tau) ~ U(0.5, 1)), z_beta ~ N(0, 1); q, k ~ N(0, 1), k NOT normalised
+    (the front-end normalises it).
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    f32 = np.float32
+    z_g = rng.standard_normal(lead + (dk,), dtype=f32)
+    u = rng.uniform(0.5, 1.0, size=lead + (dk,))
+    z_tau = np.log(u / (1.0 - u + 1e-12)).astype(f32)
+    z_beta = rng.standard_normal(lead + (dv,), dtype=f32)
+    q = rng.standard_normal(lead + (dk,), dtype=f32)
+    k = rng.standard_normal(lead + (dk,), dtype=f32)
+    return {"z_g": _io(z_g, io_dtype), "z_tau": _io(z_tau, io_dtype), "z_beta": _io(z_beta, io_dtype),
+            "q": _io(q, io_dtype), "k": _io(k, io_dtype)}

@@ -25,7 +25,7 @@ def test_every_declared_symbol_is_exported(L):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(rodimus_[a-z_]+)\s*\(", header))
     assert {"rodimus_chunk_scan_fwd", "rodimus_decode_step", "rodimus_status_string",
-            "rodimus_chunk_scan_workspace_bytes", "rodimus_chunk_scan_path"} <= declared
+            "rodimus_chunk_scan_workspace_bytes", "rodimus_chunk_scan_path", "rodimus_ddts_gates"} <= declared
     for name in declared:
         assert hasattr(L, name), name
 
@@ -75,6 +75,29 @@ def test_decode_rejects_bad_arguments_before_any_launch(L):
         assert _decode(L, **{name: 0x900008}) == E_ALIGN, name
     assert _decode(L, o=0x100000) == E_ALIAS                # o over the state
     assert _decode(L, S=0x30000) == E_ALIAS                 # state over v
+
+
+def _gates(L, *, z_g=0x10000, z_tau=0x20000, z_beta=0x30000, q=0x40000, k=0x50000, la=0x60000, beta=0x70000,
+           q_out=0x80000, k_out=0x90000, rows=4, dk=64, dv=256, io=rodimus.BF16):
+    p = lambda x: None if x is None else ctypes.c_void_p(x)
+    return L.rodimus_ddts_gates(p(z_g), p(z_tau), p(z_beta), p(q), p(k), p(la), p(beta), p(q_out), p(k_out),
+                                rows, dk, dv, io, None)
+
+
+def test_gates_reject_bad_arguments_before_any_launch(L):
+    assert _gates(L, io=5) == E_DTYPE
+    for bad in (dict(rows=-1), dict(dk=4), dict(dk=24), dict(dk=1024), dict(dv=12), dict(dv=0)):
+        assert _gates(L, **bad) == E_SHAPE, bad
+    for name in ("z_g", "z_tau", "q", "k", "la", "q_out", "k_out"):
+        assert _gates(L, **{name: None}) == E_NULL, name
+    assert _gates(L, z_beta=None) == E_NULL and _gates(L, beta=None) == E_NULL      # they come and go together
+    for name in ("z_g", "z_tau", "z_beta", "q", "k", "la", "beta", "q_out", "k_out"):
+        assert _gates(L, **{name: 0xA00008}) == E_ALIGN, name
+    assert _gates(L, q_out=0x50000) == E_ALIAS          # q_out over k
+    assert _gates(L, la=0x10000) == E_ALIAS             # log_alpha over z_g
+    assert _gates(L, k_out=0x80000) == E_ALIAS          # two outputs on top of each other
+    assert _gates(L, rows=0) == OK
+    assert _gates(L, rows=0, z_beta=None, beta=None, dv=0) == OK
 
 
 def test_empty_problems_are_successful_noops(L):
