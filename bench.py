@@ -112,6 +112,33 @@ def bench_decode(w, rodimus, wl, dev, warmup=100):
             "gbs": algo_bytes / (launch_ms * 1e-3) / 1e9, "steps_per_s": w.steps / wall, "finite": finite}
 
 
+def bench_gates(w, rodimus, wl, dev, steps=50, warmup=20):
+    """DDTS gate front-end over the token-heads of the scan workload (pre-activations -> log_alpha, beta, q, k)."""
+    d = wl.make_ddts_preactivations((w.B, w.T, w.H), w.dk, w.dv, "bf16", seed=9)
+    g = {k: v.to(dev) for k, v in d.items()}
+    la = torch.empty((w.B, w.T, w.H, w.dk), dtype=torch.float32, device=dev)
+    beta = torch.empty((w.B, w.T, w.H, w.dv), dtype=torch.float32, device=dev)
+    qo, ko = torch.empty_like(g["q"]), torch.empty_like(g["k"])
+
+    def step():
+        rodimus.rodimus_ddts_gates(g["z_g"], g["z_tau"], g["z_beta"], g["q"], g["k"], log_alpha=la, beta=beta, q_out=qo, k_out=ko)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(steps):
+        step()
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / steps
+    th = w.token_heads
+    algo = th * (4 * 2 * w.dk + 2 * w.dv + 4 * w.dk + 4 * w.dv + 2 * 2 * w.dk)    # 4 bf16 key-side inputs, z_beta; log_alpha, beta, q, k out
+    return {"ms_per_call": ms, "algorithmic_bytes": algo, "GB_per_s": algo / (ms * 1e-3) / 1e9,
+            "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "token_heads_per_s": th / (ms * 1e-3)}
+
+
 def cpu_baseline(w, inp, o_gpu, S_gpu):
     """fp64 oracle on the scan workload, timed on the host cores; also the parity check of the GPU result."""
     import numpy as np
@@ -200,6 +227,7 @@ def main():
                                            "hbm_frac": big["gbs"] / HBM_PEAK_GBS},
         }
     if not args.skip_other_configs:
+        out["ddts_gates"] = bench_gates(w, rodimus, wl, dev)
         del o, S_T
         others = {}
         for ow in (wl.MID, wl.LONG_CONTEXT):

@@ -8,7 +8,8 @@
 //     beta      = sigmoid(z_beta)
 // Elementwise apart from the key norm, hence bound by HBM bandwidth: one thread owns 8 consecutive channels of a
 // row (a row = one token of one head), the dk/8 lanes of a row reduce the squared norm by butterfly shuffles.
-// All arithmetic in fp32 with the accurate library functions.
+// All arithmetic in fp32.  exp, log and reciprocal use the hardware instructions (about 1 ulp); log(1 + e) switches to
+// its series for small e, where 1 + e would round the information away.
 #include "internal.h"
 
 namespace rodimus {
@@ -47,8 +48,16 @@ template <> struct Vec8<bf16_t> {
 
 __device__ __forceinline__ float sigmoid_f(float z)
 {
-    const float e = expf(-fabsf(z));                 // in (0, 1]: no overflow
-    return z >= 0.f ? 1.f / (1.f + e) : e / (1.f + e);
+    const float e = __expf(-fabsf(z));               // in (0, 1]: no overflow
+    const float r = __builtin_amdgcn_rcpf(1.f + e);
+    return z >= 0.f ? r : e * r;
+}
+
+// log(1 + e) for e in [0, 1]
+__device__ __forceinline__ float log1p_unit(float e)
+{
+    const float series = e * (1.f - e * (0.5f - e * (1.f / 3.f - 0.25f * e)));     // |error| < e^5 / 5
+    return e < 0.015625f ? series : __logf(1.f + e);
 }
 
 // key side: log_alpha, q_out, k_out.  lanes_per_row = dk / 8 is a power of two <= 64.
@@ -80,13 +89,13 @@ __global__ __launch_bounds__(kGateThreads) void ddts_key_gates_kernel(
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const float z = zg[i];
-        const float e = expf(-fabsf(z));
-        const float g = fmaxf(z, 0.f) + log1pf(e);                 // softplus
+        const float e = __expf(-fabsf(z));
+        const float g = fmaxf(z, 0.f) + log1p_unit(e);             // softplus
         // log g: for very negative z, g = e^z (1 - e^z / 2 + ...) underflows before its logarithm does
-        const float log_g = z < -15.f ? z - 0.5f * e : logf(g);
+        const float log_g = z < -15.f ? z - 0.5f * e : __logf(g);
         const float tau = sigmoid_f(zt[i]);
         la[i] = -g * tau;
-        ko[i] = expf(tau * log_g) * kv[i] * inv_norm;              // g^tau .* k / ||k||
+        ko[i] = __expf(tau * log_g) * kv[i] * inv_norm;            // g^tau .* k / ||k||
         qo[i] = qv[i] * q_scale;
     }
     if (active) {
