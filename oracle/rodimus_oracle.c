@@ -28,6 +28,11 @@
  *     S0, S_T         : [B, H, dk, dv]
  * The decode step uses the same layouts with T dropped ([N, H, ...]).
  *
+ * The value gate may instead arrive as its pre-activation z_beta (flag
+ * `beta_is_preactivation`): then beta_t = sigmoid(z_beta_t) (Sec. 3.1.2, the
+ * input gate on the value side) is evaluated here in double, so that the
+ * oracle again starts from the very bits the GPU receives.
+ *
  * There is no blocking, fusion or reordering: the loops below are the
  * recurrence as written.  OpenMP only distributes the independent (b, h)
  * recurrences over host threads.
@@ -48,14 +53,20 @@ int rodimus_oracle_threads(void)
 #endif
 }
 
+static double sigmoid_d(double z) { return z >= 0.0 ? 1.0 / (1.0 + exp(-z)) : exp(z) / (1.0 + exp(z)); }
+
 /* One time step of one (b, h) recurrence, in place on S (dk x dv, row-major). */
 static void ddts_update(double *S, const float *q, const float *k, const float *v,
-                        const float *log_alpha, const float *beta, double *o,
-                        int dk, int dv, double *gated_v)
+                        const float *log_alpha, const float *beta, int beta_is_preactivation,
+                        double *o, int dk, int dv, double *gated_v)
 {
-    /* gated value: beta_t .* v_t   (beta == NULL means the all-ones gate) */
-    for (int j = 0; j < dv; ++j)
-        gated_v[j] = (beta ? (double)beta[j] : 1.0) * (double)v[j];
+    /* gated value: beta_t .* v_t   (beta == NULL means the all-ones gate;
+       with the flag set the array holds z_beta and beta_t = sigmoid(z_beta_t)) */
+    for (int j = 0; j < dv; ++j) {
+        double gate = 1.0;
+        if (beta) gate = beta_is_preactivation ? sigmoid_d((double)beta[j]) : (double)beta[j];
+        gated_v[j] = gate * (double)v[j];
+    }
 
     /* S_t = diag(alpha_t) S_{t-1} + k_t^T (beta_t .* v_t) */
     for (int r = 0; r < dk; ++r) {
@@ -78,12 +89,13 @@ static void ddts_update(double *S, const float *q, const float *k, const float *
 /*
  * Sequential scan over T tokens.
  *   beta may be NULL (all ones); S0 may be NULL (zero state); S_T may be NULL.
+ *   beta_is_preactivation != 0: `beta` holds z_beta and the gate is sigmoid(z_beta).
  * Returns 0 on success, 1 on bad arguments, 2 on allocation failure.
  */
 int rodimus_oracle_scan(const float *q, const float *k, const float *v,
                         const float *log_alpha, const float *beta,
                         const double *S0, double *o, double *S_T,
-                        int B, int T, int H, int dk, int dv)
+                        int B, int T, int H, int dk, int dv, int beta_is_preactivation)
 {
     if (!q || !k || !v || !log_alpha || !o) return 1;
     if (B < 0 || T < 0 || H < 0 || dk <= 0 || dv <= 0) return 1;
@@ -107,7 +119,7 @@ int rodimus_oracle_scan(const float *q, const float *k, const float *v,
             for (int t = 0; t < T; ++t) {
                 const size_t row = ((size_t)b * T + t) * H + h;
                 ddts_update(S, q + row * dk, k + row * dk, v + row * dv,
-                            log_alpha + row * dk, beta ? beta + row * dv : NULL,
+                            log_alpha + row * dk, beta ? beta + row * dv : NULL, beta_is_preactivation,
                             o + row * dv, dk, dv, gv);
             }
             if (S_T)
@@ -125,7 +137,7 @@ int rodimus_oracle_scan(const float *q, const float *k, const float *v,
  */
 int rodimus_oracle_step(const float *q, const float *k, const float *v,
                         const float *log_alpha, const float *beta,
-                        double *S, double *o, int N, int H, int dk, int dv)
+                        double *S, double *o, int N, int H, int dk, int dv, int beta_is_preactivation)
 {
     if (!q || !k || !v || !log_alpha || !S || !o) return 1;
     if (N < 0 || H < 0 || dk <= 0 || dv <= 0) return 1;
@@ -141,7 +153,7 @@ int rodimus_oracle_step(const float *q, const float *k, const float *v,
         }
         ddts_update(S + (size_t)s * dk * dv, q + (size_t)s * dk, k + (size_t)s * dk,
                     v + (size_t)s * dv, log_alpha + (size_t)s * dk,
-                    beta ? beta + (size_t)s * dv : NULL, o + (size_t)s * dv, dk, dv, gv);
+                    beta ? beta + (size_t)s * dv : NULL, beta_is_preactivation, o + (size_t)s * dv, dk, dv, gv);
         free(gv);
     }
     return failed ? 2 : 0;
@@ -165,7 +177,6 @@ int rodimus_oracle_step(const float *q, const float *k, const float *v,
  * z_beta / beta may be NULL together.  Everything in double; no reordering.
  */
 static double softplus_d(double z) { return z > 0.0 ? z + log1p(exp(-z)) : log1p(exp(z)); }
-static double sigmoid_d(double z) { return z >= 0.0 ? 1.0 / (1.0 + exp(-z)) : exp(z) / (1.0 + exp(z)); }
 
 int rodimus_oracle_ddts_gates(const float *z_g, const float *z_tau, const float *z_beta,
                               const float *q, const float *k,

@@ -25,9 +25,9 @@ def _load():
         lib = ctypes.CDLL(path)
         f32p = ctypes.POINTER(ctypes.c_float)
         f64p = ctypes.POINTER(ctypes.c_double)
-        lib.rodimus_oracle_scan.argtypes = [f32p, f32p, f32p, f32p, f32p, f64p, f64p, f64p] + [ctypes.c_int] * 5
+        lib.rodimus_oracle_scan.argtypes = [f32p, f32p, f32p, f32p, f32p, f64p, f64p, f64p] + [ctypes.c_int] * 6
         lib.rodimus_oracle_scan.restype = ctypes.c_int
-        lib.rodimus_oracle_step.argtypes = [f32p, f32p, f32p, f32p, f32p, f64p, f64p] + [ctypes.c_int] * 4
+        lib.rodimus_oracle_step.argtypes = [f32p, f32p, f32p, f32p, f32p, f64p, f64p] + [ctypes.c_int] * 5
         lib.rodimus_oracle_step.restype = ctypes.c_int
         lib.rodimus_oracle_threads.restype = ctypes.c_int
         lib.rodimus_oracle_ddts_gates.argtypes = [f32p] * 5 + [f64p] * 4 + [ctypes.c_long, ctypes.c_int, ctypes.c_int]
@@ -68,13 +68,21 @@ def threads() -> int:
     return int(_load().rodimus_oracle_threads())
 
 
-def scan(q, k, v, log_alpha, beta=None, S0=None, want_state=True):
+def _value_gate(beta, z_beta):
+    if beta is not None and z_beta is not None:
+        raise ValueError("give the value gate either as beta or as its pre-activation z_beta, not both")
+    return (_f32(z_beta), 1) if z_beta is not None else (_f32(beta), 0)
+
+
+def scan(q, k, v, log_alpha, beta=None, S0=None, want_state=True, z_beta=None):
     """Sequential oracle.  q,k,log_alpha [B,T,H,dk]; v,beta [B,T,H,dv]; S0 [B,H,dk,dv].
 
+    ``z_beta`` (instead of ``beta``): the value gate's pre-activation, beta = sigmoid(z_beta) (Sec. 3.1.2).
     Returns (o [B,T,H,dv] float64, S_T [B,H,dk,dv] float64 or None).
     """
     lib = _load()
-    q, k, v, la, beta = _f32(q), _f32(k), _f32(v), _f32(log_alpha), _f32(beta)
+    beta, preact = _value_gate(beta, z_beta)
+    q, k, v, la = _f32(q), _f32(k), _f32(v), _f32(log_alpha)
     S0 = _f64(S0)
     B, T, H, dk = q.shape
     dv = v.shape[-1]
@@ -86,19 +94,20 @@ def scan(q, k, v, log_alpha, beta=None, S0=None, want_state=True):
     S_T = np.empty((B, H, dk, dv), dtype=np.float64) if want_state else None
     rc = lib.rodimus_oracle_scan(_ptr(q, ctypes.c_float), _ptr(k, ctypes.c_float), _ptr(v, ctypes.c_float),
                                  _ptr(la, ctypes.c_float), _ptr(beta, ctypes.c_float), _ptr(S0, ctypes.c_double),
-                                 _ptr(o, ctypes.c_double), _ptr(S_T, ctypes.c_double), B, T, H, dk, dv)
+                                 _ptr(o, ctypes.c_double), _ptr(S_T, ctypes.c_double), B, T, H, dk, dv, preact)
     if rc != 0:
         raise RuntimeError(f"rodimus_oracle_scan failed with code {rc}")
     return o, S_T
 
 
-def step(q, k, v, log_alpha, beta, S):
+def step(q, k, v, log_alpha, beta, S, z_beta=None):
     """One decode step.  q,k,log_alpha [N,H,dk]; v,beta [N,H,dv]; S [N,H,dk,dv] float64.
 
-    Returns (o [N,H,dv] float64, S' float64).  ``S`` itself is not modified.
+    ``z_beta`` as in ``scan``.  Returns (o [N,H,dv] float64, S' float64).  ``S`` itself is not modified.
     """
     lib = _load()
-    q, k, v, la, beta = _f32(q), _f32(k), _f32(v), _f32(log_alpha), _f32(beta)
+    beta, preact = _value_gate(beta, z_beta)
+    q, k, v, la = _f32(q), _f32(k), _f32(v), _f32(log_alpha)
     S = _f64(S).copy()
     N, H, dk = q.shape
     dv = v.shape[-1]
@@ -108,7 +117,7 @@ def step(q, k, v, log_alpha, beta, S):
     o = np.empty((N, H, dv), dtype=np.float64)
     rc = lib.rodimus_oracle_step(_ptr(q, ctypes.c_float), _ptr(k, ctypes.c_float), _ptr(v, ctypes.c_float),
                                  _ptr(la, ctypes.c_float), _ptr(beta, ctypes.c_float),
-                                 _ptr(S, ctypes.c_double), _ptr(o, ctypes.c_double), N, H, dk, dv)
+                                 _ptr(S, ctypes.c_double), _ptr(o, ctypes.c_double), N, H, dk, dv, preact)
     if rc != 0:
         raise RuntimeError(f"rodimus_oracle_step failed with code {rc}")
     return o, S

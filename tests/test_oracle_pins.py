@@ -154,6 +154,39 @@ def test_brute_force_unrolled_sum():
     np.testing.assert_allclose(o, _unrolled_weighted_sum(q, k, v, la, beta, S0), rtol=1e-11, atol=1e-12)
 
 
+def test_value_gate_given_as_pre_activation():
+    """Sec. 3.1.2: the value-side input gate is sigmoid(z_beta).  Given z_beta, the oracle must equal the brute-force
+    sum with that gate, coincide with an explicit gate where the sigmoid is exact in float (z = 0 -> 1/2), tend to
+    the ungated recurrence for large z and to "nothing written" for z = -inf; the decode step follows the scan."""
+    B, T, H, dk, dv = 2, 13, 2, 3, 5
+    q, k, v, la, _, S0 = _rand_case(B, T, H, dk, dv)
+    z = (2.0 * RNG.standard_normal((B, T, H, dv))).astype(np.float32)
+    o, S_T = oracle.scan(q, k, v, la, None, S0, z_beta=z)
+    gate = 1.0 / (1.0 + np.exp(-z.astype(np.float64)))
+    np.testing.assert_allclose(o, _unrolled_weighted_sum(q, k, v, la, gate, S0), rtol=1e-11, atol=1e-12)
+
+    half = np.full((B, T, H, dv), 0.5, np.float32)
+    o_a, S_a = oracle.scan(q, k, v, la, None, S0, z_beta=np.zeros_like(z))
+    o_b, S_b = oracle.scan(q, k, v, la, half, S0)
+    assert np.array_equal(o_a, o_b) and np.array_equal(S_a, S_b)
+
+    o_a, S_a = oracle.scan(q, k, v, la, None, S0, z_beta=np.full_like(z, 60.0))
+    o_b, S_b = oracle.scan(q, k, v, la, None, S0)
+    np.testing.assert_allclose(o_a, o_b, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(S_a, S_b, rtol=1e-13, atol=1e-13)
+
+    o_a, S_a = oracle.scan(q, k, v, la, None, S0, z_beta=np.full_like(z, -np.inf))
+    o_b, S_b = oracle.scan(q, k, np.zeros_like(v), la, None, S0)
+    assert np.array_equal(o_a, o_b) and np.array_equal(S_a, S_b)
+
+    with pytest.raises(ValueError):
+        oracle.scan(q, k, v, la, half, S0, z_beta=z)
+
+    o1, S1 = oracle.scan(q[:, :1], k[:, :1], v[:, :1], la[:, :1], None, S0, z_beta=z[:, :1])
+    od, Sd = oracle.step(q[:, 0], k[:, 0], v[:, 0], la[:, 0], None, S0, z_beta=z[:, 0])
+    assert np.array_equal(od, o1[:, 0]) and np.array_equal(Sd, S1)
+
+
 # --------------------------------------------------------------------------- invariances
 def test_initial_state_only_and_linearity():
     B, T, H, dk, dv = 1, 11, 2, 4, 3
