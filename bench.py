@@ -34,7 +34,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
 MEASURED_TRAFFIC_BYTES = {"scan_layer_1p6b": 1359.3e6, "decode_256x16": 547.4e6}   # profiles/*.md
 
 
-def bench_scan(w, steps, warmup, rodimus, wl, dev):
+def bench_scan(w, steps, warmup, rodimus, wl, dev, zbeta=False):
     inp = wl.make_scan_inputs(w)
     g = {k: (None if v is None else v.to(dev)) for k, v in inp.items()}
     o = torch.empty((w.B, w.T, w.H, w.dv), dtype=torch.bfloat16, device=dev)
@@ -43,8 +43,12 @@ def bench_scan(w, steps, warmup, rodimus, wl, dev):
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
 
     def step():
-        rodimus.rodimus_chunk_scan_fwd(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], g["S0"],
-                                       chunk=w.chunk, o=o, S_T=S_T, workspace=ws)
+        if zbeta:      # value gate as bf16 pre-activation, sigmoid inside the kernel
+            rodimus.rodimus_chunk_scan_fwd_zbeta(g["q"], g["k"], g["v"], g["log_alpha"], g["z_beta"], g["S0"],
+                                                 chunk=w.chunk, o=o, S_T=S_T, workspace=ws)
+        else:
+            rodimus.rodimus_chunk_scan_fwd(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], g["S0"],
+                                           chunk=w.chunk, o=o, S_T=S_T, workspace=ws)
 
     for _ in range(warmup):
         step()
@@ -61,7 +65,7 @@ def bench_scan(w, steps, warmup, rodimus, wl, dev):
 
     th = w.token_heads
     state_bytes = w.B * w.H * w.dk * w.dv * 4
-    algo_bytes = th * (8 * w.dk + 8 * w.dv) + state_bytes * ((1 if g["S0"] is not None else 0) + 1)
+    algo_bytes = th * (8 * w.dk + (6 if zbeta else 8) * w.dv) + state_bytes * ((1 if g["S0"] is not None else 0) + 1)
     flops_causal = th * 2 * (2 * w.dk * w.dv + w.chunk * (w.dk + w.dv) // 2)
     flops_dense = th * 2 * (2 * w.dk * w.dv + w.chunk * (w.dk + w.dv))
     res = {
@@ -133,10 +137,20 @@ def bench_gates(w, rodimus, wl, dev, steps=50, warmup=20):
     b.record()
     torch.cuda.synchronize()
     ms = a.elapsed_time(b) / steps
+    # key side alone (what remains of this pass when the scan takes the value gate as a pre-activation)
+    a.record()
+    for _ in range(steps):
+        rodimus.rodimus_ddts_gates(g["z_g"], g["z_tau"], None, g["q"], g["k"], log_alpha=la, q_out=qo, k_out=ko)
+    b.record()
+    torch.cuda.synchronize()
+    ms_key = a.elapsed_time(b) / steps
     th = w.token_heads
     algo = th * (4 * 2 * w.dk + 2 * w.dv + 4 * w.dk + 4 * w.dv + 2 * 2 * w.dk)    # 4 bf16 key-side inputs, z_beta; log_alpha, beta, q, k out
+    algo_key = th * (4 * 2 * w.dk + 4 * w.dk + 2 * 2 * w.dk)
     return {"ms_per_call": ms, "algorithmic_bytes": algo, "GB_per_s": algo / (ms * 1e-3) / 1e9,
-            "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "token_heads_per_s": th / (ms * 1e-3)}
+            "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "token_heads_per_s": th / (ms * 1e-3),
+            "key_side_only": {"ms_per_call": ms_key, "algorithmic_bytes": algo_key,
+                              "GB_per_s": algo_key / (ms_key * 1e-3) / 1e9}}
 
 
 def cpu_baseline(w, inp, o_gpu, S_gpu):
@@ -229,6 +243,11 @@ def main():
     if not args.skip_other_configs:
         out["ddts_gates"] = bench_gates(w, rodimus, wl, dev)
         del o, S_T
+        zb, _, _, _ = bench_scan(w, args.steps, args.warmup, rodimus, wl, dev, zbeta=True)
+        out["scan_fused_value_gate"] = {
+            "entry_point": "rodimus_chunk_scan_fwd_zbeta", "workload": "layer_1p6b, value gate as bf16 pre-activation",
+            "tokens_per_s": zb["tokens_per_s"], "ms_per_step": zb["launch_ms"], "algorithmic_bytes": zb["algo_bytes"],
+            "GB_per_s": zb["gbs"], "hbm_frac": zb["gbs"] / HBM_PEAK_GBS}
         others = {}
         for ow in (wl.MID, wl.LONG_CONTEXT):
             r, _, _, _ = bench_scan(ow, args.steps, args.warmup, rodimus, wl, dev)

@@ -146,6 +146,29 @@ int rodimus_ddts_gates(const void *z_g, const void *z_tau, const void *z_beta,
                        float *log_alpha, float *beta, void *q_out, void *k_out,
                        long long rows, int dk, int dv, int io_dtype, void *stream);
 
+/*
+ * The two recurrence calls with the value gate fused in (paper Sec. 3.1.2: the input gate on the value side is
+ * beta-hat = sigmoid of a projection of the token): identical to rodimus_chunk_scan_fwd / rodimus_decode_step in
+ * every respect except that the gate arrives as its pre-activation
+ *
+ *   z_beta      [B,T,H,dv] (scan) / [N,H,dv] (decode step), io_dtype, in, required (NULL only for an empty call)
+ *
+ * and beta = sigmoid(z_beta) is evaluated inside the kernel in fp32.  With bf16 I/O this halves the bytes of the
+ * largest input stream of the scan (1024 -> 512 per token-head at dv = 256) and makes the value half of
+ * rodimus_ddts_gates unnecessary (call that with z_beta = NULL for the key side).  Same shapes, workspace, aliasing
+ * rules, status codes and kernel families as the calls they mirror; -inf / +inf give the gate 0 / 1 exactly.
+ */
+int rodimus_chunk_scan_fwd_zbeta(const void *q, const void *k, const void *v,
+                                 const float *log_alpha, const void *z_beta, const float *S0,
+                                 void *o, float *S_T,
+                                 int B, int T, int H, int dk, int dv, int chunk, int io_dtype,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+int rodimus_decode_step_zbeta(const void *q, const void *k, const void *v,
+                              const float *log_alpha, const void *z_beta,
+                              float *S, void *o,
+                              int N, int H, int dk, int dv, int io_dtype, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -46,13 +46,6 @@ template <> struct Vec8<bf16_t> {
     }
 };
 
-__device__ __forceinline__ float sigmoid_f(float z)
-{
-    const float e = __expf(-fabsf(z));               // in (0, 1]: no overflow
-    const float r = __builtin_amdgcn_rcpf(1.f + e);
-    return z >= 0.f ? r : e * r;
-}
-
 // log(1 + e) for e in [0, 1]
 __device__ __forceinline__ float log1p_unit(float e)
 {

@@ -31,7 +31,7 @@ constexpr size_t kLastLevelCacheBytes = 256u << 20;
 template <typename IO, bool kStream>
 __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(
     const IO *__restrict__ q, const IO *__restrict__ k, const IO *__restrict__ v,
-    const float *__restrict__ log_alpha, const float *__restrict__ beta,
+    const float *__restrict__ log_alpha, const void *__restrict__ beta, bool beta_preact,
     float *__restrict__ S, IO *__restrict__ o, int dk, int dv)
 {
     constexpr int kRowBatch = kStream ? 4 : 8;      // rows in flight per wavefront
@@ -56,7 +56,12 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(
     floatx4_t gv = {0.f, 0.f, 0.f, 0.f};                 // beta .* v for this lane's columns
     if (active) {
         gv = load4_as_float(v + state * dv + col);
-        if (beta) gv *= *reinterpret_cast<const floatx4_t *>(beta + state * dv + col);
+        if (beta != nullptr && !beta_preact) {
+            gv *= *(static_cast<const floatx4_t *>(beta) + (state * dv + col) / 4);
+        } else if (beta != nullptr) {                    // the gate arrives as its pre-activation
+            const floatx4_t z = load4_as_float(static_cast<const IO *>(beta) + state * dv + col);
+            gv *= floatx4_t{sigmoid_f(z[0]), sigmoid_f(z[1]), sigmoid_f(z[2]), sigmoid_f(z[3])};
+        }
     }
     __syncthreads();
 
@@ -117,7 +122,7 @@ hipError_t launch_decode_step(const DecodeArgs &a)
     const bool stream = (size_t)states * a.dk * a.dv * sizeof(float) > kLastLevelCacheBytes;
 #define RODIMUS_LAUNCH_DECODE(IO, STREAM)                                                                         \
     hipLaunchKernelGGL((decode_step_kernel<IO, STREAM>), grid, block, 0, a.stream, (const IO *)a.q, (const IO *)a.k, \
-                       (const IO *)a.v, a.log_alpha, a.beta, a.S, (IO *)a.o, a.dk, a.dv)
+                       (const IO *)a.v, a.log_alpha, a.beta, a.beta_preact, a.S, (IO *)a.o, a.dk, a.dv)
     if (a.io_dtype == RODIMUS_BF16) {
         if (stream) RODIMUS_LAUNCH_DECODE(bf16_t, true); else RODIMUS_LAUNCH_DECODE(bf16_t, false);
     } else {

@@ -29,6 +29,14 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
     return *reinterpret_cast<uint32_t *>(&h);
 }
 
+// 1 / (1 + exp(-z)) with the hardware exponential and reciprocal; exact limits 0 and 1 at -inf / +inf.
+__device__ __forceinline__ float sigmoid_f(float z)
+{
+    const float e = __expf(-fabsf(z));               // in (0, 1]: no overflow
+    const float r = __builtin_amdgcn_rcpf(1.f + e);
+    return z >= 0.f ? r : e * r;
+}
+
 // Element loads/stores templated on the I/O element type (float or bf16_t).
 template <typename T> __device__ __forceinline__ float load_as_float(const T *p);
 template <> __device__ __forceinline__ float load_as_float<float>(const float *p) { return *p; }
@@ -64,9 +72,13 @@ template <> __device__ __forceinline__ void store4_from_float<bf16_t>(bf16_t *p,
 }
 
 // ---- launchers (host).  Arguments are already validated by the C-ABI layer. -------------------------
+// `beta` is the value gate: fp32 values, or (beta_preact) its pre-activation in the I/O dtype, or NULL (all ones).
 struct ScanArgs {
     const void *q, *k, *v;
-    const float *log_alpha, *beta, *S0;
+    const float *log_alpha;
+    const void *beta;
+    bool beta_preact;
+    const float *S0;
     void *o;
     float *S_T;
     int B, T, H, dk, dv, chunk;
@@ -78,7 +90,9 @@ struct ScanArgs {
 
 struct DecodeArgs {
     const void *q, *k, *v;
-    const float *log_alpha, *beta;
+    const float *log_alpha;
+    const void *beta;
+    bool beta_preact;
     float *S;
     void *o;
     int N, H, dk, dv;

@@ -34,6 +34,73 @@ int scan_shape_status(int B, int T, int H, int dk, int dv, int chunk, int io_dty
     return RODIMUS_OK;
 }
 
+// The value gate `beta` is either fp32 gate values or (beta_preact) pre-activations in the I/O dtype.
+int scan_entry(const void *q, const void *k, const void *v, const float *log_alpha, const void *beta, bool beta_preact,
+               const float *S0, void *o, float *S_T, int B, int T, int H, int dk, int dv, int chunk, int io_dtype,
+               void *workspace, size_t workspace_bytes, void *stream)
+{
+    const int shape = scan_shape_status(B, T, H, dk, dv, chunk, io_dtype);
+    if (shape != RODIMUS_OK) return shape;
+    const size_t tokens = (size_t)B * T * H;
+    if (tokens > 0 && (!q || !k || !v || !log_alpha || !o)) return RODIMUS_ERR_NULL;   // empty tensors may be NULL
+    if (tokens > 0 && beta_preact && !beta) return RODIMUS_ERR_NULL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(log_alpha) || misaligned(beta) ||
+        misaligned(S0) || misaligned(o) || misaligned(S_T) || misaligned(workspace))
+        return RODIMUS_ERR_ALIGN;
+
+    const size_t eb = elem_bytes(io_dtype);
+    const size_t qk_bytes = tokens * dk * eb, v_bytes = tokens * dv * eb;
+    const size_t la_bytes = tokens * dk * 4, beta_bytes = tokens * dv * (beta_preact ? eb : 4);
+    const size_t state_bytes = (size_t)B * H * dk * dv * 4;
+    if (overlaps(o, v_bytes, q, qk_bytes) || overlaps(o, v_bytes, k, qk_bytes) || overlaps(o, v_bytes, v, v_bytes) ||
+        overlaps(o, v_bytes, log_alpha, la_bytes) || overlaps(o, v_bytes, beta, beta_bytes) ||
+        overlaps(o, v_bytes, S0, state_bytes) || overlaps(o, v_bytes, S_T, state_bytes))
+        return RODIMUS_ERR_ALIAS;
+    if (S_T != nullptr && S_T != S0 && overlaps(S_T, state_bytes, S0, state_bytes)) return RODIMUS_ERR_ALIAS;
+    if (overlaps(S_T, state_bytes, q, qk_bytes) || overlaps(S_T, state_bytes, k, qk_bytes) ||
+        overlaps(S_T, state_bytes, v, v_bytes) || overlaps(S_T, state_bytes, log_alpha, la_bytes) ||
+        overlaps(S_T, state_bytes, beta, beta_bytes))
+        return RODIMUS_ERR_ALIAS;
+
+    const size_t need = scan_mfma_supports(dk, dv, chunk, io_dtype) ? scan_mfma_workspace_bytes(B, T, H, dv) : 0;
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return RODIMUS_ERR_WORKSPACE;
+
+    ScanArgs a{q, k, v, log_alpha, beta, beta_preact, S0, o, S_T, B, T, H, dk, dv, chunk, io_dtype,
+               workspace, workspace_bytes, static_cast<hipStream_t>(stream)};
+    const hipError_t err = scan_mfma_supports(dk, dv, chunk, io_dtype) ? launch_scan_mfma(a) : launch_scan_generic(a);
+    return err == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
+}
+
+int decode_entry(const void *q, const void *k, const void *v, const float *log_alpha, const void *beta, bool beta_preact,
+                 float *S, void *o, int N, int H, int dk, int dv, int io_dtype, void *stream)
+{
+    if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
+    if (N < 0 || H < 0 || dk < 1 || dk > kMaxDecodeDk || dv < 4 || (dv & 3) != 0) return RODIMUS_ERR_SHAPE;
+    if ((long long)N * H > kMaxGridX || (dv + 255) / 256 > 65535) return RODIMUS_ERR_SHAPE;
+    const size_t states = (size_t)N * H;
+    if (states > 0 && (!q || !k || !v || !log_alpha || !S || !o)) return RODIMUS_ERR_NULL;
+    if (states > 0 && beta_preact && !beta) return RODIMUS_ERR_NULL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(log_alpha) || misaligned(beta) ||
+        misaligned(S) || misaligned(o))
+        return RODIMUS_ERR_ALIGN;
+
+    const size_t eb = elem_bytes(io_dtype);
+    const size_t o_bytes = states * dv * eb, s_bytes = states * dk * dv * 4;
+    const size_t beta_bytes = states * dv * (beta_preact ? eb : 4);
+    if (overlaps(o, o_bytes, q, states * dk * eb) || overlaps(o, o_bytes, k, states * dk * eb) ||
+        overlaps(o, o_bytes, v, o_bytes) || overlaps(o, o_bytes, log_alpha, states * dk * 4) ||
+        overlaps(o, o_bytes, beta, beta_bytes) || overlaps(o, o_bytes, S, s_bytes))
+        return RODIMUS_ERR_ALIAS;
+    if (overlaps(S, s_bytes, q, states * dk * eb) || overlaps(S, s_bytes, k, states * dk * eb) ||
+        overlaps(S, s_bytes, v, o_bytes) || overlaps(S, s_bytes, log_alpha, states * dk * 4) ||
+        overlaps(S, s_bytes, beta, beta_bytes))
+        return RODIMUS_ERR_ALIAS;
+
+    DecodeArgs a{q, k, v, log_alpha, beta, beta_preact, S, o, N, H, dk, dv, io_dtype, static_cast<hipStream_t>(stream)};
+    const hipError_t err = launch_decode_step(a);
+    return err == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
+}
+
 }  // namespace
 
 extern "C" {
@@ -69,63 +136,28 @@ int rodimus_chunk_scan_fwd(const void *q, const void *k, const void *v, const fl
                            const float *S0, void *o, float *S_T, int B, int T, int H, int dk, int dv, int chunk,
                            int io_dtype, void *workspace, size_t workspace_bytes, void *stream)
 {
-    const int shape = scan_shape_status(B, T, H, dk, dv, chunk, io_dtype);
-    if (shape != RODIMUS_OK) return shape;
-    const size_t tokens = (size_t)B * T * H;
-    if (tokens > 0 && (!q || !k || !v || !log_alpha || !o)) return RODIMUS_ERR_NULL;   // empty tensors may be NULL
-    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(log_alpha) || misaligned(beta) ||
-        misaligned(S0) || misaligned(o) || misaligned(S_T) || misaligned(workspace))
-        return RODIMUS_ERR_ALIGN;
+    return scan_entry(q, k, v, log_alpha, beta, false, S0, o, S_T, B, T, H, dk, dv, chunk, io_dtype, workspace,
+                      workspace_bytes, stream);
+}
 
-    const size_t eb = elem_bytes(io_dtype);
-    const size_t qk_bytes = tokens * dk * eb, v_bytes = tokens * dv * eb;
-    const size_t la_bytes = tokens * dk * 4, beta_bytes = tokens * dv * 4;
-    const size_t state_bytes = (size_t)B * H * dk * dv * 4;
-    if (overlaps(o, v_bytes, q, qk_bytes) || overlaps(o, v_bytes, k, qk_bytes) || overlaps(o, v_bytes, v, v_bytes) ||
-        overlaps(o, v_bytes, log_alpha, la_bytes) || overlaps(o, v_bytes, beta, beta_bytes) ||
-        overlaps(o, v_bytes, S0, state_bytes) || overlaps(o, v_bytes, S_T, state_bytes))
-        return RODIMUS_ERR_ALIAS;
-    if (S_T != nullptr && S_T != S0 && overlaps(S_T, state_bytes, S0, state_bytes)) return RODIMUS_ERR_ALIAS;
-    if (overlaps(S_T, state_bytes, q, qk_bytes) || overlaps(S_T, state_bytes, k, qk_bytes) ||
-        overlaps(S_T, state_bytes, v, v_bytes) || overlaps(S_T, state_bytes, log_alpha, la_bytes) ||
-        overlaps(S_T, state_bytes, beta, beta_bytes))
-        return RODIMUS_ERR_ALIAS;
-
-    const size_t need = rodimus_chunk_scan_workspace_bytes(B, T, H, dk, dv, chunk, io_dtype);
-    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return RODIMUS_ERR_WORKSPACE;
-
-    ScanArgs a{q, k, v, log_alpha, beta, S0, o, S_T, B, T, H, dk, dv, chunk, io_dtype,
-               workspace, workspace_bytes, static_cast<hipStream_t>(stream)};
-    const hipError_t err = scan_mfma_supports(dk, dv, chunk, io_dtype) ? launch_scan_mfma(a) : launch_scan_generic(a);
-    return err == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
+int rodimus_chunk_scan_fwd_zbeta(const void *q, const void *k, const void *v, const float *log_alpha, const void *z_beta,
+                                 const float *S0, void *o, float *S_T, int B, int T, int H, int dk, int dv, int chunk,
+                                 int io_dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return scan_entry(q, k, v, log_alpha, z_beta, true, S0, o, S_T, B, T, H, dk, dv, chunk, io_dtype, workspace,
+                      workspace_bytes, stream);
 }
 
 int rodimus_decode_step(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta,
                         float *S, void *o, int N, int H, int dk, int dv, int io_dtype, void *stream)
 {
-    if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
-    if (N < 0 || H < 0 || dk < 1 || dk > kMaxDecodeDk || dv < 4 || (dv & 3) != 0) return RODIMUS_ERR_SHAPE;
-    if ((long long)N * H > kMaxGridX || (dv + 255) / 256 > 65535) return RODIMUS_ERR_SHAPE;
-    const size_t states = (size_t)N * H;
-    if (states > 0 && (!q || !k || !v || !log_alpha || !S || !o)) return RODIMUS_ERR_NULL;
-    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(log_alpha) || misaligned(beta) ||
-        misaligned(S) || misaligned(o))
-        return RODIMUS_ERR_ALIGN;
+    return decode_entry(q, k, v, log_alpha, beta, false, S, o, N, H, dk, dv, io_dtype, stream);
+}
 
-    const size_t eb = elem_bytes(io_dtype);
-    const size_t o_bytes = states * dv * eb, s_bytes = states * dk * dv * 4;
-    if (overlaps(o, o_bytes, q, states * dk * eb) || overlaps(o, o_bytes, k, states * dk * eb) ||
-        overlaps(o, o_bytes, v, o_bytes) || overlaps(o, o_bytes, log_alpha, states * dk * 4) ||
-        overlaps(o, o_bytes, beta, states * dv * 4) || overlaps(o, o_bytes, S, s_bytes))
-        return RODIMUS_ERR_ALIAS;
-    if (overlaps(S, s_bytes, q, states * dk * eb) || overlaps(S, s_bytes, k, states * dk * eb) ||
-        overlaps(S, s_bytes, v, o_bytes) || overlaps(S, s_bytes, log_alpha, states * dk * 4) ||
-        overlaps(S, s_bytes, beta, states * dv * 4))
-        return RODIMUS_ERR_ALIAS;
-
-    DecodeArgs a{q, k, v, log_alpha, beta, S, o, N, H, dk, dv, io_dtype, static_cast<hipStream_t>(stream)};
-    const hipError_t err = launch_decode_step(a);
-    return err == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
+int rodimus_decode_step_zbeta(const void *q, const void *k, const void *v, const float *log_alpha, const void *z_beta,
+                              float *S, void *o, int N, int H, int dk, int dv, int io_dtype, void *stream)
+{
+    return decode_entry(q, k, v, log_alpha, z_beta, true, S, o, N, H, dk, dv, io_dtype, stream);
 }
 
 int rodimus_ddts_gates(const void *z_g, const void *z_tau, const void *z_beta, const void *q, const void *k,

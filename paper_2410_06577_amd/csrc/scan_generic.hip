@@ -39,7 +39,7 @@ __host__ __device__ inline int next_pow2(int x)
 template <typename IO>
 __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
     const IO *__restrict__ q, const IO *__restrict__ k, const IO *__restrict__ v,
-    const float *__restrict__ log_alpha, const float *__restrict__ beta, const float *S0,
+    const float *__restrict__ log_alpha, const void *__restrict__ beta, bool beta_preact, const float *S0,
     IO *__restrict__ o, float *S_T, int T, int H, int dk, int dv, int C)
 {
     extern __shared__ float lds[];
@@ -84,7 +84,9 @@ __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
             if (t < n && c < ncol) {
                 const size_t g = (((size_t)b * T + s + t) * H + h) * dv + j0 + c;
                 x = load_as_float(v + g);
-                if (beta) x *= beta[g];
+                if (beta != nullptr)      // the value gate: given, or the sigmoid of its pre-activation
+                    x *= beta_preact ? sigmoid_f(load_as_float(static_cast<const IO *>(beta) + g))
+                                     : static_cast<const float *>(beta)[g];
             }
             gv[e] = x;
         }
@@ -181,7 +183,7 @@ static hipError_t launch_typed(const ScanArgs &a)
     if (err != hipSuccess) return err;
     dim3 grid((unsigned)(a.B * a.H), (unsigned)((a.dv + kColTile - 1) / kColTile)), block(kThreads);
     hipLaunchKernelGGL(scan_generic_kernel<IO>, grid, block, lds, a.stream, (const IO *)a.q, (const IO *)a.k,
-                       (const IO *)a.v, a.log_alpha, a.beta, a.S0, (IO *)a.o, a.S_T, a.T, a.H, a.dk, a.dv, a.chunk);
+                       (const IO *)a.v, a.log_alpha, a.beta, a.beta_preact, a.S0, (IO *)a.o, a.S_T, a.T, a.H, a.dk, a.dv, a.chunk);
     return hipGetLastError();
 }
 

@@ -100,7 +100,8 @@ constexpr int QP(int a, int b, int c, int d) { return a | (b << 2) | (c << 4) | 
 
 struct Geometry {
     const bf16_t *q, *k, *v;
-    const float *la, *beta;
+    const float *la;
+    const void *beta;       // value gate: fp32 values, or bf16 pre-activations (kZBeta), or null
     bf16_t *o;
     int T, H, dv;
     int b, h, j0;
@@ -407,11 +408,15 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
 // State wavefront `w` fetches tile w of every chunk for ALL 128 columns of the workgroup (whole 256-byte rows of v,
 // 512-byte rows of beta: long contiguous pieces are what HBM delivers at full rate) and transposes beta .* v for
 // the four state wavefronts.  Lane = (row 4u + lane/16 for u = 0..3, columns 8(lane%16) .. +7).
+// The value gate arrives as fp32 values (kZBeta = false; `has_beta` false: all ones) or as bf16 pre-activations
+// whose sigmoid is taken here (kZBeta = true; half the bytes, two transcendentals per element).
 struct StateLoads {
     uint4 v[4];
     floatx4_t beta[4][2];
+    uint4 zbeta[4];
 };
 
+template <bool kZBeta>
 __device__ __forceinline__ void state_prefetch(const Geometry &g, int s, int tile, int lane, bool has_beta, StateLoads &p)
 {
     const int rsub = lane >> 4, piece = lane & 15;
@@ -420,9 +425,11 @@ __device__ __forceinline__ void state_prefetch(const Geometry &g, int s, int til
         const int t = min(s + 16 * tile + 4 * u + rsub, g.t_end - 1);   // clamped: padded rows are zeroed in stage_values
         const size_t off = (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 8 * piece;
         p.v[u] = *reinterpret_cast<const uint4 *>(g.v + off);
-        if (has_beta) {
-            p.beta[u][0] = *reinterpret_cast<const floatx4_t *>(g.beta + off);
-            p.beta[u][1] = *reinterpret_cast<const floatx4_t *>(g.beta + off + 4);
+        if (kZBeta) {
+            p.zbeta[u] = *reinterpret_cast<const uint4 *>(static_cast<const bf16_t *>(g.beta) + off);
+        } else if (has_beta) {
+            p.beta[u][0] = *reinterpret_cast<const floatx4_t *>(static_cast<const float *>(g.beta) + off);
+            p.beta[u][1] = *reinterpret_cast<const floatx4_t *>(static_cast<const float *>(g.beta) + off + 4);
         }
     }
 }
@@ -431,6 +438,7 @@ __device__ __forceinline__ void state_prefetch(const Geometry &g, int s, int til
 // workgroup belongs to slab c/32; inside the slab it is column index n = 4(piece%4) + jj%4 of column tile ct = jj/4
 // and lives in LDS row 16ct + 4(n%4) + n/4 (32 bytes = 16 tokens).  The 8-byte token groups of a row are XOR-ed with
 // the slab number; together with the row order this spreads the 2-byte writes over all banks.
+template <bool kZBeta>
 __device__ __forceinline__ void stage_values(unsigned char *vt, int tile, int lane, bool has_beta, const StateLoads &p, int s, int t_end)
 {
     const int rsub = lane >> 4, piece = lane & 15;
@@ -446,7 +454,14 @@ __device__ __forceinline__ void stage_values(unsigned char *vt, int tile, int la
             gv[2 * j] = bf16_lo(w[j]);
             gv[2 * j + 1] = bf16_hi(w[j]);
         }
-        if (has_beta) {
+        if (kZBeta) {
+            const uint32_t z[4] = {p.zbeta[u].x, p.zbeta[u].y, p.zbeta[u].z, p.zbeta[u].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                gv[2 * j] *= sigmoid_f(bf16_lo(z[j]));
+                gv[2 * j + 1] *= sigmoid_f(bf16_hi(z[j]));
+            }
+        } else if (has_beta) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 gv[j] *= p.beta[u][0][j];
@@ -591,10 +606,11 @@ struct SegmentPlan {
 // kSummary = false: the scan proper over this workgroup's segment (blockIdx.z), reading its entering state.
 // kSummary = true : same walk from a zero state without q, scores or outputs; leaves the segment's state
 //                   increment in slot seg+1 and the segment's total decay in gamma[seg].
-template <bool kSummary>
+// kZBeta: `beta` holds bf16 pre-activations of the value gate instead of fp32 gate values.
+template <bool kSummary, bool kZBeta>
 __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
-    const float *__restrict__ log_alpha, const float *__restrict__ beta, const float *S0,
+    const float *__restrict__ log_alpha, const void *__restrict__ beta, const float *S0,
     bf16_t *__restrict__ o, float *S_T, int T, int H, int dv, SegmentPlan plan)
 {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -667,7 +683,7 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
         for (int kt = 0; kt < 4; ++kt) decay[kt] = floatx4_t{1.f, 1.f, 1.f, 1.f};
 
         StateLoads pf;            // tile `slab` of the next chunk to stage, all 128 columns
-        if (nchunks > 0) state_prefetch(g, t_begin, slab, lane, has_beta, pf);
+        if (nchunks > 0) state_prefetch<kZBeta>(g, t_begin, slab, lane, has_beta, pf);
         for (int it = 0; it <= nchunks + 1; ++it) {
             unsigned long long t0 = PROF_T();
             if (it >= 1 && it <= nchunks)      // chunk it-1: its values were staged at the end of the previous iteration
@@ -677,8 +693,8 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
             t0 = PROF_T();
             if (it < nchunks) {
                 // values of chunk `it` (requested one iteration ago) -> LDS, then request the next chunk's
-                stage_values(lds + kOffVt + (it & 1) * kVtBuf, slab, lane, has_beta, pf, t_begin + it * kChunk, g.t_end);
-                state_prefetch(g, t_begin + (it + 1) * kChunk, slab, lane, has_beta, pf);   // unconditional (clamped), see gate_prefetch
+                stage_values<kZBeta>(lds + kOffVt + (it & 1) * kVtBuf, slab, lane, has_beta, pf, t_begin + it * kChunk, g.t_end);
+                state_prefetch<kZBeta>(g, t_begin + (it + 1) * kChunk, slab, lane, has_beta, pf);   // unconditional (clamped), see gate_prefetch
             }
             PROF_ADD(16 + slab * 3, t0);
             t0 = PROF_T();
@@ -762,17 +778,18 @@ size_t scan_mfma_workspace_bytes(int B, int T, int H, int dv)
     return ((size_t)sp.nseg * bh * kK * dv + (size_t)(sp.nseg - 1) * bh * kK) * sizeof(float);
 }
 
-hipError_t launch_scan_mfma(const ScanArgs &a)
+namespace {
+
+template <bool kZBeta>
+hipError_t launch_scan_mfma_typed(const ScanArgs &a)
 {
-    if ((long long)a.B * a.H == 0) return hipSuccess;
-    if (a.T == 0 && (a.S_T == nullptr || a.S_T == a.S0)) return hipSuccess;
     const SplitShape sp = choose_split(a.B, a.T, a.H, a.dv);
     const size_t bh = (size_t)a.B * a.H;
     SegmentPlan plan{sp.nseg, sp.seg_tokens, nullptr, nullptr};
-    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel<false>),
+    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel<false, kZBeta>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (attr == hipSuccess)
-        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel<true>),
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel<true, kZBeta>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (attr != hipSuccess) return attr;
     const dim3 block(kThreads);
@@ -780,17 +797,26 @@ hipError_t launch_scan_mfma(const ScanArgs &a)
     if (sp.nseg > 1) {
         plan.slots = static_cast<float *>(a.workspace);
         plan.gamma = plan.slots + (size_t)sp.nseg * bh * kK * a.dv;
-        hipLaunchKernelGGL(scan_mfma_kernel<true>, dim3((unsigned)bh, col_tiles, (unsigned)(sp.nseg - 1)), block, kLdsBytes,
-                           a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta,
-                           (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, a.T, a.H, a.dv, plan);
+        hipLaunchKernelGGL((scan_mfma_kernel<true, kZBeta>), dim3((unsigned)bh, col_tiles, (unsigned)(sp.nseg - 1)), block,
+                           kLdsBytes, a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha,
+                           a.beta, (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, a.T, a.H, a.dv, plan);
         const size_t quads = bh * kK * a.dv / 4;
         hipLaunchKernelGGL(segment_state_scan_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, a.stream, a.S0,
                            plan, a.dv, quads);
     }
-    hipLaunchKernelGGL(scan_mfma_kernel<false>, dim3((unsigned)bh, col_tiles, (unsigned)sp.nseg), block, kLdsBytes, a.stream,
-                       (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0,
+    hipLaunchKernelGGL((scan_mfma_kernel<false, kZBeta>), dim3((unsigned)bh, col_tiles, (unsigned)sp.nseg), block, kLdsBytes,
+                       a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0,
                        (bf16_t *)a.o, a.S_T, a.T, a.H, a.dv, plan);
     return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_scan_mfma(const ScanArgs &a)
+{
+    if ((long long)a.B * a.H == 0) return hipSuccess;
+    if (a.T == 0 && (a.S_T == nullptr || a.S_T == a.S0)) return hipSuccess;
+    return (a.beta != nullptr && a.beta_preact) ? launch_scan_mfma_typed<true>(a) : launch_scan_mfma_typed<false>(a);
 }
 
 }  // namespace rodimus

@@ -47,6 +47,10 @@ def lib() -> ctypes.CDLL:
         L.rodimus_chunk_scan_path.restype = i
         L.rodimus_decode_step.argtypes = [vp] * 7 + [i] * 5 + [vp]
         L.rodimus_decode_step.restype = i
+        L.rodimus_chunk_scan_fwd_zbeta.argtypes = L.rodimus_chunk_scan_fwd.argtypes
+        L.rodimus_chunk_scan_fwd_zbeta.restype = i
+        L.rodimus_decode_step_zbeta.argtypes = L.rodimus_decode_step.argtypes
+        L.rodimus_decode_step_zbeta.restype = i
         L.rodimus_ddts_gates.argtypes = [vp] * 9 + [ctypes.c_longlong, i, i, i, vp]
         L.rodimus_ddts_gates.restype = i
         _lib = L
@@ -92,7 +96,7 @@ def rodimus_chunk_scan_path(B, T, H, dk, dv, chunk, io_dtype) -> int:
 
 
 def rodimus_chunk_scan_fwd(q, k, v, log_alpha, beta=None, S0=None, *, chunk=64, o=None, S_T=None,
-                           want_state=True, workspace=None):
+                           want_state=True, workspace=None, _preact=False):
     """Chunkwise forward scan.  q,k,log_alpha [B,T,H,dk]; v,beta [B,T,H,dv]; S0 [B,H,dk,dv] fp32.
 
     Returns (o, S_T); S_T is None when ``want_state`` is False.  Output and workspace
@@ -109,7 +113,9 @@ def rodimus_chunk_scan_fwd(q, k, v, log_alpha, beta=None, S0=None, *, chunk=64, 
     _require(k, "k", (B, T, H, dk), io, dev)
     _require(v, "v", (B, T, H, dv), io, dev)
     _require(log_alpha, "log_alpha", (B, T, H, dk), torch.float32, dev)
-    _require(beta, "beta", (B, T, H, dv), torch.float32, dev)
+    if _preact and beta is None:
+        raise ValueError("z_beta is required")
+    _require(beta, "z_beta" if _preact else "beta", (B, T, H, dv), io if _preact else torch.float32, dev)
     _require(S0, "S0", (B, H, dk, dv), torch.float32, dev)
     if o is None:
         o = torch.empty((B, T, H, dv), dtype=io, device=dev)
@@ -122,13 +128,18 @@ def rodimus_chunk_scan_fwd(q, k, v, log_alpha, beta=None, S0=None, *, chunk=64, 
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     with torch.cuda.device(dev):
-        _check(lib().rodimus_chunk_scan_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(S0),
-                                            _ptr(o), _ptr(S_T), B, T, H, dk, dv, int(chunk), _DTYPES[io],
-                                            _ptr(workspace), ws_bytes, _stream(dev)))
+        entry = lib().rodimus_chunk_scan_fwd_zbeta if _preact else lib().rodimus_chunk_scan_fwd
+        _check(entry(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(S0), _ptr(o), _ptr(S_T),
+                     B, T, H, dk, dv, int(chunk), _DTYPES[io], _ptr(workspace), ws_bytes, _stream(dev)))
     return o, S_T
 
 
-def rodimus_decode_step(q, k, v, log_alpha, beta, S, *, o=None):
+def rodimus_chunk_scan_fwd_zbeta(q, k, v, log_alpha, z_beta, S0=None, **kw):
+    """``rodimus_chunk_scan_fwd`` with the value gate given as its pre-activation z_beta [B,T,H,dv] (dtype of v)."""
+    return rodimus_chunk_scan_fwd(q, k, v, log_alpha, z_beta, S0, _preact=True, **kw)
+
+
+def rodimus_decode_step(q, k, v, log_alpha, beta, S, *, o=None, _preact=False):
     """One recurrent step.  q,k,log_alpha [N,H,dk]; v,beta [N,H,dv]; S [N,H,dk,dv] fp32, updated in place.
 
     Returns o [N,H,dv].
@@ -144,15 +155,23 @@ def rodimus_decode_step(q, k, v, log_alpha, beta, S, *, o=None):
     _require(k, "k", (N, H, dk), io, dev)
     _require(v, "v", (N, H, dv), io, dev)
     _require(log_alpha, "log_alpha", (N, H, dk), torch.float32, dev)
-    _require(beta, "beta", (N, H, dv), torch.float32, dev)
+    if _preact and beta is None:
+        raise ValueError("z_beta is required")
+    _require(beta, "z_beta" if _preact else "beta", (N, H, dv), io if _preact else torch.float32, dev)
     _require(S, "S", (N, H, dk, dv), torch.float32, dev)
     if o is None:
         o = torch.empty((N, H, dv), dtype=io, device=dev)
     _require(o, "o", (N, H, dv), io, dev)
     with torch.cuda.device(dev):
-        _check(lib().rodimus_decode_step(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(S), _ptr(o),
-                                         N, H, dk, dv, _DTYPES[io], _stream(dev)))
+        entry = lib().rodimus_decode_step_zbeta if _preact else lib().rodimus_decode_step
+        _check(entry(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(S), _ptr(o),
+                     N, H, dk, dv, _DTYPES[io], _stream(dev)))
     return o
+
+
+def rodimus_decode_step_zbeta(q, k, v, log_alpha, z_beta, S, *, o=None):
+    """``rodimus_decode_step`` with the value gate given as its pre-activation z_beta [N,H,dv] (dtype of v)."""
+    return rodimus_decode_step(q, k, v, log_alpha, z_beta, S, o=o, _preact=True)
 
 
 def rodimus_ddts_gates(z_g, z_tau, z_beta, q, k, *, log_alpha=None, beta=None, q_out=None, k_out=None):

@@ -112,11 +112,12 @@ def _draw_token_inputs(rng, lead, dk, dv, gate_mean, tau_range, io_dtype):
         "q": _io(q, io_dtype), "k": _io(k, io_dtype), "v": _io(v, io_dtype),
         "log_alpha": torch.from_numpy(log_alpha.astype(f32)),
         "beta": torch.from_numpy(beta),
+        "z_beta": _io(z_b, io_dtype),     # the same gate as a pre-activation in the I/O dtype (for the *_zbeta calls)
     }
 
 
 def make_scan_inputs(w: ScanWorkload) -> dict:
-    """CPU tensors q,k,log_alpha [B,T,H,dk]; v,beta [B,T,H,dv]; S0 [B,H,dk,dv] fp32 or None."""
+    """CPU tensors q,k,log_alpha [B,T,H,dk]; v,beta,z_beta [B,T,H,dv]; S0 [B,H,dk,dv] fp32 or None."""
     rng = np.random.Generator(np.random.PCG64(w.seed))
     d = _draw_token_inputs(rng, (w.B, w.T, w.H), w.dk, w.dv, w.gate_mean, w.tau_range, w.io_dtype)
     if w.s0_std > 0:

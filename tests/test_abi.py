@@ -25,7 +25,8 @@ def test_every_declared_symbol_is_exported(L):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(rodimus_[a-z_]+)\s*\(", header))
     assert {"rodimus_chunk_scan_fwd", "rodimus_decode_step", "rodimus_status_string",
-            "rodimus_chunk_scan_workspace_bytes", "rodimus_chunk_scan_path", "rodimus_ddts_gates"} <= declared
+            "rodimus_chunk_scan_workspace_bytes", "rodimus_chunk_scan_path", "rodimus_ddts_gates",
+            "rodimus_chunk_scan_fwd_zbeta", "rodimus_decode_step_zbeta"} <= declared
     for name in declared:
         assert hasattr(L, name), name
 
@@ -98,6 +99,27 @@ def test_gates_reject_bad_arguments_before_any_launch(L):
     assert _gates(L, k_out=0x80000) == E_ALIAS          # two outputs on top of each other
     assert _gates(L, rows=0) == OK
     assert _gates(L, rows=0, z_beta=None, beta=None, dv=0) == OK
+
+
+def test_zbeta_calls_validate_like_the_calls_they_mirror(L):
+    p = ctypes.c_void_p
+
+    def scan(z=0x50000, o=0x70000, T=4, io=rodimus.BF16):
+        S_T = p(0x80000) if T > 0 else None               # T = 0 with a final state wanted would launch a copy
+        return L.rodimus_chunk_scan_fwd_zbeta(p(0x10000), p(0x20000), p(0x30000), p(0x40000), None if z is None else p(z),
+                                              p(0x60000), p(o), S_T, 1, T, 1, 16, 32, 4, io, None, 0, None)
+
+    def dec(z=0x50000, S=0x100000, N=2, io=rodimus.BF16):
+        return L.rodimus_decode_step_zbeta(p(0x10000), p(0x20000), p(0x30000), p(0x40000), None if z is None else p(z),
+                                           p(S), p(0x70000), N, 2, 16, 32, io, None)
+
+    assert scan(z=None) == E_NULL and dec(z=None) == E_NULL            # the pre-activation is required ...
+    assert scan(z=None, T=0) == OK and dec(z=None, N=0) == OK          # ... unless the call is empty
+    assert scan(z=0x50008) == E_ALIGN and dec(z=0x50008) == E_ALIGN
+    assert scan(io=9) == E_DTYPE and dec(io=9) == E_DTYPE
+    # z_beta has the I/O element size: 4*32 bf16 = 256 bytes from 0x50000; an output just behind it is fine, on it is not
+    assert scan(o=0x50080) == E_ALIAS
+    assert dec(S=0x50040) == E_ALIAS
 
 
 def test_empty_problems_are_successful_noops(L):
