@@ -31,7 +31,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (scaled by a plain copy kernel);
 # taken from the summaries under profiles/ (scan_mfma_kernel_layer_1p6b.md, decode_step_kernel_256x16.md).
-MEASURED_TRAFFIC_BYTES = {"scan_layer_1p6b": 1359.3e6, "decode_256x16": 547.4e6}   # profiles/*.md
+MEASURED_TRAFFIC_BYTES = {"scan_layer_1p6b": 1360.1e6, "decode_256x16": 547.6e6}   # profiles/*.md
 
 
 def warm_up(step, launches, min_seconds=0.08):
