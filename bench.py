@@ -171,6 +171,37 @@ def bench_gates(w, rodimus, wl, dev, steps=50, warmup=20):
                               "GB_per_s": algo_key / (ms_key * 1e-3) / 1e9}}
 
 
+def bench_varlen(w, rodimus, wl, dev, steps, warmup, n_seq=64, longest_first=False):
+    """Packed variable-length prefill: n_seq sequences with a log-uniform length mix and the token count of the layer
+    workload (rodimus_chunk_scan_varlen_fwd, states written to a cache)."""
+    lengths = wl.serving_length_mix(n_seq, w.B * w.T)
+    if longest_first:       # workgroups start in sequence order: longest first is the better schedule
+        lengths = sorted(lengths, reverse=True)
+    d = wl.make_varlen_inputs(lengths, w.H, w.dk, w.dv, "bf16", seed=14)
+    g = {k: (None if v is None else v.to(dev)) for k, v in d.items()}
+    o = torch.empty((w.B * w.T, w.H, w.dv), dtype=torch.bfloat16, device=dev)
+    S_T = torch.empty((n_seq, w.H, w.dk, w.dv), dtype=torch.float32, device=dev)
+
+    def step():
+        rodimus.rodimus_chunk_scan_varlen_fwd(g["q"], g["k"], g["v"], g["log_alpha"], g["cu_seqlens"], beta=g["beta"],
+                                              S0=g["S0"], o=o, S_T=S_T)
+
+    warm_up(step, warmup)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(steps):
+        step()
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / steps
+    algo = w.token_heads * (8 * w.dk + 8 * w.dv) + 2 * n_seq * w.H * w.dk * w.dv * 4
+    return {"entry_point": "rodimus_chunk_scan_varlen_fwd",
+            "workload": f"{n_seq} sequences, lengths {min(lengths)}..{max(lengths)} (log-uniform mix), {w.B * w.T} tokens, "
+                        f"H={w.H} dk={w.dk} dv={w.dv}",
+            "ms_per_step": ms, "tokens_per_s": w.B * w.T / (ms * 1e-3), "GB_per_s": algo / (ms * 1e-3) / 1e9,
+            "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+
 def cpu_baseline(w, inp, o_gpu, S_gpu):
     """fp64 oracle on the scan workload, timed on the host cores; also the parity check of the GPU result."""
     import numpy as np
@@ -268,6 +299,10 @@ def main():
             "entry_point": "rodimus_chunk_scan_fwd_zbeta", "workload": "layer_1p6b, value gate as bf16 pre-activation",
             "tokens_per_s": zb["tokens_per_s"], "ms_per_step": zb["launch_ms"], "algorithmic_bytes": zb["algo_bytes"],
             "GB_per_s": zb["gbs"], "hbm_frac": zb["gbs"] / HBM_PEAK_GBS}
+        out["serving_prefill_varlen"] = bench_varlen(w, rodimus, wl, dev, args.steps, args.warmup)
+        lf = bench_varlen(w, rodimus, wl, dev, args.steps, args.warmup, longest_first=True)
+        out["serving_prefill_varlen"]["sequences_sorted_longest_first"] = {
+            k: lf[k] for k in ("ms_per_step", "tokens_per_s", "GB_per_s", "hbm_frac")}
         others = {}
         for ow in (wl.MID, wl.LONG_CONTEXT):
             r, _, _, _ = bench_scan(ow, args.steps, args.warmup, rodimus, wl, dev)

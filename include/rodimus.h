@@ -169,6 +169,43 @@ int rodimus_decode_step_zbeta(const void *q, const void *k, const void *v,
                               float *S, void *o,
                               int N, int H, int dk, int dv, int io_dtype, void *stream);
 
+/* How the value gate is passed to rodimus_chunk_scan_varlen_fwd. */
+typedef enum {
+    RODIMUS_BETA_VALUES = 0,          /* fp32 gate values (or NULL = all ones)              */
+    RODIMUS_BETA_PREACTIVATION = 1    /* pre-activations in io_dtype, beta = sigmoid(.)     */
+} rodimus_beta_kind;
+
+/*
+ * Chunkwise forward scan over a PACKED batch of N sequences of different lengths (serving prefill): the same
+ * recurrence as rodimus_chunk_scan_fwd (paper Sec. 3.1.3 and the appendix on the chunkwise form), run independently on
+ * every sequence; a sequence need not be a multiple of `chunk` long (the appendix assumes it is; a shorter last chunk
+ * behaves as if padded with alpha = 1, q = k = v = 0).
+ *
+ *   q, k        [total_tokens,H,dk] io_dtype   in    sequence b owns the rows cu_seqlens[b] .. cu_seqlens[b+1]-1
+ *   v           [total_tokens,H,dv] io_dtype   in
+ *   log_alpha   [total_tokens,H,dk] fp32       in
+ *   beta        [total_tokens,H,dv]            in    fp32 values or NULL (beta_kind = RODIMUS_BETA_VALUES), or
+ *                                                    io_dtype pre-activations (RODIMUS_BETA_PREACTIVATION, required)
+ *   S0          [N,H,dk,dv] fp32               in, or NULL = zero states
+ *   o           [total_tokens,H,dv] io_dtype   out
+ *   S_T         [N,H,dk,dv] fp32               out, or NULL; MAY be the same buffer as S0 (a state cache updated in
+ *                                                    place); it is the state rodimus_decode_step continues from
+ *   cu_seqlens  [N+1] int32, DEVICE memory     in    non-decreasing, cu_seqlens[0] = 0, cu_seqlens[N] = total_tokens.
+ *                                                    The library cannot read it on the host: the kernels clamp every
+ *                                                    entry to [0, total_tokens], so a corrupt table gives wrong
+ *                                                    results but no access outside the tensors.  Empty sequences are
+ *                                                    allowed (S_T = S0, no output rows).
+ *
+ * One workgroup set per (sequence, head): no workspace, no sequence split (a batch of few long sequences is better
+ * served by rodimus_chunk_scan_fwd per sequence).  Shapes, kernel families, alignment (16 bytes, cu_seqlens included),
+ * aliasing rules and status codes as for rodimus_chunk_scan_fwd; an unknown beta_kind gives RODIMUS_ERR_DTYPE.
+ */
+int rodimus_chunk_scan_varlen_fwd(const void *q, const void *k, const void *v,
+                                  const float *log_alpha, const void *beta, int beta_kind, const float *S0,
+                                  void *o, float *S_T,
+                                  const int *cu_seqlens, int N, int total_tokens,
+                                  int H, int dk, int dv, int chunk, int io_dtype, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -81,8 +81,9 @@ struct ScanArgs {
     const float *S0;
     void *o;
     float *S_T;
-    int B, T, H, dk, dv, chunk;
+    int B, T, H, dk, dv, chunk;      // with cu_seqlens: B sequences, T = total tokens of the packed batch
     int io_dtype;
+    const int *cu_seqlens;           // device, B + 1 entries, or NULL for the dense [B, T, H, .] layout
     void *workspace;
     size_t workspace_bytes;
     hipStream_t stream;

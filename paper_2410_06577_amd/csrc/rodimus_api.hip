@@ -35,13 +35,18 @@ int scan_shape_status(int B, int T, int H, int dk, int dv, int chunk, int io_dty
 }
 
 // The value gate `beta` is either fp32 gate values or (beta_preact) pre-activations in the I/O dtype.
+// Dense layout: B sequences of T tokens.  Packed layout (`packed`): B sequences, T tokens in total, sequence b owning
+// the rows [cu_seqlens[b], cu_seqlens[b+1]) (device memory, so its contents cannot be checked here; the kernels
+// clamp them to the tensor).
 int scan_entry(const void *q, const void *k, const void *v, const float *log_alpha, const void *beta, bool beta_preact,
                const float *S0, void *o, float *S_T, int B, int T, int H, int dk, int dv, int chunk, int io_dtype,
-               void *workspace, size_t workspace_bytes, void *stream)
+               void *workspace, size_t workspace_bytes, void *stream, bool packed = false, const int *cu_seqlens = nullptr)
 {
     const int shape = scan_shape_status(B, T, H, dk, dv, chunk, io_dtype);
     if (shape != RODIMUS_OK) return shape;
-    const size_t tokens = (size_t)B * T * H;
+    if (packed && B > 0 && cu_seqlens == nullptr) return RODIMUS_ERR_NULL;
+    if (packed && misaligned(cu_seqlens)) return RODIMUS_ERR_ALIGN;
+    const size_t tokens = packed ? (size_t)T * H : (size_t)B * T * H;
     if (tokens > 0 && (!q || !k || !v || !log_alpha || !o)) return RODIMUS_ERR_NULL;   // empty tensors may be NULL
     if (tokens > 0 && beta_preact && !beta) return RODIMUS_ERR_NULL;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(log_alpha) || misaligned(beta) ||
@@ -61,12 +66,14 @@ int scan_entry(const void *q, const void *k, const void *v, const float *log_alp
         overlaps(S_T, state_bytes, v, v_bytes) || overlaps(S_T, state_bytes, log_alpha, la_bytes) ||
         overlaps(S_T, state_bytes, beta, beta_bytes))
         return RODIMUS_ERR_ALIAS;
+    const size_t cu_bytes = packed ? ((size_t)B + 1) * sizeof(int) : 0;
+    if (overlaps(o, v_bytes, cu_seqlens, cu_bytes) || overlaps(S_T, state_bytes, cu_seqlens, cu_bytes)) return RODIMUS_ERR_ALIAS;
 
-    const size_t need = scan_mfma_supports(dk, dv, chunk, io_dtype) ? scan_mfma_workspace_bytes(B, T, H, dv) : 0;
+    const size_t need = (!packed && scan_mfma_supports(dk, dv, chunk, io_dtype)) ? scan_mfma_workspace_bytes(B, T, H, dv) : 0;
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return RODIMUS_ERR_WORKSPACE;
 
     ScanArgs a{q, k, v, log_alpha, beta, beta_preact, S0, o, S_T, B, T, H, dk, dv, chunk, io_dtype,
-               workspace, workspace_bytes, static_cast<hipStream_t>(stream)};
+               packed ? cu_seqlens : nullptr, workspace, workspace_bytes, static_cast<hipStream_t>(stream)};
     const hipError_t err = scan_mfma_supports(dk, dv, chunk, io_dtype) ? launch_scan_mfma(a) : launch_scan_generic(a);
     return err == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
 }
@@ -146,6 +153,15 @@ int rodimus_chunk_scan_fwd_zbeta(const void *q, const void *k, const void *v, co
 {
     return scan_entry(q, k, v, log_alpha, z_beta, true, S0, o, S_T, B, T, H, dk, dv, chunk, io_dtype, workspace,
                       workspace_bytes, stream);
+}
+
+int rodimus_chunk_scan_varlen_fwd(const void *q, const void *k, const void *v, const float *log_alpha, const void *beta,
+                                  int beta_kind, const float *S0, void *o, float *S_T, const int *cu_seqlens, int N,
+                                  int total_tokens, int H, int dk, int dv, int chunk, int io_dtype, void *stream)
+{
+    if (beta_kind != RODIMUS_BETA_VALUES && beta_kind != RODIMUS_BETA_PREACTIVATION) return RODIMUS_ERR_DTYPE;
+    return scan_entry(q, k, v, log_alpha, beta, beta_kind == RODIMUS_BETA_PREACTIVATION, S0, o, S_T, N, total_tokens, H,
+                      dk, dv, chunk, io_dtype, nullptr, 0, stream, true, cu_seqlens);
 }
 
 int rodimus_decode_step(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta,

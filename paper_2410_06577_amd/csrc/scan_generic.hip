@@ -40,7 +40,7 @@ template <typename IO>
 __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
     const IO *__restrict__ q, const IO *__restrict__ k, const IO *__restrict__ v,
     const float *__restrict__ log_alpha, const void *__restrict__ beta, bool beta_preact, const float *S0,
-    IO *__restrict__ o, float *S_T, int T, int H, int dk, int dv, int C)
+    IO *__restrict__ o, float *S_T, int T, int H, int dk, int dv, int C, const int *__restrict__ cu_seqlens)
 {
     extern __shared__ float lds[];
     const int dkp = dk + 1;                 // padded row stride against bank conflicts
@@ -56,6 +56,13 @@ __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
     const int tid = threadIdx.x;
     const int bh = blockIdx.x;
     const int b = bh / H, h = bh % H;
+    size_t tok0 = (size_t)b * T;          // row of the sequence's first token
+    if (cu_seqlens != nullptr) {          // packed variable-length batch; bounds clamped to the tensor (T = total tokens)
+        const int first = min(max(cu_seqlens[b], 0), T);
+        const int last = min(max(cu_seqlens[b + 1], first), T);
+        tok0 = first;
+        T = last - first;
+    }
     const int j0 = blockIdx.y * kColTile;
     const int ncol = min(kColTile, dv - j0);
     const int Cp = next_pow2(C);
@@ -71,7 +78,7 @@ __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
 
         for (int e = tid; e < C * dk; e += kThreads) {
             const int t = e / dk, r = e % dk;
-            const size_t g = (((size_t)b * T + s + t) * H + h) * dk + r;
+            const size_t g = ((tok0 + s + t) * H + h) * dk + r;
             const bool ok = t < n;
             sq[t * dkp + r] = ok ? load_as_float(q + g) : 0.f;
             sk[t * dkp + r] = ok ? load_as_float(k + g) : 0.f;
@@ -82,7 +89,7 @@ __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
             const int t = e / kColTile, c = e % kColTile;
             float x = 0.f;
             if (t < n && c < ncol) {
-                const size_t g = (((size_t)b * T + s + t) * H + h) * dv + j0 + c;
+                const size_t g = ((tok0 + s + t) * H + h) * dv + j0 + c;
                 x = load_as_float(v + g);
                 if (beta != nullptr)      // the value gate: given, or the sigmoid of its pre-activation
                     x *= beta_preact ? sigmoid_f(load_as_float(static_cast<const IO *>(beta) + g))
@@ -144,7 +151,7 @@ __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
             float acc = 0.f;
             for (int r = 0; r < dk; ++r) acc = fmaf(sq[t * dkp + r], S[r * kColTile + c], acc);
             for (int i = 0; i <= t; ++i) acc = fmaf(P[t * Pp + i], gv[i * kColTile + c], acc);
-            if (c < ncol) store_from_float(o + (((size_t)b * T + s + t) * H + h) * dv + j0 + c, acc);
+            if (c < ncol) store_from_float(o + ((tok0 + s + t) * H + h) * dv + j0 + c, acc);
         }
         __syncthreads();
 
@@ -183,7 +190,7 @@ static hipError_t launch_typed(const ScanArgs &a)
     if (err != hipSuccess) return err;
     dim3 grid((unsigned)(a.B * a.H), (unsigned)((a.dv + kColTile - 1) / kColTile)), block(kThreads);
     hipLaunchKernelGGL(scan_generic_kernel<IO>, grid, block, lds, a.stream, (const IO *)a.q, (const IO *)a.k,
-                       (const IO *)a.v, a.log_alpha, a.beta, a.beta_preact, a.S0, (IO *)a.o, a.S_T, a.T, a.H, a.dk, a.dv, a.chunk);
+                       (const IO *)a.v, a.log_alpha, a.beta, a.beta_preact, a.S0, (IO *)a.o, a.S_T, a.T, a.H, a.dk, a.dv, a.chunk, a.cu_seqlens);
     return hipGetLastError();
 }
 

@@ -125,9 +125,10 @@ struct Geometry {
     const float *la;
     const void *beta;       // value gate: fp32 values, or bf16 pre-activations (kZBeta), or null
     bf16_t *o;
-    int T, H, dv;
-    int b, h, j0;
-    int t_end;              // one past the last token this workgroup processes (its segment end, <= T)
+    int H, dv;
+    size_t tok0;            // row of the sequence's first token in the [tokens, H, .] tensors
+    int h, j0;
+    int t_end;              // one past the last token this workgroup processes (its segment end, <= sequence length)
 };
 
 // =========================================================================================================
@@ -143,7 +144,7 @@ struct GateLoads {          // one row, 16 channels: 8g..8g+7 and 32+8g..32+8g+7
 template <bool kSummary>
 __device__ __forceinline__ void gate_prefetch(const Geometry &g, int t, int grp, GateLoads &p)
 {
-    const size_t tok = ((size_t)g.b * g.T + min(t, g.t_end - 1)) * g.H + g.h;
+    const size_t tok = (g.tok0 + min(t, g.t_end - 1)) * g.H + g.h;
     const bf16_t *qp = g.q + tok * kK + 8 * grp;
     const bf16_t *kp = g.k + tok * kK + 8 * grp;
     const float *lp = g.la + tok * kK + 8 * grp;
@@ -453,7 +454,7 @@ __device__ __forceinline__ void state_prefetch(const Geometry &g, int s, int til
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int t = min(s + 16 * tile + 4 * u + rsub, g.t_end - 1);   // clamped: padded rows are zeroed in stage_values
-        const size_t off = (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 8 * piece;
+        const size_t off = ((g.tok0 + t) * g.H + g.h) * g.dv + g.j0 + 8 * piece;
         p.v[u] = load_streaming(g.v + off);
         if (kZBeta) {
             p.zbeta[u] = load_streaming(static_cast<const bf16_t *>(g.beta) + off);
@@ -516,7 +517,7 @@ __device__ __forceinline__ void store_outputs(const Geometry &g, const unsigned 
         const int t = s + row;
         if (t < g.t_end)
             __builtin_nontemporal_store(__builtin_bit_cast(floatx4_t, w),
-                                        reinterpret_cast<floatx4_t *>(g.o + (((size_t)g.b * g.T + t) * g.H + g.h) * g.dv + g.j0 + 8 * unit));
+                                        reinterpret_cast<floatx4_t *>(g.o + ((g.tok0 + t) * g.H + g.h) * g.dv + g.j0 + 8 * unit));
     }
 }
 
@@ -640,7 +641,8 @@ template <bool kSummary, bool kZBeta>
 __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const float *__restrict__ log_alpha, const void *__restrict__ beta, const float *S0,
-    bf16_t *__restrict__ o, float *S_T, int T, int H, int dv, SegmentPlan plan)
+    bf16_t *__restrict__ o, float *S_T, int T, int H, int dv, SegmentPlan plan, const int *__restrict__ cu_seqlens,
+    int total_tokens)
 {
     extern __shared__ __align__(16) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -651,8 +653,17 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
 
     Geometry g;
     g.q = q; g.k = k; g.v = v; g.la = log_alpha; g.beta = beta; g.o = o;
-    g.T = T; g.H = H; g.dv = dv;
-    g.b = bh / H; g.h = bh % H; g.j0 = blockIdx.y * kColTile;
+    g.H = H; g.dv = dv;
+    g.h = bh % H; g.j0 = blockIdx.y * kColTile;
+    g.tok0 = (size_t)(bh / H) * T;
+    if (cu_seqlens != nullptr) {
+        // packed variable-length batch: sequence bh / H owns the token rows [cu[b], cu[b+1]); the bounds are clamped
+        // to the tensor so that a corrupt table cannot take an access outside it
+        const int first = min(max(cu_seqlens[bh / H], 0), total_tokens);
+        const int last = min(max(cu_seqlens[bh / H + 1], first), total_tokens);
+        g.tok0 = first;
+        T = last - first;
+    }
     const int t_begin = seg * plan.seg_tokens;
     g.t_end = min(T, t_begin + plan.seg_tokens);
 
@@ -812,7 +823,10 @@ namespace {
 template <bool kZBeta>
 hipError_t launch_scan_mfma_typed(const ScanArgs &a)
 {
-    const SplitShape sp = choose_split(a.B, a.T, a.H, a.dv);
+    // a packed variable-length batch is never cut into segments (its lengths live in device memory): one segment
+    // that covers any length
+    const SplitShape sp = a.cu_seqlens != nullptr ? SplitShape{1, ((a.T + kChunk - 1) / kChunk) * kChunk}
+                                                  : choose_split(a.B, a.T, a.H, a.dv);
     const size_t bh = (size_t)a.B * a.H;
     SegmentPlan plan{sp.nseg, sp.seg_tokens, nullptr, nullptr};
     hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel<false, kZBeta>),
@@ -828,14 +842,15 @@ hipError_t launch_scan_mfma_typed(const ScanArgs &a)
         plan.gamma = plan.slots + (size_t)sp.nseg * bh * kK * a.dv;
         hipLaunchKernelGGL((scan_mfma_kernel<true, kZBeta>), dim3((unsigned)bh, col_tiles, (unsigned)(sp.nseg - 1)), block,
                            kLdsBytes, a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha,
-                           a.beta, (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, a.T, a.H, a.dv, plan);
+                           a.beta, (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, a.T, a.H, a.dv, plan,
+                           (const int *)nullptr, 0);
         const size_t quads = bh * kK * a.dv / 4;
         hipLaunchKernelGGL(segment_state_scan_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, a.stream, a.S0,
                            plan, a.dv, quads);
     }
     hipLaunchKernelGGL((scan_mfma_kernel<false, kZBeta>), dim3((unsigned)bh, col_tiles, (unsigned)sp.nseg), block, kLdsBytes,
                        a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0,
-                       (bf16_t *)a.o, a.S_T, a.T, a.H, a.dv, plan);
+                       (bf16_t *)a.o, a.S_T, a.T, a.H, a.dv, plan, a.cu_seqlens, a.T);
     return hipGetLastError();
 }
 

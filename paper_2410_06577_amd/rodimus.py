@@ -51,6 +51,8 @@ def lib() -> ctypes.CDLL:
         L.rodimus_chunk_scan_fwd_zbeta.restype = i
         L.rodimus_decode_step_zbeta.argtypes = L.rodimus_decode_step.argtypes
         L.rodimus_decode_step_zbeta.restype = i
+        L.rodimus_chunk_scan_varlen_fwd.argtypes = [vp] * 5 + [i] + [vp] * 4 + [i] * 7 + [vp]
+        L.rodimus_chunk_scan_varlen_fwd.restype = i
         L.rodimus_ddts_gates.argtypes = [vp] * 9 + [ctypes.c_longlong, i, i, i, vp]
         L.rodimus_ddts_gates.restype = i
         _lib = L
@@ -137,6 +139,45 @@ def rodimus_chunk_scan_fwd(q, k, v, log_alpha, beta=None, S0=None, *, chunk=64, 
 def rodimus_chunk_scan_fwd_zbeta(q, k, v, log_alpha, z_beta, S0=None, **kw):
     """``rodimus_chunk_scan_fwd`` with the value gate given as its pre-activation z_beta [B,T,H,dv] (dtype of v)."""
     return rodimus_chunk_scan_fwd(q, k, v, log_alpha, z_beta, S0, _preact=True, **kw)
+
+
+def rodimus_chunk_scan_varlen_fwd(q, k, v, log_alpha, cu_seqlens, beta=None, S0=None, *, z_beta=None, chunk=64, o=None,
+                                  S_T=None, want_state=True):
+    """Chunkwise forward scan over a packed variable-length batch.
+
+    q,k,log_alpha [total,H,dk]; v, beta (fp32) or z_beta (dtype of v) [total,H,dv]; cu_seqlens [N+1] int32 on the
+    device; S0, S_T [N,H,dk,dv] fp32.  Returns (o [total,H,dv], S_T or None).
+    """
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_chunk_scan_varlen_fwd needs device tensors (no CPU path exists)")
+    if beta is not None and z_beta is not None:
+        raise ValueError("give beta or z_beta, not both")
+    total, H, dk = q.shape
+    dv = v.shape[-1]
+    dev, io = q.device, q.dtype
+    N = cu_seqlens.numel() - 1
+    _require(cu_seqlens, "cu_seqlens", (N + 1,), torch.int32, dev)
+    _require(q, "q", (total, H, dk), io, dev)
+    _require(k, "k", (total, H, dk), io, dev)
+    _require(v, "v", (total, H, dv), io, dev)
+    _require(log_alpha, "log_alpha", (total, H, dk), torch.float32, dev)
+    _require(beta, "beta", (total, H, dv), torch.float32, dev)
+    _require(z_beta, "z_beta", (total, H, dv), io, dev)
+    _require(S0, "S0", (N, H, dk, dv), torch.float32, dev)
+    if o is None:
+        o = torch.empty((total, H, dv), dtype=io, device=dev)
+    _require(o, "o", (total, H, dv), io, dev)
+    if S_T is None and want_state:
+        S_T = torch.empty((N, H, dk, dv), dtype=torch.float32, device=dev)
+    _require(S_T, "S_T", (N, H, dk, dv), torch.float32, dev)
+    gate, kind = (z_beta, 1) if z_beta is not None else (beta, 0)
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_chunk_scan_varlen_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(gate), kind, _ptr(S0),
+                                                   _ptr(o), _ptr(S_T), _ptr(cu_seqlens), N, total, H, dk, dv, int(chunk),
+                                                   _DTYPES[io], _stream(dev)))
+    return o, S_T
 
 
 def rodimus_decode_step(q, k, v, log_alpha, beta, S, *, o=None, _preact=False):

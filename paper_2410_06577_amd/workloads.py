@@ -158,3 +158,31 @@ def make_ddts_preactivations(lead: tuple, dk: int, dv: int, io_dtype: str = "bf1
     k = rng.standard_normal(lead + (dk,), dtype=f32)
     return {"z_g": _io(z_g, io_dtype), "z_tau": _io(z_tau, io_dtype), "z_beta": _io(z_beta, io_dtype),
             "q": _io(q, io_dtype), "k": _io(k, io_dtype)}
+
+
+def serving_length_mix(n_seq: int, total_tokens: int, seed: int = 11) -> list:
+    """A prefill batch's length mix: log-uniform lengths (many short prompts, a few long ones), rescaled so that they
+    sum to ``total_tokens`` exactly; every sequence has at least one token."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    raw = np.exp(rng.uniform(np.log(16.0), np.log(4096.0), size=n_seq))
+    lens = np.maximum(1, np.floor(raw * (total_tokens / raw.sum())).astype(np.int64))
+    lens[np.argmax(lens)] += total_tokens - lens.sum()
+    assert lens.sum() == total_tokens and lens.min() >= 1
+    return [int(x) for x in lens]
+
+
+def make_varlen_inputs(lengths, H: int, dk: int, dv: int, io_dtype: str = "bf16", s0_std: float = 0.1, seed: int = 12) -> dict:
+    """Packed variable-length batch: q,k,log_alpha [total,H,dk]; v,beta,z_beta [total,H,dv]; cu_seqlens [N+1] int32;
+    S0 [N,H,dk,dv] fp32 or None.  Same per-token recipe as ``make_scan_inputs``."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    total = int(sum(lengths))
+    d = _draw_token_inputs(rng, (total, H), dk, dv, 0.0, (0.5, 1.0), io_dtype)
+    cu = np.zeros(len(lengths) + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(np.asarray(lengths, dtype=np.int64))
+    d["cu_seqlens"] = torch.from_numpy(cu)
+    if s0_std > 0:
+        S0 = rng.standard_normal((len(lengths), H, dk, dv), dtype=np.float32) * np.float32(s0_std)
+        d["S0"] = torch.from_numpy(S0)
+    else:
+        d["S0"] = None
+    return d

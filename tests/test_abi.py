@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(L):
     declared = set(re.findall(r"\b(rodimus_[a-z_]+)\s*\(", header))
     assert {"rodimus_chunk_scan_fwd", "rodimus_decode_step", "rodimus_status_string",
             "rodimus_chunk_scan_workspace_bytes", "rodimus_chunk_scan_path", "rodimus_ddts_gates",
-            "rodimus_chunk_scan_fwd_zbeta", "rodimus_decode_step_zbeta"} <= declared
+            "rodimus_chunk_scan_fwd_zbeta", "rodimus_decode_step_zbeta", "rodimus_chunk_scan_varlen_fwd"} <= declared
     for name in declared:
         assert hasattr(L, name), name
 
@@ -120,6 +120,25 @@ def test_zbeta_calls_validate_like_the_calls_they_mirror(L):
     # z_beta has the I/O element size: 4*32 bf16 = 256 bytes from 0x50000; an output just behind it is fine, on it is not
     assert scan(o=0x50080) == E_ALIAS
     assert dec(S=0x50040) == E_ALIAS
+
+
+def test_varlen_scan_validation(L):
+    p = ctypes.c_void_p
+
+    def call(beta=0x50000, kind=0, cu=0x90000, N=2, total=8, o=0x70000, S_T=0x80000, io=rodimus.F32, dk=16):
+        f = lambda x: None if x is None else p(x)
+        return L.rodimus_chunk_scan_varlen_fwd(p(0x10000), p(0x20000), p(0x30000), p(0x40000), f(beta), kind, p(0x60000),
+                                               f(o), f(S_T), f(cu), N, total, 1, dk, 32, 4, io, None)
+
+    assert call(kind=2) == E_DTYPE and call(io=3) == E_DTYPE
+    assert call(cu=None) == E_NULL
+    assert call(cu=0x90004) == E_ALIGN
+    assert call(kind=1, beta=None) == E_NULL            # a pre-activation is required, plain beta is optional
+    assert call(N=-1) == E_SHAPE and call(total=-1) == E_SHAPE and call(dk=0) == E_SHAPE
+    assert call(o=0x90000) == E_ALIAS                   # o over the length table
+    assert call(S_T=0x90000) == E_ALIAS
+    assert call(N=0, total=0, cu=None, S_T=None) == OK  # empty batch
+    assert call(total=0, S_T=None) == OK                # sequences of length zero, no state wanted
 
 
 def test_empty_problems_are_successful_noops(L):
