@@ -8,7 +8,8 @@ Contents
 --------
 ``rodimus_oracle.c``  the sequential recurrence in plain C, IEEE double
                       (paper Sec. 3.1.3, state recurrence of the Rodimus block).
-``sequential.py``     ctypes loader for it: ``scan``, ``step`` and ``ddts_gates`` (the gate front-end of Sec. 3.1.2).
+``sequential.py``     ctypes loader for it: ``scan``, ``step``, ``scan_bwd`` (reverse-mode differentiation of the
+                      recurrence, step by step) and ``ddts_gates`` (the gate front-end of Sec. 3.1.2).
 ``chunkwise.py``      the same result computed by the chunkwise form of the
                       appendix "Chunkwise Parallel Representation of the Rodimus
                       Block", in numpy fp64 -- used to check the chunk algebra
@@ -17,6 +18,8 @@ Contents
 
 Pins (tests/test_oracle_pins.py): reduction to plain causal linear attention,
 alpha = 0, the unrolled O(T^2) weighted sum, geometric-series closed form,
-a hand-worked rational example, split-sequence and chunk-size invariance.
+a hand-worked rational example, split-sequence and chunk-size invariance;
+(tests/test_oracle_backward.py): central finite differences of ``scan``, the
+linear-attention closed forms, the T = 1 case by hand, split-sequence chaining.
 """
-from .sequential import ddts_gates, scan, step, threads  # noqa: F401
+from .sequential import ddts_gates, scan, scan_bwd, step, threads  # noqa: F401

@@ -205,3 +205,115 @@ int rodimus_oracle_ddts_gates(const float *z_g, const float *z_tau, const float 
     }
     return 0;
 }
+
+/*
+ * Backward pass of the sequential scan: reverse-mode differentiation of the recurrence above, step by step
+ * (training use of the block, paper Sec. 3.1.3; the recurrence is the one printed there).  Given the
+ * cotangents do_t of the outputs and dS_T of the final state (NULL = zero), with
+ *
+ *     S_t = diag(a_t) S_{t-1} + k_t^T u_t,   u_t = beta_t .* v_t,   a_t = exp(log_alpha_t),   o_t = q_t S_t
+ *
+ * the total cotangent of S_t is  G_t = q_t^T do_t + diag(a_{t+1}) G_{t+1}  (G_{T+1} taken so that the carried term at
+ * t = T is dS_T), and
+ *
+ *     dq_t = do_t S_t^T              dk_t = u_t G_t^T              du_t = k_t G_t
+ *     dv_t = beta_t .* du_t          dbeta_t = v_t .* du_t
+ *     dlog_alpha_t = a_t .* rowsum(G_t .* S_{t-1})                 dS_0 = diag(a_1) G_1
+ *
+ * The states S_t are needed in reverse order: they are kept at every `segment`-th step during a forward sweep and
+ * recomputed inside a segment (the same arithmetic as the forward oracle, so nothing is approximated).
+ * beta == NULL means the all-ones gate (dbeta is then not written and may be NULL).  Any output pointer may be NULL.
+ * Returns 0 on success, 1 on bad arguments, 2 on allocation failure.
+ */
+int rodimus_oracle_scan_bwd(const float *q, const float *k, const float *v,
+                            const float *log_alpha, const float *beta, const double *S0,
+                            const double *d_o, const double *dS_T,
+                            double *dq, double *dk, double *dv, double *dlog_alpha, double *dbeta, double *dS0,
+                            int B, int T, int H, int dk_, int dv_)
+{
+    const int n = dk_, m = dv_, segment = 64;
+    if (!q || !k || !v || !log_alpha || !d_o) return 1;
+    if (B < 0 || T < 0 || H < 0 || n <= 0 || m <= 0) return 1;
+    int failed = 0;
+
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < H; ++h) {
+            const size_t sz = (size_t)n * m;
+            const int nseg = (T + segment - 1) / segment;
+            double *ck = (double *)malloc(sizeof(double) * sz * (size_t)(nseg + 1));      /* state entering each segment */
+            double *sb = (double *)malloc(sizeof(double) * sz * (size_t)(segment + 1));   /* states inside one segment  */
+            double *G = (double *)malloc(sizeof(double) * sz);
+            double *u = (double *)malloc(sizeof(double) * (size_t)m);
+            double *du = (double *)malloc(sizeof(double) * (size_t)m);
+            double *otmp = (double *)malloc(sizeof(double) * (size_t)m);
+            if (!ck || !sb || !G || !u || !du || !otmp) {
+                free(ck); free(sb); free(G); free(u); free(du); free(otmp);
+#pragma omp atomic write
+                failed = 1;
+                continue;
+            }
+            const size_t state_off = ((size_t)b * H + h) * sz;
+            /* forward sweep: remember the state entering every segment */
+            for (size_t e = 0; e < sz; ++e) ck[e] = S0 ? S0[state_off + e] : 0.0;
+            for (int s = 0; s < nseg; ++s) {
+                double *cur = ck + (size_t)(s + 1) * sz;
+                for (size_t e = 0; e < sz; ++e) cur[e] = ck[(size_t)s * sz + e];
+                const int t1 = (s + 1) * segment < T ? (s + 1) * segment : T;
+                for (int t = s * segment; t < t1; ++t) {
+                    const size_t row = ((size_t)b * T + t) * H + h;
+                    ddts_update(cur, q + row * n, k + row * n, v + row * m, log_alpha + row * n,
+                                beta ? beta + row * m : NULL, 0, otmp, n, m, u);
+                }
+            }
+            /* reverse sweep */
+            for (size_t e = 0; e < sz; ++e) G[e] = dS_T ? dS_T[state_off + e] : 0.0;     /* carried term diag(a_{t+1}) G_{t+1} */
+            for (int s = nseg - 1; s >= 0; --s) {
+                const int t0 = s * segment, t1 = (s + 1) * segment < T ? (s + 1) * segment : T;
+                for (size_t e = 0; e < sz; ++e) sb[e] = ck[(size_t)s * sz + e];
+                for (int t = t0; t < t1; ++t) {             /* sb[i+1] = S_t for t = t0 + i */
+                    const size_t row = ((size_t)b * T + t) * H + h;
+                    double *nxt = sb + (size_t)(t - t0 + 1) * sz;
+                    for (size_t e = 0; e < sz; ++e) nxt[e] = sb[(size_t)(t - t0) * sz + e];
+                    ddts_update(nxt, q + row * n, k + row * n, v + row * m, log_alpha + row * n,
+                                beta ? beta + row * m : NULL, 0, otmp, n, m, u);
+                }
+                for (int t = t1 - 1; t >= t0; --t) {
+                    const size_t row = ((size_t)b * T + t) * H + h;
+                    const double *St = sb + (size_t)(t - t0 + 1) * sz, *Sp = sb + (size_t)(t - t0) * sz;
+                    const float *qt = q + row * n, *kt = k + row * n, *vt = v + row * m, *lt = log_alpha + row * n;
+                    const float *bt = beta ? beta + row * m : NULL;
+                    const double *dot = d_o + row * m;
+                    /* G_t = carried + q_t^T do_t */
+                    for (int r = 0; r < n; ++r)
+                        for (int j = 0; j < m; ++j) G[(size_t)r * m + j] += (double)qt[r] * dot[j];
+                    for (int j = 0; j < m; ++j) {
+                        u[j] = (bt ? (double)bt[j] : 1.0) * (double)vt[j];
+                        double acc = 0.0;
+                        for (int r = 0; r < n; ++r) acc += (double)kt[r] * G[(size_t)r * m + j];
+                        du[j] = acc;
+                        if (dv) dv[row * m + j] = (bt ? (double)bt[j] : 1.0) * acc;
+                        if (dbeta && bt) dbeta[row * m + j] = (double)vt[j] * acc;
+                    }
+                    for (int r = 0; r < n; ++r) {
+                        const double a = exp((double)lt[r]);
+                        double accq = 0.0, acck = 0.0, acca = 0.0;
+                        for (int j = 0; j < m; ++j) {
+                            accq += St[(size_t)r * m + j] * dot[j];
+                            acck += G[(size_t)r * m + j] * u[j];
+                            acca += G[(size_t)r * m + j] * Sp[(size_t)r * m + j];
+                        }
+                        if (dq) dq[row * n + r] = accq;
+                        if (dk) dk[row * n + r] = acck;
+                        if (dlog_alpha) dlog_alpha[row * n + r] = a * acca;
+                        for (int j = 0; j < m; ++j) G[(size_t)r * m + j] *= a;       /* carried to step t-1 */
+                    }
+                }
+            }
+            if (dS0)
+                for (size_t e = 0; e < sz; ++e) dS0[state_off + e] = G[e];
+            free(ck); free(sb); free(G); free(u); free(du); free(otmp);
+        }
+    }
+    return failed ? 2 : 0;
+}

@@ -30,6 +30,8 @@ def _load():
         lib.rodimus_oracle_step.argtypes = [f32p, f32p, f32p, f32p, f32p, f64p, f64p] + [ctypes.c_int] * 5
         lib.rodimus_oracle_step.restype = ctypes.c_int
         lib.rodimus_oracle_threads.restype = ctypes.c_int
+        lib.rodimus_oracle_scan_bwd.argtypes = [f32p] * 5 + [f64p] * 9 + [ctypes.c_int] * 5
+        lib.rodimus_oracle_scan_bwd.restype = ctypes.c_int
         lib.rodimus_oracle_ddts_gates.argtypes = [f32p] * 5 + [f64p] * 4 + [ctypes.c_long, ctypes.c_int, ctypes.c_int]
         lib.rodimus_oracle_ddts_gates.restype = ctypes.c_int
         _lib = lib
@@ -98,6 +100,28 @@ def scan(q, k, v, log_alpha, beta=None, S0=None, want_state=True, z_beta=None):
     if rc != 0:
         raise RuntimeError(f"rodimus_oracle_scan failed with code {rc}")
     return o, S_T
+
+
+def scan_bwd(q, k, v, log_alpha, beta, S0, d_o, dS_T=None):
+    """Backward of ``scan``: cotangents d_o [B,T,H,dv] (and dS_T [B,H,dk,dv] or None) -> dict of float64 gradients
+    dq, dk, dlog_alpha [B,T,H,dk]; dv, dbeta (None without beta) [B,T,H,dv]; dS0 [B,H,dk,dv]."""
+    lib = _load()
+    q, k, v, la, beta = _f32(q), _f32(k), _f32(v), _f32(log_alpha), _f32(beta)
+    S0, d_o, dS_T = _f64(S0), _f64(d_o), _f64(dS_T)
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    assert d_o.shape == (B, T, H, dv) and (dS_T is None or dS_T.shape == (B, H, dk, dv))
+    out = {"dq": np.zeros((B, T, H, dk)), "dk": np.zeros((B, T, H, dk)), "dlog_alpha": np.zeros((B, T, H, dk)),
+           "dv": np.zeros((B, T, H, dv)), "dbeta": None if beta is None else np.zeros((B, T, H, dv)),
+           "dS0": np.zeros((B, H, dk, dv))}
+    d = ctypes.c_double
+    rc = lib.rodimus_oracle_scan_bwd(_ptr(q, ctypes.c_float), _ptr(k, ctypes.c_float), _ptr(v, ctypes.c_float),
+                                     _ptr(la, ctypes.c_float), _ptr(beta, ctypes.c_float), _ptr(S0, d), _ptr(d_o, d),
+                                     _ptr(dS_T, d), _ptr(out["dq"], d), _ptr(out["dk"], d), _ptr(out["dv"], d),
+                                     _ptr(out["dlog_alpha"], d), _ptr(out["dbeta"], d), _ptr(out["dS0"], d), B, T, H, dk, dv)
+    if rc != 0:
+        raise RuntimeError(f"rodimus_oracle_scan_bwd failed with code {rc}")
+    return out
 
 
 def step(q, k, v, log_alpha, beta, S, z_beta=None):
