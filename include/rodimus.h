@@ -206,6 +206,39 @@ int rodimus_chunk_scan_varlen_fwd(const void *q, const void *k, const void *v,
                                   const int *cu_seqlens, int N, int total_tokens,
                                   int H, int dk, int dv, int chunk, int io_dtype, void *stream);
 
+/*
+ * Backward pass of rodimus_chunk_scan_fwd (training; paper Sec. 3.1.3 trains the block through its chunkwise form):
+ * reverse-mode differentiation of the recurrence.  Given the cotangents d_o of the outputs and dS_T of the final
+ * state, with u_t = beta_t .* v_t, a_t = exp(log_alpha_t) and G_t = q_t^T do_t + diag(a_{t+1}) G_{t+1} the total
+ * cotangent of S_t:
+ *     dq_t = do_t S_t^T,  dk_t = u_t G_t^T,  dv_t = beta_t .* (k_t G_t),  dbeta_t = v_t .* (k_t G_t),
+ *     dlog_alpha_t = a_t .* rowsum(G_t .* S_{t-1}),  dS0 = diag(a_1) G_1.
+ *
+ *   q, k, v, log_alpha, beta, S0    as for rodimus_chunk_scan_fwd                      in
+ *   d_o         [B,T,H,dv] io_dtype      in
+ *   dS_T        [B,H,dk,dv] fp32         in, or NULL = zero
+ *   dq, dk      [B,T,H,dk] io_dtype      out
+ *   dv          [B,T,H,dv] io_dtype      out
+ *   dlog_alpha  [B,T,H,dk] fp32          out   (0 where log_alpha <= -128: such a gate is treated as closed)
+ *   dbeta       [B,T,H,dv] fp32          out, or NULL if not wanted (v .* (k G) is written even when beta is NULL)
+ *   dS0         [B,H,dk,dv] fp32         out, or NULL if not wanted
+ *   workspace   rodimus_chunk_scan_bwd_workspace_bytes(...) bytes of device scratch (q .* dq in fp32), 16-byte aligned
+ *
+ * No output may overlap an input, another output or the workspace.  Supported: io_dtype = BF16, dk = 64,
+ * dv = 128 or 256, any T (a 16-token tile is the internal chunk); other shapes return RODIMUS_ERR_SHAPE.  bf16 MFMA
+ * operands, fp32 accumulation and fp32 gate arithmetic; two kernels (a forward sweep for dq, a reverse sweep for the rest),
+ * one workgroup per (batch, head).
+ */
+int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v,
+                           const float *log_alpha, const float *beta, const float *S0,
+                           const void *d_o, const float *dS_T,
+                           void *dq, void *dk, void *dv_out, float *dlog_alpha, float *dbeta, float *dS0,
+                           int B, int T, int H, int dk_width, int dv, int io_dtype,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/* Scratch bytes the call above needs (0 if the shape is not supported). */
+size_t rodimus_chunk_scan_bwd_workspace_bytes(int B, int T, int H, int dk, int dv, int io_dtype);
+
 #ifdef __cplusplus
 }
 #endif

@@ -71,6 +71,33 @@ template <> __device__ __forceinline__ void store4_from_float<bf16_t>(bf16_t *p,
     *reinterpret_cast<uint2 *>(p) = u;
 }
 
+// ---- MFMA and LDS helpers shared by the scan kernels ---------------------------------------------------
+__device__ __forceinline__ floatx4_t mfma_k32(bf16x8_t a, bf16x8_t b, floatx4_t c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+// Contraction over the 16 tokens of a tile: each lane supplies 4 of them, the other 4 operand slots are zero.
+// (The 16x16x32 form is used on purpose: with the 16x16x16 bf16 instruction this compiler consumed MFMA results
+// before they were written.)
+__device__ __forceinline__ floatx4_t mfma_k16(uint2 a, uint2 b, floatx4_t c)
+{
+    const uint4 a8 = {a.x, a.y, 0u, 0u}, b8 = {b.x, b.y, 0u, 0u};
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a8), __builtin_bit_cast(bf16x8_t, b8), c, 0, 0, 0);
+}
+
+// k .* G and beta .* v are MFMA operands with the token as the contraction index, but arrive token-major.  They
+// are stored token-major (rows of 64 channels / 128 columns, written 8 bytes at a time) and fetched with the
+// transposing LDS read: inside each group of 16 lanes, lane 4j + c supplies the address of 4 consecutive bf16 of
+// row j, and lane 4c + e receives element e of the four rows j = 0..3.  So a lane ends up with 4 tokens of one
+// channel / column, which is the operand layout, without any 2-byte scatter.
+__device__ __forceinline__ uint2 lds_read_transposed(const unsigned char *p)
+{
+    typedef short short4_t __attribute__((ext_vector_type(4)));
+    const short4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (short4_t __attribute__((address_space(3))) *)(p));
+    return __builtin_bit_cast(uint2, r);
+}
+
 // ---- launchers (host).  Arguments are already validated by the C-ABI layer. -------------------------
 // `beta` is the value gate: fp32 values, or (beta_preact) its pre-activation in the I/O dtype, or NULL (all ones).
 struct ScanArgs {
@@ -110,6 +137,24 @@ struct GateArgs {
     hipStream_t stream;
 };
 
+// Backward of the dense scan.  d_o, dq, dk, dv in the I/O dtype; dlog_alpha, dbeta, dS0, dS_T fp32.
+struct ScanBwdArgs {
+    const void *q, *k, *v;
+    const float *log_alpha, *beta, *S0;
+    const void *d_o;
+    const float *dS_T;
+    void *dq, *dk, *dv;
+    float *dlog_alpha, *dbeta, *dS0;
+    int B, T, H, dk_width, dv_width;
+    int io_dtype;
+    void *workspace;
+    size_t workspace_bytes;
+    hipStream_t stream;
+};
+
+hipError_t launch_scan_bwd(const ScanBwdArgs &a);
+bool scan_bwd_supports(int dk, int dv, int io_dtype);
+size_t scan_bwd_workspace_bytes(int B, int T, int H);
 hipError_t launch_decode_step(const DecodeArgs &a);
 hipError_t launch_ddts_gates(const GateArgs &a);
 hipError_t launch_scan_generic(const ScanArgs &a);

@@ -176,6 +176,47 @@ int rodimus_decode_step_zbeta(const void *q, const void *k, const void *v, const
     return decode_entry(q, k, v, log_alpha, z_beta, true, S, o, N, H, dk, dv, io_dtype, stream);
 }
 
+size_t rodimus_chunk_scan_bwd_workspace_bytes(int B, int T, int H, int dk, int dv, int io_dtype)
+{
+    if (B < 0 || T < 0 || H < 0 || !scan_bwd_supports(dk, dv, io_dtype)) return 0;
+    return scan_bwd_workspace_bytes(B, T, H);
+}
+
+int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta,
+                           const float *S0, const void *d_o, const float *dS_T, void *dq, void *dk, void *dv_out,
+                           float *dlog_alpha, float *dbeta, float *dS0, int B, int T, int H, int dk_width, int dv,
+                           int io_dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
+    if (B < 0 || T < 0 || H < 0 || (long long)B * H > kMaxGridX) return RODIMUS_ERR_SHAPE;
+    if (!scan_bwd_supports(dk_width, dv, io_dtype)) return RODIMUS_ERR_SHAPE;
+    const size_t tokens = (size_t)B * T * H, states = (size_t)B * H;
+    if (tokens > 0 && (!q || !k || !v || !log_alpha || !d_o || !dq || !dk || !dv_out || !dlog_alpha)) return RODIMUS_ERR_NULL;
+    const size_t eb = elem_bytes(io_dtype);
+    const void *ins[8] = {q, k, v, log_alpha, beta, S0, d_o, dS_T};
+    const size_t in_bytes[8] = {tokens * dk_width * eb, tokens * dk_width * eb, tokens * dv * eb, tokens * dk_width * 4,
+                                tokens * dv * 4, states * dk_width * dv * 4, tokens * dv * eb, states * dk_width * dv * 4};
+    void *outs[7] = {dq, dk, dv_out, dlog_alpha, dbeta, dS0, workspace};
+    const size_t need = scan_bwd_workspace_bytes(B, T, H);
+    const size_t out_bytes[7] = {tokens * dk_width * eb, tokens * dk_width * eb, tokens * dv * eb, tokens * dk_width * 4,
+                                 tokens * dv * 4, states * dk_width * dv * 4, need};
+    for (int i = 0; i < 8; ++i)
+        if (misaligned(ins[i])) return RODIMUS_ERR_ALIGN;
+    for (int o = 0; o < 7; ++o)
+        if (misaligned(outs[o])) return RODIMUS_ERR_ALIGN;
+    for (int o = 0; o < 7; ++o) {
+        for (int i = 0; i < 8; ++i)
+            if (overlaps(outs[o], out_bytes[o], ins[i], in_bytes[i])) return RODIMUS_ERR_ALIAS;
+        for (int p = o + 1; p < 7; ++p)
+            if (overlaps(outs[o], out_bytes[o], outs[p], out_bytes[p])) return RODIMUS_ERR_ALIAS;
+    }
+    if (states > 0 && need > 0 && (workspace == nullptr || workspace_bytes < need)) return RODIMUS_ERR_WORKSPACE;
+
+    ScanBwdArgs a{q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, dk, dv_out, dlog_alpha, dbeta, dS0, B, T, H, dk_width, dv,
+                  io_dtype, workspace, workspace_bytes, static_cast<hipStream_t>(stream)};
+    return launch_scan_bwd(a) == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
+}
+
 int rodimus_ddts_gates(const void *z_g, const void *z_tau, const void *z_beta, const void *q, const void *k,
                        float *log_alpha, float *beta, void *q_out, void *k_out, long long rows, int dk, int dv,
                        int io_dtype, void *stream)

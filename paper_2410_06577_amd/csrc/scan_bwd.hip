@@ -1,0 +1,679 @@
+// Backward pass of the chunkwise scan (training use of the block, paper Sec. 3.1.3; the algebra is the reverse-mode
+// differentiation of the chunkwise form of the appendix, with a 16-token tile as the chunk).  bf16 I/O, dk = 64,
+// dv = 128 or 256.  With l_t the running sum of log_alpha inside a tile, A_t = exp(l_t), u_t = beta_t .* v_t and
+// w[t,i] = exp(l_t - l_i) (always <= 1 for i <= t: no quotient is ever formed):
+//
+//   forward sweep (scan_bwd_dq_kernel), state S entering the tile:
+//       dP[t,i] = do_t . u_i  (i <= t)
+//       dq_t    = A_t .* (do_t S^T) + sum_{i<=t} dP[t,i] (k_i .* w[t,i])
+//       S      <- diag(A_16) S + sum_i (k_i .* exp(l_16 - l_i))^T u_i
+//   reverse sweep (scan_bwd_dkv_kernel), cotangent G of the state leaving the tile:
+//       P[t,i]  = sum_n q_t k_i w[t,i]  (i <= t)
+//       du_i    = sum_{t>=i} P[t,i] do_t + (k_i .* exp(l_16 - l_i)) G
+//       dk_i    = exp(l_16 - l_i) .* (u_i G^T) + sum_{t>=i} dP[t,i] (q_t .* w[t,i])
+//       G      <- diag(A_16) G + sum_t (q_t .* A_t)^T do_t
+//       dv = beta .* du, dbeta = v .* du, dS0 = G after the first tile
+//   gates: dlog_alpha_t = sum_{s>=t} (q_s .* dq_s - k_s .* dk_s) + rowsum(S_T .* dS_T): every pair (i < t <= s) that the
+//       gate of step t decays appears once in q_s .* dq_s and not in k .* dk of a step >= t, so the reverse running
+//       sum of the difference is the gate's cotangent; it is formed from the fp32 values before dq, dk are rounded.
+//
+// log_alpha is clamped at -128 per step (exp(-128) is zero in fp32), which keeps every l finite.
+// The large contractions (over the dv value columns) run on MFMA with bf16 operands and fp32 accumulation; the
+// 16 x 16 x 64 pairwise terms of a tile run on the vector ALUs in fp32.
+#include "internal.h"
+
+namespace rodimus {
+
+namespace {
+
+constexpr int kK = 64;
+constexpr int kTile = 16;
+constexpr int kBwdThreads = 256;
+constexpr float kMinLogAlpha = -128.f;
+
+// Value columns are stored in LDS in a permuted order inside every group of 32: column 32s + 16h + 4g + e sits at
+// position 32s + 8g + 4h + e.  A 16-byte read at position 32s + 8g then delivers exactly the 8 columns that lane
+// group g of an MFMA accumulator pair (column tiles 2s and 2s+1) holds, so the accumulators can serve as the other
+// operand of a contraction over columns without being moved.
+__device__ __forceinline__ int col_position(int col)
+{
+    return (col & ~31) | (((col >> 2) & 3) << 3) | (((col >> 4) & 1) << 2) | (col & 3);
+}
+
+template <int DV> struct BwdLayout {
+    static constexpr int kRowBytes = DV * 2 + 16;                 // padded token row of bf16 values (bank spread)
+    static constexpr int kPieces = DV / 8;                        // 16-byte pieces per token row
+    static constexpr int kPerThread = kTile * kPieces / kBwdThreads;   // (token, piece) pairs per thread: 1 or 2
+};
+
+// One thread's share of a tile's global inputs, requested one tile ahead.
+template <int DV> struct TileLoads {
+    uint4 qk;                                          // threads 0..127: q piece, 128..255: k piece
+    floatx4_t la;
+    uint4 v[BwdLayout<DV>::kPerThread], d_o[BwdLayout<DV>::kPerThread];
+    floatx4_t beta[BwdLayout<DV>::kPerThread][2];
+};
+
+struct BwdGeometry {
+    const bf16_t *q, *k, *v, *d_o;
+    const float *la, *beta;
+    size_t tok0;      // row of the sequence's first token
+    int T, H, h;
+};
+
+template <int DV>
+__device__ __forceinline__ void tile_prefetch(const BwdGeometry &g, int t0, int tid, bool has_beta, TileLoads<DV> &p)
+{
+    using L = BwdLayout<DV>;
+    {
+        const int tok = (tid & 127) >> 3, piece = tid & 7;
+        const size_t row = (g.tok0 + min(t0 + tok, g.T - 1)) * g.H + g.h;
+        p.qk = *reinterpret_cast<const uint4 *>((tid < 128 ? g.q : g.k) + row * kK + 8 * piece);
+    }
+    {
+        const int tok = tid >> 4, piece = tid & 15;
+        const size_t row = (g.tok0 + min(t0 + tok, g.T - 1)) * g.H + g.h;
+        p.la = *reinterpret_cast<const floatx4_t *>(g.la + row * kK + 4 * piece);
+    }
+#pragma unroll
+    for (int u = 0; u < L::kPerThread; ++u) {
+        const int id = tid + u * kBwdThreads, tok = id / L::kPieces, piece = id % L::kPieces;
+        const size_t off = ((g.tok0 + min(t0 + tok, g.T - 1)) * g.H + g.h) * DV + 8 * piece;
+        p.v[u] = *reinterpret_cast<const uint4 *>(g.v + off);
+        p.d_o[u] = *reinterpret_cast<const uint4 *>(g.d_o + off);
+        if (has_beta) {
+            p.beta[u][0] = *reinterpret_cast<const floatx4_t *>(g.beta + off);
+            p.beta[u][1] = *reinterpret_cast<const floatx4_t *>(g.beta + off + 4);
+        }
+    }
+}
+
+__device__ __forceinline__ void unpack8(const uint4 &w, float (&x)[8])
+{
+    x[0] = bf16_lo(w.x); x[1] = bf16_hi(w.x); x[2] = bf16_lo(w.y); x[3] = bf16_hi(w.y);
+    x[4] = bf16_lo(w.z); x[5] = bf16_hi(w.z); x[6] = bf16_lo(w.w); x[7] = bf16_hi(w.w);
+}
+
+// Tile inputs from registers into LDS: q, k, log_alpha (clamped) as fp32 [16][64]; u = beta .* v and do as bf16 rows
+// with permuted columns.  Rows at or beyond T become q = k = u = do = 0, log_alpha = 0.
+template <int DV>
+__device__ __forceinline__ void tile_stage(const TileLoads<DV> &p, int t0, int T, int tid, bool has_beta, float *qs, float *ks,
+                                           float *ls, unsigned char *us, unsigned char *ds)
+{
+    using L = BwdLayout<DV>;
+    {
+        const int tok = (tid & 127) >> 3, piece = tid & 7;
+        const bool valid = t0 + tok < T;
+        float x[8];
+        unpack8(p.qk, x);
+        float *dst = (tid < 128 ? qs : ks) + tok * kK + 8 * piece;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dst[e] = valid ? x[e] : 0.f;
+    }
+    {
+        const int tok = tid >> 4, piece = tid & 15;
+        const bool valid = t0 + tok < T;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ls[tok * kK + 4 * piece + e] = valid ? fmaxf(p.la[e], kMinLogAlpha) : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < L::kPerThread; ++u) {
+        const int id = tid + u * kBwdThreads, tok = id / L::kPieces, piece = id % L::kPieces;
+        const bool valid = t0 + tok < T;
+        float x[8], d[8];
+        unpack8(p.v[u], x);
+        unpack8(p.d_o[u], d);
+        if (has_beta) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { x[e] *= p.beta[u][0][e]; x[4 + e] *= p.beta[u][1][e]; }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { x[e] = valid ? x[e] : 0.f; d[e] = valid ? d[e] : 0.f; }
+        // columns 8*piece .. +3 and +4 .. +7 are two 8-byte units at permuted positions
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int pos = col_position(8 * piece + 4 * half);
+            const uint2 wu = {pack_bf16x2(x[4 * half], x[4 * half + 1]), pack_bf16x2(x[4 * half + 2], x[4 * half + 3])};
+            const uint2 wd = {pack_bf16x2(d[4 * half], d[4 * half + 1]), pack_bf16x2(d[4 * half + 2], d[4 * half + 3])};
+            *reinterpret_cast<uint2 *>(us + tok * L::kRowBytes + pos * 2) = wu;
+            *reinterpret_cast<uint2 *>(ds + tok * L::kRowBytes + pos * 2) = wd;
+        }
+    }
+}
+
+// =========================================================================================================
+// Forward sweep: dq (and q .* dq in fp32 for the gate cotangent, and rowsum(S_T .* dS_T))
+// =========================================================================================================
+// One workgroup per (batch, head); wavefront w owns key channels 16w .. 16w+15: its slab of the state is kept
+// transposed in MFMA accumulators (lane = channel, registers = value columns), so that do_t S^T contracts over the
+// columns without any exchange between wavefronts.
+template <int DV>
+__global__ __launch_bounds__(kBwdThreads) void scan_bwd_dq_kernel(
+    const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+    const float *__restrict__ log_alpha, const float *__restrict__ beta, const float *__restrict__ S0,
+    const bf16_t *__restrict__ d_o, const float *__restrict__ dS_T, bf16_t *__restrict__ dq,
+    float *__restrict__ qdq, float *__restrict__ gate_const, int T, int H)
+{
+    using L = BwdLayout<DV>;
+    constexpr int kColTiles = DV / 16, kSteps = DV / 32;
+    __shared__ __align__(16) float qs[kTile * kK], ks[kTile * kK], ls[kTile * kK];
+    __shared__ __align__(16) unsigned char us[kTile * L::kRowBytes], ds[kTile * L::kRowBytes];
+    __shared__ __align__(16) float dPw[4][kTile][kTile];
+    __shared__ __align__(16) float qdq_s[kTile * kK];
+    __shared__ __align__(16) bf16_t dq_s[kTile * kK];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, tg = lane >> 4;          // vector-ALU role: channel 16*wave + c, tokens 4tg .. 4tg+3
+    const int ch = 16 * wave + c;
+    const int bh = blockIdx.x;
+    const bool has_beta = beta != nullptr;
+    BwdGeometry g{q, k, v, d_o, log_alpha, beta, (size_t)(bh / H) * T, T, H, bh % H};
+
+    // state slab, transposed: acc[ct][r] = S[ch][16ct + 4tg + r]
+    floatx4_t acc[kColTiles];
+    const size_t state_base = (size_t)bh * kK * DV + (size_t)ch * DV;
+#pragma unroll
+    for (int ct = 0; ct < kColTiles; ++ct)
+        acc[ct] = S0 != nullptr ? *reinterpret_cast<const floatx4_t *>(S0 + state_base + 16 * ct + 4 * tg) : floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+    const int ntiles = (T + kTile - 1) / kTile;
+    TileLoads<DV> pf;
+    if (ntiles > 0) tile_prefetch<DV>(g, 0, tid, has_beta, pf);
+
+    for (int it = 0; it < ntiles; ++it) {
+        const int t0 = it * kTile;
+        __syncthreads();                                   // everyone is done with the previous tile's LDS contents
+        tile_stage<DV>(pf, t0, T, tid, has_beta, qs, ks, ls, us, ds);
+        tile_prefetch<DV>(g, t0 + kTile, tid, has_beta, pf);        // clamped addresses; masked when staged
+        __syncthreads();
+
+        // ---- this lane's channel: running sums of log_alpha, keys
+        float lsum[kTile], kk[kTile];
+        {
+            float run = 0.f;
+#pragma unroll
+            for (int i = 0; i < kTile; ++i) {
+                run += ls[i * kK + ch];
+                lsum[i] = run;
+                kk[i] = ks[i * kK + ch];
+            }
+        }
+        float lt[4];                                       // l of this lane's own four tokens
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            lt[r] = lsum[r];
+#pragma unroll
+            for (int gsel = 1; gsel < 4; ++gsel) lt[r] = (tg == gsel) ? lsum[4 * gsel + r] : lt[r];
+        }
+        const float a_tile = __expf(lsum[kTile - 1]);      // A_16
+
+        // ---- MFMA operands: rows of do (A operand, M = token) for every 32-column step
+        bf16x8_t a_do[kSteps];
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s)
+            a_do[s] = *reinterpret_cast<const bf16x8_t *>(ds + c * L::kRowBytes + (32 * s + 8 * tg) * 2);
+        // dP[t][i] = do_t . u_i, kept for i <= t
+        {
+            floatx4_t d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < kSteps; ++s) {
+                const bf16x8_t b_u = *reinterpret_cast<const bf16x8_t *>(us + c * L::kRowBytes + (32 * s + 8 * tg) * 2);
+                d = mfma_k32(a_do[s], b_u, d);
+            }
+            // lane (i = c, token group tg) holds t = 4tg + r
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dPw[wave][4 * tg + r][c] = (c <= 4 * tg + r) ? d[r] : 0.f;
+        }
+        // do_t S^T for this wavefront's 16 channels: B operand = the state slab, straight from the accumulators
+        floatx4_t dqt = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) {
+            const floatx4_t lo = acc[2 * s], hi = acc[2 * s + 1];
+            const uint4 w = {pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]), pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3])};
+            dqt = mfma_k32(a_do[s], __builtin_bit_cast(bf16x8_t, w), dqt);
+        }
+        // lane (channel c, token group tg) now holds (do_t S^T)[ch] for t = 4tg + r
+
+        // ---- state update S <- diag(A_16) S + sum_i (k_i .* exp(l_16 - l_i))^T u_i   (uses the state before the update above)
+        {
+            float kh[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float kv = kk[r];
+#pragma unroll
+                for (int gsel = 1; gsel < 4; ++gsel) kv = (tg == gsel) ? kk[4 * gsel + r] : kv;
+                kh[r] = kv * __expf(lsum[kTile - 1] - lt[r]);
+            }
+            const uint2 b_k = {pack_bf16x2(kh[0], kh[1]), pack_bf16x2(kh[2], kh[3])};
+            const int j = c >> 2, cc = c & 3;              // transposing read: this lane addresses token 4tg + j, unit cc
+#pragma unroll
+            for (int ct = 0; ct < kColTiles; ++ct) {
+                const int pos = 32 * (ct >> 1) + 8 * cc + 4 * (ct & 1);
+                const uint2 a_u = lds_read_transposed(us + (4 * tg + j) * L::kRowBytes + pos * 2);
+                floatx4_t x = acc[ct];
+                x[0] *= a_tile; x[1] *= a_tile; x[2] *= a_tile; x[3] *= a_tile;
+                acc[ct] = mfma_k16(a_u, b_k, x);
+            }
+        }
+
+        // ---- dq_t = A_t .* (do_t S^T) + sum_{i<=t} dP[t,i] k_i exp(l_t - l_i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int t = 4 * tg + r;
+            float intra = 0.f;
+#pragma unroll
+            for (int i = 0; i < kTile; ++i) {
+                const float wgt = (i <= t) ? __expf(lt[r] - lsum[i]) : 0.f;
+                intra = fmaf(dPw[wave][t][i] * kk[i], wgt, intra);
+            }
+            const float val = fmaf(__expf(lt[r]), dqt[r], intra);
+            dq_s[t * kK + ch] = (bf16_t)val;
+            qdq_s[t * kK + ch] = qs[t * kK + ch] * val;
+        }
+        __syncthreads();
+        // ---- coalesced stores of the tile's dq (bf16) and q .* dq (fp32)
+        {
+            const int tok = tid >> 4, piece = tid & 15;
+            if (t0 + tok < T) {
+                const size_t row = (g.tok0 + t0 + tok) * H + g.h;
+                *reinterpret_cast<floatx4_t *>(qdq + row * kK + 4 * piece) = *reinterpret_cast<const floatx4_t *>(qdq_s + tok * kK + 4 * piece);
+                if (piece < 8)
+                    *reinterpret_cast<uint4 *>(dq + row * kK + 8 * piece) = *reinterpret_cast<const uint4 *>(dq_s + tok * kK + 8 * piece);
+            }
+        }
+    }
+
+    // rowsum(S_T .* dS_T) for this lane's channel: constant term of every gate cotangent of this (batch, head)
+    float part = 0.f;
+    if (dS_T != nullptr) {
+#pragma unroll
+        for (int ct = 0; ct < kColTiles; ++ct) {
+            const floatx4_t gS = *reinterpret_cast<const floatx4_t *>(dS_T + state_base + 16 * ct + 4 * tg);
+            part += acc[ct][0] * gS[0] + acc[ct][1] * gS[1] + acc[ct][2] * gS[2] + acc[ct][3] * gS[3];
+        }
+    }
+    part += __shfl_xor(part, 16);
+    part += __shfl_xor(part, 32);
+    if (tg == 0) gate_const[(size_t)bh * kK + ch] = part;
+}
+
+
+// =========================================================================================================
+// Reverse sweep: dk, dv, dbeta, dlog_alpha, dS0
+// =========================================================================================================
+// One workgroup per (batch, head); wavefront w owns DV/4 value columns: its slab of the state cotangent G lives in MFMA
+// accumulators (lane = column, registers = key channels), as the state does in the forward kernel.  Per tile, last to
+// first:  du^T = G^T khat^T + do^T P   (khat_i = k_i .* exp(l_16 - l_i));  partial u G^T over the slab's columns, summed
+// over the four wavefronts through LDS;  G <- diag(A_16) G + (q .* A)^T do.
+template <int DV> struct DkvLds {       // byte offsets of the reverse kernel's dynamic LDS
+    static constexpr int kSlabCols = DV / 4;
+    static constexpr int kQs = 0;
+    static constexpr int kKs = kQs + kTile * kK * 4;
+    static constexpr int kLs = kKs + kTile * kK * 4;
+    static constexpr int kUs = kLs + kTile * kK * 4;
+    static constexpr int kDs = kUs + kTile * BwdLayout<DV>::kRowBytes;
+    static constexpr int kQa = kDs + kTile * BwdLayout<DV>::kRowBytes;
+    static constexpr int kKh = kQa + kTile * (kK + 8) * 2;
+    static constexpr int kPt = kKh + kTile * (kK + 8) * 2;
+    static constexpr int kDp = kPt + kTile * kTile * 2;
+    static constexpr int kGt = kDp + ((kTile * (kTile + 1) * 4 + 15) / 16) * 16;
+    static constexpr int kRed = kGt + 4 * kSlabCols * (kK + 8) * 2;
+    static constexpr int kDu = kRed + 4 * kTile * kK * 4;
+    static constexpr int kTot = kDu + kTile * (DV + 4) * 4;
+    static constexpr int kBytes = kTot + 4 * kK * 4;
+};
+
+template <int DV>
+__global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
+    const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+    const float *__restrict__ log_alpha, const float *__restrict__ beta, const bf16_t *__restrict__ d_o,
+    const float *__restrict__ dS_T, const float *__restrict__ qdq, const float *__restrict__ gate_const,
+    bf16_t *__restrict__ dk, bf16_t *__restrict__ dv, float *__restrict__ dla, float *__restrict__ dbeta,
+    float *__restrict__ dS0, int T, int H)
+{
+    using L = BwdLayout<DV>;
+    constexpr int kSlab = DV / 4;                    // columns per wavefront
+    constexpr int kCt = kSlab / 16;                  // column tiles per wavefront: 4 (dv = 256) or 2 (dv = 128)
+    constexpr int kDuRow = DV + 4;                   // padded fp32 row of du
+    using M = DkvLds<DV>;
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    float *qs = reinterpret_cast<float *>(lds_raw + M::kQs), *ks = reinterpret_cast<float *>(lds_raw + M::kKs);
+    float *ls = reinterpret_cast<float *>(lds_raw + M::kLs);                 // raw log_alpha, then the running sums l_t
+    unsigned char *us = lds_raw + M::kUs, *ds = lds_raw + M::kDs;
+    bf16_t *qa_s = reinterpret_cast<bf16_t *>(lds_raw + M::kQa);             // q .* A, token-major, padded rows; later dk staging
+    bf16_t *kh_s = reinterpret_cast<bf16_t *>(lds_raw + M::kKh);             // khat, token-major, padded rows
+    bf16_t *pt_s = reinterpret_cast<bf16_t *>(lds_raw + M::kPt);             // P^T: [i][t]
+    float *dp_s = reinterpret_cast<float *>(lds_raw + M::kDp);               // dP: [t][i], padded rows
+    bf16_t *gt_s = reinterpret_cast<bf16_t *>(lds_raw + M::kGt) + (size_t)(threadIdx.x >> 6) * kSlab * (kK + 8);   // this wavefront's G slab as [column][channel]
+    float *red_s = reinterpret_cast<float *>(lds_raw + M::kRed);             // [4][16][64] partial u G^T per wavefront
+    float *du_s = reinterpret_cast<float *>(lds_raw + M::kDu);
+    float *tot_s = reinterpret_cast<float *>(lds_raw + M::kTot);             // [4][64]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, grp = lane >> 4;
+    const int bh = blockIdx.x;
+    const bool has_beta = beta != nullptr;
+    BwdGeometry g{q, k, v, d_o, log_alpha, beta, (size_t)(bh / H) * T, T, H, bh % H};
+    const int col0 = wave * kSlab;
+
+    // cotangent slab: acc[kt][ct][r] = G[16kt + 4grp + r][col0 + 16ct + n]
+    floatx4_t acc[4][kCt];
+    const size_t state_base = (size_t)bh * kK * DV;
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int ct = 0; ct < kCt; ++ct)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                acc[kt][ct][r] = dS_T != nullptr ? dS_T[state_base + (size_t)(16 * kt + 4 * grp + r) * DV + col0 + 16 * ct + n] : 0.f;
+
+    // vector-ALU role of the gate phase: channel vc, tokens 4vg .. 4vg+3
+    const int vc = tid & 63, vg = tid >> 6;
+    float carry = gate_const[(size_t)bh * kK + vc];        // sum over later tokens of (q dq - k dk), plus rowsum(S_T .* dS_T)
+
+    const int ntiles = (T + kTile - 1) / kTile;
+    TileLoads<DV> pf;
+    if (ntiles > 0) tile_prefetch<DV>(g, (ntiles - 1) * kTile, tid, has_beta, pf);
+
+    for (int it = ntiles - 1; it >= 0; --it) {
+        const int t0 = it * kTile;
+        __syncthreads();
+        tile_stage<DV>(pf, t0, T, tid, has_beta, qs, ks, ls, us, ds);
+        // this thread's v and beta pieces are needed again at the end of the tile (dv = beta .* du, dbeta = v .* du)
+        uint4 v_keep[L::kPerThread];
+        floatx4_t beta_keep[L::kPerThread][2];
+#pragma unroll
+        for (int u = 0; u < L::kPerThread; ++u) {
+            v_keep[u] = pf.v[u];
+            beta_keep[u][0] = pf.beta[u][0];
+            beta_keep[u][1] = pf.beta[u][1];
+        }
+        tile_prefetch<DV>(g, max(t0 - kTile, 0), tid, has_beta, pf);
+        // the tile's q .* dq (fp32, written by the forward sweep)
+        floatx4_t qdq_r;
+        {
+            const int tok = tid >> 4, piece = tid & 15;
+            const size_t row = (g.tok0 + min(t0 + tok, T - 1)) * H + g.h;
+            qdq_r = *reinterpret_cast<const floatx4_t *>(qdq + row * kK + 4 * piece);
+            if (t0 + tok >= T) qdq_r = floatx4_t{0.f, 0.f, 0.f, 0.f};
+        }
+        __syncthreads();
+
+        // ---- gate phase (thread = channel vc, token group vg): running sums, q .* A, khat
+        float lsum[kTile];
+        {
+            float run = 0.f;
+#pragma unroll
+            for (int i = 0; i < kTile; ++i) {
+                run += ls[i * kK + vc];
+                lsum[i] = run;
+            }
+        }
+        __syncthreads();                                   // every thread has read the raw log_alpha
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float l_own = lsum[r];
+#pragma unroll
+            for (int gsel = 1; gsel < 4; ++gsel) l_own = (vg == gsel) ? lsum[4 * gsel + r] : l_own;
+            const int t = 4 * vg + r;
+            ls[t * kK + vc] = l_own;                       // from here on ls holds l_t
+            qa_s[t * (kK + 8) + vc] = (bf16_t)(qs[t * kK + vc] * __expf(l_own));
+            kh_s[t * (kK + 8) + vc] = (bf16_t)(ks[t * kK + vc] * __expf(lsum[kTile - 1] - l_own));
+        }
+        // this wavefront's G slab, bf16, as [column][channel] for the transposing read of the u G^T product
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int ct = 0; ct < kCt; ++ct) {
+                const floatx4_t x = acc[kt][ct];
+                const uint2 w = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3])};
+                *reinterpret_cast<uint2 *>(&gt_s[(16 * ct + n) * (kK + 8) + 16 * kt + 4 * grp]) = w;
+            }
+        __syncthreads();
+
+        // ---- P^T[i][t] and dP[t][i]: thread = (t, i) pair, fp32 on the vector ALUs (P) / MFMA by wavefront 0 (dP)
+        {
+            const int t = tid >> 4, i = tid & 15;
+            float p = 0.f;
+            if (i <= t) {
+                for (int cr = 0; cr < kK; ++cr) {
+                    const int c = (cr + i) & (kK - 1);     // rotated per key row: the 16 rows of a wavefront hit 16 different banks
+                    p = fmaf(qs[t * kK + c] * ks[i * kK + c], __expf(ls[t * kK + c] - ls[i * kK + c]), p);
+                }
+            }
+            pt_s[i * kTile + t] = (bf16_t)p;
+        }
+        if (wave == 0) {
+            floatx4_t d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < DV / 32; ++s) {
+                const bf16x8_t a_do = *reinterpret_cast<const bf16x8_t *>(ds + n * L::kRowBytes + (32 * s + 8 * grp) * 2);
+                const bf16x8_t b_u = *reinterpret_cast<const bf16x8_t *>(us + n * L::kRowBytes + (32 * s + 8 * grp) * 2);
+                d = mfma_k32(a_do, b_u, d);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dp_s[(4 * grp + r) * (kTile + 1) + n] = (n <= 4 * grp + r) ? d[r] : 0.f;
+        }
+        __syncthreads();
+
+        // ---- du^T[column][i] = G^T khat^T + do^T P  for this wavefront's columns; result to LDS as du[i][column]
+        {
+            const int j = n >> 2, cc = n & 3;
+            // B operands: rows of khat (8 channels per lane and k-step), row of P^T (4 query tokens per lane)
+            bf16x8_t b_kh[2];
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                // channels 32m + {4grp..4grp+3} (tile 2m) and 32m + 16 + {4grp..} (tile 2m+1): the slots of the packed accumulators
+                const uint2 lo = *reinterpret_cast<const uint2 *>(&kh_s[n * (kK + 8) + 32 * m + 4 * grp]);
+                const uint2 hi = *reinterpret_cast<const uint2 *>(&kh_s[n * (kK + 8) + 32 * m + 16 + 4 * grp]);
+                const uint4 w = {lo.x, lo.y, hi.x, hi.y};
+                b_kh[m] = __builtin_bit_cast(bf16x8_t, w);
+            }
+            const uint2 b_p = *reinterpret_cast<const uint2 *>(&pt_s[n * kTile + 4 * grp]);
+#pragma unroll
+            for (int ct = 0; ct < kCt; ++ct) {
+                floatx4_t d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int m = 0; m < 2; ++m) {
+                    const floatx4_t lo = acc[2 * m][ct], hi = acc[2 * m + 1][ct];
+                    const uint4 w = {pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]), pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3])};
+                    d = mfma_k32(__builtin_bit_cast(bf16x8_t, w), b_kh[m], d);
+                }
+                // do^T tile: lane = column col0 + 16ct + n, 4 tokens 4grp ..; transposing read from the token-major rows
+                const int pos = col_position(col0 + 16 * ct + 4 * cc);
+                const uint2 a_do = lds_read_transposed(ds + (4 * grp + j) * L::kRowBytes + pos * 2);
+                d = mfma_k16(a_do, b_p, d);
+                // lane (token i = n, group grp) holds columns col0 + 16ct + 4grp + r
+                *reinterpret_cast<floatx4_t *>(&du_s[n * kDuRow + col0 + 16 * ct + 4 * grp]) = d;
+            }
+        }
+        // ---- partial (u G^T)[i][channel] over this wavefront's columns
+        {
+            floatx4_t d[4];
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt) d[kt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+            const int j = n >> 2, cc = n & 3;
+#pragma unroll
+            for (int s = 0; s < kSlab / 32; ++s) {
+                // A operand: u rows, columns col0 + 32s + 8grp .. +7 in natural order = two 8-byte units at permuted positions
+                const int c_lo = col0 + 32 * s + 8 * grp;
+                const uint2 u_lo = *reinterpret_cast<const uint2 *>(us + n * L::kRowBytes + col_position(c_lo) * 2);
+                const uint2 u_hi = *reinterpret_cast<const uint2 *>(us + n * L::kRowBytes + col_position(c_lo + 4) * 2);
+                const uint4 wa = {u_lo.x, u_lo.y, u_hi.x, u_hi.y};
+#pragma unroll
+                for (int kt = 0; kt < 4; ++kt) {
+                    // B operand [column][channel]: lane = channel 16kt + n, slots = columns 32s + 8grp + 0..7 (slab-relative)
+                    const bf16_t *base = &gt_s[(32 * s + 8 * grp + j) * (kK + 8) + 16 * kt + 4 * cc];
+                    const uint2 g_lo = lds_read_transposed(reinterpret_cast<const unsigned char *>(base));
+                    const uint2 g_hi = lds_read_transposed(reinterpret_cast<const unsigned char *>(base + 4 * (kK + 8)));
+                    const uint4 wb = {g_lo.x, g_lo.y, g_hi.x, g_hi.y};
+                    d[kt] = mfma_k32(__builtin_bit_cast(bf16x8_t, wa), __builtin_bit_cast(bf16x8_t, wb), d[kt]);
+                }
+            }
+            // lane (channel n of tile kt, group grp) holds tokens i = 4grp + r
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) red_s[wave * kTile * kK + (4 * grp + r) * kK + 16 * kt + n] = d[kt][r];
+        }
+        // ---- G <- diag(A_16) G + (q .* A)^T do
+        {
+            const int j = n >> 2, cc = n & 3;
+            uint2 a_q[4], b_do[kCt];
+            floatx4_t dec[4];
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt) {
+                a_q[kt] = lds_read_transposed(reinterpret_cast<const unsigned char *>(&qa_s[(4 * grp + j) * (kK + 8) + 16 * kt + 4 * cc]));
+#pragma unroll
+                for (int r = 0; r < 4; ++r) dec[kt][r] = __expf(ls[(kTile - 1) * kK + 16 * kt + 4 * grp + r]);
+            }
+#pragma unroll
+            for (int ct = 0; ct < kCt; ++ct)
+                b_do[ct] = lds_read_transposed(ds + (4 * grp + j) * L::kRowBytes + col_position(col0 + 16 * ct + 4 * cc) * 2);
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                for (int ct = 0; ct < kCt; ++ct) {
+                    floatx4_t x = acc[kt][ct];
+                    x[0] *= dec[kt][0]; x[1] *= dec[kt][1]; x[2] *= dec[kt][2]; x[3] *= dec[kt][3];
+                    acc[kt][ct] = mfma_k16(a_q[kt], b_do[ct], x);
+                }
+        }
+        __syncthreads();
+
+        // ---- dk and the gate cotangent (thread = channel vc, tokens 4vg .. 4vg+3)
+        {
+            float r_own[4];
+#pragma unroll
+            for (int r = 3; r >= 0; --r) {
+                const int i = 4 * vg + r;
+                const float l_i = ls[i * kK + vc];
+                float khat_term = red_s[i * kK + vc] + red_s[kTile * kK + i * kK + vc] + red_s[2 * kTile * kK + i * kK + vc] +
+                                  red_s[3 * kTile * kK + i * kK + vc];
+                khat_term *= __expf(lsum[kTile - 1] - l_i);
+                float intra = 0.f;
+#pragma unroll
+                for (int t = 0; t < kTile; ++t) {
+                    const float wgt = (t >= i) ? __expf(lsum[t] - l_i) : 0.f;
+                    intra = fmaf(dp_s[t * (kTile + 1) + i] * qs[t * kK + vc], wgt, intra);
+                }
+                const float dk_val = khat_term + intra;
+                qa_s[i * (kK + 8) + vc] = (bf16_t)dk_val;                       // staging for the coalesced store (q .* A is no longer needed)
+                r_own[r] = -ks[i * kK + vc] * dk_val;
+            }
+            // q .* dq of this thread's tokens comes through LDS from the row-wise loads
+            // (written below by the loading threads, read after the barrier)
+            __syncthreads();
+            {
+                const int tok = tid >> 4, piece = tid & 15;
+                *reinterpret_cast<floatx4_t *>(&red_s[tok * kK + 4 * piece]) = qdq_r;      // first quarter of red_s reused as [token][channel] q .* dq
+            }
+            __syncthreads();
+            float run = 0.f, sfx[4];
+#pragma unroll
+            for (int r = 3; r >= 0; --r) {
+                run += red_s[(4 * vg + r) * kK + vc] + r_own[r];
+                sfx[r] = run;                               // sum over this thread's tokens >= 4vg + r
+            }
+            tot_s[vg * kK + vc] = run;
+            __syncthreads();
+            float later = 0.f;                              // token groups after this one inside the tile
+#pragma unroll
+            for (int gsel = 3; gsel >= 1; --gsel) later += (gsel > vg) ? tot_s[gsel * kK + vc] : 0.f;
+            const float tile_total = tot_s[vc] + tot_s[kK + vc] + tot_s[2 * kK + vc] + tot_s[3 * kK + vc];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) red_s[kTile * kK + (4 * vg + r) * kK + vc] = carry + later + sfx[r];     // dlog_alpha, [token][channel], second quarter
+            carry += tile_total;
+        }
+        __syncthreads();
+
+        // ---- coalesced stores: dk (bf16), dlog_alpha (fp32), dv (bf16), dbeta (fp32)
+        {
+            const int tok = tid >> 4, piece = tid & 15;
+            if (t0 + tok < T) {
+                const size_t row = (g.tok0 + t0 + tok) * H + g.h;
+                floatx4_t gl = *reinterpret_cast<const floatx4_t *>(&red_s[kTile * kK + tok * kK + 4 * piece]);
+                // a closed gate (log_alpha at or below the clamp) has no cotangent
+                const floatx4_t raw = *reinterpret_cast<const floatx4_t *>(log_alpha + row * kK + 4 * piece);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) gl[e] = raw[e] <= kMinLogAlpha ? 0.f : gl[e];
+                *reinterpret_cast<floatx4_t *>(dla + row * kK + 4 * piece) = gl;
+                if (piece < 8)
+                    *reinterpret_cast<uint4 *>(dk + row * kK + 8 * piece) = *reinterpret_cast<const uint4 *>(&qa_s[tok * (kK + 8) + 8 * piece]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < L::kPerThread; ++u) {
+            const int id = tid + u * kBwdThreads, tok = id / L::kPieces, piece = id % L::kPieces;
+            if (t0 + tok < T) {
+                const size_t off = ((g.tok0 + t0 + tok) * H + g.h) * DV + 8 * piece;
+                const floatx4_t d0 = *reinterpret_cast<const floatx4_t *>(&du_s[tok * kDuRow + 8 * piece]);
+                const floatx4_t d1 = *reinterpret_cast<const floatx4_t *>(&du_s[tok * kDuRow + 8 * piece + 4]);
+                float x[8];
+                unpack8(v_keep[u], x);
+                floatx4_t b0 = {1.f, 1.f, 1.f, 1.f}, b1 = b0;
+                if (has_beta) { b0 = beta_keep[u][0]; b1 = beta_keep[u][1]; }
+                const uint4 wv = {pack_bf16x2(b0[0] * d0[0], b0[1] * d0[1]), pack_bf16x2(b0[2] * d0[2], b0[3] * d0[3]),
+                                  pack_bf16x2(b1[0] * d1[0], b1[1] * d1[1]), pack_bf16x2(b1[2] * d1[2], b1[3] * d1[3])};
+                *reinterpret_cast<uint4 *>(dv + off) = wv;
+                if (dbeta != nullptr) {
+                    *reinterpret_cast<floatx4_t *>(dbeta + off) = floatx4_t{x[0] * d0[0], x[1] * d0[1], x[2] * d0[2], x[3] * d0[3]};
+                    *reinterpret_cast<floatx4_t *>(dbeta + off + 4) = floatx4_t{x[4] * d1[0], x[5] * d1[1], x[6] * d1[2], x[7] * d1[3]};
+                }
+            }
+        }
+    }
+
+    if (dS0 != nullptr) {
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int ct = 0; ct < kCt; ++ct)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    dS0[state_base + (size_t)(16 * kt + 4 * grp + r) * DV + col0 + 16 * ct + n] = acc[kt][ct][r];
+    }
+}
+
+}  // namespace
+
+size_t scan_bwd_workspace_bytes(int B, int T, int H)
+{
+    return ((size_t)B * T * H * kK + (size_t)B * H * kK) * sizeof(float);
+}
+
+bool scan_bwd_supports(int dk, int dv, int io_dtype)
+{
+    return io_dtype == RODIMUS_BF16 && dk == kK && (dv == 128 || dv == 256);
+}
+
+namespace {
+
+template <int DV>
+hipError_t launch_scan_bwd_typed(const ScanBwdArgs &a)
+{
+    const unsigned bh = (unsigned)(a.B * a.H);
+    float *qdq = static_cast<float *>(a.workspace);
+    float *gate_const = qdq + (size_t)a.B * a.T * a.H * kK;
+    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_bwd_dkv_kernel<DV>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, DkvLds<DV>::kBytes);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL(scan_bwd_dq_kernel<DV>, dim3(bh), dim3(kBwdThreads), 0, a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k,
+                       (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0, (const bf16_t *)a.d_o, a.dS_T, (bf16_t *)a.dq, qdq,
+                       gate_const, a.T, a.H);
+    hipLaunchKernelGGL(scan_bwd_dkv_kernel<DV>, dim3(bh), dim3(kBwdThreads), DkvLds<DV>::kBytes, a.stream, (const bf16_t *)a.q,
+                       (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, (const bf16_t *)a.d_o, a.dS_T, qdq,
+                       gate_const, (bf16_t *)a.dk, (bf16_t *)a.dv, a.dlog_alpha, a.dbeta, a.dS0, a.T, a.H);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// T == 0: nothing flows through any token; dS0 = dS_T (or zero) is produced by the reverse kernel all the same.
+hipError_t launch_scan_bwd(const ScanBwdArgs &a)
+{
+    if ((long long)a.B * a.H == 0) return hipSuccess;
+    return a.dv_width == 256 ? launch_scan_bwd_typed<256>(a) : launch_scan_bwd_typed<128>(a);
+}
+
+}  // namespace rodimus

@@ -26,7 +26,8 @@ def test_every_declared_symbol_is_exported(L):
     declared = set(re.findall(r"\b(rodimus_[a-z_]+)\s*\(", header))
     assert {"rodimus_chunk_scan_fwd", "rodimus_decode_step", "rodimus_status_string",
             "rodimus_chunk_scan_workspace_bytes", "rodimus_chunk_scan_path", "rodimus_ddts_gates",
-            "rodimus_chunk_scan_fwd_zbeta", "rodimus_decode_step_zbeta", "rodimus_chunk_scan_varlen_fwd"} <= declared
+            "rodimus_chunk_scan_fwd_zbeta", "rodimus_decode_step_zbeta", "rodimus_chunk_scan_varlen_fwd",
+            "rodimus_chunk_scan_bwd", "rodimus_chunk_scan_bwd_workspace_bytes"} <= declared
     for name in declared:
         assert hasattr(L, name), name
 
@@ -139,6 +140,34 @@ def test_varlen_scan_validation(L):
     assert call(S_T=0x90000) == E_ALIAS
     assert call(N=0, total=0, cu=None, S_T=None) == OK  # empty batch
     assert call(total=0, S_T=None) == OK                # sequences of length zero, no state wanted
+
+
+def test_backward_validation(L):
+    p = ctypes.c_void_p
+    names = ["q", "k", "v", "la", "beta", "S0", "d_o", "dS_T", "dq", "dk_out", "dv_out", "dla", "dbeta", "dS0", "ws"]
+    base = {n: 0x100000 * (i + 1) for i, n in enumerate(names)}
+
+    def call(B=1, T=4, H=1, dk=64, dv=128, io=rodimus.BF16, ws_bytes=None, **over):
+        a = dict(base)
+        a.update(over)
+        f = lambda x: None if x is None else p(x)
+        need = L.rodimus_chunk_scan_bwd_workspace_bytes(B, T, H, dk, dv, io)
+        return L.rodimus_chunk_scan_bwd(*[f(a[n]) for n in names[:14]], B, T, H, dk, dv, io, f(a["ws"]),
+                                        need if ws_bytes is None else ws_bytes, None)
+
+    assert call(io=4) == E_DTYPE
+    for bad in (dict(dk=32), dict(dv=64), dict(dv=384), dict(io=rodimus.F32), dict(B=-1), dict(T=-1)):
+        assert call(**bad) == E_SHAPE, bad
+    for name in ("q", "k", "v", "la", "d_o", "dq", "dk_out", "dv_out", "dla"):
+        assert call(**{name: None}) == E_NULL, name
+    for name in names:
+        assert call(**{name: base[name] + 8}) == E_ALIGN, name
+    assert call(dq=base["q"]) == E_ALIAS and call(dv_out=base["d_o"]) == E_ALIAS and call(dk_out=base["dq"]) == E_ALIAS
+    assert call(ws=base["dla"]) == E_ALIAS
+    assert call(ws_bytes=16) == E_WS and call(ws=None) == E_WS
+    assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 64, 128, rodimus.BF16) == (2 * 100 * 3 * 64 + 2 * 3 * 64) * 4
+    assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 32, 128, rodimus.BF16) == 0
+    assert call(B=0) == OK
 
 
 def test_empty_problems_are_successful_noops(L):
