@@ -202,6 +202,40 @@ def bench_varlen(w, rodimus, wl, dev, steps, warmup, n_seq=64, longest_first=Fal
             "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
 
+def bench_backward(w, rodimus, wl, dev, steps, warmup):
+    """Backward pass of the scan over the layer workload (rodimus_chunk_scan_bwd: dq, dk, dv, dlog_alpha, dbeta, dS0)."""
+    inp = wl.make_scan_inputs(w)
+    g = {k: (None if v is None else v.to(dev)) for k, v in inp.items()}
+    gen = torch.Generator(device="cpu").manual_seed(17)
+    d_o = torch.randn((w.B, w.T, w.H, w.dv), generator=gen).to(torch.bfloat16).to(dev)
+    dS_T = (0.1 * torch.randn((w.B, w.H, w.dk, w.dv), generator=gen)).to(dev)
+    need = rodimus.lib().rodimus_chunk_scan_bwd_workspace_bytes(w.B, w.T, w.H, w.dk, w.dv, rodimus.BF16)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    out = {}
+
+    def step():
+        out.update(rodimus.rodimus_chunk_scan_bwd(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], g["S0"], d_o, dS_T, workspace=ws))
+
+    warm_up(step, min(warmup, 20), min_seconds=0.2)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n = max(5, steps // 10)
+    a.record()
+    for _ in range(n):
+        step()
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / n
+    th = w.token_heads
+    # per token-head: forward sweep reads q,k,log_alpha,v,beta,do and writes dq and q.*dq; reverse sweep reads the six
+    # inputs again plus q.*dq and writes dk, dv, dlog_alpha, dbeta
+    inputs = 2 * w.dk * 2 + 4 * w.dk + 2 * w.dv + 4 * w.dv + 2 * w.dv
+    algo = th * (2 * inputs + 2 * w.dk + 2 * 4 * w.dk + 2 * w.dk + 2 * w.dv + 4 * w.dk + 4 * w.dv)
+    flops = th * 2 * (4 * w.dk * w.dv + 2 * 16 * w.dv + 2 * 16 * w.dk) * 2    # state products + tile-local products, both sweeps
+    return {"entry_point": "rodimus_chunk_scan_bwd", "ms_per_step": ms, "tokens_per_s": w.tokens / (ms * 1e-3),
+            "algorithmic_bytes": algo, "GB_per_s": algo / (ms * 1e-3) / 1e9, "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "tflops": flops / (ms * 1e-3) / 1e12, "finite": bool(torch.isfinite(out["dlog_alpha"]).all().item())}
+
+
 def cpu_baseline(w, inp, o_gpu, S_gpu):
     """fp64 oracle on the scan workload, timed on the host cores; also the parity check of the GPU result."""
     import numpy as np
@@ -299,6 +333,7 @@ def main():
             "entry_point": "rodimus_chunk_scan_fwd_zbeta", "workload": "layer_1p6b, value gate as bf16 pre-activation",
             "tokens_per_s": zb["tokens_per_s"], "ms_per_step": zb["launch_ms"], "algorithmic_bytes": zb["algo_bytes"],
             "GB_per_s": zb["gbs"], "hbm_frac": zb["gbs"] / HBM_PEAK_GBS}
+        out["scan_backward"] = bench_backward(w, rodimus, wl, dev, args.steps, args.warmup)
         out["serving_prefill_varlen"] = bench_varlen(w, rodimus, wl, dev, args.steps, args.warmup)
         lf = bench_varlen(w, rodimus, wl, dev, args.steps, args.warmup, longest_first=True)
         out["serving_prefill_varlen"]["sequences_sorted_longest_first"] = {

@@ -18,8 +18,10 @@
 //       sum of the difference is the gate's cotangent; it is formed from the fp32 values before dq, dk are rounded.
 //
 // log_alpha is clamped at -128 per step (exp(-128) is zero in fp32), which keeps every l finite.
-// The large contractions (over the dv value columns) run on MFMA with bf16 operands and fp32 accumulation; the
-// 16 x 16 x 64 pairwise terms of a tile run on the vector ALUs in fp32.
+// The contractions run on MFMA with bf16 operands and fp32 accumulation.  The tile-local terms use w[t,i] = A_t / A_i
+// (q .* A and k ./ A as operands) when the tile's total decay A_16 is at least 2^-80 in every channel concerned, so
+// that 1 / A_i cannot overflow; otherwise (a hard reset or very strong decay inside the tile) they are evaluated pair
+// by pair on the vector ALUs in fp32 from exp(l_t - l_i) <= 1.  The choice is uniform per tile.
 #include "internal.h"
 
 namespace rodimus {
@@ -30,6 +32,7 @@ constexpr int kK = 64;
 constexpr int kTile = 16;
 constexpr int kBwdThreads = 256;
 constexpr float kMinLogAlpha = -128.f;
+constexpr float kSafeTileLog = -55.f;      // ln(2^-80) = -55.45: above it 1 / A_i stays below 2^80
 
 // Value columns are stored in LDS in a permuted order inside every group of 32: column 32s + 16h + 4g + e sits at
 // position 32s + 8g + 4h + e.  A 16-byte read at position 32s + 8g then delivers exactly the 8 columns that lane
@@ -38,6 +41,14 @@ constexpr float kMinLogAlpha = -128.f;
 __device__ __forceinline__ int col_position(int col)
 {
     return (col & ~31) | (((col >> 2) & 3) << 3) | (((col >> 4) & 1) << 2) | (col & 3);
+}
+
+// x = hi + lo with both parts bf16: products of split operands (hi*hi + hi*lo + lo*hi) are accurate to ~2^-16.  Used for
+// the tile-local terms of dq and dk, whose difference feeds the running sum behind dlog_alpha and must cancel closely.
+__device__ __forceinline__ void split_bf16(float x, float &hi, float &lo)
+{
+    hi = (float)(bf16_t)x;
+    lo = x - hi;
 }
 
 template <int DV> struct BwdLayout {
@@ -233,6 +244,28 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dq_kernel(
             dqt = mfma_k32(a_do[s], __builtin_bit_cast(bf16x8_t, w), dqt);
         }
         // lane (channel c, token group tg) now holds (do_t S^T)[ch] for t = 4tg + r
+        // tile-local term: with a safe total decay, sum_i dP[t,i] k_i exp(l_t - l_i) = A_t .* (dP (k ./ A)) joins the same
+        // accumulator (one MFMA); otherwise it is summed pair by pair below
+        const bool pairwise = __any(lsum[kTile - 1] < kSafeTileLog);
+        if (!pairwise) {
+            float kq_hi[4], kq_lo[4], dp_hi[4], dp_lo[4];
+            const floatx4_t dp4 = *reinterpret_cast<const floatx4_t *>(&dPw[wave][c][4 * tg]);     // dP[t = c][i = 4tg ..]
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float kv = kk[r];
+#pragma unroll
+                for (int gsel = 1; gsel < 4; ++gsel) kv = (tg == gsel) ? kk[4 * gsel + r] : kv;
+                split_bf16(kv * __expf(-lt[r]), kq_hi[r], kq_lo[r]);
+                split_bf16(dp4[r], dp_hi[r], dp_lo[r]);
+            }
+            const uint2 b_hi = {pack_bf16x2(kq_hi[0], kq_hi[1]), pack_bf16x2(kq_hi[2], kq_hi[3])};
+            const uint2 b_lo = {pack_bf16x2(kq_lo[0], kq_lo[1]), pack_bf16x2(kq_lo[2], kq_lo[3])};
+            const uint2 a_hi = {pack_bf16x2(dp_hi[0], dp_hi[1]), pack_bf16x2(dp_hi[2], dp_hi[3])};
+            const uint2 a_lo = {pack_bf16x2(dp_lo[0], dp_lo[1]), pack_bf16x2(dp_lo[2], dp_lo[3])};
+            dqt = mfma_k16(a_lo, b_hi, dqt);
+            dqt = mfma_k16(a_hi, b_lo, dqt);
+            dqt = mfma_k16(a_hi, b_hi, dqt);
+        }
 
         // ---- state update S <- diag(A_16) S + sum_i (k_i .* exp(l_16 - l_i))^T u_i   (uses the state before the update above)
         {
@@ -261,10 +294,12 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dq_kernel(
         for (int r = 0; r < 4; ++r) {
             const int t = 4 * tg + r;
             float intra = 0.f;
+            if (pairwise) {
 #pragma unroll
-            for (int i = 0; i < kTile; ++i) {
-                const float wgt = (i <= t) ? __expf(lt[r] - lsum[i]) : 0.f;
-                intra = fmaf(dPw[wave][t][i] * kk[i], wgt, intra);
+                for (int i = 0; i < kTile; ++i) {
+                    const float wgt = (i <= t) ? __expf(lt[r] - lsum[i]) : 0.f;
+                    intra = fmaf(dPw[wave][t][i] * kk[i], wgt, intra);
+                }
             }
             const float val = fmaf(__expf(lt[r]), dqt[r], intra);
             dq_s[t * kK + ch] = (bf16_t)val;
@@ -320,7 +355,13 @@ template <int DV> struct DkvLds {       // byte offsets of the reverse kernel's 
     static constexpr int kRed = kGt + 4 * kSlabCols * (kK + 8) * 2;
     static constexpr int kDu = kRed + 4 * kTile * kK * 4;
     static constexpr int kTot = kDu + kTile * (DV + 4) * 4;
-    static constexpr int kBytes = kTot + 4 * kK * 4;
+    static constexpr int kKq = kTot + 4 * kK * 4;                      // k ./ A, token-major, padded rows
+    static constexpr int kDpT = kKq + kTile * (kK + 8) * 2;            // dP^T as bf16: [i][t]
+    static constexpr int kIntra = kDpT + kTile * kTile * 2;            // (dP^T (q .* A))[i][channel]
+    static constexpr int kQaLo = kIntra + kTile * kK * 4;              // low part of q .* A (split bf16), token-major, padded rows
+    static constexpr int kDpTLo = kQaLo + kTile * (kK + 8) * 2;        // low part of dP^T
+    static constexpr int kFlag = kDpTLo + kTile * kTile * 2;
+    static constexpr int kBytes = kFlag + 16;
 };
 
 template <int DV>
@@ -348,6 +389,12 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
     float *red_s = reinterpret_cast<float *>(lds_raw + M::kRed);             // [4][16][64] partial u G^T per wavefront
     float *du_s = reinterpret_cast<float *>(lds_raw + M::kDu);
     float *tot_s = reinterpret_cast<float *>(lds_raw + M::kTot);             // [4][64]
+    bf16_t *kq_s = reinterpret_cast<bf16_t *>(lds_raw + M::kKq);
+    bf16_t *dpt_s = reinterpret_cast<bf16_t *>(lds_raw + M::kDpT);
+    float *intra_s = reinterpret_cast<float *>(lds_raw + M::kIntra);
+    bf16_t *qa_lo_s = reinterpret_cast<bf16_t *>(lds_raw + M::kQaLo);
+    bf16_t *dpt_lo_s = reinterpret_cast<bf16_t *>(lds_raw + M::kDpTLo);
+    int *flag_s = reinterpret_cast<int *>(lds_raw + M::kFlag);               // != 0: this tile takes the pairwise route
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, grp = lane >> 4;
@@ -379,6 +426,7 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
         const int t0 = it * kTile;
         __syncthreads();
         tile_stage<DV>(pf, t0, T, tid, has_beta, qs, ks, ls, us, ds);
+        if (tid == 0) *flag_s = 0;
         // this thread's v and beta pieces are needed again at the end of the tile (dv = beta .* du, dbeta = v .* du)
         uint4 v_keep[L::kPerThread];
         floatx4_t beta_keep[L::kPerThread][2];
@@ -409,6 +457,7 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
                 lsum[i] = run;
             }
         }
+        if (lsum[kTile - 1] < kSafeTileLog) *flag_s = 1;
         __syncthreads();                                   // every thread has read the raw log_alpha
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -417,8 +466,12 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
             for (int gsel = 1; gsel < 4; ++gsel) l_own = (vg == gsel) ? lsum[4 * gsel + r] : l_own;
             const int t = 4 * vg + r;
             ls[t * kK + vc] = l_own;                       // from here on ls holds l_t
-            qa_s[t * (kK + 8) + vc] = (bf16_t)(qs[t * kK + vc] * __expf(l_own));
+            float qa_hi, qa_lo;
+            split_bf16(qs[t * kK + vc] * __expf(l_own), qa_hi, qa_lo);
+            qa_s[t * (kK + 8) + vc] = (bf16_t)qa_hi;
+            qa_lo_s[t * (kK + 8) + vc] = (bf16_t)qa_lo;
             kh_s[t * (kK + 8) + vc] = (bf16_t)(ks[t * kK + vc] * __expf(lsum[kTile - 1] - l_own));
+            kq_s[t * (kK + 8) + vc] = (bf16_t)(ks[t * kK + vc] * __expf(-l_own));       // used only by the quotient route
         }
         // this wavefront's G slab, bf16, as [column][channel] for the transposing read of the u G^T product
 #pragma unroll
@@ -431,8 +484,10 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
             }
         __syncthreads();
 
-        // ---- P^T[i][t] and dP[t][i]: thread = (t, i) pair, fp32 on the vector ALUs (P) / MFMA by wavefront 0 (dP)
-        {
+        // ---- P^T[i][t] and dP[t][i].  dP: MFMA by wavefront 0.  P: one MFMA pair by wavefront 1 on the quotient route,
+        // else pair by pair on the vector ALUs (thread = (t, i), fp32)
+        const bool pairwise = *flag_s != 0;
+        if (pairwise) {
             const int t = tid >> 4, i = tid & 15;
             float p = 0.f;
             if (i <= t) {
@@ -442,6 +497,18 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
                 }
             }
             pt_s[i * kTile + t] = (bf16_t)p;
+        } else if (wave == 1) {
+            // D[t][i] = (q .* A)_t . (k ./ A)_i: lane (i = n, group grp) holds t = 4grp + r, i.e. four entries of row i of P^T
+            floatx4_t d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                const bf16x8_t a_qa = *reinterpret_cast<const bf16x8_t *>(&qa_s[n * (kK + 8) + 32 * m + 8 * grp]);
+                const bf16x8_t b_kq = *reinterpret_cast<const bf16x8_t *>(&kq_s[n * (kK + 8) + 32 * m + 8 * grp]);
+                d = mfma_k32(a_qa, b_kq, d);
+            }
+            const uint2 w = {pack_bf16x2(n <= 4 * grp ? d[0] : 0.f, n <= 4 * grp + 1 ? d[1] : 0.f),
+                             pack_bf16x2(n <= 4 * grp + 2 ? d[2] : 0.f, n <= 4 * grp + 3 ? d[3] : 0.f)};
+            *reinterpret_cast<uint2 *>(&pt_s[n * kTile + 4 * grp]) = w;
         }
         if (wave == 0) {
             floatx4_t d = {0.f, 0.f, 0.f, 0.f};
@@ -453,6 +520,12 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
             }
 #pragma unroll
             for (int r = 0; r < 4; ++r) dp_s[(4 * grp + r) * (kTile + 1) + n] = (n <= 4 * grp + r) ? d[r] : 0.f;
+            float hi[4], lo[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) split_bf16(n <= 4 * grp + r ? d[r] : 0.f, hi[r], lo[r]);
+            // dP^T[i = n][t = 4grp ..] as split bf16 for the quotient route
+            *reinterpret_cast<uint2 *>(&dpt_s[n * kTile + 4 * grp]) = uint2{pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3])};
+            *reinterpret_cast<uint2 *>(&dpt_lo_s[n * kTile + 4 * grp]) = uint2{pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3])};
         }
         __syncthreads();
 
@@ -527,6 +600,20 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
 #pragma unroll
                 for (int r = 0; r < 4; ++r) dec[kt][r] = __expf(ls[(kTile - 1) * kK + 16 * kt + 4 * grp + r]);
             }
+            if (!pairwise) {
+                // tile-local part of dk before its 1 / A_i factor: (dP^T (q .* A))[i][channel], channel tile = wavefront
+                const uint2 a_hi = *reinterpret_cast<const uint2 *>(&dpt_s[n * kTile + 4 * grp]);
+                const uint2 a_lo = *reinterpret_cast<const uint2 *>(&dpt_lo_s[n * kTile + 4 * grp]);
+                uint2 b_hi = a_q[0];
+#pragma unroll
+                for (int kt = 1; kt < 4; ++kt) b_hi = (wave == kt) ? a_q[kt] : b_hi;
+                const uint2 b_lo = lds_read_transposed(reinterpret_cast<const unsigned char *>(&qa_lo_s[(4 * grp + j) * (kK + 8) + 16 * wave + 4 * cc]));
+                floatx4_t d = mfma_k16(a_lo, b_hi, floatx4_t{0.f, 0.f, 0.f, 0.f});
+                d = mfma_k16(a_hi, b_lo, d);
+                d = mfma_k16(a_hi, b_hi, d);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) intra_s[(4 * grp + r) * kK + 16 * wave + n] = d[r];
+            }
 #pragma unroll
             for (int ct = 0; ct < kCt; ++ct)
                 b_do[ct] = lds_read_transposed(ds + (4 * grp + j) * L::kRowBytes + col_position(col0 + 16 * ct + 4 * cc) * 2);
@@ -552,10 +639,14 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
                                   red_s[3 * kTile * kK + i * kK + vc];
                 khat_term *= __expf(lsum[kTile - 1] - l_i);
                 float intra = 0.f;
+                if (pairwise) {
 #pragma unroll
-                for (int t = 0; t < kTile; ++t) {
-                    const float wgt = (t >= i) ? __expf(lsum[t] - l_i) : 0.f;
-                    intra = fmaf(dp_s[t * (kTile + 1) + i] * qs[t * kK + vc], wgt, intra);
+                    for (int t = 0; t < kTile; ++t) {
+                        const float wgt = (t >= i) ? __expf(lsum[t] - l_i) : 0.f;
+                        intra = fmaf(dp_s[t * (kTile + 1) + i] * qs[t * kK + vc], wgt, intra);
+                    }
+                } else {
+                    intra = intra_s[i * kK + vc] * __expf(-l_i);
                 }
                 const float dk_val = khat_term + intra;
                 qa_s[i * (kK + 8) + vc] = (bf16_t)dk_val;                       // staging for the coalesced store (q .* A is no longer needed)
