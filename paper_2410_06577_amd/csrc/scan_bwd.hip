@@ -191,9 +191,21 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dq_kernel(
     TileLoads<DV> pf;
     if (ntiles > 0) tile_prefetch<DV>(g, 0, tid, has_beta, pf);
 
+    // coalesced stores of a finished tile's dq (bf16) and q .* dq (fp32) from the staging buffers
+    auto store_tile = [&](int t0) {
+        const int tok = tid >> 4, piece = tid & 15;
+        if (t0 + tok < T) {
+            const size_t row = (g.tok0 + t0 + tok) * H + g.h;
+            *reinterpret_cast<floatx4_t *>(qdq + row * kK + 4 * piece) = *reinterpret_cast<const floatx4_t *>(qdq_s + tok * kK + 4 * piece);
+            if (piece < 8)
+                *reinterpret_cast<uint4 *>(dq + row * kK + 8 * piece) = *reinterpret_cast<const uint4 *>(dq_s + tok * kK + 8 * piece);
+        }
+    };
+
     for (int it = 0; it < ntiles; ++it) {
         const int t0 = it * kTile;
-        __syncthreads();                                   // everyone is done with the previous tile's LDS contents
+        __syncthreads();                                   // the previous tile is computed: its results are staged, its inputs free
+        if (it > 0) store_tile(t0 - kTile);
         tile_stage<DV>(pf, t0, T, tid, has_beta, qs, ks, ls, us, ds);
         tile_prefetch<DV>(g, t0 + kTile, tid, has_beta, pf);        // clamped addresses; masked when staged
         __syncthreads();
@@ -305,18 +317,9 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dq_kernel(
             dq_s[t * kK + ch] = (bf16_t)val;
             qdq_s[t * kK + ch] = qs[t * kK + ch] * val;
         }
-        __syncthreads();
-        // ---- coalesced stores of the tile's dq (bf16) and q .* dq (fp32)
-        {
-            const int tok = tid >> 4, piece = tid & 15;
-            if (t0 + tok < T) {
-                const size_t row = (g.tok0 + t0 + tok) * H + g.h;
-                *reinterpret_cast<floatx4_t *>(qdq + row * kK + 4 * piece) = *reinterpret_cast<const floatx4_t *>(qdq_s + tok * kK + 4 * piece);
-                if (piece < 8)
-                    *reinterpret_cast<uint4 *>(dq + row * kK + 8 * piece) = *reinterpret_cast<const uint4 *>(dq_s + tok * kK + 8 * piece);
-            }
-        }
     }
+    __syncthreads();
+    if (ntiles > 0) store_tile((ntiles - 1) * kTile);
 
     // rowsum(S_T .* dS_T) for this lane's channel: constant term of every gate cotangent of this (batch, head)
     float part = 0.f;
@@ -360,7 +363,9 @@ template <int DV> struct DkvLds {       // byte offsets of the reverse kernel's 
     static constexpr int kIntra = kDpT + kTile * kTile * 2;            // (dP^T (q .* A))[i][channel]
     static constexpr int kQaLo = kIntra + kTile * kK * 4;              // low part of q .* A (split bf16), token-major, padded rows
     static constexpr int kDpTLo = kQaLo + kTile * (kK + 8) * 2;        // low part of dP^T
-    static constexpr int kFlag = kDpTLo + kTile * kTile * 2;
+    static constexpr int kLt = kDpTLo + kTile * kTile * 2;             // running sums l_t, fp32 [16][64]
+    static constexpr int kQdq = kLt + kTile * kK * 4;                  // the tile's q .* dq, fp32 [16][64]
+    static constexpr int kFlag = kQdq + kTile * kK * 4;
     static constexpr int kBytes = kFlag + 16;
 };
 
@@ -379,7 +384,9 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
     using M = DkvLds<DV>;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     float *qs = reinterpret_cast<float *>(lds_raw + M::kQs), *ks = reinterpret_cast<float *>(lds_raw + M::kKs);
-    float *ls = reinterpret_cast<float *>(lds_raw + M::kLs);                 // raw log_alpha, then the running sums l_t
+    float *ls = reinterpret_cast<float *>(lds_raw + M::kLs);                 // log_alpha (clamped)
+    float *lt_s = reinterpret_cast<float *>(lds_raw + M::kLt);
+    float *qdq_s = reinterpret_cast<float *>(lds_raw + M::kQdq);
     unsigned char *us = lds_raw + M::kUs, *ds = lds_raw + M::kDs;
     bf16_t *qa_s = reinterpret_cast<bf16_t *>(lds_raw + M::kQa);             // q .* A, token-major, padded rows; later dk staging
     bf16_t *kh_s = reinterpret_cast<bf16_t *>(lds_raw + M::kKh);             // khat, token-major, padded rows
@@ -390,10 +397,8 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
     float *du_s = reinterpret_cast<float *>(lds_raw + M::kDu);
     float *tot_s = reinterpret_cast<float *>(lds_raw + M::kTot);             // [4][64]
     bf16_t *kq_s = reinterpret_cast<bf16_t *>(lds_raw + M::kKq);
-    bf16_t *dpt_s = reinterpret_cast<bf16_t *>(lds_raw + M::kDpT);
     float *intra_s = reinterpret_cast<float *>(lds_raw + M::kIntra);
     bf16_t *qa_lo_s = reinterpret_cast<bf16_t *>(lds_raw + M::kQaLo);
-    bf16_t *dpt_lo_s = reinterpret_cast<bf16_t *>(lds_raw + M::kDpTLo);
     int *flag_s = reinterpret_cast<int *>(lds_raw + M::kFlag);               // != 0: this tile takes the pairwise route
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -414,18 +419,29 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
             for (int r = 0; r < 4; ++r)
                 acc[kt][ct][r] = dS_T != nullptr ? dS_T[state_base + (size_t)(16 * kt + 4 * grp + r) * DV + col0 + 16 * ct + n] : 0.f;
 
-    // vector-ALU role of the gate phase: channel vc, tokens 4vg .. 4vg+3
+    // vector-ALU role of the gate and dk phases: channel vc, tokens 4vg .. 4vg+3
     const int vc = tid & 63, vg = tid >> 6;
     float carry = gate_const[(size_t)bh * kK + vc];        // sum over later tokens of (q dq - k dk), plus rowsum(S_T .* dS_T)
 
     const int ntiles = (T + kTile - 1) / kTile;
     TileLoads<DV> pf;
-    if (ntiles > 0) tile_prefetch<DV>(g, (ntiles - 1) * kTile, tid, has_beta, pf);
+    floatx4_t qdq_r = {0.f, 0.f, 0.f, 0.f};                // this thread's piece of the tile's q .* dq (fp32, from the forward sweep)
+    auto prefetch = [&](int t0) {
+        tile_prefetch<DV>(g, t0, tid, has_beta, pf);
+        const int tok = tid >> 4, piece = tid & 15;
+        const size_t row = (g.tok0 + min(t0 + tok, T - 1)) * H + g.h;
+        qdq_r = *reinterpret_cast<const floatx4_t *>(qdq + row * kK + 4 * piece);
+    };
+    if (ntiles > 0) prefetch((ntiles - 1) * kTile);
 
     for (int it = ntiles - 1; it >= 0; --it) {
         const int t0 = it * kTile;
-        __syncthreads();
+        __syncthreads();                                   // (1) the previous tile is fully consumed
         tile_stage<DV>(pf, t0, T, tid, has_beta, qs, ks, ls, us, ds);
+        {
+            const int tok = tid >> 4, piece = tid & 15;
+            *reinterpret_cast<floatx4_t *>(&qdq_s[tok * kK + 4 * piece]) = (t0 + tok < T) ? qdq_r : floatx4_t{0.f, 0.f, 0.f, 0.f};
+        }
         if (tid == 0) *flag_s = 0;
         // this thread's v and beta pieces are needed again at the end of the tile (dv = beta .* du, dbeta = v .* du)
         uint4 v_keep[L::kPerThread];
@@ -436,18 +452,10 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
             beta_keep[u][0] = pf.beta[u][0];
             beta_keep[u][1] = pf.beta[u][1];
         }
-        tile_prefetch<DV>(g, max(t0 - kTile, 0), tid, has_beta, pf);
-        // the tile's q .* dq (fp32, written by the forward sweep)
-        floatx4_t qdq_r;
-        {
-            const int tok = tid >> 4, piece = tid & 15;
-            const size_t row = (g.tok0 + min(t0 + tok, T - 1)) * H + g.h;
-            qdq_r = *reinterpret_cast<const floatx4_t *>(qdq + row * kK + 4 * piece);
-            if (t0 + tok >= T) qdq_r = floatx4_t{0.f, 0.f, 0.f, 0.f};
-        }
-        __syncthreads();
+        prefetch(max(t0 - kTile, 0));
+        __syncthreads();                                   // (2)
 
-        // ---- gate phase (thread = channel vc, token group vg): running sums, q .* A, khat
+        // ---- gate phase (thread = channel vc, token group vg): running sums, q .* A, khat, k ./ A
         float lsum[kTile];
         {
             float run = 0.f;
@@ -458,14 +466,13 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
             }
         }
         if (lsum[kTile - 1] < kSafeTileLog) *flag_s = 1;
-        __syncthreads();                                   // every thread has read the raw log_alpha
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             float l_own = lsum[r];
 #pragma unroll
             for (int gsel = 1; gsel < 4; ++gsel) l_own = (vg == gsel) ? lsum[4 * gsel + r] : l_own;
             const int t = 4 * vg + r;
-            ls[t * kK + vc] = l_own;                       // from here on ls holds l_t
+            lt_s[t * kK + vc] = l_own;
             float qa_hi, qa_lo;
             split_bf16(qs[t * kK + vc] * __expf(l_own), qa_hi, qa_lo);
             qa_s[t * (kK + 8) + vc] = (bf16_t)qa_hi;
@@ -482,23 +489,24 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
                 const uint2 w = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3])};
                 *reinterpret_cast<uint2 *>(&gt_s[(16 * ct + n) * (kK + 8) + 16 * kt + 4 * grp]) = w;
             }
-        __syncthreads();
+        __syncthreads();                                   // (3)
 
-        // ---- P^T[i][t] and dP[t][i].  dP: MFMA by wavefront 0.  P: one MFMA pair by wavefront 1 on the quotient route,
-        // else pair by pair on the vector ALUs (thread = (t, i), fp32)
+        // ---- MFMA phase.  dP[t][i] = do_t . u_i (i <= t) by every wavefront for itself: lane (i = n, group grp) holds
+        // t = 4grp + r, which is the operand layout of both later uses.
         const bool pairwise = *flag_s != 0;
-        if (pairwise) {
-            const int t = tid >> 4, i = tid & 15;
-            float p = 0.f;
-            if (i <= t) {
-                for (int cr = 0; cr < kK; ++cr) {
-                    const int c = (cr + i) & (kK - 1);     // rotated per key row: the 16 rows of a wavefront hit 16 different banks
-                    p = fmaf(qs[t * kK + c] * ks[i * kK + c], __expf(ls[t * kK + c] - ls[i * kK + c]), p);
-                }
-            }
-            pt_s[i * kTile + t] = (bf16_t)p;
-        } else if (wave == 1) {
-            // D[t][i] = (q .* A)_t . (k ./ A)_i: lane (i = n, group grp) holds t = 4grp + r, i.e. four entries of row i of P^T
+        const int j = n >> 2, cc = n & 3;                  // transposing reads: this lane addresses row 4grp + j, unit cc
+        floatx4_t dp = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < DV / 32; ++s) {
+            const bf16x8_t a_do = *reinterpret_cast<const bf16x8_t *>(ds + n * L::kRowBytes + (32 * s + 8 * grp) * 2);
+            const bf16x8_t b_u = *reinterpret_cast<const bf16x8_t *>(us + n * L::kRowBytes + (32 * s + 8 * grp) * 2);
+            dp = mfma_k32(a_do, b_u, dp);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) dp[r] = (n <= 4 * grp + r) ? dp[r] : 0.f;
+        // P[t][i] in the same layout (B operand of do^T P)
+        uint2 b_p;
+        if (!pairwise) {
             floatx4_t d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int m = 0; m < 2; ++m) {
@@ -506,33 +514,29 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
                 const bf16x8_t b_kq = *reinterpret_cast<const bf16x8_t *>(&kq_s[n * (kK + 8) + 32 * m + 8 * grp]);
                 d = mfma_k32(a_qa, b_kq, d);
             }
-            const uint2 w = {pack_bf16x2(n <= 4 * grp ? d[0] : 0.f, n <= 4 * grp + 1 ? d[1] : 0.f),
-                             pack_bf16x2(n <= 4 * grp + 2 ? d[2] : 0.f, n <= 4 * grp + 3 ? d[3] : 0.f)};
-            *reinterpret_cast<uint2 *>(&pt_s[n * kTile + 4 * grp]) = w;
-        }
-        if (wave == 0) {
-            floatx4_t d = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < DV / 32; ++s) {
-                const bf16x8_t a_do = *reinterpret_cast<const bf16x8_t *>(ds + n * L::kRowBytes + (32 * s + 8 * grp) * 2);
-                const bf16x8_t b_u = *reinterpret_cast<const bf16x8_t *>(us + n * L::kRowBytes + (32 * s + 8 * grp) * 2);
-                d = mfma_k32(a_do, b_u, d);
+            b_p = uint2{pack_bf16x2(n <= 4 * grp ? d[0] : 0.f, n <= 4 * grp + 1 ? d[1] : 0.f),
+                        pack_bf16x2(n <= 4 * grp + 2 ? d[2] : 0.f, n <= 4 * grp + 3 ? d[3] : 0.f)};
+        } else {
+            // pair by pair on the vector ALUs (thread = (t, i), fp32), through LDS; dP for the dk phase as well
+            const int t = tid >> 4, i = tid & 15;
+            float p = 0.f;
+            if (i <= t) {
+                for (int cr = 0; cr < kK; ++cr) {
+                    const int c = (cr + i) & (kK - 1);     // rotated per key row: the 16 rows of a wavefront hit 16 different banks
+                    p = fmaf(qs[t * kK + c] * ks[i * kK + c], __expf(lt_s[t * kK + c] - lt_s[i * kK + c]), p);
+                }
             }
+            pt_s[i * kTile + t] = (bf16_t)p;
+            if (wave == 0) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) dp_s[(4 * grp + r) * (kTile + 1) + n] = (n <= 4 * grp + r) ? d[r] : 0.f;
-            float hi[4], lo[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) split_bf16(n <= 4 * grp + r ? d[r] : 0.f, hi[r], lo[r]);
-            // dP^T[i = n][t = 4grp ..] as split bf16 for the quotient route
-            *reinterpret_cast<uint2 *>(&dpt_s[n * kTile + 4 * grp]) = uint2{pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3])};
-            *reinterpret_cast<uint2 *>(&dpt_lo_s[n * kTile + 4 * grp]) = uint2{pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3])};
+                for (int r = 0; r < 4; ++r) dp_s[(4 * grp + r) * (kTile + 1) + n] = dp[r];
+            }
+            __syncthreads();                               // uniform: the flag is the same for the whole workgroup
+            b_p = *reinterpret_cast<const uint2 *>(&pt_s[n * kTile + 4 * grp]);
         }
-        __syncthreads();
 
-        // ---- du^T[column][i] = G^T khat^T + do^T P  for this wavefront's columns; result to LDS as du[i][column]
+        // du^T[column][i] = G^T khat^T + do^T P  for this wavefront's columns; result to LDS as du[i][column]
         {
-            const int j = n >> 2, cc = n & 3;
-            // B operands: rows of khat (8 channels per lane and k-step), row of P^T (4 query tokens per lane)
             bf16x8_t b_kh[2];
 #pragma unroll
             for (int m = 0; m < 2; ++m) {
@@ -542,7 +546,6 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
                 const uint4 w = {lo.x, lo.y, hi.x, hi.y};
                 b_kh[m] = __builtin_bit_cast(bf16x8_t, w);
             }
-            const uint2 b_p = *reinterpret_cast<const uint2 *>(&pt_s[n * kTile + 4 * grp]);
 #pragma unroll
             for (int ct = 0; ct < kCt; ++ct) {
                 floatx4_t d = {0.f, 0.f, 0.f, 0.f};
@@ -560,12 +563,11 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
                 *reinterpret_cast<floatx4_t *>(&du_s[n * kDuRow + col0 + 16 * ct + 4 * grp]) = d;
             }
         }
-        // ---- partial (u G^T)[i][channel] over this wavefront's columns
+        // partial (u G^T)[i][channel] over this wavefront's columns
         {
             floatx4_t d[4];
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt) d[kt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-            const int j = n >> 2, cc = n & 3;
 #pragma unroll
             for (int s = 0; s < kSlab / 32; ++s) {
                 // A operand: u rows, columns col0 + 32s + 8grp .. +7 in natural order = two 8-byte units at permuted positions
@@ -589,21 +591,23 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
 #pragma unroll
                 for (int r = 0; r < 4; ++r) red_s[wave * kTile * kK + (4 * grp + r) * kK + 16 * kt + n] = d[kt][r];
         }
-        // ---- G <- diag(A_16) G + (q .* A)^T do
+        // G <- diag(A_16) G + (q .* A)^T do;  on the quotient route also the tile-local part of dk before its 1 / A_i factor
         {
-            const int j = n >> 2, cc = n & 3;
             uint2 a_q[4], b_do[kCt];
             floatx4_t dec[4];
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt) {
                 a_q[kt] = lds_read_transposed(reinterpret_cast<const unsigned char *>(&qa_s[(4 * grp + j) * (kK + 8) + 16 * kt + 4 * cc]));
 #pragma unroll
-                for (int r = 0; r < 4; ++r) dec[kt][r] = __expf(ls[(kTile - 1) * kK + 16 * kt + 4 * grp + r]);
+                for (int r = 0; r < 4; ++r) dec[kt][r] = __expf(lt_s[(kTile - 1) * kK + 16 * kt + 4 * grp + r]);
             }
             if (!pairwise) {
-                // tile-local part of dk before its 1 / A_i factor: (dP^T (q .* A))[i][channel], channel tile = wavefront
-                const uint2 a_hi = *reinterpret_cast<const uint2 *>(&dpt_s[n * kTile + 4 * grp]);
-                const uint2 a_lo = *reinterpret_cast<const uint2 *>(&dpt_lo_s[n * kTile + 4 * grp]);
+                // (dP^T (q .* A))[i][channel], channel tile = wavefront; split-bf16 operands
+                float hi[4], lo[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) split_bf16(dp[r], hi[r], lo[r]);
+                const uint2 a_hi = {pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3])};
+                const uint2 a_lo = {pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3])};
                 uint2 b_hi = a_q[0];
 #pragma unroll
                 for (int kt = 1; kt < 4; ++kt) b_hi = (wave == kt) ? a_q[kt] : b_hi;
@@ -626,15 +630,18 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
                     acc[kt][ct] = mfma_k16(a_q[kt], b_do[ct], x);
                 }
         }
-        __syncthreads();
+        __syncthreads();                                   // (4)
 
-        // ---- dk and the gate cotangent (thread = channel vc, tokens 4vg .. 4vg+3)
+        // ---- dk, and this thread's share of the running sum behind dlog_alpha (thread = channel vc, tokens 4vg .. 4vg+3)
+        float sfx[4];
         {
-            float r_own[4];
+            float run = 0.f;
 #pragma unroll
             for (int r = 3; r >= 0; --r) {
                 const int i = 4 * vg + r;
-                const float l_i = ls[i * kK + vc];
+                float l_i = lsum[r];
+#pragma unroll
+                for (int gsel = 1; gsel < 4; ++gsel) l_i = (vg == gsel) ? lsum[4 * gsel + r] : l_i;
                 float khat_term = red_s[i * kK + vc] + red_s[kTile * kK + i * kK + vc] + red_s[2 * kTile * kK + i * kK + vc] +
                                   red_s[3 * kTile * kK + i * kK + vc];
                 khat_term *= __expf(lsum[kTile - 1] - l_i);
@@ -649,50 +656,13 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
                     intra = intra_s[i * kK + vc] * __expf(-l_i);
                 }
                 const float dk_val = khat_term + intra;
-                qa_s[i * (kK + 8) + vc] = (bf16_t)dk_val;                       // staging for the coalesced store (q .* A is no longer needed)
-                r_own[r] = -ks[i * kK + vc] * dk_val;
-            }
-            // q .* dq of this thread's tokens comes through LDS from the row-wise loads
-            // (written below by the loading threads, read after the barrier)
-            __syncthreads();
-            {
-                const int tok = tid >> 4, piece = tid & 15;
-                *reinterpret_cast<floatx4_t *>(&red_s[tok * kK + 4 * piece]) = qdq_r;      // first quarter of red_s reused as [token][channel] q .* dq
-            }
-            __syncthreads();
-            float run = 0.f, sfx[4];
-#pragma unroll
-            for (int r = 3; r >= 0; --r) {
-                run += red_s[(4 * vg + r) * kK + vc] + r_own[r];
+                if (t0 + i < T) dk[((g.tok0 + t0 + i) * H + g.h) * kK + vc] = (bf16_t)dk_val;      // a wavefront writes whole 128-byte rows
+                run += qdq_s[i * kK + vc] - ks[i * kK + vc] * dk_val;
                 sfx[r] = run;                               // sum over this thread's tokens >= 4vg + r
             }
             tot_s[vg * kK + vc] = run;
-            __syncthreads();
-            float later = 0.f;                              // token groups after this one inside the tile
-#pragma unroll
-            for (int gsel = 3; gsel >= 1; --gsel) later += (gsel > vg) ? tot_s[gsel * kK + vc] : 0.f;
-            const float tile_total = tot_s[vc] + tot_s[kK + vc] + tot_s[2 * kK + vc] + tot_s[3 * kK + vc];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) red_s[kTile * kK + (4 * vg + r) * kK + vc] = carry + later + sfx[r];     // dlog_alpha, [token][channel], second quarter
-            carry += tile_total;
         }
-        __syncthreads();
-
-        // ---- coalesced stores: dk (bf16), dlog_alpha (fp32), dv (bf16), dbeta (fp32)
-        {
-            const int tok = tid >> 4, piece = tid & 15;
-            if (t0 + tok < T) {
-                const size_t row = (g.tok0 + t0 + tok) * H + g.h;
-                floatx4_t gl = *reinterpret_cast<const floatx4_t *>(&red_s[kTile * kK + tok * kK + 4 * piece]);
-                // a closed gate (log_alpha at or below the clamp) has no cotangent
-                const floatx4_t raw = *reinterpret_cast<const floatx4_t *>(log_alpha + row * kK + 4 * piece);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) gl[e] = raw[e] <= kMinLogAlpha ? 0.f : gl[e];
-                *reinterpret_cast<floatx4_t *>(dla + row * kK + 4 * piece) = gl;
-                if (piece < 8)
-                    *reinterpret_cast<uint4 *>(dk + row * kK + 8 * piece) = *reinterpret_cast<const uint4 *>(&qa_s[tok * (kK + 8) + 8 * piece]);
-            }
-        }
+        // dv = beta .* du, dbeta = v .* du: coalesced, by the thread that loaded the same pieces of v and beta
 #pragma unroll
         for (int u = 0; u < L::kPerThread; ++u) {
             const int id = tid + u * kBwdThreads, tok = id / L::kPieces, piece = id % L::kPieces;
@@ -712,6 +682,25 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
                     *reinterpret_cast<floatx4_t *>(dbeta + off + 4) = floatx4_t{x[4] * d1[0], x[5] * d1[1], x[6] * d1[2], x[7] * d1[3]};
                 }
             }
+        }
+        __syncthreads();                                   // (5)
+
+        // ---- dlog_alpha_t = carry + (later token groups of the tile) + (this thread's tokens >= t); a wavefront writes whole rows
+        {
+            float later = 0.f;
+#pragma unroll
+            for (int gsel = 3; gsel >= 1; --gsel) later += (gsel > vg) ? tot_s[gsel * kK + vc] : 0.f;
+            const float tile_total = tot_s[vc] + tot_s[kK + vc] + tot_s[2 * kK + vc] + tot_s[3 * kK + vc];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int i = 4 * vg + r;
+                if (t0 + i < T) {
+                    // a closed gate (log_alpha at or below the clamp) has no cotangent
+                    const float val = ls[i * kK + vc] <= kMinLogAlpha ? 0.f : carry + later + sfx[r];
+                    dla[((g.tok0 + t0 + i) * H + g.h) * kK + vc] = val;
+                }
+            }
+            carry += tile_total;
         }
     }
 
