@@ -365,7 +365,8 @@ template <int DV> struct DkvLds {       // byte offsets of the reverse kernel's 
     static constexpr int kDpTLo = kQaLo + kTile * (kK + 8) * 2;        // low part of dP^T
     static constexpr int kLt = kDpTLo + kTile * kTile * 2;             // running sums l_t, fp32 [16][64]
     static constexpr int kQdq = kLt + kTile * kK * 4;                  // the tile's q .* dq, fp32 [16][64]
-    static constexpr int kFlag = kQdq + kTile * kK * 4;
+    static constexpr int kA16 = kQdq + kTile * kK * 4;                 // A_16 per channel, fp32 [64]
+    static constexpr int kFlag = kA16 + kK * 4;
     static constexpr int kBytes = kFlag + 16;
 };
 
@@ -387,6 +388,7 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
     float *ls = reinterpret_cast<float *>(lds_raw + M::kLs);                 // log_alpha (clamped)
     float *lt_s = reinterpret_cast<float *>(lds_raw + M::kLt);
     float *qdq_s = reinterpret_cast<float *>(lds_raw + M::kQdq);
+    float *a16_s = reinterpret_cast<float *>(lds_raw + M::kA16);
     unsigned char *us = lds_raw + M::kUs, *ds = lds_raw + M::kDs;
     bf16_t *qa_s = reinterpret_cast<bf16_t *>(lds_raw + M::kQa);             // q .* A, token-major, padded rows; later dk staging
     bf16_t *kh_s = reinterpret_cast<bf16_t *>(lds_raw + M::kKh);             // khat, token-major, padded rows
@@ -466,6 +468,7 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
             }
         }
         if (lsum[kTile - 1] < kSafeTileLog) *flag_s = 1;
+        if (vg == 0) a16_s[vc] = __expf(lsum[kTile - 1]);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             float l_own = lsum[r];
@@ -598,8 +601,7 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt) {
                 a_q[kt] = lds_read_transposed(reinterpret_cast<const unsigned char *>(&qa_s[(4 * grp + j) * (kK + 8) + 16 * kt + 4 * cc]));
-#pragma unroll
-                for (int r = 0; r < 4; ++r) dec[kt][r] = __expf(lt_s[(kTile - 1) * kK + 16 * kt + 4 * grp + r]);
+                dec[kt] = *reinterpret_cast<const floatx4_t *>(&a16_s[16 * kt + 4 * grp]);
             }
             if (!pairwise) {
                 // (dP^T (q .* A))[i][channel], channel tile = wavefront; split-bf16 operands
