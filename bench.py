@@ -227,9 +227,9 @@ def bench_backward(w, rodimus, wl, dev, steps, warmup):
     ms = a.elapsed_time(b) / n
     th = w.token_heads
     # per token-head: forward sweep reads q,k,log_alpha,v,beta,do and writes dq and q.*dq; reverse sweep reads the six
-    # inputs again plus q.*dq and writes dk, dv, dlog_alpha, dbeta
+    # inputs again and writes dk, k.*dk, dv, dbeta; the gate kernel reads q.*dq, k.*dk, log_alpha and writes dlog_alpha
     inputs = 2 * w.dk * 2 + 4 * w.dk + 2 * w.dv + 4 * w.dv + 2 * w.dv
-    algo = th * (2 * inputs + 2 * w.dk + 2 * 4 * w.dk + 2 * w.dk + 2 * w.dv + 4 * w.dk + 4 * w.dv)
+    algo = th * (2 * inputs + (2 * w.dk + 4 * w.dk) + (2 * w.dk + 4 * w.dk + 2 * w.dv + 4 * w.dv) + (3 * 4 * w.dk + 4 * w.dk))
     flops = th * 2 * (4 * w.dk * w.dv + 2 * 16 * w.dv + 2 * 16 * w.dk) * 2    # state products + tile-local products, both sweeps
     return {"entry_point": "rodimus_chunk_scan_bwd", "ms_per_step": ms, "tokens_per_s": w.tokens / (ms * 1e-3),
             "algorithmic_bytes": algo, "GB_per_s": algo / (ms * 1e-3) / 1e9, "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,

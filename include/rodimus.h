@@ -222,12 +222,13 @@ int rodimus_chunk_scan_varlen_fwd(const void *q, const void *k, const void *v,
  *   dlog_alpha  [B,T,H,dk] fp32          out   (0 where log_alpha <= -128: such a gate is treated as closed)
  *   dbeta       [B,T,H,dv] fp32          out, or NULL if not wanted (v .* (k G) is written even when beta is NULL)
  *   dS0         [B,H,dk,dv] fp32         out, or NULL if not wanted
- *   workspace   rodimus_chunk_scan_bwd_workspace_bytes(...) bytes of device scratch (q .* dq in fp32), 16-byte aligned
+ *   workspace   rodimus_chunk_scan_bwd_workspace_bytes(...) bytes of device scratch (q .* dq and k .* dk in fp32),
+ *               16-byte aligned
  *
  * No output may overlap an input, another output or the workspace.  Supported: io_dtype = BF16, dk = 64,
  * dv = 128 or 256, any T (a 16-token tile is the internal chunk); other shapes return RODIMUS_ERR_SHAPE.  bf16 MFMA
- * operands, fp32 accumulation and fp32 gate arithmetic; two kernels (a forward sweep for dq, a reverse sweep for the rest),
- * one workgroup per (batch, head).
+ * operands, fp32 accumulation and fp32 gate arithmetic; a forward sweep for dq and a reverse sweep for dk, dv, dbeta, dS0 run
+ * side by side in one launch (one workgroup per (batch, head) each), a second launch forms dlog_alpha.
  */
 int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v,
                            const float *log_alpha, const float *beta, const float *S0,

@@ -15,7 +15,9 @@
 //       dv = beta .* du, dbeta = v .* du, dS0 = G after the first tile
 //   gates: dlog_alpha_t = sum_{s>=t} (q_s .* dq_s - k_s .* dk_s) + rowsum(S_T .* dS_T): every pair (i < t <= s) that the
 //       gate of step t decays appears once in q_s .* dq_s and not in k .* dk of a step >= t, so the reverse running
-//       sum of the difference is the gate's cotangent; it is formed from the fp32 values before dq, dk are rounded.
+//       sum of the difference is the gate's cotangent; it is formed from the fp32 values before dq, dk are rounded
+//       (scan_bwd_gate_kernel, from q .* dq and k .* dk left in the workspace by the two sweeps).
+// The two sweeps do not depend on each other and run concurrently as the two halves of one launch.
 //
 // log_alpha is clamped at -128 per step (exp(-128) is zero in fp32), which keeps every l finite.
 // The contractions run on MFMA with bf16 operands and fp32 accumulation.  The tile-local terms use w[t,i] = A_t / A_i
@@ -159,7 +161,7 @@ __device__ __forceinline__ void tile_stage(const TileLoads<DV> &p, int t0, int T
 // transposed in MFMA accumulators (lane = channel, registers = value columns), so that do_t S^T contracts over the
 // columns without any exchange between wavefronts.
 template <int DV>
-__global__ __launch_bounds__(kBwdThreads) void scan_bwd_dq_kernel(
+__device__ __forceinline__ void sweep_dq(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const float *__restrict__ log_alpha, const float *__restrict__ beta, const float *__restrict__ S0,
     const bf16_t *__restrict__ d_o, const float *__restrict__ dS_T, bf16_t *__restrict__ dq,
@@ -357,26 +359,21 @@ template <int DV> struct DkvLds {       // byte offsets of the reverse kernel's 
     static constexpr int kGt = kDp + ((kTile * (kTile + 1) * 4 + 15) / 16) * 16;
     static constexpr int kRed = kGt + 4 * kSlabCols * (kK + 8) * 2;
     static constexpr int kDu = kRed + 4 * kTile * kK * 4;
-    static constexpr int kTot = kDu + kTile * (DV + 4) * 4;
-    static constexpr int kKq = kTot + 4 * kK * 4;                      // k ./ A, token-major, padded rows
-    static constexpr int kDpT = kKq + kTile * (kK + 8) * 2;            // dP^T as bf16: [i][t]
-    static constexpr int kIntra = kDpT + kTile * kTile * 2;            // (dP^T (q .* A))[i][channel]
+    static constexpr int kKq = kDu + kTile * (DV + 4) * 4;             // k ./ A, token-major, padded rows
+    static constexpr int kIntra = kKq + kTile * (kK + 8) * 2;          // (dP^T (q .* A))[i][channel]
     static constexpr int kQaLo = kIntra + kTile * kK * 4;              // low part of q .* A (split bf16), token-major, padded rows
-    static constexpr int kDpTLo = kQaLo + kTile * (kK + 8) * 2;        // low part of dP^T
-    static constexpr int kLt = kDpTLo + kTile * kTile * 2;             // running sums l_t, fp32 [16][64]
-    static constexpr int kQdq = kLt + kTile * kK * 4;                  // the tile's q .* dq, fp32 [16][64]
-    static constexpr int kA16 = kQdq + kTile * kK * 4;                 // A_16 per channel, fp32 [64]
+    static constexpr int kLt = kQaLo + kTile * (kK + 8) * 2;           // running sums l_t, fp32 [16][64]
+    static constexpr int kA16 = kLt + kTile * kK * 4;                  // A_16 per channel, fp32 [64]
     static constexpr int kFlag = kA16 + kK * 4;
     static constexpr int kBytes = kFlag + 16;
 };
 
 template <int DV>
-__global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
+__device__ __forceinline__ void sweep_dkv(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const float *__restrict__ log_alpha, const float *__restrict__ beta, const bf16_t *__restrict__ d_o,
-    const float *__restrict__ dS_T, const float *__restrict__ qdq, const float *__restrict__ gate_const,
-    bf16_t *__restrict__ dk, bf16_t *__restrict__ dv, float *__restrict__ dla, float *__restrict__ dbeta,
-    float *__restrict__ dS0, int T, int H)
+    const float *__restrict__ dS_T, bf16_t *__restrict__ dk, bf16_t *__restrict__ dv, float *__restrict__ kdk,
+    float *__restrict__ dbeta, float *__restrict__ dS0, int T, int H)
 {
     using L = BwdLayout<DV>;
     constexpr int kSlab = DV / 4;                    // columns per wavefront
@@ -387,7 +384,6 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
     float *qs = reinterpret_cast<float *>(lds_raw + M::kQs), *ks = reinterpret_cast<float *>(lds_raw + M::kKs);
     float *ls = reinterpret_cast<float *>(lds_raw + M::kLs);                 // log_alpha (clamped)
     float *lt_s = reinterpret_cast<float *>(lds_raw + M::kLt);
-    float *qdq_s = reinterpret_cast<float *>(lds_raw + M::kQdq);
     float *a16_s = reinterpret_cast<float *>(lds_raw + M::kA16);
     unsigned char *us = lds_raw + M::kUs, *ds = lds_raw + M::kDs;
     bf16_t *qa_s = reinterpret_cast<bf16_t *>(lds_raw + M::kQa);             // q .* A, token-major, padded rows; later dk staging
@@ -397,7 +393,6 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
     bf16_t *gt_s = reinterpret_cast<bf16_t *>(lds_raw + M::kGt) + (size_t)(threadIdx.x >> 6) * kSlab * (kK + 8);   // this wavefront's G slab as [column][channel]
     float *red_s = reinterpret_cast<float *>(lds_raw + M::kRed);             // [4][16][64] partial u G^T per wavefront
     float *du_s = reinterpret_cast<float *>(lds_raw + M::kDu);
-    float *tot_s = reinterpret_cast<float *>(lds_raw + M::kTot);             // [4][64]
     bf16_t *kq_s = reinterpret_cast<bf16_t *>(lds_raw + M::kKq);
     float *intra_s = reinterpret_cast<float *>(lds_raw + M::kIntra);
     bf16_t *qa_lo_s = reinterpret_cast<bf16_t *>(lds_raw + M::kQaLo);
@@ -423,27 +418,16 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
 
     // vector-ALU role of the gate and dk phases: channel vc, tokens 4vg .. 4vg+3
     const int vc = tid & 63, vg = tid >> 6;
-    float carry = gate_const[(size_t)bh * kK + vc];        // sum over later tokens of (q dq - k dk), plus rowsum(S_T .* dS_T)
 
     const int ntiles = (T + kTile - 1) / kTile;
     TileLoads<DV> pf;
-    floatx4_t qdq_r = {0.f, 0.f, 0.f, 0.f};                // this thread's piece of the tile's q .* dq (fp32, from the forward sweep)
-    auto prefetch = [&](int t0) {
-        tile_prefetch<DV>(g, t0, tid, has_beta, pf);
-        const int tok = tid >> 4, piece = tid & 15;
-        const size_t row = (g.tok0 + min(t0 + tok, T - 1)) * H + g.h;
-        qdq_r = *reinterpret_cast<const floatx4_t *>(qdq + row * kK + 4 * piece);
-    };
+    auto prefetch = [&](int t0) { tile_prefetch<DV>(g, t0, tid, has_beta, pf); };
     if (ntiles > 0) prefetch((ntiles - 1) * kTile);
 
     for (int it = ntiles - 1; it >= 0; --it) {
         const int t0 = it * kTile;
         __syncthreads();                                   // (1) the previous tile is fully consumed
         tile_stage<DV>(pf, t0, T, tid, has_beta, qs, ks, ls, us, ds);
-        {
-            const int tok = tid >> 4, piece = tid & 15;
-            *reinterpret_cast<floatx4_t *>(&qdq_s[tok * kK + 4 * piece]) = (t0 + tok < T) ? qdq_r : floatx4_t{0.f, 0.f, 0.f, 0.f};
-        }
         if (tid == 0) *flag_s = 0;
         // this thread's v and beta pieces are needed again at the end of the tile (dv = beta .* du, dbeta = v .* du)
         uint4 v_keep[L::kPerThread];
@@ -634,10 +618,8 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
         }
         __syncthreads();                                   // (4)
 
-        // ---- dk, and this thread's share of the running sum behind dlog_alpha (thread = channel vc, tokens 4vg .. 4vg+3)
-        float sfx[4];
+        // ---- dk, and k .* dk in fp32 for the gate cotangent (thread = channel vc, tokens 4vg .. 4vg+3)
         {
-            float run = 0.f;
 #pragma unroll
             for (int r = 3; r >= 0; --r) {
                 const int i = 4 * vg + r;
@@ -658,11 +640,12 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
                     intra = intra_s[i * kK + vc] * __expf(-l_i);
                 }
                 const float dk_val = khat_term + intra;
-                if (t0 + i < T) dk[((g.tok0 + t0 + i) * H + g.h) * kK + vc] = (bf16_t)dk_val;      // a wavefront writes whole 128-byte rows
-                run += qdq_s[i * kK + vc] - ks[i * kK + vc] * dk_val;
-                sfx[r] = run;                               // sum over this thread's tokens >= 4vg + r
+                if (t0 + i < T) {                           // a wavefront writes whole rows
+                    const size_t e = ((g.tok0 + t0 + i) * H + g.h) * kK + vc;
+                    dk[e] = (bf16_t)dk_val;
+                    kdk[e] = ks[i * kK + vc] * dk_val;
+                }
             }
-            tot_s[vg * kK + vc] = run;
         }
         // dv = beta .* du, dbeta = v .* du: coalesced, by the thread that loaded the same pieces of v and beta
 #pragma unroll
@@ -685,25 +668,6 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
                 }
             }
         }
-        __syncthreads();                                   // (5)
-
-        // ---- dlog_alpha_t = carry + (later token groups of the tile) + (this thread's tokens >= t); a wavefront writes whole rows
-        {
-            float later = 0.f;
-#pragma unroll
-            for (int gsel = 3; gsel >= 1; --gsel) later += (gsel > vg) ? tot_s[gsel * kK + vc] : 0.f;
-            const float tile_total = tot_s[vc] + tot_s[kK + vc] + tot_s[2 * kK + vc] + tot_s[3 * kK + vc];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int i = 4 * vg + r;
-                if (t0 + i < T) {
-                    // a closed gate (log_alpha at or below the clamp) has no cotangent
-                    const float val = ls[i * kK + vc] <= kMinLogAlpha ? 0.f : carry + later + sfx[r];
-                    dla[((g.tok0 + t0 + i) * H + g.h) * kK + vc] = val;
-                }
-            }
-            carry += tile_total;
-        }
     }
 
     if (dS0 != nullptr) {
@@ -719,9 +683,10 @@ __global__ __launch_bounds__(kBwdThreads) void scan_bwd_dkv_kernel(
 
 }  // namespace
 
+// q .* dq and k .* dk in fp32 for every (token, head, channel), and rowsum(S_T .* dS_T) per (batch, head, channel)
 size_t scan_bwd_workspace_bytes(int B, int T, int H)
 {
-    return ((size_t)B * T * H * kK + (size_t)B * H * kK) * sizeof(float);
+    return (2 * (size_t)B * T * H * kK + (size_t)B * H * kK) * sizeof(float);
 }
 
 bool scan_bwd_supports(int dk, int dv, int io_dtype)
@@ -731,21 +696,74 @@ bool scan_bwd_supports(int dk, int dv, int io_dtype)
 
 namespace {
 
+// Both sweeps in one launch: blockIdx.y = 0 runs the forward sweep of (batch, head) blockIdx.x, blockIdx.y = 1 the
+// reverse sweep.  They share nothing, so with B * H workgroups each they occupy twice as many compute units.
+template <int DV>
+__global__ __launch_bounds__(kBwdThreads) void scan_bwd_sweeps_kernel(
+    const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+    const float *__restrict__ log_alpha, const float *__restrict__ beta, const float *__restrict__ S0,
+    const bf16_t *__restrict__ d_o, const float *__restrict__ dS_T, bf16_t *__restrict__ dq, bf16_t *__restrict__ dk,
+    bf16_t *__restrict__ dv, float *__restrict__ dbeta, float *__restrict__ dS0, float *__restrict__ qdq,
+    float *__restrict__ kdk, float *__restrict__ gate_const, int T, int H)
+{
+    if (blockIdx.y == 0)
+        sweep_dq<DV>(q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, qdq, gate_const, T, H);
+    else
+        sweep_dkv<DV>(q, k, v, log_alpha, beta, d_o, dS_T, dk, dv, kdk, dbeta, dS0, T, H);
+}
+
+// dlog_alpha_t = gate_const + sum_{s >= t} (q_s .* dq_s - k_s .* dk_s), zero for a closed gate.  One workgroup per
+// (batch, head, half of the channels); thread = (channel, one of 32 contiguous parts of the sequence): part totals first,
+// then the running sum inside the part on top of the totals of the later parts.
+constexpr int kGateParts = 32;
+__global__ __launch_bounds__(1024) void scan_bwd_gate_kernel(const float *__restrict__ qdq, const float *__restrict__ kdk,
+                                                             const float *__restrict__ gate_const,
+                                                             const float *__restrict__ log_alpha, float *__restrict__ dla,
+                                                             int T, int H)
+{
+    __shared__ float tot_s[kGateParts][32];
+    const int tid = threadIdx.x, c = tid & 31, part = tid >> 5;
+    const int bh = blockIdx.x, ch = 32 * blockIdx.y + c;
+    const size_t tok0 = (size_t)(bh / H) * T;
+    const int h = bh % H;
+    const int len = (T + kGateParts - 1) / kGateParts;
+    const int t_lo = min(part * len, T), t_hi = min(t_lo + len, T);
+    float total = 0.f;
+#pragma unroll 8
+    for (int t = t_lo; t < t_hi; ++t) {
+        const size_t e = ((tok0 + t) * H + h) * kK + ch;
+        total += qdq[e] - kdk[e];
+    }
+    tot_s[part][c] = total;
+    __syncthreads();
+    float run = gate_const[(size_t)bh * kK + ch];
+    for (int p = kGateParts - 1; p > part; --p) run += tot_s[p][c];
+#pragma unroll 8
+    for (int t = t_hi - 1; t >= t_lo; --t) {
+        const size_t e = ((tok0 + t) * H + h) * kK + ch;
+        run += qdq[e] - kdk[e];
+        dla[e] = log_alpha[e] <= kMinLogAlpha ? 0.f : run;
+    }
+}
+
 template <int DV>
 hipError_t launch_scan_bwd_typed(const ScanBwdArgs &a)
 {
     const unsigned bh = (unsigned)(a.B * a.H);
+    const size_t rows = (size_t)a.B * a.T * a.H * kK;
     float *qdq = static_cast<float *>(a.workspace);
-    float *gate_const = qdq + (size_t)a.B * a.T * a.H * kK;
-    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_bwd_dkv_kernel<DV>),
+    float *kdk = qdq + rows;
+    float *gate_const = kdk + rows;
+    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_bwd_sweeps_kernel<DV>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, DkvLds<DV>::kBytes);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL(scan_bwd_dq_kernel<DV>, dim3(bh), dim3(kBwdThreads), 0, a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k,
-                       (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0, (const bf16_t *)a.d_o, a.dS_T, (bf16_t *)a.dq, qdq,
+    hipLaunchKernelGGL(scan_bwd_sweeps_kernel<DV>, dim3(bh, 2), dim3(kBwdThreads), DkvLds<DV>::kBytes, a.stream,
+                       (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0,
+                       (const bf16_t *)a.d_o, a.dS_T, (bf16_t *)a.dq, (bf16_t *)a.dk, (bf16_t *)a.dv, a.dbeta, a.dS0, qdq, kdk,
                        gate_const, a.T, a.H);
-    hipLaunchKernelGGL(scan_bwd_dkv_kernel<DV>, dim3(bh), dim3(kBwdThreads), DkvLds<DV>::kBytes, a.stream, (const bf16_t *)a.q,
-                       (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, (const bf16_t *)a.d_o, a.dS_T, qdq,
-                       gate_const, (bf16_t *)a.dk, (bf16_t *)a.dv, a.dlog_alpha, a.dbeta, a.dS0, a.T, a.H);
+    if (a.T > 0)
+        hipLaunchKernelGGL(scan_bwd_gate_kernel, dim3(bh, 2), dim3(1024), 0, a.stream, qdq, kdk, gate_const, a.log_alpha,
+                           a.dlog_alpha, a.T, a.H);
     return hipGetLastError();
 }
 

@@ -165,7 +165,7 @@ def test_backward_validation(L):
     assert call(dq=base["q"]) == E_ALIAS and call(dv_out=base["d_o"]) == E_ALIAS and call(dk_out=base["dq"]) == E_ALIAS
     assert call(ws=base["dla"]) == E_ALIAS
     assert call(ws_bytes=16) == E_WS and call(ws=None) == E_WS
-    assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 64, 128, rodimus.BF16) == (2 * 100 * 3 * 64 + 2 * 3 * 64) * 4
+    assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 64, 128, rodimus.BF16) == (2 * 2 * 100 * 3 * 64 + 2 * 3 * 64) * 4
     assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 32, 128, rodimus.BF16) == 0
     assert call(B=0) == OK
 
