@@ -317,3 +317,36 @@ int rodimus_oracle_scan_bwd(const float *q, const float *k, const float *v,
     }
     return failed ? 2 : 0;
 }
+
+/*
+ * Output stage of the block around the recurrence (paper Sec. 3.1.3): the feed-through term of the block's state-space
+ * form, o_t = q_t S_t + d .* x'_t with d a learnable weight per value channel (here one row per head) and x'_t the
+ * short-convolved input, followed by the output gate of the Gated Linear Unit the block is merged into,
+ * y_t = o_t .* act(z_t).  The paper cites the GLU of Dauphin et al. (sigmoid gate) and describes the block as akin to
+ * the Mamba series (SiLU gate) without printing the activation: both are offered (act = 0: sigmoid(z), 1: z * sigmoid(z)).
+ *   o        [rows, H, dv] double (rows = B*T), the recurrence output
+ *   x_prime  [rows, H, dv] float or NULL (no feed-through);  d [H, dv] float (required with x_prime)
+ *   z_gate   [rows, H, dv] float or NULL (no output gate)
+ * Everything in double, element by element.
+ */
+int rodimus_oracle_block_output(const double *o, const float *x_prime, const float *d, const float *z_gate,
+                                double *y, long rows, int H, int dv, int act)
+{
+    if (!o || !y || rows < 0 || H < 0 || dv <= 0) return 1;
+    if (x_prime && !d) return 1;
+    if (act != 0 && act != 1) return 1;
+#pragma omp parallel for schedule(static)
+    for (long r = 0; r < rows; ++r)
+        for (int h = 0; h < H; ++h)
+            for (int j = 0; j < dv; ++j) {
+                const size_t e = ((size_t)r * H + h) * dv + j;
+                double val = o[e];
+                if (x_prime) val += (double)d[(size_t)h * dv + j] * (double)x_prime[e];
+                if (z_gate) {
+                    const double z = (double)z_gate[e];
+                    val *= act == 0 ? sigmoid_d(z) : z * sigmoid_d(z);
+                }
+                y[e] = val;
+            }
+    return 0;
+}

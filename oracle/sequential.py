@@ -32,6 +32,8 @@ def _load():
         lib.rodimus_oracle_threads.restype = ctypes.c_int
         lib.rodimus_oracle_scan_bwd.argtypes = [f32p] * 5 + [f64p] * 9 + [ctypes.c_int] * 5
         lib.rodimus_oracle_scan_bwd.restype = ctypes.c_int
+        lib.rodimus_oracle_block_output.argtypes = [f64p, f32p, f32p, f32p, f64p, ctypes.c_long, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        lib.rodimus_oracle_block_output.restype = ctypes.c_int
         lib.rodimus_oracle_ddts_gates.argtypes = [f32p] * 5 + [f64p] * 4 + [ctypes.c_long, ctypes.c_int, ctypes.c_int]
         lib.rodimus_oracle_ddts_gates.restype = ctypes.c_int
         _lib = lib
@@ -122,6 +124,27 @@ def scan_bwd(q, k, v, log_alpha, beta, S0, d_o, dS_T=None):
     if rc != 0:
         raise RuntimeError(f"rodimus_oracle_scan_bwd failed with code {rc}")
     return out
+
+
+def block_output(o, x_prime=None, d=None, z_gate=None, act="sigmoid"):
+    """Output stage around the recurrence (Sec. 3.1.3): y = (o + d .* x') .* act(z), act in {"sigmoid", "silu"}.
+
+    o [..., H, dv] float64 (a recurrence output); x_prime, z_gate same shape (float32-exact) or None; d [H, dv]."""
+    lib = _load()
+    o = _f64(o)
+    H, dv = o.shape[-2], o.shape[-1]
+    rows = o.size // (H * dv)
+    x_prime, d, z_gate = _f32(x_prime), _f32(d), _f32(z_gate)
+    assert x_prime is None or x_prime.shape == o.shape
+    assert z_gate is None or z_gate.shape == o.shape
+    assert d is None or d.shape == (H, dv)
+    y = np.empty(o.shape, np.float64)
+    rc = lib.rodimus_oracle_block_output(_ptr(o, ctypes.c_double), _ptr(x_prime, ctypes.c_float), _ptr(d, ctypes.c_float),
+                                         _ptr(z_gate, ctypes.c_float), _ptr(y, ctypes.c_double), rows, H, dv,
+                                         {"sigmoid": 0, "silu": 1}[act])
+    if rc != 0:
+        raise RuntimeError(f"rodimus_oracle_block_output failed with code {rc}")
+    return y
 
 
 def step(q, k, v, log_alpha, beta, S, z_beta=None):

@@ -108,3 +108,37 @@ def test_gates_feed_the_recurrence():
     for t in range(T):
         S = a[0, t, 0][:, None] * S + np.outer(kk[0, t, 0], bb[0, t, 0] * v[0, t, 0])
         np.testing.assert_allclose(o[0, t, 0], qq[0, t, 0] @ S, rtol=1e-12, atol=1e-14)
+
+
+def test_block_output_stage_closed_forms(golden_dir):
+    """Feed-through and output gate (Sec. 3.1.3): hand-worked values, the no-op cases, and the two activations' limits."""
+    import os
+    vals = None
+    with open(os.path.join(golden_dir, "block_output_closed_forms.txt")) as fh:
+        for line in fh:
+            if line.startswith("block_output:"):
+                vals = [float(x) for x in line.split(":")[1].split()]
+    o = np.array([[[3.0]]])
+    x = np.array([[[4.0]]], np.float32)
+    d = np.array([[0.5]], np.float32)
+    z0 = np.zeros((1, 1, 1), np.float32)
+    assert oracle.block_output(o, x, d, z0, "sigmoid")[0, 0, 0] == vals[0]
+    assert oracle.block_output(o, x, d, z0, "silu")[0, 0, 0] == vals[1]
+    o2 = np.array([[[-2.0]]])
+    z3 = np.full((1, 1, 1), np.log(3.0), np.float32)
+    z3d = float(z3[0, 0, 0])                                  # the float32 value the oracle sees
+    sg = 1.0 / (1.0 + np.exp(-z3d))
+    np.testing.assert_allclose(oracle.block_output(o2, None, None, z3, "sigmoid")[0, 0, 0], vals[2], rtol=1e-7)
+    np.testing.assert_allclose(oracle.block_output(o2, None, None, z3, "silu")[0, 0, 0], vals[3], rtol=1e-7)
+    np.testing.assert_allclose(oracle.block_output(o2, None, None, z3, "silu")[0, 0, 0], -2.0 * z3d * sg, rtol=1e-15)
+    # nothing given: identity; per-head d broadcasts over rows; saturated gates
+    rng = np.random.default_rng(5)
+    o = rng.standard_normal((7, 3, 4))
+    assert np.array_equal(oracle.block_output(o), o)
+    xp = rng.standard_normal((7, 3, 4)).astype(np.float32)
+    dd = rng.standard_normal((3, 4)).astype(np.float32)
+    np.testing.assert_allclose(oracle.block_output(o, xp, dd), o + dd[None].astype(np.float64) * xp, rtol=1e-15)
+    big = np.full((7, 3, 4), 50.0, np.float32)
+    np.testing.assert_allclose(oracle.block_output(o, None, None, big, "sigmoid"), o, rtol=1e-15)
+    np.testing.assert_allclose(oracle.block_output(o, None, None, big, "silu"), 50.0 * o, rtol=1e-15)
+    assert np.all(oracle.block_output(o, None, None, -big, "sigmoid") == o * (np.exp(-50.0) / (1.0 + np.exp(-50.0))))
