@@ -206,6 +206,42 @@ int rodimus_chunk_scan_varlen_fwd(const void *q, const void *k, const void *v,
                                   const int *cu_seqlens, int N, int total_tokens,
                                   int H, int dk, int dv, int chunk, int io_dtype, void *stream);
 
+/* Activation of the output gate in the *_block calls. */
+typedef enum {
+    RODIMUS_GATE_SIGMOID = 0,         /* act(z) = sigmoid(z): the gated linear unit as cited by the paper   */
+    RODIMUS_GATE_SILU = 1             /* act(z) = z * sigmoid(z): the gate of the Mamba-style blocks        */
+} rodimus_gate_act;
+
+/*
+ * The two recurrence calls with the output stage of the block fused into the store of o (paper Sec. 3.1.3: the block's
+ * state-space form ends with the feed-through o_t = q_t S_t + d .* x'_t, and the block is merged into a gated linear unit
+ * whose output gate multiplies o).  Identical to rodimus_chunk_scan_fwd / rodimus_decode_step except:
+ *
+ *   beta, beta_kind   the value gate as in rodimus_chunk_scan_varlen_fwd (values, pre-activations, or NULL)
+ *   x_prime     [B,T,H,dv] / [N,H,dv] io_dtype   in, or NULL = no feed-through
+ *   d           [H,dv] fp32                      in, required with x_prime
+ *   z_gate      [B,T,H,dv] / [N,H,dv] io_dtype   in, or NULL = no output gate
+ *   gate_act    rodimus_gate_act (the paper does not print the activation; both common readings are offered)
+ *   o           = (q S + d .* x') .* act(z_gate), evaluated in fp32 and rounded once
+ *
+ * The decode kernel and the generic scan kernel apply the stage where they store o (no extra pass over o); the MFMA scan
+ * kernel has no registers left for two more input streams, so on that path the stage is a second, bandwidth-bound kernel
+ * of the same call that rewrites o in place.  S_T / S are unaffected.  An unknown gate_act or beta_kind gives
+ * RODIMUS_ERR_DTYPE; x_prime without d gives RODIMUS_ERR_NULL.
+ */
+int rodimus_chunk_scan_fwd_block(const void *q, const void *k, const void *v,
+                                 const float *log_alpha, const void *beta, int beta_kind, const float *S0,
+                                 const void *x_prime, const float *d, const void *z_gate, int gate_act,
+                                 void *o, float *S_T,
+                                 int B, int T, int H, int dk, int dv, int chunk, int io_dtype,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+int rodimus_decode_step_block(const void *q, const void *k, const void *v,
+                              const float *log_alpha, const void *beta, int beta_kind,
+                              const void *x_prime, const float *d, const void *z_gate, int gate_act,
+                              float *S, void *o,
+                              int N, int H, int dk, int dv, int io_dtype, void *stream);
+
 /*
  * Backward pass of rodimus_chunk_scan_fwd (training; paper Sec. 3.1.3 trains the block through its chunkwise form):
  * reverse-mode differentiation of the recurrence.  Given the cotangents d_o of the outputs and dS_T of the final

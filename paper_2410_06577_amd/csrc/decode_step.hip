@@ -32,7 +32,7 @@ template <typename IO, bool kStream>
 __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(
     const IO *__restrict__ q, const IO *__restrict__ k, const IO *__restrict__ v,
     const float *__restrict__ log_alpha, const void *__restrict__ beta, bool beta_preact,
-    float *__restrict__ S, IO *__restrict__ o, int dk, int dv)
+    float *__restrict__ S, IO *__restrict__ o, int dk, int dv, int H, OutputStage stage)
 {
     constexpr int kRowBatch = kStream ? 4 : 8;      // rows in flight per wavefront
     __shared__ float s_q[kDecodeMaxDk];
@@ -106,6 +106,17 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(
         floatx4_t t = s_red[0][lane];
 #pragma unroll
         for (int w = 1; w < kDecodeWaves; ++w) t += s_red[w][lane];
+        // output stage of the block, if any: y = (o + d .* x') .* act(z)
+        if (stage.x_prime != nullptr) {
+            const floatx4_t x = load4_as_float(static_cast<const IO *>(stage.x_prime) + state * dv + col);
+            const floatx4_t d = *reinterpret_cast<const floatx4_t *>(stage.d + (state % H) * dv + col);
+            t += d * x;
+        }
+        if (stage.z_gate != nullptr) {
+            const floatx4_t z = load4_as_float(static_cast<const IO *>(stage.z_gate) + state * dv + col);
+            t *= floatx4_t{output_gate(z[0], stage.act), output_gate(z[1], stage.act), output_gate(z[2], stage.act),
+                           output_gate(z[3], stage.act)};
+        }
         store4_from_float(o + state * dv + col, t);
     }
 }
@@ -122,7 +133,7 @@ hipError_t launch_decode_step(const DecodeArgs &a)
     const bool stream = (size_t)states * a.dk * a.dv * sizeof(float) > kLastLevelCacheBytes;
 #define RODIMUS_LAUNCH_DECODE(IO, STREAM)                                                                         \
     hipLaunchKernelGGL((decode_step_kernel<IO, STREAM>), grid, block, 0, a.stream, (const IO *)a.q, (const IO *)a.k, \
-                       (const IO *)a.v, a.log_alpha, a.beta, a.beta_preact, a.S, (IO *)a.o, a.dk, a.dv)
+                       (const IO *)a.v, a.log_alpha, a.beta, a.beta_preact, a.S, (IO *)a.o, a.dk, a.dv, a.H, a.stage)
     if (a.io_dtype == RODIMUS_BF16) {
         if (stream) RODIMUS_LAUNCH_DECODE(bf16_t, true); else RODIMUS_LAUNCH_DECODE(bf16_t, false);
     } else {

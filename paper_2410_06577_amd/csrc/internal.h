@@ -98,6 +98,22 @@ __device__ __forceinline__ uint2 lds_read_transposed(const unsigned char *p)
     return __builtin_bit_cast(uint2, r);
 }
 
+// Output stage of the block (paper Sec. 3.1.3): y = (o + d .* x') .* act(z).  x_prime / z_gate have o's shape and dtype, d is
+// fp32 [H, dv]; a NULL x_prime drops the feed-through, a NULL z_gate the output gate.
+struct OutputStage {
+    const void *x_prime;
+    const float *d;
+    const void *z_gate;
+    int act;                         // RODIMUS_GATE_SIGMOID or RODIMUS_GATE_SILU
+    bool any() const { return x_prime != nullptr || z_gate != nullptr; }
+};
+
+__device__ __forceinline__ float output_gate(float z, int act)
+{
+    const float sg = sigmoid_f(z);
+    return act == RODIMUS_GATE_SILU ? z * sg : sg;
+}
+
 // ---- launchers (host).  Arguments are already validated by the C-ABI layer. -------------------------
 // `beta` is the value gate: fp32 values, or (beta_preact) its pre-activation in the I/O dtype, or NULL (all ones).
 struct ScanArgs {
@@ -111,6 +127,7 @@ struct ScanArgs {
     int B, T, H, dk, dv, chunk;      // with cu_seqlens: B sequences, T = total tokens of the packed batch
     int io_dtype;
     const int *cu_seqlens;           // device, B + 1 entries, or NULL for the dense [B, T, H, .] layout
+    OutputStage stage;               // feed-through and output gate applied where o is stored (all NULL: plain o)
     void *workspace;
     size_t workspace_bytes;
     hipStream_t stream;
@@ -121,6 +138,7 @@ struct DecodeArgs {
     const float *log_alpha;
     const void *beta;
     bool beta_preact;
+    OutputStage stage;
     float *S;
     void *o;
     int N, H, dk, dv;

@@ -40,7 +40,8 @@ int scan_shape_status(int B, int T, int H, int dk, int dv, int chunk, int io_dty
 // clamp them to the tensor).
 int scan_entry(const void *q, const void *k, const void *v, const float *log_alpha, const void *beta, bool beta_preact,
                const float *S0, void *o, float *S_T, int B, int T, int H, int dk, int dv, int chunk, int io_dtype,
-               void *workspace, size_t workspace_bytes, void *stream, bool packed = false, const int *cu_seqlens = nullptr)
+               void *workspace, size_t workspace_bytes, void *stream, bool packed = false, const int *cu_seqlens = nullptr,
+               OutputStage stage = OutputStage{nullptr, nullptr, nullptr, 0})
 {
     const int shape = scan_shape_status(B, T, H, dk, dv, chunk, io_dtype);
     if (shape != RODIMUS_OK) return shape;
@@ -66,6 +67,12 @@ int scan_entry(const void *q, const void *k, const void *v, const float *log_alp
         overlaps(S_T, state_bytes, v, v_bytes) || overlaps(S_T, state_bytes, log_alpha, la_bytes) ||
         overlaps(S_T, state_bytes, beta, beta_bytes))
         return RODIMUS_ERR_ALIAS;
+    if (stage.x_prime != nullptr && stage.d == nullptr) return RODIMUS_ERR_NULL;
+    if (misaligned(stage.x_prime) || misaligned(stage.d) || misaligned(stage.z_gate)) return RODIMUS_ERR_ALIGN;
+    if (overlaps(o, v_bytes, stage.x_prime, v_bytes) || overlaps(o, v_bytes, stage.z_gate, v_bytes) ||
+        overlaps(o, v_bytes, stage.d, (size_t)H * dv * 4) || overlaps(S_T, state_bytes, stage.x_prime, v_bytes) ||
+        overlaps(S_T, state_bytes, stage.z_gate, v_bytes) || overlaps(S_T, state_bytes, stage.d, (size_t)H * dv * 4))
+        return RODIMUS_ERR_ALIAS;
     const size_t cu_bytes = packed ? ((size_t)B + 1) * sizeof(int) : 0;
     if (overlaps(o, v_bytes, cu_seqlens, cu_bytes) || overlaps(S_T, state_bytes, cu_seqlens, cu_bytes)) return RODIMUS_ERR_ALIAS;
 
@@ -73,13 +80,14 @@ int scan_entry(const void *q, const void *k, const void *v, const float *log_alp
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return RODIMUS_ERR_WORKSPACE;
 
     ScanArgs a{q, k, v, log_alpha, beta, beta_preact, S0, o, S_T, B, T, H, dk, dv, chunk, io_dtype,
-               packed ? cu_seqlens : nullptr, workspace, workspace_bytes, static_cast<hipStream_t>(stream)};
+               packed ? cu_seqlens : nullptr, stage, workspace, workspace_bytes, static_cast<hipStream_t>(stream)};
     const hipError_t err = scan_mfma_supports(dk, dv, chunk, io_dtype) ? launch_scan_mfma(a) : launch_scan_generic(a);
     return err == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
 }
 
 int decode_entry(const void *q, const void *k, const void *v, const float *log_alpha, const void *beta, bool beta_preact,
-                 float *S, void *o, int N, int H, int dk, int dv, int io_dtype, void *stream)
+                 float *S, void *o, int N, int H, int dk, int dv, int io_dtype, void *stream,
+                 OutputStage stage = OutputStage{nullptr, nullptr, nullptr, 0})
 {
     if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
     if (N < 0 || H < 0 || dk < 1 || dk > kMaxDecodeDk || dv < 4 || (dv & 3) != 0) return RODIMUS_ERR_SHAPE;
@@ -103,7 +111,13 @@ int decode_entry(const void *q, const void *k, const void *v, const float *log_a
         overlaps(S, s_bytes, beta, beta_bytes))
         return RODIMUS_ERR_ALIAS;
 
-    DecodeArgs a{q, k, v, log_alpha, beta, beta_preact, S, o, N, H, dk, dv, io_dtype, static_cast<hipStream_t>(stream)};
+    if (stage.x_prime != nullptr && stage.d == nullptr) return RODIMUS_ERR_NULL;
+    if (misaligned(stage.x_prime) || misaligned(stage.d) || misaligned(stage.z_gate)) return RODIMUS_ERR_ALIGN;
+    if (overlaps(o, o_bytes, stage.x_prime, o_bytes) || overlaps(o, o_bytes, stage.z_gate, o_bytes) ||
+        overlaps(o, o_bytes, stage.d, (size_t)H * dv * 4) || overlaps(S, s_bytes, stage.x_prime, o_bytes) ||
+        overlaps(S, s_bytes, stage.z_gate, o_bytes) || overlaps(S, s_bytes, stage.d, (size_t)H * dv * 4))
+        return RODIMUS_ERR_ALIAS;
+    DecodeArgs a{q, k, v, log_alpha, beta, beta_preact, stage, S, o, N, H, dk, dv, io_dtype, static_cast<hipStream_t>(stream)};
     const hipError_t err = launch_decode_step(a);
     return err == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
 }
@@ -162,6 +176,27 @@ int rodimus_chunk_scan_varlen_fwd(const void *q, const void *k, const void *v, c
     if (beta_kind != RODIMUS_BETA_VALUES && beta_kind != RODIMUS_BETA_PREACTIVATION) return RODIMUS_ERR_DTYPE;
     return scan_entry(q, k, v, log_alpha, beta, beta_kind == RODIMUS_BETA_PREACTIVATION, S0, o, S_T, N, total_tokens, H,
                       dk, dv, chunk, io_dtype, nullptr, 0, stream, true, cu_seqlens);
+}
+
+int rodimus_chunk_scan_fwd_block(const void *q, const void *k, const void *v, const float *log_alpha, const void *beta,
+                                 int beta_kind, const float *S0, const void *x_prime, const float *d, const void *z_gate,
+                                 int gate_act, void *o, float *S_T, int B, int T, int H, int dk, int dv, int chunk,
+                                 int io_dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (beta_kind != RODIMUS_BETA_VALUES && beta_kind != RODIMUS_BETA_PREACTIVATION) return RODIMUS_ERR_DTYPE;
+    if (gate_act != RODIMUS_GATE_SIGMOID && gate_act != RODIMUS_GATE_SILU) return RODIMUS_ERR_DTYPE;
+    return scan_entry(q, k, v, log_alpha, beta, beta_kind == RODIMUS_BETA_PREACTIVATION, S0, o, S_T, B, T, H, dk, dv, chunk,
+                      io_dtype, workspace, workspace_bytes, stream, false, nullptr, OutputStage{x_prime, d, z_gate, gate_act});
+}
+
+int rodimus_decode_step_block(const void *q, const void *k, const void *v, const float *log_alpha, const void *beta,
+                              int beta_kind, const void *x_prime, const float *d, const void *z_gate, int gate_act,
+                              float *S, void *o, int N, int H, int dk, int dv, int io_dtype, void *stream)
+{
+    if (beta_kind != RODIMUS_BETA_VALUES && beta_kind != RODIMUS_BETA_PREACTIVATION) return RODIMUS_ERR_DTYPE;
+    if (gate_act != RODIMUS_GATE_SIGMOID && gate_act != RODIMUS_GATE_SILU) return RODIMUS_ERR_DTYPE;
+    return decode_entry(q, k, v, log_alpha, beta, beta_kind == RODIMUS_BETA_PREACTIVATION, S, o, N, H, dk, dv, io_dtype, stream,
+                        OutputStage{x_prime, d, z_gate, gate_act});
 }
 
 int rodimus_decode_step(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta,

@@ -40,7 +40,8 @@ template <typename IO>
 __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
     const IO *__restrict__ q, const IO *__restrict__ k, const IO *__restrict__ v,
     const float *__restrict__ log_alpha, const void *__restrict__ beta, bool beta_preact, const float *S0,
-    IO *__restrict__ o, float *S_T, int T, int H, int dk, int dv, int C, const int *__restrict__ cu_seqlens)
+    IO *__restrict__ o, float *S_T, int T, int H, int dk, int dv, int C, const int *__restrict__ cu_seqlens,
+    OutputStage stage)
 {
     extern __shared__ float lds[];
     const int dkp = dk + 1;                 // padded row stride against bank conflicts
@@ -151,7 +152,14 @@ __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
             float acc = 0.f;
             for (int r = 0; r < dk; ++r) acc = fmaf(sq[t * dkp + r], S[r * kColTile + c], acc);
             for (int i = 0; i <= t; ++i) acc = fmaf(P[t * Pp + i], gv[i * kColTile + c], acc);
-            if (c < ncol) store_from_float(o + ((tok0 + s + t) * H + h) * dv + j0 + c, acc);
+            if (c < ncol) {
+                const size_t e = ((tok0 + s + t) * H + h) * dv + j0 + c;
+                // output stage of the block, if any: y = (o + d .* x') .* act(z)
+                if (stage.x_prime != nullptr)
+                    acc = fmaf(stage.d[(size_t)h * dv + j0 + c], load_as_float(static_cast<const IO *>(stage.x_prime) + e), acc);
+                if (stage.z_gate != nullptr) acc *= output_gate(load_as_float(static_cast<const IO *>(stage.z_gate) + e), stage.act);
+                store_from_float(o + e, acc);
+            }
         }
         __syncthreads();
 
@@ -190,7 +198,7 @@ static hipError_t launch_typed(const ScanArgs &a)
     if (err != hipSuccess) return err;
     dim3 grid((unsigned)(a.B * a.H), (unsigned)((a.dv + kColTile - 1) / kColTile)), block(kThreads);
     hipLaunchKernelGGL(scan_generic_kernel<IO>, grid, block, lds, a.stream, (const IO *)a.q, (const IO *)a.k,
-                       (const IO *)a.v, a.log_alpha, a.beta, a.beta_preact, a.S0, (IO *)a.o, a.S_T, a.T, a.H, a.dk, a.dv, a.chunk, a.cu_seqlens);
+                       (const IO *)a.v, a.log_alpha, a.beta, a.beta_preact, a.S0, (IO *)a.o, a.S_T, a.T, a.H, a.dk, a.dv, a.chunk, a.cu_seqlens, a.stage);
     return hipGetLastError();
 }
 

@@ -778,6 +778,34 @@ SplitShape choose_split(int B, int T, int H, int dv)
     return sp;
 }
 
+// Output stage of the block applied to the stored outputs, in place: o <- (o + d .* x') .* act(z), 8 columns per thread.
+// The scan kernel itself has no registers left for two more input streams, so on this path the stage is a second,
+// bandwidth-bound kernel of the same call (the generic and the decode kernels apply it where they store o).
+__global__ __launch_bounds__(256) void output_stage_kernel(bf16_t *__restrict__ o, OutputStage stage, size_t pieces, int H, int dv)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= pieces) return;
+    const size_t e = i * 8;
+    const uint4 w = *reinterpret_cast<const uint4 *>(o + e);
+    float y[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y), bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
+    if (stage.x_prime != nullptr) {
+        const uint4 xw = load_streaming(static_cast<const bf16_t *>(stage.x_prime) + e);
+        const float x[8] = {bf16_lo(xw.x), bf16_hi(xw.x), bf16_lo(xw.y), bf16_hi(xw.y), bf16_lo(xw.z), bf16_hi(xw.z), bf16_lo(xw.w), bf16_hi(xw.w)};
+        const float *dp = stage.d + e % ((size_t)H * dv);          // [H, dv] repeats every token
+        const floatx4_t d0 = *reinterpret_cast<const floatx4_t *>(dp), d1 = *reinterpret_cast<const floatx4_t *>(dp + 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { y[j] = fmaf(d0[j], x[j], y[j]); y[4 + j] = fmaf(d1[j], x[4 + j], y[4 + j]); }
+    }
+    if (stage.z_gate != nullptr) {
+        const uint4 zw = load_streaming(static_cast<const bf16_t *>(stage.z_gate) + e);
+        const float z[8] = {bf16_lo(zw.x), bf16_hi(zw.x), bf16_lo(zw.y), bf16_hi(zw.y), bf16_lo(zw.z), bf16_hi(zw.z), bf16_lo(zw.w), bf16_hi(zw.w)};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) y[j] *= output_gate(z[j], stage.act);
+    }
+    const uint4 out = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7])};
+    *reinterpret_cast<uint4 *>(o + e) = out;
+}
+
 }  // namespace
 
 bool scan_mfma_supports(int dk, int dv, int chunk, int io_dtype)
@@ -826,6 +854,13 @@ hipError_t launch_scan_mfma_typed(const ScanArgs &a)
     hipLaunchKernelGGL((scan_mfma_kernel<false, kZBeta>), dim3((unsigned)bh, col_tiles, (unsigned)sp.nseg), block, kLdsBytes,
                        a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0,
                        (bf16_t *)a.o, a.S_T, a.T, a.H, a.dv, plan, a.cu_seqlens, a.T);
+    if (a.stage.any()) {
+        const size_t tokens = a.cu_seqlens != nullptr ? (size_t)a.T : (size_t)a.B * a.T;
+        const size_t pieces = tokens * a.H * a.dv / 8;
+        if (pieces > 0)
+            hipLaunchKernelGGL(output_stage_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, a.stream, (bf16_t *)a.o,
+                               a.stage, pieces, a.H, a.dv);
+    }
     return hipGetLastError();
 }
 

@@ -57,6 +57,10 @@ def lib() -> ctypes.CDLL:
         L.rodimus_chunk_scan_bwd.restype = i
         L.rodimus_chunk_scan_bwd_workspace_bytes.argtypes = [i] * 6
         L.rodimus_chunk_scan_bwd_workspace_bytes.restype = sz
+        L.rodimus_chunk_scan_fwd_block.argtypes = [vp] * 5 + [i] + [vp] * 4 + [i] + [vp] * 2 + [i] * 7 + [vp, sz, vp]
+        L.rodimus_chunk_scan_fwd_block.restype = i
+        L.rodimus_decode_step_block.argtypes = [vp] * 5 + [i] + [vp] * 3 + [i] + [vp] * 2 + [i] * 5 + [vp]
+        L.rodimus_decode_step_block.restype = i
         L.rodimus_ddts_gates.argtypes = [vp] * 9 + [ctypes.c_longlong, i, i, i, vp]
         L.rodimus_ddts_gates.restype = i
         _lib = L
@@ -143,6 +147,82 @@ def rodimus_chunk_scan_fwd(q, k, v, log_alpha, beta=None, S0=None, *, chunk=64, 
 def rodimus_chunk_scan_fwd_zbeta(q, k, v, log_alpha, z_beta, S0=None, **kw):
     """``rodimus_chunk_scan_fwd`` with the value gate given as its pre-activation z_beta [B,T,H,dv] (dtype of v)."""
     return rodimus_chunk_scan_fwd(q, k, v, log_alpha, z_beta, S0, _preact=True, **kw)
+
+
+_GATE_ACTS = {"sigmoid": 0, "silu": 1}
+
+
+def rodimus_chunk_scan_fwd_block(q, k, v, log_alpha, beta=None, S0=None, *, z_beta=None, x_prime=None, d=None, z_gate=None,
+                                 gate_act="sigmoid", chunk=64, o=None, S_T=None, want_state=True, workspace=None):
+    """Chunkwise forward scan with the block's output stage fused: o = (q S + d .* x') .* act(z_gate).
+
+    x_prime, z_gate [B,T,H,dv] (dtype of v) or None; d [H,dv] fp32; the value gate as ``beta`` (fp32) or ``z_beta``."""
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_chunk_scan_fwd_block needs device tensors (no CPU path exists)")
+    if beta is not None and z_beta is not None:
+        raise ValueError("give beta or z_beta, not both")
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    dev, io = q.device, q.dtype
+    _require(k, "k", (B, T, H, dk), io, dev)
+    _require(v, "v", (B, T, H, dv), io, dev)
+    _require(log_alpha, "log_alpha", (B, T, H, dk), torch.float32, dev)
+    _require(beta, "beta", (B, T, H, dv), torch.float32, dev)
+    _require(z_beta, "z_beta", (B, T, H, dv), io, dev)
+    _require(S0, "S0", (B, H, dk, dv), torch.float32, dev)
+    _require(x_prime, "x_prime", (B, T, H, dv), io, dev)
+    _require(d, "d", (H, dv), torch.float32, dev)
+    _require(z_gate, "z_gate", (B, T, H, dv), io, dev)
+    if o is None:
+        o = torch.empty((B, T, H, dv), dtype=io, device=dev)
+    _require(o, "o", (B, T, H, dv), io, dev)
+    if S_T is None and want_state:
+        S_T = torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev)
+    _require(S_T, "S_T", (B, H, dk, dv), torch.float32, dev)
+    need = rodimus_chunk_scan_workspace_bytes(B, T, H, dk, dv, chunk, io)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    gate, kind = (z_beta, 1) if z_beta is not None else (beta, 0)
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_chunk_scan_fwd_block(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(gate), kind, _ptr(S0),
+                                                  _ptr(x_prime), _ptr(d), _ptr(z_gate), _GATE_ACTS[gate_act], _ptr(o), _ptr(S_T),
+                                                  B, T, H, dk, dv, int(chunk), _DTYPES[io], _ptr(workspace), ws_bytes, _stream(dev)))
+    return o, S_T
+
+
+def rodimus_decode_step_block(q, k, v, log_alpha, beta, S, *, z_beta=None, x_prime=None, d=None, z_gate=None,
+                              gate_act="sigmoid", o=None):
+    """One recurrent step with the block's output stage fused (see ``rodimus_chunk_scan_fwd_block``)."""
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_decode_step_block needs device tensors (no CPU path exists)")
+    if beta is not None and z_beta is not None:
+        raise ValueError("give beta or z_beta, not both")
+    N, H, dk = q.shape
+    dv = v.shape[-1]
+    dev, io = q.device, q.dtype
+    _require(k, "k", (N, H, dk), io, dev)
+    _require(v, "v", (N, H, dv), io, dev)
+    _require(log_alpha, "log_alpha", (N, H, dk), torch.float32, dev)
+    _require(beta, "beta", (N, H, dv), torch.float32, dev)
+    _require(z_beta, "z_beta", (N, H, dv), io, dev)
+    _require(S, "S", (N, H, dk, dv), torch.float32, dev)
+    _require(x_prime, "x_prime", (N, H, dv), io, dev)
+    _require(d, "d", (H, dv), torch.float32, dev)
+    _require(z_gate, "z_gate", (N, H, dv), io, dev)
+    if o is None:
+        o = torch.empty((N, H, dv), dtype=io, device=dev)
+    _require(o, "o", (N, H, dv), io, dev)
+    gate, kind = (z_beta, 1) if z_beta is not None else (beta, 0)
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_decode_step_block(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(gate), kind, _ptr(x_prime),
+                                               _ptr(d), _ptr(z_gate), _GATE_ACTS[gate_act], _ptr(S), _ptr(o), N, H, dk, dv,
+                                               _DTYPES[io], _stream(dev)))
+    return o
 
 
 def rodimus_chunk_scan_bwd(q, k, v, log_alpha, beta, S0, d_o, dS_T=None, *, want_dbeta=True, want_dS0=True, workspace=None):

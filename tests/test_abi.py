@@ -27,7 +27,8 @@ def test_every_declared_symbol_is_exported(L):
     assert {"rodimus_chunk_scan_fwd", "rodimus_decode_step", "rodimus_status_string",
             "rodimus_chunk_scan_workspace_bytes", "rodimus_chunk_scan_path", "rodimus_ddts_gates",
             "rodimus_chunk_scan_fwd_zbeta", "rodimus_decode_step_zbeta", "rodimus_chunk_scan_varlen_fwd",
-            "rodimus_chunk_scan_bwd", "rodimus_chunk_scan_bwd_workspace_bytes"} <= declared
+            "rodimus_chunk_scan_bwd", "rodimus_chunk_scan_bwd_workspace_bytes",
+            "rodimus_chunk_scan_fwd_block", "rodimus_decode_step_block"} <= declared
     for name in declared:
         assert hasattr(L, name), name
 
@@ -140,6 +141,25 @@ def test_varlen_scan_validation(L):
     assert call(S_T=0x90000) == E_ALIAS
     assert call(N=0, total=0, cu=None, S_T=None) == OK  # empty batch
     assert call(total=0, S_T=None) == OK                # sequences of length zero, no state wanted
+
+
+def test_block_calls_validation(L):
+    p = ctypes.c_void_p
+    f = lambda x: None if x is None else p(x)
+
+    def scan(beta=0x50000, kind=0, x=0x90000, d=0xA0000, z=0xB0000, act=0, o=0x70000, io=rodimus.F32):
+        return L.rodimus_chunk_scan_fwd_block(p(0x10000), p(0x20000), p(0x30000), p(0x40000), f(beta), kind, p(0x60000), f(x),
+                                              f(d), f(z), act, f(o), p(0x80000), 1, 4, 1, 16, 32, 4, io, None, 0, None)
+
+    def dec(x=0x90000, d=0xA0000, z=0xB0000, act=1, kind=0, S=0x100000):
+        return L.rodimus_decode_step_block(p(0x10000), p(0x20000), p(0x30000), p(0x40000), p(0x50000), kind, f(x), f(d), f(z),
+                                           act, f(S), p(0x70000), 2, 2, 16, 32, rodimus.BF16, None)
+
+    assert scan(act=2) == E_DTYPE and scan(kind=3) == E_DTYPE and dec(act=-1) == E_DTYPE and dec(kind=2) == E_DTYPE
+    assert scan(d=None) == E_NULL and dec(d=None) == E_NULL            # a feed-through needs its weight
+    assert scan(x=0x90008) == E_ALIGN and scan(z=0xB0004) == E_ALIGN and dec(d=0xA0008) == E_ALIGN
+    assert scan(o=0x90000) == E_ALIAS and scan(o=0xB0000) == E_ALIAS   # o over x' / over z
+    assert dec(S=0x90000) == E_ALIAS
 
 
 def test_backward_validation(L):
