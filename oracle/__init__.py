@@ -9,7 +9,8 @@ Contents
 ``rodimus_oracle.c``  the sequential recurrence in plain C, IEEE double
                       (paper Sec. 3.1.3, state recurrence of the Rodimus block).
 ``sequential.py``     ctypes loader for it: ``scan``, ``step``, ``scan_bwd`` (reverse-mode differentiation of the
-                      recurrence, step by step), ``block_output`` (feed-through and output gate of Sec. 3.1.3) and ``ddts_gates`` (the gate front-end of Sec. 3.1.2).
+                      recurrence, step by step), ``block_output`` (feed-through and output gate of Sec. 3.1.3),
+                      ``short_conv`` (the ShortConv of Sec. 3.1.3) and ``ddts_gates`` (the gate front-end of Sec. 3.1.2).
 ``chunkwise.py``      the same result computed by the chunkwise form of the
                       appendix "Chunkwise Parallel Representation of the Rodimus
                       Block", in numpy fp64 -- used to check the chunk algebra
@@ -20,6 +21,8 @@ Pins (tests/test_oracle_pins.py): reduction to plain causal linear attention,
 alpha = 0, the unrolled O(T^2) weighted sum, geometric-series closed form,
 a hand-worked rational example, split-sequence and chunk-size invariance;
 (tests/test_oracle_backward.py): central finite differences of ``scan``, the
-linear-attention closed forms, the T = 1 case by hand, split-sequence chaining.
+linear-attention closed forms, the T = 1 case by hand, split-sequence chaining;
+(tests/test_oracle_short_conv.py): hand-worked values, numpy.convolve, impulse
+response, identity taps, split-sequence chaining through the carried inputs.
 """
-from .sequential import block_output, ddts_gates, scan, scan_bwd, step, threads  # noqa: F401
+from .sequential import block_output, ddts_gates, scan, scan_bwd, short_conv, step, threads  # noqa: F401

@@ -350,3 +350,41 @@ int rodimus_oracle_block_output(const double *o, const float *x_prime, const flo
             }
     return 0;
 }
+
+/*
+ * ShortConv of the block (paper Sec. 3.1.3): the block's input x_t is passed through a short convolution to give x'_t,
+ * which feeds the gates and the feed-through term.  The paper names the operator and points to the recurrent models
+ * that use it without printing it; the reading taken is the one of those models: a causal depthwise convolution over
+ * time of width W (each channel has its own W taps and a bias), optionally followed by SiLU,
+ *     x'_t[c] = act( bias[c] + sum_{j=0..W-1} w[c][j] * x_{t-(W-1)+j}[c] ),
+ * where inputs before the call's first token come from `state_in` (the last W-1 inputs of the previous call, oldest
+ * first) or are zero.  `state_out` receives the last W-1 inputs seen so far (for a decode step: T = 1).
+ *   x          [B, T, C] float           w [C, W] float       bias [C] float or NULL
+ *   state_in   [B, W-1, C] float or NULL  y [B, T, C] double   state_out [B, W-1, C] double or NULL
+ *   act = 0: none, 1: SiLU (z * sigmoid(z)).
+ * Everything in double, tap by tap in the order j = 0..W-1.
+ */
+int rodimus_oracle_short_conv(const float *x, const float *w, const float *bias, const float *state_in,
+                              double *y, double *state_out, int B, int T, int C, int W, int act)
+{
+    if (B < 0 || T < 0 || C < 0 || W < 1) return 1;
+    if (act != 0 && act != 1) return 1;
+    if ((size_t)B * T * C > 0 && (!x || !y)) return 1;
+    if (C > 0 && !w) return 1;
+#pragma omp parallel for schedule(static)
+    for (int b = 0; b < B; ++b)
+        for (int c = 0; c < C; ++c) {
+            /* input at time s of this (b, c): s in [-(W-1), T) */
+#define XIN(s) ((s) >= 0 ? (double)x[((size_t)b * T + (s)) * C + c] \
+                         : (state_in ? (double)state_in[((size_t)b * (W - 1) + (W - 1 + (s))) * C + c] : 0.0))
+            for (int t = 0; t < T; ++t) {
+                double acc = bias ? (double)bias[c] : 0.0;
+                for (int j = 0; j < W; ++j) acc += (double)w[(size_t)c * W + j] * XIN(t - (W - 1) + j);
+                y[((size_t)b * T + t) * C + c] = act == 1 ? acc * sigmoid_d(acc) : acc;
+            }
+            if (state_out)
+                for (int j = 0; j < W - 1; ++j) state_out[((size_t)b * (W - 1) + j) * C + c] = XIN(T - (W - 1) + j);
+#undef XIN
+        }
+    return 0;
+}

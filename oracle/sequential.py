@@ -34,6 +34,8 @@ def _load():
         lib.rodimus_oracle_scan_bwd.restype = ctypes.c_int
         lib.rodimus_oracle_block_output.argtypes = [f64p, f32p, f32p, f32p, f64p, ctypes.c_long, ctypes.c_int, ctypes.c_int, ctypes.c_int]
         lib.rodimus_oracle_block_output.restype = ctypes.c_int
+        lib.rodimus_oracle_short_conv.argtypes = [f32p, f32p, f32p, f32p, f64p, f64p] + [ctypes.c_int] * 5
+        lib.rodimus_oracle_short_conv.restype = ctypes.c_int
         lib.rodimus_oracle_ddts_gates.argtypes = [f32p] * 5 + [f64p] * 4 + [ctypes.c_long, ctypes.c_int, ctypes.c_int]
         lib.rodimus_oracle_ddts_gates.restype = ctypes.c_int
         _lib = lib
@@ -145,6 +147,28 @@ def block_output(o, x_prime=None, d=None, z_gate=None, act="sigmoid"):
     if rc != 0:
         raise RuntimeError(f"rodimus_oracle_block_output failed with code {rc}")
     return y
+
+
+def short_conv(x, w, bias=None, state=None, act="silu"):
+    """ShortConv (Sec. 3.1.3): causal depthwise convolution over time, width W, then act in {"none", "silu"}.
+
+    x [B, T, C]; w [C, W]; bias [C] or None; state [B, W-1, C] (the previous call's last inputs, oldest first) or None.
+    Returns (y [B, T, C], state_out [B, W-1, C]) in float64."""
+    lib = _load()
+    x, w, bias, state = _f32(x), _f32(w), _f32(bias), _f32(state)
+    B, T, C = x.shape
+    W = w.shape[1]
+    assert w.shape == (C, W)
+    assert bias is None or bias.shape == (C,)
+    assert state is None or state.shape == (B, W - 1, C)
+    y = np.empty((B, T, C), np.float64)
+    state_out = np.empty((B, W - 1, C), np.float64)
+    rc = lib.rodimus_oracle_short_conv(_ptr(x, ctypes.c_float), _ptr(w, ctypes.c_float), _ptr(bias, ctypes.c_float),
+                                       _ptr(state, ctypes.c_float), _ptr(y, ctypes.c_double), _ptr(state_out, ctypes.c_double),
+                                       B, T, C, W, {"none": 0, "silu": 1}[act])
+    if rc != 0:
+        raise RuntimeError(f"rodimus_oracle_short_conv failed with code {rc}")
+    return y, state_out
 
 
 def step(q, k, v, log_alpha, beta, S, z_beta=None):
