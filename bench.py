@@ -171,6 +171,31 @@ def bench_gates(w, rodimus, wl, dev, steps=50, warmup=20):
                               "GB_per_s": algo_key / (ms_key * 1e-3) / 1e9}}
 
 
+def bench_short_conv(w, rodimus, wl, dev, steps=50, warmup=20, width=4):
+    """The block's ShortConv over the layer workload's tokens: C = H * dv channels, width 4, SiLU, bf16 I/O."""
+    C = w.H * w.dv
+    d = wl.make_short_conv_inputs(w.B, w.T, C, width, "bf16", seed=15)
+    g = {k: v.to(dev) for k, v in d.items()}
+    y = torch.empty_like(g["x"])
+    st = torch.empty_like(g["state"])
+
+    def step():
+        rodimus.rodimus_short_conv_fwd(g["x"], g["w"], g["bias"], g["state"], y=y, state_out=st)
+
+    warm_up(step, warmup)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(steps):
+        step()
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / steps
+    algo = 2 * 2 * w.B * w.T * C            # x read once, y written once, bf16
+    return {"entry_point": "rodimus_short_conv_fwd", "workload": f"B={w.B} T={w.T} C={C} W={width} SiLU bf16",
+            "ms_per_call": ms, "algorithmic_bytes": algo, "GB_per_s": algo / (ms * 1e-3) / 1e9,
+            "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "tokens_per_s": w.B * w.T / (ms * 1e-3)}
+
+
 def bench_varlen(w, rodimus, wl, dev, steps, warmup, n_seq=64, longest_first=False):
     """Packed variable-length prefill: n_seq sequences with a log-uniform length mix and the token count of the layer
     workload (rodimus_chunk_scan_varlen_fwd, states written to a cache)."""
@@ -327,6 +352,7 @@ def main():
         }
     if not args.skip_other_configs:
         out["ddts_gates"] = bench_gates(w, rodimus, wl, dev)
+        out["short_conv"] = bench_short_conv(w, rodimus, wl, dev)
         del o, S_T
         zb, _, _, _ = bench_scan(w, args.steps, args.warmup, rodimus, wl, dev, zbeta=True)
         out["scan_fused_value_gate"] = {

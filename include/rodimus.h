@@ -276,6 +276,46 @@ int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v,
 /* Scratch bytes the call above needs (0 if the shape is not supported). */
 size_t rodimus_chunk_scan_bwd_workspace_bytes(int B, int T, int H, int dk, int dv, int io_dtype);
 
+/* Activation after the short convolution. */
+typedef enum {
+    RODIMUS_CONV_NONE = 0,            /* the convolution alone                                              */
+    RODIMUS_CONV_SILU = 1             /* z * sigmoid(z), as in the recurrent models the paper points to     */
+} rodimus_conv_act;
+
+/*
+ * ShortConv of the block (paper Sec. 3.1.3: the block's input x_t passes through a short convolution to give x'_t,
+ * which feeds the gates and the feed-through term).  The paper names the operator without printing it; the reading
+ * taken is a causal depthwise convolution over time of width W with a bias, then the activation:
+ *     x'_t[c] = act( bias[c] + sum_{j=0..W-1} w[c][j] * x_{t-(W-1)+j}[c] )
+ * (w[c][W-1] multiplies the current token).  Inputs before the call's first token come from state_in or are zero.
+ *
+ *   x           [B,T,C] io_dtype         in
+ *   w           [C,W] fp32               in
+ *   bias        [C] fp32                 in, or NULL = zero
+ *   state_in    [B,W-1,C] io_dtype       in, or NULL = zero history; the last W-1 inputs of the previous call, oldest first
+ *   y           [B,T,C] io_dtype         out
+ *   state_out   [B,W-1,C] io_dtype       out, or NULL if not wanted: the last W-1 inputs seen so far
+ *   act         rodimus_conv_act
+ *
+ * fp32 arithmetic, one rounding at the store.  Supported: 1 <= W <= 8, C % 8 == 0; B, T or C equal to 0 is a no-op
+ * (T = 0 still copies state_in to state_out).  No output may overlap an input or the other output.  An unknown act
+ * gives RODIMUS_ERR_DTYPE.
+ */
+int rodimus_short_conv_fwd(const void *x, const float *w, const float *bias, const void *state_in,
+                           void *y, void *state_out,
+                           int B, int T, int C, int W, int act, int io_dtype, void *stream);
+
+/*
+ * One decode step of the same operator for N sequences (paper Sec. 3.1.3: at inference only fixed-size state is kept;
+ * for ShortConv that state is the last W-1 inputs):
+ *
+ *   x           [N,C] io_dtype           in
+ *   state       [N,W-1,C] io_dtype       in/out, updated IN PLACE (shifted by one token, x appended); NULL only if W = 1
+ *   y           [N,C] io_dtype           out
+ */
+int rodimus_short_conv_step(const void *x, const float *w, const float *bias, void *state, void *y,
+                            int N, int C, int W, int act, int io_dtype, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -175,6 +175,17 @@ bool scan_bwd_supports(int dk, int dv, int io_dtype);
 size_t scan_bwd_workspace_bytes(int B, int T, int H);
 hipError_t launch_decode_step(const DecodeArgs &a);
 hipError_t launch_ddts_gates(const GateArgs &a);
+
+// Causal depthwise convolution over time (ShortConv).  x, y [B,T,C], state_in/out [B,W-1,C] in the I/O dtype.
+struct ShortConvArgs {
+    const void *x;
+    const float *w, *bias;
+    const void *state_in;
+    void *y, *state_out;
+    int B, T, C, W, act, io_dtype;
+    hipStream_t stream;
+};
+hipError_t launch_short_conv(const ShortConvArgs &a);
 hipError_t launch_scan_generic(const ScanArgs &a);
 size_t scan_generic_lds_bytes(int dk, int chunk);
 hipError_t launch_scan_mfma(const ScanArgs &a);

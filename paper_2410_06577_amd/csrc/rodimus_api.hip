@@ -289,3 +289,51 @@ int rodimus_ddts_gates(const void *z_g, const void *z_tau, const void *z_beta, c
 }
 
 }  // extern "C"
+
+namespace {
+
+int short_conv_entry(const void *x, const float *w, const float *bias, const void *state_in, void *y, void *state_out,
+                     int B, int T, int C, int W, int act, int io_dtype, void *stream, bool in_place_state)
+{
+    if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
+    if (act != RODIMUS_CONV_NONE && act != RODIMUS_CONV_SILU) return RODIMUS_ERR_DTYPE;
+    if (B < 0 || T < 0 || C < 0 || W < 1 || W > 8 || (C & 7) != 0) return RODIMUS_ERR_SHAPE;
+    if (B > 65535 || (T + 31) / 32 > 65535) return RODIMUS_ERR_SHAPE;
+    const size_t eb = elem_bytes(io_dtype);
+    const size_t x_bytes = (size_t)B * T * C * eb, st_bytes = (size_t)B * (W - 1) * C * eb;
+    if (x_bytes > 0 && (!x || !y || !w)) return RODIMUS_ERR_NULL;
+    if (st_bytes > 0 && state_out != nullptr && !w) return RODIMUS_ERR_NULL;
+    if (in_place_state && st_bytes > 0 && state_in == nullptr) return RODIMUS_ERR_NULL;
+    if (misaligned(x) || misaligned(w) || misaligned(bias) || misaligned(state_in) || misaligned(y) || misaligned(state_out))
+        return RODIMUS_ERR_ALIGN;
+    const size_t w_bytes = (size_t)C * W * 4, b_bytes = (size_t)C * 4;
+    if (overlaps(y, x_bytes, x, x_bytes) || overlaps(y, x_bytes, w, w_bytes) || overlaps(y, x_bytes, bias, b_bytes) ||
+        overlaps(y, x_bytes, state_in, st_bytes) || overlaps(y, x_bytes, state_out, st_bytes))
+        return RODIMUS_ERR_ALIAS;
+    if (overlaps(state_out, st_bytes, x, x_bytes) || overlaps(state_out, st_bytes, w, w_bytes) ||
+        overlaps(state_out, st_bytes, bias, b_bytes))
+        return RODIMUS_ERR_ALIAS;
+    if (!in_place_state && overlaps(state_out, st_bytes, state_in, st_bytes)) return RODIMUS_ERR_ALIAS;
+    ShortConvArgs a{x, w, bias, state_in, y, state_out, B, T, C, W, act, io_dtype, static_cast<hipStream_t>(stream)};
+    return launch_short_conv(a) == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rodimus_short_conv_fwd(const void *x, const float *w, const float *bias, const void *state_in, void *y, void *state_out,
+                           int B, int T, int C, int W, int act, int io_dtype, void *stream)
+{
+    return short_conv_entry(x, w, bias, state_in, y, state_out, B, T, C, W, act, io_dtype, stream, false);
+}
+
+// One token per sequence; the kernel's thread reads the W-1 carried rows of its channels before it writes them back
+// shifted, and no other thread touches them, so the state is updated in place.
+int rodimus_short_conv_step(const void *x, const float *w, const float *bias, void *state, void *y, int N, int C, int W,
+                            int act, int io_dtype, void *stream)
+{
+    return short_conv_entry(x, w, bias, state, y, state, N, 1, C, W, act, io_dtype, stream, true);
+}
+
+}  // extern "C"

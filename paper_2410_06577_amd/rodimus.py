@@ -63,6 +63,10 @@ def lib() -> ctypes.CDLL:
         L.rodimus_decode_step_block.restype = i
         L.rodimus_ddts_gates.argtypes = [vp] * 9 + [ctypes.c_longlong, i, i, i, vp]
         L.rodimus_ddts_gates.restype = i
+        L.rodimus_short_conv_fwd.argtypes = [vp] * 6 + [i] * 6 + [vp]
+        L.rodimus_short_conv_fwd.restype = i
+        L.rodimus_short_conv_step.argtypes = [vp] * 5 + [i] * 5 + [vp]
+        L.rodimus_short_conv_step.restype = i
         _lib = L
     return _lib
 
@@ -368,3 +372,56 @@ def rodimus_ddts_gates(z_g, z_tau, z_beta, q, k, *, log_alpha=None, beta=None, q
         _check(lib().rodimus_ddts_gates(_ptr(z_g), _ptr(z_tau), _ptr(z_beta), _ptr(q), _ptr(k), _ptr(log_alpha), _ptr(beta),
                                         _ptr(q_out), _ptr(k_out), rows, dk, dv, _DTYPES[io], _stream(dev)))
     return log_alpha, beta, q_out, k_out
+
+
+CONV_NONE, CONV_SILU = 0, 1
+_CONV_ACTS = {"none": CONV_NONE, "silu": CONV_SILU}
+
+
+def rodimus_short_conv_fwd(x, w, bias=None, state=None, *, act="silu", y=None, state_out=None, want_state=True):
+    """ShortConv over a sequence.  x [B,T,C]; w [C,W] fp32; bias [C] fp32 or None; state [B,W-1,C] (x's dtype) or None.
+
+    Returns (y [B,T,C], state_out [B,W-1,C] or None)."""
+    if x.dtype not in _DTYPES:
+        raise ValueError(f"x: unsupported dtype {x.dtype}")
+    if not x.is_cuda:
+        raise ValueError("rodimus_short_conv_fwd needs device tensors (no CPU path exists)")
+    dev, io = x.device, x.dtype
+    B, T, C = x.shape
+    W = w.shape[-1]
+    _require(x, "x", (B, T, C), io, dev)
+    _require(w, "w", (C, W), torch.float32, dev)
+    _require(bias, "bias", (C,), torch.float32, dev)
+    _require(state, "state", (B, W - 1, C), io, dev)
+    if y is None:
+        y = torch.empty_like(x)
+    if state_out is None and want_state:
+        state_out = torch.empty((B, W - 1, C), dtype=io, device=dev)
+    _require(y, "y", (B, T, C), io, dev)
+    _require(state_out, "state_out", (B, W - 1, C), io, dev)
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_short_conv_fwd(_ptr(x), _ptr(w), _ptr(bias), _ptr(state), _ptr(y), _ptr(state_out),
+                                            B, T, C, W, _CONV_ACTS[act], _DTYPES[io], _stream(dev)))
+    return y, state_out
+
+
+def rodimus_short_conv_step(x, w, bias, state, *, act="silu", y=None):
+    """One decode step of ShortConv.  x [N,C]; state [N,W-1,C] is updated in place.  Returns y [N,C]."""
+    if x.dtype not in _DTYPES:
+        raise ValueError(f"x: unsupported dtype {x.dtype}")
+    if not x.is_cuda:
+        raise ValueError("rodimus_short_conv_step needs device tensors (no CPU path exists)")
+    dev, io = x.device, x.dtype
+    N, C = x.shape
+    W = w.shape[-1]
+    _require(x, "x", (N, C), io, dev)
+    _require(w, "w", (C, W), torch.float32, dev)
+    _require(bias, "bias", (C,), torch.float32, dev)
+    _require(state, "state", (N, W - 1, C), io, dev)
+    if y is None:
+        y = torch.empty_like(x)
+    _require(y, "y", (N, C), io, dev)
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_short_conv_step(_ptr(x), _ptr(w), _ptr(bias), _ptr(state), _ptr(y), N, C, W,
+                                             _CONV_ACTS[act], _DTYPES[io], _stream(dev)))
+    return y

@@ -186,3 +186,17 @@ def make_varlen_inputs(lengths, H: int, dk: int, dv: int, io_dtype: str = "bf16"
     else:
         d["S0"] = None
     return d
+
+
+def make_short_conv_inputs(B: int, T: int, C: int, W: int = 4, io_dtype: str = "bf16", seed: int = 13) -> dict:
+    """Inputs of the block's ShortConv: x [B,T,C] ~ N(0,1) and a carried history state [B,W-1,C] ~ N(0,1) in the I/O
+    dtype; taps w [C,W] and bias [C] in fp32, uniform in +-1/sqrt(W) (the usual initialisation of a depthwise
+    convolution of that width)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    f32 = np.float32
+    x = rng.standard_normal((B, T, C), dtype=f32)
+    state = rng.standard_normal((B, W - 1, C), dtype=f32)
+    bound = 1.0 / np.sqrt(W)
+    w = rng.uniform(-bound, bound, size=(C, W)).astype(f32)
+    bias = rng.uniform(-bound, bound, size=(C,)).astype(f32)
+    return {"x": _io(x, io_dtype), "state": _io(state, io_dtype), "w": torch.from_numpy(w), "bias": torch.from_numpy(bias)}

@@ -28,7 +28,8 @@ def test_every_declared_symbol_is_exported(L):
             "rodimus_chunk_scan_workspace_bytes", "rodimus_chunk_scan_path", "rodimus_ddts_gates",
             "rodimus_chunk_scan_fwd_zbeta", "rodimus_decode_step_zbeta", "rodimus_chunk_scan_varlen_fwd",
             "rodimus_chunk_scan_bwd", "rodimus_chunk_scan_bwd_workspace_bytes",
-            "rodimus_chunk_scan_fwd_block", "rodimus_decode_step_block"} <= declared
+            "rodimus_chunk_scan_fwd_block", "rodimus_decode_step_block",
+            "rodimus_short_conv_fwd", "rodimus_short_conv_step"} <= declared
     for name in declared:
         assert hasattr(L, name), name
 
@@ -188,6 +189,32 @@ def test_backward_validation(L):
     assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 64, 128, rodimus.BF16) == (2 * 2 * 100 * 3 * 64 + 2 * 3 * 64) * 4
     assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 32, 128, rodimus.BF16) == 0
     assert call(B=0) == OK
+
+
+def test_short_conv_validation(L):
+    p = ctypes.c_void_p
+    f = lambda x: None if x is None else p(x)
+
+    def fwd(x=0x100000, w=0x200000, b=0x300000, si=0x400000, y=0x500000, so=0x600000, B=2, T=5, C=16, W=4, act=1,
+            io=rodimus.BF16):
+        return L.rodimus_short_conv_fwd(f(x), f(w), f(b), f(si), f(y), f(so), B, T, C, W, act, io, None)
+
+    def step(x=0x100000, w=0x200000, b=0x300000, st=0x400000, y=0x500000, N=2, C=16, W=4, act=1, io=rodimus.F32):
+        return L.rodimus_short_conv_step(f(x), f(w), f(b), f(st), f(y), N, C, W, act, io, None)
+
+    assert fwd(io=3) == E_DTYPE and fwd(act=2) == E_DTYPE and step(act=-1) == E_DTYPE
+    for bad in (dict(W=0), dict(W=9), dict(C=12), dict(B=-1), dict(T=-1), dict(C=-8)):
+        assert fwd(**bad) == E_SHAPE, bad
+    assert step(W=9) == E_SHAPE and step(C=4) == E_SHAPE and step(N=-1) == E_SHAPE
+    for name in ("x", "w", "y"):
+        assert fwd(**{name: None}) == E_NULL, name
+        assert step(**{name: None}) == E_NULL, name
+    assert step(st=None) == E_NULL and step(st=None, W=1, N=0) == OK
+    for name, val in (("x", 0x100008), ("w", 0x200004), ("b", 0x300008), ("si", 0x400002), ("y", 0x500008), ("so", 0x600008)):
+        assert fwd(**{name: val}) == E_ALIGN, name
+    assert fwd(y=0x100000) == E_ALIAS and fwd(so=0x400000) == E_ALIAS and fwd(so=0x100000) == E_ALIAS
+    assert fwd(y=0x600000) == E_ALIAS and step(y=0x400000) == E_ALIAS
+    assert fwd(B=0) == OK and fwd(C=0) == OK and fwd(T=0, so=None) == OK and step(N=0) == OK
 
 
 def test_empty_problems_are_successful_noops(L):
