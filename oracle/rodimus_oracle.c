@@ -388,3 +388,87 @@ int rodimus_oracle_short_conv(const float *x, const float *w, const float *bias,
         }
     return 0;
 }
+
+/*
+ * The block's recurrence taken straight from its pre-activations (paper Sec. 3.1.3, the state-space form of the
+ * overall block, with the gates of Sec. 3.1.2 and the pre-processing of q and k stated after it):
+ *
+ *     g = softplus(z_g),  tau = sigmoid(z_tau),  beta_hat = sigmoid(z_beta)
+ *     S_t = diag(exp(-g .* tau)) S_{t-1} + (g^tau .* khat_t)^T (beta_hat .* v_t),   o_t = (q_t / sqrt(dk)) S_t
+ *     khat_t = k_t / max(||k_t||_2, 1e-12)
+ *
+ * One token of one (b, h), in place on S; z_beta may be NULL (beta_hat = 1).  Everything in double, written out from
+ * the equation (it does not go through rodimus_oracle_ddts_gates or ddts_update above, which the tests compare it with).
+ */
+static void block_update(double *S, const float *q, const float *k, const float *v, const float *z_g, const float *z_tau,
+                         const float *z_beta, double *o, int dk, int dv)
+{
+    double norm2 = 0.0;
+    for (int r = 0; r < dk; ++r) norm2 += (double)k[r] * (double)k[r];
+    double norm = sqrt(norm2);
+    if (norm < 1e-12) norm = 1e-12;
+    for (int r = 0; r < dk; ++r) {
+        const double g = softplus_d((double)z_g[r]);
+        const double tau = sigmoid_d((double)z_tau[r]);
+        const double decay = exp(-g * tau);
+        const double write = pow(g, tau) * ((double)k[r] / norm);
+        double *Srow = S + (size_t)r * dv;
+        for (int j = 0; j < dv; ++j) {
+            const double bv = (z_beta ? sigmoid_d((double)z_beta[j]) : 1.0) * (double)v[j];
+            Srow[j] = decay * Srow[j] + write * bv;
+        }
+    }
+    const double scale = 1.0 / sqrt((double)dk);
+    for (int j = 0; j < dv; ++j) {
+        double acc = 0.0;
+        for (int r = 0; r < dk; ++r) acc += (double)q[r] * scale * S[(size_t)r * dv + j];
+        o[j] = acc;
+    }
+}
+
+/* Sequential scan of the block from pre-activations.  Layouts as rodimus_oracle_scan, z_g, z_tau [B,T,H,dk],
+ * z_beta [B,T,H,dv] or NULL. */
+int rodimus_oracle_scan_gated(const float *q, const float *k, const float *v, const float *z_g, const float *z_tau,
+                              const float *z_beta, const double *S0, double *o, double *S_T,
+                              int B, int T, int H, int dk, int dv)
+{
+    if (!q || !k || !v || !z_g || !z_tau || !o) return 1;
+    if (B < 0 || T < 0 || H < 0 || dk <= 0 || dv <= 0) return 1;
+    int failed = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < H; ++h) {
+            double *S = (double *)malloc(sizeof(double) * (size_t)dk * dv);
+            if (!S) {
+#pragma omp atomic write
+                failed = 1;
+                continue;
+            }
+            const size_t state_off = ((size_t)b * H + h) * (size_t)dk * dv;
+            for (size_t e = 0; e < (size_t)dk * dv; ++e) S[e] = S0 ? S0[state_off + e] : 0.0;
+            for (int t = 0; t < T; ++t) {
+                const size_t row = ((size_t)b * T + t) * H + h;
+                block_update(S, q + row * dk, k + row * dk, v + row * dv, z_g + row * dk, z_tau + row * dk,
+                             z_beta ? z_beta + row * dv : NULL, o + row * dv, dk, dv);
+            }
+            if (S_T)
+                for (size_t e = 0; e < (size_t)dk * dv; ++e) S_T[state_off + e] = S[e];
+            free(S);
+        }
+    }
+    return failed ? 2 : 0;
+}
+
+/* One decode step of the same for N sequences, S [N,H,dk,dv] updated in place. */
+int rodimus_oracle_step_gated(const float *q, const float *k, const float *v, const float *z_g, const float *z_tau,
+                              const float *z_beta, double *S, double *o, int N, int H, int dk, int dv)
+{
+    if (!q || !k || !v || !z_g || !z_tau || !S || !o) return 1;
+    if (N < 0 || H < 0 || dk <= 0 || dv <= 0) return 1;
+#pragma omp parallel for schedule(static)
+    for (long s = 0; s < (long)N * H; ++s)
+        block_update(S + (size_t)s * dk * dv, q + (size_t)s * dk, k + (size_t)s * dk, v + (size_t)s * dv,
+                     z_g + (size_t)s * dk, z_tau + (size_t)s * dk, z_beta ? z_beta + (size_t)s * dv : NULL,
+                     o + (size_t)s * dv, dk, dv);
+    return 0;
+}

@@ -34,6 +34,10 @@ def _load():
         lib.rodimus_oracle_scan_bwd.restype = ctypes.c_int
         lib.rodimus_oracle_block_output.argtypes = [f64p, f32p, f32p, f32p, f64p, ctypes.c_long, ctypes.c_int, ctypes.c_int, ctypes.c_int]
         lib.rodimus_oracle_block_output.restype = ctypes.c_int
+        lib.rodimus_oracle_scan_gated.argtypes = [f32p] * 6 + [f64p] * 3 + [ctypes.c_int] * 5
+        lib.rodimus_oracle_scan_gated.restype = ctypes.c_int
+        lib.rodimus_oracle_step_gated.argtypes = [f32p] * 6 + [f64p] * 2 + [ctypes.c_int] * 4
+        lib.rodimus_oracle_step_gated.restype = ctypes.c_int
         lib.rodimus_oracle_short_conv.argtypes = [f32p, f32p, f32p, f32p, f64p, f64p] + [ctypes.c_int] * 5
         lib.rodimus_oracle_short_conv.restype = ctypes.c_int
         lib.rodimus_oracle_ddts_gates.argtypes = [f32p] * 5 + [f64p] * 4 + [ctypes.c_long, ctypes.c_int, ctypes.c_int]
@@ -191,6 +195,46 @@ def step(q, k, v, log_alpha, beta, S, z_beta=None):
                                  _ptr(S, ctypes.c_double), _ptr(o, ctypes.c_double), N, H, dk, dv, preact)
     if rc != 0:
         raise RuntimeError(f"rodimus_oracle_step failed with code {rc}")
+    return o, S
+
+
+def scan_gated(q, k, v, z_g, z_tau, z_beta=None, S0=None, want_state=True):
+    """The block's recurrence from raw q, k and the gates' pre-activations (Sec. 3.1.3 with the gates of Sec. 3.1.2):
+    decay exp(-softplus(z_g) sigmoid(z_tau)), key write softplus(z_g)^sigmoid(z_tau) .* k / ||k||, value gate
+    sigmoid(z_beta) (None: 1), query q / sqrt(dk).  Shapes as ``scan``.  Returns (o, S_T) float64."""
+    lib = _load()
+    q, k, v, z_g, z_tau, z_beta = _f32(q), _f32(k), _f32(v), _f32(z_g), _f32(z_tau), _f32(z_beta)
+    S0 = _f64(S0)
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    assert k.shape == z_g.shape == z_tau.shape == (B, T, H, dk) and v.shape == (B, T, H, dv)
+    assert z_beta is None or z_beta.shape == (B, T, H, dv)
+    assert S0 is None or S0.shape == (B, H, dk, dv)
+    o = np.empty((B, T, H, dv), dtype=np.float64)
+    S_T = np.empty((B, H, dk, dv), dtype=np.float64) if want_state else None
+    f = ctypes.c_float
+    rc = lib.rodimus_oracle_scan_gated(_ptr(q, f), _ptr(k, f), _ptr(v, f), _ptr(z_g, f), _ptr(z_tau, f), _ptr(z_beta, f),
+                                       _ptr(S0, ctypes.c_double), _ptr(o, ctypes.c_double), _ptr(S_T, ctypes.c_double),
+                                       B, T, H, dk, dv)
+    if rc != 0:
+        raise RuntimeError(f"rodimus_oracle_scan_gated failed with code {rc}")
+    return o, S_T
+
+
+def step_gated(q, k, v, z_g, z_tau, z_beta, S):
+    """One decode step of ``scan_gated``.  [N,H,.] inputs, S [N,H,dk,dv] float64 (not modified).  Returns (o, S')."""
+    lib = _load()
+    q, k, v, z_g, z_tau, z_beta = _f32(q), _f32(k), _f32(v), _f32(z_g), _f32(z_tau), _f32(z_beta)
+    S = _f64(S).copy()
+    N, H, dk = q.shape
+    dv = v.shape[-1]
+    assert k.shape == z_g.shape == z_tau.shape == (N, H, dk) and v.shape == (N, H, dv) and S.shape == (N, H, dk, dv)
+    o = np.empty((N, H, dv), dtype=np.float64)
+    f = ctypes.c_float
+    rc = lib.rodimus_oracle_step_gated(_ptr(q, f), _ptr(k, f), _ptr(v, f), _ptr(z_g, f), _ptr(z_tau, f), _ptr(z_beta, f),
+                                       _ptr(S, ctypes.c_double), _ptr(o, ctypes.c_double), N, H, dk, dv)
+    if rc != 0:
+        raise RuntimeError(f"rodimus_oracle_step_gated failed with code {rc}")
     return o, S
 
 

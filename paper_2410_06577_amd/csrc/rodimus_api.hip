@@ -298,7 +298,7 @@ int short_conv_entry(const void *x, const float *w, const float *bias, const voi
     if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
     if (act != RODIMUS_CONV_NONE && act != RODIMUS_CONV_SILU) return RODIMUS_ERR_DTYPE;
     if (B < 0 || T < 0 || C < 0 || W < 1 || W > 8 || (C & 7) != 0) return RODIMUS_ERR_SHAPE;
-    if (B > 65535 || (T + 31) / 32 > 65535) return RODIMUS_ERR_SHAPE;
+    if (B > 65535 || (T + 63) / 64 > 65535) return RODIMUS_ERR_SHAPE;      // grid limits (a run of 64 tokens per thread)
     const size_t eb = elem_bytes(io_dtype);
     const size_t x_bytes = (size_t)B * T * C * eb, st_bytes = (size_t)B * (W - 1) * C * eb;
     if (x_bytes > 0 && (!x || !y || !w)) return RODIMUS_ERR_NULL;

@@ -14,13 +14,14 @@ namespace rodimus {
 namespace {
 
 constexpr int kConvThreads = 256;
-constexpr int kConvRun = 32;          // tokens per thread
+constexpr int kConvRun = 64;           // tokens per thread (32: 8 % slower, 96: 25 % slower on the layer shape)
 
 template <typename IO> struct Row8;
 template <> struct Row8<float> {
     static __device__ __forceinline__ void load(const float *p, float (&x)[8])
     {
-        const floatx4_t a = *reinterpret_cast<const floatx4_t *>(p), b = *reinterpret_cast<const floatx4_t *>(p + 4);
+        const floatx4_t a = __builtin_nontemporal_load(reinterpret_cast<const floatx4_t *>(p));
+        const floatx4_t b = __builtin_nontemporal_load(reinterpret_cast<const floatx4_t *>(p + 4));
 #pragma unroll
         for (int i = 0; i < 4; ++i) { x[i] = a[i]; x[4 + i] = b[i]; }
     }
@@ -33,7 +34,8 @@ template <> struct Row8<float> {
 template <> struct Row8<bf16_t> {
     static __device__ __forceinline__ void load(const bf16_t *p, float (&x)[8])
     {
-        const uint4 w = *reinterpret_cast<const uint4 *>(p);
+        // every row is read once (plus W-1 rows per run): non-temporal loads are 12 % faster, non-temporal stores are not
+        const uint4 w = __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const floatx4_t *>(p)));
         x[0] = bf16_lo(w.x); x[1] = bf16_hi(w.x); x[2] = bf16_lo(w.y); x[3] = bf16_hi(w.y);
         x[4] = bf16_lo(w.z); x[5] = bf16_hi(w.z); x[6] = bf16_lo(w.w); x[7] = bf16_hi(w.w);
     }
@@ -86,7 +88,7 @@ __global__ __launch_bounds__(kConvThreads) void short_conv_kernel(const IO *__re
             Row8<IO>::load(state_in + ((size_t)b * (W - 1) + (W - 1 + s)) * C + c0, win[j]);
     }
 
-#pragma unroll 4
+#pragma unroll 8
     for (int t = t0; t < t1; ++t) {
         float cur[8], acc[8];
         Row8<IO>::load(x + ((size_t)b * T + t) * C + c0, cur);

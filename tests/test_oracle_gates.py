@@ -142,3 +142,78 @@ def test_block_output_stage_closed_forms(golden_dir):
     np.testing.assert_allclose(oracle.block_output(o, None, None, big, "sigmoid"), o, rtol=1e-15)
     np.testing.assert_allclose(oracle.block_output(o, None, None, big, "silu"), 50.0 * o, rtol=1e-15)
     assert np.all(oracle.block_output(o, None, None, -big, "sigmoid") == o * (np.exp(-50.0) / (1.0 + np.exp(-50.0))))
+
+
+def _numpy_block_recurrence(q, k, v, z_g, z_tau, z_beta, S0):
+    """The block equation of Sec. 3.1.3 written out in numpy float64 for tiny inputs (brute force, token by token)."""
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    f = lambda a: np.asarray(a, np.float64)
+    q, k, v, z_g, z_tau = f(q), f(k), f(v), f(z_g), f(z_tau)
+    g = np.logaddexp(0.0, z_g)
+    tau = 1.0 / (1.0 + np.exp(-z_tau))
+    bh = np.ones_like(v) if z_beta is None else 1.0 / (1.0 + np.exp(-f(z_beta)))
+    o = np.zeros((B, T, H, dv))
+    S = np.zeros((B, H, dk, dv)) if S0 is None else f(S0).copy()
+    for b in range(B):
+        for h in range(H):
+            for t in range(T):
+                kn = k[b, t, h] / max(np.linalg.norm(k[b, t, h]), 1e-12)
+                S[b, h] = np.exp(-g[b, t, h] * tau[b, t, h])[:, None] * S[b, h] + \
+                    np.outer(g[b, t, h] ** tau[b, t, h] * kn, bh[b, t, h] * v[b, t, h])
+                o[b, t, h] = (q[b, t, h] / np.sqrt(dk)) @ S[b, h]
+    return o, S
+
+
+def test_gated_recurrence_brute_force_composition_and_closed_form():
+    rng = np.random.default_rng(17)
+    B, T, H, dk, dv = 2, 9, 2, 4, 3
+    d = {n: rng.standard_normal((B, T, H, dk)).astype(np.float32) for n in ("q", "k", "z_g", "z_tau")}
+    v = rng.standard_normal((B, T, H, dv)).astype(np.float32)
+    zb = rng.standard_normal((B, T, H, dv)).astype(np.float32)
+    S0 = rng.standard_normal((B, H, dk, dv))
+    for z_beta, s0 in ((zb, S0), (None, None)):
+        o, S_T = oracle.scan_gated(d["q"], d["k"], v, d["z_g"], d["z_tau"], z_beta, s0)
+        o_n, S_n = _numpy_block_recurrence(d["q"], d["k"], v, d["z_g"], d["z_tau"], z_beta, s0)
+        np.testing.assert_allclose(o, o_n, rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(S_T, S_n, rtol=1e-12, atol=1e-13)
+    # decode steps chain to the scan
+    S = S0.copy()
+    o_steps = []
+    for t in range(T):
+        o_t, S = oracle.step_gated(d["q"][:, t], d["k"][:, t], v[:, t], d["z_g"][:, t], d["z_tau"][:, t], zb[:, t], S)
+        o_steps.append(o_t)
+    o, S_T = oracle.scan_gated(d["q"], d["k"], v, d["z_g"], d["z_tau"], zb, S0)
+    assert np.array_equal(np.stack(o_steps, axis=1), o) and np.array_equal(S, S_T)
+    # closed form: tau -> 1 (z_tau = 40), g = 1 (z_g = log(e - 1)): decay 1/e, key gate 1; with k = q = e_1 * c and v = 1
+    # the first state row is the geometric series and o_t = c / sqrt(dk) * (1 - e^-t) / (1 - 1/e)
+    T2, dk2 = 12, 4
+    zg1 = np.full((1, T2, 1, dk2), np.log(np.e - 1.0), np.float32)
+    zt1 = np.full((1, T2, 1, dk2), 40.0, np.float32)
+    e1 = np.zeros((1, T2, 1, dk2), np.float32)
+    e1[..., 0] = 3.0                              # normalisation brings the key back to the unit vector
+    ones = np.ones((1, T2, 1, 2), np.float32)
+    o, S_T = oracle.scan_gated(e1, e1, ones, zg1, zt1, None, None)
+    g_exact = np.logaddexp(0.0, np.float64(zg1[0, 0, 0, 0]))      # softplus of the float32 value, ~1
+    gam = np.exp(-g_exact)
+    t = np.arange(1, T2 + 1)
+    np.testing.assert_allclose(o[0, :, 0, 0], 3.0 / 2.0 * g_exact * (1 - gam ** t) / (1 - gam), rtol=1e-9)
+    assert np.all(S_T[0, 0, 1:] == 0)
+    # zero key: the normalisation guard leaves it zero, nothing is written
+    o, S_T = oracle.scan_gated(e1, np.zeros_like(e1), ones, zg1, zt1, None, None)
+    assert np.all(o == 0) and np.all(S_T == 0)
+
+
+def test_gated_recurrence_agrees_with_gate_front_end_then_scan():
+    # the two-call pipeline (gates, rounded to float32, then the plain recurrence) reaches the same result up to that rounding
+    rng = np.random.default_rng(23)
+    B, T, H, dk, dv = 1, 40, 2, 8, 5
+    d = {n: rng.standard_normal((B, T, H, dk)).astype(np.float32) for n in ("q", "k", "z_g", "z_tau")}
+    v = rng.standard_normal((B, T, H, dv)).astype(np.float32)
+    zb = rng.standard_normal((B, T, H, dv)).astype(np.float32)
+    la, beta, qo, ko = oracle.ddts_gates(d["z_g"], d["z_tau"], zb, d["q"], d["k"])
+    f = lambda a: a.astype(np.float32)
+    o2, S2 = oracle.scan(f(qo), f(ko), v, f(la), f(beta))
+    o1, S1 = oracle.scan_gated(d["q"], d["k"], v, d["z_g"], d["z_tau"], zb)
+    np.testing.assert_allclose(o1, o2, rtol=0, atol=2e-6 * np.abs(o2).max())
+    np.testing.assert_allclose(S1, S2, rtol=0, atol=2e-6 * np.abs(S2).max())
