@@ -171,6 +171,44 @@ def bench_gates(w, rodimus, wl, dev, steps=50, warmup=20):
                               "GB_per_s": algo_key / (ms_key * 1e-3) / 1e9}}
 
 
+def bench_gated_scan(w, rodimus, wl, dev, steps, warmup):
+    """The layer scan with the whole gate front-end fused in (rodimus_chunk_scan_fwd_gated), beside the two-call
+    pipeline it replaces (key-side rodimus_ddts_gates, then rodimus_chunk_scan_fwd_zbeta) on the same inputs."""
+    d = wl.make_gated_scan_inputs(w.B, w.T, w.H, w.dk, w.dv, "bf16", seed=17)
+    g = {k: (None if v is None else v.to(dev)) for k, v in d.items()}
+    o = torch.empty((w.B, w.T, w.H, w.dv), dtype=torch.bfloat16, device=dev)
+    S_T = torch.empty((w.B, w.H, w.dk, w.dv), dtype=torch.float32, device=dev)
+    la = torch.empty((w.B, w.T, w.H, w.dk), dtype=torch.float32, device=dev)
+    qo, ko = torch.empty_like(g["q"]), torch.empty_like(g["k"])
+
+    def fused():
+        rodimus.rodimus_chunk_scan_fwd_gated(g["q"], g["k"], g["v"], g["z_g"], g["z_tau"], g["z_beta"], g["S0"], chunk=w.chunk,
+                                             o=o, S_T=S_T)
+
+    def two_calls():
+        rodimus.rodimus_ddts_gates(g["z_g"], g["z_tau"], None, g["q"], g["k"], log_alpha=la, q_out=qo, k_out=ko)
+        rodimus.rodimus_chunk_scan_fwd_zbeta(qo, ko, g["v"], la, g["z_beta"], g["S0"], chunk=w.chunk, o=o, S_T=S_T)
+
+    def timed(f):
+        warm_up(f, warmup)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(steps):
+            f()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / steps
+
+    ms, ms_pipe = timed(fused), timed(two_calls)
+    th = w.token_heads
+    state_bytes = w.B * w.H * w.dk * w.dv * 4
+    algo = th * (4 * 2 * w.dk + 3 * 2 * w.dv) + 2 * state_bytes       # q, k, z_g, z_tau; v, z_beta, o; S0 and S_T
+    return {"entry_point": "rodimus_chunk_scan_fwd_gated", "workload": "layer_1p6b, every gate as bf16 pre-activation, raw q and k",
+            "ms_per_step": ms, "tokens_per_s": w.tokens / (ms * 1e-3), "algorithmic_bytes": algo,
+            "GB_per_s": algo / (ms * 1e-3) / 1e9, "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "two_call_pipeline_ms": ms_pipe}
+
+
 def bench_short_conv(w, rodimus, wl, dev, steps=50, warmup=20, width=4):
     """The block's ShortConv over the layer workload's tokens: C = H * dv channels, width 4, SiLU, bf16 I/O."""
     C = w.H * w.dv
@@ -359,6 +397,7 @@ def main():
             "entry_point": "rodimus_chunk_scan_fwd_zbeta", "workload": "layer_1p6b, value gate as bf16 pre-activation",
             "tokens_per_s": zb["tokens_per_s"], "ms_per_step": zb["launch_ms"], "algorithmic_bytes": zb["algo_bytes"],
             "GB_per_s": zb["gbs"], "hbm_frac": zb["gbs"] / HBM_PEAK_GBS}
+        out["scan_fused_all_gates"] = bench_gated_scan(w, rodimus, wl, dev, args.steps, args.warmup)
         out["scan_backward"] = bench_backward(w, rodimus, wl, dev, args.steps, args.warmup)
         out["serving_prefill_varlen"] = bench_varlen(w, rodimus, wl, dev, args.steps, args.warmup)
         lf = bench_varlen(w, rodimus, wl, dev, args.steps, args.warmup, longest_first=True)

@@ -276,6 +276,33 @@ int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v,
 /* Scratch bytes the call above needs (0 if the shape is not supported). */
 size_t rodimus_chunk_scan_bwd_workspace_bytes(int B, int T, int H, int dk, int dv, int io_dtype);
 
+/*
+ * The two recurrence calls with the whole DDTS gate front-end fused in (paper Sec. 3.1.2 and the pre-processing of q and k
+ * in Sec. 3.1.3; the block's state-space form of Sec. 3.1.3 evaluated straight from the projections): every gate arrives
+ * as its pre-activation and q, k arrive raw.  Per token and head, inside the kernels, in fp32:
+ *     g = softplus(z_g), tau = sigmoid(z_tau)
+ *     S_t = diag(exp(-g .* tau)) S_{t-1} + (g^tau .* k_t / max(||k_t||_2, 1e-12))^T (sigmoid(z_beta_t) .* v_t)
+ *     o_t = (q_t / sqrt(dk)) S_t
+ * i.e. rodimus_ddts_gates followed by rodimus_chunk_scan_fwd / rodimus_decode_step without the pass over HBM in between
+ * (no log_alpha, beta, scaled q or folded k is ever stored).
+ *
+ *   q, k        [B,T,H,dk] / [N,H,dk] io_dtype   in, raw projections
+ *   z_g, z_tau  same shape as q, io_dtype        in
+ *   z_beta      [B,T,H,dv] / [N,H,dv] io_dtype   in, or NULL = value gate of all ones
+ *   everything else as in rodimus_chunk_scan_fwd / rodimus_decode_step (shapes, kernel families, workspace, alignment,
+ *   aliasing, status codes).
+ */
+int rodimus_chunk_scan_fwd_gated(const void *q, const void *k, const void *v,
+                                 const void *z_g, const void *z_tau, const void *z_beta, const float *S0,
+                                 void *o, float *S_T,
+                                 int B, int T, int H, int dk, int dv, int chunk, int io_dtype,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+int rodimus_decode_step_gated(const void *q, const void *k, const void *v,
+                              const void *z_g, const void *z_tau, const void *z_beta,
+                              float *S, void *o,
+                              int N, int H, int dk, int dv, int io_dtype, void *stream);
+
 /* Activation after the short convolution. */
 typedef enum {
     RODIMUS_CONV_NONE = 0,            /* the convolution alone                                              */

@@ -8,8 +8,7 @@
 //     beta      = sigmoid(z_beta)
 // Elementwise apart from the key norm, hence bound by HBM bandwidth: one thread owns 8 consecutive channels of a
 // row (a row = one token of one head), the dk/8 lanes of a row reduce the squared norm by butterfly shuffles.
-// All arithmetic in fp32.  exp, log and reciprocal use the hardware instructions (about 1 ulp); log(1 + e) switches to
-// its series for small e, where 1 + e would round the information away.
+// All arithmetic in fp32 (ddts_channel_gates, shared with the kernels that take the pre-activations directly).
 #include "internal.h"
 
 namespace rodimus {
@@ -49,13 +48,6 @@ template <> struct Vec8<bf16_t> {
     }
 };
 
-// log(1 + e) for e in [0, 1]
-__device__ __forceinline__ float log1p_unit(float e)
-{
-    const float series = e * (1.f - e * (0.5f - e * (1.f / 3.f - 0.25f * e)));     // |error| < e^5 / 5
-    return e < 0.015625f ? series : __logf(1.f + e);
-}
-
 // key side: log_alpha, q_out, k_out.  lanes_per_row = dk / 8 is a power of two <= 64.
 template <typename IO>
 __global__ __launch_bounds__(kGateThreads) void ddts_key_gates_kernel(
@@ -78,20 +70,15 @@ __global__ __launch_bounds__(kGateThreads) void ddts_key_gates_kernel(
 #pragma unroll
     for (int i = 0; i < 8; ++i) ss = fmaf(kv[i], kv[i], ss);
     for (int m = lanes_per_row >> 1; m > 0; m >>= 1) ss += __shfl_xor(ss, m);     // rows are aligned lane groups
-    const float inv_norm = 1.f / fmaxf(sqrtf(ss), 1e-12f);
+    const float inv_norm = inverse_key_norm(ss);
     const float q_scale = 1.f / sqrtf((float)dk);
 
     float la[8], qo[8], ko[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const float z = zg[i];
-        const float e = __expf(-fabsf(z));
-        const float g = fmaxf(z, 0.f) + log1p_unit(e);             // softplus
-        // log g: for very negative z, g = e^z (1 - e^z / 2 + ...) underflows before its logarithm does
-        const float log_g = z < -15.f ? z - 0.5f * e : __logf(g);
-        const float tau = sigmoid_f(zt[i]);
-        la[i] = -g * tau;
-        ko[i] = __expf(tau * log_g) * kv[i] * inv_norm;            // g^tau .* k / ||k||
+        float alpha_hat;
+        ddts_channel_gates(zg[i], zt[i], la[i], alpha_hat);
+        ko[i] = alpha_hat * kv[i] * inv_norm;                      // g^tau .* k / ||k||
         qo[i] = qv[i] * q_scale;
     }
     if (active) {

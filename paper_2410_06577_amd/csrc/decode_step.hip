@@ -32,7 +32,8 @@ template <typename IO, bool kStream>
 __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(
     const IO *__restrict__ q, const IO *__restrict__ k, const IO *__restrict__ v,
     const float *__restrict__ log_alpha, const void *__restrict__ beta, bool beta_preact,
-    float *__restrict__ S, IO *__restrict__ o, int dk, int dv, int H, OutputStage stage)
+    float *__restrict__ S, IO *__restrict__ o, int dk, int dv, int H, OutputStage stage,
+    const IO *__restrict__ z_g, const IO *__restrict__ z_tau)
 {
     constexpr int kRowBatch = kStream ? 4 : 8;      // rows in flight per wavefront
     __shared__ float s_q[kDecodeMaxDk];
@@ -47,10 +48,32 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(
     const int col = blockIdx.y * kDecodeCols + 4 * lane;
     const bool active = col < dv;
 
-    for (int r = tid; r < dk; r += kDecodeThreads) {
-        s_q[r] = load_as_float(q + state * dk + r);
-        s_k[r] = load_as_float(k + state * dk + r);
-        s_a[r] = expf(log_alpha[state * dk + r]);        // exp(-inf) = 0
+    if (z_tau == nullptr) {
+        for (int r = tid; r < dk; r += kDecodeThreads) {
+            s_q[r] = load_as_float(q + state * dk + r);
+            s_k[r] = load_as_float(k + state * dk + r);
+            s_a[r] = expf(log_alpha[state * dk + r]);        // exp(-inf) = 0
+        }
+    } else {
+        // gated form (uniform branch): the key-side gates from their pre-activations, the key normalised, the query scaled.
+        // dk <= 256 = one channel per thread.
+        __shared__ float s_part[kDecodeWaves];
+        const bool own = tid < dk;
+        float kr = 0.f, alpha_hat = 0.f;
+        if (own) {
+            float la;
+            ddts_channel_gates(load_as_float(z_g + state * dk + tid), load_as_float(z_tau + state * dk + tid), la, alpha_hat);
+            kr = load_as_float(k + state * dk + tid);
+            s_a[tid] = expf(la);
+            s_q[tid] = load_as_float(q + state * dk + tid) * (1.f / sqrtf((float)dk));
+        }
+        float ss = kr * kr;
+#pragma unroll
+        for (int m = 32; m > 0; m >>= 1) ss += __shfl_xor(ss, m);
+        if (lane == 0) s_part[wave] = ss;
+        __syncthreads();
+        const float inv_norm = inverse_key_norm(s_part[0] + s_part[1] + s_part[2] + s_part[3]);
+        if (own) s_k[tid] = alpha_hat * kr * inv_norm;
     }
 
     floatx4_t gv = {0.f, 0.f, 0.f, 0.f};                 // beta .* v for this lane's columns
@@ -133,7 +156,8 @@ hipError_t launch_decode_step(const DecodeArgs &a)
     const bool stream = (size_t)states * a.dk * a.dv * sizeof(float) > kLastLevelCacheBytes;
 #define RODIMUS_LAUNCH_DECODE(IO, STREAM)                                                                         \
     hipLaunchKernelGGL((decode_step_kernel<IO, STREAM>), grid, block, 0, a.stream, (const IO *)a.q, (const IO *)a.k, \
-                       (const IO *)a.v, a.log_alpha, a.beta, a.beta_preact, a.S, (IO *)a.o, a.dk, a.dv, a.H, a.stage)
+                       (const IO *)a.v, a.log_alpha, a.beta, a.beta_preact, a.S, (IO *)a.o, a.dk, a.dv, a.H, a.stage, \
+                       (const IO *)a.z_g, (const IO *)a.z_tau)
     if (a.io_dtype == RODIMUS_BF16) {
         if (stream) RODIMUS_LAUNCH_DECODE(bf16_t, true); else RODIMUS_LAUNCH_DECODE(bf16_t, false);
     } else {

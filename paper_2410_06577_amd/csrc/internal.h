@@ -37,6 +37,30 @@ __device__ __forceinline__ float sigmoid_f(float z)
     return z >= 0.f ? r : e * r;
 }
 
+// log(1 + e) for e in [0, 1]; the series where 1 + e would round the information away
+__device__ __forceinline__ float log1p_unit(float e)
+{
+    const float series = e * (1.f - e * (0.5f - e * (1.f / 3.f - 0.25f * e)));     // |error| < e^5 / 5
+    return e < 0.015625f ? series : __logf(1.f + e);
+}
+
+// The two key-side DDTS gates of one channel (paper Sec. 3.1.2) from their pre-activations, with g = softplus(z_g) and
+// tau = sigmoid(z_tau):  log_alpha = -g * tau (the decay gate is exp of it), alpha_hat = g^tau (the input gate folded
+// into the key).  Hardware exp, log and reciprocal (about 1 ulp each).
+__device__ __forceinline__ void ddts_channel_gates(float z_g, float z_tau, float &log_alpha, float &alpha_hat)
+{
+    const float e = __expf(-fabsf(z_g));
+    const float g = fmaxf(z_g, 0.f) + log1p_unit(e);             // softplus
+    // log g: for very negative z, g = e^z (1 - e^z / 2 + ...) underflows before its logarithm does
+    const float log_g = z_g < -15.f ? z_g - 0.5f * e : __logf(g);
+    const float tau = sigmoid_f(z_tau);
+    log_alpha = -g * tau;
+    alpha_hat = __expf(tau * log_g);
+}
+
+// 1 / max(||k||_2, 1e-12) from the squared norm: the key normalisation of Sec. 3.1.3
+__device__ __forceinline__ float inverse_key_norm(float sum_of_squares) { return 1.f / fmaxf(sqrtf(sum_of_squares), 1e-12f); }
+
 // Element loads/stores templated on the I/O element type (float or bf16_t).
 template <typename T> __device__ __forceinline__ float load_as_float(const T *p);
 template <> __device__ __forceinline__ float load_as_float<float>(const float *p) { return *p; }
@@ -131,6 +155,11 @@ struct ScanArgs {
     void *workspace;
     size_t workspace_bytes;
     hipStream_t stream;
+    // Gated form (both non-NULL): the key-side gates arrive as pre-activations in the I/O dtype, q and k raw; the kernels
+    // evaluate log_alpha = -softplus(z_g) sigmoid(z_tau), fold softplus(z_g)^sigmoid(z_tau) / ||k|| into k and 1 / sqrt(dk)
+    // into q.  `log_alpha` is then unused.
+    const void *z_g = nullptr, *z_tau = nullptr;
+    bool gated() const { return z_tau != nullptr; }
 };
 
 struct DecodeArgs {
@@ -144,6 +173,8 @@ struct DecodeArgs {
     int N, H, dk, dv;
     int io_dtype;
     hipStream_t stream;
+    const void *z_g = nullptr, *z_tau = nullptr;     // gated form, as in ScanArgs
+    bool gated() const { return z_tau != nullptr; }
 };
 
 struct GateArgs {

@@ -41,31 +41,36 @@ int scan_shape_status(int B, int T, int H, int dk, int dv, int chunk, int io_dty
 int scan_entry(const void *q, const void *k, const void *v, const float *log_alpha, const void *beta, bool beta_preact,
                const float *S0, void *o, float *S_T, int B, int T, int H, int dk, int dv, int chunk, int io_dtype,
                void *workspace, size_t workspace_bytes, void *stream, bool packed = false, const int *cu_seqlens = nullptr,
-               OutputStage stage = OutputStage{nullptr, nullptr, nullptr, 0})
+               OutputStage stage = OutputStage{nullptr, nullptr, nullptr, 0}, bool gated = false, const void *z_g = nullptr,
+               const void *z_tau = nullptr)
 {
     const int shape = scan_shape_status(B, T, H, dk, dv, chunk, io_dtype);
     if (shape != RODIMUS_OK) return shape;
     if (packed && B > 0 && cu_seqlens == nullptr) return RODIMUS_ERR_NULL;
     if (packed && misaligned(cu_seqlens)) return RODIMUS_ERR_ALIGN;
     const size_t tokens = packed ? (size_t)T * H : (size_t)B * T * H;
-    if (tokens > 0 && (!q || !k || !v || !log_alpha || !o)) return RODIMUS_ERR_NULL;   // empty tensors may be NULL
-    if (tokens > 0 && beta_preact && !beta) return RODIMUS_ERR_NULL;
-    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(log_alpha) || misaligned(beta) ||
+    // the key-side gates: log_alpha (fp32), or in the gated form the two pre-activations (I/O dtype)
+    const void *gate_a = gated ? z_g : static_cast<const void *>(log_alpha);
+    const void *gate_b = gated ? z_tau : nullptr;
+    if (tokens > 0 && (!q || !k || !v || !gate_a || !o)) return RODIMUS_ERR_NULL;   // empty tensors may be NULL
+    if (tokens > 0 && gated && !gate_b) return RODIMUS_ERR_NULL;
+    if (tokens > 0 && beta_preact && !beta && !gated) return RODIMUS_ERR_NULL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(gate_a) || misaligned(gate_b) || misaligned(beta) ||
         misaligned(S0) || misaligned(o) || misaligned(S_T) || misaligned(workspace))
         return RODIMUS_ERR_ALIGN;
 
     const size_t eb = elem_bytes(io_dtype);
     const size_t qk_bytes = tokens * dk * eb, v_bytes = tokens * dv * eb;
-    const size_t la_bytes = tokens * dk * 4, beta_bytes = tokens * dv * (beta_preact ? eb : 4);
+    const size_t la_bytes = tokens * dk * (gated ? eb : 4), beta_bytes = tokens * dv * (beta_preact ? eb : 4);
     const size_t state_bytes = (size_t)B * H * dk * dv * 4;
     if (overlaps(o, v_bytes, q, qk_bytes) || overlaps(o, v_bytes, k, qk_bytes) || overlaps(o, v_bytes, v, v_bytes) ||
-        overlaps(o, v_bytes, log_alpha, la_bytes) || overlaps(o, v_bytes, beta, beta_bytes) ||
-        overlaps(o, v_bytes, S0, state_bytes) || overlaps(o, v_bytes, S_T, state_bytes))
+        overlaps(o, v_bytes, gate_a, la_bytes) || overlaps(o, v_bytes, gate_b, la_bytes) ||
+        overlaps(o, v_bytes, beta, beta_bytes) || overlaps(o, v_bytes, S0, state_bytes) || overlaps(o, v_bytes, S_T, state_bytes))
         return RODIMUS_ERR_ALIAS;
     if (S_T != nullptr && S_T != S0 && overlaps(S_T, state_bytes, S0, state_bytes)) return RODIMUS_ERR_ALIAS;
     if (overlaps(S_T, state_bytes, q, qk_bytes) || overlaps(S_T, state_bytes, k, qk_bytes) ||
-        overlaps(S_T, state_bytes, v, v_bytes) || overlaps(S_T, state_bytes, log_alpha, la_bytes) ||
-        overlaps(S_T, state_bytes, beta, beta_bytes))
+        overlaps(S_T, state_bytes, v, v_bytes) || overlaps(S_T, state_bytes, gate_a, la_bytes) ||
+        overlaps(S_T, state_bytes, gate_b, la_bytes) || overlaps(S_T, state_bytes, beta, beta_bytes))
         return RODIMUS_ERR_ALIAS;
     if (stage.x_prime != nullptr && stage.d == nullptr) return RODIMUS_ERR_NULL;
     if (misaligned(stage.x_prime) || misaligned(stage.d) || misaligned(stage.z_gate)) return RODIMUS_ERR_ALIGN;
@@ -81,33 +86,38 @@ int scan_entry(const void *q, const void *k, const void *v, const float *log_alp
 
     ScanArgs a{q, k, v, log_alpha, beta, beta_preact, S0, o, S_T, B, T, H, dk, dv, chunk, io_dtype,
                packed ? cu_seqlens : nullptr, stage, workspace, workspace_bytes, static_cast<hipStream_t>(stream)};
+    if (gated) { a.log_alpha = nullptr; a.z_g = z_g; a.z_tau = z_tau; }
     const hipError_t err = scan_mfma_supports(dk, dv, chunk, io_dtype) ? launch_scan_mfma(a) : launch_scan_generic(a);
     return err == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
 }
 
 int decode_entry(const void *q, const void *k, const void *v, const float *log_alpha, const void *beta, bool beta_preact,
                  float *S, void *o, int N, int H, int dk, int dv, int io_dtype, void *stream,
-                 OutputStage stage = OutputStage{nullptr, nullptr, nullptr, 0})
+                 OutputStage stage = OutputStage{nullptr, nullptr, nullptr, 0}, bool gated = false, const void *z_g = nullptr,
+                 const void *z_tau = nullptr)
 {
     if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
     if (N < 0 || H < 0 || dk < 1 || dk > kMaxDecodeDk || dv < 4 || (dv & 3) != 0) return RODIMUS_ERR_SHAPE;
     if ((long long)N * H > kMaxGridX || (dv + 255) / 256 > 65535) return RODIMUS_ERR_SHAPE;
     const size_t states = (size_t)N * H;
-    if (states > 0 && (!q || !k || !v || !log_alpha || !S || !o)) return RODIMUS_ERR_NULL;
-    if (states > 0 && beta_preact && !beta) return RODIMUS_ERR_NULL;
-    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(log_alpha) || misaligned(beta) ||
+    const void *gate_a = gated ? z_g : static_cast<const void *>(log_alpha);
+    const void *gate_b = gated ? z_tau : nullptr;
+    if (states > 0 && (!q || !k || !v || !gate_a || !S || !o)) return RODIMUS_ERR_NULL;
+    if (states > 0 && gated && !gate_b) return RODIMUS_ERR_NULL;
+    if (states > 0 && beta_preact && !beta && !gated) return RODIMUS_ERR_NULL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(gate_a) || misaligned(gate_b) || misaligned(beta) ||
         misaligned(S) || misaligned(o))
         return RODIMUS_ERR_ALIGN;
 
     const size_t eb = elem_bytes(io_dtype);
     const size_t o_bytes = states * dv * eb, s_bytes = states * dk * dv * 4;
-    const size_t beta_bytes = states * dv * (beta_preact ? eb : 4);
+    const size_t beta_bytes = states * dv * (beta_preact ? eb : 4), la_bytes = states * dk * (gated ? eb : 4);
     if (overlaps(o, o_bytes, q, states * dk * eb) || overlaps(o, o_bytes, k, states * dk * eb) ||
-        overlaps(o, o_bytes, v, o_bytes) || overlaps(o, o_bytes, log_alpha, states * dk * 4) ||
+        overlaps(o, o_bytes, v, o_bytes) || overlaps(o, o_bytes, gate_a, la_bytes) || overlaps(o, o_bytes, gate_b, la_bytes) ||
         overlaps(o, o_bytes, beta, beta_bytes) || overlaps(o, o_bytes, S, s_bytes))
         return RODIMUS_ERR_ALIAS;
     if (overlaps(S, s_bytes, q, states * dk * eb) || overlaps(S, s_bytes, k, states * dk * eb) ||
-        overlaps(S, s_bytes, v, o_bytes) || overlaps(S, s_bytes, log_alpha, states * dk * 4) ||
+        overlaps(S, s_bytes, v, o_bytes) || overlaps(S, s_bytes, gate_a, la_bytes) || overlaps(S, s_bytes, gate_b, la_bytes) ||
         overlaps(S, s_bytes, beta, beta_bytes))
         return RODIMUS_ERR_ALIAS;
 
@@ -118,6 +128,7 @@ int decode_entry(const void *q, const void *k, const void *v, const float *log_a
         overlaps(S, s_bytes, stage.z_gate, o_bytes) || overlaps(S, s_bytes, stage.d, (size_t)H * dv * 4))
         return RODIMUS_ERR_ALIAS;
     DecodeArgs a{q, k, v, log_alpha, beta, beta_preact, stage, S, o, N, H, dk, dv, io_dtype, static_cast<hipStream_t>(stream)};
+    if (gated) { a.log_alpha = nullptr; a.z_g = z_g; a.z_tau = z_tau; }
     const hipError_t err = launch_decode_step(a);
     return err == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
 }
@@ -209,6 +220,21 @@ int rodimus_decode_step_zbeta(const void *q, const void *k, const void *v, const
                               float *S, void *o, int N, int H, int dk, int dv, int io_dtype, void *stream)
 {
     return decode_entry(q, k, v, log_alpha, z_beta, true, S, o, N, H, dk, dv, io_dtype, stream);
+}
+
+int rodimus_chunk_scan_fwd_gated(const void *q, const void *k, const void *v, const void *z_g, const void *z_tau,
+                                 const void *z_beta, const float *S0, void *o, float *S_T, int B, int T, int H, int dk, int dv,
+                                 int chunk, int io_dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return scan_entry(q, k, v, nullptr, z_beta, true, S0, o, S_T, B, T, H, dk, dv, chunk, io_dtype, workspace, workspace_bytes,
+                      stream, false, nullptr, OutputStage{nullptr, nullptr, nullptr, 0}, true, z_g, z_tau);
+}
+
+int rodimus_decode_step_gated(const void *q, const void *k, const void *v, const void *z_g, const void *z_tau,
+                              const void *z_beta, float *S, void *o, int N, int H, int dk, int dv, int io_dtype, void *stream)
+{
+    return decode_entry(q, k, v, nullptr, z_beta, true, S, o, N, H, dk, dv, io_dtype, stream,
+                        OutputStage{nullptr, nullptr, nullptr, 0}, true, z_g, z_tau);
 }
 
 size_t rodimus_chunk_scan_bwd_workspace_bytes(int B, int T, int H, int dk, int dv, int io_dtype)

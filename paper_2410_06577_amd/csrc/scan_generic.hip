@@ -41,7 +41,7 @@ __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
     const IO *__restrict__ q, const IO *__restrict__ k, const IO *__restrict__ v,
     const float *__restrict__ log_alpha, const void *__restrict__ beta, bool beta_preact, const float *S0,
     IO *__restrict__ o, float *S_T, int T, int H, int dk, int dv, int C, const int *__restrict__ cu_seqlens,
-    OutputStage stage)
+    OutputStage stage, const IO *__restrict__ z_g, const IO *__restrict__ z_tau)
 {
     extern __shared__ float lds[];
     const int dkp = dk + 1;                 // padded row stride against bank conflicts
@@ -68,6 +68,7 @@ __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
     const int ncol = min(kColTile, dv - j0);
     const int Cp = next_pow2(C);
     const size_t state_base = (size_t)bh * dk * dv + j0;
+    const float q_scale = 1.f / sqrtf((float)dk);
 
     for (int e = tid; e < dk * kColTile; e += kThreads) {
         const int r = e / kColTile, c = e % kColTile;
@@ -81,10 +82,34 @@ __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
             const int t = e / dk, r = e % dk;
             const size_t g = ((tok0 + s + t) * H + h) * dk + r;
             const bool ok = t < n;
-            sq[t * dkp + r] = ok ? load_as_float(q + g) : 0.f;
-            sk[t * dkp + r] = ok ? load_as_float(k + g) : 0.f;
-            pp[t * dkp + r] = ok ? expf(log_alpha[g]) : 1.f;
-            sp[t * dkp + r] = 1.f;
+            float qv = ok ? load_as_float(q + g) : 0.f, kv = ok ? load_as_float(k + g) : 0.f, la = 0.f;
+            if (z_tau == nullptr) {
+                if (ok) la = log_alpha[g];
+                sp[t * dkp + r] = 1.f;
+            } else {
+                // gated form: the key-side gates from their pre-activations; alpha_hat waits in sp for the key's norm
+                float alpha_hat = 0.f;
+                if (ok) ddts_channel_gates(load_as_float(z_g + g), load_as_float(z_tau + g), la, alpha_hat);
+                sp[t * dkp + r] = alpha_hat;
+                qv *= q_scale;
+            }
+            sq[t * dkp + r] = qv;
+            sk[t * dkp + r] = kv;
+            pp[t * dkp + r] = expf(la);
+        }
+        if (z_tau != nullptr) {              // uniform branch: k <- alpha_hat .* k / max(||k||_2, 1e-12)
+            __syncthreads();
+            for (int t = tid; t < C; t += kThreads) {
+                float ss = 0.f;
+                for (int r = 0; r < dk; ++r) ss = fmaf(sk[t * dkp + r], sk[t * dkp + r], ss);
+                P[t * Pp + t] = inverse_key_norm(ss);            // the diagonal is rewritten below
+            }
+            __syncthreads();
+            for (int e = tid; e < C * dk; e += kThreads) {
+                const int t = e / dk, r = e % dk;
+                sk[t * dkp + r] *= sp[t * dkp + r] * P[t * Pp + t];
+                sp[t * dkp + r] = 1.f;
+            }
         }
         for (int e = tid; e < C * kColTile; e += kThreads) {
             const int t = e / kColTile, c = e % kColTile;
@@ -198,7 +223,8 @@ static hipError_t launch_typed(const ScanArgs &a)
     if (err != hipSuccess) return err;
     dim3 grid((unsigned)(a.B * a.H), (unsigned)((a.dv + kColTile - 1) / kColTile)), block(kThreads);
     hipLaunchKernelGGL(scan_generic_kernel<IO>, grid, block, lds, a.stream, (const IO *)a.q, (const IO *)a.k,
-                       (const IO *)a.v, a.log_alpha, a.beta, a.beta_preact, a.S0, (IO *)a.o, a.S_T, a.T, a.H, a.dk, a.dv, a.chunk, a.cu_seqlens, a.stage);
+                       (const IO *)a.v, a.log_alpha, a.beta, a.beta_preact, a.S0, (IO *)a.o, a.S_T, a.T, a.H, a.dk, a.dv, a.chunk, a.cu_seqlens, a.stage,
+                       (const IO *)a.z_g, (const IO *)a.z_tau);
     return hipGetLastError();
 }
 

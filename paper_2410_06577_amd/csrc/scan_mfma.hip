@@ -98,6 +98,7 @@ constexpr int QP(int a, int b, int c, int d) { return a | (b << 2) | (c << 4) | 
 struct Geometry {
     const bf16_t *q, *k, *v;
     const float *la;
+    const bf16_t *zg, *zt;  // gated form (kGated): pre-activations of the key-side gates instead of la
     const void *beta;       // value gate: fp32 values, or bf16 pre-activations (kZBeta), or null
     bf16_t *o;
     int H, dv;
@@ -111,28 +112,88 @@ struct Geometry {
 // =========================================================================================================
 struct GateLoads {          // one row, 16 channels: 8g..8g+7 and 32+8g..32+8g+7
     uint4 q[2], k[2];
-    floatx4_t la[4];
+    floatx4_t la[4];        // gated form, until gate_activate(): the bits of z_g (la[0], la[1]) and z_tau (la[2], la[3]), 8 bf16 each
 };
 
 // Loads are unconditional (the row index is clamped to the last valid token) so that they stay in flight across
 // the barrier; rows at or beyond T are neutralised when consumed (gate_tile: q = k = 0, alpha = 1).
-template <bool kSummary>
+template <bool kSummary, bool kGated>
 __device__ __forceinline__ void gate_prefetch(const Geometry &g, int t, int grp, GateLoads &p)
 {
     const size_t tok = (g.tok0 + min(t, g.t_end - 1)) * g.H + g.h;
     const bf16_t *qp = g.q + tok * kK + 8 * grp;
     const bf16_t *kp = g.k + tok * kK + 8 * grp;
-    const float *lp = g.la + tok * kK + 8 * grp;
     if (!kSummary) {
         p.q[0] = *reinterpret_cast<const uint4 *>(qp);
         p.q[1] = *reinterpret_cast<const uint4 *>(qp + 32);
     }
     p.k[0] = *reinterpret_cast<const uint4 *>(kp);
     p.k[1] = *reinterpret_cast<const uint4 *>(kp + 32);
-    p.la[0] = *reinterpret_cast<const floatx4_t *>(lp);
-    p.la[1] = *reinterpret_cast<const floatx4_t *>(lp + 4);
-    p.la[2] = *reinterpret_cast<const floatx4_t *>(lp + 32);
-    p.la[3] = *reinterpret_cast<const floatx4_t *>(lp + 36);
+    if (kGated) {
+        const bf16_t *gp = g.zg + tok * kK + 8 * grp, *tp = g.zt + tok * kK + 8 * grp;
+        p.la[0] = *reinterpret_cast<const floatx4_t *>(gp);
+        p.la[1] = *reinterpret_cast<const floatx4_t *>(gp + 32);
+        p.la[2] = *reinterpret_cast<const floatx4_t *>(tp);
+        p.la[3] = *reinterpret_cast<const floatx4_t *>(tp + 32);
+    } else {
+        const float *lp = g.la + tok * kK + 8 * grp;
+        p.la[0] = *reinterpret_cast<const floatx4_t *>(lp);
+        p.la[1] = *reinterpret_cast<const floatx4_t *>(lp + 4);
+        p.la[2] = *reinterpret_cast<const floatx4_t *>(lp + 32);
+        p.la[3] = *reinterpret_cast<const floatx4_t *>(lp + 36);
+    }
+}
+
+__device__ __forceinline__ bf16x8_t pack8(const float *x);
+
+__device__ __forceinline__ void unpack_bf16x8(const uint4 &w, float *x)
+{
+    x[0] = bf16_lo(w.x); x[1] = bf16_hi(w.x); x[2] = bf16_lo(w.y); x[3] = bf16_hi(w.y);
+    x[4] = bf16_lo(w.z); x[5] = bf16_hi(w.z); x[6] = bf16_lo(w.w); x[7] = bf16_hi(w.w);
+}
+
+// Gated form: turn the loaded pre-activations and raw q, k of one row into what the rest of the gate wavefront expects
+// (paper Sec. 3.1.2 and the pre-processing of Sec. 3.1.3): log_alpha = -softplus(z_g) sigmoid(z_tau) in fp32,
+// k <- softplus(z_g)^sigmoid(z_tau) .* k / max(||k||_2, 1e-12) and q <- q / sqrt(64), both rounded to bf16 (what a separate
+// gate pass would have written; the division by 8 is exact).  The four lanes that share a row (one per channel group)
+// add up the squared norm.
+template <bool kSummary>
+__device__ __forceinline__ void gate_activate(GateLoads &in)
+{
+    float kf[16], zg[16], zt[16];
+    unpack_bf16x8(in.k[0], kf);
+    unpack_bf16x8(in.k[1], kf + 8);
+    unpack_bf16x8(__builtin_bit_cast(uint4, in.la[0]), zg);
+    unpack_bf16x8(__builtin_bit_cast(uint4, in.la[1]), zg + 8);
+    unpack_bf16x8(__builtin_bit_cast(uint4, in.la[2]), zt);
+    unpack_bf16x8(__builtin_bit_cast(uint4, in.la[3]), zt + 8);
+    float ss = 0.f;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) ss = fmaf(kf[c], kf[c], ss);
+    ss += __shfl_xor(ss, 16);
+    ss += __shfl_xor(ss, 32);
+    const float inv_norm = inverse_key_norm(ss);
+    float la[16], kh[16];
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+        float alpha_hat;
+        ddts_channel_gates(zg[c], zt[c], la[c], alpha_hat);
+        kh[c] = alpha_hat * kf[c] * inv_norm;
+    }
+    in.k[0] = __builtin_bit_cast(uint4, pack8(kh));
+    in.k[1] = __builtin_bit_cast(uint4, pack8(kh + 8));
+#pragma unroll
+    for (int m = 0; m < 4; ++m) in.la[m] = floatx4_t{la[4 * m], la[4 * m + 1], la[4 * m + 2], la[4 * m + 3]};
+    if (!kSummary) {
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            float qf[8];
+            unpack_bf16x8(in.q[m], qf);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) qf[c] *= 0.125f;
+            in.q[m] = __builtin_bit_cast(uint4, pack8(qf));
+        }
+    }
 }
 
 __device__ __forceinline__ void gate_mask_padding(bool valid, GateLoads &p)
@@ -294,9 +355,10 @@ __device__ __forceinline__ void gate_tile_products(unsigned char *buf, int tile,
 // product-only construction above.  The choice is per tile and wavefront-uniform.
 constexpr float kSafeTileDecay = 8.2718061e-25f;     // 2^-80: 1 / A_i stays below 2^80, far inside bf16 and fp32 range
 
-template <bool kSummary>
+template <bool kSummary, bool kGated>
 __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row, int grp, GateLoads &in, bool valid)
 {
+    if (kGated) gate_activate<kSummary>(in);
     if (kSummary) { const uint4 z = {0u, 0u, 0u, 0u}; in.q[0] = in.q[1] = z; }
     gate_mask_padding(valid, in);
 
@@ -611,11 +673,12 @@ struct SegmentPlan {
 // kSummary = false: the scan proper over this workgroup's segment (blockIdx.z), reading its entering state.
 // kSummary = true : same walk from a zero state without q, scores or outputs; leaves the segment's state
 //                   increment in slot seg+1 and the segment's total decay in gamma[seg].
-// kZBeta: `beta` holds bf16 pre-activations of the value gate instead of fp32 gate values.
-template <bool kSummary, bool kZBeta>
+// kZBeta: `beta` holds bf16 pre-activations of the value gate instead of fp32 gate values (and is not NULL).
+// kGated: `log_alpha` holds the bf16 pre-activations z_g and `z_tau` those of the temperature gate; q and k are raw.
+template <bool kSummary, bool kZBeta, bool kGated>
 __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
-    const float *__restrict__ log_alpha, const void *__restrict__ beta, const float *S0,
+    const void *__restrict__ log_alpha, const bf16_t *__restrict__ z_tau, const void *__restrict__ beta, const float *S0,
     bf16_t *__restrict__ o, float *S_T, int T, int H, int dv, SegmentPlan plan, const int *__restrict__ cu_seqlens,
     int total_tokens)
 {
@@ -627,7 +690,10 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
     const bool has_beta = beta != nullptr;
 
     Geometry g;
-    g.q = q; g.k = k; g.v = v; g.la = log_alpha; g.beta = beta; g.o = o;
+    g.q = q; g.k = k; g.v = v; g.beta = beta; g.o = o;
+    g.la = kGated ? nullptr : static_cast<const float *>(log_alpha);
+    g.zg = kGated ? static_cast<const bf16_t *>(log_alpha) : nullptr;
+    g.zt = z_tau;
     g.H = H; g.dv = dv;
     g.h = bh % H; g.j0 = blockIdx.y * kColTile;
     g.tok0 = (size_t)(bh / H) * T;
@@ -649,15 +715,15 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
         // ------------------------------------------------------------------ gate wavefront, tile = wave
         GateLoads even, odd;      // loads of even / odd chunks: no register copies between iterations
         const int row0 = t_begin + 16 * wave + n;
-        if (nchunks > 0) gate_prefetch<kSummary>(g, row0, grp, even);
+        if (nchunks > 0) gate_prefetch<kSummary, kGated>(g, row0, grp, even);
         // Iteration `it`: store the outputs of chunk it-2 (finished by the state wavefronts in iteration it-1), then
         // build chunk it.  nchunks + 2 iterations, one barrier each, for both kinds of wavefront.
         for (int it = 0;;) {
             unsigned long long t0 = PROF_T();
             if (!kSummary && it >= 2) store_outputs(g, lds + kOffOb, t_begin + (it - 2) * kChunk, wave, lane);
             if (it < nchunks) {
-                gate_prefetch<kSummary>(g, row0 + (it + 1) * kChunk, grp, odd);   // unconditional (clamped): keeps the wait counts exact
-                gate_tile<kSummary>(lds, wave, n, grp, even, row0 + it * kChunk < g.t_end);
+                gate_prefetch<kSummary, kGated>(g, row0 + (it + 1) * kChunk, grp, odd);   // unconditional (clamped): keeps the wait counts exact
+                gate_tile<kSummary, kGated>(lds, wave, n, grp, even, row0 + it * kChunk < g.t_end);
             }
             PROF_ADD(wave * 2, t0);
             t0 = PROF_T();
@@ -667,8 +733,8 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
             t0 = PROF_T();
             if (!kSummary && it >= 2) store_outputs(g, lds + kOffOb + kObBuf, t_begin + (it - 2) * kChunk, wave, lane);
             if (it < nchunks) {
-                gate_prefetch<kSummary>(g, row0 + (it + 1) * kChunk, grp, even);
-                gate_tile<kSummary>(lds + kBufBytes, wave, n, grp, odd, row0 + it * kChunk < g.t_end);
+                gate_prefetch<kSummary, kGated>(g, row0 + (it + 1) * kChunk, grp, even);
+                gate_tile<kSummary, kGated>(lds + kBufBytes, wave, n, grp, odd, row0 + it * kChunk < g.t_end);
             }
             PROF_ADD(wave * 2, t0);
             t0 = PROF_T();
@@ -823,7 +889,7 @@ size_t scan_mfma_workspace_bytes(int B, int T, int H, int dv)
 
 namespace {
 
-template <bool kZBeta>
+template <bool kZBeta, bool kGated>
 hipError_t launch_scan_mfma_typed(const ScanArgs &a)
 {
     // a packed variable-length batch is never cut into segments (its lengths live in device memory): one segment
@@ -832,27 +898,28 @@ hipError_t launch_scan_mfma_typed(const ScanArgs &a)
                                                   : choose_split(a.B, a.T, a.H, a.dv);
     const size_t bh = (size_t)a.B * a.H;
     SegmentPlan plan{sp.nseg, sp.seg_tokens, nullptr, nullptr};
-    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel<false, kZBeta>),
+    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel<false, kZBeta, kGated>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (attr == hipSuccess)
-        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel<true, kZBeta>),
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel<true, kZBeta, kGated>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (attr != hipSuccess) return attr;
     const dim3 block(kThreads);
     const unsigned col_tiles = (unsigned)(a.dv / kColTile);
+    const void *gate_a = kGated ? a.z_g : static_cast<const void *>(a.log_alpha);
     if (sp.nseg > 1) {
         plan.slots = static_cast<float *>(a.workspace);
         plan.gamma = plan.slots + (size_t)sp.nseg * bh * kK * a.dv;
-        hipLaunchKernelGGL((scan_mfma_kernel<true, kZBeta>), dim3((unsigned)bh, col_tiles, (unsigned)(sp.nseg - 1)), block,
-                           kLdsBytes, a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha,
-                           a.beta, (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, a.T, a.H, a.dv, plan,
+        hipLaunchKernelGGL((scan_mfma_kernel<true, kZBeta, kGated>), dim3((unsigned)bh, col_tiles, (unsigned)(sp.nseg - 1)), block,
+                           kLdsBytes, a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, gate_a,
+                           (const bf16_t *)a.z_tau, a.beta, (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, a.T, a.H, a.dv, plan,
                            (const int *)nullptr, 0);
         const size_t quads = bh * kK * a.dv / 4;
         hipLaunchKernelGGL(segment_state_scan_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, a.stream, a.S0,
                            plan, a.dv, quads);
     }
-    hipLaunchKernelGGL((scan_mfma_kernel<false, kZBeta>), dim3((unsigned)bh, col_tiles, (unsigned)sp.nseg), block, kLdsBytes,
-                       a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0,
+    hipLaunchKernelGGL((scan_mfma_kernel<false, kZBeta, kGated>), dim3((unsigned)bh, col_tiles, (unsigned)sp.nseg), block, kLdsBytes,
+                       a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, gate_a, (const bf16_t *)a.z_tau, a.beta, a.S0,
                        (bf16_t *)a.o, a.S_T, a.T, a.H, a.dv, plan, a.cu_seqlens, a.T);
     if (a.stage.any()) {
         const size_t tokens = a.cu_seqlens != nullptr ? (size_t)a.T : (size_t)a.B * a.T;
@@ -870,7 +937,10 @@ hipError_t launch_scan_mfma(const ScanArgs &a)
 {
     if ((long long)a.B * a.H == 0) return hipSuccess;
     if (a.T == 0 && (a.S_T == nullptr || a.S_T == a.S0)) return hipSuccess;
-    return (a.beta != nullptr && a.beta_preact) ? launch_scan_mfma_typed<true>(a) : launch_scan_mfma_typed<false>(a);
+    // the gated form takes the value gate as a pre-activation too, or none at all (kZBeta loads through `beta`
+    // unconditionally, so a missing gate must take the other instance, where a NULL beta means all ones)
+    if (a.gated()) return a.beta != nullptr ? launch_scan_mfma_typed<true, true>(a) : launch_scan_mfma_typed<false, true>(a);
+    return (a.beta != nullptr && a.beta_preact) ? launch_scan_mfma_typed<true, false>(a) : launch_scan_mfma_typed<false, false>(a);
 }
 
 }  // namespace rodimus

@@ -63,6 +63,10 @@ def lib() -> ctypes.CDLL:
         L.rodimus_decode_step_block.restype = i
         L.rodimus_ddts_gates.argtypes = [vp] * 9 + [ctypes.c_longlong, i, i, i, vp]
         L.rodimus_ddts_gates.restype = i
+        L.rodimus_chunk_scan_fwd_gated.argtypes = [vp] * 9 + [i] * 7 + [vp, sz, vp]
+        L.rodimus_chunk_scan_fwd_gated.restype = i
+        L.rodimus_decode_step_gated.argtypes = [vp] * 8 + [i] * 5 + [vp]
+        L.rodimus_decode_step_gated.restype = i
         L.rodimus_short_conv_fwd.argtypes = [vp] * 6 + [i] * 6 + [vp]
         L.rodimus_short_conv_fwd.restype = i
         L.rodimus_short_conv_step.argtypes = [vp] * 5 + [i] * 5 + [vp]
@@ -151,6 +155,67 @@ def rodimus_chunk_scan_fwd(q, k, v, log_alpha, beta=None, S0=None, *, chunk=64, 
 def rodimus_chunk_scan_fwd_zbeta(q, k, v, log_alpha, z_beta, S0=None, **kw):
     """``rodimus_chunk_scan_fwd`` with the value gate given as its pre-activation z_beta [B,T,H,dv] (dtype of v)."""
     return rodimus_chunk_scan_fwd(q, k, v, log_alpha, z_beta, S0, _preact=True, **kw)
+
+
+def rodimus_chunk_scan_fwd_gated(q, k, v, z_g, z_tau, z_beta=None, S0=None, *, chunk=64, o=None, S_T=None,
+                                 want_state=True, workspace=None):
+    """Chunkwise forward scan with the DDTS gate front-end fused in: raw q, k and the pre-activations z_g, z_tau
+    [B,T,H,dk], z_beta [B,T,H,dv] or None (all in q's dtype).  Returns (o, S_T)."""
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_chunk_scan_fwd_gated needs device tensors (no CPU path exists)")
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    dev, io = q.device, q.dtype
+    for name, t in (("q", q), ("k", k), ("z_g", z_g), ("z_tau", z_tau)):
+        if t is None:
+            raise ValueError(f"{name} is required")
+        _require(t, name, (B, T, H, dk), io, dev)
+    _require(v, "v", (B, T, H, dv), io, dev)
+    _require(z_beta, "z_beta", (B, T, H, dv), io, dev)
+    _require(S0, "S0", (B, H, dk, dv), torch.float32, dev)
+    if o is None:
+        o = torch.empty((B, T, H, dv), dtype=io, device=dev)
+    _require(o, "o", (B, T, H, dv), io, dev)
+    if S_T is None and want_state:
+        S_T = torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev)
+    _require(S_T, "S_T", (B, H, dk, dv), torch.float32, dev)
+    need = rodimus_chunk_scan_workspace_bytes(B, T, H, dk, dv, chunk, io)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_chunk_scan_fwd_gated(_ptr(q), _ptr(k), _ptr(v), _ptr(z_g), _ptr(z_tau), _ptr(z_beta), _ptr(S0),
+                                                  _ptr(o), _ptr(S_T), B, T, H, dk, dv, int(chunk), _DTYPES[io],
+                                                  _ptr(workspace), ws_bytes, _stream(dev)))
+    return o, S_T
+
+
+def rodimus_decode_step_gated(q, k, v, z_g, z_tau, z_beta, S, *, o=None):
+    """One recurrent step with the gate front-end fused in.  q, k, z_g, z_tau [N,H,dk]; v, z_beta (or None) [N,H,dv];
+    S [N,H,dk,dv] fp32, updated in place.  Returns o [N,H,dv]."""
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_decode_step_gated needs device tensors (no CPU path exists)")
+    N, H, dk = q.shape
+    dv = v.shape[-1]
+    dev, io = q.device, q.dtype
+    for name, t in (("q", q), ("k", k), ("z_g", z_g), ("z_tau", z_tau)):
+        if t is None:
+            raise ValueError(f"{name} is required")
+        _require(t, name, (N, H, dk), io, dev)
+    _require(v, "v", (N, H, dv), io, dev)
+    _require(z_beta, "z_beta", (N, H, dv), io, dev)
+    _require(S, "S", (N, H, dk, dv), torch.float32, dev)
+    if o is None:
+        o = torch.empty((N, H, dv), dtype=io, device=dev)
+    _require(o, "o", (N, H, dv), io, dev)
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_decode_step_gated(_ptr(q), _ptr(k), _ptr(v), _ptr(z_g), _ptr(z_tau), _ptr(z_beta), _ptr(S), _ptr(o),
+                                               N, H, dk, dv, _DTYPES[io], _stream(dev)))
+    return o
 
 
 _GATE_ACTS = {"sigmoid": 0, "silu": 1}

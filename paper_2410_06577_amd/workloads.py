@@ -200,3 +200,14 @@ def make_short_conv_inputs(B: int, T: int, C: int, W: int = 4, io_dtype: str = "
     w = rng.uniform(-bound, bound, size=(C, W)).astype(f32)
     bias = rng.uniform(-bound, bound, size=(C,)).astype(f32)
     return {"x": _io(x, io_dtype), "state": _io(state, io_dtype), "w": torch.from_numpy(w), "bias": torch.from_numpy(bias)}
+
+
+def make_gated_scan_inputs(B: int, T: int, H: int, dk: int, dv: int, io_dtype: str = "bf16", s0_std: float = 0.1,
+                           seed: int = 16) -> dict:
+    """Inputs of the scan that takes the gates as pre-activations: ``make_ddts_preactivations`` over [B,T,H] plus the
+    value v ~ N(0,1) [B,T,H,dv] (I/O dtype) and the initial state S0 ~ N(0, s0_std) fp32 (None when s0_std == 0)."""
+    d = make_ddts_preactivations((B, T, H), dk, dv, io_dtype, seed)
+    rng = np.random.Generator(np.random.PCG64(seed + 1000))
+    d["v"] = _io(rng.standard_normal((B, T, H, dv), dtype=np.float32), io_dtype)
+    d["S0"] = torch.from_numpy((rng.standard_normal((B, H, dk, dv), dtype=np.float32) * np.float32(s0_std))) if s0_std > 0 else None
+    return d

@@ -29,7 +29,8 @@ def test_every_declared_symbol_is_exported(L):
             "rodimus_chunk_scan_fwd_zbeta", "rodimus_decode_step_zbeta", "rodimus_chunk_scan_varlen_fwd",
             "rodimus_chunk_scan_bwd", "rodimus_chunk_scan_bwd_workspace_bytes",
             "rodimus_chunk_scan_fwd_block", "rodimus_decode_step_block",
-            "rodimus_short_conv_fwd", "rodimus_short_conv_step"} <= declared
+            "rodimus_short_conv_fwd", "rodimus_short_conv_step",
+            "rodimus_chunk_scan_fwd_gated", "rodimus_decode_step_gated"} <= declared
     for name in declared:
         assert hasattr(L, name), name
 
@@ -189,6 +190,38 @@ def test_backward_validation(L):
     assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 64, 128, rodimus.BF16) == (2 * 2 * 100 * 3 * 64 + 2 * 3 * 64) * 4
     assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 32, 128, rodimus.BF16) == 0
     assert call(B=0) == OK
+
+
+def test_gated_calls_validation(L):
+    p = ctypes.c_void_p
+    f = lambda x: None if x is None else p(x)
+
+    def scan(q=0x10000, k=0x20000, v=0x30000, zg=0x40000, zt=0x48000, zb=0x50000, S0=0x60000, o=0x70000, S_T=0x80000,
+             B=1, T=4, H=1, dk=16, dv=32, chunk=4, io=rodimus.F32, ws=None, ws_bytes=0):
+        return L.rodimus_chunk_scan_fwd_gated(f(q), f(k), f(v), f(zg), f(zt), f(zb), f(S0), f(o), f(S_T), B, T, H, dk, dv,
+                                              chunk, io, f(ws), ws_bytes, None)
+
+    def dec(q=0x10000, k=0x20000, v=0x30000, zg=0x40000, zt=0x48000, zb=0x50000, S=0x100000, o=0x70000, N=2, H=2, dk=16,
+            dv=32, io=rodimus.BF16):
+        return L.rodimus_decode_step_gated(f(q), f(k), f(v), f(zg), f(zt), f(zb), f(S), f(o), N, H, dk, dv, io, None)
+
+    assert scan(io=5) == E_DTYPE and dec(io=-1) == E_DTYPE
+    assert scan(dk=0) == E_SHAPE and scan(chunk=0) == E_SHAPE and dec(dv=6) == E_SHAPE
+    for name in ("q", "k", "v", "zg", "zt", "o"):
+        assert scan(**{name: None}) == E_NULL, name
+        assert dec(**{name: None}) == E_NULL, name
+    assert dec(S=None) == E_NULL
+    for name, val in (("zg", 0x40008), ("zt", 0x48004), ("zb", 0x50002)):
+        assert scan(**{name: val}) == E_ALIGN, name
+        assert dec(**{name: val}) == E_ALIGN, name
+    assert scan(o=0x40000) == E_ALIAS and scan(o=0x48000) == E_ALIAS and scan(S_T=0x48000) == E_ALIAS
+    assert dec(o=0x48000) == E_ALIAS and dec(S=0x40000) == E_ALIAS
+    # the MFMA shapes need their workspace in this form as well
+    need = L.rodimus_chunk_scan_workspace_bytes(1, 32768, 16, 64, 256, 64, rodimus.BF16)
+    assert need > 0
+    assert scan(B=1, T=32768, H=16, dk=64, dv=256, chunk=64, io=rodimus.BF16, q=0x10000000, k=0x20000000, v=0x30000000,
+                zg=0x40000000, zt=0x50000000, zb=0x60000000, S0=None, o=0x80000000, S_T=None) == E_WS
+    assert scan(B=0) == OK and dec(N=0) == OK and scan(T=0, S_T=None) == OK
 
 
 def test_short_conv_validation(L):
