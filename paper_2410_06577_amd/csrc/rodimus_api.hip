@@ -250,6 +250,7 @@ int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v, const fl
 {
     if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
     if (B < 0 || T < 0 || H < 0 || (long long)B * H > kMaxGridX) return RODIMUS_ERR_SHAPE;
+    if ((long long)T * H > kMaxGridX) return RODIMUS_ERR_SHAPE;          // the kernels index a sequence's rows in 32 bits
     if (!scan_bwd_supports(dk_width, dv, io_dtype)) return RODIMUS_ERR_SHAPE;
     const size_t tokens = (size_t)B * T * H, states = (size_t)B * H;
     if (tokens > 0 && (!q || !k || !v || !log_alpha || !d_o || !dq || !dk || !dv_out || !dlog_alpha)) return RODIMUS_ERR_NULL;

@@ -32,7 +32,12 @@ namespace {
 
 constexpr int kK = 64;
 constexpr int kTile = 16;
-constexpr int kBwdThreads = 256;
+// One wavefront of the reverse sweep per 32 value columns: 4 wavefronts (dv = 128) or 8 (dv = 256) per workgroup; the
+// forward sweep computes with 4 wavefronts and uses the others only to fetch and stage the tile inputs.
+template <int DV> struct BwdShape {
+    static constexpr int kWaves = DV / 32;
+    static constexpr int kThreads = 64 * kWaves;
+};
 constexpr float kMinLogAlpha = -128.f;
 constexpr float kSafeTileLog = -55.f;      // ln(2^-80) = -55.45: above it 1 / A_i stays below 2^80
 
@@ -56,42 +61,54 @@ __device__ __forceinline__ void split_bf16(float x, float &hi, float &lo)
 template <int DV> struct BwdLayout {
     static constexpr int kRowBytes = DV * 2 + 16;                 // padded token row of bf16 values (bank spread)
     static constexpr int kPieces = DV / 8;                        // 16-byte pieces per token row
-    static constexpr int kPerThread = kTile * kPieces / kBwdThreads;   // (token, piece) pairs per thread: 1 or 2
+    static constexpr int kPerThread = kTile * kPieces / BwdShape<DV>::kThreads;   // (token, piece) pairs per thread: 1
+    static_assert(kPerThread == 1, "one 16-byte piece of v, do (and beta) per thread");
 };
 
 // One thread's share of a tile's global inputs, requested one tile ahead.
 template <int DV> struct TileLoads {
     uint4 qk;                                          // threads 0..127: q piece, 128..255: k piece
-    floatx4_t la;
+    floatx4_t la;                                      // dv = 128: every thread; dv = 256: threads 256..511
     uint4 v[BwdLayout<DV>::kPerThread], d_o[BwdLayout<DV>::kPerThread];
     floatx4_t beta[BwdLayout<DV>::kPerThread][2];
 };
 
+// Input pointers of one (batch, head), already advanced to its first token and its head: token t of the sequence is at
+// element offset t * H * width.  t * H fits 32 bits; the byte offset is formed in 64 bits.
 struct BwdGeometry {
     const bf16_t *q, *k, *v, *d_o;
     const float *la, *beta;
-    size_t tok0;      // row of the sequence's first token
-    int T, H, h;
+    int T, H;
+    __device__ BwdGeometry(const bf16_t *q_, const bf16_t *k_, const bf16_t *v_, const bf16_t *do_, const float *la_,
+                           const float *beta_, int b, int h, int T_, int H_, int dv)
+        : T(T_), H(H_)
+    {
+        const size_t row0 = ((size_t)b * T_) * H_ + h;
+        q = q_ + row0 * kK; k = k_ + row0 * kK; la = la_ + row0 * kK;
+        v = v_ + row0 * dv; d_o = do_ + row0 * dv;
+        beta = beta_ != nullptr ? beta_ + row0 * dv : nullptr;
+    }
+    // token index (clamped to the sequence) times H
+    __device__ __forceinline__ unsigned row(int t) const { return (unsigned)min(t, T - 1) * (unsigned)H; }
 };
 
 template <int DV>
 __device__ __forceinline__ void tile_prefetch(const BwdGeometry &g, int t0, int tid, bool has_beta, TileLoads<DV> &p)
 {
     using L = BwdLayout<DV>;
-    {
+    constexpr bool kWide = BwdShape<DV>::kThreads == 512;      // the log_alpha pieces then go to the upper 256 threads
+    if (tid < 256) {
         const int tok = (tid & 127) >> 3, piece = tid & 7;
-        const size_t row = (g.tok0 + min(t0 + tok, g.T - 1)) * g.H + g.h;
-        p.qk = *reinterpret_cast<const uint4 *>((tid < 128 ? g.q : g.k) + row * kK + 8 * piece);
+        p.qk = *reinterpret_cast<const uint4 *>((tid < 128 ? g.q : g.k) + (size_t)g.row(t0 + tok) * kK + 8 * piece);
     }
-    {
-        const int tok = tid >> 4, piece = tid & 15;
-        const size_t row = (g.tok0 + min(t0 + tok, g.T - 1)) * g.H + g.h;
-        p.la = *reinterpret_cast<const floatx4_t *>(g.la + row * kK + 4 * piece);
+    if (!kWide || tid >= 256) {
+        const int tok = (tid & 255) >> 4, piece = tid & 15;
+        p.la = *reinterpret_cast<const floatx4_t *>(g.la + (size_t)g.row(t0 + tok) * kK + 4 * piece);
     }
 #pragma unroll
     for (int u = 0; u < L::kPerThread; ++u) {
-        const int id = tid + u * kBwdThreads, tok = id / L::kPieces, piece = id % L::kPieces;
-        const size_t off = ((g.tok0 + min(t0 + tok, g.T - 1)) * g.H + g.h) * DV + 8 * piece;
+        const int id = tid, tok = id / L::kPieces, piece = id % L::kPieces;
+        const size_t off = (size_t)g.row(t0 + tok) * DV + 8 * piece;
         p.v[u] = *reinterpret_cast<const uint4 *>(g.v + off);
         p.d_o[u] = *reinterpret_cast<const uint4 *>(g.d_o + off);
         if (has_beta) {
@@ -114,7 +131,8 @@ __device__ __forceinline__ void tile_stage(const TileLoads<DV> &p, int t0, int T
                                            float *ls, unsigned char *us, unsigned char *ds)
 {
     using L = BwdLayout<DV>;
-    {
+    constexpr bool kWide = BwdShape<DV>::kThreads == 512;
+    if (tid < 256) {
         const int tok = (tid & 127) >> 3, piece = tid & 7;
         const bool valid = t0 + tok < T;
         float x[8];
@@ -123,15 +141,15 @@ __device__ __forceinline__ void tile_stage(const TileLoads<DV> &p, int t0, int T
 #pragma unroll
         for (int e = 0; e < 8; ++e) dst[e] = valid ? x[e] : 0.f;
     }
-    {
-        const int tok = tid >> 4, piece = tid & 15;
+    if (!kWide || tid >= 256) {
+        const int tok = (tid & 255) >> 4, piece = tid & 15;
         const bool valid = t0 + tok < T;
 #pragma unroll
         for (int e = 0; e < 4; ++e) ls[tok * kK + 4 * piece + e] = valid ? fmaxf(p.la[e], kMinLogAlpha) : 0.f;
     }
 #pragma unroll
     for (int u = 0; u < L::kPerThread; ++u) {
-        const int id = tid + u * kBwdThreads, tok = id / L::kPieces, piece = id % L::kPieces;
+        const int id = tid, tok = id / L::kPieces, piece = id % L::kPieces;
         const bool valid = t0 + tok < T;
         float x[8], d[8];
         unpack8(p.v[u], x);
@@ -169,25 +187,31 @@ __device__ __forceinline__ void sweep_dq(
 {
     using L = BwdLayout<DV>;
     constexpr int kColTiles = DV / 16, kSteps = DV / 32;
-    __shared__ __align__(16) float qs[kTile * kK], ks[kTile * kK], ls[kTile * kK];
-    __shared__ __align__(16) unsigned char us[kTile * L::kRowBytes], ds[kTile * L::kRowBytes];
-    __shared__ __align__(16) float dPw[4][kTile][kTile];
-    __shared__ __align__(16) float qdq_s[kTile * kK];
-    __shared__ __align__(16) bf16_t dq_s[kTile * kK];
+    // LDS (the workgroup's dynamic allocation, sized for the reverse sweep): tile inputs, then this sweep's buffers
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    float *qs = reinterpret_cast<float *>(lds_raw), *ks = qs + kTile * kK, *ls = ks + kTile * kK;
+    unsigned char *us = reinterpret_cast<unsigned char *>(ls + kTile * kK), *ds = us + kTile * L::kRowBytes;
+    float (*dPw)[kTile][kTile] = reinterpret_cast<float (*)[kTile][kTile]>(ds + kTile * L::kRowBytes);     // [4][16][16]
+    float *qdq_s = reinterpret_cast<float *>(dPw + 4);
+    bf16_t *dq_s = reinterpret_cast<bf16_t *>(qdq_s + kTile * kK);
 
+    // wavefronts 0..3 compute (16 key channels each); any further wavefronts of the workgroup only fetch and stage
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool computes = wave < 4;
     const int c = lane & 15, tg = lane >> 4;          // vector-ALU role: channel 16*wave + c, tokens 4tg .. 4tg+3
-    const int ch = 16 * wave + c;
+    const int ch = 16 * (wave & 3) + c;
     const int bh = blockIdx.x;
     const bool has_beta = beta != nullptr;
-    BwdGeometry g{q, k, v, d_o, log_alpha, beta, (size_t)(bh / H) * T, T, H, bh % H};
+    const BwdGeometry g(q, k, v, d_o, log_alpha, beta, bh / H, bh % H, T, H, DV);
+    const size_t row0 = ((size_t)(bh / H) * T) * H + bh % H;      // outputs: same layout as the inputs
 
     // state slab, transposed: acc[ct][r] = S[ch][16ct + 4tg + r]
     floatx4_t acc[kColTiles];
     const size_t state_base = (size_t)bh * kK * DV + (size_t)ch * DV;
 #pragma unroll
     for (int ct = 0; ct < kColTiles; ++ct)
-        acc[ct] = S0 != nullptr ? *reinterpret_cast<const floatx4_t *>(S0 + state_base + 16 * ct + 4 * tg) : floatx4_t{0.f, 0.f, 0.f, 0.f};
+        acc[ct] = (S0 != nullptr && computes) ? *reinterpret_cast<const floatx4_t *>(S0 + state_base + 16 * ct + 4 * tg)
+                                              : floatx4_t{0.f, 0.f, 0.f, 0.f};
 
     const int ntiles = (T + kTile - 1) / kTile;
     TileLoads<DV> pf;
@@ -196,8 +220,8 @@ __device__ __forceinline__ void sweep_dq(
     // coalesced stores of a finished tile's dq (bf16) and q .* dq (fp32) from the staging buffers
     auto store_tile = [&](int t0) {
         const int tok = tid >> 4, piece = tid & 15;
-        if (t0 + tok < T) {
-            const size_t row = (g.tok0 + t0 + tok) * H + g.h;
+        if (tid < 256 && t0 + tok < T) {
+            const size_t row = row0 + (size_t)((unsigned)(t0 + tok) * (unsigned)H);
             *reinterpret_cast<floatx4_t *>(qdq + row * kK + 4 * piece) = *reinterpret_cast<const floatx4_t *>(qdq_s + tok * kK + 4 * piece);
             if (piece < 8)
                 *reinterpret_cast<uint4 *>(dq + row * kK + 8 * piece) = *reinterpret_cast<const uint4 *>(dq_s + tok * kK + 8 * piece);
@@ -211,6 +235,7 @@ __device__ __forceinline__ void sweep_dq(
         tile_stage<DV>(pf, t0, T, tid, has_beta, qs, ks, ls, us, ds);
         tile_prefetch<DV>(g, t0 + kTile, tid, has_beta, pf);        // clamped addresses; masked when staged
         __syncthreads();
+        if (!computes) continue;          // wavefront-uniform; the two barriers above are reached by every wavefront
 
         // ---- this lane's channel: running sums of log_alpha, keys
         float lsum[kTile], kk[kTile];
@@ -324,6 +349,7 @@ __device__ __forceinline__ void sweep_dq(
     if (ntiles > 0) store_tile((ntiles - 1) * kTile);
 
     // rowsum(S_T .* dS_T) for this lane's channel: constant term of every gate cotangent of this (batch, head)
+    if (!computes) return;
     float part = 0.f;
     if (dS_T != nullptr) {
 #pragma unroll
@@ -341,12 +367,13 @@ __device__ __forceinline__ void sweep_dq(
 // =========================================================================================================
 // Reverse sweep: dk, dv, dbeta, dlog_alpha, dS0
 // =========================================================================================================
-// One workgroup per (batch, head); wavefront w owns DV/4 value columns: its slab of the state cotangent G lives in MFMA
+// One workgroup per (batch, head); wavefront w owns 32 value columns: its slab of the state cotangent G lives in MFMA
 // accumulators (lane = column, registers = key channels), as the state does in the forward kernel.  Per tile, last to
 // first:  du^T = G^T khat^T + do^T P   (khat_i = k_i .* exp(l_16 - l_i));  partial u G^T over the slab's columns, summed
-// over the four wavefronts through LDS;  G <- diag(A_16) G + (q .* A)^T do.
+// over the wavefronts through LDS;  G <- diag(A_16) G + (q .* A)^T do.
 template <int DV> struct DkvLds {       // byte offsets of the reverse kernel's dynamic LDS
-    static constexpr int kSlabCols = DV / 4;
+    static constexpr int kWaves = BwdShape<DV>::kWaves;
+    static constexpr int kSlabCols = 32;
     static constexpr int kQs = 0;
     static constexpr int kKs = kQs + kTile * kK * 4;
     static constexpr int kLs = kKs + kTile * kK * 4;
@@ -357,15 +384,16 @@ template <int DV> struct DkvLds {       // byte offsets of the reverse kernel's 
     static constexpr int kPt = kKh + kTile * (kK + 8) * 2;
     static constexpr int kDp = kPt + kTile * kTile * 2;
     static constexpr int kGt = kDp + ((kTile * (kTile + 1) * 4 + 15) / 16) * 16;
-    static constexpr int kRed = kGt + 4 * kSlabCols * (kK + 8) * 2;
-    static constexpr int kDu = kRed + 4 * kTile * kK * 4;
+    static constexpr int kRed = kGt + kWaves * kSlabCols * (kK + 8) * 2;
+    static constexpr int kDu = kRed + kWaves * kTile * kK * 4;
     static constexpr int kKq = kDu + kTile * (DV + 4) * 4;             // k ./ A, token-major, padded rows
     static constexpr int kIntra = kKq + kTile * (kK + 8) * 2;          // (dP^T (q .* A))[i][channel]
     static constexpr int kQaLo = kIntra + kTile * kK * 4;              // low part of q .* A (split bf16), token-major, padded rows
     static constexpr int kLt = kQaLo + kTile * (kK + 8) * 2;           // running sums l_t, fp32 [16][64]
     static constexpr int kA16 = kLt + kTile * kK * 4;                  // A_16 per channel, fp32 [64]
     static constexpr int kFlag = kA16 + kK * 4;
-    static constexpr int kBytes = kFlag + 16;
+    static constexpr int kDpPart = kFlag + 16;                         // partial dP per wavefront, fp32 [kWaves][i][t]
+    static constexpr int kBytes = kDpPart + kWaves * kTile * kTile * 4;
 };
 
 template <int DV>
@@ -376,8 +404,10 @@ __device__ __forceinline__ void sweep_dkv(
     float *__restrict__ dbeta, float *__restrict__ dS0, int T, int H)
 {
     using L = BwdLayout<DV>;
-    constexpr int kSlab = DV / 4;                    // columns per wavefront
-    constexpr int kCt = kSlab / 16;                  // column tiles per wavefront: 4 (dv = 256) or 2 (dv = 128)
+    constexpr int kWaves = BwdShape<DV>::kWaves;     // 4 (dv = 128) or 8 (dv = 256)
+    constexpr int kSlab = 32;                        // columns per wavefront
+    constexpr int kCt = kSlab / 16;                  // column tiles per wavefront
+    constexpr int kTok = kTile / kWaves;             // tokens per thread in the vector-ALU phases: 4 or 2
     constexpr int kDuRow = DV + 4;                   // padded fp32 row of du
     using M = DkvLds<DV>;
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -391,18 +421,20 @@ __device__ __forceinline__ void sweep_dkv(
     bf16_t *pt_s = reinterpret_cast<bf16_t *>(lds_raw + M::kPt);             // P^T: [i][t]
     float *dp_s = reinterpret_cast<float *>(lds_raw + M::kDp);               // dP: [t][i], padded rows
     bf16_t *gt_s = reinterpret_cast<bf16_t *>(lds_raw + M::kGt) + (size_t)(threadIdx.x >> 6) * kSlab * (kK + 8);   // this wavefront's G slab as [column][channel]
-    float *red_s = reinterpret_cast<float *>(lds_raw + M::kRed);             // [4][16][64] partial u G^T per wavefront
+    float *red_s = reinterpret_cast<float *>(lds_raw + M::kRed);             // [kWaves][16][64] partial u G^T per wavefront
     float *du_s = reinterpret_cast<float *>(lds_raw + M::kDu);
     bf16_t *kq_s = reinterpret_cast<bf16_t *>(lds_raw + M::kKq);
     float *intra_s = reinterpret_cast<float *>(lds_raw + M::kIntra);
     bf16_t *qa_lo_s = reinterpret_cast<bf16_t *>(lds_raw + M::kQaLo);
     int *flag_s = reinterpret_cast<int *>(lds_raw + M::kFlag);               // != 0: this tile takes the pairwise route
+    float *dpp_s = reinterpret_cast<float *>(lds_raw + M::kDpPart);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, grp = lane >> 4;
     const int bh = blockIdx.x;
     const bool has_beta = beta != nullptr;
-    BwdGeometry g{q, k, v, d_o, log_alpha, beta, (size_t)(bh / H) * T, T, H, bh % H};
+    const BwdGeometry g(q, k, v, d_o, log_alpha, beta, bh / H, bh % H, T, H, DV);
+    const size_t row0 = ((size_t)(bh / H) * T) * H + bh % H;      // outputs: same layout as the inputs
     const int col0 = wave * kSlab;
 
     // cotangent slab: acc[kt][ct][r] = G[16kt + 4grp + r][col0 + 16ct + n]
@@ -416,8 +448,8 @@ __device__ __forceinline__ void sweep_dkv(
             for (int r = 0; r < 4; ++r)
                 acc[kt][ct][r] = dS_T != nullptr ? dS_T[state_base + (size_t)(16 * kt + 4 * grp + r) * DV + col0 + 16 * ct + n] : 0.f;
 
-    // vector-ALU role of the gate and dk phases: channel vc, tokens 4vg .. 4vg+3
-    const int vc = tid & 63, vg = tid >> 6;
+    // vector-ALU role of the gate and dk phases: channel vc, tokens kTok * vg .. + kTok - 1
+    const int vc = tid & 63, vg = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     const int ntiles = (T + kTile - 1) / kTile;
     TileLoads<DV> pf;
@@ -454,11 +486,11 @@ __device__ __forceinline__ void sweep_dkv(
         if (lsum[kTile - 1] < kSafeTileLog) *flag_s = 1;
         if (vg == 0) a16_s[vc] = __expf(lsum[kTile - 1]);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < kTok; ++r) {
             float l_own = lsum[r];
 #pragma unroll
-            for (int gsel = 1; gsel < 4; ++gsel) l_own = (vg == gsel) ? lsum[4 * gsel + r] : l_own;
-            const int t = 4 * vg + r;
+            for (int gsel = 1; gsel < kWaves; ++gsel) l_own = (vg == gsel) ? lsum[kTok * gsel + r] : l_own;
+            const int t = kTok * vg + r;
             lt_s[t * kK + vc] = l_own;
             float qa_hi, qa_lo;
             split_bf16(qs[t * kK + vc] * __expf(l_own), qa_hi, qa_lo);
@@ -476,19 +508,22 @@ __device__ __forceinline__ void sweep_dkv(
                 const uint2 w = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3])};
                 *reinterpret_cast<uint2 *>(&gt_s[(16 * ct + n) * (kK + 8) + 16 * kt + 4 * grp]) = w;
             }
+        // this wavefront's share of dP[t][i] = do_t . u_i: the 32 columns of its slab; summed over the wavefronts after the barrier
+        {
+            const bf16x8_t a_do = *reinterpret_cast<const bf16x8_t *>(ds + n * L::kRowBytes + (col0 + 8 * grp) * 2);
+            const bf16x8_t b_u = *reinterpret_cast<const bf16x8_t *>(us + n * L::kRowBytes + (col0 + 8 * grp) * 2);
+            const floatx4_t d = mfma_k32(a_do, b_u, floatx4_t{0.f, 0.f, 0.f, 0.f});
+            *reinterpret_cast<floatx4_t *>(&dpp_s[(wave * kTile + n) * kTile + 4 * grp]) = d;      // [wave][i = n][t = 4grp ..]
+        }
         __syncthreads();                                   // (3)
 
-        // ---- MFMA phase.  dP[t][i] = do_t . u_i (i <= t) by every wavefront for itself: lane (i = n, group grp) holds
+        // ---- MFMA phase.  dP[t][i] = do_t . u_i (i <= t), the sum of the wavefronts' shares: lane (i = n, group grp) holds
         // t = 4grp + r, which is the operand layout of both later uses.
         const bool pairwise = *flag_s != 0;
         const int j = n >> 2, cc = n & 3;                  // transposing reads: this lane addresses row 4grp + j, unit cc
         floatx4_t dp = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int s = 0; s < DV / 32; ++s) {
-            const bf16x8_t a_do = *reinterpret_cast<const bf16x8_t *>(ds + n * L::kRowBytes + (32 * s + 8 * grp) * 2);
-            const bf16x8_t b_u = *reinterpret_cast<const bf16x8_t *>(us + n * L::kRowBytes + (32 * s + 8 * grp) * 2);
-            dp = mfma_k32(a_do, b_u, dp);
-        }
+        for (int w = 0; w < kWaves; ++w) dp += *reinterpret_cast<const floatx4_t *>(&dpp_s[(w * kTile + n) * kTile + 4 * grp]);
 #pragma unroll
         for (int r = 0; r < 4; ++r) dp[r] = (n <= 4 * grp + r) ? dp[r] : 0.f;
         // P[t][i] in the same layout (B operand of do^T P)
@@ -505,15 +540,15 @@ __device__ __forceinline__ void sweep_dkv(
                         pack_bf16x2(n <= 4 * grp + 2 ? d[2] : 0.f, n <= 4 * grp + 3 ? d[3] : 0.f)};
         } else {
             // pair by pair on the vector ALUs (thread = (t, i), fp32), through LDS; dP for the dk phase as well
-            const int t = tid >> 4, i = tid & 15;
+            const int t = (tid & 255) >> 4, i = tid & 15;
             float p = 0.f;
-            if (i <= t) {
+            if (tid < 256 && i <= t) {
                 for (int cr = 0; cr < kK; ++cr) {
                     const int c = (cr + i) & (kK - 1);     // rotated per key row: the 16 rows of a wavefront hit 16 different banks
                     p = fmaf(qs[t * kK + c] * ks[i * kK + c], __expf(lt_s[t * kK + c] - lt_s[i * kK + c]), p);
                 }
             }
-            pt_s[i * kTile + t] = (bf16_t)p;
+            if (tid < 256) pt_s[i * kTile + t] = (bf16_t)p;
             if (wave == 0) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) dp_s[(4 * grp + r) * (kTile + 1) + n] = dp[r];
@@ -587,8 +622,8 @@ __device__ __forceinline__ void sweep_dkv(
                 a_q[kt] = lds_read_transposed(reinterpret_cast<const unsigned char *>(&qa_s[(4 * grp + j) * (kK + 8) + 16 * kt + 4 * cc]));
                 dec[kt] = *reinterpret_cast<const floatx4_t *>(&a16_s[16 * kt + 4 * grp]);
             }
-            if (!pairwise) {
-                // (dP^T (q .* A))[i][channel], channel tile = wavefront; split-bf16 operands
+            if (!pairwise && wave < 4) {
+                // (dP^T (q .* A))[i][channel], channel tile = wavefront (the first four); split-bf16 operands
                 float hi[4], lo[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) split_bf16(dp[r], hi[r], lo[r]);
@@ -621,13 +656,14 @@ __device__ __forceinline__ void sweep_dkv(
         // ---- dk, and k .* dk in fp32 for the gate cotangent (thread = channel vc, tokens 4vg .. 4vg+3)
         {
 #pragma unroll
-            for (int r = 3; r >= 0; --r) {
-                const int i = 4 * vg + r;
+            for (int r = kTok - 1; r >= 0; --r) {
+                const int i = kTok * vg + r;
                 float l_i = lsum[r];
 #pragma unroll
-                for (int gsel = 1; gsel < 4; ++gsel) l_i = (vg == gsel) ? lsum[4 * gsel + r] : l_i;
-                float khat_term = red_s[i * kK + vc] + red_s[kTile * kK + i * kK + vc] + red_s[2 * kTile * kK + i * kK + vc] +
-                                  red_s[3 * kTile * kK + i * kK + vc];
+                for (int gsel = 1; gsel < kWaves; ++gsel) l_i = (vg == gsel) ? lsum[kTok * gsel + r] : l_i;
+                float khat_term = 0.f;
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) khat_term += red_s[w * kTile * kK + i * kK + vc];
                 khat_term *= __expf(lsum[kTile - 1] - l_i);
                 float intra = 0.f;
                 if (pairwise) {
@@ -641,7 +677,7 @@ __device__ __forceinline__ void sweep_dkv(
                 }
                 const float dk_val = khat_term + intra;
                 if (t0 + i < T) {                           // a wavefront writes whole rows
-                    const size_t e = ((g.tok0 + t0 + i) * H + g.h) * kK + vc;
+                    const size_t e = (row0 + (size_t)((unsigned)(t0 + i) * (unsigned)H)) * kK + vc;
                     dk[e] = (bf16_t)dk_val;
                     kdk[e] = ks[i * kK + vc] * dk_val;
                 }
@@ -650,9 +686,9 @@ __device__ __forceinline__ void sweep_dkv(
         // dv = beta .* du, dbeta = v .* du: coalesced, by the thread that loaded the same pieces of v and beta
 #pragma unroll
         for (int u = 0; u < L::kPerThread; ++u) {
-            const int id = tid + u * kBwdThreads, tok = id / L::kPieces, piece = id % L::kPieces;
+            const int id = tid, tok = id / L::kPieces, piece = id % L::kPieces;
             if (t0 + tok < T) {
-                const size_t off = ((g.tok0 + t0 + tok) * H + g.h) * DV + 8 * piece;
+                const size_t off = (row0 + (size_t)((unsigned)(t0 + tok) * (unsigned)H)) * DV + 8 * piece;
                 const floatx4_t d0 = *reinterpret_cast<const floatx4_t *>(&du_s[tok * kDuRow + 8 * piece]);
                 const floatx4_t d1 = *reinterpret_cast<const floatx4_t *>(&du_s[tok * kDuRow + 8 * piece + 4]);
                 float x[8];
@@ -699,7 +735,7 @@ namespace {
 // Both sweeps in one launch: blockIdx.y = 0 runs the forward sweep of (batch, head) blockIdx.x, blockIdx.y = 1 the
 // reverse sweep.  They share nothing, so with B * H workgroups each they occupy twice as many compute units.
 template <int DV>
-__global__ __launch_bounds__(kBwdThreads) void scan_bwd_sweeps_kernel(
+__global__ __launch_bounds__(BwdShape<DV>::kThreads) void scan_bwd_sweeps_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const float *__restrict__ log_alpha, const float *__restrict__ beta, const float *__restrict__ S0,
     const bf16_t *__restrict__ d_o, const float *__restrict__ dS_T, bf16_t *__restrict__ dq, bf16_t *__restrict__ dk,
@@ -757,7 +793,7 @@ hipError_t launch_scan_bwd_typed(const ScanBwdArgs &a)
     hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_bwd_sweeps_kernel<DV>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, DkvLds<DV>::kBytes);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL(scan_bwd_sweeps_kernel<DV>, dim3(bh, 2), dim3(kBwdThreads), DkvLds<DV>::kBytes, a.stream,
+    hipLaunchKernelGGL(scan_bwd_sweeps_kernel<DV>, dim3(bh, 2), dim3(BwdShape<DV>::kThreads), DkvLds<DV>::kBytes, a.stream,
                        (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0,
                        (const bf16_t *)a.d_o, a.dS_T, (bf16_t *)a.dq, (bf16_t *)a.dk, (bf16_t *)a.dv, a.dbeta, a.dS0, qdq, kdk,
                        gate_const, a.T, a.H);

@@ -75,6 +75,18 @@ def test_strong_decay_and_closed_gates():
     assert float(out["dlog_alpha"][:, 7::31].abs().max()) == 0.0
 
 
+def test_strong_decay_wide_values():
+    """The same routes with dv = 256 (eight wavefronts per workgroup in the reverse sweep)."""
+    inp = _case(1, 100, 2, 256, seed=19)
+    la = inp["log_alpha"]
+    la[:, 20:30, :, 5:40] = -25.0
+    la[:, 60:70] = 0.0
+    la[:, 3::17] = float("-inf")
+    print("bwd strong decay dv256", flush=True)
+    out, ref = _check(inp, "strong decay dv256")
+    assert float(out["dlog_alpha"][:, 3::17].abs().max()) == 0.0
+
+
 def test_long_sequence_mid_config():
     """Half of the mid configuration (B=2, T=2048, H=8, dv=128): 128 tiles of carried state and cotangent."""
     print("bwd mid-size", flush=True)
