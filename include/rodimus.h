@@ -258,13 +258,16 @@ int rodimus_decode_step_block(const void *q, const void *k, const void *v,
  *   dlog_alpha  [B,T,H,dk] fp32          out   (0 where log_alpha <= -128: such a gate is treated as closed)
  *   dbeta       [B,T,H,dv] fp32          out, or NULL if not wanted (v .* (k G) is written even when beta is NULL)
  *   dS0         [B,H,dk,dv] fp32         out, or NULL if not wanted
- *   workspace   rodimus_chunk_scan_bwd_workspace_bytes(...) bytes of device scratch (q .* dq and k .* dk in fp32),
- *               16-byte aligned
+ *   workspace   rodimus_chunk_scan_bwd_workspace_bytes(...) bytes of device scratch (q .* dq, and on the MFMA path k .* dk,
+ *               in fp32), 16-byte aligned
  *
- * No output may overlap an input, another output or the workspace.  Supported: io_dtype = BF16, dk = 64,
- * dv = 128 or 256, any T (a 16-token tile is the internal chunk); other shapes return RODIMUS_ERR_SHAPE.  bf16 MFMA
- * operands, fp32 accumulation and fp32 gate arithmetic; a forward sweep for dq and a reverse sweep for dk, dv, dbeta, dS0 run
- * side by side in one launch (one workgroup per (batch, head) each), a second launch forms dlog_alpha.
+ * No output may overlap an input, another output or the workspace.  Two kernel families:
+ *   io_dtype = BF16, dk = 64, dv = 128 or 256, any T: bf16 MFMA operands, fp32 accumulation and fp32 gate arithmetic, a
+ *     16-token tile as the internal chunk; a forward sweep for dq and a reverse sweep for dk, dv, dbeta, dS0 run side by
+ *     side in one launch (one workgroup per (batch, head) each), a second launch forms dlog_alpha;
+ *   any other shape with dk <= 128 and dk * (dv + 1) <= 32768, either io_dtype: token by token in fp32 with the state in
+ *     LDS (one workgroup per (batch, head), a forward launch then a reverse launch) -- complete, not fast.
+ * Anything else returns RODIMUS_ERR_SHAPE (also T * H >= 2^31).
  */
 int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v,
                            const float *log_alpha, const float *beta, const float *S0,

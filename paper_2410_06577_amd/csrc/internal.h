@@ -202,6 +202,9 @@ struct ScanBwdArgs {
 };
 
 hipError_t launch_scan_bwd(const ScanBwdArgs &a);
+hipError_t launch_scan_bwd_generic(const ScanBwdArgs &a);       // any other supported shape: fp32 on the vector ALUs
+bool scan_bwd_generic_supports(int dk, int dv);
+size_t scan_bwd_generic_workspace_bytes(int B, int T, int H, int dk);
 bool scan_bwd_supports(int dk, int dv, int io_dtype);
 size_t scan_bwd_workspace_bytes(int B, int T, int H);
 hipError_t launch_decode_step(const DecodeArgs &a);

@@ -239,8 +239,9 @@ int rodimus_decode_step_gated(const void *q, const void *k, const void *v, const
 
 size_t rodimus_chunk_scan_bwd_workspace_bytes(int B, int T, int H, int dk, int dv, int io_dtype)
 {
-    if (B < 0 || T < 0 || H < 0 || !scan_bwd_supports(dk, dv, io_dtype)) return 0;
-    return scan_bwd_workspace_bytes(B, T, H);
+    if (B < 0 || T < 0 || H < 0 || (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16)) return 0;
+    if (scan_bwd_supports(dk, dv, io_dtype)) return scan_bwd_workspace_bytes(B, T, H);
+    return scan_bwd_generic_supports(dk, dv) ? scan_bwd_generic_workspace_bytes(B, T, H, dk) : 0;
 }
 
 int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta,
@@ -251,7 +252,8 @@ int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v, const fl
     if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
     if (B < 0 || T < 0 || H < 0 || (long long)B * H > kMaxGridX) return RODIMUS_ERR_SHAPE;
     if ((long long)T * H > kMaxGridX) return RODIMUS_ERR_SHAPE;          // the kernels index a sequence's rows in 32 bits
-    if (!scan_bwd_supports(dk_width, dv, io_dtype)) return RODIMUS_ERR_SHAPE;
+    const bool mfma = scan_bwd_supports(dk_width, dv, io_dtype);
+    if (!mfma && !scan_bwd_generic_supports(dk_width, dv)) return RODIMUS_ERR_SHAPE;
     const size_t tokens = (size_t)B * T * H, states = (size_t)B * H;
     if (tokens > 0 && (!q || !k || !v || !log_alpha || !d_o || !dq || !dk || !dv_out || !dlog_alpha)) return RODIMUS_ERR_NULL;
     const size_t eb = elem_bytes(io_dtype);
@@ -259,7 +261,7 @@ int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v, const fl
     const size_t in_bytes[8] = {tokens * dk_width * eb, tokens * dk_width * eb, tokens * dv * eb, tokens * dk_width * 4,
                                 tokens * dv * 4, states * dk_width * dv * 4, tokens * dv * eb, states * dk_width * dv * 4};
     void *outs[7] = {dq, dk, dv_out, dlog_alpha, dbeta, dS0, workspace};
-    const size_t need = scan_bwd_workspace_bytes(B, T, H);
+    const size_t need = mfma ? scan_bwd_workspace_bytes(B, T, H) : scan_bwd_generic_workspace_bytes(B, T, H, dk_width);
     const size_t out_bytes[7] = {tokens * dk_width * eb, tokens * dk_width * eb, tokens * dv * eb, tokens * dk_width * 4,
                                  tokens * dv * 4, states * dk_width * dv * 4, need};
     for (int i = 0; i < 8; ++i)
@@ -276,7 +278,7 @@ int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v, const fl
 
     ScanBwdArgs a{q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, dk, dv_out, dlog_alpha, dbeta, dS0, B, T, H, dk_width, dv,
                   io_dtype, workspace, workspace_bytes, static_cast<hipStream_t>(stream)};
-    return launch_scan_bwd(a) == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
+    return (mfma ? launch_scan_bwd(a) : launch_scan_bwd_generic(a)) == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
 }
 
 int rodimus_ddts_gates(const void *z_g, const void *z_tau, const void *z_beta, const void *q, const void *k,

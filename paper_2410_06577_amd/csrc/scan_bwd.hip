@@ -3,11 +3,11 @@
 // dv = 128 or 256.  With l_t the running sum of log_alpha inside a tile, A_t = exp(l_t), u_t = beta_t .* v_t and
 // w[t,i] = exp(l_t - l_i) (always <= 1 for i <= t: no quotient is ever formed):
 //
-//   forward sweep (scan_bwd_dq_kernel), state S entering the tile:
+//   forward sweep (sweep_dq), state S entering the tile:
 //       dP[t,i] = do_t . u_i  (i <= t)
 //       dq_t    = A_t .* (do_t S^T) + sum_{i<=t} dP[t,i] (k_i .* w[t,i])
 //       S      <- diag(A_16) S + sum_i (k_i .* exp(l_16 - l_i))^T u_i
-//   reverse sweep (scan_bwd_dkv_kernel), cotangent G of the state leaving the tile:
+//   reverse sweep (sweep_dkv), cotangent G of the state leaving the tile:
 //       P[t,i]  = sum_n q_t k_i w[t,i]  (i <= t)
 //       du_i    = sum_{t>=i} P[t,i] do_t + (k_i .* exp(l_16 - l_i)) G
 //       dk_i    = exp(l_16 - l_i) .* (u_i G^T) + sum_{t>=i} dP[t,i] (q_t .* w[t,i])

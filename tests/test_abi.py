@@ -178,7 +178,8 @@ def test_backward_validation(L):
                                         need if ws_bytes is None else ws_bytes, None)
 
     assert call(io=4) == E_DTYPE
-    for bad in (dict(dk=32), dict(dv=64), dict(dv=384), dict(io=rodimus.F32), dict(B=-1), dict(T=-1)):
+    for bad in (dict(dk=0), dict(dk=129), dict(dv=0), dict(dk=128, dv=256), dict(B=-1), dict(T=-1),
+                dict(T=1 << 20, H=1 << 12)):
         assert call(**bad) == E_SHAPE, bad
     for name in ("q", "k", "v", "la", "d_o", "dq", "dk_out", "dv_out", "dla"):
         assert call(**{name: None}) == E_NULL, name
@@ -188,7 +189,11 @@ def test_backward_validation(L):
     assert call(ws=base["dla"]) == E_ALIAS
     assert call(ws_bytes=16) == E_WS and call(ws=None) == E_WS
     assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 64, 128, rodimus.BF16) == (2 * 2 * 100 * 3 * 64 + 2 * 3 * 64) * 4
-    assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 32, 128, rodimus.BF16) == 0
+    # any other shape takes the generic kernels: q .* dq only
+    assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 32, 128, rodimus.BF16) == (2 * 100 * 3 * 32 + 2 * 3 * 32) * 4
+    assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 64, 128, rodimus.F32) == (2 * 100 * 3 * 64 + 2 * 3 * 64) * 4
+    assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 129, 8, rodimus.F32) == 0
+    assert call(dk=16, dv=32, io=rodimus.F32, ws_bytes=16) == E_WS
     assert call(B=0) == OK
 
 
