@@ -11,7 +11,8 @@ Contents
 ``sequential.py``     ctypes loader for it: ``scan``, ``step``, ``scan_bwd`` (reverse-mode differentiation of the
                       recurrence, step by step), ``block_output`` (feed-through and output gate of Sec. 3.1.3),
                       ``short_conv`` (the ShortConv of Sec. 3.1.3), ``ddts_gates`` (the gate front-end of Sec. 3.1.2) and
-                      ``scan_gated`` / ``step_gated`` (the recurrence straight from the gates' pre-activations).
+                      ``scan_gated`` / ``step_gated`` (the recurrence straight from the gates' pre-activations),
+                      ``scan_general`` / ``step_general`` (the general transition of Sec. 3.1.1 with a gate along the value dimension too).
 ``chunkwise.py``      the same result computed by the chunkwise form of the
                       appendix "Chunkwise Parallel Representation of the Rodimus
                       Block", in numpy fp64 -- used to check the chunk algebra
@@ -26,5 +27,5 @@ linear-attention closed forms, the T = 1 case by hand, split-sequence chaining;
 (tests/test_oracle_short_conv.py): hand-worked values, numpy.convolve, impulse
 response, identity taps, split-sequence chaining through the carried inputs.
 """
-from .sequential import (block_output, ddts_gates, scan, scan_bwd, scan_gated, short_conv, step, step_gated,  # noqa: F401
-                         threads)
+from .sequential import (block_output, ddts_gates, scan, scan_bwd, scan_gated, scan_general, short_conv, step,  # noqa: F401
+                         step_gated, step_general, threads)

@@ -56,9 +56,23 @@ int rodimus_oracle_threads(void)
 static double sigmoid_d(double z) { return z >= 0.0 ? 1.0 / (1.0 + exp(-z)) : exp(z) / (1.0 + exp(z)); }
 
 /* One time step of one (b, h) recurrence, in place on S (dk x dv, row-major). */
+static void ddts_update_general(double *S, const float *q, const float *k, const float *v,
+                                const float *log_alpha, const float *log_beta_t, const float *beta, int beta_is_preactivation,
+                                double *o, int dk, int dv, double *gated_v);
+
 static void ddts_update(double *S, const float *q, const float *k, const float *v,
                         const float *log_alpha, const float *beta, int beta_is_preactivation,
                         double *o, int dk, int dv, double *gated_v)
+{
+    ddts_update_general(S, q, k, v, log_alpha, NULL, beta, beta_is_preactivation, o, dk, dv, gated_v);
+}
+
+/* The general gated transition of Sec. 3.1.1 (first equation of the section): the state is decayed along both of its
+   dimensions, S_t = (alpha_t^T beta_t) .* S_{t-1} + k_t^T (beta_hat_t .* v_t), with beta_t = exp(log_beta_t) a 1 x dv row
+   (log_beta_t == NULL: beta_t = 1, the choice the paper makes for the block). */
+static void ddts_update_general(double *S, const float *q, const float *k, const float *v,
+                                const float *log_alpha, const float *log_beta_t, const float *beta, int beta_is_preactivation,
+                                double *o, int dk, int dv, double *gated_v)
 {
     /* gated value: beta_t .* v_t   (beta == NULL means the all-ones gate;
        with the flag set the array holds z_beta and beta_t = sigmoid(z_beta_t)) */
@@ -73,8 +87,10 @@ static void ddts_update(double *S, const float *q, const float *k, const float *
         const double alpha = exp((double)log_alpha[r]);   /* exp(-inf) == 0 */
         const double kr = (double)k[r];
         double *Srow = S + (size_t)r * dv;
-        for (int j = 0; j < dv; ++j)
-            Srow[j] = alpha * Srow[j] + kr * gated_v[j];
+        for (int j = 0; j < dv; ++j) {
+            const double decay = log_beta_t ? alpha * exp((double)log_beta_t[j]) : alpha;
+            Srow[j] = decay * Srow[j] + kr * gated_v[j];
+        }
     }
 
     /* o_t = q_t S_t  (the updated state) */
@@ -471,4 +487,64 @@ int rodimus_oracle_step_gated(const float *q, const float *k, const float *v, co
                      z_g + (size_t)s * dk, z_tau + (size_t)s * dk, z_beta ? z_beta + (size_t)s * dv : NULL,
                      o + (size_t)s * dv, dk, dv);
     return 0;
+}
+
+/*
+ * The recurrence with the general transition of Sec. 3.1.1: as rodimus_oracle_scan / rodimus_oracle_step with one more
+ * input, log_beta_t [B,T,H,dv] / [N,H,dv] (<= 0), the logarithm of the transition gate along the value dimension.
+ * `beta` stays the input gate on the value (values, not pre-activations).
+ */
+int rodimus_oracle_scan_general(const float *q, const float *k, const float *v, const float *log_alpha,
+                                const float *log_beta_t, const float *beta, const double *S0, double *o, double *S_T,
+                                int B, int T, int H, int dk, int dv)
+{
+    if (!q || !k || !v || !log_alpha || !log_beta_t || !o) return 1;
+    if (B < 0 || T < 0 || H < 0 || dk <= 0 || dv <= 0) return 1;
+    int failed = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < H; ++h) {
+            double *S = (double *)malloc(sizeof(double) * (size_t)dk * dv);
+            double *gv = (double *)malloc(sizeof(double) * (size_t)dv);
+            if (!S || !gv) {
+                free(S); free(gv);
+#pragma omp atomic write
+                failed = 1;
+                continue;
+            }
+            const size_t state_off = ((size_t)b * H + h) * (size_t)dk * dv;
+            for (size_t e = 0; e < (size_t)dk * dv; ++e) S[e] = S0 ? S0[state_off + e] : 0.0;
+            for (int t = 0; t < T; ++t) {
+                const size_t row = ((size_t)b * T + t) * H + h;
+                ddts_update_general(S, q + row * dk, k + row * dk, v + row * dv, log_alpha + row * dk, log_beta_t + row * dv,
+                                    beta ? beta + row * dv : NULL, 0, o + row * dv, dk, dv, gv);
+            }
+            if (S_T)
+                for (size_t e = 0; e < (size_t)dk * dv; ++e) S_T[state_off + e] = S[e];
+            free(S); free(gv);
+        }
+    }
+    return failed ? 2 : 0;
+}
+
+int rodimus_oracle_step_general(const float *q, const float *k, const float *v, const float *log_alpha,
+                                const float *log_beta_t, const float *beta, double *S, double *o, int N, int H, int dk, int dv)
+{
+    if (!q || !k || !v || !log_alpha || !log_beta_t || !S || !o) return 1;
+    if (N < 0 || H < 0 || dk <= 0 || dv <= 0) return 1;
+    int failed = 0;
+#pragma omp parallel for schedule(static)
+    for (long s = 0; s < (long)N * H; ++s) {
+        double *gv = (double *)malloc(sizeof(double) * (size_t)dv);
+        if (!gv) {
+#pragma omp atomic write
+            failed = 1;
+            continue;
+        }
+        ddts_update_general(S + (size_t)s * dk * dv, q + (size_t)s * dk, k + (size_t)s * dk, v + (size_t)s * dv,
+                            log_alpha + (size_t)s * dk, log_beta_t + (size_t)s * dv, beta ? beta + (size_t)s * dv : NULL, 0,
+                            o + (size_t)s * dv, dk, dv, gv);
+        free(gv);
+    }
+    return failed ? 2 : 0;
 }

@@ -38,6 +38,10 @@ def _load():
         lib.rodimus_oracle_scan_gated.restype = ctypes.c_int
         lib.rodimus_oracle_step_gated.argtypes = [f32p] * 6 + [f64p] * 2 + [ctypes.c_int] * 4
         lib.rodimus_oracle_step_gated.restype = ctypes.c_int
+        lib.rodimus_oracle_scan_general.argtypes = [f32p] * 6 + [f64p] * 3 + [ctypes.c_int] * 5
+        lib.rodimus_oracle_scan_general.restype = ctypes.c_int
+        lib.rodimus_oracle_step_general.argtypes = [f32p] * 6 + [f64p] * 2 + [ctypes.c_int] * 4
+        lib.rodimus_oracle_step_general.restype = ctypes.c_int
         lib.rodimus_oracle_short_conv.argtypes = [f32p, f32p, f32p, f32p, f64p, f64p] + [ctypes.c_int] * 5
         lib.rodimus_oracle_short_conv.restype = ctypes.c_int
         lib.rodimus_oracle_ddts_gates.argtypes = [f32p] * 5 + [f64p] * 4 + [ctypes.c_long, ctypes.c_int, ctypes.c_int]
@@ -235,6 +239,44 @@ def step_gated(q, k, v, z_g, z_tau, z_beta, S):
                                        _ptr(S, ctypes.c_double), _ptr(o, ctypes.c_double), N, H, dk, dv)
     if rc != 0:
         raise RuntimeError(f"rodimus_oracle_step_gated failed with code {rc}")
+    return o, S
+
+
+def scan_general(q, k, v, log_alpha, log_beta_t, beta=None, S0=None, want_state=True):
+    """The recurrence with the general transition of Sec. 3.1.1: S_t = (alpha_t^T beta_t) .* S_{t-1} + k_t^T (beta_hat_t .* v_t),
+    beta_t = exp(log_beta_t) [B,T,H,dv]; ``beta`` is the input gate beta_hat as in ``scan``.  Returns (o, S_T) float64."""
+    lib = _load()
+    q, k, v, la, lb, beta = _f32(q), _f32(k), _f32(v), _f32(log_alpha), _f32(log_beta_t), _f32(beta)
+    S0 = _f64(S0)
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    assert k.shape == la.shape == (B, T, H, dk) and v.shape == lb.shape == (B, T, H, dv)
+    assert beta is None or beta.shape == (B, T, H, dv)
+    o = np.empty((B, T, H, dv), dtype=np.float64)
+    S_T = np.empty((B, H, dk, dv), dtype=np.float64) if want_state else None
+    f = ctypes.c_float
+    rc = lib.rodimus_oracle_scan_general(_ptr(q, f), _ptr(k, f), _ptr(v, f), _ptr(la, f), _ptr(lb, f), _ptr(beta, f),
+                                         _ptr(S0, ctypes.c_double), _ptr(o, ctypes.c_double), _ptr(S_T, ctypes.c_double),
+                                         B, T, H, dk, dv)
+    if rc != 0:
+        raise RuntimeError(f"rodimus_oracle_scan_general failed with code {rc}")
+    return o, S_T
+
+
+def step_general(q, k, v, log_alpha, log_beta_t, beta, S):
+    """One decode step of ``scan_general``.  Returns (o, S'); ``S`` is not modified."""
+    lib = _load()
+    q, k, v, la, lb, beta = _f32(q), _f32(k), _f32(v), _f32(log_alpha), _f32(log_beta_t), _f32(beta)
+    S = _f64(S).copy()
+    N, H, dk = q.shape
+    dv = v.shape[-1]
+    assert k.shape == la.shape == (N, H, dk) and v.shape == lb.shape == (N, H, dv) and S.shape == (N, H, dk, dv)
+    o = np.empty((N, H, dv), dtype=np.float64)
+    f = ctypes.c_float
+    rc = lib.rodimus_oracle_step_general(_ptr(q, f), _ptr(k, f), _ptr(v, f), _ptr(la, f), _ptr(lb, f), _ptr(beta, f),
+                                         _ptr(S, ctypes.c_double), _ptr(o, ctypes.c_double), N, H, dk, dv)
+    if rc != 0:
+        raise RuntimeError(f"rodimus_oracle_step_general failed with code {rc}")
     return o, S
 
 

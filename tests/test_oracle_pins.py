@@ -288,3 +288,45 @@ def test_mutation_sensitivity_of_the_pins():
     np.testing.assert_allclose(run("good"), good)
     for bad in ("pre", "decay_own", "transposed"):
         assert not np.allclose(run(bad), good), bad
+
+
+def test_general_transition_unrolled_sum_reduction_and_separable_case():
+    """The value-side transition gate of Sec. 3.1.1: the unrolled form printed with it (both gates' products between write
+    and read), reduction to the block's recurrence at beta_t = 1, and a closed form where the two gates are constants."""
+    rng = np.random.default_rng(31)
+    B, T, H, dk, dv = 1, 11, 2, 3, 4
+    q = rng.standard_normal((B, T, H, dk)).astype(np.float32)
+    k = rng.standard_normal((B, T, H, dk)).astype(np.float32)
+    v = rng.standard_normal((B, T, H, dv)).astype(np.float32)
+    la = -rng.uniform(0.0, 1.0, (B, T, H, dk)).astype(np.float32)
+    lb = -rng.uniform(0.0, 1.0, (B, T, H, dv)).astype(np.float32)
+    bh = rng.uniform(0.0, 1.0, (B, T, H, dv)).astype(np.float32)
+    o, S_T = oracle.scan_general(q, k, v, la, lb, bh)
+    # o_t = sum_{i<=t} [q_t (prod_{j=i+1..t} alpha_j .* k_i)^T] (prod_{j=i+1..t} beta_j .* beta_hat_i .* v_i)
+    la64, lb64 = la.astype(np.float64), lb.astype(np.float64)
+    for h in range(H):
+        for t in range(T):
+            acc = np.zeros(dv)
+            for i in range(t + 1):
+                da = np.exp(la64[0, i + 1:t + 1, h].sum(axis=0))
+                db = np.exp(lb64[0, i + 1:t + 1, h].sum(axis=0))
+                acc += (q[0, t, h].astype(np.float64) @ (da * k[0, i, h])) * (db * bh[0, i, h].astype(np.float64) * v[0, i, h])
+            np.testing.assert_allclose(o[0, t, h], acc, rtol=1e-12, atol=1e-13)
+    # beta_t = 1 is the block's recurrence
+    zero = np.zeros_like(lb)
+    o1, S1 = oracle.scan_general(q, k, v, la, zero, bh)
+    o2, S2 = oracle.scan(q, k, v, la, bh)
+    assert np.array_equal(o1, o2) and np.array_equal(S1, S2)
+    # constant scalar gates a (keys) and b (values): the state decays by (a b)^(t-i): same as the block's recurrence with
+    # the key-side gate a * b
+    a_log, b_log = np.float32(-0.25), np.float32(-0.5)
+    o3, S3 = oracle.scan_general(q, k, v, np.full_like(la, a_log), np.full_like(lb, b_log), None)
+    o4, S4 = oracle.scan(q, k, v, np.full_like(la, a_log + b_log), None)
+    np.testing.assert_allclose(o3, o4, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(S3, S4, rtol=1e-13, atol=1e-14)
+    # decode steps chain to the scan
+    S = np.zeros((B, H, dk, dv))
+    for t in range(T):
+        o_t, S = oracle.step_general(q[:, t], k[:, t], v[:, t], la[:, t], lb[:, t], bh[:, t], S)
+        assert np.array_equal(o_t, o[:, t])
+    assert np.array_equal(S, S_T)
