@@ -306,6 +306,32 @@ int rodimus_decode_step_gated(const void *q, const void *k, const void *v,
                               float *S, void *o,
                               int N, int H, int dk, int dv, int io_dtype, void *stream);
 
+/*
+ * The two recurrence calls with the general transition of paper Sec. 3.1.1 (first equation of the section), which gates
+ * the state along the value dimension as well:
+ *     S_t = (alpha_t^T beta_t) .* S_{t-1} + k_t^T (beta_hat_t .* v_t),   o_t = q_t S_t
+ * The paper fixes beta_t = 1 for the block after an ablation (the other calls); this variant is for the models of its
+ * comparison table that use such a gate.
+ *
+ *   log_beta_t  [B,T,H,dv] / [N,H,dv] fp32     in, required: log of the transition gate beta_t, <= 0 (-inf allowed)
+ *   beta        the input gate beta_hat on the value, fp32 values or NULL = all ones (as in rodimus_chunk_scan_fwd)
+ *   everything else as in rodimus_chunk_scan_fwd / rodimus_decode_step.
+ *
+ * The scan always runs on the any-shape fp32 kernel (no workspace): the pair (write i, read t) carries
+ * exp(sum_{j=i+1..t} log_beta_j) per value column, which is evaluated per pair (never as a quotient of running
+ * products), so this form is several times slower than the block's own recurrence.  The decode step costs the same as
+ * rodimus_decode_step.
+ */
+int rodimus_chunk_scan_fwd_general(const void *q, const void *k, const void *v,
+                                   const float *log_alpha, const float *log_beta_t, const float *beta, const float *S0,
+                                   void *o, float *S_T,
+                                   int B, int T, int H, int dk, int dv, int chunk, int io_dtype, void *stream);
+
+int rodimus_decode_step_general(const void *q, const void *k, const void *v,
+                                const float *log_alpha, const float *log_beta_t, const float *beta,
+                                float *S, void *o,
+                                int N, int H, int dk, int dv, int io_dtype, void *stream);
+
 /* Activation after the short convolution. */
 typedef enum {
     RODIMUS_CONV_NONE = 0,            /* the convolution alone                                              */

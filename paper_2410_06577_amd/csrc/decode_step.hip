@@ -28,12 +28,14 @@ constexpr int kDecodeCols = 256;   // value columns per workgroup (64 lanes x 4)
 constexpr int kDecodeMaxDk = 256;
 constexpr size_t kLastLevelCacheBytes = 256u << 20;
 
-template <typename IO, bool kStream>
+// kGeneral: the general transition of Sec. 3.1.1, S' = (alpha^T beta_t) .* S + k^T (beta_hat .* v), with the value-side
+// transition gate given as log_beta_t [N, H, dv] fp32.
+template <typename IO, bool kStream, bool kGeneral>
 __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(
     const IO *__restrict__ q, const IO *__restrict__ k, const IO *__restrict__ v,
     const float *__restrict__ log_alpha, const void *__restrict__ beta, bool beta_preact,
     float *__restrict__ S, IO *__restrict__ o, int dk, int dv, int H, OutputStage stage,
-    const IO *__restrict__ z_g, const IO *__restrict__ z_tau)
+    const IO *__restrict__ z_g, const IO *__restrict__ z_tau, const float *__restrict__ log_beta_t)
 {
     constexpr int kRowBatch = kStream ? 4 : 8;      // rows in flight per wavefront
     __shared__ float s_q[kDecodeMaxDk];
@@ -86,6 +88,11 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(
             gv *= floatx4_t{sigmoid_f(z[0]), sigmoid_f(z[1]), sigmoid_f(z[2]), sigmoid_f(z[3])};
         }
     }
+    floatx4_t bdec = {1.f, 1.f, 1.f, 1.f};               // transition gate of this lane's columns (general form only)
+    if (kGeneral && active) {
+        const floatx4_t lb = *reinterpret_cast<const floatx4_t *>(log_beta_t + state * dv + col);
+        bdec = floatx4_t{expf(lb[0]), expf(lb[1]), expf(lb[2]), expf(lb[3])};
+    }
     __syncthreads();
 
     float *Sp = S + state * (size_t)dk * dv + col;
@@ -108,10 +115,17 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(
                 if (r < dk) {
                     const float a = s_a[r], kr = s_k[r], qr = s_q[r];
                     floatx4_t n;
-                    n[0] = fmaf(a, s[u][0], kr * gv[0]);
-                    n[1] = fmaf(a, s[u][1], kr * gv[1]);
-                    n[2] = fmaf(a, s[u][2], kr * gv[2]);
-                    n[3] = fmaf(a, s[u][3], kr * gv[3]);
+                    if (kGeneral) {
+                        n[0] = fmaf(a * bdec[0], s[u][0], kr * gv[0]);
+                        n[1] = fmaf(a * bdec[1], s[u][1], kr * gv[1]);
+                        n[2] = fmaf(a * bdec[2], s[u][2], kr * gv[2]);
+                        n[3] = fmaf(a * bdec[3], s[u][3], kr * gv[3]);
+                    } else {
+                        n[0] = fmaf(a, s[u][0], kr * gv[0]);
+                        n[1] = fmaf(a, s[u][1], kr * gv[1]);
+                        n[2] = fmaf(a, s[u][2], kr * gv[2]);
+                        n[3] = fmaf(a, s[u][3], kr * gv[3]);
+                    }
                     floatx4_t *p = reinterpret_cast<floatx4_t *>(Sp + (size_t)r * dv);
                     if (kStream) __builtin_nontemporal_store(n, p); else *p = n;
                     acc[0] = fmaf(qr, n[0], acc[0]);
@@ -154,15 +168,20 @@ hipError_t launch_decode_step(const DecodeArgs &a)
     // grid.x is limited to 2^31-1 workgroups; the C-ABI layer has checked N*H against it.
     dim3 grid((unsigned)states, col_tiles), block(kDecodeThreads);
     const bool stream = (size_t)states * a.dk * a.dv * sizeof(float) > kLastLevelCacheBytes;
-#define RODIMUS_LAUNCH_DECODE(IO, STREAM)                                                                         \
-    hipLaunchKernelGGL((decode_step_kernel<IO, STREAM>), grid, block, 0, a.stream, (const IO *)a.q, (const IO *)a.k, \
-                       (const IO *)a.v, a.log_alpha, a.beta, a.beta_preact, a.S, (IO *)a.o, a.dk, a.dv, a.H, a.stage, \
-                       (const IO *)a.z_g, (const IO *)a.z_tau)
-    if (a.io_dtype == RODIMUS_BF16) {
-        if (stream) RODIMUS_LAUNCH_DECODE(bf16_t, true); else RODIMUS_LAUNCH_DECODE(bf16_t, false);
-    } else {
-        if (stream) RODIMUS_LAUNCH_DECODE(float, true); else RODIMUS_LAUNCH_DECODE(float, false);
-    }
+#define RODIMUS_LAUNCH_DECODE(IO, STREAM, GENERAL)                                                                        \
+    hipLaunchKernelGGL((decode_step_kernel<IO, STREAM, GENERAL>), grid, block, 0, a.stream, (const IO *)a.q, (const IO *)a.k, \
+                       (const IO *)a.v, a.log_alpha, a.beta, a.beta_preact, a.S, (IO *)a.o, a.dk, a.dv, a.H, a.stage,         \
+                       (const IO *)a.z_g, (const IO *)a.z_tau, a.log_beta_t)
+#define RODIMUS_LAUNCH_DECODE_IO(IO)                                                                    \
+    do {                                                                                                \
+        if (a.log_beta_t != nullptr) {                                                                  \
+            if (stream) RODIMUS_LAUNCH_DECODE(IO, true, true); else RODIMUS_LAUNCH_DECODE(IO, false, true);   \
+        } else {                                                                                        \
+            if (stream) RODIMUS_LAUNCH_DECODE(IO, true, false); else RODIMUS_LAUNCH_DECODE(IO, false, false); \
+        }                                                                                               \
+    } while (0)
+    if (a.io_dtype == RODIMUS_BF16) RODIMUS_LAUNCH_DECODE_IO(bf16_t); else RODIMUS_LAUNCH_DECODE_IO(float);
+#undef RODIMUS_LAUNCH_DECODE_IO
 #undef RODIMUS_LAUNCH_DECODE
     return hipGetLastError();
 }

@@ -160,6 +160,8 @@ struct ScanArgs {
     // into q.  `log_alpha` is then unused.
     const void *z_g = nullptr, *z_tau = nullptr;
     bool gated() const { return z_tau != nullptr; }
+    // General transition of Sec. 3.1.1: log of the gate along the value dimension, [tokens, H, dv] fp32 (generic kernel only)
+    const float *log_beta_t = nullptr;
 };
 
 struct DecodeArgs {
@@ -175,6 +177,7 @@ struct DecodeArgs {
     hipStream_t stream;
     const void *z_g = nullptr, *z_tau = nullptr;     // gated form, as in ScanArgs
     bool gated() const { return z_tau != nullptr; }
+    const float *log_beta_t = nullptr;               // general transition, [N, H, dv] fp32
 };
 
 struct GateArgs {
@@ -221,7 +224,7 @@ struct ShortConvArgs {
 };
 hipError_t launch_short_conv(const ShortConvArgs &a);
 hipError_t launch_scan_generic(const ScanArgs &a);
-size_t scan_generic_lds_bytes(int dk, int chunk);
+size_t scan_generic_lds_bytes(int dk, int chunk, bool general = false);
 hipError_t launch_scan_mfma(const ScanArgs &a);
 bool scan_mfma_supports(int dk, int dv, int chunk, int io_dtype);
 size_t scan_mfma_workspace_bytes(int B, int T, int H, int dv);

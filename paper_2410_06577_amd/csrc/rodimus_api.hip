@@ -42,7 +42,7 @@ int scan_entry(const void *q, const void *k, const void *v, const float *log_alp
                const float *S0, void *o, float *S_T, int B, int T, int H, int dk, int dv, int chunk, int io_dtype,
                void *workspace, size_t workspace_bytes, void *stream, bool packed = false, const int *cu_seqlens = nullptr,
                OutputStage stage = OutputStage{nullptr, nullptr, nullptr, 0}, bool gated = false, const void *z_g = nullptr,
-               const void *z_tau = nullptr)
+               const void *z_tau = nullptr, bool general = false, const float *log_beta_t = nullptr)
 {
     const int shape = scan_shape_status(B, T, H, dk, dv, chunk, io_dtype);
     if (shape != RODIMUS_OK) return shape;
@@ -55,8 +55,9 @@ int scan_entry(const void *q, const void *k, const void *v, const float *log_alp
     if (tokens > 0 && (!q || !k || !v || !gate_a || !o)) return RODIMUS_ERR_NULL;   // empty tensors may be NULL
     if (tokens > 0 && gated && !gate_b) return RODIMUS_ERR_NULL;
     if (tokens > 0 && beta_preact && !beta && !gated) return RODIMUS_ERR_NULL;
+    if (tokens > 0 && general && !log_beta_t) return RODIMUS_ERR_NULL;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(gate_a) || misaligned(gate_b) || misaligned(beta) ||
-        misaligned(S0) || misaligned(o) || misaligned(S_T) || misaligned(workspace))
+        misaligned(S0) || misaligned(o) || misaligned(S_T) || misaligned(workspace) || misaligned(log_beta_t))
         return RODIMUS_ERR_ALIGN;
 
     const size_t eb = elem_bytes(io_dtype);
@@ -78,23 +79,28 @@ int scan_entry(const void *q, const void *k, const void *v, const float *log_alp
         overlaps(o, v_bytes, stage.d, (size_t)H * dv * 4) || overlaps(S_T, state_bytes, stage.x_prime, v_bytes) ||
         overlaps(S_T, state_bytes, stage.z_gate, v_bytes) || overlaps(S_T, state_bytes, stage.d, (size_t)H * dv * 4))
         return RODIMUS_ERR_ALIAS;
+    if (overlaps(o, v_bytes, log_beta_t, tokens * dv * 4) || overlaps(S_T, state_bytes, log_beta_t, tokens * dv * 4))
+        return RODIMUS_ERR_ALIAS;
     const size_t cu_bytes = packed ? ((size_t)B + 1) * sizeof(int) : 0;
     if (overlaps(o, v_bytes, cu_seqlens, cu_bytes) || overlaps(S_T, state_bytes, cu_seqlens, cu_bytes)) return RODIMUS_ERR_ALIAS;
 
-    const size_t need = (!packed && scan_mfma_supports(dk, dv, chunk, io_dtype)) ? scan_mfma_workspace_bytes(B, T, H, dv) : 0;
+    // the general transition runs on the any-shape kernel only
+    const bool mfma = !general && scan_mfma_supports(dk, dv, chunk, io_dtype);
+    const size_t need = (!packed && mfma) ? scan_mfma_workspace_bytes(B, T, H, dv) : 0;
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return RODIMUS_ERR_WORKSPACE;
 
     ScanArgs a{q, k, v, log_alpha, beta, beta_preact, S0, o, S_T, B, T, H, dk, dv, chunk, io_dtype,
                packed ? cu_seqlens : nullptr, stage, workspace, workspace_bytes, static_cast<hipStream_t>(stream)};
     if (gated) { a.log_alpha = nullptr; a.z_g = z_g; a.z_tau = z_tau; }
-    const hipError_t err = scan_mfma_supports(dk, dv, chunk, io_dtype) ? launch_scan_mfma(a) : launch_scan_generic(a);
+    if (general) a.log_beta_t = log_beta_t;
+    const hipError_t err = mfma ? launch_scan_mfma(a) : launch_scan_generic(a);
     return err == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
 }
 
 int decode_entry(const void *q, const void *k, const void *v, const float *log_alpha, const void *beta, bool beta_preact,
                  float *S, void *o, int N, int H, int dk, int dv, int io_dtype, void *stream,
                  OutputStage stage = OutputStage{nullptr, nullptr, nullptr, 0}, bool gated = false, const void *z_g = nullptr,
-                 const void *z_tau = nullptr)
+                 const void *z_tau = nullptr, bool general = false, const float *log_beta_t = nullptr)
 {
     if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
     if (N < 0 || H < 0 || dk < 1 || dk > kMaxDecodeDk || dv < 4 || (dv & 3) != 0) return RODIMUS_ERR_SHAPE;
@@ -105,8 +111,9 @@ int decode_entry(const void *q, const void *k, const void *v, const float *log_a
     if (states > 0 && (!q || !k || !v || !gate_a || !S || !o)) return RODIMUS_ERR_NULL;
     if (states > 0 && gated && !gate_b) return RODIMUS_ERR_NULL;
     if (states > 0 && beta_preact && !beta && !gated) return RODIMUS_ERR_NULL;
+    if (states > 0 && general && !log_beta_t) return RODIMUS_ERR_NULL;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(gate_a) || misaligned(gate_b) || misaligned(beta) ||
-        misaligned(S) || misaligned(o))
+        misaligned(S) || misaligned(o) || misaligned(log_beta_t))
         return RODIMUS_ERR_ALIGN;
 
     const size_t eb = elem_bytes(io_dtype);
@@ -121,6 +128,8 @@ int decode_entry(const void *q, const void *k, const void *v, const float *log_a
         overlaps(S, s_bytes, beta, beta_bytes))
         return RODIMUS_ERR_ALIAS;
 
+    if (overlaps(o, o_bytes, log_beta_t, states * dv * 4) || overlaps(S, s_bytes, log_beta_t, states * dv * 4))
+        return RODIMUS_ERR_ALIAS;
     if (stage.x_prime != nullptr && stage.d == nullptr) return RODIMUS_ERR_NULL;
     if (misaligned(stage.x_prime) || misaligned(stage.d) || misaligned(stage.z_gate)) return RODIMUS_ERR_ALIGN;
     if (overlaps(o, o_bytes, stage.x_prime, o_bytes) || overlaps(o, o_bytes, stage.z_gate, o_bytes) ||
@@ -129,6 +138,7 @@ int decode_entry(const void *q, const void *k, const void *v, const float *log_a
         return RODIMUS_ERR_ALIAS;
     DecodeArgs a{q, k, v, log_alpha, beta, beta_preact, stage, S, o, N, H, dk, dv, io_dtype, static_cast<hipStream_t>(stream)};
     if (gated) { a.log_alpha = nullptr; a.z_g = z_g; a.z_tau = z_tau; }
+    if (general) a.log_beta_t = log_beta_t;
     const hipError_t err = launch_decode_step(a);
     return err == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
 }
@@ -235,6 +245,21 @@ int rodimus_decode_step_gated(const void *q, const void *k, const void *v, const
 {
     return decode_entry(q, k, v, nullptr, z_beta, true, S, o, N, H, dk, dv, io_dtype, stream,
                         OutputStage{nullptr, nullptr, nullptr, 0}, true, z_g, z_tau);
+}
+
+int rodimus_chunk_scan_fwd_general(const void *q, const void *k, const void *v, const float *log_alpha,
+                                   const float *log_beta_t, const float *beta, const float *S0, void *o, float *S_T, int B, int T,
+                                   int H, int dk, int dv, int chunk, int io_dtype, void *stream)
+{
+    return scan_entry(q, k, v, log_alpha, beta, false, S0, o, S_T, B, T, H, dk, dv, chunk, io_dtype, nullptr, 0, stream, false,
+                      nullptr, OutputStage{nullptr, nullptr, nullptr, 0}, false, nullptr, nullptr, true, log_beta_t);
+}
+
+int rodimus_decode_step_general(const void *q, const void *k, const void *v, const float *log_alpha, const float *log_beta_t,
+                                const float *beta, float *S, void *o, int N, int H, int dk, int dv, int io_dtype, void *stream)
+{
+    return decode_entry(q, k, v, log_alpha, beta, false, S, o, N, H, dk, dv, io_dtype, stream,
+                        OutputStage{nullptr, nullptr, nullptr, 0}, false, nullptr, nullptr, true, log_beta_t);
 }
 
 size_t rodimus_chunk_scan_bwd_workspace_bytes(int B, int T, int H, int dk, int dv, int io_dtype)

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
     const IO *__restrict__ q, const IO *__restrict__ k, const IO *__restrict__ v,
     const float *__restrict__ log_alpha, const void *__restrict__ beta, bool beta_preact, const float *S0,
     IO *__restrict__ o, float *S_T, int T, int H, int dk, int dv, int C, const int *__restrict__ cu_seqlens,
-    OutputStage stage, const IO *__restrict__ z_g, const IO *__restrict__ z_tau)
+    OutputStage stage, const IO *__restrict__ z_g, const IO *__restrict__ z_tau, const float *__restrict__ log_beta_t)
 {
     extern __shared__ float lds[];
     const int dkp = dk + 1;                 // padded row stride against bank conflicts
@@ -53,6 +53,8 @@ __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
     float *gv = sp + C * dkp;               // [C][64]   beta .* v
     float *P = gv + C * kColTile;           // [C][C+1]  masked decayed scores
     float *S = P + C * Pp;                  // [dk][64]  state tile
+    float *LB = S + dk * kColTile;          // [C][64]   general transition only: running sum of log_beta_t inside the chunk
+    const bool general = log_beta_t != nullptr;
 
     const int tid = threadIdx.x;
     const int bh = blockIdx.x;
@@ -123,6 +125,18 @@ __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
             }
             gv[e] = x;
         }
+        if (general) {
+            // General transition of Sec. 3.1.1 (a gate beta_t along the value dimension as well): the pair (write i, read t)
+            // carries the factor prod_{j=i+1..t} beta_j = exp(LB_t - LB_i) per column, always <= 1; nothing is divided.
+            for (int c = tid; c < kColTile; c += kThreads) {
+                float run = 0.f;
+                for (int t = 0; t < C; ++t) {
+                    // clamped per step: exp(-128) is zero in fp32, and the running sums stay finite for a closed gate
+                    if (t < n && c < ncol) run += fmaxf(log_beta_t[((tok0 + s + t) * H + h) * dv + j0 + c], -128.f);
+                    LB[t * kColTile + c] = run;
+                }
+            }
+        }
         __syncthreads();
 
         // diagonal of the scores: a token sees its own write undecayed
@@ -176,7 +190,14 @@ __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
             const int t = e / kColTile, c = e % kColTile;
             float acc = 0.f;
             for (int r = 0; r < dk; ++r) acc = fmaf(sq[t * dkp + r], S[r * kColTile + c], acc);
-            for (int i = 0; i <= t; ++i) acc = fmaf(P[t * Pp + i], gv[i * kColTile + c], acc);
+            if (!general) {
+                for (int i = 0; i <= t; ++i) acc = fmaf(P[t * Pp + i], gv[i * kColTile + c], acc);
+            } else {
+                const float lbt = LB[t * kColTile + c];
+                acc *= __expf(lbt);                                  // the entering state has decayed by beta_1 .. beta_t
+                for (int i = 0; i <= t; ++i)
+                    acc = fmaf(P[t * Pp + i] * __expf(lbt - LB[i * kColTile + c]), gv[i * kColTile + c], acc);
+            }
             if (c < ncol) {
                 const size_t e = ((tok0 + s + t) * H + h) * dv + j0 + c;
                 // output stage of the block, if any: y = (o + d .* x') .* act(z)
@@ -188,9 +209,18 @@ __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
         }
         __syncthreads();
 
+        if (general) {
+            // writes decay by the gates of the rows after them up to the chunk end; the state by the whole chunk
+            for (int e = tid; e < n * kColTile; e += kThreads) {
+                const int c = e % kColTile;
+                gv[e] *= __expf(LB[(C - 1) * kColTile + c] - LB[e]);
+            }
+            __syncthreads();
+        }
         for (int e = tid; e < dk * kColTile; e += kThreads) {
             const int r = e / kColTile, c = e % kColTile;
             float acc = pp[(C - 1) * dkp + r] * S[e];
+            if (general) acc *= __expf(LB[(C - 1) * kColTile + c]);
             for (int i = 0; i < n; ++i) acc = fmaf(sk[i * dkp + r], gv[i * kColTile + c], acc);
             S[e] = acc;
         }
@@ -207,24 +237,24 @@ __global__ __launch_bounds__(kThreads) void scan_generic_kernel(
 
 }  // namespace
 
-size_t scan_generic_lds_bytes(int dk, int chunk)
+size_t scan_generic_lds_bytes(int dk, int chunk, bool general)
 {
     const size_t floats = (size_t)4 * chunk * (dk + 1) + (size_t)chunk * kColTile + (size_t)chunk * (chunk + 1) +
-                          (size_t)dk * kColTile;
+                          (size_t)dk * kColTile + (general ? (size_t)chunk * kColTile : 0);
     return floats * sizeof(float);
 }
 
 template <typename IO>
 static hipError_t launch_typed(const ScanArgs &a)
 {
-    const size_t lds = scan_generic_lds_bytes(a.dk, a.chunk);
+    const size_t lds = scan_generic_lds_bytes(a.dk, a.chunk, a.log_beta_t != nullptr);
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_generic_kernel<IO>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (err != hipSuccess) return err;
     dim3 grid((unsigned)(a.B * a.H), (unsigned)((a.dv + kColTile - 1) / kColTile)), block(kThreads);
     hipLaunchKernelGGL(scan_generic_kernel<IO>, grid, block, lds, a.stream, (const IO *)a.q, (const IO *)a.k,
                        (const IO *)a.v, a.log_alpha, a.beta, a.beta_preact, a.S0, (IO *)a.o, a.S_T, a.T, a.H, a.dk, a.dv, a.chunk, a.cu_seqlens, a.stage,
-                       (const IO *)a.z_g, (const IO *)a.z_tau);
+                       (const IO *)a.z_g, (const IO *)a.z_tau, a.log_beta_t);
     return hipGetLastError();
 }
 

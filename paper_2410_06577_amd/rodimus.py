@@ -67,6 +67,10 @@ def lib() -> ctypes.CDLL:
         L.rodimus_chunk_scan_fwd_gated.restype = i
         L.rodimus_decode_step_gated.argtypes = [vp] * 8 + [i] * 5 + [vp]
         L.rodimus_decode_step_gated.restype = i
+        L.rodimus_chunk_scan_fwd_general.argtypes = [vp] * 9 + [i] * 7 + [vp]
+        L.rodimus_chunk_scan_fwd_general.restype = i
+        L.rodimus_decode_step_general.argtypes = [vp] * 8 + [i] * 5 + [vp]
+        L.rodimus_decode_step_general.restype = i
         L.rodimus_short_conv_fwd.argtypes = [vp] * 6 + [i] * 6 + [vp]
         L.rodimus_short_conv_fwd.restype = i
         L.rodimus_short_conv_step.argtypes = [vp] * 5 + [i] * 5 + [vp]
@@ -215,6 +219,64 @@ def rodimus_decode_step_gated(q, k, v, z_g, z_tau, z_beta, S, *, o=None):
     with torch.cuda.device(dev):
         _check(lib().rodimus_decode_step_gated(_ptr(q), _ptr(k), _ptr(v), _ptr(z_g), _ptr(z_tau), _ptr(z_beta), _ptr(S), _ptr(o),
                                                N, H, dk, dv, _DTYPES[io], _stream(dev)))
+    return o
+
+
+def rodimus_chunk_scan_fwd_general(q, k, v, log_alpha, log_beta_t, beta=None, S0=None, *, chunk=64, o=None, S_T=None,
+                                   want_state=True):
+    """Forward scan with the general transition of Sec. 3.1.1: log_beta_t [B,T,H,dv] fp32 gates the state along the value
+    dimension; ``beta`` is the input gate on the value.  Returns (o, S_T)."""
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_chunk_scan_fwd_general needs device tensors (no CPU path exists)")
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    dev, io = q.device, q.dtype
+    _require(k, "k", (B, T, H, dk), io, dev)
+    _require(v, "v", (B, T, H, dv), io, dev)
+    _require(log_alpha, "log_alpha", (B, T, H, dk), torch.float32, dev)
+    if log_beta_t is None:
+        raise ValueError("log_beta_t is required")
+    _require(log_beta_t, "log_beta_t", (B, T, H, dv), torch.float32, dev)
+    _require(beta, "beta", (B, T, H, dv), torch.float32, dev)
+    _require(S0, "S0", (B, H, dk, dv), torch.float32, dev)
+    if o is None:
+        o = torch.empty((B, T, H, dv), dtype=io, device=dev)
+    _require(o, "o", (B, T, H, dv), io, dev)
+    if S_T is None and want_state:
+        S_T = torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev)
+    _require(S_T, "S_T", (B, H, dk, dv), torch.float32, dev)
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_chunk_scan_fwd_general(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(log_beta_t), _ptr(beta),
+                                                    _ptr(S0), _ptr(o), _ptr(S_T), B, T, H, dk, dv, int(chunk), _DTYPES[io],
+                                                    _stream(dev)))
+    return o, S_T
+
+
+def rodimus_decode_step_general(q, k, v, log_alpha, log_beta_t, beta, S, *, o=None):
+    """One recurrent step with the general transition.  log_beta_t [N,H,dv] fp32; S updated in place.  Returns o."""
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_decode_step_general needs device tensors (no CPU path exists)")
+    N, H, dk = q.shape
+    dv = v.shape[-1]
+    dev, io = q.device, q.dtype
+    _require(k, "k", (N, H, dk), io, dev)
+    _require(v, "v", (N, H, dv), io, dev)
+    _require(log_alpha, "log_alpha", (N, H, dk), torch.float32, dev)
+    if log_beta_t is None:
+        raise ValueError("log_beta_t is required")
+    _require(log_beta_t, "log_beta_t", (N, H, dv), torch.float32, dev)
+    _require(beta, "beta", (N, H, dv), torch.float32, dev)
+    _require(S, "S", (N, H, dk, dv), torch.float32, dev)
+    if o is None:
+        o = torch.empty((N, H, dv), dtype=io, device=dev)
+    _require(o, "o", (N, H, dv), io, dev)
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_decode_step_general(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(log_beta_t), _ptr(beta),
+                                                 _ptr(S), _ptr(o), N, H, dk, dv, _DTYPES[io], _stream(dev)))
     return o
 
 

@@ -211,3 +211,11 @@ def make_gated_scan_inputs(B: int, T: int, H: int, dk: int, dv: int, io_dtype: s
     d["v"] = _io(rng.standard_normal((B, T, H, dv), dtype=np.float32), io_dtype)
     d["S0"] = torch.from_numpy((rng.standard_normal((B, H, dk, dv), dtype=np.float32) * np.float32(s0_std))) if s0_std > 0 else None
     return d
+
+
+def make_value_transition_gate(shape: tuple, seed: int = 18, mean: float = -3.0) -> torch.Tensor:
+    """log of a transition gate along the value dimension (the beta_t of the general recurrence): -softplus(N(mean, 1)),
+    i.e. mostly weak decays (around 0.05 per step for mean = -3) with a tail of stronger ones; fp32, shape [..., dv]."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    z = rng.standard_normal(shape, dtype=np.float32) + np.float32(mean)
+    return torch.from_numpy((-_softplus(z)).astype(np.float32))

@@ -30,7 +30,8 @@ def test_every_declared_symbol_is_exported(L):
             "rodimus_chunk_scan_bwd", "rodimus_chunk_scan_bwd_workspace_bytes",
             "rodimus_chunk_scan_fwd_block", "rodimus_decode_step_block",
             "rodimus_short_conv_fwd", "rodimus_short_conv_step",
-            "rodimus_chunk_scan_fwd_gated", "rodimus_decode_step_gated"} <= declared
+            "rodimus_chunk_scan_fwd_gated", "rodimus_decode_step_gated",
+            "rodimus_chunk_scan_fwd_general", "rodimus_decode_step_general"} <= declared
     for name in declared:
         assert hasattr(L, name), name
 
@@ -226,6 +227,25 @@ def test_gated_calls_validation(L):
     assert need > 0
     assert scan(B=1, T=32768, H=16, dk=64, dv=256, chunk=64, io=rodimus.BF16, q=0x10000000, k=0x20000000, v=0x30000000,
                 zg=0x40000000, zt=0x50000000, zb=0x60000000, S0=None, o=0x80000000, S_T=None) == E_WS
+    assert scan(B=0) == OK and dec(N=0) == OK and scan(T=0, S_T=None) == OK
+
+
+def test_general_transition_calls_validation(L):
+    p = ctypes.c_void_p
+    f = lambda x: None if x is None else p(x)
+
+    def scan(la=0x40000, lb=0x48000, beta=0x50000, o=0x70000, S_T=0x80000, B=1, T=4, H=1, dk=16, dv=32, chunk=4, io=rodimus.F32):
+        return L.rodimus_chunk_scan_fwd_general(p(0x10000), p(0x20000), p(0x30000), f(la), f(lb), f(beta), p(0x60000), f(o),
+                                                f(S_T), B, T, H, dk, dv, chunk, io, None)
+
+    def dec(la=0x40000, lb=0x48000, beta=0x50000, S=0x100000, o=0x70000, N=2, H=2, dk=16, dv=32, io=rodimus.BF16):
+        return L.rodimus_decode_step_general(p(0x10000), p(0x20000), p(0x30000), f(la), f(lb), f(beta), f(S), f(o), N, H, dk,
+                                             dv, io, None)
+
+    assert scan(lb=None) == E_NULL and dec(lb=None) == E_NULL and scan(la=None) == E_NULL
+    assert scan(lb=0x48008) == E_ALIGN and dec(lb=0x48004) == E_ALIGN
+    assert scan(o=0x48000) == E_ALIAS and scan(S_T=0x48000) == E_ALIAS and dec(o=0x48000) == E_ALIAS and dec(S=0x48000) == E_ALIAS
+    assert scan(io=9) == E_DTYPE and scan(dk=0) == E_SHAPE and dec(dv=2) == E_SHAPE
     assert scan(B=0) == OK and dec(N=0) == OK and scan(T=0, S_T=None) == OK
 
 
