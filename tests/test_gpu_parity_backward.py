@@ -100,8 +100,9 @@ def test_layer_head_shape():
 
 
 def test_unsupported_shapes_are_refused():
-    x = torch.zeros(1, 4, 1, 16, device="cuda:0")
-    v = torch.zeros(1, 4, 1, 32, device="cuda:0")
+    # a state that neither kernel family holds: 128 x 256 in fp32 I/O (the token-by-token kernels keep it in LDS)
+    x = torch.zeros(1, 4, 1, 128, device="cuda:0")
+    v = torch.zeros(1, 4, 1, 256, device="cuda:0")
     with pytest.raises(rodimus.RodimusError) as e:
         rodimus.rodimus_chunk_scan_bwd(x, x, v, x, None, None, v)
     assert e.value.status == 2
