@@ -280,6 +280,28 @@ int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v,
 size_t rodimus_chunk_scan_bwd_workspace_bytes(int B, int T, int H, int dk, int dv, int io_dtype);
 
 /*
+ * Backward pass over a packed batch of sequences of different lengths (training on packed sequences; the backward of
+ * rodimus_chunk_scan_varlen_fwd with the value gate given as values): exactly rodimus_chunk_scan_bwd applied to every
+ * sequence, with the layouts of rodimus_chunk_scan_varlen_fwd:
+ *
+ *   q, k, log_alpha, dq, dk, dlog_alpha   [total_tokens,H,dk]          v, beta, d_o, dv, dbeta   [total_tokens,H,dv]
+ *   S0, dS_T, dS0                         [N,H,dk,dv] fp32             cu_seqlens   [N+1] int32, device (clamped as there)
+ *   workspace   rodimus_chunk_scan_varlen_bwd_workspace_bytes(...) bytes
+ *
+ * Same kernel families, NULL conventions, alignment, aliasing rules and status codes as rodimus_chunk_scan_bwd; an empty
+ * sequence gets dS0 = dS_T.
+ */
+int rodimus_chunk_scan_varlen_bwd(const void *q, const void *k, const void *v,
+                                  const float *log_alpha, const float *beta, const float *S0,
+                                  const void *d_o, const float *dS_T,
+                                  void *dq, void *dk, void *dv_out, float *dlog_alpha, float *dbeta, float *dS0,
+                                  const int *cu_seqlens, int N, int total_tokens,
+                                  int H, int dk_width, int dv, int io_dtype,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+
+size_t rodimus_chunk_scan_varlen_bwd_workspace_bytes(int N, int total_tokens, int H, int dk, int dv, int io_dtype);
+
+/*
  * The two recurrence calls with the whole DDTS gate front-end fused in (paper Sec. 3.1.2 and the pre-processing of q and k
  * in Sec. 3.1.3; the block's state-space form of Sec. 3.1.3 evaluated straight from the projections): every gate arrives
  * as its pre-activation and q, k arrive raw.  Per token and head, inside the kernels, in fp32:

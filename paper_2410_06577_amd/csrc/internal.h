@@ -197,19 +197,35 @@ struct ScanBwdArgs {
     const float *dS_T;
     void *dq, *dk, *dv;
     float *dlog_alpha, *dbeta, *dS0;
-    int B, T, H, dk_width, dv_width;
+    int B, T, H, dk_width, dv_width;      // with cu_seqlens: B sequences, T = total tokens of the packed batch
     int io_dtype;
     void *workspace;
     size_t workspace_bytes;
     hipStream_t stream;
+    const int *cu_seqlens = nullptr;      // device, B + 1 entries, or NULL for the dense [B, T, H, .] layout
+    size_t token_rows() const { return cu_seqlens != nullptr ? (size_t)T : (size_t)B * T; }
 };
+
+// Where sequence b of a batch lives in the [tokens, H, .] tensors: dense (b * T, T), or from the length table of a
+// packed batch, clamped to the tensor so that a corrupt table cannot take an access outside it.
+struct SeqSpan {
+    size_t first;
+    int length;
+};
+__device__ __forceinline__ SeqSpan seq_span(int b, int T, const int *cu_seqlens)
+{
+    if (cu_seqlens == nullptr) return SeqSpan{(size_t)b * T, T};
+    const int lo = min(max(cu_seqlens[b], 0), T);
+    const int hi = min(max(cu_seqlens[b + 1], lo), T);
+    return SeqSpan{(size_t)lo, hi - lo};
+}
 
 hipError_t launch_scan_bwd(const ScanBwdArgs &a);
 hipError_t launch_scan_bwd_generic(const ScanBwdArgs &a);       // any other supported shape: fp32 on the vector ALUs
 bool scan_bwd_generic_supports(int dk, int dv);
-size_t scan_bwd_generic_workspace_bytes(int B, int T, int H, int dk);
+size_t scan_bwd_generic_workspace_bytes(size_t token_rows, int B, int H, int dk);
 bool scan_bwd_supports(int dk, int dv, int io_dtype);
-size_t scan_bwd_workspace_bytes(int B, int T, int H);
+size_t scan_bwd_workspace_bytes(size_t token_rows, int B, int H);
 hipError_t launch_decode_step(const DecodeArgs &a);
 hipError_t launch_ddts_gates(const GateArgs &a);
 

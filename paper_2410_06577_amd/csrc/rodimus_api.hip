@@ -262,39 +262,48 @@ int rodimus_decode_step_general(const void *q, const void *k, const void *v, con
                         OutputStage{nullptr, nullptr, nullptr, 0}, false, nullptr, nullptr, true, log_beta_t);
 }
 
-size_t rodimus_chunk_scan_bwd_workspace_bytes(int B, int T, int H, int dk, int dv, int io_dtype)
+}  // extern "C"
+
+namespace {
+
+size_t bwd_workspace(size_t token_rows, int B, int H, int dk, int dv, int io_dtype)
 {
-    if (B < 0 || T < 0 || H < 0 || (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16)) return 0;
-    if (scan_bwd_supports(dk, dv, io_dtype)) return scan_bwd_workspace_bytes(B, T, H);
-    return scan_bwd_generic_supports(dk, dv) ? scan_bwd_generic_workspace_bytes(B, T, H, dk) : 0;
+    if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return 0;
+    if (scan_bwd_supports(dk, dv, io_dtype)) return scan_bwd_workspace_bytes(token_rows, B, H);
+    return scan_bwd_generic_supports(dk, dv) ? scan_bwd_generic_workspace_bytes(token_rows, B, H, dk) : 0;
 }
 
-int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta,
-                           const float *S0, const void *d_o, const float *dS_T, void *dq, void *dk, void *dv_out,
-                           float *dlog_alpha, float *dbeta, float *dS0, int B, int T, int H, int dk_width, int dv,
-                           int io_dtype, void *workspace, size_t workspace_bytes, void *stream)
+// Dense layout: B sequences of T tokens.  Packed (`packed`): B sequences, T tokens in total, lengths in cu_seqlens (device).
+int bwd_entry(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta, const float *S0,
+              const void *d_o, const float *dS_T, void *dq, void *dk, void *dv_out, float *dlog_alpha, float *dbeta, float *dS0,
+              int B, int T, int H, int dk_width, int dv, int io_dtype, void *workspace, size_t workspace_bytes, void *stream,
+              bool packed, const int *cu_seqlens)
 {
     if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
     if (B < 0 || T < 0 || H < 0 || (long long)B * H > kMaxGridX) return RODIMUS_ERR_SHAPE;
     if ((long long)T * H > kMaxGridX) return RODIMUS_ERR_SHAPE;          // the kernels index a sequence's rows in 32 bits
     const bool mfma = scan_bwd_supports(dk_width, dv, io_dtype);
     if (!mfma && !scan_bwd_generic_supports(dk_width, dv)) return RODIMUS_ERR_SHAPE;
-    const size_t tokens = (size_t)B * T * H, states = (size_t)B * H;
+    if (packed && B > 0 && cu_seqlens == nullptr) return RODIMUS_ERR_NULL;
+    if (packed && misaligned(cu_seqlens)) return RODIMUS_ERR_ALIGN;
+    const size_t token_rows = packed ? (size_t)T : (size_t)B * T;
+    const size_t tokens = token_rows * H, states = (size_t)B * H;
     if (tokens > 0 && (!q || !k || !v || !log_alpha || !d_o || !dq || !dk || !dv_out || !dlog_alpha)) return RODIMUS_ERR_NULL;
     const size_t eb = elem_bytes(io_dtype);
-    const void *ins[8] = {q, k, v, log_alpha, beta, S0, d_o, dS_T};
-    const size_t in_bytes[8] = {tokens * dk_width * eb, tokens * dk_width * eb, tokens * dv * eb, tokens * dk_width * 4,
-                                tokens * dv * 4, states * dk_width * dv * 4, tokens * dv * eb, states * dk_width * dv * 4};
+    const void *ins[9] = {q, k, v, log_alpha, beta, S0, d_o, dS_T, packed ? cu_seqlens : nullptr};
+    const size_t in_bytes[9] = {tokens * dk_width * eb, tokens * dk_width * eb, tokens * dv * eb, tokens * dk_width * 4,
+                                tokens * dv * 4, states * dk_width * dv * 4, tokens * dv * eb, states * dk_width * dv * 4,
+                                packed ? ((size_t)B + 1) * sizeof(int) : 0};
     void *outs[7] = {dq, dk, dv_out, dlog_alpha, dbeta, dS0, workspace};
-    const size_t need = mfma ? scan_bwd_workspace_bytes(B, T, H) : scan_bwd_generic_workspace_bytes(B, T, H, dk_width);
+    const size_t need = bwd_workspace(token_rows, B, H, dk_width, dv, io_dtype);
     const size_t out_bytes[7] = {tokens * dk_width * eb, tokens * dk_width * eb, tokens * dv * eb, tokens * dk_width * 4,
                                  tokens * dv * 4, states * dk_width * dv * 4, need};
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 9; ++i)
         if (misaligned(ins[i])) return RODIMUS_ERR_ALIGN;
     for (int o = 0; o < 7; ++o)
         if (misaligned(outs[o])) return RODIMUS_ERR_ALIGN;
     for (int o = 0; o < 7; ++o) {
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < 9; ++i)
             if (overlaps(outs[o], out_bytes[o], ins[i], in_bytes[i])) return RODIMUS_ERR_ALIAS;
         for (int p = o + 1; p < 7; ++p)
             if (overlaps(outs[o], out_bytes[o], outs[p], out_bytes[p])) return RODIMUS_ERR_ALIAS;
@@ -303,7 +312,42 @@ int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v, const fl
 
     ScanBwdArgs a{q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, dk, dv_out, dlog_alpha, dbeta, dS0, B, T, H, dk_width, dv,
                   io_dtype, workspace, workspace_bytes, static_cast<hipStream_t>(stream)};
+    if (packed) a.cu_seqlens = cu_seqlens;
     return (mfma ? launch_scan_bwd(a) : launch_scan_bwd_generic(a)) == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t rodimus_chunk_scan_bwd_workspace_bytes(int B, int T, int H, int dk, int dv, int io_dtype)
+{
+    if (B < 0 || T < 0 || H < 0) return 0;
+    return bwd_workspace((size_t)B * T, B, H, dk, dv, io_dtype);
+}
+
+size_t rodimus_chunk_scan_varlen_bwd_workspace_bytes(int N, int total_tokens, int H, int dk, int dv, int io_dtype)
+{
+    if (N < 0 || total_tokens < 0 || H < 0) return 0;
+    return bwd_workspace((size_t)total_tokens, N, H, dk, dv, io_dtype);
+}
+
+int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta,
+                           const float *S0, const void *d_o, const float *dS_T, void *dq, void *dk, void *dv_out,
+                           float *dlog_alpha, float *dbeta, float *dS0, int B, int T, int H, int dk_width, int dv,
+                           int io_dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return bwd_entry(q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, dk, dv_out, dlog_alpha, dbeta, dS0, B, T, H, dk_width, dv,
+                     io_dtype, workspace, workspace_bytes, stream, false, nullptr);
+}
+
+int rodimus_chunk_scan_varlen_bwd(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta,
+                                  const float *S0, const void *d_o, const float *dS_T, void *dq, void *dk, void *dv_out,
+                                  float *dlog_alpha, float *dbeta, float *dS0, const int *cu_seqlens, int N, int total_tokens,
+                                  int H, int dk_width, int dv, int io_dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return bwd_entry(q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, dk, dv_out, dlog_alpha, dbeta, dS0, N, total_tokens, H,
+                     dk_width, dv, io_dtype, workspace, workspace_bytes, stream, true, cu_seqlens);
 }
 
 int rodimus_ddts_gates(const void *z_g, const void *z_tau, const void *z_beta, const void *q, const void *k,

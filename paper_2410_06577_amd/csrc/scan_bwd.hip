@@ -80,10 +80,10 @@ struct BwdGeometry {
     const float *la, *beta;
     int T, H;
     __device__ BwdGeometry(const bf16_t *q_, const bf16_t *k_, const bf16_t *v_, const bf16_t *do_, const float *la_,
-                           const float *beta_, int b, int h, int T_, int H_, int dv)
+                           const float *beta_, size_t first_token, int h, int T_, int H_, int dv)
         : T(T_), H(H_)
     {
-        const size_t row0 = ((size_t)b * T_) * H_ + h;
+        const size_t row0 = first_token * H_ + h;
         q = q_ + row0 * kK; k = k_ + row0 * kK; la = la_ + row0 * kK;
         v = v_ + row0 * dv; d_o = do_ + row0 * dv;
         beta = beta_ != nullptr ? beta_ + row0 * dv : nullptr;
@@ -183,7 +183,7 @@ __device__ __forceinline__ void sweep_dq(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const float *__restrict__ log_alpha, const float *__restrict__ beta, const float *__restrict__ S0,
     const bf16_t *__restrict__ d_o, const float *__restrict__ dS_T, bf16_t *__restrict__ dq,
-    float *__restrict__ qdq, float *__restrict__ gate_const, int T, int H)
+    float *__restrict__ qdq, float *__restrict__ gate_const, int T, int H, const int *__restrict__ cu_seqlens)
 {
     using L = BwdLayout<DV>;
     constexpr int kColTiles = DV / 16, kSteps = DV / 32;
@@ -202,8 +202,10 @@ __device__ __forceinline__ void sweep_dq(
     const int ch = 16 * (wave & 3) + c;
     const int bh = blockIdx.x;
     const bool has_beta = beta != nullptr;
-    const BwdGeometry g(q, k, v, d_o, log_alpha, beta, bh / H, bh % H, T, H, DV);
-    const size_t row0 = ((size_t)(bh / H) * T) * H + bh % H;      // outputs: same layout as the inputs
+    const SeqSpan span = seq_span(bh / H, T, cu_seqlens);
+    T = span.length;
+    const BwdGeometry g(q, k, v, d_o, log_alpha, beta, span.first, bh % H, T, H, DV);
+    const size_t row0 = span.first * H + bh % H;                  // outputs: same layout as the inputs
 
     // state slab, transposed: acc[ct][r] = S[ch][16ct + 4tg + r]
     floatx4_t acc[kColTiles];
@@ -401,7 +403,7 @@ __device__ __forceinline__ void sweep_dkv(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const float *__restrict__ log_alpha, const float *__restrict__ beta, const bf16_t *__restrict__ d_o,
     const float *__restrict__ dS_T, bf16_t *__restrict__ dk, bf16_t *__restrict__ dv, float *__restrict__ kdk,
-    float *__restrict__ dbeta, float *__restrict__ dS0, int T, int H)
+    float *__restrict__ dbeta, float *__restrict__ dS0, int T, int H, const int *__restrict__ cu_seqlens)
 {
     using L = BwdLayout<DV>;
     constexpr int kWaves = BwdShape<DV>::kWaves;     // 4 (dv = 128) or 8 (dv = 256)
@@ -433,8 +435,10 @@ __device__ __forceinline__ void sweep_dkv(
     const int n = lane & 15, grp = lane >> 4;
     const int bh = blockIdx.x;
     const bool has_beta = beta != nullptr;
-    const BwdGeometry g(q, k, v, d_o, log_alpha, beta, bh / H, bh % H, T, H, DV);
-    const size_t row0 = ((size_t)(bh / H) * T) * H + bh % H;      // outputs: same layout as the inputs
+    const SeqSpan span = seq_span(bh / H, T, cu_seqlens);
+    T = span.length;
+    const BwdGeometry g(q, k, v, d_o, log_alpha, beta, span.first, bh % H, T, H, DV);
+    const size_t row0 = span.first * H + bh % H;                  // outputs: same layout as the inputs
     const int col0 = wave * kSlab;
 
     // cotangent slab: acc[kt][ct][r] = G[16kt + 4grp + r][col0 + 16ct + n]
@@ -720,9 +724,9 @@ __device__ __forceinline__ void sweep_dkv(
 }  // namespace
 
 // q .* dq and k .* dk in fp32 for every (token, head, channel), and rowsum(S_T .* dS_T) per (batch, head, channel)
-size_t scan_bwd_workspace_bytes(int B, int T, int H)
+size_t scan_bwd_workspace_bytes(size_t token_rows, int B, int H)
 {
-    return (2 * (size_t)B * T * H * kK + (size_t)B * H * kK) * sizeof(float);
+    return (2 * token_rows * H * kK + (size_t)B * H * kK) * sizeof(float);
 }
 
 bool scan_bwd_supports(int dk, int dv, int io_dtype)
@@ -740,12 +744,12 @@ __global__ __launch_bounds__(BwdShape<DV>::kThreads) void scan_bwd_sweeps_kernel
     const float *__restrict__ log_alpha, const float *__restrict__ beta, const float *__restrict__ S0,
     const bf16_t *__restrict__ d_o, const float *__restrict__ dS_T, bf16_t *__restrict__ dq, bf16_t *__restrict__ dk,
     bf16_t *__restrict__ dv, float *__restrict__ dbeta, float *__restrict__ dS0, float *__restrict__ qdq,
-    float *__restrict__ kdk, float *__restrict__ gate_const, int T, int H)
+    float *__restrict__ kdk, float *__restrict__ gate_const, int T, int H, const int *__restrict__ cu_seqlens)
 {
     if (blockIdx.y == 0)
-        sweep_dq<DV>(q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, qdq, gate_const, T, H);
+        sweep_dq<DV>(q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, qdq, gate_const, T, H, cu_seqlens);
     else
-        sweep_dkv<DV>(q, k, v, log_alpha, beta, d_o, dS_T, dk, dv, kdk, dbeta, dS0, T, H);
+        sweep_dkv<DV>(q, k, v, log_alpha, beta, d_o, dS_T, dk, dv, kdk, dbeta, dS0, T, H, cu_seqlens);
 }
 
 // dlog_alpha_t = gate_const + sum_{s >= t} (q_s .* dq_s - k_s .* dk_s), zero for a closed gate.  One workgroup per
@@ -755,12 +759,14 @@ constexpr int kGateParts = 32;
 __global__ __launch_bounds__(1024) void scan_bwd_gate_kernel(const float *__restrict__ qdq, const float *__restrict__ kdk,
                                                              const float *__restrict__ gate_const,
                                                              const float *__restrict__ log_alpha, float *__restrict__ dla,
-                                                             int T, int H)
+                                                             int T, int H, const int *__restrict__ cu_seqlens)
 {
     __shared__ float tot_s[kGateParts][32];
     const int tid = threadIdx.x, c = tid & 31, part = tid >> 5;
     const int bh = blockIdx.x, ch = 32 * blockIdx.y + c;
-    const size_t tok0 = (size_t)(bh / H) * T;
+    const SeqSpan span = seq_span(bh / H, T, cu_seqlens);
+    T = span.length;
+    const size_t tok0 = span.first;
     const int h = bh % H;
     const int len = (T + kGateParts - 1) / kGateParts;
     const int t_lo = min(part * len, T), t_hi = min(t_lo + len, T);
@@ -786,7 +792,7 @@ template <int DV>
 hipError_t launch_scan_bwd_typed(const ScanBwdArgs &a)
 {
     const unsigned bh = (unsigned)(a.B * a.H);
-    const size_t rows = (size_t)a.B * a.T * a.H * kK;
+    const size_t rows = a.token_rows() * a.H * kK;
     float *qdq = static_cast<float *>(a.workspace);
     float *kdk = qdq + rows;
     float *gate_const = kdk + rows;
@@ -796,10 +802,10 @@ hipError_t launch_scan_bwd_typed(const ScanBwdArgs &a)
     hipLaunchKernelGGL(scan_bwd_sweeps_kernel<DV>, dim3(bh, 2), dim3(BwdShape<DV>::kThreads), DkvLds<DV>::kBytes, a.stream,
                        (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0,
                        (const bf16_t *)a.d_o, a.dS_T, (bf16_t *)a.dq, (bf16_t *)a.dk, (bf16_t *)a.dv, a.dbeta, a.dS0, qdq, kdk,
-                       gate_const, a.T, a.H);
+                       gate_const, a.T, a.H, a.cu_seqlens);
     if (a.T > 0)
         hipLaunchKernelGGL(scan_bwd_gate_kernel, dim3(bh, 2), dim3(1024), 0, a.stream, qdq, kdk, gate_const, a.log_alpha,
-                           a.dlog_alpha, a.T, a.H);
+                           a.dlog_alpha, a.T, a.H, a.cu_seqlens);
     return hipGetLastError();
 }
 

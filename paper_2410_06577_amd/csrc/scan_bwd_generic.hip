@@ -24,6 +24,7 @@ constexpr int kGenMaxStateFloats = 32768;        // dk * (dv + 1) floats of LDS 
 
 struct GenShape {
     int T, H, dk, dv;
+    const int *cu_seqlens;      // packed batch (T = total tokens), or null
 };
 
 // LDS: state [dk][dv + 1] (padded rows: a row reduction walks along the row, a column reduction down the column),
@@ -40,7 +41,9 @@ __global__ __launch_bounds__(kGenThreads) void scan_bwd_generic_dq_kernel(
     const int dk = sh.dk, dv = sh.dv, dvp = dv + 1;
     float *S = lds, *sq = S + dk * dvp, *skk = sq + dk, *sa = skk + dk, *su = sa + dk, *sdo = su + dv;
     const int tid = threadIdx.x, bh = blockIdx.x;
-    const size_t row0 = ((size_t)(bh / sh.H) * sh.T) * sh.H + bh % sh.H;
+    const SeqSpan span = seq_span(bh / sh.H, sh.T, sh.cu_seqlens);
+    sh.T = span.length;
+    const size_t row0 = span.first * sh.H + bh % sh.H;
     const size_t state0 = (size_t)bh * dk * dv;
     const int elems = dk * dv;
 
@@ -94,7 +97,9 @@ __global__ __launch_bounds__(kGenThreads) void scan_bwd_generic_dkv_kernel(
     float *G = lds, *sq = G + dk * dvp, *skk = sq + dk, *sa = skk + dk, *su = sa + dk, *sdo = su + dv, *sv = sdo + dv;
     float *run = sv + dv;                       // [dk] reverse running sum behind dlog_alpha
     const int tid = threadIdx.x, bh = blockIdx.x;
-    const size_t row0 = ((size_t)(bh / sh.H) * sh.T) * sh.H + bh % sh.H;
+    const SeqSpan span = seq_span(bh / sh.H, sh.T, sh.cu_seqlens);
+    sh.T = span.length;
+    const size_t row0 = span.first * sh.H + bh % sh.H;
     const size_t state0 = (size_t)bh * dk * dv;
     const int elems = dk * dv;
 
@@ -162,8 +167,8 @@ hipError_t launch_typed(const ScanBwdArgs &a)
     if (err != hipSuccess) return err;
     const unsigned bh = (unsigned)(a.B * a.H);
     float *qdq = static_cast<float *>(a.workspace);
-    float *gate_const = qdq + (size_t)a.B * a.T * a.H * dk;
-    const GenShape sh{a.T, a.H, dk, dv};
+    float *gate_const = qdq + a.token_rows() * a.H * dk;
+    const GenShape sh{a.T, a.H, dk, dv, a.cu_seqlens};
     hipLaunchKernelGGL(scan_bwd_generic_dq_kernel<IO>, dim3(bh), dim3(kGenThreads), lds, a.stream, (const IO *)a.q,
                        (const IO *)a.k, (const IO *)a.v, a.log_alpha, a.beta, a.S0, (const IO *)a.d_o, a.dS_T, (IO *)a.dq, qdq,
                        gate_const, sh);
@@ -181,9 +186,9 @@ bool scan_bwd_generic_supports(int dk, int dv)
 }
 
 // q .* dq in fp32 for every (token, head, channel) and rowsum(S_T .* dS_T) per (batch, head, channel)
-size_t scan_bwd_generic_workspace_bytes(int B, int T, int H, int dk)
+size_t scan_bwd_generic_workspace_bytes(size_t token_rows, int B, int H, int dk)
 {
-    return ((size_t)B * T * H * dk + (size_t)B * H * dk) * sizeof(float);
+    return (token_rows * H * dk + (size_t)B * H * dk) * sizeof(float);
 }
 
 hipError_t launch_scan_bwd_generic(const ScanBwdArgs &a)

@@ -57,6 +57,10 @@ def lib() -> ctypes.CDLL:
         L.rodimus_chunk_scan_bwd.restype = i
         L.rodimus_chunk_scan_bwd_workspace_bytes.argtypes = [i] * 6
         L.rodimus_chunk_scan_bwd_workspace_bytes.restype = sz
+        L.rodimus_chunk_scan_varlen_bwd.argtypes = [vp] * 15 + [i] * 6 + [vp, sz, vp]
+        L.rodimus_chunk_scan_varlen_bwd.restype = i
+        L.rodimus_chunk_scan_varlen_bwd_workspace_bytes.argtypes = [i] * 6
+        L.rodimus_chunk_scan_varlen_bwd_workspace_bytes.restype = sz
         L.rodimus_chunk_scan_fwd_block.argtypes = [vp] * 5 + [i] + [vp] * 4 + [i] + [vp] * 2 + [i] * 7 + [vp, sz, vp]
         L.rodimus_chunk_scan_fwd_block.restype = i
         L.rodimus_decode_step_block.argtypes = [vp] * 5 + [i] + [vp] * 3 + [i] + [vp] * 2 + [i] * 5 + [vp]
@@ -159,6 +163,42 @@ def rodimus_chunk_scan_fwd(q, k, v, log_alpha, beta=None, S0=None, *, chunk=64, 
 def rodimus_chunk_scan_fwd_zbeta(q, k, v, log_alpha, z_beta, S0=None, **kw):
     """``rodimus_chunk_scan_fwd`` with the value gate given as its pre-activation z_beta [B,T,H,dv] (dtype of v)."""
     return rodimus_chunk_scan_fwd(q, k, v, log_alpha, z_beta, S0, _preact=True, **kw)
+
+
+def rodimus_chunk_scan_varlen_bwd(q, k, v, log_alpha, cu_seqlens, beta, S0, d_o, dS_T=None, *, want_dbeta=True, want_dS0=True,
+                                  workspace=None):
+    """Backward over a packed variable-length batch.  q, k, log_alpha [total,H,dk]; v, beta, d_o [total,H,dv];
+    S0, dS_T [N,H,dk,dv] fp32; cu_seqlens [N+1] int32 on the device.  Returns the same dict as ``rodimus_chunk_scan_bwd``."""
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_chunk_scan_varlen_bwd needs device tensors (no CPU path exists)")
+    total, H, dk = q.shape
+    dv = v.shape[-1]
+    dev, io = q.device, q.dtype
+    N = cu_seqlens.numel() - 1
+    _require(cu_seqlens, "cu_seqlens", (N + 1,), torch.int32, dev)
+    _require(k, "k", (total, H, dk), io, dev)
+    _require(v, "v", (total, H, dv), io, dev)
+    _require(log_alpha, "log_alpha", (total, H, dk), torch.float32, dev)
+    _require(beta, "beta", (total, H, dv), torch.float32, dev)
+    _require(S0, "S0", (N, H, dk, dv), torch.float32, dev)
+    _require(d_o, "d_o", (total, H, dv), io, dev)
+    _require(dS_T, "dS_T", (N, H, dk, dv), torch.float32, dev)
+    out = {"dq": torch.empty_like(q), "dk": torch.empty_like(k), "dv": torch.empty_like(v),
+           "dlog_alpha": torch.empty_like(log_alpha),
+           "dbeta": torch.empty((total, H, dv), dtype=torch.float32, device=dev) if want_dbeta else None,
+           "dS0": torch.empty((N, H, dk, dv), dtype=torch.float32, device=dev) if want_dS0 else None}
+    need = int(lib().rodimus_chunk_scan_varlen_bwd_workspace_bytes(N, total, H, dk, dv, _DTYPES[io]))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_chunk_scan_varlen_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(S0), _ptr(d_o),
+                                                   _ptr(dS_T), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]),
+                                                   _ptr(out["dlog_alpha"]), _ptr(out["dbeta"]), _ptr(out["dS0"]), _ptr(cu_seqlens),
+                                                   N, total, H, dk, dv, _DTYPES[io], _ptr(workspace), ws_bytes, _stream(dev)))
+    return out
 
 
 def rodimus_chunk_scan_fwd_gated(q, k, v, z_g, z_tau, z_beta=None, S0=None, *, chunk=64, o=None, S_T=None,

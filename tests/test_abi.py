@@ -31,7 +31,8 @@ def test_every_declared_symbol_is_exported(L):
             "rodimus_chunk_scan_fwd_block", "rodimus_decode_step_block",
             "rodimus_short_conv_fwd", "rodimus_short_conv_step",
             "rodimus_chunk_scan_fwd_gated", "rodimus_decode_step_gated",
-            "rodimus_chunk_scan_fwd_general", "rodimus_decode_step_general"} <= declared
+            "rodimus_chunk_scan_fwd_general", "rodimus_decode_step_general",
+            "rodimus_chunk_scan_varlen_bwd", "rodimus_chunk_scan_varlen_bwd_workspace_bytes"} <= declared
     for name in declared:
         assert hasattr(L, name), name
 
@@ -273,6 +274,27 @@ def test_short_conv_validation(L):
     assert fwd(y=0x100000) == E_ALIAS and fwd(so=0x400000) == E_ALIAS and fwd(so=0x100000) == E_ALIAS
     assert fwd(y=0x600000) == E_ALIAS and step(y=0x400000) == E_ALIAS
     assert fwd(B=0) == OK and fwd(C=0) == OK and fwd(T=0, so=None) == OK and step(N=0) == OK
+
+
+def test_packed_backward_validation(L):
+    p = ctypes.c_void_p
+    names = ["q", "k", "v", "la", "beta", "S0", "d_o", "dS_T", "dq", "dk_out", "dv_out", "dla", "dbeta", "dS0", "cu", "ws"]
+    base = {n: 0x100000 * (i + 1) for i, n in enumerate(names)}
+
+    def call(N=2, total=10, H=1, dk=64, dv=128, io=rodimus.BF16, ws_bytes=None, **over):
+        a = dict(base)
+        a.update(over)
+        f = lambda x: None if x is None else p(x)
+        need = L.rodimus_chunk_scan_varlen_bwd_workspace_bytes(N, total, H, dk, dv, io)
+        return L.rodimus_chunk_scan_varlen_bwd(*[f(a[n]) for n in names[:15]], N, total, H, dk, dv, io, f(a["ws"]),
+                                               need if ws_bytes is None else ws_bytes, None)
+
+    assert L.rodimus_chunk_scan_varlen_bwd_workspace_bytes(3, 100, 2, 64, 128, rodimus.BF16) == (2 * 100 * 2 * 64 + 3 * 2 * 64) * 4
+    assert L.rodimus_chunk_scan_varlen_bwd_workspace_bytes(3, 100, 2, 16, 32, rodimus.F32) == (100 * 2 * 16 + 3 * 2 * 16) * 4
+    assert call(cu=None) == E_NULL and call(cu=base["cu"] + 4) == E_ALIGN and call(q=None) == E_NULL
+    assert call(dq=base["cu"]) == E_ALIAS and call(ws=base["cu"]) == E_ALIAS
+    assert call(ws_bytes=16) == E_WS and call(io=7) == E_DTYPE and call(dk=0) == E_SHAPE and call(total=-1) == E_SHAPE
+    assert call(N=0, total=0, cu=None) == OK
 
 
 def test_empty_problems_are_successful_noops(L):
