@@ -39,7 +39,12 @@ template <int DV> struct BwdShape {
     static constexpr int kThreads = 64 * kWaves;
 };
 constexpr float kMinLogAlpha = -128.f;
-constexpr float kSafeTileLog = -55.f;      // ln(2^-80) = -55.45: above it 1 / A_i stays below 2^80
+constexpr float kSafeTileLog = -55.f;
+// The gate cotangent is a reverse running sum over the sequence; the sequence is cut into kGateParts runs of whole
+// tiles, the sweeps leave the sum of q .* dq (k .* dk) over every run, and the gate kernel starts each run from the
+// totals of the later ones.
+constexpr int kGateParts = 32;
+__host__ __device__ inline int gate_part_tiles(int T) { return (((T + kTile - 1) / kTile) + kGateParts - 1) / kGateParts; }      // ln(2^-80) = -55.45: above it 1 / A_i stays below 2^80
 
 // Value columns are stored in LDS in a permuted order inside every group of 32: column 32s + 16h + 4g + e sits at
 // position 32s + 8g + 4h + e.  A 16-byte read at position 32s + 8g then delivers exactly the 8 columns that lane
@@ -183,7 +188,8 @@ __device__ __forceinline__ void sweep_dq(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const float *__restrict__ log_alpha, const float *__restrict__ beta, const float *__restrict__ S0,
     const bf16_t *__restrict__ d_o, const float *__restrict__ dS_T, bf16_t *__restrict__ dq,
-    float *__restrict__ qdq, float *__restrict__ gate_const, int T, int H, const int *__restrict__ cu_seqlens)
+    float *__restrict__ qdq, float *__restrict__ gate_const, float *__restrict__ qtot, int T, int H,
+    const int *__restrict__ cu_seqlens)
 {
     using L = BwdLayout<DV>;
     constexpr int kColTiles = DV / 16, kSteps = DV / 32;
@@ -216,6 +222,9 @@ __device__ __forceinline__ void sweep_dq(
                                               : floatx4_t{0.f, 0.f, 0.f, 0.f};
 
     const int ntiles = (T + kTile - 1) / kTile;
+    const int part_tiles = gate_part_tiles(T);
+    int run_index = 0, run_last = part_tiles - 1;      // the current run of tiles and its last tile
+    float qpart = 0.f;                                 // sum of q .* dq over this lane's tokens of the current run of tiles
     TileLoads<DV> pf;
     if (ntiles > 0) tile_prefetch<DV>(g, 0, tid, has_beta, pf);
 
@@ -344,7 +353,18 @@ __device__ __forceinline__ void sweep_dq(
             }
             const float val = fmaf(__expf(lt[r]), dqt[r], intra);
             dq_s[t * kK + ch] = (bf16_t)val;
-            qdq_s[t * kK + ch] = qs[t * kK + ch] * val;
+            const float qd = qs[t * kK + ch] * val;        // zero for rows beyond the sequence (q is staged as zero)
+            qdq_s[t * kK + ch] = qd;
+            qpart += qd;
+        }
+        if (it == run_last || it == ntiles - 1) {          // the run ends: its total over the four token groups
+            float x = qpart;
+            x += __shfl_xor(x, 16);
+            x += __shfl_xor(x, 32);
+            if (tg == 0) qtot[((size_t)bh * kGateParts + run_index) * kK + ch] = x;
+            qpart = 0.f;
+            ++run_index;
+            run_last += part_tiles;
         }
     }
     __syncthreads();
@@ -403,7 +423,8 @@ __device__ __forceinline__ void sweep_dkv(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const float *__restrict__ log_alpha, const float *__restrict__ beta, const bf16_t *__restrict__ d_o,
     const float *__restrict__ dS_T, bf16_t *__restrict__ dk, bf16_t *__restrict__ dv, float *__restrict__ kdk,
-    float *__restrict__ dbeta, float *__restrict__ dS0, int T, int H, const int *__restrict__ cu_seqlens)
+    float *__restrict__ dbeta, float *__restrict__ dS0, float *__restrict__ ktot, int T, int H,
+    const int *__restrict__ cu_seqlens)
 {
     using L = BwdLayout<DV>;
     constexpr int kWaves = BwdShape<DV>::kWaves;     // 4 (dv = 128) or 8 (dv = 256)
@@ -456,6 +477,10 @@ __device__ __forceinline__ void sweep_dkv(
     const int vc = tid & 63, vg = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     const int ntiles = (T + kTile - 1) / kTile;
+    const int part_tiles = gate_part_tiles(T);
+    int run_index = ntiles > 0 ? (ntiles - 1) / part_tiles : 0;      // the current run of tiles, walked from the last one back
+    int run_first = run_index * part_tiles;                           // its first tile (the last one in this direction)
+    float kpart = 0.f;                                 // sum of k .* dk over this thread's tokens of the current run of tiles
     TileLoads<DV> pf;
     auto prefetch = [&](int t0) { tile_prefetch<DV>(g, t0, tid, has_beta, pf); };
     if (ntiles > 0) prefetch((ntiles - 1) * kTile);
@@ -680,11 +705,19 @@ __device__ __forceinline__ void sweep_dkv(
                     intra = intra_s[i * kK + vc] * __expf(-l_i);
                 }
                 const float dk_val = khat_term + intra;
+                const float kd = ks[i * kK + vc] * dk_val;  // zero for rows beyond the sequence (k is staged as zero)
+                kpart += kd;
                 if (t0 + i < T) {                           // a wavefront writes whole rows
                     const size_t e = (row0 + (size_t)((unsigned)(t0 + i) * (unsigned)H)) * kK + vc;
                     dk[e] = (bf16_t)dk_val;
-                    kdk[e] = ks[i * kK + vc] * dk_val;
+                    kdk[e] = kd;
                 }
+            }
+            if (it == run_first) {                          // the run's first tile is its last in this direction
+                ktot[(((size_t)bh * kGateParts + run_index) * kWaves + vg) * kK + vc] = kpart;
+                kpart = 0.f;
+                --run_index;
+                run_first -= part_tiles;
             }
         }
         // dv = beta .* du, dbeta = v .* du: coalesced, by the thread that loaded the same pieces of v and beta
@@ -724,9 +757,10 @@ __device__ __forceinline__ void sweep_dkv(
 }  // namespace
 
 // q .* dq and k .* dk in fp32 for every (token, head, channel), and rowsum(S_T .* dS_T) per (batch, head, channel)
+// and the totals of both over kGateParts runs of the sequence (one per wavefront of the reverse sweep, at most 8)
 size_t scan_bwd_workspace_bytes(size_t token_rows, int B, int H)
 {
-    return (2 * token_rows * H * kK + (size_t)B * H * kK) * sizeof(float);
+    return (2 * token_rows * H * kK + (size_t)B * H * kK * (1 + kGateParts + 8 * kGateParts)) * sizeof(float);
 }
 
 bool scan_bwd_supports(int dk, int dv, int io_dtype)
@@ -744,22 +778,25 @@ __global__ __launch_bounds__(BwdShape<DV>::kThreads) void scan_bwd_sweeps_kernel
     const float *__restrict__ log_alpha, const float *__restrict__ beta, const float *__restrict__ S0,
     const bf16_t *__restrict__ d_o, const float *__restrict__ dS_T, bf16_t *__restrict__ dq, bf16_t *__restrict__ dk,
     bf16_t *__restrict__ dv, float *__restrict__ dbeta, float *__restrict__ dS0, float *__restrict__ qdq,
-    float *__restrict__ kdk, float *__restrict__ gate_const, int T, int H, const int *__restrict__ cu_seqlens)
+    float *__restrict__ kdk, float *__restrict__ gate_const, float *__restrict__ qtot, float *__restrict__ ktot, int T, int H,
+    const int *__restrict__ cu_seqlens)
 {
     if (blockIdx.y == 0)
-        sweep_dq<DV>(q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, qdq, gate_const, T, H, cu_seqlens);
+        sweep_dq<DV>(q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, qdq, gate_const, qtot, T, H, cu_seqlens);
     else
-        sweep_dkv<DV>(q, k, v, log_alpha, beta, d_o, dS_T, dk, dv, kdk, dbeta, dS0, T, H, cu_seqlens);
+        sweep_dkv<DV>(q, k, v, log_alpha, beta, d_o, dS_T, dk, dv, kdk, dbeta, dS0, ktot, T, H, cu_seqlens);
 }
 
 // dlog_alpha_t = gate_const + sum_{s >= t} (q_s .* dq_s - k_s .* dk_s), zero for a closed gate.  One workgroup per
-// (batch, head, half of the channels); thread = (channel, one of 32 contiguous parts of the sequence): part totals first,
-// then the running sum inside the part on top of the totals of the later parts.
-constexpr int kGateParts = 32;
+// (batch, head, half of the channels); thread = (channel, one of the kGateParts runs of tiles): the runs' totals come from
+// the sweeps (the reverse sweep leaves one per wavefront), then one pass over the run on top of the totals of the later
+// runs.
 __global__ __launch_bounds__(1024) void scan_bwd_gate_kernel(const float *__restrict__ qdq, const float *__restrict__ kdk,
                                                              const float *__restrict__ gate_const,
-                                                             const float *__restrict__ log_alpha, float *__restrict__ dla,
-                                                             int T, int H, const int *__restrict__ cu_seqlens)
+                                                             const float *__restrict__ qtot, const float *__restrict__ ktot,
+                                                             int ktot_waves, const float *__restrict__ log_alpha,
+                                                             float *__restrict__ dla, int T, int H,
+                                                             const int *__restrict__ cu_seqlens)
 {
     __shared__ float tot_s[kGateParts][32];
     const int tid = threadIdx.x, c = tid & 31, part = tid >> 5;
@@ -768,13 +805,13 @@ __global__ __launch_bounds__(1024) void scan_bwd_gate_kernel(const float *__rest
     T = span.length;
     const size_t tok0 = span.first;
     const int h = bh % H;
-    const int len = (T + kGateParts - 1) / kGateParts;
-    const int t_lo = min(part * len, T), t_hi = min(t_lo + len, T);
+    const int ntiles = (T + kTile - 1) / kTile, part_tiles = gate_part_tiles(T);
+    const int t_lo = min(part * part_tiles * kTile, T), t_hi = min(t_lo + part_tiles * kTile, T);
     float total = 0.f;
-#pragma unroll 8
-    for (int t = t_lo; t < t_hi; ++t) {
-        const size_t e = ((tok0 + t) * H + h) * kK + ch;
-        total += qdq[e] - kdk[e];
+    if (part * part_tiles < ntiles) {                  // runs beyond the sequence were never written
+        const size_t slot = (size_t)bh * kGateParts + part;
+        total = qtot[slot * kK + ch];
+        for (int w = 0; w < ktot_waves; ++w) total -= ktot[(slot * ktot_waves + w) * kK + ch];
     }
     tot_s[part][c] = total;
     __syncthreads();
@@ -796,15 +833,18 @@ hipError_t launch_scan_bwd_typed(const ScanBwdArgs &a)
     float *qdq = static_cast<float *>(a.workspace);
     float *kdk = qdq + rows;
     float *gate_const = kdk + rows;
+    float *qtot = gate_const + (size_t)bh * kK;                         // [B*H][kGateParts][64]
+    float *ktot = qtot + (size_t)bh * kGateParts * kK;                  // [B*H][kGateParts][wavefronts][64]
     hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_bwd_sweeps_kernel<DV>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, DkvLds<DV>::kBytes);
     if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL(scan_bwd_sweeps_kernel<DV>, dim3(bh, 2), dim3(BwdShape<DV>::kThreads), DkvLds<DV>::kBytes, a.stream,
                        (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0,
                        (const bf16_t *)a.d_o, a.dS_T, (bf16_t *)a.dq, (bf16_t *)a.dk, (bf16_t *)a.dv, a.dbeta, a.dS0, qdq, kdk,
-                       gate_const, a.T, a.H, a.cu_seqlens);
+                       gate_const, qtot, ktot, a.T, a.H, a.cu_seqlens);
     if (a.T > 0)
-        hipLaunchKernelGGL(scan_bwd_gate_kernel, dim3(bh, 2), dim3(1024), 0, a.stream, qdq, kdk, gate_const, a.log_alpha,
+        hipLaunchKernelGGL(scan_bwd_gate_kernel, dim3(bh, 2), dim3(1024), 0, a.stream, qdq, kdk, gate_const, qtot, ktot,
+                           BwdShape<DV>::kWaves, a.log_alpha,
                            a.dlog_alpha, a.T, a.H, a.cu_seqlens);
     return hipGetLastError();
 }

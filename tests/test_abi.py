@@ -190,7 +190,8 @@ def test_backward_validation(L):
     assert call(dq=base["q"]) == E_ALIAS and call(dv_out=base["d_o"]) == E_ALIAS and call(dk_out=base["dq"]) == E_ALIAS
     assert call(ws=base["dla"]) == E_ALIAS
     assert call(ws_bytes=16) == E_WS and call(ws=None) == E_WS
-    assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 64, 128, rodimus.BF16) == (2 * 2 * 100 * 3 * 64 + 2 * 3 * 64) * 4
+    # q .* dq and k .* dk per token, and per (batch, head, channel): one constant, 32 run totals of the first, 32 x 8 of the second
+    assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 64, 128, rodimus.BF16) == (2 * 2 * 100 * 3 * 64 + 2 * 3 * 64 * 289) * 4
     # any other shape takes the generic kernels: q .* dq only
     assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 32, 128, rodimus.BF16) == (2 * 100 * 3 * 32 + 2 * 3 * 32) * 4
     assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 64, 128, rodimus.F32) == (2 * 100 * 3 * 64 + 2 * 3 * 64) * 4
@@ -289,7 +290,7 @@ def test_packed_backward_validation(L):
         return L.rodimus_chunk_scan_varlen_bwd(*[f(a[n]) for n in names[:15]], N, total, H, dk, dv, io, f(a["ws"]),
                                                need if ws_bytes is None else ws_bytes, None)
 
-    assert L.rodimus_chunk_scan_varlen_bwd_workspace_bytes(3, 100, 2, 64, 128, rodimus.BF16) == (2 * 100 * 2 * 64 + 3 * 2 * 64) * 4
+    assert L.rodimus_chunk_scan_varlen_bwd_workspace_bytes(3, 100, 2, 64, 128, rodimus.BF16) == (2 * 100 * 2 * 64 + 3 * 2 * 64 * 289) * 4
     assert L.rodimus_chunk_scan_varlen_bwd_workspace_bytes(3, 100, 2, 16, 32, rodimus.F32) == (100 * 2 * 16 + 3 * 2 * 16) * 4
     assert call(cu=None) == E_NULL and call(cu=base["cu"] + 4) == E_ALIGN and call(q=None) == E_NULL
     assert call(dq=base["cu"]) == E_ALIAS and call(ws=base["cu"]) == E_ALIAS
