@@ -37,6 +37,10 @@ __device__ __forceinline__ float sigmoid_f(float z)
     return z >= 0.f ? r : e * r;
 }
 
+// The same without the branch on the sign: exp(-z) overflows to +inf for z < -88 and 1 / (1 + inf) = 0 is the right
+// limit; three instructions shorter, for the wavefronts on the critical path of the matrix-core scan.
+__device__ __forceinline__ float sigmoid_short(float z) { return __builtin_amdgcn_rcpf(1.f + __expf(-z)); }
+
 // log(1 + e) for e in [0, 1]; the series where 1 + e would round the information away
 __device__ __forceinline__ float log1p_unit(float e)
 {
@@ -47,13 +51,17 @@ __device__ __forceinline__ float log1p_unit(float e)
 // The two key-side DDTS gates of one channel (paper Sec. 3.1.2) from their pre-activations, with g = softplus(z_g) and
 // tau = sigmoid(z_tau):  log_alpha = -g * tau (the decay gate is exp of it), alpha_hat = g^tau (the input gate folded
 // into the key).  Hardware exp, log and reciprocal (about 1 ulp each).
+// kShortLog1p: log(1 + e) without the series for small e, and the sigmoid without its branch on the sign.  The absolute error of g stays below 1e-7, its relative error
+// grows to ~1e-3 only where g < 1e-4 (no visible effect on the decay; 0.1 % on a key that is then rounded to bf16): for
+// the matrix-core scan, where this arithmetic sits on the critical wavefronts.
+template <bool kShortLog1p = false>
 __device__ __forceinline__ void ddts_channel_gates(float z_g, float z_tau, float &log_alpha, float &alpha_hat)
 {
     const float e = __expf(-fabsf(z_g));
-    const float g = fmaxf(z_g, 0.f) + log1p_unit(e);             // softplus
+    const float g = fmaxf(z_g, 0.f) + (kShortLog1p ? __logf(1.f + e) : log1p_unit(e));             // softplus
     // log g: for very negative z, g = e^z (1 - e^z / 2 + ...) underflows before its logarithm does
     const float log_g = z_g < -15.f ? z_g - 0.5f * e : __logf(g);
-    const float tau = sigmoid_f(z_tau);
+    const float tau = kShortLog1p ? sigmoid_short(z_tau) : sigmoid_f(z_tau);
     log_alpha = -g * tau;
     alpha_hat = __expf(tau * log_g);
 }

@@ -177,7 +177,7 @@ __device__ __forceinline__ void gate_activate(GateLoads &in)
 #pragma unroll
     for (int c = 0; c < 16; ++c) {
         float alpha_hat;
-        ddts_channel_gates(zg[c], zt[c], la[c], alpha_hat);
+        ddts_channel_gates<true>(zg[c], zt[c], la[c], alpha_hat);
         kh[c] = alpha_hat * kf[c] * inv_norm;
     }
     in.k[0] = __builtin_bit_cast(uint4, pack8(kh));
@@ -523,8 +523,8 @@ __device__ __forceinline__ void stage_values(unsigned char *vt, int tile, int la
             const uint32_t z[4] = {p.zbeta[u].x, p.zbeta[u].y, p.zbeta[u].z, p.zbeta[u].w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                gv[2 * j] *= sigmoid_f(bf16_lo(z[j]));
-                gv[2 * j + 1] *= sigmoid_f(bf16_hi(z[j]));
+                gv[2 * j] *= sigmoid_short(bf16_lo(z[j]));
+                gv[2 * j + 1] *= sigmoid_short(bf16_hi(z[j]));
             }
         } else if (has_beta) {
 #pragma unroll
