@@ -1,0 +1,70 @@
+"""The library's calls can be recorded into a HIP graph (they allocate nothing, do not synchronise and launch on the
+caller's stream): a captured decode loop and a captured prefill scan are replayed several times, with eager work and
+synchronisations between the replays, and every replay is compared with the eager result (needs an MI355X)."""
+import pytest
+import torch
+
+from paper_2410_06577_amd import rodimus, workloads as wl
+from _parity import to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def test_captured_decode_loop_replays_like_eager_steps():
+    N, H, dk, dv, steps = 8, 4, 64, 256, 6
+    w = wl.DecodeWorkload("g", N=N, H=H, dk=dk, dv=dv, io_dtype="bf16", steps=steps, ring=steps, seed=4)
+    d = wl.make_decode_inputs(w)
+    ring = [to_dev(tok) for tok in d["ring"]]
+    S0 = d["S"].cuda()
+
+    def run_steps(S, outs):
+        for i, t in enumerate(ring):
+            rodimus.rodimus_decode_step(t["q"], t["k"], t["v"], t["log_alpha"], t["beta"], S, o=outs[i])
+
+    # eager reference
+    S_eager = S0.clone()
+    o_eager = [torch.empty((N, H, dv), dtype=torch.bfloat16, device="cuda") for _ in range(steps)]
+    run_steps(S_eager, o_eager)
+    torch.cuda.synchronize()
+
+    # capture (static buffers), after a warm-up launch on the capture stream
+    S_graph = S0.clone()
+    o_graph = [torch.empty_like(x) for x in o_eager]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run_steps(S_graph, o_graph)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run_steps(S_graph, o_graph)
+    for replay in range(3):
+        S_graph.copy_(S0)                      # eager work between the replays
+        for x in o_graph:
+            x.fill_(0)                         # a fill kernel, not a memset node
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(S_graph, S_eager), replay
+        for a, b in zip(o_graph, o_eager):
+            assert torch.equal(a, b), replay
+
+
+def test_captured_prefill_scan_replays_like_the_eager_call():
+    w = wl.ScanWorkload("g", B=2, T=300, H=4, dk=64, dv=256, chunk=64, io_dtype="bf16", s0_std=0.1, seed=6)
+    g = to_dev(wl.make_scan_inputs(w))
+    o_eager, S_eager = rodimus.rodimus_chunk_scan_fwd(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], g["S0"])
+    torch.cuda.synchronize()
+    o = torch.empty_like(o_eager)
+    S_T = torch.empty_like(S_eager)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        rodimus.rodimus_chunk_scan_fwd(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], g["S0"], o=o, S_T=S_T)
+    for replay in range(3):
+        o.fill_(0)
+        S_T.fill_(0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o, o_eager) and torch.equal(S_T, S_eager), replay
