@@ -136,6 +136,47 @@ def bench_decode(w, rodimus, wl, dev, warmup=100):
             "gbs": algo_bytes / (launch_ms * 1e-3) / 1e9, "steps_per_s": w.steps / wall, "finite": finite}
 
 
+def bench_decode_small(rodimus, wl, dev, H=16, dk=64, dv=256, chained=64, reps=20):
+    """Latency of the decode step at serving batch sizes where the launch, not the bandwidth, is the cost: `chained` steps
+    issued one by one from Python, and the same steps recorded once into a HIP graph and replayed."""
+    out = {}
+    for N in (1, 8, 32):
+        w = wl.DecodeWorkload("small", N=N, H=H, dk=dk, dv=dv, io_dtype="bf16", steps=chained, ring=8, seed=5)
+        d = wl.make_decode_inputs(w)
+        S = d["S"].to(dev)
+        ring = [{k: v.to(dev) for k, v in tok.items()} for tok in d["ring"]]
+        o = torch.empty((N, H, dv), dtype=torch.bfloat16, device=dev)
+
+        def run():
+            for i in range(chained):
+                t = ring[i % len(ring)]
+                rodimus.rodimus_decode_step(t["q"], t["k"], t["v"], t["log_alpha"], t["beta"], S, o=o)
+
+        run()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            run()
+        torch.cuda.synchronize()
+        eager_us = (time.perf_counter() - t0) / (reps * chained) * 1e6
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            run()
+        graph.replay()
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            graph.replay()
+        b.record()
+        torch.cuda.synchronize()
+        graph_us = a.elapsed_time(b) / (reps * chained) * 1e3
+        out[f"{N}_sequences"] = {"us_per_step_eager": eager_us, "us_per_step_hip_graph": graph_us,
+                                 "state_bytes": N * H * dk * dv * 4}
+    out["note"] = f"{chained} chained steps; eager = ctypes call per step from Python (wall clock), graph = one replay per {chained} steps"
+    return out
+
+
 def bench_gates(w, rodimus, wl, dev, steps=50, warmup=20):
     """DDTS gate front-end over the token-heads of the scan workload (pre-activations -> log_alpha, beta, q, k)."""
     d = wl.make_ddts_preactivations((w.B, w.T, w.H), w.dk, w.dv, "bf16", seed=9)
@@ -389,6 +430,7 @@ def main():
                                            "hbm_frac": big["gbs"] / HBM_PEAK_GBS},
         }
     if not args.skip_other_configs:
+        out["decode_small_batch"] = bench_decode_small(rodimus, wl, dev)
         out["ddts_gates"] = bench_gates(w, rodimus, wl, dev)
         out["short_conv"] = bench_short_conv(w, rodimus, wl, dev)
         del o, S_T
