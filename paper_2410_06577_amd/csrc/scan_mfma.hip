@@ -87,6 +87,12 @@ __device__ __forceinline__ float dpp_any(float src)
 {
     return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(src), __float_as_int(src), kCtrl, 0xf, 0xf, true));
 }
+// row_shift_right: lane n of a 16-lane row reads lane n - kShift of the same row; the first kShift lanes get `fill`
+template <int kShift>
+__device__ __forceinline__ float row_shift_right(float src, float fill)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(fill), __float_as_int(src), 0x110 + kShift, 0xf, 0xf, false));
+}
 // swizzle_lane: every lane reads lane ((lane & kAnd) | kOr) of its 32-lane half
 template <int kAnd, int kOr>
 __device__ __forceinline__ float swizzle_lane(float src)
@@ -355,7 +361,12 @@ __device__ __forceinline__ void gate_tile_products(unsigned char *buf, int tile,
 // product-only construction above.  The choice is per tile and wavefront-uniform.
 constexpr float kSafeTileDecay = 8.2718061e-25f;     // 2^-80: 1 / A_i stays below 2^80, far inside bf16 and fp32 range
 
-template <bool kSummary, bool kGated>
+// kShiftPrefix picks one of two instruction sequences for the prefix products A_t (same values up to rounding order):
+// four doubling steps of DPP row shifts with the identity shifted in (no selects, no LDS-pipe swizzles), or products
+// inside blocks of 2, 4, 8, 16 rows.  Measured on the layer workload, same box: the shifts are 1.6 % faster in the
+// fp32-beta kernel (224.3 -> 220.7 us) and 1.7 .. 2 % slower in the z_beta and gated kernels (200.6 -> 204.2, 283 -> 289 us),
+// so each instance takes the one that is faster for it.
+template <bool kSummary, bool kGated, bool kShiftPrefix>
 __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row, int grp, GateLoads &in, bool valid)
 {
     if (kGated) gate_activate<kSummary>(in);
@@ -370,27 +381,38 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
             pre[8 * m + j] = __expf(in.la[2 * m][j]);           // exp(-inf) = 0
             pre[8 * m + 4 + j] = __expf(in.la[2 * m + 1][j]);
         }
-    const bool b0 = row & 1, b1 = row & 2, b2 = row & 4, b3 = row & 8;
-    // prefix products inside blocks of 2, 4, 8, 16 rows
+    if (kShiftPrefix) {
 #pragma unroll
-    for (int c = 0; c < 16; ++c) {
-        const float x = pre[c] * dpp_any<QP(0, 0, 2, 2)>(pre[c]);
-        pre[c] = b0 ? x : pre[c];
+        for (int c = 0; c < 16; ++c) pre[c] *= row_shift_right<1>(pre[c], 1.f);
+#pragma unroll
+        for (int c = 0; c < 16; ++c) pre[c] *= row_shift_right<2>(pre[c], 1.f);
+#pragma unroll
+        for (int c = 0; c < 16; ++c) pre[c] *= row_shift_right<4>(pre[c], 1.f);
+#pragma unroll
+        for (int c = 0; c < 16; ++c) pre[c] *= row_shift_right<8>(pre[c], 1.f);      // A_t
+    } else {
+        const bool b0 = row & 1, b1 = row & 2, b2 = row & 4, b3 = row & 8;
+        // prefix products inside blocks of 2, 4, 8, 16 rows
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            const float x = pre[c] * dpp_any<QP(0, 0, 2, 2)>(pre[c]);
+            pre[c] = b0 ? x : pre[c];
+        }
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            const float x = pre[c] * dpp_any<QP(1, 1, 1, 1)>(pre[c]);
+            pre[c] = b1 ? x : pre[c];
+        }
+        float t[16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) t[c] = swizzle_lane<0x18, 0x03>(pre[c]);
+#pragma unroll
+        for (int c = 0; c < 16; ++c) pre[c] = b2 ? pre[c] * t[c] : pre[c];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) t[c] = swizzle_lane<0x10, 0x07>(pre[c]);
+#pragma unroll
+        for (int c = 0; c < 16; ++c) pre[c] = b3 ? pre[c] * t[c] : pre[c];      // A_t
     }
-#pragma unroll
-    for (int c = 0; c < 16; ++c) {
-        const float x = pre[c] * dpp_any<QP(1, 1, 1, 1)>(pre[c]);
-        pre[c] = b1 ? x : pre[c];
-    }
-    float t[16];
-#pragma unroll
-    for (int c = 0; c < 16; ++c) t[c] = swizzle_lane<0x18, 0x03>(pre[c]);
-#pragma unroll
-    for (int c = 0; c < 16; ++c) pre[c] = b2 ? pre[c] * t[c] : pre[c];
-#pragma unroll
-    for (int c = 0; c < 16; ++c) t[c] = swizzle_lane<0x10, 0x07>(pre[c]);
-#pragma unroll
-    for (int c = 0; c < 16; ++c) pre[c] = b3 ? pre[c] * t[c] : pre[c];      // A_t
     float total[16];
 #pragma unroll
     for (int c = 0; c < 16; ++c) total[c] = swizzle_lane<0x10, 0x0f>(pre[c]);    // A_16 (row 15 of the tile)
@@ -713,6 +735,7 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
 
     if (wave < 4) {
         // ------------------------------------------------------------------ gate wavefront, tile = wave
+        constexpr bool kShiftPrefix = !kSummary && !kZBeta && !kGated;      // see gate_tile
         GateLoads even, odd;      // loads of even / odd chunks: no register copies between iterations
         const int row0 = t_begin + 16 * wave + n;
         if (nchunks > 0) gate_prefetch<kSummary, kGated>(g, row0, grp, even);
@@ -723,7 +746,7 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
             if (!kSummary && it >= 2) store_outputs(g, lds + kOffOb, t_begin + (it - 2) * kChunk, wave, lane);
             if (it < nchunks) {
                 gate_prefetch<kSummary, kGated>(g, row0 + (it + 1) * kChunk, grp, odd);   // unconditional (clamped): keeps the wait counts exact
-                gate_tile<kSummary, kGated>(lds, wave, n, grp, even, row0 + it * kChunk < g.t_end);
+                gate_tile<kSummary, kGated, kShiftPrefix>(lds, wave, n, grp, even, row0 + it * kChunk < g.t_end);
             }
             PROF_ADD(wave * 2, t0);
             t0 = PROF_T();
@@ -734,7 +757,7 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
             if (!kSummary && it >= 2) store_outputs(g, lds + kOffOb + kObBuf, t_begin + (it - 2) * kChunk, wave, lane);
             if (it < nchunks) {
                 gate_prefetch<kSummary, kGated>(g, row0 + (it + 1) * kChunk, grp, even);
-                gate_tile<kSummary, kGated>(lds + kBufBytes, wave, n, grp, odd, row0 + it * kChunk < g.t_end);
+                gate_tile<kSummary, kGated, kShiftPrefix>(lds + kBufBytes, wave, n, grp, odd, row0 + it * kChunk < g.t_end);
             }
             PROF_ADD(wave * 2, t0);
             t0 = PROF_T();
