@@ -264,7 +264,9 @@ int rodimus_decode_step_block(const void *q, const void *k, const void *v,
  * No output may overlap an input, another output or the workspace.  Two kernel families:
  *   io_dtype = BF16, dk = 64, dv = 128 or 256, any T: bf16 MFMA operands, fp32 accumulation and fp32 gate arithmetic, a
  *     16-token tile as the internal chunk; a forward sweep for dq and a reverse sweep for dk, dv, dbeta, dS0 run side by
- *     side in one launch (one workgroup per (batch, head) each), a second launch forms dlog_alpha;
+ *     side in one launch (one workgroup per (batch, head) each), a second launch forms dlog_alpha; when B * H is small
+ *     (2 * B * H < 192) and T >= 512 the sequences are cut into segments of at least 256 tokens that run as workgroups of
+ *     their own, the states and state cotangents at the cuts coming from two summary passes (larger workspace);
  *   any other shape with dk <= 128 and dk * (dv + 1) <= 32768, either io_dtype: token by token in fp32 with the state in
  *     LDS (one workgroup per (batch, head), a forward launch then a reverse launch) -- complete, not fast.
  * Anything else returns RODIMUS_ERR_SHAPE (also T * H >= 2^31).

@@ -233,7 +233,7 @@ hipError_t launch_scan_bwd_generic(const ScanBwdArgs &a);       // any other sup
 bool scan_bwd_generic_supports(int dk, int dv);
 size_t scan_bwd_generic_workspace_bytes(size_t token_rows, int B, int H, int dk);
 bool scan_bwd_supports(int dk, int dv, int io_dtype);
-size_t scan_bwd_workspace_bytes(size_t token_rows, int B, int H);
+size_t scan_bwd_workspace_bytes(size_t token_rows, int B, int T, int H, int dv, bool packed);
 hipError_t launch_decode_step(const DecodeArgs &a);
 hipError_t launch_ddts_gates(const GateArgs &a);
 
@@ -252,5 +252,10 @@ size_t scan_generic_lds_bytes(int dk, int chunk, bool general = false);
 hipError_t launch_scan_mfma(const ScanArgs &a);
 bool scan_mfma_supports(int dk, int dv, int chunk, int io_dtype);
 size_t scan_mfma_workspace_bytes(int B, int T, int H, int dv);
+// State entering each of nseg sequence segments (seg_tokens a multiple of 64) of a dense bf16 batch with dk = 64:
+// slots [nseg][B*H][64][dv] and the segment decays gamma [nseg-1][B*H][64], fp32 (used by the backward pass)
+hipError_t launch_scan_segment_states(const void *k, const void *v, const float *log_alpha, const float *beta, const float *S0,
+                                      int B, int T, int H, int dv, int nseg, int seg_tokens, float *slots, float *gamma,
+                                      hipStream_t stream);
 
 }  // namespace rodimus

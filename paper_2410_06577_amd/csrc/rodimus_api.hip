@@ -266,10 +266,10 @@ int rodimus_decode_step_general(const void *q, const void *k, const void *v, con
 
 namespace {
 
-size_t bwd_workspace(size_t token_rows, int B, int H, int dk, int dv, int io_dtype)
+size_t bwd_workspace(size_t token_rows, int B, int T, int H, int dk, int dv, int io_dtype, bool packed)
 {
     if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return 0;
-    if (scan_bwd_supports(dk, dv, io_dtype)) return scan_bwd_workspace_bytes(token_rows, B, H);
+    if (scan_bwd_supports(dk, dv, io_dtype)) return scan_bwd_workspace_bytes(token_rows, B, T, H, dv, packed);
     return scan_bwd_generic_supports(dk, dv) ? scan_bwd_generic_workspace_bytes(token_rows, B, H, dk) : 0;
 }
 
@@ -295,7 +295,7 @@ int bwd_entry(const void *q, const void *k, const void *v, const float *log_alph
                                 tokens * dv * 4, states * dk_width * dv * 4, tokens * dv * eb, states * dk_width * dv * 4,
                                 packed ? ((size_t)B + 1) * sizeof(int) : 0};
     void *outs[7] = {dq, dk, dv_out, dlog_alpha, dbeta, dS0, workspace};
-    const size_t need = bwd_workspace(token_rows, B, H, dk_width, dv, io_dtype);
+    const size_t need = bwd_workspace(token_rows, B, T, H, dk_width, dv, io_dtype, packed);
     const size_t out_bytes[7] = {tokens * dk_width * eb, tokens * dk_width * eb, tokens * dv * eb, tokens * dk_width * 4,
                                  tokens * dv * 4, states * dk_width * dv * 4, need};
     for (int i = 0; i < 9; ++i)
@@ -323,13 +323,13 @@ extern "C" {
 size_t rodimus_chunk_scan_bwd_workspace_bytes(int B, int T, int H, int dk, int dv, int io_dtype)
 {
     if (B < 0 || T < 0 || H < 0) return 0;
-    return bwd_workspace((size_t)B * T, B, H, dk, dv, io_dtype);
+    return bwd_workspace((size_t)B * T, B, T, H, dk, dv, io_dtype, false);
 }
 
 size_t rodimus_chunk_scan_varlen_bwd_workspace_bytes(int N, int total_tokens, int H, int dk, int dv, int io_dtype)
 {
     if (N < 0 || total_tokens < 0 || H < 0) return 0;
-    return bwd_workspace((size_t)total_tokens, N, H, dk, dv, io_dtype);
+    return bwd_workspace((size_t)total_tokens, N, total_tokens, H, dk, dv, io_dtype, true);
 }
 
 int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta,

@@ -46,6 +46,22 @@ constexpr float kSafeTileLog = -55.f;
 constexpr int kGateParts = 32;
 __host__ __device__ inline int gate_part_tiles(int T) { return (((T + kTile - 1) / kTile) + kGateParts - 1) / kGateParts; }      // ln(2^-80) = -55.45: above it 1 / A_i stays below 2^80
 
+// How a call is cut along the sequence.  Slots: [segment][B*H][64][dv] fp32.
+struct BwdSegments {
+    int nseg;                    // 1: whole sequences, no slots
+    int seg_tokens;              // a multiple of 64
+    const float *S_slots;        // state entering each segment
+    const float *G_slots;        // cotangent of the state leaving each segment
+};
+
+// The tokens of segment `seg` of a sequence (empty beyond its end)
+__device__ __forceinline__ SeqSpan segment_span(SeqSpan s, const BwdSegments &sg, int seg)
+{
+    if (sg.nseg <= 1) return s;
+    const int begin = seg * sg.seg_tokens;
+    return SeqSpan{s.first + (size_t)begin, max(min(sg.seg_tokens, s.length - begin), 0)};
+}
+
 // Value columns are stored in LDS in a permuted order inside every group of 32: column 32s + 16h + 4g + e sits at
 // position 32s + 8g + 4h + e.  A 16-byte read at position 32s + 8g then delivers exactly the 8 columns that lane
 // group g of an MFMA accumulator pair (column tiles 2s and 2s+1) holds, so the accumulators can serve as the other
@@ -189,7 +205,7 @@ __device__ __forceinline__ void sweep_dq(
     const float *__restrict__ log_alpha, const float *__restrict__ beta, const float *__restrict__ S0,
     const bf16_t *__restrict__ d_o, const float *__restrict__ dS_T, bf16_t *__restrict__ dq,
     float *__restrict__ qdq, float *__restrict__ gate_const, float *__restrict__ qtot, int T, int H,
-    const int *__restrict__ cu_seqlens)
+    const int *__restrict__ cu_seqlens, const BwdSegments &segs)
 {
     using L = BwdLayout<DV>;
     constexpr int kColTiles = DV / 16, kSteps = DV / 32;
@@ -206,12 +222,18 @@ __device__ __forceinline__ void sweep_dq(
     const bool computes = wave < 4;
     const int c = lane & 15, tg = lane >> 4;          // vector-ALU role: channel 16*wave + c, tokens 4tg .. 4tg+3
     const int ch = 16 * (wave & 3) + c;
-    const int bh = blockIdx.x;
+    const int bh = blockIdx.x, seg = blockIdx.z;
+    const size_t unit = (size_t)seg * gridDim.x + bh;             // (segment, batch, head): index of the per-unit totals
     const bool has_beta = beta != nullptr;
-    const SeqSpan span = seq_span(bh / H, T, cu_seqlens);
+    const SeqSpan span = segment_span(seq_span(bh / H, T, cu_seqlens), segs, seg);
     T = span.length;
     const BwdGeometry g(q, k, v, d_o, log_alpha, beta, span.first, bh % H, T, H, DV);
     const size_t row0 = span.first * H + bh % H;                  // outputs: same layout as the inputs
+    if (segs.nseg > 1) {                                          // the segment's own boundary states
+        const size_t slot = (size_t)seg * gridDim.x * kK * DV; // state_base below adds the (batch, head)
+        S0 = segs.S_slots + slot;
+        dS_T = segs.G_slots + slot;
+    }
 
     // state slab, transposed: acc[ct][r] = S[ch][16ct + 4tg + r]
     floatx4_t acc[kColTiles];
@@ -361,7 +383,7 @@ __device__ __forceinline__ void sweep_dq(
             float x = qpart;
             x += __shfl_xor(x, 16);
             x += __shfl_xor(x, 32);
-            if (tg == 0) qtot[((size_t)bh * kGateParts + run_index) * kK + ch] = x;
+            if (tg == 0) qtot[(unit * kGateParts + run_index) * kK + ch] = x;
             qpart = 0.f;
             ++run_index;
             run_last += part_tiles;
@@ -382,7 +404,7 @@ __device__ __forceinline__ void sweep_dq(
     }
     part += __shfl_xor(part, 16);
     part += __shfl_xor(part, 32);
-    if (tg == 0) gate_const[(size_t)bh * kK + ch] = part;
+    if (tg == 0) gate_const[unit * kK + ch] = part;
 }
 
 
@@ -424,7 +446,7 @@ __device__ __forceinline__ void sweep_dkv(
     const float *__restrict__ log_alpha, const float *__restrict__ beta, const bf16_t *__restrict__ d_o,
     const float *__restrict__ dS_T, bf16_t *__restrict__ dk, bf16_t *__restrict__ dv, float *__restrict__ kdk,
     float *__restrict__ dbeta, float *__restrict__ dS0, float *__restrict__ ktot, int T, int H,
-    const int *__restrict__ cu_seqlens)
+    const int *__restrict__ cu_seqlens, const BwdSegments &segs)
 {
     using L = BwdLayout<DV>;
     constexpr int kWaves = BwdShape<DV>::kWaves;     // 4 (dv = 128) or 8 (dv = 256)
@@ -454,13 +476,18 @@ __device__ __forceinline__ void sweep_dkv(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, grp = lane >> 4;
-    const int bh = blockIdx.x;
+    const int bh = blockIdx.x, seg = blockIdx.z;
+    const size_t unit = (size_t)seg * gridDim.x + bh;
     const bool has_beta = beta != nullptr;
-    const SeqSpan span = seq_span(bh / H, T, cu_seqlens);
+    const SeqSpan span = segment_span(seq_span(bh / H, T, cu_seqlens), segs, seg);
     T = span.length;
     const BwdGeometry g(q, k, v, d_o, log_alpha, beta, span.first, bh % H, T, H, DV);
     const size_t row0 = span.first * H + bh % H;                  // outputs: same layout as the inputs
     const int col0 = wave * kSlab;
+    if (segs.nseg > 1) {
+        dS_T = segs.G_slots + (size_t)seg * gridDim.x * kK * DV;
+        if (seg > 0) dS0 = nullptr;                               // only the first segment's cotangent leaves the call
+    }
 
     // cotangent slab: acc[kt][ct][r] = G[16kt + 4grp + r][col0 + 16ct + n]
     floatx4_t acc[4][kCt];
@@ -714,7 +741,7 @@ __device__ __forceinline__ void sweep_dkv(
                 }
             }
             if (it == run_first) {                          // the run's first tile is its last in this direction
-                ktot[(((size_t)bh * kGateParts + run_index) * kWaves + vg) * kK + vc] = kpart;
+                ktot[((unit * kGateParts + run_index) * kWaves + vg) * kK + vc] = kpart;
                 kpart = 0.f;
                 --run_index;
                 run_first -= part_tiles;
@@ -756,11 +783,36 @@ __device__ __forceinline__ void sweep_dkv(
 
 }  // namespace
 
-// q .* dq and k .* dk in fp32 for every (token, head, channel), and rowsum(S_T .* dS_T) per (batch, head, channel)
-// and the totals of both over kGateParts runs of the sequence (one per wavefront of the reverse sweep, at most 8)
-size_t scan_bwd_workspace_bytes(size_t token_rows, int B, int H)
+// When 2 * B * H workgroups would leave much of the chip idle, a dense batch is cut into segments of whole 64-token
+// chunks so that about 512 workgroups exist (the two sweeps differ in length, two rounds even them out), each segment
+// keeping at least 256 tokens.  A packed batch is never cut: its lengths live in device memory.
+struct BwdSplit { int nseg, seg_tokens; };
+static BwdSplit choose_bwd_split(int B, int T, int H, bool packed)
 {
-    return (2 * token_rows * H * kK + (size_t)B * H * kK * (1 + kGateParts + 8 * kGateParts)) * sizeof(float);
+    const int nchunks = (T + 63) / 64;
+    const BwdSplit whole{1, nchunks * 64};
+    const long long wgs = 2ll * B * H;
+    if (packed || wgs == 0 || wgs >= 192 || nchunks < 8) return whole;
+    long long want = (512 + wgs - 1) / wgs;
+    if (want > nchunks / 4) want = nchunks / 4;
+    if (want > 64) want = 64;
+    if (want < 2) return whole;
+    const int seg_chunks = (int)((nchunks + want - 1) / want);
+    const int nseg = (nchunks + seg_chunks - 1) / seg_chunks;
+    return nseg < 2 ? whole : BwdSplit{nseg, seg_chunks * 64};
+}
+
+// Workspace: q .* dq and k .* dk in fp32 for every (token, head, channel); per unit (segment, batch, head) and channel
+// rowsum(S .* dS) at the unit's end and the totals of both products over kGateParts runs of tiles (the reverse sweep
+// leaves one per wavefront, at most 8); for a call cut into segments also the two sets of state slots and the segment
+// decays of both directions.
+size_t scan_bwd_workspace_bytes(size_t token_rows, int B, int T, int H, int dv, bool packed)
+{
+    const BwdSplit sp = choose_bwd_split(B, T, H, packed);
+    const size_t units = (size_t)B * H * sp.nseg;
+    size_t floats = 2 * token_rows * H * kK + units * kK * (1 + kGateParts + 8 * kGateParts);
+    if (sp.nseg > 1) floats += 2 * units * kK * dv + 2 * (size_t)(sp.nseg - 1) * B * H * kK;
+    return floats * sizeof(float);
 }
 
 bool scan_bwd_supports(int dk, int dv, int io_dtype)
@@ -779,16 +831,165 @@ __global__ __launch_bounds__(BwdShape<DV>::kThreads) void scan_bwd_sweeps_kernel
     const bf16_t *__restrict__ d_o, const float *__restrict__ dS_T, bf16_t *__restrict__ dq, bf16_t *__restrict__ dk,
     bf16_t *__restrict__ dv, float *__restrict__ dbeta, float *__restrict__ dS0, float *__restrict__ qdq,
     float *__restrict__ kdk, float *__restrict__ gate_const, float *__restrict__ qtot, float *__restrict__ ktot, int T, int H,
-    const int *__restrict__ cu_seqlens)
+    const int *__restrict__ cu_seqlens, BwdSegments segs)
 {
     if (blockIdx.y == 0)
-        sweep_dq<DV>(q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, qdq, gate_const, qtot, T, H, cu_seqlens);
+        sweep_dq<DV>(q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, qdq, gate_const, qtot, T, H, cu_seqlens, segs);
     else
-        sweep_dkv<DV>(q, k, v, log_alpha, beta, d_o, dS_T, dk, dv, kdk, dbeta, dS0, ktot, T, H, cu_seqlens);
+        sweep_dkv<DV>(q, k, v, log_alpha, beta, d_o, dS_T, dk, dv, kdk, dbeta, dS0, ktot, T, H, cu_seqlens, segs);
+}
+
+// The G recurrence alone over one segment (blockIdx.y + 1; the first segment's result would be dS0 and is left to the
+// sweep), from a zero cotangent: G <- diag(A_16) G + (q .* A)^T do over the segment's tiles, last to first, one wavefront
+// per 32 value columns as in the reverse sweep.  Leaves the result in slot seg-1 (the segment that receives it) and the
+// segment's total decay in decay[seg-1].
+template <int DV>
+__global__ __launch_bounds__(BwdShape<DV>::kThreads) void scan_bwd_cotangent_summary_kernel(
+    const bf16_t *__restrict__ q, const float *__restrict__ log_alpha, const bf16_t *__restrict__ d_o,
+    float *__restrict__ G_slots, float *__restrict__ decay, int T, int H, int seg_tokens)
+{
+    using L = BwdLayout<DV>;
+    constexpr int kWaves = BwdShape<DV>::kWaves, kSlab = 32, kCt = kSlab / 16, kTok = kTile / kWaves;
+    constexpr bool kWide = BwdShape<DV>::kThreads == 512;
+    __shared__ __align__(16) float qs[kTile * kK], ls[kTile * kK], a16_s[kK];
+    __shared__ __align__(16) unsigned char ds[kTile * L::kRowBytes];
+    __shared__ __align__(16) bf16_t qa_s[kTile * (kK + 8)];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, grp = lane >> 4;
+    const int bh = blockIdx.x, seg = blockIdx.y + 1;
+    const int t_begin = seg * seg_tokens;
+    const int len = min(seg_tokens, T - t_begin);                 // > 0: the host cuts T into ceil(T / seg_tokens) segments
+    const size_t row0 = ((size_t)(bh / H) * T + t_begin) * H + bh % H;
+    q += row0 * kK; log_alpha += row0 * kK; d_o += row0 * DV;
+    const int col0 = wave * kSlab;
+    const int vc = tid & 63, vg = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    floatx4_t acc[4][kCt];
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int ct = 0; ct < kCt; ++ct) acc[kt][ct] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    float log_decay = 0.f;
+
+    uint4 pq = {0u, 0u, 0u, 0u}, pdo;
+    floatx4_t pla = {0.f, 0.f, 0.f, 0.f};
+    auto prefetch = [&](int t0) {
+        if (tid < 128) pq = *reinterpret_cast<const uint4 *>(q + (size_t)((unsigned)min(t0 + (tid >> 3), len - 1) * (unsigned)H) * kK + 8 * (tid & 7));
+        if (!kWide || tid >= 256)
+            pla = *reinterpret_cast<const floatx4_t *>(log_alpha + (size_t)((unsigned)min(t0 + ((tid & 255) >> 4), len - 1) * (unsigned)H) * kK + 4 * (tid & 15));
+        pdo = *reinterpret_cast<const uint4 *>(d_o + (size_t)((unsigned)min(t0 + tid / L::kPieces, len - 1) * (unsigned)H) * DV + 8 * (tid % L::kPieces));
+    };
+    const int ntiles = (len + kTile - 1) / kTile;
+    prefetch((ntiles - 1) * kTile);
+    for (int it = ntiles - 1; it >= 0; --it) {
+        const int t0 = it * kTile;
+        __syncthreads();                                   // the previous tile is consumed
+        if (tid < 128) {
+            const int tok = tid >> 3;
+            float x[8];
+            unpack8(pq, x);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qs[tok * kK + 8 * (tid & 7) + e] = (t0 + tok < len) ? x[e] : 0.f;
+        }
+        if (!kWide || tid >= 256) {
+            const int tok = (tid & 255) >> 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) ls[tok * kK + 4 * (tid & 15) + e] = (t0 + tok < len) ? fmaxf(pla[e], kMinLogAlpha) : 0.f;
+        }
+        {
+            const int tok = tid / L::kPieces, piece = tid % L::kPieces;
+            float d[8];
+            unpack8(pdo, d);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) d[e] = (t0 + tok < len) ? d[e] : 0.f;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const uint2 wd = {pack_bf16x2(d[4 * half], d[4 * half + 1]), pack_bf16x2(d[4 * half + 2], d[4 * half + 3])};
+                *reinterpret_cast<uint2 *>(ds + tok * L::kRowBytes + col_position(8 * piece + 4 * half) * 2) = wd;
+            }
+        }
+        prefetch(max(t0 - kTile, 0));
+        __syncthreads();
+        // thread = (channel vc, tokens kTok * vg ..): running sums of log_alpha, q .* A
+        {
+            float lsum[kTile], run = 0.f;
+#pragma unroll
+            for (int i = 0; i < kTile; ++i) {
+                run += ls[i * kK + vc];
+                lsum[i] = run;
+            }
+            if (vg == 0) {
+                a16_s[vc] = __expf(run);
+                log_decay += run;
+            }
+#pragma unroll
+            for (int r = 0; r < kTok; ++r) {
+                float l_own = lsum[r];
+#pragma unroll
+                for (int gsel = 1; gsel < kWaves; ++gsel) l_own = (vg == gsel) ? lsum[kTok * gsel + r] : l_own;
+                const int t = kTok * vg + r;
+                qa_s[t * (kK + 8) + vc] = (bf16_t)(qs[t * kK + vc] * __expf(l_own));
+            }
+        }
+        __syncthreads();
+        {
+            const int j = n >> 2, cc = n & 3;              // transposing reads: this lane addresses row 4grp + j, unit cc
+            uint2 a_q[4], b_do[kCt];
+            floatx4_t dec[4];
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt) {
+                a_q[kt] = lds_read_transposed(reinterpret_cast<const unsigned char *>(&qa_s[(4 * grp + j) * (kK + 8) + 16 * kt + 4 * cc]));
+                dec[kt] = *reinterpret_cast<const floatx4_t *>(&a16_s[16 * kt + 4 * grp]);
+            }
+#pragma unroll
+            for (int ct = 0; ct < kCt; ++ct)
+                b_do[ct] = lds_read_transposed(ds + (4 * grp + j) * L::kRowBytes + col_position(col0 + 16 * ct + 4 * cc) * 2);
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                for (int ct = 0; ct < kCt; ++ct) {
+                    floatx4_t x = acc[kt][ct];
+                    x[0] *= dec[kt][0]; x[1] *= dec[kt][1]; x[2] *= dec[kt][2]; x[3] *= dec[kt][3];
+                    acc[kt][ct] = mfma_k16(a_q[kt], b_do[ct], x);
+                }
+        }
+    }
+    const size_t unit = (size_t)(seg - 1) * gridDim.x + bh;
+    float *out = G_slots + unit * kK * DV;
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int ct = 0; ct < kCt; ++ct)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) out[(size_t)(16 * kt + 4 * grp + r) * DV + col0 + 16 * ct + n] = acc[kt][ct][r];
+    if (vg == 0) decay[unit * kK + vc] = __expf(log_decay);
+}
+
+// Cotangent of the state leaving every segment, from the summary pass: the last slot = dS_T (or zero), and for
+// s < nseg-1  slot s <- decay[s] .* slot[s+1] + slot[s]  (decay[s] is the total decay of segment s+1, slot[s] held the
+// summary of segment s+1).  One thread per four adjacent state elements; the segments are walked from the last one back.
+__global__ __launch_bounds__(256) void scan_bwd_cotangent_chain_kernel(const float *__restrict__ dS_T, float *__restrict__ G_slots,
+                                                                      const float *__restrict__ decay, int nseg, int dv,
+                                                                      size_t quads_per_slot)
+{
+    const size_t e4 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e4 >= quads_per_slot) return;
+    const size_t elem = e4 * 4, row = elem / dv, slot_elems = quads_per_slot * 4;      // row = (batch, head) * 64 + channel
+    floatx4_t g = dS_T != nullptr ? *reinterpret_cast<const floatx4_t *>(dS_T + elem) : floatx4_t{0.f, 0.f, 0.f, 0.f};
+    *reinterpret_cast<floatx4_t *>(G_slots + (size_t)(nseg - 1) * slot_elems + elem) = g;
+    for (int sg = nseg - 2; sg >= 0; --sg) {
+        const float a = decay[(size_t)sg * (slot_elems / dv) + row];
+        floatx4_t *p = reinterpret_cast<floatx4_t *>(G_slots + (size_t)sg * slot_elems + elem);
+        const floatx4_t loc = *p;
+        g[0] = fmaf(a, g[0], loc[0]); g[1] = fmaf(a, g[1], loc[1]);
+        g[2] = fmaf(a, g[2], loc[2]); g[3] = fmaf(a, g[3], loc[3]);
+        *p = g;
+    }
 }
 
 // dlog_alpha_t = gate_const + sum_{s >= t} (q_s .* dq_s - k_s .* dk_s), zero for a closed gate.  One workgroup per
-// (batch, head, half of the channels); thread = (channel, one of the kGateParts runs of tiles): the runs' totals come from
+// (batch, head, half of the channels, segment); thread = (channel, one of the kGateParts runs of tiles): the runs' totals come from
 // the sweeps (the reverse sweep leaves one per wavefront), then one pass over the run on top of the totals of the later
 // runs.
 __global__ __launch_bounds__(1024) void scan_bwd_gate_kernel(const float *__restrict__ qdq, const float *__restrict__ kdk,
@@ -796,12 +997,13 @@ __global__ __launch_bounds__(1024) void scan_bwd_gate_kernel(const float *__rest
                                                              const float *__restrict__ qtot, const float *__restrict__ ktot,
                                                              int ktot_waves, const float *__restrict__ log_alpha,
                                                              float *__restrict__ dla, int T, int H,
-                                                             const int *__restrict__ cu_seqlens)
+                                                             const int *__restrict__ cu_seqlens, BwdSegments segs)
 {
     __shared__ float tot_s[kGateParts][32];
     const int tid = threadIdx.x, c = tid & 31, part = tid >> 5;
     const int bh = blockIdx.x, ch = 32 * blockIdx.y + c;
-    const SeqSpan span = seq_span(bh / H, T, cu_seqlens);
+    const size_t unit = (size_t)blockIdx.z * gridDim.x + bh;
+    const SeqSpan span = segment_span(seq_span(bh / H, T, cu_seqlens), segs, blockIdx.z);
     T = span.length;
     const size_t tok0 = span.first;
     const int h = bh % H;
@@ -809,13 +1011,13 @@ __global__ __launch_bounds__(1024) void scan_bwd_gate_kernel(const float *__rest
     const int t_lo = min(part * part_tiles * kTile, T), t_hi = min(t_lo + part_tiles * kTile, T);
     float total = 0.f;
     if (part * part_tiles < ntiles) {                  // runs beyond the sequence were never written
-        const size_t slot = (size_t)bh * kGateParts + part;
+        const size_t slot = unit * kGateParts + part;
         total = qtot[slot * kK + ch];
         for (int w = 0; w < ktot_waves; ++w) total -= ktot[(slot * ktot_waves + w) * kK + ch];
     }
     tot_s[part][c] = total;
     __syncthreads();
-    float run = gate_const[(size_t)bh * kK + ch];
+    float run = gate_const[unit * kK + ch];
     for (int p = kGateParts - 1; p > part; --p) run += tot_s[p][c];
 #pragma unroll 8
     for (int t = t_hi - 1; t >= t_lo; --t) {
@@ -829,23 +1031,43 @@ template <int DV>
 hipError_t launch_scan_bwd_typed(const ScanBwdArgs &a)
 {
     const unsigned bh = (unsigned)(a.B * a.H);
+    const BwdSplit sp = choose_bwd_split(a.B, a.T, a.H, a.cu_seqlens != nullptr);
+    const size_t units = (size_t)bh * sp.nseg;
     const size_t rows = a.token_rows() * a.H * kK;
     float *qdq = static_cast<float *>(a.workspace);
     float *kdk = qdq + rows;
     float *gate_const = kdk + rows;
-    float *qtot = gate_const + (size_t)bh * kK;                         // [B*H][kGateParts][64]
-    float *ktot = qtot + (size_t)bh * kGateParts * kK;                  // [B*H][kGateParts][wavefronts][64]
+    float *qtot = gate_const + units * kK;                              // [units][kGateParts][64]
+    float *ktot = qtot + units * kGateParts * kK;                       // [units][kGateParts][wavefronts][64]
+    BwdSegments segs{sp.nseg, sp.seg_tokens, nullptr, nullptr};
+    if (sp.nseg > 1) {
+        const size_t slot_elems = (size_t)bh * kK * DV;
+        float *S_slots = ktot + units * kGateParts * 8 * kK;
+        float *G_slots = S_slots + sp.nseg * slot_elems;
+        float *s_decay = G_slots + sp.nseg * slot_elems;                // [nseg-1][B*H][64], forward direction
+        float *g_decay = s_decay + (size_t)(sp.nseg - 1) * bh * kK;     // the same for the cotangent chain
+        hipError_t e = launch_scan_segment_states(a.k, a.v, a.log_alpha, a.beta, a.S0, a.B, a.T, a.H, DV, sp.nseg,
+                                                  sp.seg_tokens, S_slots, s_decay, a.stream);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(scan_bwd_cotangent_summary_kernel<DV>, dim3(bh, (unsigned)(sp.nseg - 1)), dim3(BwdShape<DV>::kThreads), 0,
+                           a.stream, (const bf16_t *)a.q, a.log_alpha, (const bf16_t *)a.d_o, G_slots, g_decay, a.T, a.H,
+                           sp.seg_tokens);
+        const size_t quads = slot_elems / 4;
+        hipLaunchKernelGGL(scan_bwd_cotangent_chain_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, a.stream, a.dS_T,
+                           G_slots, g_decay, sp.nseg, DV, quads);
+        segs.S_slots = S_slots;
+        segs.G_slots = G_slots;
+    }
     hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_bwd_sweeps_kernel<DV>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, DkvLds<DV>::kBytes);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL(scan_bwd_sweeps_kernel<DV>, dim3(bh, 2), dim3(BwdShape<DV>::kThreads), DkvLds<DV>::kBytes, a.stream,
-                       (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0,
+    hipLaunchKernelGGL(scan_bwd_sweeps_kernel<DV>, dim3(bh, 2, (unsigned)sp.nseg), dim3(BwdShape<DV>::kThreads), DkvLds<DV>::kBytes,
+                       a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0,
                        (const bf16_t *)a.d_o, a.dS_T, (bf16_t *)a.dq, (bf16_t *)a.dk, (bf16_t *)a.dv, a.dbeta, a.dS0, qdq, kdk,
-                       gate_const, qtot, ktot, a.T, a.H, a.cu_seqlens);
+                       gate_const, qtot, ktot, a.T, a.H, a.cu_seqlens, segs);
     if (a.T > 0)
-        hipLaunchKernelGGL(scan_bwd_gate_kernel, dim3(bh, 2), dim3(1024), 0, a.stream, qdq, kdk, gate_const, qtot, ktot,
-                           BwdShape<DV>::kWaves, a.log_alpha,
-                           a.dlog_alpha, a.T, a.H, a.cu_seqlens);
+        hipLaunchKernelGGL(scan_bwd_gate_kernel, dim3(bh, 2, (unsigned)sp.nseg), dim3(1024), 0, a.stream, qdq, kdk, gate_const, qtot,
+                           ktot, BwdShape<DV>::kWaves, a.log_alpha, a.dlog_alpha, a.T, a.H, a.cu_seqlens, segs);
     return hipGetLastError();
 }
 

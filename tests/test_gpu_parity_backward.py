@@ -99,6 +99,42 @@ def test_layer_head_shape():
     _check(_case(2, 1024, 16, 256, seed=22), "layer")
 
 
+@pytest.mark.parametrize("B,T,H,dv,s0", [
+    (1, 1000, 2, 256, True),     # four segments of 256 tokens, the last one ragged (232 = 14 * 16 + 8)
+    (2, 520, 1, 128, True),      # 9 chunks -> three segments of 192 tokens, the last one 136
+    (1, 768, 3, 128, False),     # zero initial state
+])
+def test_sequence_cut_into_segments(B, T, H, dv, s0):
+    """Few (batch, head) pairs and a long sequence: the call is cut along the sequence, boundary states and cotangents
+    come from the summary passes."""
+    print(f"bwd segments B{B} T{T} H{H} dv{dv} s0={s0}", flush=True)
+    _check(_case(B, T, H, dv, s0, seed=T + dv + 1), f"segments B{B}T{T}H{H}dv{dv}")
+
+
+def test_segments_with_weak_decay():
+    """Decays near one (a sequence's total decay is about exp(-3)): the states and cotangents handed across the segment
+    borders dominate every gradient, so a wrong border term cannot hide behind the decay."""
+    print("bwd segments weak decay", flush=True)
+    _check(_case(1, 1000, 2, 256, seed=33, gate_mean=-6.0), "segments weak decay")
+    print("bwd segments weak decay, 32 segments", flush=True)
+    _check(_case(1, 8192, 1, 128, seed=34, gate_mean=-5.0), "segments long")
+
+
+def test_segments_without_state_cotangent_and_with_resets():
+    """Segment route with dS_T = NULL, no value gate, and hard resets / strong decays inside and at segment borders."""
+    inp = _case(1, 1024, 2, 256, seed=31)
+    la = inp["log_alpha"]
+    la[:, 255] = float("-inf")               # the last token of a segment
+    la[:, 256, :, :16] = float("-inf")       # the first token of the next one
+    la[:, 600:640, :, 8:24] = -20.0
+    la[:, 700:760] = 0.0
+    print("bwd segments no dS_T", flush=True)
+    _check(inp, "segments no dS_T", with_dS=False)
+    print("bwd segments no beta", flush=True)
+    out, _ = _check(inp, "segments no beta", with_beta=False)
+    assert float(out["dlog_alpha"][:, 255].abs().max()) == 0.0
+
+
 def test_unsupported_shapes_are_refused():
     # a state that neither kernel family holds: 128 x 256 in fp32 I/O (the token-by-token kernels keep it in LDS)
     x = torch.zeros(1, 4, 1, 128, device="cuda:0")
