@@ -441,6 +441,13 @@ def main():
             "GB_per_s": zb["gbs"], "hbm_frac": zb["gbs"] / HBM_PEAK_GBS}
         out["scan_fused_all_gates"] = bench_gated_scan(w, rodimus, wl, dev, args.steps, args.warmup)
         out["scan_backward"] = bench_backward(w, rodimus, wl, dev, args.steps, args.warmup)
+        # the same layer at a micro-batch of two sequences: too few (batch, head) pairs to fill the chip, the call is cut
+        # along the sequence
+        import dataclasses
+        small = dataclasses.replace(w, name="layer_1p6b_micro_batch_2", B=2)
+        mb = bench_backward(small, rodimus, wl, dev, args.steps, args.warmup)
+        out["scan_backward_micro_batch"] = {"workload": f"B={small.B} T={small.T} H={small.H} dk={small.dk} dv={small.dv}",
+                                            **{k: mb[k] for k in ("ms_per_step", "tokens_per_s", "GB_per_s", "hbm_frac", "finite")}}
         out["serving_prefill_varlen"] = bench_varlen(w, rodimus, wl, dev, args.steps, args.warmup)
         lf = bench_varlen(w, rodimus, wl, dev, args.steps, args.warmup, longest_first=True)
         out["serving_prefill_varlen"]["sequences_sorted_longest_first"] = {

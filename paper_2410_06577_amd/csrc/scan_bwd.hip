@@ -412,32 +412,50 @@ __device__ __forceinline__ void sweep_dq(
 // Reverse sweep: dk, dv, dbeta, dlog_alpha, dS0
 // =========================================================================================================
 // One workgroup per (batch, head); wavefront w owns 32 value columns: its slab of the state cotangent G lives in MFMA
-// accumulators (lane = column, registers = key channels), as the state does in the forward kernel.  Per tile, last to
-// first:  du^T = G^T khat^T + do^T P   (khat_i = k_i .* exp(l_16 - l_i));  partial u G^T over the slab's columns, summed
-// over the wavefronts through LDS;  G <- diag(A_16) G + (q .* A)^T do.
+// accumulators (lane = column, registers = key channels), as the state does in the forward kernel.
+// Per tile, last to first:  du^T = G^T khat^T + do^T P   (khat_i = k_i .* exp(l_16 - l_i));  partial u G^T over the slab's
+// columns, summed over the wavefronts through LDS;  G <- diag(A_16) G + (q .* A)^T do.
+// Only these products depend on G; the rest of a tile's work (staging, running sums, decayed operands, dP, and after
+// the products dk, dv, dbeta) does not, and is laid out so that it overlaps the G-dependent work of a neighbouring tile
+// inside the same wavefronts.  Between two workgroup barriers a wavefront therefore always has two independent
+// instruction streams:
+//   phase X: products of tile `it` (P, du, u G^T, the tile-local part of dk, G update)  |  staging of tile it-1 into
+//            the other input buffer, request of tile it-2
+//   phase Y: dk, dv, dbeta of tile `it`                                                   |  running sums, decayed
+//            operands and this wavefront's share of dP for tile it-1
+// Two barriers per tile (three on the pair-by-pair route).
 template <int DV> struct DkvLds {       // byte offsets of the reverse kernel's dynamic LDS
     static constexpr int kWaves = BwdShape<DV>::kWaves;
     static constexpr int kSlabCols = 32;
-    static constexpr int kQs = 0;
-    static constexpr int kKs = kQs + kTile * kK * 4;
-    static constexpr int kLs = kKs + kTile * kK * 4;
-    static constexpr int kUs = kLs + kTile * kK * 4;
-    static constexpr int kDs = kUs + kTile * BwdLayout<DV>::kRowBytes;
-    static constexpr int kQa = kDs + kTile * BwdLayout<DV>::kRowBytes;
-    static constexpr int kKh = kQa + kTile * (kK + 8) * 2;
-    static constexpr int kPt = kKh + kTile * (kK + 8) * 2;
-    static constexpr int kDp = kPt + kTile * kTile * 2;
+    // one tile's inputs: q, k, log_alpha (clamped) as fp32 [16][64]; u and do as bf16 rows.  Two such buffers.
+    static constexpr int kInKs = kTile * kK * 4;
+    static constexpr int kInLs = 2 * kTile * kK * 4;
+    static constexpr int kInUs = 3 * kTile * kK * 4;
+    static constexpr int kInDs = kInUs + kTile * BwdLayout<DV>::kRowBytes;
+    static constexpr int kInBytes = kInDs + kTile * BwdLayout<DV>::kRowBytes;
+    static constexpr int kQa = 2 * kInBytes;                           // q .* A (high part), token-major, padded rows
+    static constexpr int kKh = kQa + kTile * (kK + 8) * 2;             // khat
+    static constexpr int kKq = kKh + kTile * (kK + 8) * 2;             // k ./ A
+    static constexpr int kQaLo = kKq + kTile * (kK + 8) * 2;           // low part of q .* A (split bf16)
+    static constexpr int kPt = kQaLo + kTile * (kK + 8) * 2;           // P^T [i][t] (pair-by-pair route)
+    static constexpr int kDp = kPt + kTile * kTile * 2;                // dP [t][i], padded rows (pair-by-pair route)
     static constexpr int kGt = kDp + ((kTile * (kTile + 1) * 4 + 15) / 16) * 16;
-    static constexpr int kRed = kGt + kWaves * kSlabCols * (kK + 8) * 2;
-    static constexpr int kDu = kRed + kWaves * kTile * kK * 4;
-    static constexpr int kKq = kDu + kTile * (DV + 4) * 4;             // k ./ A, token-major, padded rows
-    static constexpr int kIntra = kKq + kTile * (kK + 8) * 2;          // (dP^T (q .* A))[i][channel]
-    static constexpr int kQaLo = kIntra + kTile * kK * 4;              // low part of q .* A (split bf16), token-major, padded rows
-    static constexpr int kLt = kQaLo + kTile * (kK + 8) * 2;           // running sums l_t, fp32 [16][64]
-    static constexpr int kA16 = kLt + kTile * kK * 4;                  // A_16 per channel, fp32 [64]
-    static constexpr int kFlag = kA16 + kK * 4;
+    // per wavefront: its G slab as bf16 [column][channel] (padded rows), and afterwards, in the same bytes, its partial
+    // u G^T as fp32 [16][64] (the slab is read before the partial exists)
+    static constexpr int kGtWave = kSlabCols * (kK + 8) * 2;
+    static_assert(kGtWave >= kTile * kK * 4, "the partial u G^T must fit the slab's bytes");
+    static constexpr int kDu = kGt + kWaves * kGtWave;
+    static constexpr int kIntra = kDu + kTile * (DV + 4) * 4;          // (dP^T (q .* A))[i][channel]
+    static constexpr int kLt = kIntra + kTile * kK * 4;                // running sums l_t, fp32 [16][64], two buffers
+    static constexpr int kA16 = kLt + 2 * kTile * kK * 4;              // A_16 per channel, fp32 [64]
+    static constexpr int kFlag = kA16 + kK * 4;                        // two flags (tile parity): != 0 = pair-by-pair route
     static constexpr int kDpPart = kFlag + 16;                         // partial dP per wavefront, fp32 [kWaves][i][t]
     static constexpr int kBytes = kDpPart + kWaves * kTile * kTile * 4;
+};
+
+struct TileBuffers {
+    float *qs, *ks, *ls;
+    unsigned char *us, *ds;
 };
 
 template <int DV>
@@ -456,22 +474,23 @@ __device__ __forceinline__ void sweep_dkv(
     constexpr int kDuRow = DV + 4;                   // padded fp32 row of du
     using M = DkvLds<DV>;
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    float *qs = reinterpret_cast<float *>(lds_raw + M::kQs), *ks = reinterpret_cast<float *>(lds_raw + M::kKs);
-    float *ls = reinterpret_cast<float *>(lds_raw + M::kLs);                 // log_alpha (clamped)
-    float *lt_s = reinterpret_cast<float *>(lds_raw + M::kLt);
+    auto tile_buffers = [&](int parity) {
+        unsigned char *b = lds_raw + parity * M::kInBytes;
+        return TileBuffers{reinterpret_cast<float *>(b), reinterpret_cast<float *>(b + M::kInKs),
+                           reinterpret_cast<float *>(b + M::kInLs), b + M::kInUs, b + M::kInDs};
+    };
     float *a16_s = reinterpret_cast<float *>(lds_raw + M::kA16);
-    unsigned char *us = lds_raw + M::kUs, *ds = lds_raw + M::kDs;
-    bf16_t *qa_s = reinterpret_cast<bf16_t *>(lds_raw + M::kQa);             // q .* A, token-major, padded rows; later dk staging
-    bf16_t *kh_s = reinterpret_cast<bf16_t *>(lds_raw + M::kKh);             // khat, token-major, padded rows
+    bf16_t *qa_s = reinterpret_cast<bf16_t *>(lds_raw + M::kQa);
+    bf16_t *kh_s = reinterpret_cast<bf16_t *>(lds_raw + M::kKh);
+    bf16_t *kq_s = reinterpret_cast<bf16_t *>(lds_raw + M::kKq);
+    bf16_t *qa_lo_s = reinterpret_cast<bf16_t *>(lds_raw + M::kQaLo);
     bf16_t *pt_s = reinterpret_cast<bf16_t *>(lds_raw + M::kPt);             // P^T: [i][t]
     float *dp_s = reinterpret_cast<float *>(lds_raw + M::kDp);               // dP: [t][i], padded rows
-    bf16_t *gt_s = reinterpret_cast<bf16_t *>(lds_raw + M::kGt) + (size_t)(threadIdx.x >> 6) * kSlab * (kK + 8);   // this wavefront's G slab as [column][channel]
-    float *red_s = reinterpret_cast<float *>(lds_raw + M::kRed);             // [kWaves][16][64] partial u G^T per wavefront
+    bf16_t *gt_s = reinterpret_cast<bf16_t *>(lds_raw + M::kGt + (threadIdx.x >> 6) * M::kGtWave);
+    float *red_own = reinterpret_cast<float *>(lds_raw + M::kGt + (threadIdx.x >> 6) * M::kGtWave);
     float *du_s = reinterpret_cast<float *>(lds_raw + M::kDu);
-    bf16_t *kq_s = reinterpret_cast<bf16_t *>(lds_raw + M::kKq);
     float *intra_s = reinterpret_cast<float *>(lds_raw + M::kIntra);
-    bf16_t *qa_lo_s = reinterpret_cast<bf16_t *>(lds_raw + M::kQaLo);
-    int *flag_s = reinterpret_cast<int *>(lds_raw + M::kFlag);               // != 0: this tile takes the pairwise route
+    int *flag_s = reinterpret_cast<int *>(lds_raw + M::kFlag);
     float *dpp_s = reinterpret_cast<float *>(lds_raw + M::kDpPart);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -502,59 +521,85 @@ __device__ __forceinline__ void sweep_dkv(
 
     // vector-ALU role of the gate and dk phases: channel vc, tokens kTok * vg .. + kTok - 1
     const int vc = tid & 63, vg = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int j = n >> 2, cc = n & 3;                  // transposing reads: this lane addresses row 4grp + j, unit cc
 
     const int ntiles = (T + kTile - 1) / kTile;
     const int part_tiles = gate_part_tiles(T);
     int run_index = ntiles > 0 ? (ntiles - 1) / part_tiles : 0;      // the current run of tiles, walked from the last one back
     int run_first = run_index * part_tiles;                           // its first tile (the last one in this direction)
     float kpart = 0.f;                                 // sum of k .* dk over this thread's tokens of the current run of tiles
-    TileLoads<DV> pf;
-    auto prefetch = [&](int t0) { tile_prefetch<DV>(g, t0, tid, has_beta, pf); };
-    if (ntiles > 0) prefetch((ntiles - 1) * kTile);
 
-    for (int it = ntiles - 1; it >= 0; --it) {
-        const int t0 = it * kTile;
-        __syncthreads();                                   // (1) the previous tile is fully consumed
-        tile_stage<DV>(pf, t0, T, tid, has_beta, qs, ks, ls, us, ds);
-        if (tid == 0) *flag_s = 0;
-        // this thread's v and beta pieces are needed again at the end of the tile (dv = beta .* du, dbeta = v .* du)
-        uint4 v_keep[L::kPerThread];
-        floatx4_t beta_keep[L::kPerThread][2];
-#pragma unroll
-        for (int u = 0; u < L::kPerThread; ++u) {
-            v_keep[u] = pf.v[u];
-            beta_keep[u][0] = pf.beta[u][0];
-            beta_keep[u][1] = pf.beta[u][1];
-        }
-        prefetch(max(t0 - kTile, 0));
-        __syncthreads();                                   // (2)
-
-        // ---- gate phase (thread = channel vc, token group vg): running sums, q .* A, khat, k ./ A
+    // ---- running sums, decayed operands and this wavefront's share of dP for the tile staged in `in` (thread = channel
+    // vc, token group vg); leaves l of the thread's own tokens and of the whole tile in registers
+    auto gate_phase = [&](const TileBuffers &in, float *lt_s, int *flag, float (&l_own)[kTok], float &l_tile) {
         float lsum[kTile];
         {
             float run = 0.f;
 #pragma unroll
             for (int i = 0; i < kTile; ++i) {
-                run += ls[i * kK + vc];
+                run += in.ls[i * kK + vc];
                 lsum[i] = run;
             }
         }
-        if (lsum[kTile - 1] < kSafeTileLog) *flag_s = 1;
-        if (vg == 0) a16_s[vc] = __expf(lsum[kTile - 1]);
+        l_tile = lsum[kTile - 1];
+        if (l_tile < kSafeTileLog) *flag = 1;
+        if (vg == 0) a16_s[vc] = __expf(l_tile);
 #pragma unroll
         for (int r = 0; r < kTok; ++r) {
-            float l_own = lsum[r];
+            float l = lsum[r];
 #pragma unroll
-            for (int gsel = 1; gsel < kWaves; ++gsel) l_own = (vg == gsel) ? lsum[kTok * gsel + r] : l_own;
+            for (int gsel = 1; gsel < kWaves; ++gsel) l = (vg == gsel) ? lsum[kTok * gsel + r] : l;
+            l_own[r] = l;
             const int t = kTok * vg + r;
-            lt_s[t * kK + vc] = l_own;
+            lt_s[t * kK + vc] = l;
             float qa_hi, qa_lo;
-            split_bf16(qs[t * kK + vc] * __expf(l_own), qa_hi, qa_lo);
+            split_bf16(in.qs[t * kK + vc] * __expf(l), qa_hi, qa_lo);
             qa_s[t * (kK + 8) + vc] = (bf16_t)qa_hi;
             qa_lo_s[t * (kK + 8) + vc] = (bf16_t)qa_lo;
-            kh_s[t * (kK + 8) + vc] = (bf16_t)(ks[t * kK + vc] * __expf(lsum[kTile - 1] - l_own));
-            kq_s[t * (kK + 8) + vc] = (bf16_t)(ks[t * kK + vc] * __expf(-l_own));       // used only by the quotient route
+            kh_s[t * (kK + 8) + vc] = (bf16_t)(in.ks[t * kK + vc] * __expf(l_tile - l));
+            kq_s[t * (kK + 8) + vc] = (bf16_t)(in.ks[t * kK + vc] * __expf(-l));       // used only by the quotient route
         }
+        // dP[t][i] = do_t . u_i over the 32 columns of this wavefront's slab; summed over the wavefronts by the readers
+        const bf16x8_t a_do = *reinterpret_cast<const bf16x8_t *>(in.ds + n * L::kRowBytes + (col0 + 8 * grp) * 2);
+        const bf16x8_t b_u = *reinterpret_cast<const bf16x8_t *>(in.us + n * L::kRowBytes + (col0 + 8 * grp) * 2);
+        const floatx4_t d = mfma_k32(a_do, b_u, floatx4_t{0.f, 0.f, 0.f, 0.f});
+        *reinterpret_cast<floatx4_t *>(&dpp_s[(wave * kTile + n) * kTile + 4 * grp]) = d;      // [wave][i = n][t = 4grp ..]
+    };
+
+    TileLoads<DV> pf;
+    uint4 v_cur, v_nxt;                                // this thread's v and beta pieces of the tile in phase Y and of the next
+    floatx4_t beta_cur[2], beta_nxt[2];
+    float l_cur[kTok], l_cur_tile = 0.f;
+#pragma unroll
+    for (int r = 0; r < kTok; ++r) l_cur[r] = 0.f;
+    if (ntiles > 0) {
+        // the last tile: staged and prepared before the loop
+        const int last = ntiles - 1;
+        const TileBuffers in = tile_buffers(last & 1);
+        tile_prefetch<DV>(g, last * kTile, tid, has_beta, pf);
+        tile_stage<DV>(pf, last * kTile, T, tid, has_beta, in.qs, in.ks, in.ls, in.us, in.ds);
+        v_cur = pf.v[0]; beta_cur[0] = pf.beta[0][0]; beta_cur[1] = pf.beta[0][1];
+        tile_prefetch<DV>(g, max(last - 1, 0) * kTile, tid, has_beta, pf);
+        if (tid < 2) flag_s[tid] = 0;
+        __syncthreads();
+        gate_phase(in, reinterpret_cast<float *>(lds_raw + M::kLt) + (last & 1) * kTile * kK, flag_s + (last & 1), l_cur, l_cur_tile);
+        __syncthreads();
+    }
+
+    for (int it = ntiles - 1; it >= 0; --it) {
+        const int t0 = it * kTile, par = it & 1;
+        const TileBuffers cur = tile_buffers(par), nxt = tile_buffers(par ^ 1);
+        float *lt_cur = reinterpret_cast<float *>(lds_raw + M::kLt) + par * kTile * kK;
+        float *lt_nxt = reinterpret_cast<float *>(lds_raw + M::kLt) + (par ^ 1) * kTile * kK;
+
+        // =============================== phase X ===============================
+        const bool pairwise = flag_s[par] != 0;
+        // tile it-1 (at it = 0: a harmless repeat of tile 0) into the other buffer, tile it-2 requested
+        tile_stage<DV>(pf, t0 - kTile, T, tid, has_beta, nxt.qs, nxt.ks, nxt.ls, nxt.us, nxt.ds);
+        v_nxt = pf.v[0]; beta_nxt[0] = pf.beta[0][0]; beta_nxt[1] = pf.beta[0][1];
+        tile_prefetch<DV>(g, max(t0 - 2 * kTile, 0), tid, has_beta, pf);
+        if (tid == 0) flag_s[par ^ 1] = 0;
+
         // this wavefront's G slab, bf16, as [column][channel] for the transposing read of the u G^T product
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
@@ -564,19 +609,8 @@ __device__ __forceinline__ void sweep_dkv(
                 const uint2 w = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3])};
                 *reinterpret_cast<uint2 *>(&gt_s[(16 * ct + n) * (kK + 8) + 16 * kt + 4 * grp]) = w;
             }
-        // this wavefront's share of dP[t][i] = do_t . u_i: the 32 columns of its slab; summed over the wavefronts after the barrier
-        {
-            const bf16x8_t a_do = *reinterpret_cast<const bf16x8_t *>(ds + n * L::kRowBytes + (col0 + 8 * grp) * 2);
-            const bf16x8_t b_u = *reinterpret_cast<const bf16x8_t *>(us + n * L::kRowBytes + (col0 + 8 * grp) * 2);
-            const floatx4_t d = mfma_k32(a_do, b_u, floatx4_t{0.f, 0.f, 0.f, 0.f});
-            *reinterpret_cast<floatx4_t *>(&dpp_s[(wave * kTile + n) * kTile + 4 * grp]) = d;      // [wave][i = n][t = 4grp ..]
-        }
-        __syncthreads();                                   // (3)
-
-        // ---- MFMA phase.  dP[t][i] = do_t . u_i (i <= t), the sum of the wavefronts' shares: lane (i = n, group grp) holds
-        // t = 4grp + r, which is the operand layout of both later uses.
-        const bool pairwise = *flag_s != 0;
-        const int j = n >> 2, cc = n & 3;                  // transposing reads: this lane addresses row 4grp + j, unit cc
+        // dP[t][i] = do_t . u_i (i <= t), the sum of the wavefronts' shares: lane (i = n, group grp) holds t = 4grp + r,
+        // which is the operand layout of both later uses.
         floatx4_t dp = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) dp += *reinterpret_cast<const floatx4_t *>(&dpp_s[(w * kTile + n) * kTile + 4 * grp]);
@@ -601,7 +635,7 @@ __device__ __forceinline__ void sweep_dkv(
             if (tid < 256 && i <= t) {
                 for (int cr = 0; cr < kK; ++cr) {
                     const int c = (cr + i) & (kK - 1);     // rotated per key row: the 16 rows of a wavefront hit 16 different banks
-                    p = fmaf(qs[t * kK + c] * ks[i * kK + c], __expf(lt_s[t * kK + c] - lt_s[i * kK + c]), p);
+                    p = fmaf(cur.qs[t * kK + c] * cur.ks[i * kK + c], __expf(lt_cur[t * kK + c] - lt_cur[i * kK + c]), p);
                 }
             }
             if (tid < 256) pt_s[i * kTile + t] = (bf16_t)p;
@@ -635,7 +669,7 @@ __device__ __forceinline__ void sweep_dkv(
                 }
                 // do^T tile: lane = column col0 + 16ct + n, 4 tokens 4grp ..; transposing read from the token-major rows
                 const int pos = col_position(col0 + 16 * ct + 4 * cc);
-                const uint2 a_do = lds_read_transposed(ds + (4 * grp + j) * L::kRowBytes + pos * 2);
+                const uint2 a_do = lds_read_transposed(cur.ds + (4 * grp + j) * L::kRowBytes + pos * 2);
                 d = mfma_k16(a_do, b_p, d);
                 // lane (token i = n, group grp) holds columns col0 + 16ct + 4grp + r
                 *reinterpret_cast<floatx4_t *>(&du_s[n * kDuRow + col0 + 16 * ct + 4 * grp]) = d;
@@ -650,8 +684,8 @@ __device__ __forceinline__ void sweep_dkv(
             for (int s = 0; s < kSlab / 32; ++s) {
                 // A operand: u rows, columns col0 + 32s + 8grp .. +7 in natural order = two 8-byte units at permuted positions
                 const int c_lo = col0 + 32 * s + 8 * grp;
-                const uint2 u_lo = *reinterpret_cast<const uint2 *>(us + n * L::kRowBytes + col_position(c_lo) * 2);
-                const uint2 u_hi = *reinterpret_cast<const uint2 *>(us + n * L::kRowBytes + col_position(c_lo + 4) * 2);
+                const uint2 u_lo = *reinterpret_cast<const uint2 *>(cur.us + n * L::kRowBytes + col_position(c_lo) * 2);
+                const uint2 u_hi = *reinterpret_cast<const uint2 *>(cur.us + n * L::kRowBytes + col_position(c_lo + 4) * 2);
                 const uint4 wa = {u_lo.x, u_lo.y, u_hi.x, u_hi.y};
 #pragma unroll
                 for (int kt = 0; kt < 4; ++kt) {
@@ -663,11 +697,11 @@ __device__ __forceinline__ void sweep_dkv(
                     d[kt] = mfma_k32(__builtin_bit_cast(bf16x8_t, wa), __builtin_bit_cast(bf16x8_t, wb), d[kt]);
                 }
             }
-            // lane (channel n of tile kt, group grp) holds tokens i = 4grp + r
+            // lane (channel n of tile kt, group grp) holds tokens i = 4grp + r; the partial replaces the slab it was made from
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) red_s[wave * kTile * kK + (4 * grp + r) * kK + 16 * kt + n] = d[kt][r];
+                for (int r = 0; r < 4; ++r) red_own[(4 * grp + r) * kK + 16 * kt + n] = d[kt][r];
         }
         // G <- diag(A_16) G + (q .* A)^T do;  on the quotient route also the tile-local part of dk before its 1 / A_i factor
         {
@@ -697,7 +731,7 @@ __device__ __forceinline__ void sweep_dkv(
             }
 #pragma unroll
             for (int ct = 0; ct < kCt; ++ct)
-                b_do[ct] = lds_read_transposed(ds + (4 * grp + j) * L::kRowBytes + col_position(col0 + 16 * ct + 4 * cc) * 2);
+                b_do[ct] = lds_read_transposed(cur.ds + (4 * grp + j) * L::kRowBytes + col_position(col0 + 16 * ct + 4 * cc) * 2);
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
@@ -707,32 +741,32 @@ __device__ __forceinline__ void sweep_dkv(
                     acc[kt][ct] = mfma_k16(a_q[kt], b_do[ct], x);
                 }
         }
-        __syncthreads();                                   // (4)
+        __syncthreads();
 
-        // ---- dk, and k .* dk in fp32 for the gate cotangent (thread = channel vc, tokens 4vg .. 4vg+3)
+        // =============================== phase Y ===============================
+        // ---- dk, and k .* dk in fp32 for the gate cotangent (thread = channel vc, tokens kTok * vg ..)
         {
 #pragma unroll
             for (int r = kTok - 1; r >= 0; --r) {
                 const int i = kTok * vg + r;
-                float l_i = lsum[r];
-#pragma unroll
-                for (int gsel = 1; gsel < kWaves; ++gsel) l_i = (vg == gsel) ? lsum[kTok * gsel + r] : l_i;
+                const float l_i = l_cur[r];
                 float khat_term = 0.f;
 #pragma unroll
-                for (int w = 0; w < kWaves; ++w) khat_term += red_s[w * kTile * kK + i * kK + vc];
-                khat_term *= __expf(lsum[kTile - 1] - l_i);
+                for (int w = 0; w < kWaves; ++w)
+                    khat_term += reinterpret_cast<const float *>(lds_raw + M::kGt + w * M::kGtWave)[i * kK + vc];
+                khat_term *= __expf(l_cur_tile - l_i);
                 float intra = 0.f;
                 if (pairwise) {
 #pragma unroll
                     for (int t = 0; t < kTile; ++t) {
-                        const float wgt = (t >= i) ? __expf(lsum[t] - l_i) : 0.f;
-                        intra = fmaf(dp_s[t * (kTile + 1) + i] * qs[t * kK + vc], wgt, intra);
+                        const float wgt = (t >= i) ? __expf(lt_cur[t * kK + vc] - l_i) : 0.f;
+                        intra = fmaf(dp_s[t * (kTile + 1) + i] * cur.qs[t * kK + vc], wgt, intra);
                     }
                 } else {
                     intra = intra_s[i * kK + vc] * __expf(-l_i);
                 }
                 const float dk_val = khat_term + intra;
-                const float kd = ks[i * kK + vc] * dk_val;  // zero for rows beyond the sequence (k is staged as zero)
+                const float kd = cur.ks[i * kK + vc] * dk_val;  // zero for rows beyond the sequence (k is staged as zero)
                 kpart += kd;
                 if (t0 + i < T) {                           // a wavefront writes whole rows
                     const size_t e = (row0 + (size_t)((unsigned)(t0 + i) * (unsigned)H)) * kK + vc;
@@ -748,17 +782,16 @@ __device__ __forceinline__ void sweep_dkv(
             }
         }
         // dv = beta .* du, dbeta = v .* du: coalesced, by the thread that loaded the same pieces of v and beta
-#pragma unroll
-        for (int u = 0; u < L::kPerThread; ++u) {
-            const int id = tid, tok = id / L::kPieces, piece = id % L::kPieces;
+        {
+            const int tok = tid / L::kPieces, piece = tid % L::kPieces;
             if (t0 + tok < T) {
                 const size_t off = (row0 + (size_t)((unsigned)(t0 + tok) * (unsigned)H)) * DV + 8 * piece;
                 const floatx4_t d0 = *reinterpret_cast<const floatx4_t *>(&du_s[tok * kDuRow + 8 * piece]);
                 const floatx4_t d1 = *reinterpret_cast<const floatx4_t *>(&du_s[tok * kDuRow + 8 * piece + 4]);
                 float x[8];
-                unpack8(v_keep[u], x);
+                unpack8(v_cur, x);
                 floatx4_t b0 = {1.f, 1.f, 1.f, 1.f}, b1 = b0;
-                if (has_beta) { b0 = beta_keep[u][0]; b1 = beta_keep[u][1]; }
+                if (has_beta) { b0 = beta_cur[0]; b1 = beta_cur[1]; }
                 const uint4 wv = {pack_bf16x2(b0[0] * d0[0], b0[1] * d0[1]), pack_bf16x2(b0[2] * d0[2], b0[3] * d0[3]),
                                   pack_bf16x2(b1[0] * d1[0], b1[1] * d1[1]), pack_bf16x2(b1[2] * d1[2], b1[3] * d1[3])};
                 *reinterpret_cast<uint4 *>(dv + off) = wv;
@@ -768,6 +801,10 @@ __device__ __forceinline__ void sweep_dkv(
                 }
             }
         }
+        // ---- tile it-1: running sums, decayed operands, share of dP
+        gate_phase(nxt, lt_nxt, flag_s + (par ^ 1), l_cur, l_cur_tile);
+        v_cur = v_nxt; beta_cur[0] = beta_nxt[0]; beta_cur[1] = beta_nxt[1];
+        __syncthreads();
     }
 
     if (dS0 != nullptr) {
