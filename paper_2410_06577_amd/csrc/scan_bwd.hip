@@ -213,7 +213,7 @@ __device__ __forceinline__ void sweep_dq(
     extern __shared__ __align__(16) unsigned char lds_raw[];
     float *qs = reinterpret_cast<float *>(lds_raw), *ks = qs + kTile * kK, *ls = ks + kTile * kK;
     unsigned char *us = reinterpret_cast<unsigned char *>(ls + kTile * kK), *ds = us + kTile * L::kRowBytes;
-    float (*dPw)[kTile][kTile] = reinterpret_cast<float (*)[kTile][kTile]>(ds + kTile * L::kRowBytes);     // [4][16][16]
+    float (*dPw)[kTile][kTile + 4] = reinterpret_cast<float (*)[kTile][kTile + 4]>(ds + kTile * L::kRowBytes);     // [4][16][16], rows padded: the four token groups write different banks
     float *qdq_s = reinterpret_cast<float *>(dPw + 4);
     bf16_t *dq_s = reinterpret_cast<bf16_t *>(qdq_s + kTile * kK);
 
@@ -443,10 +443,11 @@ template <int DV> struct DkvLds {       // byte offsets of the reverse kernel's 
     // per wavefront: its G slab as bf16 [column][channel] (padded rows), and afterwards, in the same bytes, its partial
     // u G^T as fp32 [16][64] (the slab is read before the partial exists)
     static constexpr int kGtWave = kSlabCols * (kK + 8) * 2;
-    static_assert(kGtWave >= kTile * kK * 4, "the partial u G^T must fit the slab's bytes");
+    static constexpr int kRedRow = kK + 4;                             // floats per token row of a partial: the four token groups of a wavefront land in different banks
+    static_assert(kGtWave >= kTile * kRedRow * 4, "the partial u G^T must fit the slab's bytes");
     static constexpr int kDu = kGt + kWaves * kGtWave;
     static constexpr int kIntra = kDu + kTile * (DV + 4) * 4;          // (dP^T (q .* A))[i][channel]
-    static constexpr int kLt = kIntra + kTile * kK * 4;                // running sums l_t, fp32 [16][64], two buffers
+    static constexpr int kLt = kIntra + kTile * kRedRow * 4;           // running sums l_t, fp32 [16][64], two buffers
     static constexpr int kA16 = kLt + 2 * kTile * kK * 4;              // A_16 per channel, fp32 [64]
     static constexpr int kFlag = kA16 + kK * 4;                        // two flags (tile parity): != 0 = pair-by-pair route
     static constexpr int kDpPart = kFlag + 16;                         // partial dP per wavefront, fp32 [kWaves][i][t]
@@ -612,10 +613,12 @@ __device__ __forceinline__ void sweep_dkv(
         // dP[t][i] = do_t . u_i (i <= t), the sum of the wavefronts' shares: lane (i = n, group grp) holds t = 4grp + r,
         // which is the operand layout of both later uses.
         floatx4_t dp = {0.f, 0.f, 0.f, 0.f};
+        if (wave < 4) {                                    // only the first four wavefronts use it (tile-local part of dk)
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) dp += *reinterpret_cast<const floatx4_t *>(&dpp_s[(w * kTile + n) * kTile + 4 * grp]);
+            for (int w = 0; w < kWaves; ++w) dp += *reinterpret_cast<const floatx4_t *>(&dpp_s[(w * kTile + n) * kTile + 4 * grp]);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) dp[r] = (n <= 4 * grp + r) ? dp[r] : 0.f;
+            for (int r = 0; r < 4; ++r) dp[r] = (n <= 4 * grp + r) ? dp[r] : 0.f;
+        }
         // P[t][i] in the same layout (B operand of do^T P)
         uint2 b_p;
         if (!pairwise) {
@@ -701,7 +704,7 @@ __device__ __forceinline__ void sweep_dkv(
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) red_own[(4 * grp + r) * kK + 16 * kt + n] = d[kt][r];
+                for (int r = 0; r < 4; ++r) red_own[(4 * grp + r) * M::kRedRow + 16 * kt + n] = d[kt][r];
         }
         // G <- diag(A_16) G + (q .* A)^T do;  on the quotient route also the tile-local part of dk before its 1 / A_i factor
         {
@@ -727,7 +730,7 @@ __device__ __forceinline__ void sweep_dkv(
                 d = mfma_k16(a_hi, b_lo, d);
                 d = mfma_k16(a_hi, b_hi, d);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) intra_s[(4 * grp + r) * kK + 16 * wave + n] = d[r];
+                for (int r = 0; r < 4; ++r) intra_s[(4 * grp + r) * M::kRedRow + 16 * wave + n] = d[r];
             }
 #pragma unroll
             for (int ct = 0; ct < kCt; ++ct)
@@ -753,7 +756,7 @@ __device__ __forceinline__ void sweep_dkv(
                 float khat_term = 0.f;
 #pragma unroll
                 for (int w = 0; w < kWaves; ++w)
-                    khat_term += reinterpret_cast<const float *>(lds_raw + M::kGt + w * M::kGtWave)[i * kK + vc];
+                    khat_term += reinterpret_cast<const float *>(lds_raw + M::kGt + w * M::kGtWave)[i * M::kRedRow + vc];
                 khat_term *= __expf(l_cur_tile - l_i);
                 float intra = 0.f;
                 if (pairwise) {
@@ -763,7 +766,7 @@ __device__ __forceinline__ void sweep_dkv(
                         intra = fmaf(dp_s[t * (kTile + 1) + i] * cur.qs[t * kK + vc], wgt, intra);
                     }
                 } else {
-                    intra = intra_s[i * kK + vc] * __expf(-l_i);
+                    intra = intra_s[i * M::kRedRow + vc] * __expf(-l_i);
                 }
                 const float dk_val = khat_term + intra;
                 const float kd = cur.ks[i * kK + vc] * dk_val;  // zero for rows beyond the sequence (k is staged as zero)
