@@ -39,12 +39,12 @@ template <int DV> struct BwdShape {
     static constexpr int kThreads = 64 * kWaves;
 };
 constexpr float kMinLogAlpha = -128.f;
-constexpr float kSafeTileLog = -55.f;
+constexpr float kSafeTileLog = -55.f;      // ln(2^-80) = -55.45: above it 1 / A_i stays below 2^80
 // The gate cotangent is a reverse running sum over the sequence; the sequence is cut into kGateParts runs of whole
 // tiles, the sweeps leave the sum of q .* dq (k .* dk) over every run, and the gate kernel starts each run from the
 // totals of the later ones.
 constexpr int kGateParts = 32;
-__host__ __device__ inline int gate_part_tiles(int T) { return (((T + kTile - 1) / kTile) + kGateParts - 1) / kGateParts; }      // ln(2^-80) = -55.45: above it 1 / A_i stays below 2^80
+__host__ __device__ inline int gate_part_tiles(int T) { return (((T + kTile - 1) / kTile) + kGateParts - 1) / kGateParts; }
 
 // How a call is cut along the sequence.  Slots: [segment][B*H][64][dv] fp32.
 struct BwdSegments {
@@ -1065,8 +1065,8 @@ __global__ __launch_bounds__(1024) void scan_bwd_gate_kernel(const float *__rest
 #pragma unroll 8
     for (int t = t_hi - 1; t >= t_lo; --t) {
         const size_t e = ((tok0 + t) * H + h) * kK + ch;
-        run += qdq[e] - kdk[e];
-        dla[e] = log_alpha[e] <= kMinLogAlpha ? 0.f : run;
+        run += __builtin_nontemporal_load(qdq + e) - __builtin_nontemporal_load(kdk + e);      // read once, never again
+        dla[e] = __builtin_nontemporal_load(log_alpha + e) <= kMinLogAlpha ? 0.f : run;
     }
 }
 
