@@ -192,6 +192,14 @@ def test_backward_validation(L):
     assert call(ws_bytes=16) == E_WS and call(ws=None) == E_WS
     # q .* dq and k .* dk per token, and per (batch, head, channel): one constant, 32 run totals of the first, 32 x 8 of the second
     assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 64, 128, rodimus.BF16) == (2 * 2 * 100 * 3 * 64 + 2 * 3 * 64 * 289) * 4
+    # few (batch, head) pairs and a long sequence: the call is cut along the sequence (here 2 * 1 * 2 = 4 workgroups, 16 chunks
+    # -> 4 segments of 4 chunks); units = (batch, head, segment), plus two sets of state slots and the segment decays
+    units = 1 * 2 * 4
+    assert L.rodimus_chunk_scan_bwd_workspace_bytes(1, 1000, 2, 64, 256, rodimus.BF16) == (
+        2 * 1000 * 2 * 64 + units * 64 * 289 + 2 * units * 64 * 256 + 2 * 3 * 2 * 64) * 4
+    # the layer workload fills the chip without a cut; a packed batch is never cut
+    assert L.rodimus_chunk_scan_bwd_workspace_bytes(8, 4096, 16, 64, 256, rodimus.BF16) == (2 * 8 * 4096 * 16 * 64 + 128 * 64 * 289) * 4
+    assert L.rodimus_chunk_scan_varlen_bwd_workspace_bytes(1, 1000, 2, 64, 256, rodimus.BF16) == (2 * 1000 * 2 * 64 + 2 * 64 * 289) * 4
     # any other shape takes the generic kernels: q .* dq only
     assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 32, 128, rodimus.BF16) == (2 * 100 * 3 * 32 + 2 * 3 * 32) * 4
     assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 64, 128, rodimus.F32) == (2 * 100 * 3 * 64 + 2 * 3 * 64) * 4
