@@ -135,6 +135,32 @@ def test_segments_without_state_cotangent_and_with_resets():
     assert float(out["dlog_alpha"][:, 255].abs().max()) == 0.0
 
 
+def test_full_size_layer_workload():
+    """The layer workload at its full size (B=8, T=4096, H=16, dv=256: 256 workgroups, no cut), in the launch configuration
+    bench.py times; the oracle follows the first and the last sequence (sequences are independent, so the subset check is
+    exact for them)."""
+    w = wl.LAYER_1P6B
+    print("bwd full layer workload: inputs ...", flush=True)
+    inp = wl.make_scan_inputs(w)
+    rng = np.random.Generator(np.random.PCG64(77))
+    inp["d_o"] = torch.from_numpy(rng.standard_normal((w.B, w.T, w.H, w.dv), dtype=np.float32)).to(torch.bfloat16)
+    inp["dS_T"] = torch.from_numpy(rng.standard_normal((w.B, w.H, w.dk, w.dv), dtype=np.float32) * np.float32(0.1))
+    g = to_dev(inp)
+    print("bwd full layer workload: GPU ...", flush=True)
+    out = rodimus.rodimus_chunk_scan_bwd(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], g["S0"], g["d_o"], g["dS_T"])
+    torch.cuda.synchronize()
+    for b in (0, w.B - 1):
+        print(f"bwd full layer workload: oracle on sequence {b} ...", flush=True)
+        one = {k: v[b:b + 1].contiguous() for k, v in inp.items()}
+        ref = oracle.scan_bwd(one["q"], one["k"], one["v"], one["log_alpha"], one["beta"], one["S0"], one["d_o"], one["dS_T"])
+        errs = {name: rel_err(out[name][b:b + 1], ref[name]) for name in ("dq", "dk", "dv", "dlog_alpha", "dbeta", "dS0")}
+        print("   " + "  ".join(f"{k} {v:.2e}" for k, v in errs.items()), flush=True)
+        for name, e in errs.items():
+            assert e <= TOL_BF16, (b, name, e)
+    for name in ("dq", "dk", "dv", "dlog_alpha", "dbeta", "dS0"):
+        assert torch.isfinite(out[name].float()).all(), name
+
+
 def test_unsupported_shapes_are_refused():
     # a state that neither kernel family holds: 128 x 256 in fp32 I/O (the token-by-token kernels keep it in LDS)
     x = torch.zeros(1, 4, 1, 128, device="cuda:0")
