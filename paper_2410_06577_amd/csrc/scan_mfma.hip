@@ -29,6 +29,8 @@
 // Global loads are issued one chunk ahead into registers by the wavefront that consumes them.
 #include "internal.h"
 
+// Optional cycle counters per wavefront role and loop part (build with -DRODIMUS_PROF; not part of the library's
+// interface and not in the shipped build): how the per-chunk clock budgets quoted for this kernel were measured.
 #ifdef RODIMUS_PROF
 __device__ unsigned long long g_prof[64];
 #define PROF_T() clock64()

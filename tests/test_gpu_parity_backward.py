@@ -103,6 +103,7 @@ def test_layer_head_shape():
     (1, 1000, 2, 256, True),     # four segments of 256 tokens, the last one ragged (232 = 14 * 16 + 8)
     (2, 520, 1, 128, True),      # 9 chunks -> three segments of 192 tokens, the last one 136
     (1, 768, 3, 128, False),     # zero initial state
+    (1, 16424, 1, 256, True),    # 257 chunks -> 52 segments of 5 chunks, the last one 2 chunks and 40 tokens
 ])
 def test_sequence_cut_into_segments(B, T, H, dv, s0):
     """Few (batch, head) pairs and a long sequence: the call is cut along the sequence, boundary states and cotangents
