@@ -197,7 +197,8 @@ typedef enum {
  *                                                    allowed (S_T = S0, no output rows).
  *
  * One workgroup set per (sequence, head): no workspace, no sequence split (a batch of few long sequences is better
- * served by rodimus_chunk_scan_fwd per sequence).  Shapes, kernel families, alignment (16 bytes, cu_seqlens included),
+ * served by rodimus_chunk_scan_fwd per sequence).  With up to 64 sequences the workgroups take the sequences longest
+ * first, whatever their order in the batch.  Shapes, kernel families, alignment (16 bytes, cu_seqlens included),
  * aliasing rules and status codes as for rodimus_chunk_scan_fwd; an unknown beta_kind gives RODIMUS_ERR_DTYPE.
  */
 int rodimus_chunk_scan_varlen_fwd(const void *q, const void *k, const void *v,

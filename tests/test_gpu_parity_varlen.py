@@ -65,6 +65,9 @@ def _check(lengths, H, dk, dv, chunk, io, gate="beta", s0=True, seed=1):
     ([100, 0, 17, 0], 1, 128, "beta", True),             # empty sequences keep their state
     ([700, 3, 129], 3, 384, "z_beta", False),            # value gate as pre-activation, zero initial states
     ([50, 60], 2, 128, "none", True),                    # no value gate
+    ([40, 40, 0, 130, 40, 0, 130, 7], 2, 256, "beta", True),   # equal lengths and empty sequences: the rank by length has ties
+    ([3 + (7 * i) % 50 for i in range(70)], 1, 128, "beta", True),   # more than 64 sequences: taken in batch order
+    ([1 + (5 * i) % 90 for i in range(64)], 1, 128, "z_beta", True),  # exactly 64: the largest batch that is ranked
 ])
 def test_mfma_path(lengths, H, dv, gate, s0):
     print(f"varlen mfma {lengths} H{H} dv{dv} {gate}", flush=True)
