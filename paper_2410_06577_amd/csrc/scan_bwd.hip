@@ -222,7 +222,10 @@ __device__ __forceinline__ void sweep_dq(
     const bool computes = wave < 4;
     const int c = lane & 15, tg = lane >> 4;          // vector-ALU role: channel 16*wave + c, tokens 4tg .. 4tg+3
     const int ch = 16 * (wave & 3) + c;
-    const int bh = blockIdx.x, seg = blockIdx.y;
+    int bh = blockIdx.x;
+    const int seg = blockIdx.y;
+    if (cu_seqlens != nullptr)                                    // packed batch: sequences by descending length (small batches)
+        bh = sequence_by_length_rank(cu_seqlens, (int)gridDim.x / H, T, bh / H, reinterpret_cast<int *>(lds_raw)) * H + bh % H;
     const size_t unit = (size_t)seg * gridDim.x + bh;             // (segment, batch, head): index of the per-unit totals
     const bool has_beta = beta != nullptr;
     const SeqSpan span = segment_span(seq_span(bh / H, T, cu_seqlens), segs, seg);
@@ -496,7 +499,10 @@ __device__ __forceinline__ void sweep_dkv(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, grp = lane >> 4;
-    const int bh = blockIdx.x, seg = blockIdx.y;
+    int bh = blockIdx.x;
+    const int seg = blockIdx.y;
+    if (cu_seqlens != nullptr)                                    // packed batch: sequences by descending length (small batches)
+        bh = sequence_by_length_rank(cu_seqlens, (int)gridDim.x / H, T, bh / H, reinterpret_cast<int *>(lds_raw)) * H + bh % H;
     const size_t unit = (size_t)seg * gridDim.x + bh;
     const bool has_beta = beta != nullptr;
     const SeqSpan span = segment_span(seq_span(bh / H, T, cu_seqlens), segs, seg);

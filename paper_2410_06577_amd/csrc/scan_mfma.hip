@@ -55,8 +55,6 @@ constexpr int kTile = 16;        // rows per state update
 constexpr int kChunk = 64;       // tokens per barrier (4 tiles)
 constexpr int kColTile = 128;    // value columns per workgroup
 constexpr int kThreads = 512;
-constexpr int kRankedSeqs = 64;  // packed batches of up to this many sequences are walked longest first (beyond that the
-                                 // ranking in every workgroup costs more than the order gains: 128 sequences 371 against 349 us)
 
 // ---- LDS map (bytes).  Two buffers (chunk parity) of what the gate wavefronts hand to the state wavefronts.
 constexpr int kQnTile = kTile * 128;                 // q .* A,      [16 rows][64 ch] bf16, 16-byte units swizzled by row
@@ -717,34 +715,12 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
     const bool has_beta = beta != nullptr;
     if (!kSummary && cu_seqlens != nullptr) {
         // Packed batch, launched as a flat grid: the column tiles of one (sequence, head) are neighbours in dispatch order
-        // (they read the same q, k and gates while those are in the cache), and with up to kRankedSeqs sequences the
-        // workgroups take the sequences by descending length, because workgroups start in index order and a long
-        // sequence that starts last would run on alone at the end.
+        // (they read the same q, k and gates while those are in the cache), and the workgroups take the sequences by
+        // descending length (small batches).
         const int col_tiles = dv / kColTile, nseq = (int)(gridDim.x / (unsigned)(col_tiles * H));
         col_tile = blockIdx.x % col_tiles;
         const int slot = blockIdx.x / col_tiles, rank = slot / H;
-        int b = rank;
-        if (nseq <= kRankedSeqs) {
-            int *len_s = reinterpret_cast<int *>(lds);             // the dynamic LDS is free until the walk starts
-            __shared__ int chosen;
-            for (int i = tid; i < nseq; i += kThreads) {
-                const int first = min(max(cu_seqlens[i], 0), total_tokens);
-                len_s[i] = min(max(cu_seqlens[i + 1], first), total_tokens) - first;
-            }
-            __syncthreads();
-            // kThreads / npad threads per candidate sequence (npad = nseq rounded up to a power of two), each counting over
-            // a stride of the others; the counts of a candidate's threads (neighbouring lanes) are added by shuffles
-            int npad = 8;
-            while (npad < nseq) npad *= 2;
-            const int per = min(kThreads / npad, 64), cand = tid / per, part = tid % per;
-            const int mine = len_s[min(cand, nseq - 1)];
-            int before = 0;                                         // sequences that come before cand: longer, or as long with a smaller index
-            for (int u = part; u < nseq; u += per) before += (len_s[u] > mine || (len_s[u] == mine && u < cand)) ? 1 : 0;
-            for (int step = 1; step < per; step *= 2) before += __shfl_xor(before, step);
-            if (cand < nseq && part == 0 && before == rank) chosen = cand;
-            __syncthreads();
-            b = chosen;                                             // (every read of len_s lies before the barrier above)
-        }
+        const int b = sequence_by_length_rank(cu_seqlens, nseq, total_tokens, rank, reinterpret_cast<int *>(lds));   // the dynamic LDS is free until the walk starts
         bh = b * H + slot % H;
     }
 
