@@ -238,8 +238,8 @@ __device__ __forceinline__ int sequence_by_length_rank(const int *cu_seqlens, in
 {
     if (nseq > kRankedSeqs) return rank;
     __shared__ int chosen;
-    const int tid = threadIdx.x, nthreads = blockDim.x;
-    for (int i = tid; i < nseq; i += nthreads) {
+    const int tid = threadIdx.x, nthreads = 1 << (31 - __clz((int)blockDim.x));      // a power of two; any further threads only wait
+    for (int i = tid; i < nseq; i += (int)blockDim.x) {
         const int first = min(max(cu_seqlens[i], 0), total_tokens);
         scratch[i] = min(max(cu_seqlens[i + 1], first), total_tokens) - first;
     }

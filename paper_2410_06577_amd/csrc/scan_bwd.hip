@@ -37,6 +37,11 @@ constexpr int kTile = 16;
 template <int DV> struct BwdShape {
     static constexpr int kWaves = DV / 32;
     static constexpr int kThreads = 64 * kWaves;
+    // The sweeps kernel adds half as many helper wavefronts: in the reverse sweep they load and stage the tile inputs and
+    // write dv and dbeta, which takes that work and its registers off the wavefronts that carry G (three wavefronts per
+    // SIMD instead of two); in the forward sweep they only take part in the barriers.
+    static constexpr int kHelpers = kWaves / 2;
+    static constexpr int kSweepThreads = 64 * (kWaves + kHelpers);
 };
 constexpr float kMinLogAlpha = -128.f;
 constexpr float kSafeTileLog = -55.f;      // ln(2^-80) = -55.45: above it 1 / A_i stays below 2^80
@@ -193,6 +198,88 @@ __device__ __forceinline__ void tile_stage(const TileLoads<DV> &p, int t0, int T
     }
 }
 
+// ---- the reverse sweep's helper wavefronts: thread `hid` of 32 * kWaves takes two (token, piece) pairs of v, do, beta and
+// one (dv = 256) or two (dv = 128) pieces each of q / k and log_alpha
+template <int DV> struct HelperLoads {
+    uint4 qk[2];
+    floatx4_t la[2];
+    uint4 v[2], d_o[2];
+    floatx4_t beta[2][2];
+};
+
+template <int DV>
+__device__ __forceinline__ void helper_prefetch(const BwdGeometry &g, int t0, int hid, bool has_beta, HelperLoads<DV> &p)
+{
+    using L = BwdLayout<DV>;
+    constexpr int kHelp = 32 * BwdShape<DV>::kWaves;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const int idx = hid + s * kHelp;
+        if (s * kHelp < 256) {                             // 256 pieces of q and k together, 256 of log_alpha
+            const int tok = (idx & 127) >> 3, piece = idx & 7;
+            p.qk[s] = *reinterpret_cast<const uint4 *>((idx < 128 ? g.q : g.k) + (size_t)g.row(t0 + tok) * kK + 8 * piece);
+            p.la[s] = *reinterpret_cast<const floatx4_t *>(g.la + (size_t)g.row(t0 + (idx >> 4)) * kK + 4 * (idx & 15));
+        }
+        const int tok = idx / L::kPieces, piece = idx % L::kPieces;
+        const size_t off = (size_t)g.row(t0 + tok) * DV + 8 * piece;
+        p.v[s] = *reinterpret_cast<const uint4 *>(g.v + off);
+        p.d_o[s] = *reinterpret_cast<const uint4 *>(g.d_o + off);
+        if (has_beta) {
+            p.beta[s][0] = *reinterpret_cast<const floatx4_t *>(g.beta + off);
+            p.beta[s][1] = *reinterpret_cast<const floatx4_t *>(g.beta + off + 4);
+        }
+    }
+}
+
+// The same LDS image as tile_stage leaves
+template <int DV>
+__device__ __forceinline__ void helper_stage(const HelperLoads<DV> &p, int t0, int T, int hid, bool has_beta, float *qs, float *ks,
+                                             float *ls, unsigned char *us, unsigned char *ds)
+{
+    using L = BwdLayout<DV>;
+    constexpr int kHelp = 32 * BwdShape<DV>::kWaves;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const int idx = hid + s * kHelp;
+        if (s * kHelp < 256) {
+            {
+                const int tok = (idx & 127) >> 3, piece = idx & 7;
+                const bool valid = t0 + tok < T;
+                float x[8];
+                unpack8(p.qk[s], x);
+                float *dst = (idx < 128 ? qs : ks) + tok * kK + 8 * piece;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dst[e] = valid ? x[e] : 0.f;
+            }
+            {
+                const int tok = idx >> 4, piece = idx & 15;
+                const bool valid = t0 + tok < T;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) ls[tok * kK + 4 * piece + e] = valid ? fmaxf(p.la[s][e], kMinLogAlpha) : 0.f;
+            }
+        }
+        const int tok = idx / L::kPieces, piece = idx % L::kPieces;
+        const bool valid = t0 + tok < T;
+        float x[8], d[8];
+        unpack8(p.v[s], x);
+        unpack8(p.d_o[s], d);
+        if (has_beta) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { x[e] *= p.beta[s][0][e]; x[4 + e] *= p.beta[s][1][e]; }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { x[e] = valid ? x[e] : 0.f; d[e] = valid ? d[e] : 0.f; }
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int pos = col_position(8 * piece + 4 * half);
+            const uint2 wu = {pack_bf16x2(x[4 * half], x[4 * half + 1]), pack_bf16x2(x[4 * half + 2], x[4 * half + 3])};
+            const uint2 wd = {pack_bf16x2(d[4 * half], d[4 * half + 1]), pack_bf16x2(d[4 * half + 2], d[4 * half + 3])};
+            *reinterpret_cast<uint2 *>(us + tok * L::kRowBytes + pos * 2) = wu;
+            *reinterpret_cast<uint2 *>(ds + tok * L::kRowBytes + pos * 2) = wd;
+        }
+    }
+}
+
 // =========================================================================================================
 // Forward sweep: dq (and q .* dq in fp32 for the gate cotangent, and rowsum(S_T .* dS_T))
 // =========================================================================================================
@@ -250,13 +337,10 @@ __device__ __forceinline__ void sweep_dq(
     const int part_tiles = gate_part_tiles(T);
     int run_index = 0, run_last = part_tiles - 1;      // the current run of tiles and its last tile
     float qpart = 0.f;                                 // sum of q .* dq over this lane's tokens of the current run of tiles
-    TileLoads<DV> pf;
-    if (ntiles > 0) tile_prefetch<DV>(g, 0, tid, has_beta, pf);
-
-    // coalesced stores of a finished tile's dq (bf16) and q .* dq (fp32) from the staging buffers
-    auto store_tile = [&](int t0) {
-        const int tok = tid >> 4, piece = tid & 15;
-        if (tid < 256 && t0 + tok < T) {
+    // coalesced stores of a finished tile's dq (bf16) and q .* dq (fp32) from the staging buffers, by 256 threads
+    auto store_tile = [&](int t0, int stid) {
+        const int tok = stid >> 4, piece = stid & 15;
+        if (stid < 256 && t0 + tok < T) {
             const size_t row = row0 + (size_t)((unsigned)(t0 + tok) * (unsigned)H);
             *reinterpret_cast<floatx4_t *>(qdq + row * kK + 4 * piece) = *reinterpret_cast<const floatx4_t *>(qdq_s + tok * kK + 4 * piece);
             if (piece < 8)
@@ -264,12 +348,38 @@ __device__ __forceinline__ void sweep_dq(
         }
     };
 
+    // With 512 threads behind the four computing wavefronts (dv = 256) those fetch, stage and store, and the computing
+    // wavefronts keep no loads in registers; otherwise (dv = 128) the computing wavefronts stage as well and the helper
+    // wavefronts of the kernel only take part in the barriers.
+    constexpr bool kSplitRoles = BwdShape<DV>::kSweepThreads >= 256 + BwdShape<DV>::kThreads;
+    if (kSplitRoles && wave >= 4) {
+        const int stid = tid - 256;
+        TileLoads<DV> pf;
+        if (ntiles > 0) tile_prefetch<DV>(g, 0, stid, has_beta, pf);
+        for (int it = 0; it < ntiles; ++it) {
+            const int t0 = it * kTile;
+            __syncthreads();                               // the previous tile is computed: its results are staged, its inputs free
+            if (it > 0) store_tile(t0 - kTile, stid);
+            tile_stage<DV>(pf, t0, T, stid, has_beta, qs, ks, ls, us, ds);
+            tile_prefetch<DV>(g, t0 + kTile, stid, has_beta, pf);   // clamped addresses; masked when staged
+            __syncthreads();
+        }
+        __syncthreads();
+        if (ntiles > 0) store_tile((ntiles - 1) * kTile, stid);
+        return;
+    }
+    TileLoads<DV> pf;
+    const bool stages = !kSplitRoles && tid < BwdShape<DV>::kThreads;
+    if (ntiles > 0 && stages) tile_prefetch<DV>(g, 0, tid, has_beta, pf);
+
     for (int it = 0; it < ntiles; ++it) {
         const int t0 = it * kTile;
         __syncthreads();                                   // the previous tile is computed: its results are staged, its inputs free
-        if (it > 0) store_tile(t0 - kTile);
-        tile_stage<DV>(pf, t0, T, tid, has_beta, qs, ks, ls, us, ds);
-        tile_prefetch<DV>(g, t0 + kTile, tid, has_beta, pf);        // clamped addresses; masked when staged
+        if (stages) {
+            if (it > 0) store_tile(t0 - kTile, tid);
+            tile_stage<DV>(pf, t0, T, tid, has_beta, qs, ks, ls, us, ds);
+            tile_prefetch<DV>(g, t0 + kTile, tid, has_beta, pf);    // clamped addresses; masked when staged
+        }
         __syncthreads();
         if (!computes) continue;          // wavefront-uniform; the two barriers above are reached by every wavefront
 
@@ -393,7 +503,7 @@ __device__ __forceinline__ void sweep_dq(
         }
     }
     __syncthreads();
-    if (ntiles > 0) store_tile((ntiles - 1) * kTile);
+    if (ntiles > 0 && stages) store_tile((ntiles - 1) * kTile, tid);
 
     // rowsum(S_T .* dS_T) for this lane's channel: constant term of every gate cotangent of this (batch, head)
     if (!computes) return;
@@ -524,7 +634,7 @@ __device__ __forceinline__ void sweep_dkv(
         for (int ct = 0; ct < kCt; ++ct)
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                acc[kt][ct][r] = dS_T != nullptr ? dS_T[state_base + (size_t)(16 * kt + 4 * grp + r) * DV + col0 + 16 * ct + n] : 0.f;
+                acc[kt][ct][r] = (dS_T != nullptr && wave < kWaves) ? dS_T[state_base + (size_t)(16 * kt + 4 * grp + r) * DV + col0 + 16 * ct + n] : 0.f;
 
     // vector-ALU role of the gate and dk phases: channel vc, tokens kTok * vg .. + kTok - 1
     const int vc = tid & 63, vg = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -573,20 +683,73 @@ __device__ __forceinline__ void sweep_dkv(
         *reinterpret_cast<floatx4_t *>(&dpp_s[(wave * kTile + n) * kTile + 4 * grp]) = d;      // [wave][i = n][t = 4grp ..]
     };
 
-    TileLoads<DV> pf;
-    uint4 v_cur, v_nxt;                                // this thread's v and beta pieces of the tile in phase Y and of the next
-    floatx4_t beta_cur[2], beta_nxt[2];
+    // Roles (wavefront-uniform): the first kWaves wavefronts carry G and do the products, dk and the running sums; the
+    // helper wavefronts behind them load and stage the tile inputs and write dv and dbeta.
+    constexpr int kHelp = 32 * kWaves;
+    const bool helper = wave >= kWaves;
+    const int hid = tid - 64 * kWaves;
+    if (helper) {
+        // The helper wavefronts' whole walk: the same barriers as the other wavefronts, in the same order.
+        HelperLoads<DV> pf;
+        uint4 v_cur[2], v_nxt[2];                      // this thread's v and beta pieces of the tile in phase Y and of the next
+        floatx4_t beta_cur[2][2], beta_nxt[2][2];
+        if (ntiles > 0) {
+            const int last = ntiles - 1;
+            const TileBuffers in = tile_buffers(last & 1);
+            helper_prefetch<DV>(g, last * kTile, hid, has_beta, pf);
+            helper_stage<DV>(pf, last * kTile, T, hid, has_beta, in.qs, in.ks, in.ls, in.us, in.ds);
+#pragma unroll
+            for (int s = 0; s < 2; ++s) { v_cur[s] = pf.v[s]; beta_cur[s][0] = pf.beta[s][0]; beta_cur[s][1] = pf.beta[s][1]; }
+            helper_prefetch<DV>(g, max(last - 1, 0) * kTile, hid, has_beta, pf);
+            __syncthreads();
+            __syncthreads();
+        }
+        for (int it = ntiles - 1; it >= 0; --it) {
+            const int t0 = it * kTile, par = it & 1;
+            const TileBuffers nxt = tile_buffers(par ^ 1);
+            // phase X: tile it-1 (at it = 0: a harmless repeat of tile 0) into the other buffer, tile it-2 requested
+            const bool pairwise = flag_s[par] != 0;
+            helper_stage<DV>(pf, t0 - kTile, T, hid, has_beta, nxt.qs, nxt.ks, nxt.ls, nxt.us, nxt.ds);
+#pragma unroll
+            for (int s = 0; s < 2; ++s) { v_nxt[s] = pf.v[s]; beta_nxt[s][0] = pf.beta[s][0]; beta_nxt[s][1] = pf.beta[s][1]; }
+            helper_prefetch<DV>(g, max(t0 - 2 * kTile, 0), hid, has_beta, pf);
+            if (pairwise) __syncthreads();                 // the pair-by-pair route of the other wavefronts has a barrier of its own
+            __syncthreads();
+            // phase Y
+            // dv = beta .* du, dbeta = v .* du: coalesced, by the helper thread that loaded the same pieces of v and beta
+    #pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const int idx = hid + s * kHelp, tok = idx / L::kPieces, piece = idx % L::kPieces;
+                if (t0 + tok < T) {
+                    const size_t off = (row0 + (size_t)((unsigned)(t0 + tok) * (unsigned)H)) * DV + 8 * piece;
+                    const floatx4_t d0 = *reinterpret_cast<const floatx4_t *>(&du_s[tok * kDuRow + 8 * piece]);
+                    const floatx4_t d1 = *reinterpret_cast<const floatx4_t *>(&du_s[tok * kDuRow + 8 * piece + 4]);
+                    float x[8];
+                    unpack8(v_cur[s], x);
+                    floatx4_t b0 = {1.f, 1.f, 1.f, 1.f}, b1 = b0;
+                    if (has_beta) { b0 = beta_cur[s][0]; b1 = beta_cur[s][1]; }
+                    const uint4 wv = {pack_bf16x2(b0[0] * d0[0], b0[1] * d0[1]), pack_bf16x2(b0[2] * d0[2], b0[3] * d0[3]),
+                                      pack_bf16x2(b1[0] * d1[0], b1[1] * d1[1]), pack_bf16x2(b1[2] * d1[2], b1[3] * d1[3])};
+                    *reinterpret_cast<uint4 *>(dv + off) = wv;
+                    if (dbeta != nullptr) {
+                        *reinterpret_cast<floatx4_t *>(dbeta + off) = floatx4_t{x[0] * d0[0], x[1] * d0[1], x[2] * d0[2], x[3] * d0[3]};
+                        *reinterpret_cast<floatx4_t *>(dbeta + off + 4) = floatx4_t{x[4] * d1[0], x[5] * d1[1], x[6] * d1[2], x[7] * d1[3]};
+                    }
+                }
+                v_cur[s] = v_nxt[s]; beta_cur[s][0] = beta_nxt[s][0]; beta_cur[s][1] = beta_nxt[s][1];
+            }
+            __syncthreads();
+        }
+        return;
+    }
+
     float l_cur[kTok], l_cur_tile = 0.f;
 #pragma unroll
     for (int r = 0; r < kTok; ++r) l_cur[r] = 0.f;
     if (ntiles > 0) {
-        // the last tile: staged and prepared before the loop
+        // the last tile (staged by the helpers) is prepared before the loop
         const int last = ntiles - 1;
         const TileBuffers in = tile_buffers(last & 1);
-        tile_prefetch<DV>(g, last * kTile, tid, has_beta, pf);
-        tile_stage<DV>(pf, last * kTile, T, tid, has_beta, in.qs, in.ks, in.ls, in.us, in.ds);
-        v_cur = pf.v[0]; beta_cur[0] = pf.beta[0][0]; beta_cur[1] = pf.beta[0][1];
-        tile_prefetch<DV>(g, max(last - 1, 0) * kTile, tid, has_beta, pf);
         if (tid < 2) flag_s[tid] = 0;
         __syncthreads();
         gate_phase(in, reinterpret_cast<float *>(lds_raw + M::kLt) + (last & 1) * kTile * kK, flag_s + (last & 1), l_cur, l_cur_tile);
@@ -601,10 +764,6 @@ __device__ __forceinline__ void sweep_dkv(
 
         // =============================== phase X ===============================
         const bool pairwise = flag_s[par] != 0;
-        // tile it-1 (at it = 0: a harmless repeat of tile 0) into the other buffer, tile it-2 requested
-        tile_stage<DV>(pf, t0 - kTile, T, tid, has_beta, nxt.qs, nxt.ks, nxt.ls, nxt.us, nxt.ds);
-        v_nxt = pf.v[0]; beta_nxt[0] = pf.beta[0][0]; beta_nxt[1] = pf.beta[0][1];
-        tile_prefetch<DV>(g, max(t0 - 2 * kTile, 0), tid, has_beta, pf);
         if (tid == 0) flag_s[par ^ 1] = 0;
 
         // this wavefront's G slab, bf16, as [column][channel] for the transposing read of the u G^T product
@@ -790,29 +949,8 @@ __device__ __forceinline__ void sweep_dkv(
                 run_first -= part_tiles;
             }
         }
-        // dv = beta .* du, dbeta = v .* du: coalesced, by the thread that loaded the same pieces of v and beta
-        {
-            const int tok = tid / L::kPieces, piece = tid % L::kPieces;
-            if (t0 + tok < T) {
-                const size_t off = (row0 + (size_t)((unsigned)(t0 + tok) * (unsigned)H)) * DV + 8 * piece;
-                const floatx4_t d0 = *reinterpret_cast<const floatx4_t *>(&du_s[tok * kDuRow + 8 * piece]);
-                const floatx4_t d1 = *reinterpret_cast<const floatx4_t *>(&du_s[tok * kDuRow + 8 * piece + 4]);
-                float x[8];
-                unpack8(v_cur, x);
-                floatx4_t b0 = {1.f, 1.f, 1.f, 1.f}, b1 = b0;
-                if (has_beta) { b0 = beta_cur[0]; b1 = beta_cur[1]; }
-                const uint4 wv = {pack_bf16x2(b0[0] * d0[0], b0[1] * d0[1]), pack_bf16x2(b0[2] * d0[2], b0[3] * d0[3]),
-                                  pack_bf16x2(b1[0] * d1[0], b1[1] * d1[1]), pack_bf16x2(b1[2] * d1[2], b1[3] * d1[3])};
-                *reinterpret_cast<uint4 *>(dv + off) = wv;
-                if (dbeta != nullptr) {
-                    *reinterpret_cast<floatx4_t *>(dbeta + off) = floatx4_t{x[0] * d0[0], x[1] * d0[1], x[2] * d0[2], x[3] * d0[3]};
-                    *reinterpret_cast<floatx4_t *>(dbeta + off + 4) = floatx4_t{x[4] * d1[0], x[5] * d1[1], x[6] * d1[2], x[7] * d1[3]};
-                }
-            }
-        }
         // ---- tile it-1: running sums, decayed operands, share of dP
         gate_phase(nxt, lt_nxt, flag_s + (par ^ 1), l_cur, l_cur_tile);
-        v_cur = v_nxt; beta_cur[0] = beta_nxt[0]; beta_cur[1] = beta_nxt[1];
         __syncthreads();
     }
 
@@ -874,7 +1012,7 @@ namespace {
 // workgroups than compute units the short ones fill the gaps at the end (the other order measured 1058 us against the
 // 988 us of an uncut call on the layer workload cut in two).
 template <int DV>
-__global__ __launch_bounds__(BwdShape<DV>::kThreads) void scan_bwd_sweeps_kernel(
+__global__ __launch_bounds__(BwdShape<DV>::kSweepThreads) void scan_bwd_sweeps_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const float *__restrict__ log_alpha, const float *__restrict__ beta, const float *__restrict__ S0,
     const bf16_t *__restrict__ d_o, const float *__restrict__ dS_T, bf16_t *__restrict__ dq, bf16_t *__restrict__ dk,
@@ -1110,7 +1248,7 @@ hipError_t launch_scan_bwd_typed(const ScanBwdArgs &a)
     hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_bwd_sweeps_kernel<DV>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, DkvLds<DV>::kBytes);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL(scan_bwd_sweeps_kernel<DV>, dim3(bh, (unsigned)sp.nseg, 2), dim3(BwdShape<DV>::kThreads), DkvLds<DV>::kBytes,
+    hipLaunchKernelGGL(scan_bwd_sweeps_kernel<DV>, dim3(bh, (unsigned)sp.nseg, 2), dim3(BwdShape<DV>::kSweepThreads), DkvLds<DV>::kBytes,
                        a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0,
                        (const bf16_t *)a.d_o, a.dS_T, (bf16_t *)a.dq, (bf16_t *)a.dk, (bf16_t *)a.dv, a.dbeta, a.dS0, qdq, kdk,
                        gate_const, qtot, ktot, a.T, a.H, a.cu_seqlens, segs);
