@@ -704,7 +704,7 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const void *__restrict__ log_alpha, const bf16_t *__restrict__ z_tau, const void *__restrict__ beta, const float *S0,
     bf16_t *__restrict__ o, float *S_T, int T, int H, int dv, SegmentPlan plan, const int *__restrict__ cu_seqlens,
-    int total_tokens)
+    int total_tokens, int total_seqs)
 {
     extern __shared__ __align__(16) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -713,6 +713,15 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
     const int seg = blockIdx.z;
     const int BH = gridDim.x;
     const bool has_beta = beta != nullptr;
+    if (!kSummary && cu_seqlens == nullptr && gridDim.y == 1 && gridDim.z == 1 && dv > kColTile) {
+        // Dense batch with more workgroups than compute units, launched flat: workgroups go round-robin over the eight XCDs
+        // (each with its own L2), so in every run of 8 * col_tiles workgroups the column tiles of a (batch, head) are 8
+        // apart: on the same XCD and started together, they share q, k and the gates in its L2.
+        const int col_tiles = dv / kColTile;
+        col_tile = (blockIdx.x / 8) % col_tiles;
+        bh = (blockIdx.x / (8 * col_tiles)) * 8 + blockIdx.x % 8;
+        if (bh >= total_seqs * H) return;                   // the grid is rounded up to whole runs
+    }
     if (!kSummary && cu_seqlens != nullptr) {
         // Packed batch, launched as a flat grid: the column tiles of one (sequence, head) are neighbours in dispatch order
         // (they read the same q, k and gates while those are in the cache), and the workgroups take the sequences by
@@ -949,16 +958,18 @@ hipError_t launch_scan_mfma_typed(const ScanArgs &a)
         hipLaunchKernelGGL((scan_mfma_kernel<true, kZBeta, kGated>), dim3((unsigned)bh, col_tiles, (unsigned)(sp.nseg - 1)), block,
                            kLdsBytes, a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, gate_a,
                            (const bf16_t *)a.z_tau, a.beta, (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, a.T, a.H, a.dv, plan,
-                           (const int *)nullptr, 0);
+                           (const int *)nullptr, 0, 0);
         const size_t quads = bh * kK * a.dv / 4;
         hipLaunchKernelGGL(segment_state_scan_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, a.stream, a.S0,
                            plan, a.dv, quads);
     }
     // dense: (batch, head) x column tile x segment; packed: one flat index (see the kernel)
-    const dim3 grid = a.cu_seqlens != nullptr ? dim3((unsigned)(bh * col_tiles)) : dim3((unsigned)bh, col_tiles, (unsigned)sp.nseg);
+    const bool flat_dense = a.cu_seqlens == nullptr && sp.nseg == 1 && col_tiles > 1 && bh * col_tiles > 256;
+    const dim3 grid = a.cu_seqlens != nullptr ? dim3((unsigned)(bh * col_tiles))
+                      : flat_dense ? dim3((unsigned)((bh + 7) / 8 * 8 * col_tiles)) : dim3((unsigned)bh, col_tiles, (unsigned)sp.nseg);
     hipLaunchKernelGGL((scan_mfma_kernel<false, kZBeta, kGated>), grid, block, kLdsBytes,
                        a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, gate_a, (const bf16_t *)a.z_tau, a.beta, a.S0,
-                       (bf16_t *)a.o, a.S_T, a.T, a.H, a.dv, plan, a.cu_seqlens, a.T);
+                       (bf16_t *)a.o, a.S_T, a.T, a.H, a.dv, plan, a.cu_seqlens, a.T, a.B);
     if (a.stage.any()) {
         const size_t tokens = a.cu_seqlens != nullptr ? (size_t)a.T : (size_t)a.B * a.T;
         const size_t pieces = tokens * a.H * a.dv / 8;
@@ -987,7 +998,7 @@ hipError_t launch_scan_segment_states(const void *k, const void *v, const float 
     hipLaunchKernelGGL((scan_mfma_kernel<true, false, false>), dim3((unsigned)bh, (unsigned)(dv / kColTile), (unsigned)(nseg - 1)),
                        dim3(kThreads), kLdsBytes, stream, (const bf16_t *)nullptr, (const bf16_t *)k, (const bf16_t *)v,
                        static_cast<const void *>(log_alpha), (const bf16_t *)nullptr, static_cast<const void *>(beta),
-                       (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, T, H, dv, plan, (const int *)nullptr, 0);
+                       (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, T, H, dv, plan, (const int *)nullptr, 0, 0);
     const size_t quads = bh * kK * dv / 4;
     hipLaunchKernelGGL(segment_state_scan_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, S0, plan, dv, quads);
     return hipGetLastError();

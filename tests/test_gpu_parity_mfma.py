@@ -40,6 +40,20 @@ def test_small_shapes(B, T, H, dv, s0):
     print(f"   o {eo:.2e}  S_T {es:.2e}", flush=True)
 
 
+@pytest.mark.parametrize("B,T,H,dv", [
+    (9, 130, 15, 256),           # 135 (batch, head) pairs x 2 column tiles = 270 workgroups; 135 is not a multiple of 8
+    (6, 70, 15, 384),            # 90 pairs x 3 column tiles
+])
+def test_more_workgroups_than_compute_units(B, T, H, dv):
+    """Dense batches with more than 256 workgroups run on a flat grid that keeps the column tiles of a (batch, head) on one
+    XCD; the grid is rounded up to whole runs of eight pairs."""
+    print(f"mfma flat grid B{B} T{T} H{H} dv{dv}", flush=True)
+    assert rodimus.rodimus_chunk_scan_workspace_bytes(B, T, H, 64, dv, 64, torch.bfloat16) == 0      # not the split path
+    inp = _case(B, T, H, dv, True, seed=B + dv)
+    eo, es = check_scan(inp, 64, f"flat B{B}T{T}H{H}dv{dv}")
+    print(f"   o {eo:.2e}  S_T {es:.2e}", flush=True)
+
+
 @pytest.mark.parametrize("B,T,H,dv,s0", [
     (1, 640, 2, 384, True),      # 10 chunks -> 2 segments of 5
     (1, 581, 1, 128, True),      # ragged last segment
