@@ -241,11 +241,11 @@ int rodimus_oracle_ddts_gates(const float *z_g, const float *z_tau, const float 
  * beta == NULL means the all-ones gate (dbeta is then not written and may be NULL).  Any output pointer may be NULL.
  * Returns 0 on success, 1 on bad arguments, 2 on allocation failure.
  */
-int rodimus_oracle_scan_bwd(const float *q, const float *k, const float *v,
-                            const float *log_alpha, const float *beta, const double *S0,
-                            const double *d_o, const double *dS_T,
-                            double *dq, double *dk, double *dv, double *dlog_alpha, double *dbeta, double *dS0,
-                            int B, int T, int H, int dk_, int dv_)
+static int scan_bwd_impl(const float *q, const float *k, const float *v,
+                         const float *log_alpha, const float *beta, int beta_is_preactivation, const double *S0,
+                         const double *d_o, const double *dS_T,
+                         double *dq, double *dk, double *dv, double *dlog_alpha, double *dbeta, double *dS0,
+                         int B, int T, int H, int dk_, int dv_)
 {
     const int n = dk_, m = dv_, segment = 64;
     if (!q || !k || !v || !log_alpha || !d_o) return 1;
@@ -279,7 +279,7 @@ int rodimus_oracle_scan_bwd(const float *q, const float *k, const float *v,
                 for (int t = s * segment; t < t1; ++t) {
                     const size_t row = ((size_t)b * T + t) * H + h;
                     ddts_update(cur, q + row * n, k + row * n, v + row * m, log_alpha + row * n,
-                                beta ? beta + row * m : NULL, 0, otmp, n, m, u);
+                                beta ? beta + row * m : NULL, beta_is_preactivation, otmp, n, m, u);
                 }
             }
             /* reverse sweep */
@@ -292,7 +292,7 @@ int rodimus_oracle_scan_bwd(const float *q, const float *k, const float *v,
                     double *nxt = sb + (size_t)(t - t0 + 1) * sz;
                     for (size_t e = 0; e < sz; ++e) nxt[e] = sb[(size_t)(t - t0) * sz + e];
                     ddts_update(nxt, q + row * n, k + row * n, v + row * m, log_alpha + row * n,
-                                beta ? beta + row * m : NULL, 0, otmp, n, m, u);
+                                beta ? beta + row * m : NULL, beta_is_preactivation, otmp, n, m, u);
                 }
                 for (int t = t1 - 1; t >= t0; --t) {
                     const size_t row = ((size_t)b * T + t) * H + h;
@@ -304,12 +304,16 @@ int rodimus_oracle_scan_bwd(const float *q, const float *k, const float *v,
                     for (int r = 0; r < n; ++r)
                         for (int j = 0; j < m; ++j) G[(size_t)r * m + j] += (double)qt[r] * dot[j];
                     for (int j = 0; j < m; ++j) {
-                        u[j] = (bt ? (double)bt[j] : 1.0) * (double)vt[j];
+                        /* the gate's value; with the flag set the array holds z_beta and the gate is sigmoid(z_beta) */
+                        double gate = 1.0;
+                        if (bt) gate = beta_is_preactivation ? sigmoid_d((double)bt[j]) : (double)bt[j];
+                        u[j] = gate * (double)vt[j];
                         double acc = 0.0;
                         for (int r = 0; r < n; ++r) acc += (double)kt[r] * G[(size_t)r * m + j];
                         du[j] = acc;
-                        if (dv) dv[row * m + j] = (bt ? (double)bt[j] : 1.0) * acc;
-                        if (dbeta && bt) dbeta[row * m + j] = (double)vt[j] * acc;
+                        if (dv) dv[row * m + j] = gate * acc;
+                        /* cotangent of the gate, v .* du; of its pre-activation: times sigmoid'(z) = gate (1 - gate) */
+                        if (dbeta && bt) dbeta[row * m + j] = (double)vt[j] * acc * (beta_is_preactivation ? gate * (1.0 - gate) : 1.0);
                     }
                     for (int r = 0; r < n; ++r) {
                         const double a = exp((double)lt[r]);
@@ -332,6 +336,27 @@ int rodimus_oracle_scan_bwd(const float *q, const float *k, const float *v,
         }
     }
     return failed ? 2 : 0;
+}
+
+int rodimus_oracle_scan_bwd(const float *q, const float *k, const float *v,
+                            const float *log_alpha, const float *beta, const double *S0,
+                            const double *d_o, const double *dS_T,
+                            double *dq, double *dk, double *dv, double *dlog_alpha, double *dbeta, double *dS0,
+                            int B, int T, int H, int dk_, int dv_)
+{
+    return scan_bwd_impl(q, k, v, log_alpha, beta, 0, S0, d_o, dS_T, dq, dk, dv, dlog_alpha, dbeta, dS0, B, T, H, dk_, dv_);
+}
+
+/* The same with the value gate given as its pre-activation (Sec. 3.1.2: beta_hat = sigmoid(z_beta)): `z_beta` in place of
+ * beta, and dz_beta = (v .* du) .* beta_hat (1 - beta_hat) in place of dbeta. */
+int rodimus_oracle_scan_bwd_zbeta(const float *q, const float *k, const float *v,
+                                  const float *log_alpha, const float *z_beta, const double *S0,
+                                  const double *d_o, const double *dS_T,
+                                  double *dq, double *dk, double *dv, double *dlog_alpha, double *dz_beta, double *dS0,
+                                  int B, int T, int H, int dk_, int dv_)
+{
+    if (!z_beta) return 1;
+    return scan_bwd_impl(q, k, v, log_alpha, z_beta, 1, S0, d_o, dS_T, dq, dk, dv, dlog_alpha, dz_beta, dS0, B, T, H, dk_, dv_);
 }
 
 /*

@@ -32,6 +32,8 @@ def _load():
         lib.rodimus_oracle_threads.restype = ctypes.c_int
         lib.rodimus_oracle_scan_bwd.argtypes = [f32p] * 5 + [f64p] * 9 + [ctypes.c_int] * 5
         lib.rodimus_oracle_scan_bwd.restype = ctypes.c_int
+        lib.rodimus_oracle_scan_bwd_zbeta.argtypes = [f32p] * 5 + [f64p] * 9 + [ctypes.c_int] * 5
+        lib.rodimus_oracle_scan_bwd_zbeta.restype = ctypes.c_int
         lib.rodimus_oracle_block_output.argtypes = [f64p, f32p, f32p, f32p, f64p, ctypes.c_long, ctypes.c_int, ctypes.c_int, ctypes.c_int]
         lib.rodimus_oracle_block_output.restype = ctypes.c_int
         lib.rodimus_oracle_scan_gated.argtypes = [f32p] * 6 + [f64p] * 3 + [ctypes.c_int] * 5
@@ -114,9 +116,16 @@ def scan(q, k, v, log_alpha, beta=None, S0=None, want_state=True, z_beta=None):
     return o, S_T
 
 
-def scan_bwd(q, k, v, log_alpha, beta, S0, d_o, dS_T=None):
+def scan_bwd(q, k, v, log_alpha, beta, S0, d_o, dS_T=None, z_beta=None):
     """Backward of ``scan``: cotangents d_o [B,T,H,dv] (and dS_T [B,H,dk,dv] or None) -> dict of float64 gradients
-    dq, dk, dlog_alpha [B,T,H,dk]; dv, dbeta (None without beta) [B,T,H,dv]; dS0 [B,H,dk,dv]."""
+    dq, dk, dlog_alpha [B,T,H,dk]; dv, dbeta (None without beta) [B,T,H,dv]; dS0 [B,H,dk,dv].
+
+    ``z_beta`` (instead of ``beta``): the value gate's pre-activation as in ``scan``; the dict then holds ``dz_beta`` (the
+    cotangent of the pre-activation) instead of ``dbeta``."""
+    if z_beta is not None:
+        if beta is not None:
+            raise ValueError("give the value gate either as beta or as its pre-activation z_beta, not both")
+        return _scan_bwd_zbeta(q, k, v, log_alpha, z_beta, S0, d_o, dS_T)
     lib = _load()
     q, k, v, la, beta = _f32(q), _f32(k), _f32(v), _f32(log_alpha), _f32(beta)
     S0, d_o, dS_T = _f64(S0), _f64(d_o), _f64(dS_T)
@@ -133,6 +142,25 @@ def scan_bwd(q, k, v, log_alpha, beta, S0, d_o, dS_T=None):
                                      _ptr(out["dlog_alpha"], d), _ptr(out["dbeta"], d), _ptr(out["dS0"], d), B, T, H, dk, dv)
     if rc != 0:
         raise RuntimeError(f"rodimus_oracle_scan_bwd failed with code {rc}")
+    return out
+
+
+def _scan_bwd_zbeta(q, k, v, log_alpha, z_beta, S0, d_o, dS_T):
+    lib = _load()
+    q, k, v, la, z_beta = _f32(q), _f32(k), _f32(v), _f32(log_alpha), _f32(z_beta)
+    S0, d_o, dS_T = _f64(S0), _f64(d_o), _f64(dS_T)
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    assert z_beta.shape == (B, T, H, dv) and d_o.shape == (B, T, H, dv) and (dS_T is None or dS_T.shape == (B, H, dk, dv))
+    out = {"dq": np.zeros((B, T, H, dk)), "dk": np.zeros((B, T, H, dk)), "dlog_alpha": np.zeros((B, T, H, dk)),
+           "dv": np.zeros((B, T, H, dv)), "dz_beta": np.zeros((B, T, H, dv)), "dS0": np.zeros((B, H, dk, dv))}
+    d = ctypes.c_double
+    rc = lib.rodimus_oracle_scan_bwd_zbeta(_ptr(q, ctypes.c_float), _ptr(k, ctypes.c_float), _ptr(v, ctypes.c_float),
+                                           _ptr(la, ctypes.c_float), _ptr(z_beta, ctypes.c_float), _ptr(S0, d), _ptr(d_o, d),
+                                           _ptr(dS_T, d), _ptr(out["dq"], d), _ptr(out["dk"], d), _ptr(out["dv"], d),
+                                           _ptr(out["dlog_alpha"], d), _ptr(out["dz_beta"], d), _ptr(out["dS0"], d), B, T, H, dk, dv)
+    if rc != 0:
+        raise RuntimeError(f"rodimus_oracle_scan_bwd_zbeta failed with code {rc}")
     return out
 
 

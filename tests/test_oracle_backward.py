@@ -160,3 +160,42 @@ def test_mutations_of_the_backward_rules_fail_the_finite_difference_pin():
 
     for kind in ("pre_update_output", "own_gate_on_own_write"):
         assert np.abs(wrong_dk(kind) - g["dk"][0, :, 0]).max() > 1e-2
+
+
+def test_value_gate_as_pre_activation():
+    """beta = sigmoid(z_beta) (Sec. 3.1.2): the z_beta form of the backward oracle against central finite differences of the
+    z_beta form of the forward oracle in z_beta, and against the chain rule on the plain form for every other gradient."""
+    B, T, H, dk, dv = 1, 37, 2, 3, 5
+    q, k, v, la, _, S0 = _case(B, T, H, dk, dv)
+    z = (np.round(RNG.standard_normal((B, T, H, dv)) * 2 * 256) / 256).astype(np.float32)
+    q, k, v, la, S0 = [(np.round(x * 256) / 256).astype(np.float32) for x in (q, k, v, la, S0)]
+    Wo = RNG.standard_normal((B, T, H, dv))
+    Ws = RNG.standard_normal((B, H, dk, dv))
+    g = oracle.scan_bwd(q, k, v, la, None, S0, Wo, Ws, z_beta=z)
+    assert "dbeta" not in g
+
+    def loss(zz):
+        o, S_T = oracle.scan(q, k, v, la, None, S0, z_beta=zz)
+        return float((o * Wo).sum() + (S_T * Ws).sum())
+
+    h = 2.0 ** -10
+    flat = z.reshape(-1)
+    for idx in RNG.choice(flat.size, size=16, replace=False):
+        keep = flat[idx]
+        flat[idx] = keep + h
+        up = loss(z)
+        flat[idx] = keep - h
+        down = loss(z)
+        flat[idx] = keep
+        fd = (up - down) / (2 * h)
+        assert abs(g["dz_beta"].reshape(-1)[idx] - fd) <= 1e-5 * max(1.0, abs(fd)), (idx, g["dz_beta"].reshape(-1)[idx], fd)
+    # the other gradients are those of the plain form at beta = sigmoid(z) (the float32 rounding of beta is all that differs)
+    beta = (1.0 / (1.0 + np.exp(-z.astype(np.float64))))
+    plain = oracle.scan_bwd(q, k, v, la, beta.astype(np.float32), S0, Wo, Ws)
+    for name in ("dq", "dk", "dv", "dlog_alpha", "dS0"):
+        assert np.abs(g[name] - plain[name]).max() <= 1e-6 * max(1.0, np.abs(plain[name]).max()), name
+    assert np.abs(g["dz_beta"] - plain["dbeta"] * beta * (1 - beta)).max() <= 1e-6 * np.abs(g["dz_beta"]).max()
+    # a saturated gate passes no gradient to its pre-activation
+    z_sat = z.copy(); z_sat[:, 5] = 60.0; z_sat[:, 6] = -60.0
+    gs = oracle.scan_bwd(q, k, v, la, None, S0, Wo, Ws, z_beta=z_sat)
+    assert np.abs(gs["dz_beta"][:, 5:7]).max() < 1e-20
