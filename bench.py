@@ -306,8 +306,9 @@ def bench_varlen(w, rodimus, wl, dev, steps, warmup, n_seq=64, longest_first=Fal
             "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
 
-def bench_backward(w, rodimus, wl, dev, steps, warmup):
-    """Backward pass of the scan over the layer workload (rodimus_chunk_scan_bwd: dq, dk, dv, dlog_alpha, dbeta, dS0)."""
+def bench_backward(w, rodimus, wl, dev, steps, warmup, zbeta=False):
+    """Backward pass of the scan over the layer workload (rodimus_chunk_scan_bwd: dq, dk, dv, dlog_alpha, dbeta, dS0; with
+    zbeta the form that reads the value gate's bf16 pre-activation and writes its cotangent, rodimus_chunk_scan_bwd_zbeta)."""
     inp = wl.make_scan_inputs(w)
     g = {k: (None if v is None else v.to(dev)) for k, v in inp.items()}
     gen = torch.Generator(device="cpu").manual_seed(17)
@@ -318,7 +319,12 @@ def bench_backward(w, rodimus, wl, dev, steps, warmup):
     out = {}
 
     def step():
-        out.update(rodimus.rodimus_chunk_scan_bwd(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], g["S0"], d_o, dS_T, workspace=ws))
+        if zbeta:
+            out.update(rodimus.rodimus_chunk_scan_bwd_zbeta(g["q"], g["k"], g["v"], g["log_alpha"], g["z_beta"], g["S0"], d_o, dS_T,
+                                                            workspace=ws))
+        else:
+            out.update(rodimus.rodimus_chunk_scan_bwd(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], g["S0"], d_o, dS_T,
+                                                      workspace=ws))
 
     warm_up(step, min(warmup, 20), min_seconds=0.2)
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -332,10 +338,11 @@ def bench_backward(w, rodimus, wl, dev, steps, warmup):
     th = w.token_heads
     # per token-head: forward sweep reads q,k,log_alpha,v,beta,do and writes dq and q.*dq; reverse sweep reads the six
     # inputs again and writes dk, k.*dk, dv, dbeta; the gate kernel reads q.*dq, k.*dk, log_alpha and writes dlog_alpha
-    inputs = 2 * w.dk * 2 + 4 * w.dk + 2 * w.dv + 4 * w.dv + 2 * w.dv
-    algo = th * (2 * inputs + (2 * w.dk + 4 * w.dk) + (2 * w.dk + 4 * w.dk + 2 * w.dv + 4 * w.dv) + (3 * 4 * w.dk + 4 * w.dk))
+    gate = 2 if zbeta else 4                      # bytes per element of the value gate and of its cotangent
+    inputs = 2 * w.dk * 2 + 4 * w.dk + 2 * w.dv + gate * w.dv + 2 * w.dv
+    algo = th * (2 * inputs + (2 * w.dk + 4 * w.dk) + (2 * w.dk + 4 * w.dk + 2 * w.dv + gate * w.dv) + (3 * 4 * w.dk + 4 * w.dk))
     flops = th * 2 * (4 * w.dk * w.dv + 2 * 16 * w.dv + 2 * 16 * w.dk) * 2    # state products + tile-local products, both sweeps
-    return {"entry_point": "rodimus_chunk_scan_bwd", "ms_per_step": ms, "tokens_per_s": w.tokens / (ms * 1e-3),
+    return {"entry_point": "rodimus_chunk_scan_bwd_zbeta" if zbeta else "rodimus_chunk_scan_bwd", "ms_per_step": ms, "tokens_per_s": w.tokens / (ms * 1e-3),
             "algorithmic_bytes": algo, "GB_per_s": algo / (ms * 1e-3) / 1e9, "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "tflops": flops / (ms * 1e-3) / 1e12, "finite": bool(torch.isfinite(out["dlog_alpha"]).all().item())}
 
@@ -441,6 +448,9 @@ def main():
             "GB_per_s": zb["gbs"], "hbm_frac": zb["gbs"] / HBM_PEAK_GBS}
         out["scan_fused_all_gates"] = bench_gated_scan(w, rodimus, wl, dev, args.steps, args.warmup)
         out["scan_backward"] = bench_backward(w, rodimus, wl, dev, args.steps, args.warmup)
+        zb_bwd = bench_backward(w, rodimus, wl, dev, args.steps, args.warmup, zbeta=True)
+        out["scan_backward_fused_value_gate"] = {k: zb_bwd[k] for k in ("entry_point", "ms_per_step", "tokens_per_s", "algorithmic_bytes",
+                                                                       "GB_per_s", "hbm_frac", "finite")}
         # the same layer at a micro-batch of two sequences: too few (batch, head) pairs to fill the chip, the call is cut
         # along the sequence
         import dataclasses

@@ -283,6 +283,25 @@ int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v,
 size_t rodimus_chunk_scan_bwd_workspace_bytes(int B, int T, int H, int dk, int dv, int io_dtype);
 
 /*
+ * The backward pass of rodimus_chunk_scan_fwd_zbeta: the value gate arrives as its pre-activation (paper Sec. 3.1.2,
+ * beta_hat = sigmoid(z_beta)) and its cotangent leaves as that of the pre-activation, so that no fp32 gate tensor is
+ * read or written (18 % fewer bytes than rodimus_chunk_scan_bwd on the layer shapes):
+ *
+ *   z_beta      [B,T,H,dv] io_dtype      in    required
+ *   dz_beta     [B,T,H,dv] io_dtype      out, or NULL if not wanted:  (v .* (k G)) .* beta_hat (1 - beta_hat)
+ *   everything else as in rodimus_chunk_scan_bwd (same workspace size).
+ *
+ * Matrix-core shapes only (io_dtype = BF16, dk = 64, dv = 128 or 256); any other shape returns RODIMUS_ERR_SHAPE (evaluate
+ * the gate with rodimus_ddts_gates and call rodimus_chunk_scan_bwd there).
+ */
+int rodimus_chunk_scan_bwd_zbeta(const void *q, const void *k, const void *v,
+                                 const float *log_alpha, const void *z_beta, const float *S0,
+                                 const void *d_o, const float *dS_T,
+                                 void *dq, void *dk, void *dv_out, float *dlog_alpha, void *dz_beta, float *dS0,
+                                 int B, int T, int H, int dk_width, int dv, int io_dtype,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Backward pass over a packed batch of sequences of different lengths (training on packed sequences; the backward of
  * rodimus_chunk_scan_varlen_fwd with the value gate given as values): exactly rodimus_chunk_scan_bwd applied to every
  * sequence, with the layouts of rodimus_chunk_scan_varlen_fwd:

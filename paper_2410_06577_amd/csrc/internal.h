@@ -197,20 +197,27 @@ struct GateArgs {
     hipStream_t stream;
 };
 
-// Backward of the dense scan.  d_o, dq, dk, dv in the I/O dtype; dlog_alpha, dbeta, dS0, dS_T fp32.
+// Backward of the dense scan.  d_o, dq, dk, dv in the I/O dtype; dlog_alpha, dbeta, dS0, dS_T fp32.  With beta_preact
+// `beta` holds the pre-activations of the value gate in the I/O dtype and `dbeta` receives their cotangent in that dtype
+// (matrix-core kernels only).
 struct ScanBwdArgs {
     const void *q, *k, *v;
-    const float *log_alpha, *beta, *S0;
+    const float *log_alpha;
+    const void *beta;
+    const float *S0;
     const void *d_o;
     const float *dS_T;
     void *dq, *dk, *dv;
-    float *dlog_alpha, *dbeta, *dS0;
+    float *dlog_alpha;
+    void *dbeta;
+    float *dS0;
     int B, T, H, dk_width, dv_width;      // with cu_seqlens: B sequences, T = total tokens of the packed batch
     int io_dtype;
     void *workspace;
     size_t workspace_bytes;
     hipStream_t stream;
     const int *cu_seqlens = nullptr;      // device, B + 1 entries, or NULL for the dense [B, T, H, .] layout
+    bool beta_preact = false;
     size_t token_rows() const { return cu_seqlens != nullptr ? (size_t)T : (size_t)B * T; }
 };
 
@@ -283,8 +290,9 @@ hipError_t launch_scan_mfma(const ScanArgs &a);
 bool scan_mfma_supports(int dk, int dv, int chunk, int io_dtype);
 size_t scan_mfma_workspace_bytes(int B, int T, int H, int dv);
 // State entering each of nseg sequence segments (seg_tokens a multiple of 64) of a dense bf16 batch with dk = 64:
-// slots [nseg][B*H][64][dv] and the segment decays gamma [nseg-1][B*H][64], fp32 (used by the backward pass)
-hipError_t launch_scan_segment_states(const void *k, const void *v, const float *log_alpha, const float *beta, const float *S0,
+// slots [nseg][B*H][64][dv] and the segment decays gamma [nseg-1][B*H][64], fp32 (used by the backward pass); beta: fp32
+// gate values or, with beta_preact, bf16 pre-activations (then not NULL)
+hipError_t launch_scan_segment_states(const void *k, const void *v, const float *log_alpha, const void *beta, bool beta_preact, const float *S0,
                                       int B, int T, int H, int dv, int nseg, int seg_tokens, float *slots, float *gamma,
                                       hipStream_t stream);
 

@@ -275,30 +275,34 @@ size_t bwd_workspace(size_t token_rows, int B, int T, int H, int dk, int dv, int
 }
 
 // Dense layout: B sequences of T tokens.  Packed (`packed`): B sequences, T tokens in total, lengths in cu_seqlens (device).
-int bwd_entry(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta, const float *S0,
-              const void *d_o, const float *dS_T, void *dq, void *dk, void *dv_out, float *dlog_alpha, float *dbeta, float *dS0,
+// beta_preact: `beta` holds the pre-activations of the value gate in the I/O dtype (required then) and `dbeta` receives their
+// cotangent in the I/O dtype; matrix-core shapes only.
+int bwd_entry(const void *q, const void *k, const void *v, const float *log_alpha, const void *beta, const float *S0,
+              const void *d_o, const float *dS_T, void *dq, void *dk, void *dv_out, float *dlog_alpha, void *dbeta, float *dS0,
               int B, int T, int H, int dk_width, int dv, int io_dtype, void *workspace, size_t workspace_bytes, void *stream,
-              bool packed, const int *cu_seqlens)
+              bool packed, const int *cu_seqlens, bool beta_preact = false)
 {
     if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
     if (B < 0 || T < 0 || H < 0 || (long long)B * H > kMaxGridX) return RODIMUS_ERR_SHAPE;
     if ((long long)T * H > kMaxGridX) return RODIMUS_ERR_SHAPE;          // the kernels index a sequence's rows in 32 bits
     const bool mfma = scan_bwd_supports(dk_width, dv, io_dtype);
-    if (!mfma && !scan_bwd_generic_supports(dk_width, dv)) return RODIMUS_ERR_SHAPE;
+    if (!mfma && (beta_preact || !scan_bwd_generic_supports(dk_width, dv))) return RODIMUS_ERR_SHAPE;
     if (packed && B > 0 && cu_seqlens == nullptr) return RODIMUS_ERR_NULL;
     if (packed && misaligned(cu_seqlens)) return RODIMUS_ERR_ALIGN;
     const size_t token_rows = packed ? (size_t)T : (size_t)B * T;
     const size_t tokens = token_rows * H, states = (size_t)B * H;
     if (tokens > 0 && (!q || !k || !v || !log_alpha || !d_o || !dq || !dk || !dv_out || !dlog_alpha)) return RODIMUS_ERR_NULL;
+    if (tokens > 0 && beta_preact && !beta) return RODIMUS_ERR_NULL;
     const size_t eb = elem_bytes(io_dtype);
+    const size_t gate_bytes = beta_preact ? eb : 4;                      // bytes per element of beta and of dbeta
     const void *ins[9] = {q, k, v, log_alpha, beta, S0, d_o, dS_T, packed ? cu_seqlens : nullptr};
     const size_t in_bytes[9] = {tokens * dk_width * eb, tokens * dk_width * eb, tokens * dv * eb, tokens * dk_width * 4,
-                                tokens * dv * 4, states * dk_width * dv * 4, tokens * dv * eb, states * dk_width * dv * 4,
+                                tokens * dv * gate_bytes, states * dk_width * dv * 4, tokens * dv * eb, states * dk_width * dv * 4,
                                 packed ? ((size_t)B + 1) * sizeof(int) : 0};
     void *outs[7] = {dq, dk, dv_out, dlog_alpha, dbeta, dS0, workspace};
     const size_t need = bwd_workspace(token_rows, B, T, H, dk_width, dv, io_dtype, packed);
     const size_t out_bytes[7] = {tokens * dk_width * eb, tokens * dk_width * eb, tokens * dv * eb, tokens * dk_width * 4,
-                                 tokens * dv * 4, states * dk_width * dv * 4, need};
+                                 tokens * dv * gate_bytes, states * dk_width * dv * 4, need};
     for (int i = 0; i < 9; ++i)
         if (misaligned(ins[i])) return RODIMUS_ERR_ALIGN;
     for (int o = 0; o < 7; ++o)
@@ -314,6 +318,7 @@ int bwd_entry(const void *q, const void *k, const void *v, const float *log_alph
     ScanBwdArgs a{q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, dk, dv_out, dlog_alpha, dbeta, dS0, B, T, H, dk_width, dv,
                   io_dtype, workspace, workspace_bytes, static_cast<hipStream_t>(stream)};
     if (packed) a.cu_seqlens = cu_seqlens;
+    a.beta_preact = beta_preact;
     return (mfma ? launch_scan_bwd(a) : launch_scan_bwd_generic(a)) == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
 }
 
@@ -340,6 +345,15 @@ int rodimus_chunk_scan_bwd(const void *q, const void *k, const void *v, const fl
 {
     return bwd_entry(q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, dk, dv_out, dlog_alpha, dbeta, dS0, B, T, H, dk_width, dv,
                      io_dtype, workspace, workspace_bytes, stream, false, nullptr);
+}
+
+int rodimus_chunk_scan_bwd_zbeta(const void *q, const void *k, const void *v, const float *log_alpha, const void *z_beta,
+                                 const float *S0, const void *d_o, const float *dS_T, void *dq, void *dk, void *dv_out,
+                                 float *dlog_alpha, void *dz_beta, float *dS0, int B, int T, int H, int dk_width, int dv,
+                                 int io_dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return bwd_entry(q, k, v, log_alpha, z_beta, S0, d_o, dS_T, dq, dk, dv_out, dlog_alpha, dz_beta, dS0, B, T, H, dk_width, dv,
+                     io_dtype, workspace, workspace_bytes, stream, false, nullptr, true);
 }
 
 int rodimus_chunk_scan_varlen_bwd(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta,

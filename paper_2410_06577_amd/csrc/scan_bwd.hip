@@ -103,22 +103,59 @@ template <int DV> struct TileLoads {
 // element offset t * H * width.  t * H fits 32 bits; the byte offset is formed in 64 bits.
 struct BwdGeometry {
     const bf16_t *q, *k, *v, *d_o;
-    const float *la, *beta;
+    const float *la;
+    const void *beta;            // fp32 gate values or bf16 pre-activations, not advanced: element offset beta_row0 + ...
+    size_t beta_row0;
     int T, H;
     __device__ BwdGeometry(const bf16_t *q_, const bf16_t *k_, const bf16_t *v_, const bf16_t *do_, const float *la_,
-                           const float *beta_, size_t first_token, int h, int T_, int H_, int dv)
+                           const void *beta_, size_t first_token, int h, int T_, int H_, int dv)
         : T(T_), H(H_)
     {
         const size_t row0 = first_token * H_ + h;
         q = q_ + row0 * kK; k = k_ + row0 * kK; la = la_ + row0 * kK;
         v = v_ + row0 * dv; d_o = do_ + row0 * dv;
-        beta = beta_ != nullptr ? beta_ + row0 * dv : nullptr;
+        beta = beta_;
+        beta_row0 = row0 * dv;
     }
     // token index (clamped to the sequence) times H
     __device__ __forceinline__ unsigned row(int t) const { return (unsigned)min(t, T - 1) * (unsigned)H; }
 };
 
-template <int DV>
+__device__ __forceinline__ void unpack8(const uint4 &w, float (&x)[8])
+{
+    x[0] = bf16_lo(w.x); x[1] = bf16_hi(w.x); x[2] = bf16_lo(w.y); x[3] = bf16_hi(w.y);
+    x[4] = bf16_lo(w.z); x[5] = bf16_hi(w.z); x[6] = bf16_lo(w.w); x[7] = bf16_hi(w.w);
+}
+
+// The value gate of eight columns as it is loaded: fp32 values (two 16-byte pieces) or, with kZBeta, the bf16
+// pre-activations of the gate (one 16-byte piece, raw[1] unused), and its eight values from that (paper Sec. 3.1.2:
+// beta_hat = sigmoid(z_beta)).
+template <bool kZBeta>
+__device__ __forceinline__ void load_gate8(const BwdGeometry &g, size_t off, floatx4_t (&raw)[2])
+{
+    if (kZBeta) {
+        raw[0] = *reinterpret_cast<const floatx4_t *>(static_cast<const bf16_t *>(g.beta) + g.beta_row0 + off);
+    } else {
+        const float *p = static_cast<const float *>(g.beta) + g.beta_row0 + off;
+        raw[0] = *reinterpret_cast<const floatx4_t *>(p);
+        raw[1] = *reinterpret_cast<const floatx4_t *>(p + 4);
+    }
+}
+template <bool kZBeta>
+__device__ __forceinline__ void gate_values8(const floatx4_t (&raw)[2], float (&gate)[8])
+{
+    if (kZBeta) {
+        float z[8];
+        unpack8(__builtin_bit_cast(uint4, raw[0]), z);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) gate[e] = sigmoid_short(z[e]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { gate[e] = raw[0][e]; gate[4 + e] = raw[1][e]; }
+    }
+}
+
+template <int DV, bool kZBeta>
 __device__ __forceinline__ void tile_prefetch(const BwdGeometry &g, int t0, int tid, bool has_beta, TileLoads<DV> &p)
 {
     using L = BwdLayout<DV>;
@@ -137,22 +174,13 @@ __device__ __forceinline__ void tile_prefetch(const BwdGeometry &g, int t0, int 
         const size_t off = (size_t)g.row(t0 + tok) * DV + 8 * piece;
         p.v[u] = *reinterpret_cast<const uint4 *>(g.v + off);
         p.d_o[u] = *reinterpret_cast<const uint4 *>(g.d_o + off);
-        if (has_beta) {
-            p.beta[u][0] = *reinterpret_cast<const floatx4_t *>(g.beta + off);
-            p.beta[u][1] = *reinterpret_cast<const floatx4_t *>(g.beta + off + 4);
-        }
+        if (has_beta) load_gate8<kZBeta>(g, off, p.beta[u]);
     }
-}
-
-__device__ __forceinline__ void unpack8(const uint4 &w, float (&x)[8])
-{
-    x[0] = bf16_lo(w.x); x[1] = bf16_hi(w.x); x[2] = bf16_lo(w.y); x[3] = bf16_hi(w.y);
-    x[4] = bf16_lo(w.z); x[5] = bf16_hi(w.z); x[6] = bf16_lo(w.w); x[7] = bf16_hi(w.w);
 }
 
 // Tile inputs from registers into LDS: q, k, log_alpha (clamped) as fp32 [16][64]; u = beta .* v and do as bf16 rows
 // with permuted columns.  Rows at or beyond T become q = k = u = do = 0, log_alpha = 0.
-template <int DV>
+template <int DV, bool kZBeta>
 __device__ __forceinline__ void tile_stage(const TileLoads<DV> &p, int t0, int T, int tid, bool has_beta, float *qs, float *ks,
                                            float *ls, unsigned char *us, unsigned char *ds)
 {
@@ -181,8 +209,10 @@ __device__ __forceinline__ void tile_stage(const TileLoads<DV> &p, int t0, int T
         unpack8(p.v[u], x);
         unpack8(p.d_o[u], d);
         if (has_beta) {
+            float gate[8];
+            gate_values8<kZBeta>(p.beta[u], gate);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { x[e] *= p.beta[u][0][e]; x[4 + e] *= p.beta[u][1][e]; }
+            for (int e = 0; e < 8; ++e) x[e] *= gate[e];
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) { x[e] = valid ? x[e] : 0.f; d[e] = valid ? d[e] : 0.f; }
@@ -207,7 +237,7 @@ template <int DV> struct HelperLoads {
     floatx4_t beta[2][2];
 };
 
-template <int DV>
+template <int DV, bool kZBeta>
 __device__ __forceinline__ void helper_prefetch(const BwdGeometry &g, int t0, int hid, bool has_beta, HelperLoads<DV> &p)
 {
     using L = BwdLayout<DV>;
@@ -224,15 +254,12 @@ __device__ __forceinline__ void helper_prefetch(const BwdGeometry &g, int t0, in
         const size_t off = (size_t)g.row(t0 + tok) * DV + 8 * piece;
         p.v[s] = *reinterpret_cast<const uint4 *>(g.v + off);
         p.d_o[s] = *reinterpret_cast<const uint4 *>(g.d_o + off);
-        if (has_beta) {
-            p.beta[s][0] = *reinterpret_cast<const floatx4_t *>(g.beta + off);
-            p.beta[s][1] = *reinterpret_cast<const floatx4_t *>(g.beta + off + 4);
-        }
+        if (has_beta) load_gate8<kZBeta>(g, off, p.beta[s]);
     }
 }
 
 // The same LDS image as tile_stage leaves
-template <int DV>
+template <int DV, bool kZBeta>
 __device__ __forceinline__ void helper_stage(const HelperLoads<DV> &p, int t0, int T, int hid, bool has_beta, float *qs, float *ks,
                                              float *ls, unsigned char *us, unsigned char *ds)
 {
@@ -264,8 +291,10 @@ __device__ __forceinline__ void helper_stage(const HelperLoads<DV> &p, int t0, i
         unpack8(p.v[s], x);
         unpack8(p.d_o[s], d);
         if (has_beta) {
+            float gate[8];
+            gate_values8<kZBeta>(p.beta[s], gate);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { x[e] *= p.beta[s][0][e]; x[4 + e] *= p.beta[s][1][e]; }
+            for (int e = 0; e < 8; ++e) x[e] *= gate[e];
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) { x[e] = valid ? x[e] : 0.f; d[e] = valid ? d[e] : 0.f; }
@@ -286,10 +315,10 @@ __device__ __forceinline__ void helper_stage(const HelperLoads<DV> &p, int t0, i
 // One workgroup per (batch, head); wavefront w owns key channels 16w .. 16w+15: its slab of the state is kept
 // transposed in MFMA accumulators (lane = channel, registers = value columns), so that do_t S^T contracts over the
 // columns without any exchange between wavefronts.
-template <int DV>
+template <int DV, bool kZBeta>
 __device__ __forceinline__ void sweep_dq(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
-    const float *__restrict__ log_alpha, const float *__restrict__ beta, const float *__restrict__ S0,
+    const float *__restrict__ log_alpha, const void *__restrict__ beta, const float *__restrict__ S0,
     const bf16_t *__restrict__ d_o, const float *__restrict__ dS_T, bf16_t *__restrict__ dq,
     float *__restrict__ qdq, float *__restrict__ gate_const, float *__restrict__ qtot, int T, int H,
     const int *__restrict__ cu_seqlens, const BwdSegments &segs)
@@ -355,13 +384,13 @@ __device__ __forceinline__ void sweep_dq(
     if (kSplitRoles && wave >= 4) {
         const int stid = tid - 256;
         TileLoads<DV> pf;
-        if (ntiles > 0) tile_prefetch<DV>(g, 0, stid, has_beta, pf);
+        if (ntiles > 0) tile_prefetch<DV, kZBeta>(g, 0, stid, has_beta, pf);
         for (int it = 0; it < ntiles; ++it) {
             const int t0 = it * kTile;
             __syncthreads();                               // the previous tile is computed: its results are staged, its inputs free
             if (it > 0) store_tile(t0 - kTile, stid);
-            tile_stage<DV>(pf, t0, T, stid, has_beta, qs, ks, ls, us, ds);
-            tile_prefetch<DV>(g, t0 + kTile, stid, has_beta, pf);   // clamped addresses; masked when staged
+            tile_stage<DV, kZBeta>(pf, t0, T, stid, has_beta, qs, ks, ls, us, ds);
+            tile_prefetch<DV, kZBeta>(g, t0 + kTile, stid, has_beta, pf);   // clamped addresses; masked when staged
             __syncthreads();
         }
         __syncthreads();
@@ -370,15 +399,15 @@ __device__ __forceinline__ void sweep_dq(
     }
     TileLoads<DV> pf;
     const bool stages = !kSplitRoles && tid < BwdShape<DV>::kThreads;
-    if (ntiles > 0 && stages) tile_prefetch<DV>(g, 0, tid, has_beta, pf);
+    if (ntiles > 0 && stages) tile_prefetch<DV, kZBeta>(g, 0, tid, has_beta, pf);
 
     for (int it = 0; it < ntiles; ++it) {
         const int t0 = it * kTile;
         __syncthreads();                                   // the previous tile is computed: its results are staged, its inputs free
         if (stages) {
             if (it > 0) store_tile(t0 - kTile, tid);
-            tile_stage<DV>(pf, t0, T, tid, has_beta, qs, ks, ls, us, ds);
-            tile_prefetch<DV>(g, t0 + kTile, tid, has_beta, pf);    // clamped addresses; masked when staged
+            tile_stage<DV, kZBeta>(pf, t0, T, tid, has_beta, qs, ks, ls, us, ds);
+            tile_prefetch<DV, kZBeta>(g, t0 + kTile, tid, has_beta, pf);    // clamped addresses; masked when staged
         }
         __syncthreads();
         if (!computes) continue;          // wavefront-uniform; the two barriers above are reached by every wavefront
@@ -572,12 +601,12 @@ struct TileBuffers {
     unsigned char *us, *ds;
 };
 
-template <int DV>
+template <int DV, bool kZBeta>
 __device__ __forceinline__ void sweep_dkv(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
-    const float *__restrict__ log_alpha, const float *__restrict__ beta, const bf16_t *__restrict__ d_o,
+    const float *__restrict__ log_alpha, const void *__restrict__ beta, const bf16_t *__restrict__ d_o,
     const float *__restrict__ dS_T, bf16_t *__restrict__ dk, bf16_t *__restrict__ dv, float *__restrict__ kdk,
-    float *__restrict__ dbeta, float *__restrict__ dS0, float *__restrict__ ktot, int T, int H,
+    void *__restrict__ dbeta, float *__restrict__ dS0, float *__restrict__ ktot, int T, int H,
     const int *__restrict__ cu_seqlens, const BwdSegments &segs)
 {
     using L = BwdLayout<DV>;
@@ -696,11 +725,11 @@ __device__ __forceinline__ void sweep_dkv(
         if (ntiles > 0) {
             const int last = ntiles - 1;
             const TileBuffers in = tile_buffers(last & 1);
-            helper_prefetch<DV>(g, last * kTile, hid, has_beta, pf);
-            helper_stage<DV>(pf, last * kTile, T, hid, has_beta, in.qs, in.ks, in.ls, in.us, in.ds);
+            helper_prefetch<DV, kZBeta>(g, last * kTile, hid, has_beta, pf);
+            helper_stage<DV, kZBeta>(pf, last * kTile, T, hid, has_beta, in.qs, in.ks, in.ls, in.us, in.ds);
 #pragma unroll
             for (int s = 0; s < 2; ++s) { v_cur[s] = pf.v[s]; beta_cur[s][0] = pf.beta[s][0]; beta_cur[s][1] = pf.beta[s][1]; }
-            helper_prefetch<DV>(g, max(last - 1, 0) * kTile, hid, has_beta, pf);
+            helper_prefetch<DV, kZBeta>(g, max(last - 1, 0) * kTile, hid, has_beta, pf);
             __syncthreads();
             __syncthreads();
         }
@@ -709,10 +738,10 @@ __device__ __forceinline__ void sweep_dkv(
             const TileBuffers nxt = tile_buffers(par ^ 1);
             // phase X: tile it-1 (at it = 0: a harmless repeat of tile 0) into the other buffer, tile it-2 requested
             const bool pairwise = flag_s[par] != 0;
-            helper_stage<DV>(pf, t0 - kTile, T, hid, has_beta, nxt.qs, nxt.ks, nxt.ls, nxt.us, nxt.ds);
+            helper_stage<DV, kZBeta>(pf, t0 - kTile, T, hid, has_beta, nxt.qs, nxt.ks, nxt.ls, nxt.us, nxt.ds);
 #pragma unroll
             for (int s = 0; s < 2; ++s) { v_nxt[s] = pf.v[s]; beta_nxt[s][0] = pf.beta[s][0]; beta_nxt[s][1] = pf.beta[s][1]; }
-            helper_prefetch<DV>(g, max(t0 - 2 * kTile, 0), hid, has_beta, pf);
+            helper_prefetch<DV, kZBeta>(g, max(t0 - 2 * kTile, 0), hid, has_beta, pf);
             if (pairwise) __syncthreads();                 // the pair-by-pair route of the other wavefronts has a barrier of its own
             __syncthreads();
             // phase Y
@@ -726,14 +755,24 @@ __device__ __forceinline__ void sweep_dkv(
                     const floatx4_t d1 = *reinterpret_cast<const floatx4_t *>(&du_s[tok * kDuRow + 8 * piece + 4]);
                     float x[8];
                     unpack8(v_cur[s], x);
-                    floatx4_t b0 = {1.f, 1.f, 1.f, 1.f}, b1 = b0;
-                    if (has_beta) { b0 = beta_cur[s][0]; b1 = beta_cur[s][1]; }
-                    const uint4 wv = {pack_bf16x2(b0[0] * d0[0], b0[1] * d0[1]), pack_bf16x2(b0[2] * d0[2], b0[3] * d0[3]),
-                                      pack_bf16x2(b1[0] * d1[0], b1[1] * d1[1]), pack_bf16x2(b1[2] * d1[2], b1[3] * d1[3])};
+                    const float du8[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
+                    float gate[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
+                    if (has_beta) gate_values8<kZBeta>(beta_cur[s], gate);
+                    const uint4 wv = {pack_bf16x2(gate[0] * du8[0], gate[1] * du8[1]), pack_bf16x2(gate[2] * du8[2], gate[3] * du8[3]),
+                                      pack_bf16x2(gate[4] * du8[4], gate[5] * du8[5]), pack_bf16x2(gate[6] * du8[6], gate[7] * du8[7])};
                     *reinterpret_cast<uint4 *>(dv + off) = wv;
                     if (dbeta != nullptr) {
-                        *reinterpret_cast<floatx4_t *>(dbeta + off) = floatx4_t{x[0] * d0[0], x[1] * d0[1], x[2] * d0[2], x[3] * d0[3]};
-                        *reinterpret_cast<floatx4_t *>(dbeta + off + 4) = floatx4_t{x[4] * d1[0], x[5] * d1[1], x[6] * d1[2], x[7] * d1[3]};
+                        float db[8];                       // cotangent of the gate; of its pre-activation: times sigmoid' = gate (1 - gate)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) db[e] = x[e] * du8[e] * (kZBeta ? gate[e] * (1.f - gate[e]) : 1.f);
+                        if (kZBeta) {
+                            const uint4 wz = {pack_bf16x2(db[0], db[1]), pack_bf16x2(db[2], db[3]), pack_bf16x2(db[4], db[5]), pack_bf16x2(db[6], db[7])};
+                            *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(dbeta) + off) = wz;
+                        } else {
+                            float *dst = static_cast<float *>(dbeta) + off;
+                            *reinterpret_cast<floatx4_t *>(dst) = floatx4_t{db[0], db[1], db[2], db[3]};
+                            *reinterpret_cast<floatx4_t *>(dst + 4) = floatx4_t{db[4], db[5], db[6], db[7]};
+                        }
                     }
                 }
                 v_cur[s] = v_nxt[s]; beta_cur[s][0] = beta_nxt[s][0]; beta_cur[s][1] = beta_nxt[s][1];
@@ -1011,19 +1050,20 @@ namespace {
 // units.  The reverse sweeps take almost twice as long and come first in dispatch order, so that when there are more
 // workgroups than compute units the short ones fill the gaps at the end (the other order measured 1058 us against the
 // 988 us of an uncut call on the layer workload cut in two).
-template <int DV>
+// kZBeta: `beta` holds the bf16 pre-activations of the value gate and `dbeta` receives the cotangent of those, in bf16.
+template <int DV, bool kZBeta>
 __global__ __launch_bounds__(BwdShape<DV>::kSweepThreads) void scan_bwd_sweeps_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
-    const float *__restrict__ log_alpha, const float *__restrict__ beta, const float *__restrict__ S0,
+    const float *__restrict__ log_alpha, const void *__restrict__ beta, const float *__restrict__ S0,
     const bf16_t *__restrict__ d_o, const float *__restrict__ dS_T, bf16_t *__restrict__ dq, bf16_t *__restrict__ dk,
-    bf16_t *__restrict__ dv, float *__restrict__ dbeta, float *__restrict__ dS0, float *__restrict__ qdq,
+    bf16_t *__restrict__ dv, void *__restrict__ dbeta, float *__restrict__ dS0, float *__restrict__ qdq,
     float *__restrict__ kdk, float *__restrict__ gate_const, float *__restrict__ qtot, float *__restrict__ ktot, int T, int H,
     const int *__restrict__ cu_seqlens, BwdSegments segs)
 {
     if (blockIdx.z == 1)
-        sweep_dq<DV>(q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, qdq, gate_const, qtot, T, H, cu_seqlens, segs);
+        sweep_dq<DV, kZBeta>(q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, qdq, gate_const, qtot, T, H, cu_seqlens, segs);
     else
-        sweep_dkv<DV>(q, k, v, log_alpha, beta, d_o, dS_T, dk, dv, kdk, dbeta, dS0, ktot, T, H, cu_seqlens, segs);
+        sweep_dkv<DV, kZBeta>(q, k, v, log_alpha, beta, d_o, dS_T, dk, dv, kdk, dbeta, dS0, ktot, T, H, cu_seqlens, segs);
 }
 
 // The G recurrence alone over one segment (blockIdx.y + 1; the first segment's result would be dS0 and is left to the
@@ -1214,7 +1254,7 @@ __global__ __launch_bounds__(1024) void scan_bwd_gate_kernel(const float *__rest
     }
 }
 
-template <int DV>
+template <int DV, bool kZBeta>
 hipError_t launch_scan_bwd_typed(const ScanBwdArgs &a)
 {
     const unsigned bh = (unsigned)(a.B * a.H);
@@ -1233,7 +1273,7 @@ hipError_t launch_scan_bwd_typed(const ScanBwdArgs &a)
         float *G_slots = S_slots + sp.nseg * slot_elems;
         float *s_decay = G_slots + sp.nseg * slot_elems;                // [nseg-1][B*H][64], forward direction
         float *g_decay = s_decay + (size_t)(sp.nseg - 1) * bh * kK;     // the same for the cotangent chain
-        hipError_t e = launch_scan_segment_states(a.k, a.v, a.log_alpha, a.beta, a.S0, a.B, a.T, a.H, DV, sp.nseg,
+        hipError_t e = launch_scan_segment_states(a.k, a.v, a.log_alpha, a.beta, kZBeta, a.S0, a.B, a.T, a.H, DV, sp.nseg,
                                                   sp.seg_tokens, S_slots, s_decay, a.stream);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(scan_bwd_cotangent_summary_kernel<DV>, dim3(bh, (unsigned)(sp.nseg - 1)), dim3(BwdShape<DV>::kThreads), 0,
@@ -1245,10 +1285,10 @@ hipError_t launch_scan_bwd_typed(const ScanBwdArgs &a)
         segs.S_slots = S_slots;
         segs.G_slots = G_slots;
     }
-    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_bwd_sweeps_kernel<DV>),
+    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_bwd_sweeps_kernel<DV, kZBeta>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, DkvLds<DV>::kBytes);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL(scan_bwd_sweeps_kernel<DV>, dim3(bh, (unsigned)sp.nseg, 2), dim3(BwdShape<DV>::kSweepThreads), DkvLds<DV>::kBytes,
+    hipLaunchKernelGGL((scan_bwd_sweeps_kernel<DV, kZBeta>), dim3(bh, (unsigned)sp.nseg, 2), dim3(BwdShape<DV>::kSweepThreads), DkvLds<DV>::kBytes,
                        a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0,
                        (const bf16_t *)a.d_o, a.dS_T, (bf16_t *)a.dq, (bf16_t *)a.dk, (bf16_t *)a.dv, a.dbeta, a.dS0, qdq, kdk,
                        gate_const, qtot, ktot, a.T, a.H, a.cu_seqlens, segs);
@@ -1264,7 +1304,8 @@ hipError_t launch_scan_bwd_typed(const ScanBwdArgs &a)
 hipError_t launch_scan_bwd(const ScanBwdArgs &a)
 {
     if ((long long)a.B * a.H == 0) return hipSuccess;
-    return a.dv_width == 256 ? launch_scan_bwd_typed<256>(a) : launch_scan_bwd_typed<128>(a);
+    if (a.beta_preact) return a.dv_width == 256 ? launch_scan_bwd_typed<256, true>(a) : launch_scan_bwd_typed<128, true>(a);
+    return a.dv_width == 256 ? launch_scan_bwd_typed<256, false>(a) : launch_scan_bwd_typed<128, false>(a);
 }
 
 }  // namespace rodimus

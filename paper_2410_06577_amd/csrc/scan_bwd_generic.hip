@@ -170,11 +170,11 @@ hipError_t launch_typed(const ScanBwdArgs &a)
     float *gate_const = qdq + a.token_rows() * a.H * dk;
     const GenShape sh{a.T, a.H, dk, dv, a.cu_seqlens};
     hipLaunchKernelGGL(scan_bwd_generic_dq_kernel<IO>, dim3(bh), dim3(kGenThreads), lds, a.stream, (const IO *)a.q,
-                       (const IO *)a.k, (const IO *)a.v, a.log_alpha, a.beta, a.S0, (const IO *)a.d_o, a.dS_T, (IO *)a.dq, qdq,
+                       (const IO *)a.k, (const IO *)a.v, a.log_alpha, static_cast<const float *>(a.beta), a.S0, (const IO *)a.d_o, a.dS_T, (IO *)a.dq, qdq,
                        gate_const, sh);
     hipLaunchKernelGGL(scan_bwd_generic_dkv_kernel<IO>, dim3(bh), dim3(kGenThreads), lds, a.stream, (const IO *)a.q,
-                       (const IO *)a.k, (const IO *)a.v, a.log_alpha, a.beta, (const IO *)a.d_o, a.dS_T, qdq, gate_const,
-                       (IO *)a.dk, (IO *)a.dv, a.dlog_alpha, a.dbeta, a.dS0, sh);
+                       (const IO *)a.k, (const IO *)a.v, a.log_alpha, static_cast<const float *>(a.beta), (const IO *)a.d_o, a.dS_T, qdq, gate_const,
+                       (IO *)a.dk, (IO *)a.dv, a.dlog_alpha, static_cast<float *>(a.dbeta), a.dS0, sh);
     return hipGetLastError();
 }
 

@@ -984,24 +984,38 @@ hipError_t launch_scan_mfma_typed(const ScanArgs &a)
 
 // The state entering every one of `nseg` segments of `seg_tokens` tokens (a multiple of 64) of a dense batch, for the
 // backward pass cut along the sequence: summary pass over the first nseg-1 segments, then the chain over the segments.
-// slots: [nseg][B*H][64][dv] fp32, gamma: [nseg-1][B*H][64] fp32 (the segment decays); beta fp32 or NULL.
-hipError_t launch_scan_segment_states(const void *k, const void *v, const float *log_alpha, const float *beta, const float *S0,
-                                      int B, int T, int H, int dv, int nseg, int seg_tokens, float *slots, float *gamma,
-                                      hipStream_t stream)
+// slots: [nseg][B*H][64][dv] fp32, gamma: [nseg-1][B*H][64] fp32 (the segment decays); beta: fp32 values or NULL, or
+// (beta_preact) bf16 pre-activations.
+namespace {
+
+template <bool kZBeta>
+hipError_t launch_segment_states_typed(const void *k, const void *v, const float *log_alpha, const void *beta, const float *S0,
+                                       int B, int T, int H, int dv, int nseg, int seg_tokens, float *slots, float *gamma,
+                                       hipStream_t stream)
 {
-    if (nseg < 2 || seg_tokens % kChunk != 0 || dv % kColTile != 0) return hipErrorInvalidValue;
     const size_t bh = (size_t)B * H;
     SegmentPlan plan{nseg, seg_tokens, slots, gamma};
-    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel<true, false, false>),
+    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel<true, kZBeta, false>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((scan_mfma_kernel<true, false, false>), dim3((unsigned)bh, (unsigned)(dv / kColTile), (unsigned)(nseg - 1)),
+    hipLaunchKernelGGL((scan_mfma_kernel<true, kZBeta, false>), dim3((unsigned)bh, (unsigned)(dv / kColTile), (unsigned)(nseg - 1)),
                        dim3(kThreads), kLdsBytes, stream, (const bf16_t *)nullptr, (const bf16_t *)k, (const bf16_t *)v,
-                       static_cast<const void *>(log_alpha), (const bf16_t *)nullptr, static_cast<const void *>(beta),
+                       static_cast<const void *>(log_alpha), (const bf16_t *)nullptr, beta,
                        (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, T, H, dv, plan, (const int *)nullptr, 0, 0);
     const size_t quads = bh * kK * dv / 4;
     hipLaunchKernelGGL(segment_state_scan_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, S0, plan, dv, quads);
     return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_scan_segment_states(const void *k, const void *v, const float *log_alpha, const void *beta, bool beta_preact,
+                                      const float *S0, int B, int T, int H, int dv, int nseg, int seg_tokens, float *slots,
+                                      float *gamma, hipStream_t stream)
+{
+    if (nseg < 2 || seg_tokens % kChunk != 0 || dv % kColTile != 0 || (beta_preact && beta == nullptr)) return hipErrorInvalidValue;
+    return beta_preact ? launch_segment_states_typed<true>(k, v, log_alpha, beta, S0, B, T, H, dv, nseg, seg_tokens, slots, gamma, stream)
+                       : launch_segment_states_typed<false>(k, v, log_alpha, beta, S0, B, T, H, dv, nseg, seg_tokens, slots, gamma, stream);
 }
 
 hipError_t launch_scan_mfma(const ScanArgs &a)

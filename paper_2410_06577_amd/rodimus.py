@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
         L.rodimus_chunk_scan_varlen_fwd.restype = i
         L.rodimus_chunk_scan_bwd.argtypes = [vp] * 14 + [i] * 6 + [vp, sz, vp]
         L.rodimus_chunk_scan_bwd.restype = i
+        L.rodimus_chunk_scan_bwd_zbeta.argtypes = L.rodimus_chunk_scan_bwd.argtypes
+        L.rodimus_chunk_scan_bwd_zbeta.restype = i
         L.rodimus_chunk_scan_bwd_workspace_bytes.argtypes = [i] * 6
         L.rodimus_chunk_scan_bwd_workspace_bytes.restype = sz
         L.rodimus_chunk_scan_varlen_bwd.argtypes = [vp] * 15 + [i] * 6 + [vp, sz, vp]
@@ -426,6 +428,42 @@ def rodimus_chunk_scan_bwd(q, k, v, log_alpha, beta, S0, d_o, dS_T=None, *, want
                                             _ptr(dS_T), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]),
                                             _ptr(out["dlog_alpha"]), _ptr(out["dbeta"]), _ptr(out["dS0"]), B, T, H, dk, dv,
                                             _DTYPES[io], _ptr(workspace), ws_bytes, _stream(dev)))
+    return out
+
+
+def rodimus_chunk_scan_bwd_zbeta(q, k, v, log_alpha, z_beta, S0, d_o, dS_T=None, *, want_dz_beta=True, want_dS0=True,
+                                 workspace=None):
+    """Backward of ``rodimus_chunk_scan_fwd_zbeta``: ``z_beta`` [B,T,H,dv] (dtype of v) is the value gate's pre-activation.
+    Returns the dict of ``rodimus_chunk_scan_bwd`` with ``dz_beta`` (dtype of v) in place of ``dbeta``."""
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_chunk_scan_bwd_zbeta needs device tensors (no CPU path exists)")
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    dev, io = q.device, q.dtype
+    _require(k, "k", (B, T, H, dk), io, dev)
+    _require(v, "v", (B, T, H, dv), io, dev)
+    _require(log_alpha, "log_alpha", (B, T, H, dk), torch.float32, dev)
+    if z_beta is None:
+        raise ValueError("z_beta is required")
+    _require(z_beta, "z_beta", (B, T, H, dv), io, dev)
+    _require(S0, "S0", (B, H, dk, dv), torch.float32, dev)
+    _require(d_o, "d_o", (B, T, H, dv), io, dev)
+    _require(dS_T, "dS_T", (B, H, dk, dv), torch.float32, dev)
+    out = {"dq": torch.empty_like(q), "dk": torch.empty_like(k), "dv": torch.empty_like(v),
+           "dlog_alpha": torch.empty_like(log_alpha),
+           "dz_beta": torch.empty_like(z_beta) if want_dz_beta else None,
+           "dS0": torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev) if want_dS0 else None}
+    need = int(lib().rodimus_chunk_scan_bwd_workspace_bytes(B, T, H, dk, dv, _DTYPES[io]))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_chunk_scan_bwd_zbeta(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(z_beta), _ptr(S0), _ptr(d_o),
+                                                  _ptr(dS_T), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]),
+                                                  _ptr(out["dlog_alpha"]), _ptr(out["dz_beta"]), _ptr(out["dS0"]), B, T, H, dk, dv,
+                                                  _DTYPES[io], _ptr(workspace), ws_bytes, _stream(dev)))
     return out
 
 

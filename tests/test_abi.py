@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported(L):
     assert {"rodimus_chunk_scan_fwd", "rodimus_decode_step", "rodimus_status_string",
             "rodimus_chunk_scan_workspace_bytes", "rodimus_chunk_scan_path", "rodimus_ddts_gates",
             "rodimus_chunk_scan_fwd_zbeta", "rodimus_decode_step_zbeta", "rodimus_chunk_scan_varlen_fwd",
-            "rodimus_chunk_scan_bwd", "rodimus_chunk_scan_bwd_workspace_bytes",
+            "rodimus_chunk_scan_bwd", "rodimus_chunk_scan_bwd_workspace_bytes", "rodimus_chunk_scan_bwd_zbeta",
             "rodimus_chunk_scan_fwd_block", "rodimus_decode_step_block",
             "rodimus_short_conv_fwd", "rodimus_short_conv_step",
             "rodimus_chunk_scan_fwd_gated", "rodimus_decode_step_gated",
@@ -206,6 +206,19 @@ def test_backward_validation(L):
     assert L.rodimus_chunk_scan_bwd_workspace_bytes(2, 100, 3, 129, 8, rodimus.F32) == 0
     assert call(dk=16, dv=32, io=rodimus.F32, ws_bytes=16) == E_WS
     assert call(B=0) == OK
+
+    # the pre-activation form: the gate is required, and only the matrix-core shapes are served
+    def call_z(B=1, T=4, H=1, dk=64, dv=128, io=rodimus.BF16, **over):
+        a = dict(base)
+        a.update(over)
+        f = lambda x: None if x is None else p(x)
+        need = L.rodimus_chunk_scan_bwd_workspace_bytes(B, T, H, dk, dv, io)
+        return L.rodimus_chunk_scan_bwd_zbeta(*[f(a[n]) for n in names[:14]], B, T, H, dk, dv, io, f(a["ws"]), need, None)
+
+    assert call_z(beta=None) == E_NULL
+    assert call_z(dk=16, dv=32, io=rodimus.F32) == E_SHAPE and call_z(dk=64, dv=128, io=rodimus.F32) == E_SHAPE
+    assert call_z(dbeta=base["beta"]) == E_ALIAS and call_z(beta=base["beta"] + 8) == E_ALIGN
+    assert call_z(B=0) == OK
 
 
 def test_gated_calls_validation(L):
