@@ -12,7 +12,8 @@
 //       du_i    = sum_{t>=i} P[t,i] do_t + (k_i .* exp(l_16 - l_i)) G
 //       dk_i    = exp(l_16 - l_i) .* (u_i G^T) + sum_{t>=i} dP[t,i] (q_t .* w[t,i])
 //       G      <- diag(A_16) G + sum_t (q_t .* A_t)^T do_t
-//       dv = beta .* du, dbeta = v .* du, dS0 = G after the first tile
+//       dv = beta .* du, dbeta = v .* du (with the gate given as its pre-activation z, beta = sigmoid(z):
+//       dz = dbeta .* beta (1 - beta)), dS0 = G after the first tile
 //   gates: dlog_alpha_t = sum_{s>=t} (q_s .* dq_s - k_s .* dk_s) + rowsum(S_T .* dS_T): every pair (i < t <= s) that the
 //       gate of step t decays appears once in q_s .* dq_s and not in k .* dk of a step >= t, so the reverse running
 //       sum of the difference is the gate's cotangent; it is formed from the fp32 values before dq, dk are rounded
@@ -32,14 +33,16 @@ namespace {
 
 constexpr int kK = 64;
 constexpr int kTile = 16;
-// One wavefront of the reverse sweep per 32 value columns: 4 wavefronts (dv = 128) or 8 (dv = 256) per workgroup; the
-// forward sweep computes with 4 wavefronts and uses the others only to fetch and stage the tile inputs.
+// One wavefront of the reverse sweep per 32 value columns: 4 wavefronts (dv = 128) or 8 (dv = 256); the forward sweep
+// computes with 4 wavefronts.
 template <int DV> struct BwdShape {
     static constexpr int kWaves = DV / 32;
     static constexpr int kThreads = 64 * kWaves;
     // The sweeps kernel adds half as many helper wavefronts: in the reverse sweep they load and stage the tile inputs and
     // write dv and dbeta, which takes that work and its registers off the wavefronts that carry G (three wavefronts per
-    // SIMD instead of two); in the forward sweep they only take part in the barriers.
+    // SIMD instead of two); in the forward sweep (dv = 256) all wavefronts behind the four computing ones fetch, stage and
+    // store, so that those keep no loads in registers (dv = 128: the computing wavefronts stage themselves and the helpers
+    // only take part in the barriers).
     static constexpr int kHelpers = kWaves / 2;
     static constexpr int kSweepThreads = 64 * (kWaves + kHelpers);
 };
