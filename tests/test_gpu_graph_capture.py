@@ -68,3 +68,41 @@ def test_captured_prefill_scan_replays_like_the_eager_call():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(o, o_eager) and torch.equal(S_T, S_eager), replay
+
+
+def test_captured_backward_pass_replays_like_the_eager_call():
+    """The backward pass of a call that is cut along the sequence (two summary passes, two chains, sweeps, gate kernel) and
+    of the packed forward scan (which ranks the sequence lengths on the device), recorded and replayed."""
+    w = wl.ScanWorkload("g", B=1, T=1000, H=2, dk=64, dv=256, chunk=64, io_dtype="bf16", s0_std=0.1, seed=8)
+    g = to_dev(wl.make_scan_inputs(w))
+    gen = torch.Generator(device="cpu").manual_seed(3)
+    d_o = torch.randn((1, 1000, 2, 256), generator=gen).to(torch.bfloat16).cuda()
+    dS_T = (0.1 * torch.randn((1, 2, 64, 256), generator=gen)).cuda()
+    need = rodimus.lib().rodimus_chunk_scan_bwd_workspace_bytes(1, 1000, 2, 64, 256, rodimus.BF16)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    eager = rodimus.rodimus_chunk_scan_bwd(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], g["S0"], d_o, dS_T, workspace=ws)
+    eager = {k: v.clone() for k, v in eager.items()}
+    lengths = [300, 17, 0, 450, 233]
+    pk = to_dev(wl.make_varlen_inputs(lengths, 2, 64, 256, "bf16", seed=9))
+    o_eager, S_eager = rodimus.rodimus_chunk_scan_varlen_fwd(pk["q"], pk["k"], pk["v"], pk["log_alpha"], pk["cu_seqlens"],
+                                                             beta=pk["beta"], S0=pk["S0"])
+    torch.cuda.synchronize()
+    o = torch.empty_like(o_eager)
+    S_T = torch.empty_like(S_eager)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        out = rodimus.rodimus_chunk_scan_bwd(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], g["S0"], d_o, dS_T, workspace=ws)
+        rodimus.rodimus_chunk_scan_varlen_fwd(pk["q"], pk["k"], pk["v"], pk["log_alpha"], pk["cu_seqlens"], beta=pk["beta"],
+                                              S0=pk["S0"], o=o, S_T=S_T)
+    for replay in range(3):
+        for x in out.values():
+            x.fill_(0)
+        ws.fill_(0)
+        o.fill_(0)
+        S_T.fill_(0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, ref in eager.items():
+            assert torch.equal(out[name], ref), (replay, name)
+        assert torch.equal(o, o_eager) and torch.equal(S_T, S_eager), replay
