@@ -398,73 +398,55 @@ def rodimus_decode_step_block(q, k, v, log_alpha, beta, S, *, z_beta=None, x_pri
     return o
 
 
-def rodimus_chunk_scan_bwd(q, k, v, log_alpha, beta, S0, d_o, dS_T=None, *, want_dbeta=True, want_dS0=True, workspace=None):
-    """Backward of ``rodimus_chunk_scan_fwd``.  Returns a dict with dq, dk [B,T,H,dk] and dv [B,T,H,dv] (dtype of q),
-    dlog_alpha [B,T,H,dk], dbeta [B,T,H,dv] and dS0 [B,H,dk,dv] in fp32 (dbeta / dS0 None when not wanted)."""
+def _scan_bwd(fn_name, gate_key, q, k, v, log_alpha, gate, S0, d_o, dS_T, want_gate, want_dS0, workspace):
+    """Shared by the two dense backward calls: ``gate`` is beta (fp32) or z_beta (dtype of v), ``gate_key`` names its
+    cotangent in the returned dict."""
     if q.dtype not in _DTYPES:
         raise ValueError(f"q: unsupported dtype {q.dtype}")
     if not q.is_cuda:
-        raise ValueError("rodimus_chunk_scan_bwd needs device tensors (no CPU path exists)")
+        raise ValueError(f"{fn_name} needs device tensors (no CPU path exists)")
     B, T, H, dk = q.shape
     dv = v.shape[-1]
     dev, io = q.device, q.dtype
+    preact = gate_key == "dz_beta"
+    gate_dtype = io if preact else torch.float32
     _require(k, "k", (B, T, H, dk), io, dev)
     _require(v, "v", (B, T, H, dv), io, dev)
     _require(log_alpha, "log_alpha", (B, T, H, dk), torch.float32, dev)
-    _require(beta, "beta", (B, T, H, dv), torch.float32, dev)
+    if preact and gate is None:
+        raise ValueError("z_beta is required")
+    _require(gate, "z_beta" if preact else "beta", (B, T, H, dv), gate_dtype, dev)
     _require(S0, "S0", (B, H, dk, dv), torch.float32, dev)
     _require(d_o, "d_o", (B, T, H, dv), io, dev)
     _require(dS_T, "dS_T", (B, H, dk, dv), torch.float32, dev)
     out = {"dq": torch.empty_like(q), "dk": torch.empty_like(k), "dv": torch.empty_like(v),
            "dlog_alpha": torch.empty_like(log_alpha),
-           "dbeta": torch.empty((B, T, H, dv), dtype=torch.float32, device=dev) if want_dbeta else None,
+           gate_key: torch.empty((B, T, H, dv), dtype=gate_dtype, device=dev) if want_gate else None,
            "dS0": torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev) if want_dS0 else None}
     need = int(lib().rodimus_chunk_scan_bwd_workspace_bytes(B, T, H, dk, dv, _DTYPES[io]))
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     with torch.cuda.device(dev):
-        _check(lib().rodimus_chunk_scan_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(S0), _ptr(d_o),
-                                            _ptr(dS_T), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]),
-                                            _ptr(out["dlog_alpha"]), _ptr(out["dbeta"]), _ptr(out["dS0"]), B, T, H, dk, dv,
-                                            _DTYPES[io], _ptr(workspace), ws_bytes, _stream(dev)))
+        _check(getattr(lib(), fn_name)(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(gate), _ptr(S0), _ptr(d_o),
+                                       _ptr(dS_T), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]),
+                                       _ptr(out["dlog_alpha"]), _ptr(out[gate_key]), _ptr(out["dS0"]), B, T, H, dk, dv,
+                                       _DTYPES[io], _ptr(workspace), ws_bytes, _stream(dev)))
     return out
+
+
+def rodimus_chunk_scan_bwd(q, k, v, log_alpha, beta, S0, d_o, dS_T=None, *, want_dbeta=True, want_dS0=True, workspace=None):
+    """Backward of ``rodimus_chunk_scan_fwd``.  Returns a dict with dq, dk [B,T,H,dk] and dv [B,T,H,dv] (dtype of q),
+    dlog_alpha [B,T,H,dk], dbeta [B,T,H,dv] and dS0 [B,H,dk,dv] in fp32 (dbeta / dS0 None when not wanted)."""
+    return _scan_bwd("rodimus_chunk_scan_bwd", "dbeta", q, k, v, log_alpha, beta, S0, d_o, dS_T, want_dbeta, want_dS0, workspace)
 
 
 def rodimus_chunk_scan_bwd_zbeta(q, k, v, log_alpha, z_beta, S0, d_o, dS_T=None, *, want_dz_beta=True, want_dS0=True,
                                  workspace=None):
     """Backward of ``rodimus_chunk_scan_fwd_zbeta``: ``z_beta`` [B,T,H,dv] (dtype of v) is the value gate's pre-activation.
     Returns the dict of ``rodimus_chunk_scan_bwd`` with ``dz_beta`` (dtype of v) in place of ``dbeta``."""
-    if q.dtype not in _DTYPES:
-        raise ValueError(f"q: unsupported dtype {q.dtype}")
-    if not q.is_cuda:
-        raise ValueError("rodimus_chunk_scan_bwd_zbeta needs device tensors (no CPU path exists)")
-    B, T, H, dk = q.shape
-    dv = v.shape[-1]
-    dev, io = q.device, q.dtype
-    _require(k, "k", (B, T, H, dk), io, dev)
-    _require(v, "v", (B, T, H, dv), io, dev)
-    _require(log_alpha, "log_alpha", (B, T, H, dk), torch.float32, dev)
-    if z_beta is None:
-        raise ValueError("z_beta is required")
-    _require(z_beta, "z_beta", (B, T, H, dv), io, dev)
-    _require(S0, "S0", (B, H, dk, dv), torch.float32, dev)
-    _require(d_o, "d_o", (B, T, H, dv), io, dev)
-    _require(dS_T, "dS_T", (B, H, dk, dv), torch.float32, dev)
-    out = {"dq": torch.empty_like(q), "dk": torch.empty_like(k), "dv": torch.empty_like(v),
-           "dlog_alpha": torch.empty_like(log_alpha),
-           "dz_beta": torch.empty_like(z_beta) if want_dz_beta else None,
-           "dS0": torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev) if want_dS0 else None}
-    need = int(lib().rodimus_chunk_scan_bwd_workspace_bytes(B, T, H, dk, dv, _DTYPES[io]))
-    if workspace is None and need > 0:
-        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
-    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    with torch.cuda.device(dev):
-        _check(lib().rodimus_chunk_scan_bwd_zbeta(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(z_beta), _ptr(S0), _ptr(d_o),
-                                                  _ptr(dS_T), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]),
-                                                  _ptr(out["dlog_alpha"]), _ptr(out["dz_beta"]), _ptr(out["dS0"]), B, T, H, dk, dv,
-                                                  _DTYPES[io], _ptr(workspace), ws_bytes, _stream(dev)))
-    return out
+    return _scan_bwd("rodimus_chunk_scan_bwd_zbeta", "dz_beta", q, k, v, log_alpha, z_beta, S0, d_o, dS_T, want_dz_beta, want_dS0,
+                     workspace)
 
 
 def rodimus_chunk_scan_varlen_fwd(q, k, v, log_alpha, cu_seqlens, beta=None, S0=None, *, z_beta=None, chunk=64, o=None,
