@@ -792,7 +792,8 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
         const int slab = wave - 4;
         StateSlab st;
         const size_t state_base = (size_t)bh * kK * dv + g.j0 + 32 * slab;
-        // entering state: zero (summary), the caller's S0 (no split), or this segment's workspace slot
+        // entering state: zero (summary), the caller's S0 (no split), or this segment's workspace slot.  The state is read
+        // once here and written once at the end: streaming accesses (layer workload 225 -> 221 us, gated form 288 -> 277 us)
         const float *S_in = kSummary ? nullptr : (plan.nseg > 1 ? plan.slots + seg * slot_elems : S0);
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
@@ -801,7 +802,7 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
                     st.S[kt][ct][r] = (S_in != nullptr)
-                                          ? S_in[state_base + (size_t)slab_channel(kt, 4 * grp + r) * dv + slab_column(ct, n)]
+                                          ? __builtin_nontemporal_load(S_in + state_base + (size_t)slab_channel(kt, 4 * grp + r) * dv + slab_column(ct, n))
                                           : 0.f;
         refresh_operands(st);
         floatx4_t decay[4];       // summary pass: product of the tile decays for this lane's state rows
@@ -836,7 +837,7 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
                 for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
-                        S_out[state_base + (size_t)slab_channel(kt, 4 * grp + r) * dv + slab_column(ct, n)] = st.S[kt][ct][r];
+                        __builtin_nontemporal_store(st.S[kt][ct][r], S_out + state_base + (size_t)slab_channel(kt, 4 * grp + r) * dv + slab_column(ct, n));
         }
         if (kSummary && col_tile == 0 && slab == 0 && n == 0) {
             float *gam = plan.gamma + ((size_t)seg * BH + bh) * kK;
