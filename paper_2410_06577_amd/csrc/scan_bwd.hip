@@ -748,7 +748,8 @@ __device__ __forceinline__ void sweep_dkv(
             if (pairwise) __syncthreads();                 // the pair-by-pair route of the other wavefronts has a barrier of its own
             __syncthreads();
             // phase Y
-            // dv = beta .* du, dbeta = v .* du: coalesced, by the helper thread that loaded the same pieces of v and beta
+            // dv = beta .* du, dbeta = v .* du: coalesced, by the helper thread that loaded the same pieces of v and beta;
+            // streaming stores (nothing on this GPU reads them again soon: -2 % on the layer workload)
     #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 const int idx = hid + s * kHelp, tok = idx / L::kPieces, piece = idx % L::kPieces;
@@ -763,18 +764,18 @@ __device__ __forceinline__ void sweep_dkv(
                     if (has_beta) gate_values8<kZBeta>(beta_cur[s], gate);
                     const uint4 wv = {pack_bf16x2(gate[0] * du8[0], gate[1] * du8[1]), pack_bf16x2(gate[2] * du8[2], gate[3] * du8[3]),
                                       pack_bf16x2(gate[4] * du8[4], gate[5] * du8[5]), pack_bf16x2(gate[6] * du8[6], gate[7] * du8[7])};
-                    *reinterpret_cast<uint4 *>(dv + off) = wv;
+                    __builtin_nontemporal_store(__builtin_bit_cast(floatx4_t, wv), reinterpret_cast<floatx4_t *>(dv + off));
                     if (dbeta != nullptr) {
                         float db[8];                       // cotangent of the gate; of its pre-activation: times sigmoid' = gate (1 - gate)
 #pragma unroll
                         for (int e = 0; e < 8; ++e) db[e] = x[e] * du8[e] * (kZBeta ? gate[e] * (1.f - gate[e]) : 1.f);
                         if (kZBeta) {
                             const uint4 wz = {pack_bf16x2(db[0], db[1]), pack_bf16x2(db[2], db[3]), pack_bf16x2(db[4], db[5]), pack_bf16x2(db[6], db[7])};
-                            *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(dbeta) + off) = wz;
+                            __builtin_nontemporal_store(__builtin_bit_cast(floatx4_t, wz), reinterpret_cast<floatx4_t *>(static_cast<bf16_t *>(dbeta) + off));
                         } else {
                             float *dst = static_cast<float *>(dbeta) + off;
-                            *reinterpret_cast<floatx4_t *>(dst) = floatx4_t{db[0], db[1], db[2], db[3]};
-                            *reinterpret_cast<floatx4_t *>(dst + 4) = floatx4_t{db[4], db[5], db[6], db[7]};
+                            __builtin_nontemporal_store(floatx4_t{db[0], db[1], db[2], db[3]}, reinterpret_cast<floatx4_t *>(dst));
+                            __builtin_nontemporal_store(floatx4_t{db[4], db[5], db[6], db[7]}, reinterpret_cast<floatx4_t *>(dst + 4));
                         }
                     }
                 }
