@@ -78,6 +78,15 @@ def bench_scan(w, steps, warmup, rodimus, wl, dev, zbeta=False, exact_warmup=Fal
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     launch_ms = start.elapsed_time(stop) / steps      # HIP events on the launch stream around the K back-to-back launches
+    # afterwards (outside the timed region): single launches between their own pairs of events, for the median and the minimum
+    n_single = min(steps, 50)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_single)]
+    for a, b in pairs:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    singles = sorted(a.elapsed_time(b) for a, b in pairs)
 
     th = w.token_heads
     state_bytes = w.B * w.H * w.dk * w.dv * 4
@@ -91,6 +100,7 @@ def bench_scan(w, steps, warmup, rodimus, wl, dev, zbeta=False, exact_warmup=Fal
         "tflops_causal": flops_causal / (launch_ms * 1e-3) / 1e12,
         "tflops_dense_tiles": flops_dense / (launch_ms * 1e-3) / 1e12,
         "path": rodimus.rodimus_chunk_scan_path(w.B, w.T, w.H, w.dk, w.dv, w.chunk, torch.bfloat16),
+        "single_launch_ms": {"median": singles[len(singles) // 2], "min": singles[0], "launches": n_single} if singles else None,
     }
     return res, inp, o, S_T
 
@@ -134,6 +144,23 @@ def bench_decode(w, rodimus, wl, dev, warmup=100):
     finite = bool(torch.isfinite(S).all().item())
     return {"wall_s": wall, "launch_ms": launch_ms, "algo_bytes": algo_bytes,
             "gbs": algo_bytes / (launch_ms * 1e-3) / 1e9, "steps_per_s": w.steps / wall, "finite": finite}
+
+
+def decode_cpu_baseline(w, wl, steps=10):
+    """The step oracle over all sequences of the decode workload for a few chained steps, on the host cores."""
+    import oracle
+    d = wl.make_decode_inputs(w)
+    S = d["S"].double().numpy()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        tok = d["ring"][i % len(d["ring"])]
+        _, S = oracle.step(tok["q"], tok["k"], tok["v"], tok["log_alpha"], tok["beta"], S)
+    dt = (time.perf_counter() - t0) / steps
+    states = w.N * w.H
+    algo_bytes = states * (2 * 4 * w.dk * w.dv + 2 * (2 * w.dk) + 4 * w.dk + 2 * w.dv + 4 * w.dv + 2 * w.dv)
+    return {"value": algo_bytes / dt / 1e9, "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{steps} chained steps over all {w.N} sequences (fp64 state; GB/s counted on the GPU step's algorithmic bytes), "
+                      f"{dt * 1e3:.0f} ms per step"}
 
 
 def bench_decode_small(rodimus, wl, dev, H=16, dk=64, dv=256, chained=64, reps=20):
@@ -359,11 +386,19 @@ def cpu_baseline(w, inp, o_gpu, S_gpu):
         got = got.detach().cpu().double().numpy()
         return float(np.abs(got - ref).max() / np.abs(ref).max())
 
+    # one (batch, head) of the same workload: the oracle parallelises over (batch, head), so this runs on one thread
+    one = {k: (None if v is None else v[:1, :, :1].contiguous()) for k, v in inp.items() if k in ("q", "k", "v", "log_alpha", "beta")}
+    s0 = None if inp["S0"] is None else inp["S0"][:1, :1].contiguous()
+    t1 = time.perf_counter()
+    oracle.scan(one["q"], one["k"], one["v"], one["log_alpha"], one["beta"], s0)
+    dt1 = time.perf_counter() - t1
     return {
         "value": w.tokens / dt, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
         "sample": f"the whole scan workload once (B={w.B}, T={w.T}, H={w.H}, dk={w.dk}, dv={w.dv}), fp64 sequential "
                   f"recurrence, OpenMP over (batch, head), {dt:.2f} s",
         "seconds": dt,
+        "single_thread": {"value": w.T / w.H / dt1, "unit": "tokens/s", "cores": 1,
+                          "sample": f"one (batch, head) of the workload ({w.T} token-heads), {dt1:.2f} s; tokens/s = token-heads/s / H"},
     }, {"o_rel_err": rel(o_gpu, o_ref), "S_T_rel_err": rel(S_gpu, S_ref), "tolerance": 2e-2}
 
 
@@ -412,7 +447,8 @@ def main():
                    "kernel_path": {1: "generic", 2: "mfma"}.get(scan["path"], "none")},
         "roofline": {"bound": "hbm", "achieved": scan["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": scan["gbs"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES["scan_layer_1p6b"],
-                     "kernel": "scan_mfma_kernel", "launch_ms": scan["launch_ms"], "algorithmic_bytes": scan["algo_bytes"]},
+                     "kernel": "scan_mfma_kernel", "launch_ms": scan["launch_ms"], "algorithmic_bytes": scan["algo_bytes"],
+                     "single_launch_ms": scan["single_launch_ms"]},
         "mfma": {"achieved_causal": scan["tflops_causal"], "achieved_dense_tiles": scan["tflops_dense_tiles"],
                  "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": scan["tflops_causal"] / MFMA_BF16_PEAK_TFLOPS,
                  "note": "41.6 flop/B at dk=64: a single-pass scan is HBM-bound and cannot exceed ~13% of MFMA peak"},
@@ -436,6 +472,8 @@ def main():
             "beyond_cache_512_sequences": {"ms_per_step": big["launch_ms"], "GB_per_s": big["gbs"],
                                            "hbm_frac": big["gbs"] / HBM_PEAK_GBS},
         }
+        if not args.skip_cpu_baseline:
+            out["decode"]["cpu_baseline"] = decode_cpu_baseline(dw, wl)
     if not args.skip_other_configs:
         out["decode_small_batch"] = bench_decode_small(rodimus, wl, dev)
         out["ddts_gates"] = bench_gates(w, rodimus, wl, dev)
