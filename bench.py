@@ -47,7 +47,7 @@ def warm_up(step, launches, min_seconds=0.08):
     return done
 
 
-def bench_scan(w, steps, warmup, rodimus, wl, dev, zbeta=False, exact_warmup=False):
+def bench_scan(w, steps, warmup, rodimus, wl, dev, zbeta=False):
     inp = wl.make_scan_inputs(w)
     g = {k: (None if v is None else v.to(dev)) for k, v in inp.items()}
     o = torch.empty((w.B, w.T, w.H, w.dv), dtype=torch.bfloat16, device=dev)
@@ -63,12 +63,9 @@ def bench_scan(w, steps, warmup, rodimus, wl, dev, zbeta=False, exact_warmup=Fal
             rodimus.rodimus_chunk_scan_fwd(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], g["S0"],
                                            chunk=w.chunk, o=o, S_T=S_T, workspace=ws)
 
-    if exact_warmup:
-        for _ in range(warmup):
-            step()
-        torch.cuda.synchronize()
-    else:
-        warm_up(step, warmup)
+    # `warmup` untimed launches as asked, and more until the clocks have settled (see warm_up): with a handful of warm-up
+    # launches alone the timed region would still lie in the clock ramp and read up to 25 % slow
+    settle = warm_up(step, warmup, min_seconds=0.15)
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     start.record()
@@ -101,6 +98,7 @@ def bench_scan(w, steps, warmup, rodimus, wl, dev, zbeta=False, exact_warmup=Fal
         "tflops_dense_tiles": flops_dense / (launch_ms * 1e-3) / 1e12,
         "path": rodimus.rodimus_chunk_scan_path(w.B, w.T, w.H, w.dk, w.dv, w.chunk, torch.bfloat16),
         "single_launch_ms": {"median": singles[len(singles) // 2], "min": singles[0], "launches": n_single} if singles else None,
+        "settle_launches": settle,
     }
     return res, inp, o, S_T
 
@@ -407,8 +405,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=200,
-                    help="untimed launches before the timed ones (exactly this many for the headline scan; the clocks need "
-                         "about 130 launches = 30 ms after an idle phase to settle)")
+                    help="untimed launches before the timed ones (at least this many; every leg goes on launching until the "
+                         "clocks have settled, about 30 ms after an idle phase, and reports the count)")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--skip-decode", action="store_true")
     ap.add_argument("--skip-other-configs", action="store_true")
@@ -436,7 +434,7 @@ def main():
         del src, dst
 
     w = wl.LAYER_1P6B
-    scan, inp, o, S_T = bench_scan(w, args.steps, args.warmup, rodimus, wl, dev, exact_warmup=True)
+    scan, inp, o, S_T = bench_scan(w, args.steps, args.warmup, rodimus, wl, dev)
     out = {
         "metric": "chunk_scan_tokens_per_s", "value": scan["tokens_per_s"], "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": scan["ms_per_step"],
@@ -447,8 +445,12 @@ def main():
                    "kernel_path": {1: "generic", 2: "mfma"}.get(scan["path"], "none")},
         "roofline": {"bound": "hbm", "achieved": scan["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": scan["gbs"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES["scan_layer_1p6b"],
+                     "traffic_source": "profiles/scan_mfma_kernel_layer_1p6b.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of the same "
+                                       "launch, a counter figure from the profile run, not measured by this run)",
                      "kernel": "scan_mfma_kernel", "launch_ms": scan["launch_ms"], "algorithmic_bytes": scan["algo_bytes"],
-                     "single_launch_ms": scan["single_launch_ms"]},
+                     "single_launch_ms": scan["single_launch_ms"], "settle_launches": scan["settle_launches"],
+                     "settle_note": "untimed launches before the timed region: --warmup as given, continued until 150 ms of "
+                                    "back-to-back launches have passed (GPU clocks ramp for ~30 ms after an idle phase)"},
         "mfma": {"achieved_causal": scan["tflops_causal"], "achieved_dense_tiles": scan["tflops_dense_tiles"],
                  "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": scan["tflops_causal"] / MFMA_BF16_PEAK_TFLOPS,
                  "note": "41.6 flop/B at dk=64: a single-pass scan is HBM-bound and cannot exceed ~13% of MFMA peak"},
@@ -464,13 +466,19 @@ def main():
             "steps": dw.steps, "state_finite": dec["finite"],
             "workload": f"{dw.name}: {dw.N} sequences x H={dw.H} x ({dw.dk}x{dw.dv}) fp32 states, bf16 q/k/v/o, "
                         f"{dw.steps} chained steps",
-            "roofline": {"bound": "hbm", "achieved": dec["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": dec["gbs"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES["decode_256x16"],
-                         "kernel": "decode_step_kernel", "algorithmic_bytes": dec["algo_bytes"]},
-            "note": "256 sequences hold exactly 256 MiB of state, the size of the last-level cache: chained steps find part "
-                    "of it there, so `achieved` is an effective rate; `beyond_cache_512_sequences` is the all-HBM rate",
-            "beyond_cache_512_sequences": {"ms_per_step": big["launch_ms"], "GB_per_s": big["gbs"],
-                                           "hbm_frac": big["gbs"] / HBM_PEAK_GBS},
+            # the figure claimed against the HBM roofline is the all-HBM one: 512 sequences hold 512 MiB of state, twice the
+            # last-level cache, so every byte of a step comes from and goes to HBM
+            "roofline": {"bound": "hbm", "achieved": big["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": big["gbs"] / HBM_PEAK_GBS, "traffic": None,
+                         "kernel": "decode_step_kernel (streaming variant)", "algorithmic_bytes": big["algo_bytes"],
+                         "launch_ms": big["launch_ms"], "workload": "512 sequences x 16 heads, 200 chained steps"},
+            "cache_assisted_256_sequences": {
+                "GB_per_s_effective": dec["gbs"], "frac_of_hbm_peak": dec["gbs"] / HBM_PEAK_GBS, "ms_per_step": dec["launch_ms"],
+                "algorithmic_bytes": dec["algo_bytes"], "traffic": MEASURED_TRAFFIC_BYTES["decode_256x16"],
+                "traffic_source": "profiles/decode_step_kernel_256x16.md (counter figure of the profile run)",
+                "note": "256 sequences hold exactly 256 MiB of state, the size of the last-level cache: chained steps find part "
+                        "of it there, so this is an effective rate, not an HBM rate; with other layers running between two "
+                        "steps of a model it would not be reached"},
         }
         if not args.skip_cpu_baseline:
             out["decode"]["cpu_baseline"] = decode_cpu_baseline(dw, wl)

@@ -89,6 +89,14 @@ int scan_entry(const void *q, const void *k, const void *v, const float *log_alp
     const bool mfma = !general && scan_mfma_supports(dk, dv, chunk, io_dtype);
     const size_t need = (!packed && mfma) ? scan_mfma_workspace_bytes(B, T, H, dv) : 0;
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return RODIMUS_ERR_WORKSPACE;
+    if (need > 0) {
+        // the kernels write the first `need` bytes of the workspace while they read the inputs and write the outputs
+        const void *others[13] = {q, k, v, gate_a, gate_b, beta, S0, o, S_T, stage.x_prime, stage.d, stage.z_gate, log_beta_t};
+        const size_t other_bytes[13] = {qk_bytes, qk_bytes, v_bytes, la_bytes, la_bytes, beta_bytes, state_bytes, v_bytes, state_bytes,
+                                        v_bytes, (size_t)H * dv * 4, v_bytes, tokens * dv * 4};
+        for (int i = 0; i < 13; ++i)
+            if (overlaps(workspace, need, others[i], other_bytes[i])) return RODIMUS_ERR_ALIAS;
+    }
 
     ScanArgs a{q, k, v, log_alpha, beta, beta_preact, S0, o, S_T, B, T, H, dk, dv, chunk, io_dtype,
                packed ? cu_seqlens : nullptr, stage, workspace, workspace_bytes, static_cast<hipStream_t>(stream)};

@@ -72,6 +72,20 @@ def test_scan_rejects_bad_arguments_before_any_launch(L):
     assert _scan(L, S_T=0x10000) == E_ALIAS                 # S_T over q
 
 
+def test_scan_workspace_may_not_overlap_a_tensor_of_the_call(L):
+    # a call that is cut along the sequence (few (batch, head) pairs, long T) writes its workspace while it reads the inputs
+    G = 0x100000000
+    shape = dict(B=1, T=32768, H=16, dk=64, dv=256, chunk=64, io=rodimus.BF16)
+    need = L.rodimus_chunk_scan_workspace_bytes(1, 32768, 16, 64, 256, 64, rodimus.BF16)
+    assert need > 0
+    ptrs = dict(q=1 * G, k=2 * G, v=3 * G, la=4 * G, beta=5 * G, S0=6 * G, o=7 * G, S_T=8 * G)
+    assert _scan(L, **shape, **ptrs, ws=None, ws_bytes=0) == E_WS
+    assert _scan(L, **shape, **ptrs, ws=9 * G, ws_bytes=need - 16) == E_WS
+    for name, at in ptrs.items():
+        assert _scan(L, **shape, **ptrs, ws=at, ws_bytes=need) == E_ALIAS, name
+        assert _scan(L, **shape, **ptrs, ws=at - need + 16, ws_bytes=need) == E_ALIAS, name     # its tail reaches into the tensor
+
+
 def test_decode_rejects_bad_arguments_before_any_launch(L):
     assert _decode(L, io=-1) == E_DTYPE
     for bad in (dict(N=-1), dict(H=-1), dict(dk=0), dict(dk=257), dict(dv=0), dict(dv=30)):
