@@ -19,7 +19,8 @@
  * General conventions
  *   - Every pointer is a DEVICE pointer owned by the caller.  The library never
  *     allocates or frees device memory, never synchronises and keeps no global
- *     state; all work is enqueued on `stream` (a hipStream_t, NULL = default).
+ *     state (one exception: rodimus_chunk_scan_fwd_noalloc and its built-in scratch
+ *     buffer); all work is enqueued on `stream` (a hipStream_t, NULL = default).
  *   - Innermost index contiguous, no strides:
  *         q, k, log_alpha : [B, T, H, dk]     v, beta, o : [B, T, H, dv]
  *         S0, S_T, S      : [B, H, dk, dv]    (decode: B -> N, T dropped)
@@ -50,7 +51,8 @@ typedef enum {
     RODIMUS_ERR_ALIGN = 4,       /* a base pointer is not 16-byte aligned                 */
     RODIMUS_ERR_WORKSPACE = 5,   /* workspace missing or smaller than required            */
     RODIMUS_ERR_LAUNCH = 6,      /* the HIP runtime refused the launch                    */
-    RODIMUS_ERR_ALIAS = 7        /* an output overlaps an input it must not overlap       */
+    RODIMUS_ERR_ALIAS = 7,       /* an output overlaps an input it must not overlap       */
+    RODIMUS_ERR_SCRATCH = 8      /* rodimus_chunk_scan_fwd_noalloc: the shape needs more than the built-in scratch */
 } rodimus_status;
 
 typedef enum { RODIMUS_F32 = 0, RODIMUS_BF16 = 1 } rodimus_dtype;
@@ -101,6 +103,29 @@ size_t rodimus_chunk_scan_workspace_bytes(int B, int T, int H, int dk, int dv, i
 
 /* Kernel family (rodimus_path) the call above would run for this shape. */
 int rodimus_chunk_scan_path(int B, int T, int H, int dk, int dv, int chunk, int io_dtype);
+
+/*
+ * rodimus_chunk_scan_fwd for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical results, but no
+ * workspace argument: a call that is cut along the sequence keeps its segment summaries and entering states in a
+ * buffer of RODIMUS_NOALLOC_SCRATCH_BYTES that is part of the library's device image (every GPU the library runs
+ * on holds its own copy until the process ends).  The call allocates and frees nothing.
+ *   - A shape whose workspace (rodimus_chunk_scan_workspace_bytes) exceeds the buffer returns RODIMUS_ERR_SCRATCH
+ *     before anything is launched; so does a failure to locate the buffer on the current device.
+ *   - Every call on a GPU shares that GPU's buffer, which keeps the last call's contents (nothing in it has to start
+ *     at zero).  Calls that overlap in time on one GPU, on different streams, race on it: order them on one stream
+ *     or with events.
+ *   - The first call on each device looks the buffer's address up (hipGetSymbolAddress, once per device, under a
+ *     lock); make that first call outside stream capture.
+ */
+#define RODIMUS_NOALLOC_SCRATCH_BYTES (10u << 20)
+int rodimus_chunk_scan_fwd_noalloc(const void *q, const void *k, const void *v,
+                                   const float *log_alpha, const float *beta, const float *S0,
+                                   void *o, float *S_T,
+                                   int B, int T, int H, int dk, int dv, int chunk, int io_dtype, void *stream);
+
+/* Size of that built-in buffer (RODIMUS_NOALLOC_SCRATCH_BYTES of the library that is loaded). */
+size_t rodimus_chunk_scan_fwd_noalloc_scratch_bytes(void);
 
 /*
  * One recurrent decode step for N independent sequences (paper Sec. 3.1.3: at inference the

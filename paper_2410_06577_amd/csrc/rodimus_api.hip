@@ -2,6 +2,8 @@
 // family.  Nothing here allocates, synchronises or keeps state.  See include/rodimus.h for the contract.
 #include "internal.h"
 
+#include <mutex>
+
 namespace {
 
 using namespace rodimus;
@@ -167,6 +169,7 @@ const char *rodimus_status_string(int status)
     case RODIMUS_ERR_WORKSPACE: return "workspace is missing or too small";
     case RODIMUS_ERR_LAUNCH: return "the HIP runtime refused the launch";
     case RODIMUS_ERR_ALIAS: return "an output overlaps an input it must not overlap";
+    case RODIMUS_ERR_SCRATCH: return "the call needs more scratch than the library's built-in buffer holds (or the buffer could not be located)";
     default: return "unknown status";
     }
 }
@@ -455,6 +458,59 @@ int rodimus_short_conv_step(const void *x, const float *w, const float *bias, vo
                             int act, int io_dtype, void *stream)
 {
     return short_conv_entry(x, w, bias, state, y, state, N, 1, C, W, act, io_dtype, stream, true);
+}
+
+}  // extern "C"
+
+// ---- the scan for callers that cannot allocate ------------------------------------------------------------------
+// Same kernels as rodimus_chunk_scan_fwd; the workspace of a call that is cut along the sequence is a buffer inside the
+// library's own device image instead of a caller allocation.  Every GPU holds its own copy of the array at its own
+// address; host code may use the array's memory only through the address hipGetSymbolAddress returns for the current device.
+namespace {
+
+constexpr size_t kScratchBytes = (size_t)RODIMUS_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];       // device address of `scratch` on each device, once looked up
+
+// Address of the current device's copy of `scratch` (looked up once per device), or NULL on failure.
+void *scratch_on_current_device()
+{
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device] == nullptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[device] = ptr;
+    }
+    return g_scratch_ptr[device];
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t rodimus_chunk_scan_fwd_noalloc_scratch_bytes(void) { return kScratchBytes; }
+
+int rodimus_chunk_scan_fwd_noalloc(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta,
+                                   const float *S0, void *o, float *S_T, int B, int T, int H, int dk, int dv, int chunk,
+                                   int io_dtype, void *stream)
+{
+    const int shape = scan_shape_status(B, T, H, dk, dv, chunk, io_dtype);
+    if (shape != RODIMUS_OK) return shape;
+    const size_t need = scan_mfma_supports(dk, dv, chunk, io_dtype) ? scan_mfma_workspace_bytes(B, T, H, dv) : 0;
+    if (need > kScratchBytes) return RODIMUS_ERR_SCRATCH;
+    // the buffer's address on this device; if it cannot be found the call below still validates every argument and then
+    // ends at its workspace check, before any launch
+    void *ws = need > 0 ? scratch_on_current_device() : nullptr;
+    // nothing in the buffer has to start at zero: the segment summaries, decays and entering states are all written by the
+    // call's own kernels before they are read
+    const int status = scan_entry(q, k, v, log_alpha, beta, false, S0, o, S_T, B, T, H, dk, dv, chunk, io_dtype, ws,
+                                  ws != nullptr ? need : 0, stream);
+    return status == RODIMUS_ERR_WORKSPACE ? RODIMUS_ERR_SCRATCH : status;
 }
 
 }  // extern "C"

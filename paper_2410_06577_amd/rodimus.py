@@ -41,6 +41,10 @@ def lib() -> ctypes.CDLL:
         L.rodimus_status_string.restype = ctypes.c_char_p
         L.rodimus_chunk_scan_fwd.argtypes = [vp] * 8 + [i] * 7 + [vp, sz, vp]
         L.rodimus_chunk_scan_fwd.restype = i
+        L.rodimus_chunk_scan_fwd_noalloc.argtypes = [vp] * 8 + [i] * 7 + [vp]
+        L.rodimus_chunk_scan_fwd_noalloc.restype = i
+        L.rodimus_chunk_scan_fwd_noalloc_scratch_bytes.argtypes = []
+        L.rodimus_chunk_scan_fwd_noalloc_scratch_bytes.restype = sz
         L.rodimus_chunk_scan_workspace_bytes.argtypes = [i] * 7
         L.rodimus_chunk_scan_workspace_bytes.restype = sz
         L.rodimus_chunk_scan_path.argtypes = [i] * 7
@@ -159,6 +163,32 @@ def rodimus_chunk_scan_fwd(q, k, v, log_alpha, beta=None, S0=None, *, chunk=64, 
         entry = lib().rodimus_chunk_scan_fwd_zbeta if _preact else lib().rodimus_chunk_scan_fwd
         _check(entry(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(S0), _ptr(o), _ptr(S_T),
                      B, T, H, dk, dv, int(chunk), _DTYPES[io], _ptr(workspace), ws_bytes, _stream(dev)))
+    return o, S_T
+
+
+def rodimus_chunk_scan_fwd_noalloc(q, k, v, log_alpha, beta, S0, o, S_T, *, chunk=64):
+    """``rodimus_chunk_scan_fwd`` through the entry point that allocates nothing: the caller passes every tensor, outputs
+    included (S_T may be None); a call that is cut along the sequence uses the library's built-in scratch buffer."""
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_chunk_scan_fwd_noalloc needs device tensors (no CPU path exists)")
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    dev, io = q.device, q.dtype
+    _require(q, "q", (B, T, H, dk), io, dev)
+    _require(k, "k", (B, T, H, dk), io, dev)
+    _require(v, "v", (B, T, H, dv), io, dev)
+    _require(log_alpha, "log_alpha", (B, T, H, dk), torch.float32, dev)
+    _require(beta, "beta", (B, T, H, dv), torch.float32, dev)
+    _require(S0, "S0", (B, H, dk, dv), torch.float32, dev)
+    if o is None:
+        raise ValueError("o: the caller passes the output tensor")
+    _require(o, "o", (B, T, H, dv), io, dev)
+    _require(S_T, "S_T", (B, H, dk, dv), torch.float32, dev)
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_chunk_scan_fwd_noalloc(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(S0), _ptr(o),
+                                                    _ptr(S_T), B, T, H, dk, dv, int(chunk), _DTYPES[io], _stream(dev)))
     return o, S_T
 
 

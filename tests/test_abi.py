@@ -9,7 +9,7 @@ import pytest
 from paper_2410_06577_amd import rodimus
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_WS, E_LAUNCH, E_ALIAS = range(8)
+OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_WS, E_LAUNCH, E_ALIAS, E_SCRATCH = range(9)
 
 
 @pytest.fixture(scope="module")
@@ -32,14 +32,15 @@ def test_every_declared_symbol_is_exported(L):
             "rodimus_short_conv_fwd", "rodimus_short_conv_step",
             "rodimus_chunk_scan_fwd_gated", "rodimus_decode_step_gated",
             "rodimus_chunk_scan_fwd_general", "rodimus_decode_step_general",
-            "rodimus_chunk_scan_varlen_bwd", "rodimus_chunk_scan_varlen_bwd_workspace_bytes"} <= declared
+            "rodimus_chunk_scan_varlen_bwd", "rodimus_chunk_scan_varlen_bwd_workspace_bytes",
+            "rodimus_chunk_scan_fwd_noalloc", "rodimus_chunk_scan_fwd_noalloc_scratch_bytes"} <= declared
     for name in declared:
         assert hasattr(L, name), name
 
 
 def test_status_strings(L):
-    seen = {rodimus.status_string(s) for s in range(8)}
-    assert len(seen) == 8 and "ok" in seen
+    seen = {rodimus.status_string(s) for s in range(9)}
+    assert len(seen) == 9 and "ok" in seen
     assert rodimus.status_string(1234) == "unknown status"
 
 
@@ -84,6 +85,27 @@ def test_scan_workspace_may_not_overlap_a_tensor_of_the_call(L):
     for name, at in ptrs.items():
         assert _scan(L, **shape, **ptrs, ws=at, ws_bytes=need) == E_ALIAS, name
         assert _scan(L, **shape, **ptrs, ws=at - need + 16, ws_bytes=need) == E_ALIAS, name     # its tail reaches into the tensor
+
+
+def test_noalloc_scan_validates_and_refuses_shapes_beyond_its_scratch(L):
+    G = 0x100000000
+    p = lambda x: None if x is None else ctypes.c_void_p(x)
+
+    def call(B=1, T=32768, H=16, dk=64, dv=256, chunk=64, io=rodimus.BF16, **ptr):
+        a = dict(q=1 * G, k=2 * G, v=3 * G, la=4 * G, beta=5 * G, S0=6 * G, o=7 * G, S_T=8 * G)
+        a.update(ptr)
+        return L.rodimus_chunk_scan_fwd_noalloc(p(a["q"]), p(a["k"]), p(a["v"]), p(a["la"]), p(a["beta"]), p(a["S0"]), p(a["o"]),
+                                                p(a["S_T"]), B, T, H, dk, dv, chunk, io, None)
+
+    limit = L.rodimus_chunk_scan_fwd_noalloc_scratch_bytes()
+    assert limit == 10 << 20
+    # 95 (batch, head) pairs at dv = 256 are cut in two and need 2 x 95 x 64 KiB of entering states: more than the buffer
+    assert L.rodimus_chunk_scan_workspace_bytes(95, 4096, 1, 64, 256, 64, rodimus.BF16) > limit
+    assert call(B=95, T=4096, H=1) == E_SCRATCH
+    # the usual validation still comes first / still applies
+    assert call(io=7) == E_DTYPE and call(dk=0) == E_SHAPE
+    assert call(q=None) == E_NULL and call(o=3 * G) == E_ALIAS and call(k=2 * G + 8) == E_ALIGN
+    assert call(B=0) == OK and call(T=0, S_T=None) == OK
 
 
 def test_decode_rejects_bad_arguments_before_any_launch(L):
