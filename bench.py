@@ -275,6 +275,39 @@ def bench_gated_scan(w, rodimus, wl, dev, steps, warmup):
             "two_call_pipeline_ms": ms_pipe}
 
 
+def bench_block_scan(w, rodimus, wl, dev, steps, warmup):
+    """The layer scan with the block's output stage fused in (rodimus_chunk_scan_fwd_block): feed-through d .* x' and the SiLU
+    output gate applied where the outputs leave the kernel, o written once."""
+    import numpy as np
+    inp = wl.make_scan_inputs(w)
+    g = {k: (None if v is None else v.to(dev)) for k, v in inp.items()}
+    rng = np.random.Generator(np.random.PCG64(21))
+    shape = (w.B, w.T, w.H, w.dv)
+    x_prime = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(torch.bfloat16).to(dev)
+    z_gate = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(torch.bfloat16).to(dev)
+    d = torch.from_numpy(rng.standard_normal((w.H, w.dv), dtype=np.float32)).to(dev)
+    o = torch.empty(shape, dtype=torch.bfloat16, device=dev)
+    S_T = torch.empty((w.B, w.H, w.dk, w.dv), dtype=torch.float32, device=dev)
+
+    def step():
+        rodimus.rodimus_chunk_scan_fwd_block(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], g["S0"], x_prime=x_prime, d=d,
+                                             z_gate=z_gate, gate_act="silu", chunk=w.chunk, o=o, S_T=S_T)
+
+    warm_up(step, warmup)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(steps):
+        step()
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / steps
+    th = w.token_heads
+    algo = th * (8 * w.dk + 8 * w.dv + 2 * 2 * w.dv) + 2 * w.B * w.H * w.dk * w.dv * 4      # the scan's bytes + x' and z_gate
+    return {"entry_point": "rodimus_chunk_scan_fwd_block", "workload": "layer_1p6b + x' and z_gate (bf16), d fp32, SiLU gate",
+            "launches_per_call": 1, "ms_per_step": ms, "tokens_per_s": w.tokens / (ms * 1e-3), "algorithmic_bytes": algo,
+            "GB_per_s": algo / (ms * 1e-3) / 1e9, "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+
 def bench_short_conv(w, rodimus, wl, dev, steps=50, warmup=20, width=4):
     """The block's ShortConv over the layer workload's tokens: C = H * dv channels, width 4, SiLU, bf16 I/O."""
     C = w.H * w.dv
@@ -493,6 +526,8 @@ def main():
             "tokens_per_s": zb["tokens_per_s"], "ms_per_step": zb["launch_ms"], "algorithmic_bytes": zb["algo_bytes"],
             "GB_per_s": zb["gbs"], "hbm_frac": zb["gbs"] / HBM_PEAK_GBS}
         out["scan_fused_all_gates"] = bench_gated_scan(w, rodimus, wl, dev, args.steps, args.warmup)
+        out["scan_block_output"] = bench_block_scan(w, rodimus, wl, dev, args.steps, args.warmup)
+        out["scan_block_output"]["vs_plain_scan"] = out["scan_block_output"]["ms_per_step"] / scan["launch_ms"]
         out["scan_backward"] = bench_backward(w, rodimus, wl, dev, args.steps, args.warmup)
         zb_bwd = bench_backward(w, rodimus, wl, dev, args.steps, args.warmup, zbeta=True)
         out["scan_backward_fused_value_gate"] = {k: zb_bwd[k] for k in ("entry_point", "ms_per_step", "tokens_per_s", "algorithmic_bytes",

@@ -8,42 +8,40 @@
 //     o_t   = (q_t .* A_t) S_prev + sum_{i<=t} P[t,i] (beta_i .* v_i)
 //     P[t,i]= sum_n q_t[n] k_i[n] prod_{j=i+1..t} alpha_j[n]
 //     S_new = diag(A_16) S_prev + sum_i (k_i .* G_i)^T (beta_i .* v_i)
-// The appendix's quotient A_t / A_i is never formed.  The pairwise decay is built from PRODUCTS of gates by
-// binary splitting of the tile: for a power of two h, a row t with bit h set pairs with the rows i of the first
-// half of its aligned 2h-block and
-//     prod_{j=i+1..t} alpha_j = (prod over t's h-block from its start through t) * (prod over the rows after i
-//                               to the end of i's h-block).
-// Every pair i < t belongs to exactly one h, all factors are <= 1 for log_alpha <= 0 and exactly 0 after
-// alpha = 0, so hard resets and decays beyond the fp32 range are exact.
+// The pairwise decay inside a tile is built in one of two ways, chosen per tile (wavefront-uniform):
+//   * quotient form (the appendix's (Q .* A)(K / A)^T, the common case): one copy of q scaled by A_t, one of k
+//     scaled by 1 / A_i, a single masked Gram matrix, G_i = A_16 / A_i.  Taken only when the tile's total decay
+//     A_16 is at least 2^-80 in every channel, so that no reciprocal can overflow;
+//   * product-only form (a hard reset or a very strong decay inside the tile): binary splitting of the tile.  For a
+//     power of two h, a row t with bit h set pairs with the rows i of the first half of its aligned 2h-block and
+//         prod_{j=i+1..t} alpha_j = (prod over t's h-block from its start through t) * (prod over the rows after i
+//                                   to the end of i's h-block).
+//     Every pair i < t belongs to exactly one h, all factors are <= 1 for log_alpha <= 0 and exactly 0 after
+//     alpha = 0, so hard resets and decays beyond the fp32 range are exact.
 //
-// One workgroup (8 wavefronts) owns one (batch, head) and 128 value columns and walks its tokens in order.
+// One workgroup (12 wavefronts) owns one (batch, head) and 128 value columns and walks its tokens in order.
 // The wavefronts are specialised and work one chunk apart through double-buffered LDS, with ONE barrier per
 // 64 tokens:
 //   wavefronts 0-3 ("gate" wavefronts), one 16-row tile each: lane = (row, 16 key channels).  exp of the
-//       log-gates, the prefix/suffix products of every split level by DPP across the 16 lanes of a row group,
-//       the decayed copies of q and k as bf16 MFMA operands straight from registers, the level scores as
-//       masked Gram matrices (MFMA), and for the other half: q .* A, (k .* G)^T, A_16 and P into LDS.
+//       log-gates, the prefix products by DPP across the 16 lanes of a row group, the decayed copies of q and k
+//       as bf16 MFMA operands straight from registers, the scores as masked Gram matrices (MFMA), and for the
+//       state wavefronts: q .* A, (k .* G)^T, A_16 and P into LDS.  They fetch their own q, k and gates one chunk
+//       ahead into registers.
 //   wavefronts 4-7 ("state" wavefronts), 32 value columns each: the fp32 state slab (64 x 32) lives in MFMA
-//       accumulators for the whole walk; per tile o^T = S^T (q .* A)^T + (beta .* v)^T P^T, the bf16 store of
-//       o, S = diag(A_16) S + (k .* G)^T (beta .* v), and the bf16 copy of S that feeds the next tile.
-// Global loads are issued one chunk ahead into registers by the wavefront that consumes them.
+//       accumulators for the whole walk; per tile o^T = S^T (q .* A)^T + (beta .* v)^T P^T into LDS,
+//       S = diag(A_16) S + (k .* G)^T (beta .* v), and the bf16 copy of S that feeds the next tile.  They touch
+//       no global memory inside the walk: the serial chain of the recurrence never waits on a memory queue.
+//   wavefronts 8-11 ("value" wavefronts), one 16-row tile each, all 128 columns: fetch v and the value gate one
+//       chunk ahead, stage beta .* v into LDS, and move finished outputs from LDS to global memory in whole
+//       256-byte rows, applying the block's output stage (feed-through and output gate, Sec. 3.1.3) on the way.
 #include "internal.h"
 
-// Optional cycle counters per wavefront role and loop part (build with -DRODIMUS_PROF; not part of the library's
-// interface and not in the shipped build): how the per-chunk clock budgets quoted for this kernel were measured.
-#ifdef RODIMUS_PROF
-__device__ unsigned long long g_prof[64];
-#define PROF_T() clock64()
-#define PROF_ADD(slot, t0) do { if (blockIdx.x == 0 && blockIdx.y == 0 && lane == 0) g_prof[slot] += clock64() - (t0); } while (0)
-extern "C" int rodimus_debug_read_prof(unsigned long long *out, int reset)
-{
-    hipError_t e = hipMemcpyFromSymbol(out, HIP_SYMBOL(g_prof), sizeof(unsigned long long) * 64);
-    if (reset) { unsigned long long z[64] = {0}; hipMemcpyToSymbol(HIP_SYMBOL(g_prof), z, sizeof(z)); }
-    return (int)e;
-}
-#else
-#define PROF_T() 0ull
-#define PROF_ADD(slot, t0) do { (void)(t0); } while (0)
+#include <atomic>
+
+#ifndef PRIO_GATE
+#define PRIO_GATE 0
+#define PRIO_STATE 1
+#define PRIO_VALUE 0
 #endif
 
 namespace rodimus {
@@ -54,7 +52,7 @@ constexpr int kK = 64;           // key width
 constexpr int kTile = 16;        // rows per state update
 constexpr int kChunk = 64;       // tokens per barrier (4 tiles)
 constexpr int kColTile = 128;    // value columns per workgroup
-constexpr int kThreads = 512;
+constexpr int kThreads = 768;        // 12 wavefronts: 4 gate, 4 state, 4 value
 
 // ---- LDS map (bytes).  Two buffers (chunk parity) of what the gate wavefronts hand to the state wavefronts.
 constexpr int kQnTile = kTile * 128;                 // q .* A,      [16 rows][64 ch] bf16, 16-byte units swizzled by row
@@ -68,9 +66,12 @@ constexpr int kOffGm = kOffPd + 4 * kPdTile;
 constexpr int kBufBytes = kOffGm + 4 * kGmTile;      // 19456
 constexpr int kOffVt = 2 * kBufBytes;                // beta .* v, two chunk buffers of [64 t][128 col] bf16, 8-byte units placed by lds_value_unit()
 constexpr int kVtBuf = kChunk * 256;
-constexpr int kOffOb = kOffVt + 2 * kVtBuf;          // outputs, two chunk buffers of [64 t][128 col] bf16, 16-byte units swizzled by row
-constexpr int kObBuf = kChunk * 256;
-constexpr int kLdsBytes = kOffOb + 2 * kObBuf;       // 104448
+constexpr int kOffOb = kOffVt + 2 * kVtBuf;          // outputs, two chunk buffers of [64 t][128 col], 16-byte units swizzled by row:
+                                                     // bf16 (256-byte rows), or fp32 (512-byte rows) when the block's output stage
+                                                     // follows, so that o is rounded once, after the stage
+constexpr int ob_buf_bytes(bool block) { return kChunk * (block ? 512 : 256); }
+constexpr int kFeedBytes = kColTile * 4;             // block form: the feed-through weights d of this head and column tile, fp32, after the output buffers
+constexpr int lds_bytes(bool block) { return kOffOb + 2 * ob_buf_bytes(block) + (block ? kFeedBytes : 0); }     // 104448 / 137728
 
 // Where an 8-byte unit lives inside its token row; the XOR with the token index spreads the 32 (reader) or 64
 // (writer) lanes of an access over all banks.
@@ -103,12 +104,20 @@ __device__ __forceinline__ float swizzle_lane(float src)
 }
 constexpr int QP(int a, int b, int c, int d) { return a | (b << 2) | (c << 4) | (d << 6); }
 
+// Value gate of a call (template parameter kBeta) and parts of the block's output stage it applies (kStage): compile-time,
+// so that no load of the walk sits behind a branch.
+constexpr int kBetaNone = 0, kBetaValues = 1, kBetaPreact = 2;      // all ones / fp32 gate values / bf16 pre-activations (sigmoid in the kernel)
+constexpr int kStageFeed = 1, kStageGate = 2;                       // bit flags: feed-through d .* x', output gate act(z)
+
 struct Geometry {
     const bf16_t *q, *k, *v;
     const float *la;
     const bf16_t *zg, *zt;  // gated form (kGated): pre-activations of the key-side gates instead of la
-    const void *beta;       // value gate: fp32 values, or bf16 pre-activations (kZBeta), or null
+    const void *beta;       // value gate: fp32 values, or bf16 pre-activations, or null (kBeta)
     bf16_t *o;
+    const bf16_t *x_prime, *z_gate;     // output stage of the block (kStage): feed-through input and gate pre-activation, or null
+    const float *d;                     // feed-through weights [H, dv]
+    int act;
     int H, dv;
     size_t tok0;            // row of the sequence's first token in the [tokens, H, .] tensors
     int h, j0;
@@ -120,35 +129,84 @@ struct Geometry {
 // =========================================================================================================
 struct GateLoads {          // one row, 16 channels: 8g..8g+7 and 32+8g..32+8g+7
     uint4 q[2], k[2];
-    floatx4_t la[4];        // gated form, until gate_activate(): the bits of z_g (la[0], la[1]) and z_tau (la[2], la[3]), 8 bf16 each
+    floatx4_t la[4];        // gated form: the bits of z_g (la[0], la[1]) and z_tau (la[2], la[3]), 8 bf16 each
 };
 
-// Loads are unconditional (the row index is clamped to the last valid token) so that they stay in flight across
-// the barrier; rows at or beyond T are neutralised when consumed (gate_tile: q = k = 0, alpha = 1).
-template <bool kSummary, bool kGated>
-__device__ __forceinline__ void gate_prefetch(const Geometry &g, int t, int grp, GateLoads &p)
+// Addressing of the per-chunk global accesses: a base that is uniform over the wavefront (the chunk's first token row of
+// this (batch, head), kept in scalar registers) plus a 32-bit byte offset per lane (the lane's row inside the chunk and its
+// channels / columns).  One vector register per access instead of a 64-bit address pair: the address registers are what
+// the three roles cannot afford at twelve wavefronts per workgroup.
+// Loads are unconditional so that they stay in flight across the barrier: a chunk start beyond the sequence end is moved
+// back to the last valid token and the lane's row is clamped to it; rows at or beyond the end are neutralised where
+// they are consumed (gate_tile: q = k = 0, alpha = 1; stage_values: v = 0) and never stored.
+struct ChunkRows {
+    size_t first;           // token-head index ((tok0 + s') * H + h) of the chunk's first row, uniform
+    int s_clamped;          // s' = min(s, t_end - 1), uniform
+};
+__device__ __forceinline__ ChunkRows chunk_rows(const Geometry &g, int s)
 {
-    const size_t tok = (g.tok0 + min(t, g.t_end - 1)) * g.H + g.h;
-    const bf16_t *qp = g.q + tok * kK + 8 * grp;
-    const bf16_t *kp = g.k + tok * kK + 8 * grp;
+    const int s_clamped = min(s, g.t_end - 1);
+    return ChunkRows{(g.tok0 + (size_t)s_clamped) * g.H + g.h, s_clamped};
+}
+// rows of the lane's token past the chunk's first row (0 for every lane of a chunk that lies beyond the end)
+__device__ __forceinline__ uint32_t row_in_chunk(const Geometry &g, const ChunkRows &c, int s, int row)
+{
+    return (uint32_t)(min(s + row, g.t_end - 1) - c.s_clamped);
+}
+// A global-memory pointer that is the same in every lane, pinned to scalar registers (when scalar registers run short the
+// compiler otherwise keeps such bases in vector register pairs and falls back to 64-bit vector addresses).  The result is
+// typed as a global (address space 1) pointer: the round trip through integers hides that from the compiler.
+typedef __attribute__((address_space(1))) char global_char_t;
+__device__ __forceinline__ global_char_t *scalar_base(const void *p)
+{
+    const uint64_t a = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a), hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+    return reinterpret_cast<global_char_t *>(((uint64_t)hi << 32) | lo);
+}
+template <typename T>
+__device__ __forceinline__ T load_at(const void *uniform_base, uint32_t byte_offset)
+{
+    static_assert(sizeof(T) == 16, "16-byte accesses only");
+    typedef __attribute__((address_space(1))) const floatx4_t global_t;
+    return __builtin_bit_cast(T, *reinterpret_cast<global_t *>(scalar_base(uniform_base) + (size_t)byte_offset));
+}
+__device__ __forceinline__ uint4 load_streaming_at(const void *uniform_base, uint32_t byte_offset)
+{
+    typedef __attribute__((address_space(1))) const floatx4_t global_t;
+    return __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<global_t *>(scalar_base(uniform_base) + (size_t)byte_offset)));
+}
+__device__ __forceinline__ void store_streaming_at(void *uniform_base, uint32_t byte_offset, uint4 w)
+{
+    typedef __attribute__((address_space(1))) floatx4_t global_t;
+    __builtin_nontemporal_store(__builtin_bit_cast(floatx4_t, w), reinterpret_cast<global_t *>(scalar_base(uniform_base) + (size_t)byte_offset));
+}
+
+// Chunk starting at token `s`, this lane's row `row` of it (16 * tile + n) and channel group `grp`.
+template <bool kSummary, bool kGated>
+__device__ __forceinline__ void gate_prefetch(const Geometry &g, int s, int row, int grp, GateLoads &p)
+{
+    const ChunkRows c = chunk_rows(g, s);
+    const uint32_t off = row_in_chunk(g, c, s, row) * (uint32_t)(g.H * kK * 2) + 16u * grp;      // bytes into a bf16 [.., H, 64] tensor
     if (!kSummary) {
-        p.q[0] = *reinterpret_cast<const uint4 *>(qp);
-        p.q[1] = *reinterpret_cast<const uint4 *>(qp + 32);
+        const bf16_t *qb = g.q + c.first * kK;
+        p.q[0] = load_at<uint4>(qb, off);
+        p.q[1] = load_at<uint4>(qb, off + 64);
     }
-    p.k[0] = *reinterpret_cast<const uint4 *>(kp);
-    p.k[1] = *reinterpret_cast<const uint4 *>(kp + 32);
+    const bf16_t *kb = g.k + c.first * kK;
+    p.k[0] = load_at<uint4>(kb, off);
+    p.k[1] = load_at<uint4>(kb, off + 64);
     if (kGated) {
-        const bf16_t *gp = g.zg + tok * kK + 8 * grp, *tp = g.zt + tok * kK + 8 * grp;
-        p.la[0] = *reinterpret_cast<const floatx4_t *>(gp);
-        p.la[1] = *reinterpret_cast<const floatx4_t *>(gp + 32);
-        p.la[2] = *reinterpret_cast<const floatx4_t *>(tp);
-        p.la[3] = *reinterpret_cast<const floatx4_t *>(tp + 32);
+        const bf16_t *gb = g.zg + c.first * kK, *tb = g.zt + c.first * kK;
+        p.la[0] = load_at<floatx4_t>(gb, off);
+        p.la[1] = load_at<floatx4_t>(gb, off + 64);
+        p.la[2] = load_at<floatx4_t>(tb, off);
+        p.la[3] = load_at<floatx4_t>(tb, off + 64);
     } else {
-        const float *lp = g.la + tok * kK + 8 * grp;
-        p.la[0] = *reinterpret_cast<const floatx4_t *>(lp);
-        p.la[1] = *reinterpret_cast<const floatx4_t *>(lp + 4);
-        p.la[2] = *reinterpret_cast<const floatx4_t *>(lp + 32);
-        p.la[3] = *reinterpret_cast<const floatx4_t *>(lp + 36);
+        const float *lb = g.la + c.first * kK;
+        p.la[0] = load_at<floatx4_t>(lb, 2 * off);
+        p.la[1] = load_at<floatx4_t>(lb, 2 * off + 16);
+        p.la[2] = load_at<floatx4_t>(lb, 2 * off + 128);
+        p.la[3] = load_at<floatx4_t>(lb, 2 * off + 144);
     }
 }
 
@@ -160,60 +218,6 @@ __device__ __forceinline__ void unpack_bf16x8(const uint4 &w, float *x)
     x[4] = bf16_lo(w.z); x[5] = bf16_hi(w.z); x[6] = bf16_lo(w.w); x[7] = bf16_hi(w.w);
 }
 
-// Gated form: turn the loaded pre-activations and raw q, k of one row into what the rest of the gate wavefront expects
-// (paper Sec. 3.1.2 and the pre-processing of Sec. 3.1.3): log_alpha = -softplus(z_g) sigmoid(z_tau) in fp32,
-// k <- softplus(z_g)^sigmoid(z_tau) .* k / max(||k||_2, 1e-12) and q <- q / sqrt(64), both rounded to bf16 (what a separate
-// gate pass would have written; the division by 8 is exact).  The four lanes that share a row (one per channel group)
-// add up the squared norm.
-template <bool kSummary>
-__device__ __forceinline__ void gate_activate(GateLoads &in)
-{
-    float kf[16], zg[16], zt[16];
-    unpack_bf16x8(in.k[0], kf);
-    unpack_bf16x8(in.k[1], kf + 8);
-    unpack_bf16x8(__builtin_bit_cast(uint4, in.la[0]), zg);
-    unpack_bf16x8(__builtin_bit_cast(uint4, in.la[1]), zg + 8);
-    unpack_bf16x8(__builtin_bit_cast(uint4, in.la[2]), zt);
-    unpack_bf16x8(__builtin_bit_cast(uint4, in.la[3]), zt + 8);
-    float ss = 0.f;
-#pragma unroll
-    for (int c = 0; c < 16; ++c) ss = fmaf(kf[c], kf[c], ss);
-    ss += __shfl_xor(ss, 16);
-    ss += __shfl_xor(ss, 32);
-    const float inv_norm = inverse_key_norm(ss);
-    float la[16], kh[16];
-#pragma unroll
-    for (int c = 0; c < 16; ++c) {
-        float alpha_hat;
-        ddts_channel_gates<true>(zg[c], zt[c], la[c], alpha_hat);
-        kh[c] = alpha_hat * kf[c] * inv_norm;
-    }
-    in.k[0] = __builtin_bit_cast(uint4, pack8(kh));
-    in.k[1] = __builtin_bit_cast(uint4, pack8(kh + 8));
-#pragma unroll
-    for (int m = 0; m < 4; ++m) in.la[m] = floatx4_t{la[4 * m], la[4 * m + 1], la[4 * m + 2], la[4 * m + 3]};
-    if (!kSummary) {
-#pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            float qf[8];
-            unpack_bf16x8(in.q[m], qf);
-#pragma unroll
-            for (int c = 0; c < 8; ++c) qf[c] *= 0.125f;
-            in.q[m] = __builtin_bit_cast(uint4, pack8(qf));
-        }
-    }
-}
-
-__device__ __forceinline__ void gate_mask_padding(bool valid, GateLoads &p)
-{
-    if (!valid) {
-        const uint4 z = {0u, 0u, 0u, 0u};
-        const floatx4_t zf = {0.f, 0.f, 0.f, 0.f};
-        p.q[0] = p.q[1] = p.k[0] = p.k[1] = z;
-        p.la[0] = p.la[1] = p.la[2] = p.la[3] = zf;
-    }
-}
-
 __device__ __forceinline__ bf16x8_t pack8(const float *x)
 {
     uint4 w = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7])};
@@ -221,8 +225,11 @@ __device__ __forceinline__ bf16x8_t pack8(const float *x)
 }
 
 // ---- product-only construction of one tile (every split level).  Exact for any gates, including alpha = 0.
-// It works on one half of the lane's channels at a time (8 channels = the 8 operand slots of one MFMA), which
-// keeps its register footprint small; the two halves add into the same score accumulator.
+// It works on one half of the lane's channels at a time (8 channels = the 8 operand slots of one MFMA), which keeps
+// its register footprint small; the two halves add into the same score accumulator.
+struct HalfRow {            // 8 channels of one row: 8g..8g+7 (half 0) or 32+8g..32+8g+7 (half 1)
+    float q[8], k[8], la[8];
+};
 
 // scores of one split level from 8 channels: entries (key row m = 4*grp + r, query row n = row) of
 // (k .* suffix)(q .* prefix)^T that belong to the level
@@ -247,30 +254,59 @@ __device__ __forceinline__ void level_scores(const float (&q)[8], const float (&
     }
 }
 
-// Channels 32*kHalf + 8grp .. +7 of one tile.
-template <bool kSummary, int kHalf>
-__device__ __forceinline__ void gate_half_products(unsigned char *buf, int tile, int row, int grp, const GateLoads &in,
-                                                   floatx4_t &acc)
+// A value rounded to bf16 and widened again (what a pass that writes bf16 to memory would hand on).
+__device__ __forceinline__ float round_to_bf16(float x) { return bf16_lo(pack_bf16x2(x, 0.f)); }
+
+// Channels of `kHalf` of a loaded row as the tile construction wants them: fp32 log_alpha, k and q widened.
+// Gated form (Sec. 3.1.2 and the pre-processing of Sec. 3.1.3): log_alpha = -softplus(z_g) sigmoid(z_tau) in fp32,
+// k <- softplus(z_g)^sigmoid(z_tau) .* k / max(||k||_2, 1e-12) and q <- q / sqrt(64), both rounded to bf16 (what a separate
+// gate pass would have written; the division by 8 is exact); `inv_norm` is the reciprocal norm of the whole key row.
+// Summary pass: q = 0.  Rows at or beyond the sequence end: q = k = 0, alpha = 1.
+template <bool kSummary, bool kGated, int kHalf>
+__device__ __forceinline__ void prepare_half_row(const GateLoads &in, bool valid, float inv_norm, HalfRow &r)
 {
-    float q[8], k[8], a[8];
-    {
-        const uint32_t qw[4] = {in.q[kHalf].x, in.q[kHalf].y, in.q[kHalf].z, in.q[kHalf].w};
-        const uint32_t kw[4] = {in.k[kHalf].x, in.k[kHalf].y, in.k[kHalf].z, in.k[kHalf].w};
+    unpack_bf16x8(in.k[kHalf], r.k);
+    if (!kSummary) unpack_bf16x8(in.q[kHalf], r.q);
+    if (kGated) {
+        float zg[8], zt[8];
+        unpack_bf16x8(__builtin_bit_cast(uint4, in.la[kHalf]), zg);
+        unpack_bf16x8(__builtin_bit_cast(uint4, in.la[2 + kHalf]), zt);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            float alpha_hat;
+            ddts_channel_gates<true>(zg[j], zt[j], r.la[j], alpha_hat);
+            r.k[j] = round_to_bf16(alpha_hat * r.k[j] * inv_norm);
+            if (!kSummary) r.q[j] *= 0.125f;
+        }
+    } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            q[2 * j] = bf16_lo(qw[j]);
-            q[2 * j + 1] = bf16_hi(qw[j]);
-            k[2 * j] = bf16_lo(kw[j]);
-            k[2 * j + 1] = bf16_hi(kw[j]);
-            a[j] = __expf(in.la[2 * kHalf][j]);           // exp(-inf) = 0
-            a[4 + j] = __expf(in.la[2 * kHalf + 1][j]);
+            r.la[j] = in.la[2 * kHalf][j];
+            r.la[4 + j] = in.la[2 * kHalf + 1][j];
         }
     }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        if (kSummary || !valid) r.q[j] = 0.f;
+        if (!valid) { r.k[j] = 0.f; r.la[j] = 0.f; }
+    }
+}
+
+// Channels 32*half + 8grp .. +7 of one tile.
+template <bool kSummary>
+__device__ __forceinline__ void gate_half_products(unsigned char *buf, int tile, int row, int grp, int half, const HalfRow &in,
+                                                   floatx4_t &acc)
+{
+    const float (&q)[8] = in.q;
+    const float (&k)[8] = in.k;
+    float a[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) a[j] = __expf(in.la[j]);           // exp(-inf) = 0
     const bool b0 = row & 1, b1 = row & 2, b2 = row & 4, b3 = row & 8;
     const floatx4_t zero = {0.f, 0.f, 0.f, 0.f};
     if (!kSummary) {
         // undecayed diagonal: a token sees its own write with weight one
-        const floatx4_t d = mfma_k32(__builtin_bit_cast(bf16x8_t, in.k[kHalf]), __builtin_bit_cast(bf16x8_t, in.q[kHalf]), zero);
+        const floatx4_t d = mfma_k32(pack8(k), pack8(q), zero);
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc[r] += (4 * grp + r == row) ? d[r] : 0.f;
     }
@@ -321,17 +357,86 @@ __device__ __forceinline__ void gate_half_products(unsigned char *buf, int tile,
 #pragma unroll
         for (int c = 0; c < 8; ++c) x[c] = q[c] * pre[c];                      // q .* A
         unsigned char *qn = buf + kOffQn + tile * kQnTile + row * 128;
-        *reinterpret_cast<bf16x8_t *>(qn + (((4 * kHalf + grp) ^ (row & 7)) << 4)) = pack8(x);
+        *reinterpret_cast<bf16x8_t *>(qn + (((4 * half + grp) ^ (row & 7)) << 4)) = pack8(x);
     }
     {
-        // k .* G, channels 32*kHalf + 8grp .. +7 of token `row`: two 8-byte units
+        // k .* G, channels 32*half + 8grp .. +7 of token `row`: two 8-byte units
         unsigned char *kt = buf + kOffKt + tile * kKtTile + row * 128;
 #pragma unroll
         for (int par = 0; par < 2; ++par) {
             const int e = 4 * par;
             const uint2 w = {pack_bf16x2(k[e] * suf[e], k[e + 1] * suf[e + 1]), pack_bf16x2(k[e + 2] * suf[e + 2], k[e + 3] * suf[e + 3])};
-            *reinterpret_cast<uint2 *>(kt + (lds_key_unit(kHalf, par, grp, row) << 3)) = w;
+            *reinterpret_cast<uint2 *>(kt + (lds_key_unit(half, par, grp, row) << 3)) = w;
         }
+    }
+    if (row == 15) {              // decay of the whole tile
+        float *gm = reinterpret_cast<float *>(buf + kOffGm + tile * kGmTile);
+        floatx4_t lo = {pre[0], pre[1], pre[2], pre[3]};
+        floatx4_t hi = {pre[4], pre[5], pre[6], pre[7]};
+        *reinterpret_cast<floatx4_t *>(gm + 32 * half + 8 * grp) = lo;
+        *reinterpret_cast<floatx4_t *>(gm + 32 * half + 8 * grp + 4) = hi;
+    }
+}
+
+// One 16-row tile, one half of the lane's channels (8 channels = the 8 operand slots of one MFMA) at a time: the register
+// budget of a wavefront does not hold the unpacked copies of all 16.  The prefix products A_t of the gates are needed in
+// any case.  When the total decay A_16 of these channels is far from underflow (the common case), the pairwise decay inside
+// the tile is taken as the quotient A_t / A_i of the appendix's parallel form: one version of q (q .* A, which is also the
+// inter-tile operand) and one of k (k ./ A), a single masked Gram matrix, and G_i = A_16 / A_i.  Otherwise (a hard reset or
+// a very strong decay inside the tile, where 1 / A_i would overflow or divide by zero) these channels take the
+// product-only construction above.  The scores are a sum over channels, so the choice is made per half; it is
+// wavefront-uniform.  `d` collects the scores [key row 4grp + r][query row `row`] of both halves.
+constexpr float kSafeTileDecay = 8.2718061e-25f;     // 2^-80: 1 / A_i stays below 2^80, far inside bf16 and fp32 range
+
+template <bool kSummary, bool kGated, int kHalf>
+__device__ __forceinline__ void gate_half_tile(unsigned char *buf, int tile, int row, int grp, const GateLoads &in, bool valid,
+                                               float inv_norm, floatx4_t &d)
+{
+    HalfRow r;
+    prepare_half_row<kSummary, kGated, kHalf>(in, valid, inv_norm, r);
+    float pre[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) pre[c] = __expf(r.la[c]);           // exp(-inf) = 0
+    // prefix products A_t over the 16 rows: four doubling steps of DPP row shifts with the identity shifted in
+#pragma unroll
+    for (int c = 0; c < 8; ++c) pre[c] *= row_shift_right<1>(pre[c], 1.f);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) pre[c] *= row_shift_right<2>(pre[c], 1.f);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) pre[c] *= row_shift_right<4>(pre[c], 1.f);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) pre[c] *= row_shift_right<8>(pre[c], 1.f);
+    // the total decay A_16 is row 15's prefix product: that lane decides for its channels
+    bool weak = true;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) weak = weak && (pre[c] >= kSafeTileDecay);        // false for 0 and NaN as well
+    if (__any(row == 15 && !weak)) {
+        gate_half_products<kSummary>(buf, tile, row, grp, kHalf, r, d);
+        return;
+    }
+
+    float total[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        r.k[c] *= __builtin_amdgcn_rcpf(pre[c]);                                   // k ./ A
+        total[c] = swizzle_lane<0x10, 0x0f>(pre[c]);                               // A_16 (row 15 of the tile)
+    }
+    if (!kSummary) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) r.q[c] *= pre[c];                              // q .* A
+        const bf16x8_t qa = pack8(r.q);
+        d = mfma_k32(pack8(r.k), qa, d);
+        unsigned char *qn = buf + kOffQn + tile * kQnTile + row * 128;
+        *reinterpret_cast<bf16x8_t *>(qn + (((4 * kHalf + grp) ^ (row & 7)) << 4)) = qa;
+    }
+    // k .* G with G_i = A_16 / A_i; same LDS placement as in gate_half_products
+    unsigned char *kt = buf + kOffKt + tile * kKtTile + row * 128;
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+        const int c = 4 * par;
+        const uint2 w = {pack_bf16x2(r.k[c] * total[c], r.k[c + 1] * total[c + 1]),
+                         pack_bf16x2(r.k[c + 2] * total[c + 2], r.k[c + 3] * total[c + 3])};
+        *reinterpret_cast<uint2 *>(kt + (lds_key_unit(kHalf, par, grp, row) << 3)) = w;
     }
     if (row == 15) {              // decay of the whole tile
         float *gm = reinterpret_cast<float *>(buf + kOffGm + tile * kGmTile);
@@ -342,147 +447,32 @@ __device__ __forceinline__ void gate_half_products(unsigned char *buf, int tile,
     }
 }
 
-template <bool kSummary>
-__device__ __forceinline__ void gate_tile_products(unsigned char *buf, int tile, int row, int grp, const GateLoads &in)
+template <bool kSummary, bool kGated>
+__device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row, int grp, const GateLoads &in, bool valid)
 {
-    floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
-    gate_half_products<kSummary, 0>(buf, tile, row, grp, in, acc);
-    gate_half_products<kSummary, 1>(buf, tile, row, grp, in, acc);
+    float inv_norm = 1.f;
+    if (kGated) {
+        // squared norm of the raw key row: this lane's 16 channels, then the four lanes that share the row
+        float kf[16];
+        unpack_bf16x8(in.k[0], kf);
+        unpack_bf16x8(in.k[1], kf + 8);
+        float ss = 0.f;
+#pragma unroll
+        for (int c = 0; c < 16; ++c) ss = fmaf(kf[c], kf[c], ss);
+        ss += __shfl_xor(ss, 16);
+        ss += __shfl_xor(ss, 32);
+        inv_norm = inverse_key_norm(ss);
+    }
+    floatx4_t d = {0.f, 0.f, 0.f, 0.f};
+    gate_half_tile<kSummary, kGated, 0>(buf, tile, row, grp, in, valid, inv_norm, d);
+    gate_half_tile<kSummary, kGated, 1>(buf, tile, row, grp, in, valid, inv_norm, d);
     if (!kSummary) {
-        // P[t = row][i = 4grp .. 4grp+3]
-        uint2 w = {pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3])};
-        *reinterpret_cast<uint2 *>(buf + kOffPd + tile * kPdTile + row * 32 + grp * 8) = w;
-    }
-}
-
-// One 16-row tile.  The prefix products A_t of the gates are needed in any case.  When the tile's total decay A_16
-// is far from underflow in every channel (the common case), the pairwise decay inside the tile is taken as the
-// quotient A_t / A_i of the appendix's parallel form: one version of q (q .* A, which is also the inter-tile
-// operand) and one of k (k ./ A), a single masked Gram matrix, and G_i = A_16 / A_i.  Otherwise (a hard reset or
-// a very strong decay inside the tile, where 1 / A_i would overflow or divide by zero) the tile falls back to the
-// product-only construction above.  The choice is per tile and wavefront-uniform.
-constexpr float kSafeTileDecay = 8.2718061e-25f;     // 2^-80: 1 / A_i stays below 2^80, far inside bf16 and fp32 range
-
-// kShiftPrefix picks one of two instruction sequences for the prefix products A_t (same values up to rounding order):
-// four doubling steps of DPP row shifts with the identity shifted in (no selects, no LDS-pipe swizzles), or products
-// inside blocks of 2, 4, 8, 16 rows.  Measured on the layer workload, same box: the shifts are 1.6 % faster in the
-// fp32-beta kernel (224.3 -> 220.7 us) and 1.7 .. 2 % slower in the z_beta and gated kernels (200.6 -> 204.2, 283 -> 289 us),
-// so each instance takes the one that is faster for it.
-template <bool kSummary, bool kGated, bool kShiftPrefix>
-__device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row, int grp, GateLoads &in, bool valid)
-{
-    if (kGated) gate_activate<kSummary>(in);
-    if (kSummary) { const uint4 z = {0u, 0u, 0u, 0u}; in.q[0] = in.q[1] = z; }
-    gate_mask_padding(valid, in);
-
-    float pre[16];
-#pragma unroll
-    for (int m = 0; m < 2; ++m)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            pre[8 * m + j] = __expf(in.la[2 * m][j]);           // exp(-inf) = 0
-            pre[8 * m + 4 + j] = __expf(in.la[2 * m + 1][j]);
-        }
-    if (kShiftPrefix) {
-#pragma unroll
-        for (int c = 0; c < 16; ++c) pre[c] *= row_shift_right<1>(pre[c], 1.f);
-#pragma unroll
-        for (int c = 0; c < 16; ++c) pre[c] *= row_shift_right<2>(pre[c], 1.f);
-#pragma unroll
-        for (int c = 0; c < 16; ++c) pre[c] *= row_shift_right<4>(pre[c], 1.f);
-#pragma unroll
-        for (int c = 0; c < 16; ++c) pre[c] *= row_shift_right<8>(pre[c], 1.f);      // A_t
-    } else {
-        const bool b0 = row & 1, b1 = row & 2, b2 = row & 4, b3 = row & 8;
-        // prefix products inside blocks of 2, 4, 8, 16 rows
-#pragma unroll
-        for (int c = 0; c < 16; ++c) {
-            const float x = pre[c] * dpp_any<QP(0, 0, 2, 2)>(pre[c]);
-            pre[c] = b0 ? x : pre[c];
-        }
-#pragma unroll
-        for (int c = 0; c < 16; ++c) {
-            const float x = pre[c] * dpp_any<QP(1, 1, 1, 1)>(pre[c]);
-            pre[c] = b1 ? x : pre[c];
-        }
-        float t[16];
-#pragma unroll
-        for (int c = 0; c < 16; ++c) t[c] = swizzle_lane<0x18, 0x03>(pre[c]);
-#pragma unroll
-        for (int c = 0; c < 16; ++c) pre[c] = b2 ? pre[c] * t[c] : pre[c];
-#pragma unroll
-        for (int c = 0; c < 16; ++c) t[c] = swizzle_lane<0x10, 0x07>(pre[c]);
-#pragma unroll
-        for (int c = 0; c < 16; ++c) pre[c] = b3 ? pre[c] * t[c] : pre[c];      // A_t
-    }
-    float total[16];
-#pragma unroll
-    for (int c = 0; c < 16; ++c) total[c] = swizzle_lane<0x10, 0x0f>(pre[c]);    // A_16 (row 15 of the tile)
-
-    bool weak = true;
-#pragma unroll
-    for (int c = 0; c < 16; ++c) weak = weak && (total[c] >= kSafeTileDecay);     // false for 0 and NaN as well
-    if (__any(!weak)) {
-        gate_tile_products<kSummary>(buf, tile, row, grp, in);
-        return;
-    }
-
-    float k[16];
-#pragma unroll
-    for (int m = 0; m < 2; ++m) {
-        const uint32_t kw[4] = {in.k[m].x, in.k[m].y, in.k[m].z, in.k[m].w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            k[8 * m + 2 * j] = bf16_lo(kw[j]) * __builtin_amdgcn_rcpf(pre[8 * m + 2 * j]);           // k ./ A
-            k[8 * m + 2 * j + 1] = bf16_hi(kw[j]) * __builtin_amdgcn_rcpf(pre[8 * m + 2 * j + 1]);
-        }
-    }
-    if (!kSummary) {
-        float q[16];
-#pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            const uint32_t qw[4] = {in.q[m].x, in.q[m].y, in.q[m].z, in.q[m].w};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                q[8 * m + 2 * j] = bf16_lo(qw[j]) * pre[8 * m + 2 * j];                               // q .* A
-                q[8 * m + 2 * j + 1] = bf16_hi(qw[j]) * pre[8 * m + 2 * j + 1];
-            }
-        }
-        const bf16x8_t qa0 = pack8(q), qa1 = pack8(q + 8);
-        floatx4_t d = {0.f, 0.f, 0.f, 0.f};
-        d = mfma_k32(pack8(k), qa0, d);
-        d = mfma_k32(pack8(k + 8), qa1, d);
-        unsigned char *qn = buf + kOffQn + tile * kQnTile + row * 128;
-        *reinterpret_cast<bf16x8_t *>(qn + (((0 + grp) ^ (row & 7)) << 4)) = qa0;
-        *reinterpret_cast<bf16x8_t *>(qn + (((4 + grp) ^ (row & 7)) << 4)) = qa1;
-        // P[t = row][i = 4grp .. 4grp+3], keys up to and including the query row
+        // P[t = row][i = 4grp .. 4grp+3], keys up to and including the query row (the product-only construction adds nothing
+        // beyond the diagonal, the quotient form does)
         const int i0 = 4 * grp;
         uint2 w = {pack_bf16x2(i0 <= row ? d[0] : 0.f, i0 + 1 <= row ? d[1] : 0.f),
                    pack_bf16x2(i0 + 2 <= row ? d[2] : 0.f, i0 + 3 <= row ? d[3] : 0.f)};
         *reinterpret_cast<uint2 *>(buf + kOffPd + tile * kPdTile + row * 32 + grp * 8) = w;
-    }
-    {
-        // k .* G with G_i = A_16 / A_i; same LDS placement as in gate_half_products
-        unsigned char *kt = buf + kOffKt + tile * kKtTile + row * 128;
-#pragma unroll
-        for (int m = 0; m < 2; ++m)
-#pragma unroll
-            for (int par = 0; par < 2; ++par) {
-                const int c = 8 * m + 4 * par;
-                const uint2 w = {pack_bf16x2(k[c] * total[c], k[c + 1] * total[c + 1]),
-                                 pack_bf16x2(k[c + 2] * total[c + 2], k[c + 3] * total[c + 3])};
-                *reinterpret_cast<uint2 *>(kt + (lds_key_unit(m, par, grp, row) << 3)) = w;
-            }
-    }
-    if (row == 15) {              // decay of the whole tile
-        float *gm = reinterpret_cast<float *>(buf + kOffGm + tile * kGmTile);
-#pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            floatx4_t lo = {pre[8 * m], pre[8 * m + 1], pre[8 * m + 2], pre[8 * m + 3]};
-            floatx4_t hi = {pre[8 * m + 4], pre[8 * m + 5], pre[8 * m + 6], pre[8 * m + 7]};
-            *reinterpret_cast<floatx4_t *>(gm + 32 * m + 8 * grp) = lo;
-            *reinterpret_cast<floatx4_t *>(gm + 32 * m + 8 * grp + 4) = hi;
-        }
     }
 }
 
@@ -492,8 +482,8 @@ __device__ __forceinline__ void gate_tile(unsigned char *buf, int tile, int row,
 // State wavefront `w` fetches tile w of every chunk for ALL 128 columns of the workgroup (whole 256-byte rows of v,
 // 512-byte rows of beta: long contiguous pieces are what HBM delivers at full rate) and stages beta .* v for
 // the four state wavefronts.  Lane = (row 4u + lane/16 for u = 0..3, columns 8(lane%16) .. +7).
-// The value gate arrives as fp32 values (kZBeta = false; `has_beta` false: all ones) or as bf16 pre-activations
-// whose sigmoid is taken here (kZBeta = true; half the bytes, two transcendentals per element).
+// The value gate arrives as fp32 values, as bf16 pre-activations whose sigmoid is taken here (half the bytes, two
+// transcendentals per element), or not at all (all ones).
 // v, the value gate and o are touched exactly once by exactly one workgroup: their loads and stores are marked
 // non-temporal so that they do not displace q, k and log_alpha, which the workgroups of the other column tiles of
 // the same (batch, head) read again from the cache.
@@ -508,28 +498,32 @@ struct StateLoads {
     uint4 zbeta[4];
 };
 
-template <bool kZBeta>
-__device__ __forceinline__ void state_prefetch(const Geometry &g, int s, int tile, int lane, bool has_beta, StateLoads &p)
+template <int kBeta>
+__device__ __forceinline__ void state_prefetch(const Geometry &g, int s, int tile, int lane, StateLoads &p)
 {
     const int rsub = lane >> 4, piece = lane & 15;
+    const ChunkRows c = chunk_rows(g, s);
+    const size_t first = c.first * g.dv + g.j0;              // element index of the chunk's first row, this column tile
+    const bf16_t *vb = g.v + first;
+    const uint32_t row_bytes = (uint32_t)(g.H * g.dv * 2);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-        const int t = min(s + 16 * tile + 4 * u + rsub, g.t_end - 1);   // clamped: padded rows are zeroed in stage_values
-        const size_t off = ((g.tok0 + t) * g.H + g.h) * g.dv + g.j0 + 8 * piece;
-        p.v[u] = load_streaming(g.v + off);
-        if (kZBeta) {
-            p.zbeta[u] = load_streaming(static_cast<const bf16_t *>(g.beta) + off);
-        } else if (has_beta) {
-            p.beta[u][0] = __builtin_nontemporal_load(reinterpret_cast<const floatx4_t *>(static_cast<const float *>(g.beta) + off));
-            p.beta[u][1] = __builtin_nontemporal_load(reinterpret_cast<const floatx4_t *>(static_cast<const float *>(g.beta) + off + 4));
+        const uint32_t off = row_in_chunk(g, c, s, 16 * tile + 4 * u + rsub) * row_bytes + 16u * piece;    // bytes, bf16 tensors
+        p.v[u] = load_streaming_at(vb, off);
+        if (kBeta == kBetaPreact) {
+            p.zbeta[u] = load_streaming_at(static_cast<const bf16_t *>(g.beta) + first, off);
+        } else if (kBeta == kBetaValues) {
+            const float *bb = static_cast<const float *>(g.beta) + first;
+            p.beta[u][0] = __builtin_bit_cast(floatx4_t, load_streaming_at(bb, 2 * off));
+            p.beta[u][1] = __builtin_bit_cast(floatx4_t, load_streaming_at(bb, 2 * off + 16));
         }
     }
 }
 
 // beta .* v of one tile, rounded to bf16, into the chunk buffer `vt` (token-major, see lds_value_unit).  The lane's
 // 8 columns 8*piece .. +7 are the units (slab = piece/4, c = piece%4, ct = 0 and 1) of its token row.
-template <bool kZBeta>
-__device__ __forceinline__ void stage_values(unsigned char *vt, int tile, int lane, bool has_beta, const StateLoads &p, int s, int t_end)
+template <int kBeta>
+__device__ __forceinline__ void stage_values(unsigned char *vt, int tile, int lane, const StateLoads &p, int s, int t_end)
 {
     const int rsub = lane >> 4, piece = lane & 15;
 #pragma unroll
@@ -543,14 +537,14 @@ __device__ __forceinline__ void stage_values(unsigned char *vt, int tile, int la
             gv[2 * j] = bf16_lo(w[j]);
             gv[2 * j + 1] = bf16_hi(w[j]);
         }
-        if (kZBeta) {
+        if (kBeta == kBetaPreact) {
             const uint32_t z[4] = {p.zbeta[u].x, p.zbeta[u].y, p.zbeta[u].z, p.zbeta[u].w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 gv[2 * j] *= sigmoid_short(bf16_lo(z[j]));
                 gv[2 * j + 1] *= sigmoid_short(bf16_hi(z[j]));
             }
-        } else if (has_beta) {
+        } else if (kBeta == kBetaValues) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 gv[j] *= p.beta[u][0][j];
@@ -566,19 +560,83 @@ __device__ __forceinline__ void stage_values(unsigned char *vt, int tile, int la
     }
 }
 
-// Outputs of a finished chunk: LDS -> global, whole 256-byte rows.  Done by the gate wavefronts (they have slack),
-// wavefront w taking rows 16w .. 16w+15.
+// Outputs of a finished chunk: LDS -> global, whole 256-byte rows.  Done by the value wavefronts, wavefront w taking
+// rows 16w .. 16w+15; lane = (row 4u + lane/16 for u = 0..3, columns 8(lane%16) .. +7).
+__device__ __forceinline__ void store_row(const Geometry &g, int s, int row, int unit, uint4 w)
+{
+    // chunk start s <= t_end - 1 here (the chunk exists); rows at or beyond the end are not stored
+    bf16_t *ob = g.o + ((g.tok0 + (size_t)s) * g.H + g.h) * g.dv + g.j0;
+    const uint32_t off = (uint32_t)row * (uint32_t)(g.H * g.dv * 2) + 16u * unit;
+    if (s + row < g.t_end) store_streaming_at(ob, off, w);
+}
+
 __device__ __forceinline__ void store_outputs(const Geometry &g, const unsigned char *ob, int s, int wave, int lane)
 {
+    asm volatile("" : "+v"(lane));       // offsets recomputed per chunk: hoisted out of the loop they would cost ten registers
     const int rsub = lane >> 4, unit = lane & 15;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int row = 16 * wave + 4 * u + rsub;
         const uint4 w = *reinterpret_cast<const uint4 *>(ob + row * 256 + ((unit ^ (row & 15)) << 4));
-        const int t = s + row;
-        if (t < g.t_end)
-            __builtin_nontemporal_store(__builtin_bit_cast(floatx4_t, w),
-                                        reinterpret_cast<floatx4_t *>(g.o + ((g.tok0 + t) * g.H + g.h) * g.dv + g.j0 + 8 * unit));
+        store_row(g, s, row, unit, w);
+    }
+}
+
+// Output stage of the block (Sec. 3.1.3: y = (o + d .* x') .* act(z)), applied where the outputs leave LDS.  The rows of x'
+// and z that belong to a chunk are requested one iteration before that chunk is stored.
+struct StageLoads {
+    uint4 x[4], z[4];
+};
+
+template <int kStage>
+__device__ __forceinline__ void stage_prefetch(const Geometry &g, int s, int t_begin, int wave, int lane, StageLoads &p)
+{
+    const int rsub = lane >> 4, unit = lane & 15;
+    s = max(s, t_begin);                                     // the first iteration asks for the chunk before the segment
+    const ChunkRows c = chunk_rows(g, s);
+    const size_t first = c.first * g.dv + g.j0;
+    const uint32_t row_bytes = (uint32_t)(g.H * g.dv * 2);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const uint32_t off = row_in_chunk(g, c, s, 16 * wave + 4 * u + rsub) * row_bytes + 16u * unit;
+        if (kStage & kStageFeed) p.x[u] = load_streaming_at(g.x_prime + first, off);
+        if (kStage & kStageGate) p.z[u] = load_streaming_at(g.z_gate + first, off);
+    }
+}
+
+// fp32 outputs of a finished chunk from LDS (512-byte rows, 32-byte units swizzled by row), the stage in fp32, one
+// rounding to bf16, whole 256-byte rows to global memory.  feed: the 128 feed-through weights of this column tile in LDS.
+template <int kStage>
+__device__ __forceinline__ void store_outputs_block(const Geometry &g, const unsigned char *ob, int s, int wave, int lane,
+                                                    const StageLoads &p, const unsigned char *feed)
+{
+    const int rsub = lane >> 4, unit = lane & 15;
+    float d8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (kStage & kStageFeed) {
+        const floatx4_t lo = *reinterpret_cast<const floatx4_t *>(feed + 32 * unit), hi = *reinterpret_cast<const floatx4_t *>(feed + 32 * unit + 16);
+        d8[0] = lo[0]; d8[1] = lo[1]; d8[2] = lo[2]; d8[3] = lo[3]; d8[4] = hi[0]; d8[5] = hi[1]; d8[6] = hi[2]; d8[7] = hi[3];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int row = 16 * wave + 4 * u + rsub;
+        const unsigned char *src = ob + row * 512 + ((unit ^ (row & 15)) << 5);
+        const floatx4_t lo = *reinterpret_cast<const floatx4_t *>(src), hi = *reinterpret_cast<const floatx4_t *>(src + 16);
+        float y[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        if (kStage & kStageFeed) {
+            float x[8];
+            unpack_bf16x8(p.x[u], x);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) y[j] = fmaf(d8[j], x[j], y[j]);
+        }
+        if (kStage & kStageGate) {
+            float z[8];
+            unpack_bf16x8(p.z[u], z);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) y[j] *= output_gate(z[j], g.act);
+        }
+        const uint4 w = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7])};
+        store_row(g, s, row, unit, w);
+        __builtin_amdgcn_sched_barrier(0);       // one row group at a time: interleaving all four does not fit the registers
     }
 }
 
@@ -610,7 +668,6 @@ struct TileOperands {       // what one tile of the state recurrence reads from 
     bf16x8_t qb[2];         // rows of q .* A
     uint2 pb;               // row of P
     uint2 va[2], ka[4];     // (beta .* v)^T and (k .* G)^T
-    floatx4_t dec[4];       // A_16 for this lane's state rows
 };
 
 template <bool kSummary>
@@ -628,17 +685,14 @@ __device__ __forceinline__ void load_tile_operands(const unsigned char *buf, con
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct)
         op.va[ct] = lds_read_transposed(vt + (16 * tile + r) * 256 + (lds_value_unit(slab, ct, c, r) << 3));
-    const float *gm = reinterpret_cast<const float *>(buf + kOffGm + tile * kGmTile);
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt) {
+    for (int kt = 0; kt < 4; ++kt)
         op.ka[kt] = lds_read_transposed(buf + kOffKt + tile * kKtTile + r * 128 + (lds_key_unit(kt >> 1, kt & 1, c, r) << 3));
-        op.dec[kt] = *reinterpret_cast<const floatx4_t *>(gm + slab_channel(kt, 4 * grp));
-    }
 }
 
 // One chunk (4 tiles) of the state recurrence and the outputs for this wavefront's 32 columns.  The LDS operands
 // of tile i+1 are requested before tile i is computed.
-template <bool kSummary>
+template <bool kSummary, bool kBlock>
 __device__ __forceinline__ void state_chunk(const unsigned char *buf, const unsigned char *vt, unsigned char *ob,
                                             int slab, int n, int grp, StateSlab &st, floatx4_t (&decay)[4])
 {
@@ -648,6 +702,12 @@ __device__ __forceinline__ void state_chunk(const unsigned char *buf, const unsi
     for (int tile = 0; tile < 4; ++tile) {
         if (tile + 1 < 4) load_tile_operands<kSummary>(buf, vt, tile + 1, slab, n, grp, ops[(tile + 1) & 1]);
         const TileOperands &op = ops[tile & 1];
+        // the tile's decay A_16 for this lane's state rows: wanted only after the output products, so it is fetched here
+        // rather than a tile ahead with the rest (16 registers)
+        floatx4_t dec[4];
+        const float *gm = reinterpret_cast<const float *>(buf + kOffGm + tile * kGmTile);
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt) dec[kt] = *reinterpret_cast<const floatx4_t *>(gm + slab_channel(kt, 4 * grp));
 
         // o^T[column][t] = S^T (q .* A)^T + (beta .* v)^T P^T
         floatx4_t O[2];
@@ -662,7 +722,7 @@ __device__ __forceinline__ void state_chunk(const unsigned char *buf, const unsi
         } else {
             // summary pass: only the segment's decay and state increment are wanted
 #pragma unroll
-            for (int kt = 0; kt < 4; ++kt) decay[kt] *= op.dec[kt];
+            for (int kt = 0; kt < 4; ++kt) decay[kt] *= dec[kt];
         }
         // S = diag(A_16) S + (k .* G)^T (beta .* v)
 #pragma unroll
@@ -670,15 +730,22 @@ __device__ __forceinline__ void state_chunk(const unsigned char *buf, const unsi
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct) {
                 floatx4_t x = st.S[kt][ct];
-                x[0] *= op.dec[kt][0]; x[1] *= op.dec[kt][1]; x[2] *= op.dec[kt][2]; x[3] *= op.dec[kt][3];
+                x[0] *= dec[kt][0]; x[1] *= dec[kt][1]; x[2] *= dec[kt][2]; x[3] *= dec[kt][3];
                 st.S[kt][ct] = mfma_k16(op.ka[kt], op.va[ct], x);
             }
         }
         if (!kSummary) {
             // row 16tile + n of the chunk's output buffer, columns 32slab + 8grp .. +7 (16-byte unit 4slab + grp)
-            uint4 w = {pack_bf16x2(O[0][0], O[0][1]), pack_bf16x2(O[0][2], O[0][3]),
-                       pack_bf16x2(O[1][0], O[1][1]), pack_bf16x2(O[1][2], O[1][3])};
-            *reinterpret_cast<uint4 *>(ob + (16 * tile + n) * 256 + (((4 * slab + grp) ^ n) << 4)) = w;
+            if (kBlock) {
+                // fp32, 32-byte unit 4slab + grp of the row: the output stage and the rounding follow where the row leaves LDS
+                unsigned char *dst = ob + (16 * tile + n) * 512 + (((4 * slab + grp) ^ n) << 5);
+                *reinterpret_cast<floatx4_t *>(dst) = O[0];
+                *reinterpret_cast<floatx4_t *>(dst + 16) = O[1];
+            } else {
+                uint4 w = {pack_bf16x2(O[0][0], O[0][1]), pack_bf16x2(O[0][2], O[0][3]),
+                           pack_bf16x2(O[1][0], O[1][1]), pack_bf16x2(O[1][2], O[1][3])};
+                *reinterpret_cast<uint4 *>(ob + (16 * tile + n) * 256 + (((4 * slab + grp) ^ n) << 4)) = w;
+            }
             refresh_operands(st);
         }
     }
@@ -697,22 +764,24 @@ struct SegmentPlan {
 // kSummary = false: the scan proper over this workgroup's segment (blockIdx.z), reading its entering state.
 // kSummary = true : same walk from a zero state without q, scores or outputs; leaves the segment's state
 //                   increment in slot seg+1 and the segment's total decay in gamma[seg].
-// kZBeta: `beta` holds bf16 pre-activations of the value gate instead of fp32 gate values (and is not NULL).
+// kBeta: what `beta` holds: nothing (NULL, all ones), fp32 gate values, or bf16 pre-activations of the value gate.
 // kGated: `log_alpha` holds the bf16 pre-activations z_g and `z_tau` those of the temperature gate; q and k are raw.
-template <bool kSummary, bool kZBeta, bool kGated>
+// kStage: the parts of the block's output stage (`stage`) applied to the outputs on their way from LDS to global memory.
+template <bool kSummary, int kBeta, bool kGated, int kStage>
 __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const void *__restrict__ log_alpha, const bf16_t *__restrict__ z_tau, const void *__restrict__ beta, const float *S0,
     bf16_t *__restrict__ o, float *S_T, int T, int H, int dv, SegmentPlan plan, const int *__restrict__ cu_seqlens,
-    int total_tokens, int total_seqs)
+    int total_tokens, int total_seqs, OutputStage stage)
 {
     extern __shared__ __align__(16) unsigned char lds[];
+    constexpr bool kBlock = kStage != 0;
+    constexpr int kObBuf = ob_buf_bytes(kBlock);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, grp = lane >> 4;
     int bh = blockIdx.x, col_tile = blockIdx.y;
     const int seg = blockIdx.z;
     const int BH = gridDim.x;
-    const bool has_beta = beta != nullptr;
     if (!kSummary && cu_seqlens == nullptr && gridDim.y == 1 && gridDim.z == 1 && dv > kColTile) {
         // Dense batch with more workgroups than compute units, launched flat: workgroups go round-robin over the eight XCDs
         // (each with its own L2), so in every run of 8 * col_tiles workgroups the column tiles of a (batch, head) are 8
@@ -730,7 +799,7 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
         col_tile = blockIdx.x % col_tiles;
         const int slot = blockIdx.x / col_tiles, rank = slot / H;
         const int b = sequence_by_length_rank(cu_seqlens, nseq, total_tokens, rank, reinterpret_cast<int *>(lds));   // the dynamic LDS is free until the walk starts
-        bh = b * H + slot % H;
+        bh = __builtin_amdgcn_readfirstlane(b * H + slot % H);      // the same in every lane: keeps the row bases in scalar registers
     }
 
     Geometry g;
@@ -738,6 +807,9 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
     g.la = kGated ? nullptr : static_cast<const float *>(log_alpha);
     g.zg = kGated ? static_cast<const bf16_t *>(log_alpha) : nullptr;
     g.zt = z_tau;
+    g.x_prime = (kStage & kStageFeed) ? static_cast<const bf16_t *>(stage.x_prime) : nullptr;
+    g.z_gate = (kStage & kStageGate) ? static_cast<const bf16_t *>(stage.z_gate) : nullptr;
+    g.d = stage.d; g.act = stage.act;
     g.H = H; g.dv = dv;
     g.h = bh % H; g.j0 = col_tile * kColTile;
     g.tok0 = (size_t)(bh / H) * T;
@@ -755,45 +827,40 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
     const int nchunks = (g.t_end - t_begin + kChunk - 1) / kChunk;
     const size_t slot_elems = (size_t)BH * kK * dv;
 
+    // Every role runs nchunks + 2 iterations with one barrier each.  Iteration `it`: the gate wavefronts build chunk `it`,
+    // the value wavefronts stage the values of chunk `it` and store the outputs of chunk it-2, the state wavefronts
+    // advance the recurrence over chunk it-1.
+    // The three wavefronts of a SIMD compete for its issue slots; the ones with the least slack go first.
     if (wave < 4) {
         // ------------------------------------------------------------------ gate wavefront, tile = wave
-        constexpr bool kShiftPrefix = !kSummary && !kZBeta && !kGated;      // see gate_tile
-        GateLoads even, odd;      // loads of even / odd chunks: no register copies between iterations
-        const int row0 = t_begin + 16 * wave + n;
-        if (nchunks > 0) gate_prefetch<kSummary, kGated>(g, row0, grp, even);
-        // Iteration `it`: store the outputs of chunk it-2 (finished by the state wavefronts in iteration it-1), then
-        // build chunk it.  nchunks + 2 iterations, one barrier each, for both kinds of wavefront.
+        __builtin_amdgcn_s_setprio(PRIO_GATE);
+        GateLoads even, odd;      // loads of even / odd chunks, requested one chunk ahead: no register copies between iterations
+        const int row = 16 * wave + n;             // this lane's row of every chunk
+        if (nchunks > 0) gate_prefetch<kSummary, kGated>(g, t_begin, row, grp, even);
         for (int it = 0;;) {
-            unsigned long long t0 = PROF_T();
-            if (!kSummary && it >= 2) store_outputs(g, lds + kOffOb, t_begin + (it - 2) * kChunk, wave, lane);
             if (it < nchunks) {
-                gate_prefetch<kSummary, kGated>(g, row0 + (it + 1) * kChunk, grp, odd);   // unconditional (clamped): keeps the wait counts exact
-                gate_tile<kSummary, kGated, kShiftPrefix>(lds, wave, n, grp, even, row0 + it * kChunk < g.t_end);
+                const int s = t_begin + it * kChunk;
+                gate_prefetch<kSummary, kGated>(g, s + kChunk, row, grp, odd);     // unconditional (clamped): keeps the wait counts exact
+                gate_tile<kSummary, kGated>(lds, wave, n, grp, even, s + row < g.t_end);
             }
-            PROF_ADD(wave * 2, t0);
-            t0 = PROF_T();
             __syncthreads();
-            PROF_ADD(wave * 2 + 1, t0);
             if (++it > nchunks + 1) break;
-            t0 = PROF_T();
-            if (!kSummary && it >= 2) store_outputs(g, lds + kOffOb + kObBuf, t_begin + (it - 2) * kChunk, wave, lane);
             if (it < nchunks) {
-                gate_prefetch<kSummary, kGated>(g, row0 + (it + 1) * kChunk, grp, even);
-                gate_tile<kSummary, kGated, kShiftPrefix>(lds + kBufBytes, wave, n, grp, odd, row0 + it * kChunk < g.t_end);
+                const int s = t_begin + it * kChunk;
+                gate_prefetch<kSummary, kGated>(g, s + kChunk, row, grp, even);
+                gate_tile<kSummary, kGated>(lds + kBufBytes, wave, n, grp, odd, s + row < g.t_end);
             }
-            PROF_ADD(wave * 2, t0);
-            t0 = PROF_T();
             __syncthreads();
-            PROF_ADD(wave * 2 + 1, t0);
             if (++it > nchunks + 1) break;
         }
-    } else {
+    } else if (wave < 8) {
         // ------------------------------------------------------------------ state wavefront, slab = wave - 4
         const int slab = wave - 4;
+        __builtin_amdgcn_s_setprio(PRIO_STATE);
         StateSlab st;
         const size_t state_base = (size_t)bh * kK * dv + g.j0 + 32 * slab;
         // entering state: zero (summary), the caller's S0 (no split), or this segment's workspace slot.  The state is read
-        // once here and written once at the end: streaming accesses (layer workload 225 -> 221 us, gated form 288 -> 277 us)
+        // once here and written once at the end: streaming accesses
         const float *S_in = kSummary ? nullptr : (plan.nseg > 1 ? plan.slots + seg * slot_elems : S0);
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
@@ -809,24 +876,14 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt) decay[kt] = floatx4_t{1.f, 1.f, 1.f, 1.f};
 
-        StateLoads pf;            // tile `slab` of the next chunk to stage, all 128 columns
-        if (nchunks > 0) state_prefetch<kZBeta>(g, t_begin, slab, lane, has_beta, pf);
         for (int it = 0; it <= nchunks + 1; ++it) {
-            unsigned long long t0 = PROF_T();
-            if (it >= 1 && it <= nchunks)      // chunk it-1: its values were staged at the end of the previous iteration
-                state_chunk<kSummary>(lds + ((it - 1) & 1) * kBufBytes, lds + kOffVt + ((it - 1) & 1) * kVtBuf,
-                                      lds + kOffOb + ((it - 1) & 1) * kObBuf, slab, n, grp, st, decay);
-            PROF_ADD(16 + slab * 3 + 1, t0);
-            t0 = PROF_T();
-            if (it < nchunks) {
-                // values of chunk `it` (requested one iteration ago) -> LDS, then request the next chunk's
-                stage_values<kZBeta>(lds + kOffVt + (it & 1) * kVtBuf, slab, lane, has_beta, pf, t_begin + it * kChunk, g.t_end);
-                state_prefetch<kZBeta>(g, t_begin + (it + 1) * kChunk, slab, lane, has_beta, pf);   // unconditional (clamped), see gate_prefetch
-            }
-            PROF_ADD(16 + slab * 3, t0);
-            t0 = PROF_T();
+            // outputs of chunk it-2 (finished in iteration it-1), rows 16 slab .. +15: these wavefronts wait for no loads, so the
+            // slow completion of the stores holds nothing up (memory operations of a wavefront retire in order)
+            if (!kSummary && !kBlock && it >= 2) store_outputs(g, lds + kOffOb + (it & 1) * kObBuf, t_begin + (it - 2) * kChunk, slab, lane);
+            if (it >= 1 && it <= nchunks)      // chunk it-1: built and staged by the other wavefronts in the previous iteration
+                state_chunk<kSummary, kBlock>(lds + ((it - 1) & 1) * kBufBytes, lds + kOffVt + ((it - 1) & 1) * kVtBuf,
+                                              lds + kOffOb + ((it - 1) & 1) * kObBuf, slab, n, grp, st, decay);
             __syncthreads();
-            PROF_ADD(16 + slab * 3 + 2, t0);
         }
 
         float *S_out = kSummary ? plan.slots + (size_t)(seg + 1) * slot_elems : (seg == plan.nseg - 1 ? S_T : nullptr);
@@ -843,6 +900,42 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
             float *gam = plan.gamma + ((size_t)seg * BH + bh) * kK;
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt) *reinterpret_cast<floatx4_t *>(gam + slab_channel(kt, 4 * grp)) = decay[kt];
+        }
+    } else {
+        // ------------------------------------------------------------------ value wavefront, tile = wave - 8
+        const int tile = wave - 8;
+        __builtin_amdgcn_s_setprio(PRIO_VALUE);
+        StateLoads pf;            // tile `tile` of the next chunk to stage, all 128 columns
+        StageLoads sl;            // kBlock: rows of x' and z for the next chunk to store
+        unsigned char *feed = lds + kOffOb + 2 * kObBuf;
+        if ((kStage & kStageFeed) && tile == 0 && lane < kColTile / 4)      // read back two or more barriers later
+            *reinterpret_cast<floatx4_t *>(feed + 16 * lane) = *reinterpret_cast<const floatx4_t *>(g.d + (size_t)g.h * dv + g.j0 + 4 * lane);
+        // Iteration `it`: stage the values of chunk `it`, store the outputs of chunk it-2 (finished by the state wavefronts in
+        // iteration it-1), then request the stage inputs of chunk it-1 and the values of chunk it+2 into the registers just
+        // freed.  Every request has most of an iteration to arrive.  Requests are unconditional (clamped rows).
+        auto iteration = [&](int it, StateLoads &cur) {
+            if (it < nchunks)
+                stage_values<kBeta>(lds + kOffVt + (it & 1) * kVtBuf, tile, lane, cur, t_begin + it * kChunk, g.t_end);
+            if (!kSummary && it >= 2) {
+                const unsigned char *ob = lds + kOffOb + (it & 1) * kObBuf;
+                if (kBlock) store_outputs_block<kStage>(g, ob, t_begin + (it - 2) * kChunk, tile, lane, sl, feed);
+
+            }
+            if (kBlock && !kSummary && nchunks > 0) stage_prefetch<kStage>(g, t_begin + (it - 1) * kChunk, t_begin, tile, lane, sl);
+            if (it < nchunks) state_prefetch<kBeta>(g, t_begin + (it + 2) * kChunk, tile, lane, cur);
+        };
+        StateLoads pf_odd;
+        if (nchunks > 0) {
+            state_prefetch<kBeta>(g, t_begin, tile, lane, pf);
+            state_prefetch<kBeta>(g, t_begin + kChunk, tile, lane, pf_odd);
+        }
+        for (int it = 0;;) {
+            iteration(it, pf);
+            __syncthreads();
+            if (++it > nchunks + 1) break;
+            iteration(it, pf_odd);
+            __syncthreads();
+            if (++it > nchunks + 1) break;
         }
     }
 }
@@ -890,34 +983,6 @@ SplitShape choose_split(int B, int T, int H, int dv)
     return sp;
 }
 
-// Output stage of the block applied to the stored outputs, in place: o <- (o + d .* x') .* act(z), 8 columns per thread.
-// The scan kernel itself has no registers left for two more input streams, so on this path the stage is a second,
-// bandwidth-bound kernel of the same call (the generic and the decode kernels apply it where they store o).
-__global__ __launch_bounds__(256) void output_stage_kernel(bf16_t *__restrict__ o, OutputStage stage, size_t pieces, int H, int dv)
-{
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= pieces) return;
-    const size_t e = i * 8;
-    const uint4 w = *reinterpret_cast<const uint4 *>(o + e);
-    float y[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y), bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
-    if (stage.x_prime != nullptr) {
-        const uint4 xw = load_streaming(static_cast<const bf16_t *>(stage.x_prime) + e);
-        const float x[8] = {bf16_lo(xw.x), bf16_hi(xw.x), bf16_lo(xw.y), bf16_hi(xw.y), bf16_lo(xw.z), bf16_hi(xw.z), bf16_lo(xw.w), bf16_hi(xw.w)};
-        const float *dp = stage.d + e % ((size_t)H * dv);          // [H, dv] repeats every token
-        const floatx4_t d0 = *reinterpret_cast<const floatx4_t *>(dp), d1 = *reinterpret_cast<const floatx4_t *>(dp + 4);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { y[j] = fmaf(d0[j], x[j], y[j]); y[4 + j] = fmaf(d1[j], x[4 + j], y[4 + j]); }
-    }
-    if (stage.z_gate != nullptr) {
-        const uint4 zw = load_streaming(static_cast<const bf16_t *>(stage.z_gate) + e);
-        const float z[8] = {bf16_lo(zw.x), bf16_hi(zw.x), bf16_lo(zw.y), bf16_hi(zw.y), bf16_lo(zw.z), bf16_hi(zw.z), bf16_lo(zw.w), bf16_hi(zw.w)};
-#pragma unroll
-        for (int j = 0; j < 8; ++j) y[j] *= output_gate(z[j], stage.act);
-    }
-    const uint4 out = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7])};
-    *reinterpret_cast<uint4 *>(o + e) = out;
-}
-
 }  // namespace
 
 bool scan_mfma_supports(int dk, int dv, int chunk, int io_dtype)
@@ -935,7 +1000,24 @@ size_t scan_mfma_workspace_bytes(int B, int T, int H, int dv)
 
 namespace {
 
-template <bool kZBeta, bool kGated>
+// The kernels use more than the default 64 KB of dynamic LDS: raise the limit once per kernel instance and device.
+constexpr int kMaxDevices = 64;
+template <bool kSummary, int kBeta, bool kGated, int kStage>
+hipError_t allow_lds()
+{
+    static std::atomic<bool> done[kMaxDevices];
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    if (done[device].load(std::memory_order_acquire)) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel<kSummary, kBeta, kGated, kStage>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(kStage != 0));
+    if (e == hipSuccess) done[device].store(true, std::memory_order_release);
+    return e;
+}
+
+template <int kBeta, bool kGated, int kStage>
 hipError_t launch_scan_mfma_typed(const ScanArgs &a)
 {
     // a packed variable-length batch is never cut into segments (its lengths live in device memory): one segment
@@ -944,22 +1026,20 @@ hipError_t launch_scan_mfma_typed(const ScanArgs &a)
                                                   : choose_split(a.B, a.T, a.H, a.dv);
     const size_t bh = (size_t)a.B * a.H;
     SegmentPlan plan{sp.nseg, sp.seg_tokens, nullptr, nullptr};
-    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel<false, kZBeta, kGated>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (attr == hipSuccess)
-        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel<true, kZBeta, kGated>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    hipError_t attr = allow_lds<false, kBeta, kGated, kStage>();
+    if (attr == hipSuccess && sp.nseg > 1) attr = allow_lds<true, kBeta, kGated, 0>();
     if (attr != hipSuccess) return attr;
     const dim3 block(kThreads);
     const unsigned col_tiles = (unsigned)(a.dv / kColTile);
     const void *gate_a = kGated ? a.z_g : static_cast<const void *>(a.log_alpha);
+    const OutputStage no_stage{nullptr, nullptr, nullptr, 0};
     if (sp.nseg > 1) {
         plan.slots = static_cast<float *>(a.workspace);
         plan.gamma = plan.slots + (size_t)sp.nseg * bh * kK * a.dv;
-        hipLaunchKernelGGL((scan_mfma_kernel<true, kZBeta, kGated>), dim3((unsigned)bh, col_tiles, (unsigned)(sp.nseg - 1)), block,
-                           kLdsBytes, a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, gate_a,
+        hipLaunchKernelGGL((scan_mfma_kernel<true, kBeta, kGated, 0>), dim3((unsigned)bh, col_tiles, (unsigned)(sp.nseg - 1)), block,
+                           lds_bytes(false), a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, gate_a,
                            (const bf16_t *)a.z_tau, a.beta, (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, a.T, a.H, a.dv, plan,
-                           (const int *)nullptr, 0, 0);
+                           (const int *)nullptr, 0, 0, no_stage);
         const size_t quads = bh * kK * a.dv / 4;
         hipLaunchKernelGGL(segment_state_scan_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, a.stream, a.S0,
                            plan, a.dv, quads);
@@ -968,17 +1048,21 @@ hipError_t launch_scan_mfma_typed(const ScanArgs &a)
     const bool flat_dense = a.cu_seqlens == nullptr && sp.nseg == 1 && col_tiles > 1 && bh * col_tiles > 256;
     const dim3 grid = a.cu_seqlens != nullptr ? dim3((unsigned)(bh * col_tiles))
                       : flat_dense ? dim3((unsigned)((bh + 7) / 8 * 8 * col_tiles)) : dim3((unsigned)bh, col_tiles, (unsigned)sp.nseg);
-    hipLaunchKernelGGL((scan_mfma_kernel<false, kZBeta, kGated>), grid, block, kLdsBytes,
+    hipLaunchKernelGGL((scan_mfma_kernel<false, kBeta, kGated, kStage>), grid, block, lds_bytes(kStage != 0),
                        a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, gate_a, (const bf16_t *)a.z_tau, a.beta, a.S0,
-                       (bf16_t *)a.o, a.S_T, a.T, a.H, a.dv, plan, a.cu_seqlens, a.T, a.B);
-    if (a.stage.any()) {
-        const size_t tokens = a.cu_seqlens != nullptr ? (size_t)a.T : (size_t)a.B * a.T;
-        const size_t pieces = tokens * a.H * a.dv / 8;
-        if (pieces > 0)
-            hipLaunchKernelGGL(output_stage_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, a.stream, (bf16_t *)a.o,
-                               a.stage, pieces, a.H, a.dv);
-    }
+                       (bf16_t *)a.o, a.S_T, a.T, a.H, a.dv, plan, a.cu_seqlens, a.T, a.B, kStage != 0 ? a.stage : no_stage);
     return hipGetLastError();
+}
+
+template <int kBeta, bool kGated>
+hipError_t launch_scan_mfma_staged(const ScanArgs &a)
+{
+    switch ((a.stage.x_prime != nullptr ? kStageFeed : 0) | (a.stage.z_gate != nullptr ? kStageGate : 0)) {
+    case 0: return launch_scan_mfma_typed<kBeta, kGated, 0>(a);
+    case kStageFeed: return launch_scan_mfma_typed<kBeta, kGated, kStageFeed>(a);
+    case kStageGate: return launch_scan_mfma_typed<kBeta, kGated, kStageGate>(a);
+    default: return launch_scan_mfma_typed<kBeta, kGated, kStageFeed | kStageGate>(a);
+    }
 }
 
 }  // namespace
@@ -989,20 +1073,20 @@ hipError_t launch_scan_mfma_typed(const ScanArgs &a)
 // (beta_preact) bf16 pre-activations.
 namespace {
 
-template <bool kZBeta>
+template <int kBeta>
 hipError_t launch_segment_states_typed(const void *k, const void *v, const float *log_alpha, const void *beta, const float *S0,
                                        int B, int T, int H, int dv, int nseg, int seg_tokens, float *slots, float *gamma,
                                        hipStream_t stream)
 {
     const size_t bh = (size_t)B * H;
     SegmentPlan plan{nseg, seg_tokens, slots, gamma};
-    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_mfma_kernel<true, kZBeta, false>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    const hipError_t attr = allow_lds<true, kBeta, false, 0>();
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((scan_mfma_kernel<true, kZBeta, false>), dim3((unsigned)bh, (unsigned)(dv / kColTile), (unsigned)(nseg - 1)),
-                       dim3(kThreads), kLdsBytes, stream, (const bf16_t *)nullptr, (const bf16_t *)k, (const bf16_t *)v,
+    hipLaunchKernelGGL((scan_mfma_kernel<true, kBeta, false, 0>), dim3((unsigned)bh, (unsigned)(dv / kColTile), (unsigned)(nseg - 1)),
+                       dim3(kThreads), lds_bytes(false), stream, (const bf16_t *)nullptr, (const bf16_t *)k, (const bf16_t *)v,
                        static_cast<const void *>(log_alpha), (const bf16_t *)nullptr, beta,
-                       (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, T, H, dv, plan, (const int *)nullptr, 0, 0);
+                       (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, T, H, dv, plan, (const int *)nullptr, 0, 0,
+                       OutputStage{nullptr, nullptr, nullptr, 0});
     const size_t quads = bh * kK * dv / 4;
     hipLaunchKernelGGL(segment_state_scan_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, S0, plan, dv, quads);
     return hipGetLastError();
@@ -1015,18 +1099,19 @@ hipError_t launch_scan_segment_states(const void *k, const void *v, const float 
                                       float *gamma, hipStream_t stream)
 {
     if (nseg < 2 || seg_tokens % kChunk != 0 || dv % kColTile != 0 || (beta_preact && beta == nullptr)) return hipErrorInvalidValue;
-    return beta_preact ? launch_segment_states_typed<true>(k, v, log_alpha, beta, S0, B, T, H, dv, nseg, seg_tokens, slots, gamma, stream)
-                       : launch_segment_states_typed<false>(k, v, log_alpha, beta, S0, B, T, H, dv, nseg, seg_tokens, slots, gamma, stream);
+    if (beta == nullptr) return launch_segment_states_typed<kBetaNone>(k, v, log_alpha, beta, S0, B, T, H, dv, nseg, seg_tokens, slots, gamma, stream);
+    return beta_preact ? launch_segment_states_typed<kBetaPreact>(k, v, log_alpha, beta, S0, B, T, H, dv, nseg, seg_tokens, slots, gamma, stream)
+                       : launch_segment_states_typed<kBetaValues>(k, v, log_alpha, beta, S0, B, T, H, dv, nseg, seg_tokens, slots, gamma, stream);
 }
 
 hipError_t launch_scan_mfma(const ScanArgs &a)
 {
     if ((long long)a.B * a.H == 0) return hipSuccess;
     if (a.T == 0 && (a.S_T == nullptr || a.S_T == a.S0)) return hipSuccess;
-    // the gated form takes the value gate as a pre-activation too, or none at all (kZBeta loads through `beta`
-    // unconditionally, so a missing gate must take the other instance, where a NULL beta means all ones)
-    if (a.gated()) return a.beta != nullptr ? launch_scan_mfma_typed<true, true>(a) : launch_scan_mfma_typed<false, true>(a);
-    return (a.beta != nullptr && a.beta_preact) ? launch_scan_mfma_typed<true, false>(a) : launch_scan_mfma_typed<false, false>(a);
+    // the gated form takes the value gate as a pre-activation too, or none at all
+    if (a.gated()) return a.beta != nullptr ? launch_scan_mfma_staged<kBetaPreact, true>(a) : launch_scan_mfma_staged<kBetaNone, true>(a);
+    if (a.beta == nullptr) return launch_scan_mfma_staged<kBetaNone, false>(a);
+    return a.beta_preact ? launch_scan_mfma_staged<kBetaPreact, false>(a) : launch_scan_mfma_staged<kBetaValues, false>(a);
 }
 
 }  // namespace rodimus
