@@ -228,8 +228,11 @@ __device__ __forceinline__ bf16x8_t pack8(const float *x)
 // It works on one half of the lane's channels at a time (8 channels = the 8 operand slots of one MFMA), which keeps
 // its register footprint small; the two halves add into the same score accumulator.
 struct HalfRow {            // 8 channels of one row: 8g..8g+7 (half 0) or 32+8g..32+8g+7 (half 1)
-    float q[8], k[8], la[8];
+    float q[8], k[8], la[8];    // la: log of the decay gate; natural log as loaded, base 2 when the kernel evaluated it (gated form)
 };
+// the decay gate from its logarithm; exp(-inf) = 0
+template <bool kBase2>
+__device__ __forceinline__ float gate_from_log(float la) { return kBase2 ? __builtin_amdgcn_exp2f(la) : __expf(la); }
 
 // scores of one split level from 8 channels: entries (key row m = 4*grp + r, query row n = row) of
 // (k .* suffix)(q .* prefix)^T that belong to the level
@@ -254,11 +257,27 @@ __device__ __forceinline__ void level_scores(const float (&q)[8], const float (&
     }
 }
 
+// The two key-side gates of one channel (Sec. 3.1.2) for the gated form of this kernel, in base 2 throughout (the hardware
+// exponential and logarithm are base 2, so no conversion factors are spent on the wavefronts that are bound by the vector
+// ALUs): g = softplus(z_g), tau = sigmoid(z_tau); log2_alpha = -g tau log2(e) (the decay gate is 2^log2_alpha) and
+// alpha_hat = g^tau = 2^(tau log2 g).  Same short forms as ddts_channel_gates<true>.
+__device__ __forceinline__ void ddts_channel_gates_base2(float z_g, float z_tau, float &log2_alpha, float &alpha_hat)
+{
+    constexpr float kLog2e = 1.44269504088896341f, kLn2 = 0.693147180559945309f;
+    const float e = __builtin_amdgcn_exp2f(-fabsf(z_g) * kLog2e);                                 // exp(-|z_g|)
+    const float g = fmaf(kLn2, __builtin_amdgcn_logf(1.f + e), fmaxf(z_g, 0.f));                  // softplus
+    // log2 g: for very negative z, g = e^z (1 - e^z / 2 + ...) underflows before its logarithm does
+    const float log2_g = z_g < -15.f ? fmaf(z_g, kLog2e, (-0.5f * kLog2e) * e) : __builtin_amdgcn_logf(g);
+    const float tau = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(z_tau * -kLog2e));       // overflows to the right limit 0
+    log2_alpha = (g * tau) * -kLog2e;
+    alpha_hat = __builtin_amdgcn_exp2f(tau * log2_g);
+}
+
 // A value rounded to bf16 and widened again (what a pass that writes bf16 to memory would hand on).
 __device__ __forceinline__ float round_to_bf16(float x) { return bf16_lo(pack_bf16x2(x, 0.f)); }
 
 // Channels of `kHalf` of a loaded row as the tile construction wants them: fp32 log_alpha, k and q widened.
-// Gated form (Sec. 3.1.2 and the pre-processing of Sec. 3.1.3): log_alpha = -softplus(z_g) sigmoid(z_tau) in fp32,
+// Gated form (Sec. 3.1.2 and the pre-processing of Sec. 3.1.3): log_alpha = -softplus(z_g) sigmoid(z_tau) in fp32 (base 2),
 // k <- softplus(z_g)^sigmoid(z_tau) .* k / max(||k||_2, 1e-12) and q <- q / sqrt(64), both rounded to bf16 (what a separate
 // gate pass would have written; the division by 8 is exact); `inv_norm` is the reciprocal norm of the whole key row.
 // Summary pass: q = 0.  Rows at or beyond the sequence end: q = k = 0, alpha = 1.
@@ -274,7 +293,7 @@ __device__ __forceinline__ void prepare_half_row(const GateLoads &in, bool valid
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             float alpha_hat;
-            ddts_channel_gates<true>(zg[j], zt[j], r.la[j], alpha_hat);
+            ddts_channel_gates_base2(zg[j], zt[j], r.la[j], alpha_hat);
             r.k[j] = round_to_bf16(alpha_hat * r.k[j] * inv_norm);
             if (!kSummary) r.q[j] *= 0.125f;
         }
@@ -293,7 +312,7 @@ __device__ __forceinline__ void prepare_half_row(const GateLoads &in, bool valid
 }
 
 // Channels 32*half + 8grp .. +7 of one tile.
-template <bool kSummary>
+template <bool kSummary, bool kGated>
 __device__ __forceinline__ void gate_half_products(unsigned char *buf, int tile, int row, int grp, int half, const HalfRow &in,
                                                    floatx4_t &acc)
 {
@@ -301,7 +320,7 @@ __device__ __forceinline__ void gate_half_products(unsigned char *buf, int tile,
     const float (&k)[8] = in.k;
     float a[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) a[j] = __expf(in.la[j]);           // exp(-inf) = 0
+    for (int j = 0; j < 8; ++j) a[j] = gate_from_log<kGated>(in.la[j]);
     const bool b0 = row & 1, b1 = row & 2, b2 = row & 4, b3 = row & 8;
     const floatx4_t zero = {0.f, 0.f, 0.f, 0.f};
     if (!kSummary) {
@@ -396,7 +415,7 @@ __device__ __forceinline__ void gate_half_tile(unsigned char *buf, int tile, int
     prepare_half_row<kSummary, kGated, kHalf>(in, valid, inv_norm, r);
     float pre[8];
 #pragma unroll
-    for (int c = 0; c < 8; ++c) pre[c] = __expf(r.la[c]);           // exp(-inf) = 0
+    for (int c = 0; c < 8; ++c) pre[c] = gate_from_log<kGated>(r.la[c]);
     // prefix products A_t over the 16 rows: four doubling steps of DPP row shifts with the identity shifted in
 #pragma unroll
     for (int c = 0; c < 8; ++c) pre[c] *= row_shift_right<1>(pre[c], 1.f);
@@ -411,7 +430,7 @@ __device__ __forceinline__ void gate_half_tile(unsigned char *buf, int tile, int
 #pragma unroll
     for (int c = 0; c < 8; ++c) weak = weak && (pre[c] >= kSafeTileDecay);        // false for 0 and NaN as well
     if (__any(row == 15 && !weak)) {
-        gate_half_products<kSummary>(buf, tile, row, grp, kHalf, r, d);
+        gate_half_products<kSummary, kGated>(buf, tile, row, grp, kHalf, r, d);
         return;
     }
 
@@ -588,7 +607,9 @@ struct StageLoads {
     uint4 x[4], z[4];
 };
 
-template <int kStage>
+// The 16 rows of a tile come in four groups u (rows 4u + lane/16); a wavefront handles the groups kU0 .. kU1-1 (the value
+// wavefront of the tile takes the first two, its gate wavefront the last two: each has the registers for two).
+template <int kStage, int kU0, int kU1>
 __device__ __forceinline__ void stage_prefetch(const Geometry &g, int s, int t_begin, int wave, int lane, StageLoads &p)
 {
     const int rsub = lane >> 4, unit = lane & 15;
@@ -597,7 +618,7 @@ __device__ __forceinline__ void stage_prefetch(const Geometry &g, int s, int t_b
     const size_t first = c.first * g.dv + g.j0;
     const uint32_t row_bytes = (uint32_t)(g.H * g.dv * 2);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = kU0; u < kU1; ++u) {
         const uint32_t off = row_in_chunk(g, c, s, 16 * wave + 4 * u + rsub) * row_bytes + 16u * unit;
         if (kStage & kStageFeed) p.x[u] = load_streaming_at(g.x_prime + first, off);
         if (kStage & kStageGate) p.z[u] = load_streaming_at(g.z_gate + first, off);
@@ -606,7 +627,7 @@ __device__ __forceinline__ void stage_prefetch(const Geometry &g, int s, int t_b
 
 // fp32 outputs of a finished chunk from LDS (512-byte rows, 32-byte units swizzled by row), the stage in fp32, one
 // rounding to bf16, whole 256-byte rows to global memory.  feed: the 128 feed-through weights of this column tile in LDS.
-template <int kStage>
+template <int kStage, int kU0, int kU1>
 __device__ __forceinline__ void store_outputs_block(const Geometry &g, const unsigned char *ob, int s, int wave, int lane,
                                                     const StageLoads &p, const unsigned char *feed)
 {
@@ -617,7 +638,7 @@ __device__ __forceinline__ void store_outputs_block(const Geometry &g, const uns
         d8[0] = lo[0]; d8[1] = lo[1]; d8[2] = lo[2]; d8[3] = lo[3]; d8[4] = hi[0]; d8[5] = hi[1]; d8[6] = hi[2]; d8[7] = hi[3];
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = kU0; u < kU1; ++u) {
         const int row = 16 * wave + 4 * u + rsub;
         const unsigned char *src = ob + row * 512 + ((unit ^ (row & 15)) << 5);
         const floatx4_t lo = *reinterpret_cast<const floatx4_t *>(src), hi = *reinterpret_cast<const floatx4_t *>(src + 16);
@@ -636,7 +657,6 @@ __device__ __forceinline__ void store_outputs_block(const Geometry &g, const uns
         }
         const uint4 w = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7])};
         store_row(g, s, row, unit, w);
-        __builtin_amdgcn_sched_barrier(0);       // one row group at a time: interleaving all four does not fit the registers
     }
 }
 
@@ -834,6 +854,29 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
     if (wave < 4) {
         // ------------------------------------------------------------------ gate wavefront, tile = wave
         __builtin_amdgcn_s_setprio(PRIO_GATE);
+        if (kBlock && !kSummary) {
+            // With the block's output stage these wavefronts also finish half of their tile's output rows (the value
+            // wavefronts are the busiest otherwise).  They then keep ONE set of loads: the next chunk's rows are requested after
+            // the current chunk is built, into the registers it has just freed, and are in flight across the barrier; with the
+            // stage the iteration is long enough to cover them.
+            GateLoads in;
+            StageLoads sl;
+            const unsigned char *feed = lds + kOffOb + 2 * kObBuf;
+            const int row = 16 * wave + n;
+            if (nchunks > 0) gate_prefetch<kSummary, kGated>(g, t_begin, row, grp, in);
+            for (int it = 0; it <= nchunks + 1; ++it) {
+                if (it < nchunks) {
+                    const int s = t_begin + it * kChunk;
+                    gate_tile<kSummary, kGated>(lds + (it & 1) * kBufBytes, wave, n, grp, in, s + row < g.t_end);
+                    gate_prefetch<kSummary, kGated>(g, s + kChunk, row, grp, in);
+                }
+                if (it >= 2)
+                    store_outputs_block<kStage, 2, 4>(g, lds + kOffOb + (it & 1) * kObBuf, t_begin + (it - 2) * kChunk, wave, lane, sl, feed);
+                if (nchunks > 0) stage_prefetch<kStage, 2, 4>(g, t_begin + (it - 1) * kChunk, t_begin, wave, lane, sl);
+                __syncthreads();
+            }
+            return;
+        }
         GateLoads even, odd;      // loads of even / odd chunks, requested one chunk ahead: no register copies between iterations
         const int row = 16 * wave + n;             // this lane's row of every chunk
         if (nchunks > 0) gate_prefetch<kSummary, kGated>(g, t_begin, row, grp, even);
@@ -918,10 +961,10 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
                 stage_values<kBeta>(lds + kOffVt + (it & 1) * kVtBuf, tile, lane, cur, t_begin + it * kChunk, g.t_end);
             if (!kSummary && it >= 2) {
                 const unsigned char *ob = lds + kOffOb + (it & 1) * kObBuf;
-                if (kBlock) store_outputs_block<kStage>(g, ob, t_begin + (it - 2) * kChunk, tile, lane, sl, feed);
+                if (kBlock) store_outputs_block<kStage, 0, 2>(g, ob, t_begin + (it - 2) * kChunk, tile, lane, sl, feed);
 
             }
-            if (kBlock && !kSummary && nchunks > 0) stage_prefetch<kStage>(g, t_begin + (it - 1) * kChunk, t_begin, tile, lane, sl);
+            if (kBlock && !kSummary && nchunks > 0) stage_prefetch<kStage, 0, 2>(g, t_begin + (it - 1) * kChunk, t_begin, tile, lane, sl);
             if (it < nchunks) state_prefetch<kBeta>(g, t_begin + (it + 2) * kChunk, tile, lane, cur);
         };
         StateLoads pf_odd;
