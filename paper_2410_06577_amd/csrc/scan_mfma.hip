@@ -995,13 +995,27 @@ __global__ __launch_bounds__(256) void segment_state_scan_kernel(const float *S0
     floatx4_t s = (S0 != nullptr) ? *reinterpret_cast<const floatx4_t *>(S0 + elem) : floatx4_t{0.f, 0.f, 0.f, 0.f};
     const size_t slot_elems = quads_per_slot * 4;
     *reinterpret_cast<floatx4_t *>(plan.slots + elem) = s;
-    for (int sg = 1; sg < plan.nseg; ++sg) {
-        const float gmm = plan.gamma[(size_t)(sg - 1) * (slot_elems / dv) + row];
-        floatx4_t *p = reinterpret_cast<floatx4_t *>(plan.slots + (size_t)sg * slot_elems + elem);
-        const floatx4_t inc = *p;
-        s[0] = fmaf(gmm, s[0], inc[0]); s[1] = fmaf(gmm, s[1], inc[1]);
-        s[2] = fmaf(gmm, s[2], inc[2]); s[3] = fmaf(gmm, s[3], inc[3]);
-        *p = s;
+    // eight segments at a time: their increments and decays are requested together, so that the walk costs one memory
+    // latency per eight segments and not one per segment
+    constexpr int kBatch = 8;
+    for (int s0 = 1; s0 < plan.nseg; s0 += kBatch) {
+        floatx4_t inc[kBatch];
+        float gmm[kBatch];
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            const int sg = min(s0 + i, plan.nseg - 1);          // past the end: the last segment again, not used
+            inc[i] = *reinterpret_cast<const floatx4_t *>(plan.slots + (size_t)sg * slot_elems + elem);
+            gmm[i] = plan.gamma[(size_t)(sg - 1) * (slot_elems / dv) + row];
+        }
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            const int sg = s0 + i;
+            if (sg < plan.nseg) {
+                s[0] = fmaf(gmm[i], s[0], inc[i][0]); s[1] = fmaf(gmm[i], s[1], inc[i][1]);
+                s[2] = fmaf(gmm[i], s[2], inc[i][2]); s[3] = fmaf(gmm[i], s[3], inc[i][3]);
+                *reinterpret_cast<floatx4_t *>(plan.slots + (size_t)sg * slot_elems + elem) = s;
+            }
+        }
     }
 }
 
