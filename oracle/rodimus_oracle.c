@@ -500,6 +500,147 @@ int rodimus_oracle_scan_gated(const float *q, const float *k, const float *v, co
     return failed ? 2 : 0;
 }
 
+/*
+ * Backward pass of rodimus_oracle_scan_gated: reverse-mode differentiation of the block's recurrence (Sec. 3.1.3) through
+ * the gates of Sec. 3.1.2 and the pre-processing of q and k, step by step in double.  Per step, with
+ *
+ *     g = softplus(z_g)   tau = sigmoid(z_tau)   a = exp(-g tau)   w = g^tau   n = max(||k||_2, 1e-12)
+ *     khat = w .* k / n   qhat = q / sqrt(dk)    s = sigmoid(z_beta)   u = s .* v
+ *     S_t = diag(a) S_{t-1} + khat^T u           o_t = qhat S_t
+ *
+ * and G_t = qhat_t^T do_t + diag(a_{t+1}) G_{t+1} the cotangent of S_t (the carried term at t = T is dS_T):
+ *
+ *     dqhat = do S_t^T      dkhat = u G_t^T      du = khat G_t      da = rowsum(G_t .* S_{t-1})
+ *     dq = dqhat / sqrt(dk)
+ *     dv = s .* du          dz_beta = v .* du .* s (1 - s)
+ *     dw = dkhat .* k / n
+ *     dk = dkhat .* w / n - k (sum_r dkhat_r w_r k_r) / n^3       (second term only while ||k|| is above the guard)
+ *     dg   = -da a tau + dw tau g^(tau - 1)
+ *     dtau = -da a g   + dw w ln g
+ *     dz_g = dg sigmoid(z_g)       dz_tau = dtau tau (1 - tau)
+ *
+ * (g > 0 always; where g underflows to 0 in double, w = 0 and the dw terms are taken as 0.)  The states are recomputed
+ * per segment of 64 steps as in the backward pass above.  z_beta == NULL means the all-ones value gate (dz_beta is then
+ * not written).  Any output pointer may be NULL.  Returns 0 on success, 1 on bad arguments, 2 on allocation failure.
+ */
+int rodimus_oracle_scan_gated_bwd(const float *q, const float *k, const float *v, const float *z_g, const float *z_tau,
+                                  const float *z_beta, const double *S0, const double *d_o, const double *dS_T,
+                                  double *dq, double *dk, double *dv, double *dz_g, double *dz_tau, double *dz_beta, double *dS0,
+                                  int B, int T, int H, int dk_, int dv_)
+{
+    const int n = dk_, m = dv_, segment = 64;
+    if (!q || !k || !v || !z_g || !z_tau || !d_o) return 1;
+    if (B < 0 || T < 0 || H < 0 || n <= 0 || m <= 0) return 1;
+    int failed = 0;
+
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < H; ++h) {
+            const size_t sz = (size_t)n * m;
+            const int nseg = (T + segment - 1) / segment;
+            double *ck = (double *)malloc(sizeof(double) * sz * (size_t)(nseg + 1));      /* state entering each segment */
+            double *sb = (double *)malloc(sizeof(double) * sz * (size_t)(segment + 1));   /* states inside one segment  */
+            double *G = (double *)malloc(sizeof(double) * sz);
+            double *u = (double *)malloc(sizeof(double) * (size_t)m);
+            double *otmp = (double *)malloc(sizeof(double) * (size_t)m);
+            double *dkhat = (double *)malloc(sizeof(double) * (size_t)n);
+            if (!ck || !sb || !G || !u || !otmp || !dkhat) {
+                free(ck); free(sb); free(G); free(u); free(otmp); free(dkhat);
+#pragma omp atomic write
+                failed = 1;
+                continue;
+            }
+            const size_t state_off = ((size_t)b * H + h) * sz;
+            /* forward sweep: remember the state entering every segment */
+            for (size_t e = 0; e < sz; ++e) ck[e] = S0 ? S0[state_off + e] : 0.0;
+            for (int s = 0; s < nseg; ++s) {
+                double *cur = ck + (size_t)(s + 1) * sz;
+                for (size_t e = 0; e < sz; ++e) cur[e] = ck[(size_t)s * sz + e];
+                const int t1 = (s + 1) * segment < T ? (s + 1) * segment : T;
+                for (int t = s * segment; t < t1; ++t) {
+                    const size_t row = ((size_t)b * T + t) * H + h;
+                    block_update(cur, q + row * n, k + row * n, v + row * m, z_g + row * n, z_tau + row * n,
+                                 z_beta ? z_beta + row * m : NULL, otmp, n, m);
+                }
+            }
+            /* reverse sweep */
+            for (size_t e = 0; e < sz; ++e) G[e] = dS_T ? dS_T[state_off + e] : 0.0;     /* carried term diag(a_{t+1}) G_{t+1} */
+            const double qscale = 1.0 / sqrt((double)n);
+            for (int s = nseg - 1; s >= 0; --s) {
+                const int t0 = s * segment, t1 = (s + 1) * segment < T ? (s + 1) * segment : T;
+                for (size_t e = 0; e < sz; ++e) sb[e] = ck[(size_t)s * sz + e];
+                for (int t = t0; t < t1; ++t) {             /* sb[i+1] = S_t for t = t0 + i */
+                    const size_t row = ((size_t)b * T + t) * H + h;
+                    double *nxt = sb + (size_t)(t - t0 + 1) * sz;
+                    for (size_t e = 0; e < sz; ++e) nxt[e] = sb[(size_t)(t - t0) * sz + e];
+                    block_update(nxt, q + row * n, k + row * n, v + row * m, z_g + row * n, z_tau + row * n,
+                                 z_beta ? z_beta + row * m : NULL, otmp, n, m);
+                }
+                for (int t = t1 - 1; t >= t0; --t) {
+                    const size_t row = ((size_t)b * T + t) * H + h;
+                    const double *St = sb + (size_t)(t - t0 + 1) * sz, *Sp = sb + (size_t)(t - t0) * sz;
+                    const float *qt = q + row * n, *kt = k + row * n, *vt = v + row * m;
+                    const float *zgt = z_g + row * n, *ztt = z_tau + row * n, *zbt = z_beta ? z_beta + row * m : NULL;
+                    const double *dot = d_o + row * m;
+                    double norm2 = 0.0;
+                    for (int r = 0; r < n; ++r) norm2 += (double)kt[r] * (double)kt[r];
+                    const int guarded = !(sqrt(norm2) > 1e-12);
+                    const double norm = guarded ? 1e-12 : sqrt(norm2);
+                    /* G_t = carried + qhat_t^T do_t */
+                    for (int r = 0; r < n; ++r)
+                        for (int j = 0; j < m; ++j) G[(size_t)r * m + j] += (double)qt[r] * qscale * dot[j];
+                    /* value side: du = khat G_t */
+                    for (int j = 0; j < m; ++j) {
+                        const double sg = zbt ? sigmoid_d((double)zbt[j]) : 1.0;
+                        u[j] = sg * (double)vt[j];
+                        double acc = 0.0;
+                        for (int r = 0; r < n; ++r) {
+                            const double w = pow(softplus_d((double)zgt[r]), sigmoid_d((double)ztt[r]));
+                            acc += w * ((double)kt[r] / norm) * G[(size_t)r * m + j];
+                        }
+                        if (dv) dv[row * m + j] = sg * acc;
+                        if (dz_beta && zbt) dz_beta[row * m + j] = (double)vt[j] * acc * sg * (1.0 - sg);
+                    }
+                    /* key side */
+                    double through_norm = 0.0;                   /* sum_r dkhat_r w_r k_r */
+                    for (int r = 0; r < n; ++r) {
+                        double acc = 0.0;
+                        for (int j = 0; j < m; ++j) acc += G[(size_t)r * m + j] * u[j];
+                        dkhat[r] = acc;
+                        through_norm += acc * pow(softplus_d((double)zgt[r]), sigmoid_d((double)ztt[r])) * (double)kt[r];
+                    }
+                    for (int r = 0; r < n; ++r) {
+                        const double g = softplus_d((double)zgt[r]), tau = sigmoid_d((double)ztt[r]);
+                        const double a = exp(-g * tau), w = pow(g, tau);
+                        double accq = 0.0, acca = 0.0;
+                        for (int j = 0; j < m; ++j) {
+                            accq += St[(size_t)r * m + j] * dot[j];
+                            acca += G[(size_t)r * m + j] * Sp[(size_t)r * m + j];
+                        }
+                        if (dq) dq[row * n + r] = accq * qscale;
+                        double dk_r = dkhat[r] * w / norm;
+                        if (!guarded) dk_r -= (double)kt[r] * through_norm / (norm * norm * norm);
+                        if (dk) dk[row * n + r] = dk_r;
+                        const double dw = dkhat[r] * (double)kt[r] / norm;
+                        double dg = -acca * a * tau, dtau = -acca * a * g;
+                        if (g > 0.0) {
+                            dg += dw * tau * pow(g, tau - 1.0);
+                            dtau += dw * w * log(g);
+                        }
+                        if (dz_g) dz_g[row * n + r] = dg * sigmoid_d((double)zgt[r]);
+                        if (dz_tau) dz_tau[row * n + r] = dtau * tau * (1.0 - tau);
+                        for (int j = 0; j < m; ++j) G[(size_t)r * m + j] *= a;       /* carried to step t-1 */
+                    }
+                }
+            }
+            if (dS0)
+                for (size_t e = 0; e < sz; ++e) dS0[state_off + e] = G[e];
+            free(ck); free(sb); free(G); free(u); free(otmp); free(dkhat);
+        }
+    }
+    return failed ? 2 : 0;
+}
+
 /* One decode step of the same for N sequences, S [N,H,dk,dv] updated in place. */
 int rodimus_oracle_step_gated(const float *q, const float *k, const float *v, const float *z_g, const float *z_tau,
                               const float *z_beta, double *S, double *o, int N, int H, int dk, int dv)

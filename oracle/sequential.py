@@ -38,6 +38,8 @@ def _load():
         lib.rodimus_oracle_block_output.restype = ctypes.c_int
         lib.rodimus_oracle_scan_gated.argtypes = [f32p] * 6 + [f64p] * 3 + [ctypes.c_int] * 5
         lib.rodimus_oracle_scan_gated.restype = ctypes.c_int
+        lib.rodimus_oracle_scan_gated_bwd.argtypes = [f32p] * 6 + [f64p] * 10 + [ctypes.c_int] * 5
+        lib.rodimus_oracle_scan_gated_bwd.restype = ctypes.c_int
         lib.rodimus_oracle_step_gated.argtypes = [f32p] * 6 + [f64p] * 2 + [ctypes.c_int] * 4
         lib.rodimus_oracle_step_gated.restype = ctypes.c_int
         lib.rodimus_oracle_scan_general.argtypes = [f32p] * 6 + [f64p] * 3 + [ctypes.c_int] * 5
@@ -251,6 +253,32 @@ def scan_gated(q, k, v, z_g, z_tau, z_beta=None, S0=None, want_state=True):
     if rc != 0:
         raise RuntimeError(f"rodimus_oracle_scan_gated failed with code {rc}")
     return o, S_T
+
+
+def scan_gated_bwd(q, k, v, z_g, z_tau, z_beta, S0, d_o, dS_T=None):
+    """Backward pass of ``scan_gated``: cotangents of the raw q, k, v, of the three pre-activations and of S0, from d_o
+    (cotangent of the outputs) and dS_T (of the final state, None = zero).  Returns a dict of float64 arrays ``dq, dk, dv,
+    dz_g, dz_tau, dz_beta, dS0`` (``dz_beta`` is None without a value gate)."""
+    lib = _load()
+    q, k, v, z_g, z_tau, z_beta = _f32(q), _f32(k), _f32(v), _f32(z_g), _f32(z_tau), _f32(z_beta)
+    S0, d_o, dS_T = _f64(S0), _f64(d_o), _f64(dS_T)
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    assert k.shape == z_g.shape == z_tau.shape == (B, T, H, dk) and v.shape == d_o.shape == (B, T, H, dv)
+    assert z_beta is None or z_beta.shape == (B, T, H, dv)
+    assert S0 is None or S0.shape == (B, H, dk, dv)
+    assert dS_T is None or dS_T.shape == (B, H, dk, dv)
+    out = {"dq": np.zeros((B, T, H, dk)), "dk": np.zeros((B, T, H, dk)), "dv": np.zeros((B, T, H, dv)),
+           "dz_g": np.zeros((B, T, H, dk)), "dz_tau": np.zeros((B, T, H, dk)),
+           "dz_beta": np.zeros((B, T, H, dv)) if z_beta is not None else None, "dS0": np.zeros((B, H, dk, dv))}
+    f, d = ctypes.c_float, ctypes.c_double
+    rc = lib.rodimus_oracle_scan_gated_bwd(_ptr(q, f), _ptr(k, f), _ptr(v, f), _ptr(z_g, f), _ptr(z_tau, f), _ptr(z_beta, f),
+                                           _ptr(S0, d), _ptr(d_o, d), _ptr(dS_T, d), _ptr(out["dq"], d), _ptr(out["dk"], d),
+                                           _ptr(out["dv"], d), _ptr(out["dz_g"], d), _ptr(out["dz_tau"], d), _ptr(out["dz_beta"], d),
+                                           _ptr(out["dS0"], d), B, T, H, dk, dv)
+    if rc != 0:
+        raise RuntimeError(f"rodimus_oracle_scan_gated_bwd failed with code {rc}")
+    return out
 
 
 def step_gated(q, k, v, z_g, z_tau, z_beta, S):
