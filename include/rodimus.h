@@ -327,6 +327,42 @@ int rodimus_chunk_scan_bwd_zbeta(const void *q, const void *k, const void *v,
                                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The backward pass of rodimus_chunk_scan_fwd_gated: training through the whole DDTS gate front-end (paper Sec. 3.1.2,
+ * definitions of alpha, alpha-hat and beta-hat; pre-processing of q and k in Sec. 3.1.3).  With g = softplus(z_g),
+ * tau = sigmoid(z_tau), w = g^tau, n = max(||k||_2, 1e-12) the forward call scans with log_alpha = -g .* tau,
+ * k_hat = w .* k / n, q_hat = q / sqrt(dk), beta_hat = sigmoid(z_beta); this call returns the cotangents of the RAW q, k, v
+ * and of the three pre-activations:
+ *
+ *   q, k, z_g, z_tau   [B,T,H,dk] io_dtype     in
+ *   v, d_o             [B,T,H,dv] io_dtype     in
+ *   z_beta             [B,T,H,dv] io_dtype     in, or NULL = no value gate (then dz_beta must be NULL)
+ *   S0, dS_T           [B,H,dk,dv] fp32        in, or NULL = zero
+ *   dq, dk, dz_g, dz_tau [B,T,H,dk] io_dtype   out
+ *   dv, dz_beta        [B,T,H,dv] io_dtype     out (dz_beta may be NULL)
+ *   dS0                [B,H,dk,dv] fp32        out, or NULL
+ *
+ *     dq   = dq_hat / sqrt(dk)
+ *     dk   = dk_hat .* w / n - k (sum_r dk_hat_r w_r k_r) / n^3     (second term only while ||k|| is above the guard)
+ *     dz_g   = (-dlog_alpha .* tau + dw .* tau .* w ./ g) .* sigmoid(z_g),        dw = dk_hat .* k / n
+ *     dz_tau = (-dlog_alpha .* g   + dw .* w .* ln g) .* tau .* (1 - tau)
+ *
+ * where dq_hat, dk_hat, dlog_alpha, dv, dz_beta, dS0 are what rodimus_chunk_scan_bwd_zbeta returns for the scan on
+ * (q_hat, k_hat, log_alpha, z_beta).  Three steps on `stream`: the key-side gate pass into the workspace, the backward of
+ * the scan, the backward of the gate pass (dq_hat and dk_hat pass through the dq and dk buffers, in the I/O dtype).
+ * Matrix-core shapes only (io_dtype = BF16, dk = 64, dv = 128 or 256), others return RODIMUS_ERR_SHAPE.  On an argument
+ * error no output is written (the workspace may have been).
+ */
+int rodimus_chunk_scan_bwd_gated(const void *q, const void *k, const void *v,
+                                 const void *z_g, const void *z_tau, const void *z_beta,
+                                 const float *S0, const void *d_o, const float *dS_T,
+                                 void *dq, void *dk, void *dv_out, void *dz_g, void *dz_tau, void *dz_beta, float *dS0,
+                                 int B, int T, int H, int dk_width, int dv, int io_dtype,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* Scratch bytes the call above needs (0 if the shape is not supported). */
+size_t rodimus_chunk_scan_bwd_gated_workspace_bytes(int B, int T, int H, int dk, int dv, int io_dtype);
+
+/*
  * Backward pass over a packed batch of sequences of different lengths (training on packed sequences; the backward of
  * rodimus_chunk_scan_varlen_fwd with the value gate given as values): exactly rodimus_chunk_scan_bwd applied to every
  * sequence, with the layouts of rodimus_chunk_scan_varlen_fwd:

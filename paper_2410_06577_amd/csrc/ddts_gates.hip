@@ -102,6 +102,84 @@ __global__ __launch_bounds__(kGateThreads) void ddts_value_gate_kernel(const IO 
     *reinterpret_cast<floatx4_t *>(beta + i * 8 + 4) = floatx4_t{sigmoid_f(z[4]), sigmoid_f(z[5]), sigmoid_f(z[6]), sigmoid_f(z[7])};
 }
 
+// Backward of the key side (reverse mode of ddts_key_gates_kernel), same thread layout.  With g = softplus(z_g),
+// tau = sigmoid(z_tau), w = g^tau, n = max(||k||, 1e-12), k_out = w .* k / n, q_out = q / sqrt(dk), log_alpha = -g tau:
+//     dq   = dq_hat / sqrt(dk)
+//     dk   = dk_hat .* w / n - k (sum_r dk_hat_r w_r k_r) / n^3        (second term only while ||k|| is above the guard)
+//     dw   = dk_hat .* k / n
+//     dg   = -dlog_alpha tau + dw tau w / g          dtau = -dlog_alpha g + dw w ln g
+//     dz_g = dg sigmoid(z_g)                         dz_tau = dtau tau (1 - tau)
+// dq / dk may be the buffers dq_hat / dk_hat: every thread reads its eight values before it writes them.
+template <typename IO>
+__global__ __launch_bounds__(kGateThreads) void ddts_key_gates_bwd_kernel(
+    const IO *__restrict__ z_g, const IO *__restrict__ z_tau, const IO *__restrict__ k, const IO *dq_hat, const IO *dk_hat,
+    const float *__restrict__ dlog_alpha, IO *__restrict__ dz_g, IO *__restrict__ dz_tau, IO *dq, IO *dk, long long rows,
+    int dk_width, int lanes_per_row)
+{
+    const long long tid = (long long)blockIdx.x * kGateThreads + threadIdx.x;
+    const long long row = tid / lanes_per_row;
+    const int piece = (int)(tid % lanes_per_row);
+    const bool active = row < rows;                  // inactive lanes still take part in the shuffles
+    const size_t off = (size_t)(active ? row : 0) * dk_width + piece * 8;
+
+    float zg[8], zt[8], kv[8], dqh[8], dkh[8], dla[8];
+    Vec8<IO>::load(z_g + off, zg);
+    Vec8<IO>::load(z_tau + off, zt);
+    Vec8<IO>::load(k + off, kv);
+    Vec8<IO>::load(dq_hat + off, dqh);
+    Vec8<IO>::load(dk_hat + off, dkh);
+    Vec8<float>::load(dlog_alpha + off, dla);
+
+    float g[8], tau[8], log_g[8], w[8];
+    float ss = 0.f, through = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        ddts_channel_gates_full(zg[i], zt[i], g[i], tau[i], log_g[i], w[i]);
+        ss = fmaf(kv[i], kv[i], ss);
+        through = fmaf(dkh[i] * w[i], kv[i], through);
+    }
+    for (int m = lanes_per_row >> 1; m > 0; m >>= 1) {      // rows are aligned lane groups
+        ss += __shfl_xor(ss, m);
+        through += __shfl_xor(through, m);
+    }
+    const float norm = sqrtf(ss);
+    const bool guarded = !(norm > 1e-12f);
+    const float inv_norm = 1.f / (guarded ? 1e-12f : norm);
+    const float pull = guarded ? 0.f : through * inv_norm * inv_norm * inv_norm;
+    const float q_scale = 1.f / sqrtf((float)dk_width);
+
+    float o_zg[8], o_zt[8], o_q[8], o_k[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        o_q[i] = dqh[i] * q_scale;
+        o_k[i] = dkh[i] * w[i] * inv_norm - kv[i] * pull;
+        const float dw = dkh[i] * kv[i] * inv_norm;
+        const float w_over_g = g[i] > 0.f ? w[i] / g[i] : 0.f;
+        const float dg = -dla[i] * tau[i] + dw * tau[i] * w_over_g;
+        const float dtau = -dla[i] * g[i] + (w[i] > 0.f ? dw * w[i] * log_g[i] : 0.f);
+        o_zg[i] = dg * sigmoid_f(zg[i]);
+        o_zt[i] = dtau * tau[i] * (1.f - tau[i]);
+    }
+    if (active) {
+        Vec8<IO>::store(dz_g + off, o_zg);
+        Vec8<IO>::store(dz_tau + off, o_zt);
+        Vec8<IO>::store(dq + off, o_q);
+        Vec8<IO>::store(dk + off, o_k);
+    }
+}
+
+template <typename IO>
+hipError_t launch_bwd_typed(const GateBwdArgs &a)
+{
+    if (a.rows == 0) return hipSuccess;
+    const int lanes_per_row = a.dk_width / 8;
+    const long long threads = a.rows * lanes_per_row;
+    hipLaunchKernelGGL(ddts_key_gates_bwd_kernel<IO>, dim3((unsigned)((threads + kGateThreads - 1) / kGateThreads)), dim3(kGateThreads),
+                       0, a.stream, (const IO *)a.z_g, (const IO *)a.z_tau, (const IO *)a.k, (const IO *)a.dq_hat, (const IO *)a.dk_hat,
+                       a.dlog_alpha, (IO *)a.dz_g, (IO *)a.dz_tau, (IO *)a.dq, (IO *)a.dk, a.rows, a.dk_width, lanes_per_row);
+    return hipGetLastError();
+}
+
 template <typename IO>
 hipError_t launch_typed(const GateArgs &a)
 {
@@ -124,6 +202,11 @@ hipError_t launch_typed(const GateArgs &a)
 hipError_t launch_ddts_gates(const GateArgs &a)
 {
     return a.io_dtype == RODIMUS_BF16 ? launch_typed<bf16_t>(a) : launch_typed<float>(a);
+}
+
+hipError_t launch_ddts_gates_bwd(const GateBwdArgs &a)
+{
+    return a.io_dtype == RODIMUS_BF16 ? launch_bwd_typed<bf16_t>(a) : launch_bwd_typed<float>(a);
 }
 
 }  // namespace rodimus

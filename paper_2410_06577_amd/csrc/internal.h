@@ -55,15 +55,21 @@ __device__ __forceinline__ float log1p_unit(float e)
 // grows to ~1e-3 only where g < 1e-4 (no visible effect on the decay; 0.1 % on a key that is then rounded to bf16): for
 // the matrix-core scan, where this arithmetic sits on the critical wavefronts.
 template <bool kShortLog1p = false>
-__device__ __forceinline__ void ddts_channel_gates(float z_g, float z_tau, float &log_alpha, float &alpha_hat)
+__device__ __forceinline__ void ddts_channel_gates_full(float z_g, float z_tau, float &g, float &tau, float &log_g, float &alpha_hat)
 {
     const float e = __expf(-fabsf(z_g));
-    const float g = fmaxf(z_g, 0.f) + (kShortLog1p ? __logf(1.f + e) : log1p_unit(e));             // softplus
+    g = fmaxf(z_g, 0.f) + (kShortLog1p ? __logf(1.f + e) : log1p_unit(e));             // softplus
     // log g: for very negative z, g = e^z (1 - e^z / 2 + ...) underflows before its logarithm does
-    const float log_g = z_g < -15.f ? z_g - 0.5f * e : __logf(g);
-    const float tau = kShortLog1p ? sigmoid_short(z_tau) : sigmoid_f(z_tau);
-    log_alpha = -g * tau;
+    log_g = z_g < -15.f ? z_g - 0.5f * e : __logf(g);
+    tau = kShortLog1p ? sigmoid_short(z_tau) : sigmoid_f(z_tau);
     alpha_hat = __expf(tau * log_g);
+}
+template <bool kShortLog1p = false>
+__device__ __forceinline__ void ddts_channel_gates(float z_g, float z_tau, float &log_alpha, float &alpha_hat)
+{
+    float g, tau, log_g;
+    ddts_channel_gates_full<kShortLog1p>(z_g, z_tau, g, tau, log_g, alpha_hat);
+    log_alpha = -g * tau;
 }
 
 // 1 / max(||k||_2, 1e-12) from the squared norm: the key normalisation of Sec. 3.1.3
@@ -273,6 +279,18 @@ bool scan_bwd_supports(int dk, int dv, int io_dtype);
 size_t scan_bwd_workspace_bytes(size_t token_rows, int B, int T, int H, int dv, bool packed);
 hipError_t launch_decode_step(const DecodeArgs &a);
 hipError_t launch_ddts_gates(const GateArgs &a);
+// Backward of the key side of the gate front-end: cotangents of z_g, z_tau and of the raw q, k from those of log_alpha
+// (fp32) and of the scaled q and folded k (I/O dtype).  dq may be dq_hat and dk may be dk_hat (updated in place).
+struct GateBwdArgs {
+    const void *z_g, *z_tau, *k;
+    const void *dq_hat, *dk_hat;
+    const float *dlog_alpha;
+    void *dz_g, *dz_tau, *dq, *dk;
+    long long rows;
+    int dk_width, io_dtype;
+    hipStream_t stream;
+};
+hipError_t launch_ddts_gates_bwd(const GateBwdArgs &a);
 
 // Causal depthwise convolution over time (ShortConv).  x, y [B,T,C], state_in/out [B,W-1,C] in the I/O dtype.
 struct ShortConvArgs {

@@ -367,6 +367,71 @@ int rodimus_chunk_scan_bwd_zbeta(const void *q, const void *k, const void *v, co
                      io_dtype, workspace, workspace_bytes, stream, false, nullptr, true);
 }
 
+// Backward of the gated scan: key-side gate pass into the workspace, backward of the scan on its outputs (value gate as
+// its pre-activation), then the backward of the gate pass.  Workspace: log_alpha fp32, scaled q and folded k in the I/O
+// dtype, dlog_alpha fp32 (each [B,T,H,dk]), then the scan backward's own workspace.  The cotangents of the scaled q and the
+// folded k pass through the caller's dq and dk buffers, which the last kernel updates in place.
+static size_t gated_bwd_front_bytes(size_t tokens, int dk, int io_dtype) { return tokens * dk * (4 + 2 * elem_bytes(io_dtype) + 4); }
+
+size_t rodimus_chunk_scan_bwd_gated_workspace_bytes(int B, int T, int H, int dk, int dv, int io_dtype)
+{
+    if (B < 0 || T < 0 || H < 0 || !scan_bwd_supports(dk, dv, io_dtype)) return 0;
+    return gated_bwd_front_bytes((size_t)B * T * H, dk, io_dtype) + bwd_workspace((size_t)B * T, B, T, H, dk, dv, io_dtype, false);
+}
+
+int rodimus_chunk_scan_bwd_gated(const void *q, const void *k, const void *v, const void *z_g, const void *z_tau, const void *z_beta,
+                                 const float *S0, const void *d_o, const float *dS_T, void *dq, void *dk, void *dv_out, void *dz_g,
+                                 void *dz_tau, void *dz_beta, float *dS0, int B, int T, int H, int dk_width, int dv, int io_dtype,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
+    if (B < 0 || T < 0 || H < 0 || (long long)B * H > kMaxGridX || (long long)T * H > kMaxGridX) return RODIMUS_ERR_SHAPE;
+    if (!scan_bwd_supports(dk_width, dv, io_dtype)) return RODIMUS_ERR_SHAPE;       // matrix-core shapes only
+    const size_t tokens = (size_t)B * T * H;
+    if (tokens == 0) return bwd_entry(q, k, v, nullptr, z_beta, S0, d_o, dS_T, dq, dk, dv_out, nullptr, dz_beta, dS0, B, T, H, dk_width,
+                                      dv, io_dtype, workspace, workspace_bytes, stream, false, nullptr, z_beta != nullptr);
+    if (!q || !k || !v || !z_g || !z_tau || !d_o || !dq || !dk || !dv_out || !dz_g || !dz_tau) return RODIMUS_ERR_NULL;
+    if (z_beta == nullptr && dz_beta != nullptr) return RODIMUS_ERR_NULL;
+    if (misaligned(z_g) || misaligned(z_tau) || misaligned(dz_g) || misaligned(dz_tau) || misaligned(workspace)) return RODIMUS_ERR_ALIGN;
+    const size_t eb = elem_bytes(io_dtype), key_bytes = tokens * dk_width * eb;
+    const size_t front = gated_bwd_front_bytes(tokens, dk_width, io_dtype);
+    const size_t need = front + bwd_workspace((size_t)B * T, B, T, H, dk_width, dv, io_dtype, false);
+    if (workspace == nullptr || workspace_bytes < need) return RODIMUS_ERR_WORKSPACE;
+    // the two extra inputs and outputs against everything else (the call below checks the rest, workspace included)
+    const void *others[16] = {q, k, v, z_beta, S0, d_o, dS_T, dq, dk, dv_out, dz_beta, dS0, workspace, z_g, z_tau, nullptr};
+    const size_t state_bytes = (size_t)B * H * dk_width * dv * 4, val_bytes = tokens * dv * eb;
+    const size_t other_bytes[16] = {key_bytes, key_bytes, val_bytes, val_bytes, state_bytes, val_bytes, state_bytes, key_bytes, key_bytes,
+                                    val_bytes, val_bytes, state_bytes, need, key_bytes, key_bytes, 0};
+    void *extra_out[2] = {dz_g, dz_tau};
+    for (int o = 0; o < 2; ++o)
+        for (int i = 0; i < 15; ++i)
+            if (overlaps(extra_out[o], key_bytes, others[i], other_bytes[i])) return RODIMUS_ERR_ALIAS;
+    if (overlaps(dz_g, key_bytes, dz_tau, key_bytes)) return RODIMUS_ERR_ALIAS;
+    const void *extra_in[2] = {z_g, z_tau};
+    for (int e = 0; e < 2; ++e)
+        for (int i = 7; i < 13; ++i)
+            if (overlaps(extra_in[e], key_bytes, others[i], other_bytes[i])) return RODIMUS_ERR_ALIAS;
+
+    char *ws = static_cast<char *>(workspace);
+    float *log_alpha = reinterpret_cast<float *>(ws);
+    void *q_hat = ws + tokens * dk_width * 4;
+    void *k_hat = static_cast<char *>(q_hat) + key_bytes;
+    float *dlog_alpha = reinterpret_cast<float *>(static_cast<char *>(k_hat) + key_bytes);
+    void *inner_ws = ws + front;
+
+    // validate the inner call's arguments before anything is launched: a dry run with zero sequences is not possible, so
+    // the order is gate pass, inner call (which validates and returns before its own launches on error), gate backward
+    GateArgs ga{z_g, z_tau, nullptr, q, k, log_alpha, nullptr, q_hat, k_hat, (long long)tokens, dk_width, dv, io_dtype,
+                static_cast<hipStream_t>(stream)};
+    if (launch_ddts_gates(ga) != hipSuccess) return RODIMUS_ERR_LAUNCH;
+    const int inner = bwd_entry(q_hat, k_hat, v, log_alpha, z_beta, S0, d_o, dS_T, dq, dk, dv_out, dlog_alpha, dz_beta, dS0, B, T, H,
+                                dk_width, dv, io_dtype, inner_ws, workspace_bytes - front, stream, false, nullptr, z_beta != nullptr);
+    if (inner != RODIMUS_OK) return inner;
+    GateBwdArgs gb{z_g, z_tau, k, dq, dk, dlog_alpha, dz_g, dz_tau, dq, dk, (long long)tokens, dk_width, io_dtype,
+                   static_cast<hipStream_t>(stream)};
+    return launch_ddts_gates_bwd(gb) == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
+}
+
 int rodimus_chunk_scan_varlen_bwd(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta,
                                   const float *S0, const void *d_o, const float *dS_T, void *dq, void *dk, void *dv_out,
                                   float *dlog_alpha, float *dbeta, float *dS0, const int *cu_seqlens, int N, int total_tokens,

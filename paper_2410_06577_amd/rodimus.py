@@ -61,6 +61,10 @@ def lib() -> ctypes.CDLL:
         L.rodimus_chunk_scan_bwd.restype = i
         L.rodimus_chunk_scan_bwd_zbeta.argtypes = L.rodimus_chunk_scan_bwd.argtypes
         L.rodimus_chunk_scan_bwd_zbeta.restype = i
+        L.rodimus_chunk_scan_bwd_gated.argtypes = [vp] * 16 + [i] * 6 + [vp, sz, vp]
+        L.rodimus_chunk_scan_bwd_gated.restype = i
+        L.rodimus_chunk_scan_bwd_gated_workspace_bytes.argtypes = [i] * 6
+        L.rodimus_chunk_scan_bwd_gated_workspace_bytes.restype = sz
         L.rodimus_chunk_scan_bwd_workspace_bytes.argtypes = [i] * 6
         L.rodimus_chunk_scan_bwd_workspace_bytes.restype = sz
         L.rodimus_chunk_scan_varlen_bwd.argtypes = [vp] * 15 + [i] * 6 + [vp, sz, vp]
@@ -195,6 +199,37 @@ def rodimus_chunk_scan_fwd_noalloc(q, k, v, log_alpha, beta, S0, o, S_T, *, chun
 def rodimus_chunk_scan_fwd_zbeta(q, k, v, log_alpha, z_beta, S0=None, **kw):
     """``rodimus_chunk_scan_fwd`` with the value gate given as its pre-activation z_beta [B,T,H,dv] (dtype of v)."""
     return rodimus_chunk_scan_fwd(q, k, v, log_alpha, z_beta, S0, _preact=True, **kw)
+
+
+def rodimus_chunk_scan_bwd_gated(q, k, v, z_g, z_tau, z_beta, S0, d_o, dS_T=None, *, want_dS0=True, workspace=None):
+    """Backward of ``rodimus_chunk_scan_fwd_gated``: cotangents of the raw q, k, v, of the pre-activations z_g, z_tau,
+    z_beta (None: no value gate) and of S0.  Returns a dict ``dq, dk, dv, dz_g, dz_tau, dz_beta, dS0``."""
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_chunk_scan_bwd_gated needs device tensors (no CPU path exists)")
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    dev, io = q.device, q.dtype
+    for name, t in (("k", k), ("z_g", z_g), ("z_tau", z_tau)):
+        _require(t, name, (B, T, H, dk), io, dev)
+    for name, t in (("v", v), ("z_beta", z_beta), ("d_o", d_o)):
+        _require(t, name, (B, T, H, dv), io, dev)
+    _require(S0, "S0", (B, H, dk, dv), torch.float32, dev)
+    _require(dS_T, "dS_T", (B, H, dk, dv), torch.float32, dev)
+    out = {"dq": torch.empty_like(q), "dk": torch.empty_like(k), "dv": torch.empty_like(v), "dz_g": torch.empty_like(q),
+           "dz_tau": torch.empty_like(q), "dz_beta": torch.empty_like(v) if z_beta is not None else None,
+           "dS0": torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev) if want_dS0 else None}
+    need = int(lib().rodimus_chunk_scan_bwd_gated_workspace_bytes(B, T, H, dk, dv, _DTYPES[io]))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_chunk_scan_bwd_gated(_ptr(q), _ptr(k), _ptr(v), _ptr(z_g), _ptr(z_tau), _ptr(z_beta), _ptr(S0), _ptr(d_o),
+                                                  _ptr(dS_T), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]), _ptr(out["dz_g"]),
+                                                  _ptr(out["dz_tau"]), _ptr(out["dz_beta"]), _ptr(out["dS0"]), B, T, H, dk, dv,
+                                                  _DTYPES[io], _ptr(workspace), ws_bytes, _stream(dev)))
+    return out
 
 
 def rodimus_chunk_scan_varlen_bwd(q, k, v, log_alpha, cu_seqlens, beta, S0, d_o, dS_T=None, *, want_dbeta=True, want_dS0=True,

@@ -33,7 +33,8 @@ def test_every_declared_symbol_is_exported(L):
             "rodimus_chunk_scan_fwd_gated", "rodimus_decode_step_gated",
             "rodimus_chunk_scan_fwd_general", "rodimus_decode_step_general",
             "rodimus_chunk_scan_varlen_bwd", "rodimus_chunk_scan_varlen_bwd_workspace_bytes",
-            "rodimus_chunk_scan_fwd_noalloc", "rodimus_chunk_scan_fwd_noalloc_scratch_bytes"} <= declared
+            "rodimus_chunk_scan_fwd_noalloc", "rodimus_chunk_scan_fwd_noalloc_scratch_bytes",
+            "rodimus_chunk_scan_bwd_gated", "rodimus_chunk_scan_bwd_gated_workspace_bytes"} <= declared
     for name in declared:
         assert hasattr(L, name), name
 
@@ -353,6 +354,33 @@ def test_packed_backward_validation(L):
     assert call(dq=base["cu"]) == E_ALIAS and call(ws=base["cu"]) == E_ALIAS
     assert call(ws_bytes=16) == E_WS and call(io=7) == E_DTYPE and call(dk=0) == E_SHAPE and call(total=-1) == E_SHAPE
     assert call(N=0, total=0, cu=None) == OK
+
+
+def test_gated_backward_validation(L):
+    G = 0x100000000
+    p = lambda x: None if x is None else ctypes.c_void_p(x)
+    names = ["q", "k", "v", "z_g", "z_tau", "z_beta", "S0", "d_o", "dS_T", "dq", "dk", "dv", "dz_g", "dz_tau", "dz_beta", "dS0"]
+    base = {n: (i + 1) * G for i, n in enumerate(names)}
+    shape = dict(B=2, T=128, H=2, dk=64, dv=128, io=rodimus.BF16)
+    need = L.rodimus_chunk_scan_bwd_gated_workspace_bytes(2, 128, 2, 64, 128, rodimus.BF16)
+    inner = L.rodimus_chunk_scan_bwd_workspace_bytes(2, 128, 2, 64, 128, rodimus.BF16)
+    assert need == inner + 2 * 128 * 2 * 64 * (4 + 2 + 2 + 4)           # log_alpha, scaled q, folded k, dlog_alpha in front
+
+    def call(ws=20 * G, ws_bytes=need, B=2, T=128, H=2, key_width=64, value_width=128, io=rodimus.BF16, **ptr):
+        a = dict(base)
+        a.update(ptr)
+        return L.rodimus_chunk_scan_bwd_gated(*[p(a[n]) for n in names], B, T, H, key_width, value_width, io, p(ws), ws_bytes, None)
+
+    assert call(io=9) == E_DTYPE
+    assert call(key_width=32) == E_SHAPE and call(value_width=64) == E_SHAPE and call(io=rodimus.F32) == E_SHAPE and call(B=-1) == E_SHAPE
+    for n in ("q", "k", "v", "z_g", "z_tau", "d_o", "dq", "dk", "dv", "dz_g", "dz_tau"):
+        assert call(**{n: None}) == E_NULL, n
+    assert call(z_beta=None) == E_NULL                       # dz_beta without z_beta
+    assert call(ws=None) == E_WS and call(ws_bytes=need - 16) == E_WS
+    assert call(z_g=base["z_g"] + 8) == E_ALIGN and call(dz_tau=base["dz_tau"] + 4) == E_ALIGN
+    assert call(dz_g=base["q"]) == E_ALIAS and call(dz_tau=base["dz_g"]) == E_ALIAS and call(dz_g=20 * G + 64) == E_ALIAS
+    assert call(dq=base["z_g"]) == E_ALIAS and call(dk=base["z_tau"]) == E_ALIAS
+    assert call(B=0) == OK
 
 
 def test_empty_problems_are_successful_noops(L):
