@@ -32,13 +32,24 @@ def _compile(src: str, extra) -> str:
     return obj
 
 
-def build(extra_flags=(), jobs: int = 4) -> str:
+# AddressSanitizer + UndefinedBehaviorSanitizer on the HOST side only (argument validation and dispatch in
+# csrc/rodimus_api.hip and the launchers); the device code is compiled as usual.  A checking build: run the CPU tests of
+# the boundary with LD_PRELOAD set to clang's ASan runtime (`hipcc -print-file-name=libclang_rt.asan-x86_64.so`) and
+# ASAN_OPTIONS=detect_leaks=0, then build again without the flag.
+HOST_SANITIZE = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-omit-frame-pointer",
+                 "-Xarch_host", "-g"]
+
+
+def build(extra_flags=(), jobs: int = 4, sanitize_host: bool = False) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
+    extra = list(extra_flags) + (HOST_SANITIZE if sanitize_host else [])
     with ThreadPoolExecutor(max_workers=jobs) as pool:
-        objs = list(pool.map(lambda s: _compile(s, list(extra_flags)), sources()))
-    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB], check=True)
+        objs = list(pool.map(lambda s: _compile(s, extra), sources()))
+    link = ["-fsanitize=address", "-fsanitize=undefined", "-shared-libsan"] if sanitize_host else []
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *link, *objs, "-o", LIB], check=True)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build(extra_flags=sys.argv[1:]))
+    args = sys.argv[1:]
+    print(build(extra_flags=[a for a in args if a != "--sanitize-host"], sanitize_host="--sanitize-host" in args))

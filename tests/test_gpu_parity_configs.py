@@ -1,14 +1,14 @@
 """GPU parity at the FULL sizes of the baseline file's configurations, in the launch configuration bench.py times
 (needs an MI355X).  The fp64 oracle finishes each of them in seconds on the machine's host cores, so every output
-element is compared; the decode configuration is checked on a subset of sequences (sequences are independent, so
-the subset check is exact for those sequences)."""
+element is compared; the decode configuration is checked on all sequences for 100 steps and on a subset of 16 for all
+1000 (sequences are independent, so the subset check is exact for those sequences)."""
 import numpy as np
 import pytest
 import torch
 
 import oracle
 from paper_2410_06577_amd import rodimus, workloads as wl
-from _parity import TOL_BF16, gpu_scan, oracle_scan, rel_err, to_dev
+from _parity import REGRESSION_BF16, TOL_BF16, gpu_scan, oracle_scan, per_head_errors, rel_err, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -26,33 +26,51 @@ def test_full_size_scan_configs(name):
     eo, es = rel_err(o, o_ref), rel_err(S_T, S_ref)
     print(f"{name}: o rel err {eo:.2e}, S_T rel err {es:.2e}", flush=True)
     assert eo <= TOL_BF16 and es <= TOL_BF16
+    assert eo <= REGRESSION_BF16 and es <= REGRESSION_BF16          # regression bar (observed: 7e-3 and 3e-3)
     # per-(batch, head) check as well: a single bad sequence must not hide behind the global maximum
-    go = o.float().cpu().numpy().astype(np.float64)
-    for b in range(w.B):
-        for h in range(w.H):
-            ref = o_ref[b, :, h]
-            assert np.abs(go[b, :, h] - ref).max() <= TOL_BF16 * np.abs(ref).max(), (b, h)
+    assert per_head_errors(o, o_ref, 2).max() <= TOL_BF16 and per_head_errors(S_T, S_ref, 1).max() <= TOL_BF16
 
 
 def test_decode_config_1000_chained_steps():
-    """256 sequences x 16 heads of 64x256 fp32 states, 1000 chained steps on the GPU; the oracle follows 8 of the
-    sequences through all 1000 steps."""
+    """256 sequences x 16 heads of 64x256 fp32 states, 1000 chained steps on the GPU.  The oracle follows ALL 256 sequences
+    through the first 100 steps (every state and every output of the checked steps compared), and 16 of them through all
+    1000 steps (sequences are independent, so the subset check is exact for those)."""
     w = wl.DECODE
     d = wl.make_decode_inputs(w)
-    sub = [0, 1, 2, 100, 101, 200, 254, 255]
+    sub = [0, 1, 2, 3, 63, 64, 100, 101, 127, 128, 191, 200, 201, 253, 254, 255]
     S = d["S"].to("cuda:0")
     ring = [to_dev(tok) for tok in d["ring"]]
+    S_all = d["S"].double().numpy()
     S_ref = d["S"][sub].double().numpy()
-    check_steps = {0, 1, 2, 499, 998, 999}
+    all_steps, check_all = 100, {0, 1, 49, 99}
+    check_steps = {0, 1, 2, 99, 100, 499, 998, 999}
     print("decode: 1000 chained steps ...", flush=True)
-    outs = {}
+    outs, outs_all, S_at_100 = {}, {}, None
     for i in range(w.steps):
         t = ring[i % w.ring]
         o = rodimus.rodimus_decode_step(t["q"], t["k"], t["v"], t["log_alpha"], t["beta"], S)
         if i in check_steps:
             outs[i] = o[sub].float().cpu().numpy().astype(np.float64)
+        if i in check_all:
+            outs_all[i] = o.float().cpu().numpy().astype(np.float64)
+        if i == all_steps - 1:
+            S_at_100 = S.clone()
     torch.cuda.synchronize()
-    print("decode: oracle on the subset ...", flush=True)
+    print(f"decode: oracle on all {w.N} sequences for {all_steps} steps ...", flush=True)
+    for i in range(all_steps):
+        tok = d["ring"][i % w.ring]
+        o_ref, S_all = oracle.step(tok["q"], tok["k"], tok["v"], tok["log_alpha"], tok["beta"], S_all)
+        if i in check_all:
+            e = float(np.abs(outs_all[i] - o_ref).max() / np.abs(o_ref).max())
+            assert e <= TOL_BF16, (i, e)
+            per_seq = np.abs(outs_all[i] - o_ref).reshape(w.N, -1).max(1) / np.abs(o_ref).reshape(w.N, -1).max(1)
+            assert per_seq.max() <= TOL_BF16, (i, int(per_seq.argmax()), float(per_seq.max()))
+    es_all = rel_err(S_at_100, S_all)
+    print(f"decode: state of all sequences after {all_steps} steps, rel err {es_all:.2e}", flush=True)
+    assert es_all <= 1e-4
+    per_seq_state = (np.abs(S_at_100.cpu().double().numpy() - S_all).reshape(w.N, -1).max(1) / np.abs(S_all).reshape(w.N, -1).max(1))
+    assert per_seq_state.max() <= 1e-4, int(per_seq_state.argmax())
+    print("decode: oracle on the subset for all 1000 steps ...", flush=True)
     worst = 0.0
     for i in range(w.steps):
         tok = d["ring"][i % w.ring]
