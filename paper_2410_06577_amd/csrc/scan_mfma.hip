@@ -625,11 +625,13 @@ __device__ __forceinline__ void stage_prefetch(const Geometry &g, int s, int t_b
     }
 }
 
-// fp32 outputs of a finished chunk from LDS (512-byte rows, 32-byte units swizzled by row), the stage in fp32, one
-// rounding to bf16, whole 256-byte rows to global memory.  feed: the 128 feed-through weights of this column tile in LDS.
+// fp32 outputs of a finished chunk in LDS (512-byte rows, 32-byte units swizzled by row): the stage in fp32, one rounding
+// to bf16, and the eight results written back over the first half of the unit they came from (a lane touches its own
+// units only).  The state wavefronts move them to global memory one iteration later (store_outputs_block).
+// feed: the 128 feed-through weights of this column tile in LDS.
 template <int kStage, int kU0, int kU1>
-__device__ __forceinline__ void store_outputs_block(const Geometry &g, const unsigned char *ob, int s, int wave, int lane,
-                                                    const StageLoads &p, const unsigned char *feed)
+__device__ __forceinline__ void finish_outputs_block(const Geometry &g, unsigned char *ob, int wave, int lane,
+                                                     const StageLoads &p, const unsigned char *feed)
 {
     const int rsub = lane >> 4, unit = lane & 15;
     float d8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -640,7 +642,7 @@ __device__ __forceinline__ void store_outputs_block(const Geometry &g, const uns
 #pragma unroll
     for (int u = kU0; u < kU1; ++u) {
         const int row = 16 * wave + 4 * u + rsub;
-        const unsigned char *src = ob + row * 512 + ((unit ^ (row & 15)) << 5);
+        unsigned char *src = ob + row * 512 + ((unit ^ (row & 15)) << 5);
         const floatx4_t lo = *reinterpret_cast<const floatx4_t *>(src), hi = *reinterpret_cast<const floatx4_t *>(src + 16);
         float y[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         if (kStage & kStageFeed) {
@@ -655,7 +657,21 @@ __device__ __forceinline__ void store_outputs_block(const Geometry &g, const uns
 #pragma unroll
             for (int j = 0; j < 8; ++j) y[j] *= output_gate(z[j], g.act);
         }
-        const uint4 w = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7])};
+        *reinterpret_cast<uint4 *>(src) = uint4{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7])};
+    }
+}
+
+// The finished bf16 outputs of a chunk (see finish_outputs_block) to global memory, by the state wavefronts: wavefront
+// `slab` takes ITS OWN 32 columns of all 64 rows, 64 bytes per row, because it is about to overwrite exactly those bytes
+// with the next chunk's outputs (program order inside the wavefront is the only ordering there is between the two).
+__device__ __forceinline__ void store_outputs_block(const Geometry &g, const unsigned char *ob, int s, int slab, int lane)
+{
+    asm volatile("" : "+v"(lane));       // offsets recomputed per chunk, see store_outputs
+    const int rsub = lane >> 2, piece = lane & 3;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int row = 16 * j + rsub, unit = 4 * slab + piece;
+        const uint4 w = *reinterpret_cast<const uint4 *>(ob + row * 512 + ((unit ^ (row & 15)) << 5));
         store_row(g, s, row, unit, w);
     }
 }
@@ -863,15 +879,16 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
             StageLoads sl;
             const unsigned char *feed = lds + kOffOb + 2 * kObBuf;
             const int row = 16 * wave + n;
+            constexpr int kDrain = 2;          // iterations after the last chunk is built: state, finish, store
             if (nchunks > 0) gate_prefetch<kSummary, kGated>(g, t_begin, row, grp, in);
-            for (int it = 0; it <= nchunks + 1; ++it) {
+            for (int it = 0; it <= nchunks + kDrain; ++it) {
                 if (it < nchunks) {
                     const int s = t_begin + it * kChunk;
                     gate_tile<kSummary, kGated>(lds + (it & 1) * kBufBytes, wave, n, grp, in, s + row < g.t_end);
                     gate_prefetch<kSummary, kGated>(g, s + kChunk, row, grp, in);
                 }
-                if (it >= 2)
-                    store_outputs_block<kStage, 2, 4>(g, lds + kOffOb + (it & 1) * kObBuf, t_begin + (it - 2) * kChunk, wave, lane, sl, feed);
+                if (it >= 2 && it <= nchunks + 1)
+                    finish_outputs_block<kStage, 2, 4>(g, lds + kOffOb + (it & 1) * kObBuf, wave, lane, sl, feed);
                 if (nchunks > 0) stage_prefetch<kStage, 2, 4>(g, t_begin + (it - 1) * kChunk, t_begin, wave, lane, sl);
                 __syncthreads();
             }
@@ -919,10 +936,13 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt) decay[kt] = floatx4_t{1.f, 1.f, 1.f, 1.f};
 
-        for (int it = 0; it <= nchunks + 1; ++it) {
+        for (int it = 0; it <= nchunks + (kBlock ? 2 : 1); ++it) {
             // outputs of chunk it-2 (finished in iteration it-1), rows 16 slab .. +15: these wavefronts wait for no loads, so the
             // slow completion of the stores holds nothing up (memory operations of a wavefront retire in order)
             if (!kSummary && !kBlock && it >= 2) store_outputs(g, lds + kOffOb + (it & 1) * kObBuf, t_begin + (it - 2) * kChunk, slab, lane);
+            // with the output stage: chunk it-3, which the other wavefronts finished in place in iteration it-1, from the buffer
+            // that this iteration's chunk is about to overwrite
+            if (!kSummary && kBlock && it >= 3) store_outputs_block(g, lds + kOffOb + ((it - 1) & 1) * kObBuf, t_begin + (it - 3) * kChunk, slab, lane);
             if (it >= 1 && it <= nchunks)      // chunk it-1: built and staged by the other wavefronts in the previous iteration
                 state_chunk<kSummary, kBlock>(lds + ((it - 1) & 1) * kBufBytes, lds + kOffVt + ((it - 1) & 1) * kVtBuf,
                                               lds + kOffOb + ((it - 1) & 1) * kObBuf, slab, n, grp, st, decay);
@@ -960,8 +980,8 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
             if (it < nchunks)
                 stage_values<kBeta>(lds + kOffVt + (it & 1) * kVtBuf, tile, lane, cur, t_begin + it * kChunk, g.t_end);
             if (!kSummary && it >= 2) {
-                const unsigned char *ob = lds + kOffOb + (it & 1) * kObBuf;
-                if (kBlock) store_outputs_block<kStage, 0, 2>(g, ob, t_begin + (it - 2) * kChunk, tile, lane, sl, feed);
+                unsigned char *ob = lds + kOffOb + (it & 1) * kObBuf;
+                if (kBlock && it <= nchunks + 1) finish_outputs_block<kStage, 0, 2>(g, ob, tile, lane, sl, feed);
 
             }
             if (kBlock && !kSummary && nchunks > 0) stage_prefetch<kStage, 0, 2>(g, t_begin + (it - 1) * kChunk, t_begin, tile, lane, sl);
@@ -972,13 +992,14 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
             state_prefetch<kBeta>(g, t_begin, tile, lane, pf);
             state_prefetch<kBeta>(g, t_begin + kChunk, tile, lane, pf_odd);
         }
+        const int last_it = nchunks + (kBlock ? 2 : 1);
         for (int it = 0;;) {
             iteration(it, pf);
             __syncthreads();
-            if (++it > nchunks + 1) break;
+            if (++it > last_it) break;
             iteration(it, pf_odd);
             __syncthreads();
-            if (++it > nchunks + 1) break;
+            if (++it > last_it) break;
         }
     }
 }
