@@ -391,9 +391,11 @@ __device__ __forceinline__ void sweep_dq(
         for (int it = 0; it < ntiles; ++it) {
             const int t0 = it * kTile;
             __syncthreads();                               // the previous tile is computed: its results are staged, its inputs free
-            if (it > 0) store_tile(t0 - kTile, stid);
             tile_stage<DV, kZBeta>(pf, t0, T, stid, has_beta, qs, ks, ls, us, ds);
             tile_prefetch<DV, kZBeta>(g, t0 + kTile, stid, has_beta, pf);   // clamped addresses; masked when staged
+            // the stores come after the next tile's loads are requested: memory operations of a wavefront retire in order and
+            // stores retire slowly, so a load must not queue behind a fresh store
+            if (it > 0) store_tile(t0 - kTile, stid);
             __syncthreads();
         }
         __syncthreads();
