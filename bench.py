@@ -31,7 +31,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (scaled by a plain copy kernel);
 # taken from the summaries under profiles/ (scan_mfma_kernel_layer_1p6b.md, decode_step_kernel_256x16.md).
-MEASURED_TRAFFIC_BYTES = {"scan_layer_1p6b": 1360.1e6, "decode_256x16": 547.6e6}   # profiles/*.md
+MEASURED_TRAFFIC_BYTES = {"scan_layer_1p6b": 1388.3e6, "decode_256x16": 54.8e6, "decode_512x16": 1094.8e6}   # profiles/*.md
 
 
 def warm_up(step, launches, min_seconds=0.08):
@@ -405,6 +405,35 @@ def bench_backward(w, rodimus, wl, dev, steps, warmup, zbeta=False):
             "tflops": flops / (ms * 1e-3) / 1e12, "finite": bool(torch.isfinite(out["dlog_alpha"]).all().item())}
 
 
+def bench_backward_gated(w, rodimus, wl, dev, steps, warmup):
+    """Backward pass of the gated scan over the layer workload (rodimus_chunk_scan_bwd_gated: cotangents of the raw q, k, v and
+    of the three pre-activations): key-side gate pass, backward of the scan, backward of the gate pass."""
+    d = wl.make_gated_scan_inputs(w.B, w.T, w.H, w.dk, w.dv, "bf16", seed=17)
+    g = {k: (None if v is None else v.to(dev)) for k, v in d.items()}
+    gen = torch.Generator(device="cpu").manual_seed(19)
+    d_o = torch.randn((w.B, w.T, w.H, w.dv), generator=gen).to(torch.bfloat16).to(dev)
+    dS_T = (0.1 * torch.randn((w.B, w.H, w.dk, w.dv), generator=gen)).to(dev)
+    need = int(rodimus.lib().rodimus_chunk_scan_bwd_gated_workspace_bytes(w.B, w.T, w.H, w.dk, w.dv, rodimus.BF16))
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    out = {}
+
+    def step():
+        out.update(rodimus.rodimus_chunk_scan_bwd_gated(g["q"], g["k"], g["v"], g["z_g"], g["z_tau"], g["z_beta"], g["S0"], d_o, dS_T,
+                                                        workspace=ws))
+
+    warm_up(step, min(warmup, 20), min_seconds=0.2)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n = max(5, steps // 10)
+    a.record()
+    for _ in range(n):
+        step()
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / n
+    return {"entry_point": "rodimus_chunk_scan_bwd_gated", "ms_per_step": ms, "tokens_per_s": w.tokens / (ms * 1e-3),
+            "workspace_bytes": need, "finite": bool(torch.isfinite(out["dz_g"].float()).all().item())}
+
+
 def cpu_baseline(w, inp, o_gpu, S_gpu):
     """fp64 oracle on the scan workload, timed on the host cores; also the parity check of the GPU result."""
     import numpy as np
@@ -502,16 +531,17 @@ def main():
             # the figure claimed against the HBM roofline is the all-HBM one: 512 sequences hold 512 MiB of state, twice the
             # last-level cache, so every byte of a step comes from and goes to HBM
             "roofline": {"bound": "hbm", "achieved": big["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": big["gbs"] / HBM_PEAK_GBS, "traffic": None,
+                         "frac": big["gbs"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES["decode_512x16"],
+                         "traffic_source": "profiles/decode_step_kernel_256x16.md (counter figure of the profile run)",
                          "kernel": "decode_step_kernel (streaming variant)", "algorithmic_bytes": big["algo_bytes"],
                          "launch_ms": big["launch_ms"], "workload": "512 sequences x 16 heads, 200 chained steps"},
             "cache_assisted_256_sequences": {
                 "GB_per_s_effective": dec["gbs"], "frac_of_hbm_peak": dec["gbs"] / HBM_PEAK_GBS, "ms_per_step": dec["launch_ms"],
                 "algorithmic_bytes": dec["algo_bytes"], "traffic": MEASURED_TRAFFIC_BYTES["decode_256x16"],
                 "traffic_source": "profiles/decode_step_kernel_256x16.md (counter figure of the profile run)",
-                "note": "256 sequences hold exactly 256 MiB of state, the size of the last-level cache: chained steps find part "
-                        "of it there, so this is an effective rate, not an HBM rate; with other layers running between two "
-                        "steps of a model it would not be reached"},
+                "note": "256 sequences hold exactly 256 MiB of state, the size of the last-level cache: chained steps find it "
+                        "there (a tenth of the algorithmic bytes reach HBM), so this is a cache rate, not an HBM rate; with "
+                        "other layers running between two steps of a model it would not be reached"},
         }
         if not args.skip_cpu_baseline:
             out["decode"]["cpu_baseline"] = decode_cpu_baseline(dw, wl)
@@ -532,6 +562,7 @@ def main():
         zb_bwd = bench_backward(w, rodimus, wl, dev, args.steps, args.warmup, zbeta=True)
         out["scan_backward_fused_value_gate"] = {k: zb_bwd[k] for k in ("entry_point", "ms_per_step", "tokens_per_s", "algorithmic_bytes",
                                                                        "GB_per_s", "hbm_frac", "finite")}
+        out["scan_backward_all_gates"] = bench_backward_gated(w, rodimus, wl, dev, args.steps, args.warmup)
         # the same layer at a micro-batch of two sequences: too few (batch, head) pairs to fill the chip, the call is cut
         # along the sequence
         import dataclasses
