@@ -308,6 +308,40 @@ def bench_block_scan(w, rodimus, wl, dev, steps, warmup):
             "GB_per_s": algo / (ms * 1e-3) / 1e9, "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
 
+def bench_whole_block_scan(w, rodimus, wl, dev, steps, warmup):
+    """The layer scan with both ends of the block fused in (rodimus_chunk_scan_fwd_gated_block): every gate taken as a bf16
+    pre-activation on the way in, feed-through and SiLU output gate on the way out; one launch."""
+    import numpy as np
+    d = wl.make_gated_scan_inputs(w.B, w.T, w.H, w.dk, w.dv, "bf16", seed=17)
+    g = {k: (None if v is None else v.to(dev)) for k, v in d.items()}
+    rng = np.random.Generator(np.random.PCG64(21))
+    shape = (w.B, w.T, w.H, w.dv)
+    x_prime = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(torch.bfloat16).to(dev)
+    z_gate = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(torch.bfloat16).to(dev)
+    dw = torch.from_numpy(rng.standard_normal((w.H, w.dv), dtype=np.float32)).to(dev)
+    o = torch.empty(shape, dtype=torch.bfloat16, device=dev)
+    S_T = torch.empty((w.B, w.H, w.dk, w.dv), dtype=torch.float32, device=dev)
+
+    def step():
+        rodimus.rodimus_chunk_scan_fwd_gated_block(g["q"], g["k"], g["v"], g["z_g"], g["z_tau"], g["z_beta"], g["S0"],
+                                                   x_prime=x_prime, d=dw, z_gate=z_gate, gate_act="silu", chunk=w.chunk, o=o, S_T=S_T)
+
+    warm_up(step, warmup)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(steps):
+        step()
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / steps
+    # q, k, z_g, z_tau; v, z_beta, x', z_gate, o; S0 and S_T
+    algo = w.token_heads * (4 * 2 * w.dk + 5 * 2 * w.dv) + 2 * w.B * w.H * w.dk * w.dv * 4
+    return {"entry_point": "rodimus_chunk_scan_fwd_gated_block",
+            "workload": "layer_1p6b, every gate as bf16 pre-activation, raw q and k, x' and z_gate (bf16), d fp32, SiLU gate",
+            "launches_per_call": 1, "ms_per_step": ms, "tokens_per_s": w.tokens / (ms * 1e-3), "algorithmic_bytes": algo,
+            "GB_per_s": algo / (ms * 1e-3) / 1e9, "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+
 def bench_short_conv(w, rodimus, wl, dev, steps=50, warmup=20, width=4):
     """The block's ShortConv over the layer workload's tokens: C = H * dv channels, width 4, SiLU, bf16 I/O."""
     C = w.H * w.dv
@@ -558,6 +592,8 @@ def main():
         out["scan_fused_all_gates"] = bench_gated_scan(w, rodimus, wl, dev, args.steps, args.warmup)
         out["scan_block_output"] = bench_block_scan(w, rodimus, wl, dev, args.steps, args.warmup)
         out["scan_block_output"]["vs_plain_scan"] = out["scan_block_output"]["ms_per_step"] / scan["launch_ms"]
+        out["scan_whole_block"] = bench_whole_block_scan(w, rodimus, wl, dev, args.steps, args.warmup)
+        out["scan_whole_block"]["vs_plain_scan"] = out["scan_whole_block"]["ms_per_step"] / scan["launch_ms"]
         out["scan_backward"] = bench_backward(w, rodimus, wl, dev, args.steps, args.warmup)
         zb_bwd = bench_backward(w, rodimus, wl, dev, args.steps, args.warmup, zbeta=True)
         out["scan_backward_fused_value_gate"] = {k: zb_bwd[k] for k in ("entry_point", "ms_per_step", "tokens_per_s", "algorithmic_bytes",

@@ -412,6 +412,26 @@ int rodimus_decode_step_gated(const void *q, const void *k, const void *v,
                               int N, int H, int dk, int dv, int io_dtype, void *stream);
 
 /*
+ * The whole block of Sec. 3.1.3 around the recurrence in one call: the gates and the pre-processing of q and k as in
+ * rodimus_chunk_scan_fwd_gated / rodimus_decode_step_gated (Sec. 3.1.2) AND the output stage of rodimus_chunk_scan_fwd_block /
+ * rodimus_decode_step_block (feed-through d .* x' and output gate act(z_gate)), all inside the kernel that runs the
+ * recurrence:
+ *     y_t = (q_t / sqrt(dk) S_t + d .* x'_t) .* act(z_gate_t)
+ * Arguments as in those calls (x_prime, z_gate may each be NULL; d is required with x_prime; z_beta may be NULL).
+ */
+int rodimus_chunk_scan_fwd_gated_block(const void *q, const void *k, const void *v,
+                                       const void *z_g, const void *z_tau, const void *z_beta, const float *S0,
+                                       const void *x_prime, const float *d, const void *z_gate, int gate_act,
+                                       void *o, float *S_T,
+                                       int B, int T, int H, int dk, int dv, int chunk, int io_dtype,
+                                       void *workspace, size_t workspace_bytes, void *stream);
+int rodimus_decode_step_gated_block(const void *q, const void *k, const void *v,
+                                    const void *z_g, const void *z_tau, const void *z_beta,
+                                    const void *x_prime, const float *d, const void *z_gate, int gate_act,
+                                    float *S, void *o,
+                                    int N, int H, int dk, int dv, int io_dtype, void *stream);
+
+/*
  * The two recurrence calls with the general transition of paper Sec. 3.1.1 (first equation of the section), which gates
  * the state along the value dimension as well:
  *     S_t = (alpha_t^T beta_t) .* S_{t-1} + k_t^T (beta_hat_t .* v_t),   o_t = q_t S_t

@@ -81,6 +81,10 @@ def lib() -> ctypes.CDLL:
         L.rodimus_chunk_scan_fwd_gated.restype = i
         L.rodimus_decode_step_gated.argtypes = [vp] * 8 + [i] * 5 + [vp]
         L.rodimus_decode_step_gated.restype = i
+        L.rodimus_chunk_scan_fwd_gated_block.argtypes = [vp] * 10 + [i] + [vp] * 2 + [i] * 7 + [vp, sz, vp]
+        L.rodimus_chunk_scan_fwd_gated_block.restype = i
+        L.rodimus_decode_step_gated_block.argtypes = [vp] * 9 + [i] + [vp] * 2 + [i] * 5 + [vp]
+        L.rodimus_decode_step_gated_block.restype = i
         L.rodimus_chunk_scan_fwd_general.argtypes = [vp] * 9 + [i] * 7 + [vp]
         L.rodimus_chunk_scan_fwd_general.restype = i
         L.rodimus_decode_step_general.argtypes = [vp] * 8 + [i] * 5 + [vp]
@@ -326,6 +330,71 @@ def rodimus_decode_step_gated(q, k, v, z_g, z_tau, z_beta, S, *, o=None):
     with torch.cuda.device(dev):
         _check(lib().rodimus_decode_step_gated(_ptr(q), _ptr(k), _ptr(v), _ptr(z_g), _ptr(z_tau), _ptr(z_beta), _ptr(S), _ptr(o),
                                                N, H, dk, dv, _DTYPES[io], _stream(dev)))
+    return o
+
+
+def rodimus_chunk_scan_fwd_gated_block(q, k, v, z_g, z_tau, z_beta=None, S0=None, *, x_prime=None, d=None, z_gate=None,
+                                       gate_act="sigmoid", chunk=64, o=None, S_T=None, want_state=True, workspace=None):
+    """The whole block around the recurrence in one call: gates and pre-processing as ``rodimus_chunk_scan_fwd_gated``, output
+    stage as ``rodimus_chunk_scan_fwd_block``: y = (q / sqrt(dk) S + d .* x') .* act(z_gate).  Returns (y, S_T)."""
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_chunk_scan_fwd_gated_block needs device tensors (no CPU path exists)")
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    dev, io = q.device, q.dtype
+    for name, t in (("q", q), ("k", k), ("z_g", z_g), ("z_tau", z_tau)):
+        if t is None:
+            raise ValueError(f"{name} is required")
+        _require(t, name, (B, T, H, dk), io, dev)
+    for name, t in (("v", v), ("z_beta", z_beta), ("x_prime", x_prime), ("z_gate", z_gate)):
+        _require(t, name, (B, T, H, dv), io, dev)
+    _require(d, "d", (H, dv), torch.float32, dev)
+    _require(S0, "S0", (B, H, dk, dv), torch.float32, dev)
+    if o is None:
+        o = torch.empty((B, T, H, dv), dtype=io, device=dev)
+    _require(o, "o", (B, T, H, dv), io, dev)
+    if S_T is None and want_state:
+        S_T = torch.empty((B, H, dk, dv), dtype=torch.float32, device=dev)
+    _require(S_T, "S_T", (B, H, dk, dv), torch.float32, dev)
+    need = rodimus_chunk_scan_workspace_bytes(B, T, H, dk, dv, chunk, io)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_chunk_scan_fwd_gated_block(_ptr(q), _ptr(k), _ptr(v), _ptr(z_g), _ptr(z_tau), _ptr(z_beta), _ptr(S0),
+                                                        _ptr(x_prime), _ptr(d), _ptr(z_gate), _GATE_ACTS[gate_act], _ptr(o), _ptr(S_T),
+                                                        B, T, H, dk, dv, int(chunk), _DTYPES[io], _ptr(workspace), ws_bytes,
+                                                        _stream(dev)))
+    return o, S_T
+
+
+def rodimus_decode_step_gated_block(q, k, v, z_g, z_tau, z_beta, S, *, x_prime=None, d=None, z_gate=None, gate_act="sigmoid",
+                                    o=None):
+    """One recurrent step of the whole block (see ``rodimus_chunk_scan_fwd_gated_block``); S updated in place.  Returns y."""
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_decode_step_gated_block needs device tensors (no CPU path exists)")
+    N, H, dk = q.shape
+    dv = v.shape[-1]
+    dev, io = q.device, q.dtype
+    for name, t in (("q", q), ("k", k), ("z_g", z_g), ("z_tau", z_tau)):
+        if t is None:
+            raise ValueError(f"{name} is required")
+        _require(t, name, (N, H, dk), io, dev)
+    for name, t in (("v", v), ("z_beta", z_beta), ("x_prime", x_prime), ("z_gate", z_gate)):
+        _require(t, name, (N, H, dv), io, dev)
+    _require(d, "d", (H, dv), torch.float32, dev)
+    _require(S, "S", (N, H, dk, dv), torch.float32, dev)
+    if o is None:
+        o = torch.empty((N, H, dv), dtype=io, device=dev)
+    _require(o, "o", (N, H, dv), io, dev)
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_decode_step_gated_block(_ptr(q), _ptr(k), _ptr(v), _ptr(z_g), _ptr(z_tau), _ptr(z_beta), _ptr(x_prime),
+                                                     _ptr(d), _ptr(z_gate), _GATE_ACTS[gate_act], _ptr(S), _ptr(o), N, H, dk, dv,
+                                                     _DTYPES[io], _stream(dev)))
     return o
 
 

@@ -34,7 +34,8 @@ def test_every_declared_symbol_is_exported(L):
             "rodimus_chunk_scan_fwd_general", "rodimus_decode_step_general",
             "rodimus_chunk_scan_varlen_bwd", "rodimus_chunk_scan_varlen_bwd_workspace_bytes",
             "rodimus_chunk_scan_fwd_noalloc", "rodimus_chunk_scan_fwd_noalloc_scratch_bytes",
-            "rodimus_chunk_scan_bwd_gated", "rodimus_chunk_scan_bwd_gated_workspace_bytes"} <= declared
+            "rodimus_chunk_scan_bwd_gated", "rodimus_chunk_scan_bwd_gated_workspace_bytes",
+            "rodimus_chunk_scan_fwd_gated_block", "rodimus_decode_step_gated_block"} <= declared
     for name in declared:
         assert hasattr(L, name), name
 
@@ -288,6 +289,30 @@ def test_gated_calls_validation(L):
     assert scan(B=1, T=32768, H=16, dk=64, dv=256, chunk=64, io=rodimus.BF16, q=0x10000000, k=0x20000000, v=0x30000000,
                 zg=0x40000000, zt=0x50000000, zb=0x60000000, S0=None, o=0x80000000, S_T=None) == E_WS
     assert scan(B=0) == OK and dec(N=0) == OK and scan(T=0, S_T=None) == OK
+
+
+def test_gated_block_calls_validation(L):
+    p = lambda x: None if x is None else ctypes.c_void_p(x)
+
+    def scan(o=0xA0000, S_T=0xB0000, act=0, **kw):
+        a = dict(q=0x10000, k=0x20000, v=0x30000, zg=0x40000, zt=0x48000, zb=0x50000, S0=0x60000, x=0x70000, d=0x80000, z=0x90000)
+        a.update(kw)
+        return L.rodimus_chunk_scan_fwd_gated_block(p(a["q"]), p(a["k"]), p(a["v"]), p(a["zg"]), p(a["zt"]), p(a["zb"]), p(a["S0"]),
+                                                    p(a["x"]), p(a["d"]), p(a["z"]), act, p(o), p(S_T), 1, 4, 1, 16, 32, 4, rodimus.F32,
+                                                    None, 0, None)
+
+    def dec(o=0xA0000, S=0x100000, act=1, **kw):
+        a = dict(q=0x10000, k=0x20000, v=0x30000, zg=0x40000, zt=0x48000, zb=0x50000, x=0x70000, d=0x80000, z=0x90000)
+        a.update(kw)
+        return L.rodimus_decode_step_gated_block(p(a["q"]), p(a["k"]), p(a["v"]), p(a["zg"]), p(a["zt"]), p(a["zb"]), p(a["x"]), p(a["d"]),
+                                                 p(a["z"]), act, p(S), p(o), 2, 2, 16, 32, rodimus.BF16, None)
+
+    assert scan(act=5) == E_DTYPE and dec(act=-1) == E_DTYPE
+    assert scan(zg=None) == E_NULL and scan(zt=None) == E_NULL and dec(zt=None) == E_NULL
+    assert scan(d=None) == E_NULL and dec(d=None) == E_NULL                  # feed-through without its weights
+    assert scan(x=0x70008) == E_ALIGN and dec(z=0x90004) == E_ALIGN
+    assert scan(o=0x70000) == E_ALIAS and scan(o=0x40000) == E_ALIAS and scan(S_T=0x90000) == E_ALIAS
+    assert dec(o=0x90000) == E_ALIAS and dec(S=0x48000) == E_ALIAS
 
 
 def test_general_transition_calls_validation(L):
