@@ -367,9 +367,10 @@ def bench_short_conv(w, rodimus, wl, dev, steps=50, warmup=20, width=4):
             "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "tokens_per_s": w.B * w.T / (ms * 1e-3)}
 
 
-def bench_varlen(w, rodimus, wl, dev, steps, warmup, n_seq=64, longest_first=False):
+def bench_varlen(w, rodimus, wl, dev, steps, warmup, n_seq=64, longest_first=False, cut=False):
     """Packed variable-length prefill: n_seq sequences with a log-uniform length mix and the token count of the layer
-    workload (rodimus_chunk_scan_varlen_fwd, states written to a cache)."""
+    workload (rodimus_chunk_scan_varlen_fwd, states written to a cache; with `cut` rodimus_chunk_scan_varlen_fwd_cut, whose
+    kernels cut the sequences into segments that run side by side)."""
     lengths = wl.serving_length_mix(n_seq, w.B * w.T)
     if longest_first:       # workgroups start in sequence order: longest first is the better schedule
         lengths = sorted(lengths, reverse=True)
@@ -378,9 +379,16 @@ def bench_varlen(w, rodimus, wl, dev, steps, warmup, n_seq=64, longest_first=Fal
     o = torch.empty((w.B * w.T, w.H, w.dv), dtype=torch.bfloat16, device=dev)
     S_T = torch.empty((n_seq, w.H, w.dk, w.dv), dtype=torch.float32, device=dev)
 
+    need = rodimus.rodimus_chunk_scan_varlen_workspace_bytes(n_seq, w.B * w.T, w.H, w.dk, w.dv, w.chunk, torch.bfloat16) if cut else 0
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+
     def step():
-        rodimus.rodimus_chunk_scan_varlen_fwd(g["q"], g["k"], g["v"], g["log_alpha"], g["cu_seqlens"], beta=g["beta"],
-                                              S0=g["S0"], o=o, S_T=S_T)
+        if cut:
+            rodimus.rodimus_chunk_scan_varlen_fwd_cut(g["q"], g["k"], g["v"], g["log_alpha"], g["cu_seqlens"], beta=g["beta"],
+                                                      S0=g["S0"], o=o, S_T=S_T, workspace=ws)
+        else:
+            rodimus.rodimus_chunk_scan_varlen_fwd(g["q"], g["k"], g["v"], g["log_alpha"], g["cu_seqlens"], beta=g["beta"],
+                                                  S0=g["S0"], o=o, S_T=S_T)
 
     warm_up(step, warmup)
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -391,7 +399,7 @@ def bench_varlen(w, rodimus, wl, dev, steps, warmup, n_seq=64, longest_first=Fal
     torch.cuda.synchronize()
     ms = a.elapsed_time(b) / steps
     algo = w.token_heads * (8 * w.dk + 8 * w.dv) + 2 * n_seq * w.H * w.dk * w.dv * 4
-    return {"entry_point": "rodimus_chunk_scan_varlen_fwd",
+    return {"entry_point": "rodimus_chunk_scan_varlen_fwd_cut" if cut else "rodimus_chunk_scan_varlen_fwd",
             "workload": f"{n_seq} sequences, lengths {min(lengths)}..{max(lengths)} (log-uniform mix), {w.B * w.T} tokens, "
                         f"H={w.H} dk={w.dk} dv={w.dv}",
             "ms_per_step": ms, "tokens_per_s": w.B * w.T / (ms * 1e-3), "GB_per_s": algo / (ms * 1e-3) / 1e9,
@@ -610,6 +618,10 @@ def main():
         lf = bench_varlen(w, rodimus, wl, dev, args.steps, args.warmup, longest_first=True)
         out["serving_prefill_varlen"]["sequences_sorted_longest_first"] = {
             k: lf[k] for k in ("ms_per_step", "tokens_per_s", "GB_per_s", "hbm_frac")}
+        # few long sequences: the packed call lasts as long as its longest sequence unless the kernels cut the sequences
+        few = bench_varlen(w, rodimus, wl, dev, args.steps, args.warmup, n_seq=8)
+        few_cut = bench_varlen(w, rodimus, wl, dev, args.steps, args.warmup, n_seq=8, cut=True)
+        out["serving_prefill_few_long_sequences"] = {**few_cut, "uncut_ms_per_step": few["ms_per_step"]}
         others = {}
         for ow in (wl.MID, wl.LONG_CONTEXT):
             r, _, _, _ = bench_scan(ow, args.steps, args.warmup, rodimus, wl, dev)

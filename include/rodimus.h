@@ -222,7 +222,7 @@ typedef enum {
  *                                                    allowed (S_T = S0, no output rows).
  *
  * One workgroup set per (sequence, head): no workspace, no sequence split (a batch of few long sequences is better
- * served by rodimus_chunk_scan_fwd per sequence).  With up to 64 sequences the workgroups take the sequences longest
+ * served by rodimus_chunk_scan_varlen_fwd_cut).  With up to 64 sequences the workgroups take the sequences longest
  * first, whatever their order in the batch.  Shapes, kernel families, alignment (16 bytes, cu_seqlens included),
  * aliasing rules and status codes as for rodimus_chunk_scan_fwd; an unknown beta_kind gives RODIMUS_ERR_DTYPE.
  */
@@ -231,6 +231,40 @@ int rodimus_chunk_scan_varlen_fwd(const void *q, const void *k, const void *v,
                                   void *o, float *S_T,
                                   const int *cu_seqlens, int N, int total_tokens,
                                   int H, int dk, int dv, int chunk, int io_dtype, void *stream);
+
+/*
+ * rodimus_chunk_scan_varlen_fwd for a packed batch dominated by FEW LONG sequences (a handful of long prompts, or one
+ * long prompt among short ones): one workgroup set per (sequence, head) lasts as long as the longest sequence and leaves
+ * most of the chip idle meanwhile.  Here every sequence is cut into segments of a fixed length chosen from total_tokens
+ * alone (the lengths stay on the device: every workgroup finds its sequence and segment from cu_seqlens), and the
+ * segments run side by side: the state increment and decay of every segment (one pass over k, v and the gates), the
+ * chain of entering states along each sequence, then the scan proper of every segment from its entering state -- the
+ * split of the recurrence across chunks that the appendix on the chunkwise form states, applied at segment level.
+ * Same results as rodimus_chunk_scan_varlen_fwd to rounding (the state passes through one more fp32 sum per segment).
+ * The cut reads k, v and the gates of all but each sequence's last segment twice, so its duration depends on
+ * total_tokens and hardly on the lengths; which call is faster is the caller's decision (it built cu_seqlens).  A
+ * segment has total_tokens * H * (dv / 128) / 256 tokens (the share of one of the 256 compute units), rounded up to a
+ * multiple of 64 and at least 512; as a rule this call wins when the longest sequence is longer than about 2.5
+ * segments (measured at H = 16, dv = 256, 32768 tokens, segments of 4096: 405 us whatever the lengths, against 340 us
+ * uncut when the longest sequence has 8192 tokens, 650 us at 16311 and 1020 us at 25045).
+ *
+ *   workspace   rodimus_chunk_scan_varlen_workspace_bytes(...) bytes of device memory, 16-byte aligned, contents
+ *               undefined before and after; must not overlap any other argument.  The size depends on N and
+ *               total_tokens only (the largest number of segments the batch can have); 0 = this batch is not cut
+ *               (under 1024 tokens in all, or a shape the matrix-core kernels do not take) and the call is then
+ *               exactly rodimus_chunk_scan_varlen_fwd; workspace may be NULL.
+ *
+ * Every other argument, layout, aliasing rule and status code as for rodimus_chunk_scan_varlen_fwd (S_T may be S0);
+ * RODIMUS_ERR_WORKSPACE if the workspace is missing or too small, RODIMUS_ERR_ALIAS if it overlaps another argument.
+ */
+int rodimus_chunk_scan_varlen_fwd_cut(const void *q, const void *k, const void *v,
+                                      const float *log_alpha, const void *beta, int beta_kind, const float *S0,
+                                      void *o, float *S_T,
+                                      const int *cu_seqlens, int N, int total_tokens,
+                                      int H, int dk, int dv, int chunk, int io_dtype,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
+size_t rodimus_chunk_scan_varlen_workspace_bytes(int N, int total_tokens, int H, int dk, int dv, int chunk, int io_dtype);
 
 /* Activation of the output gate in the *_block calls. */
 typedef enum {

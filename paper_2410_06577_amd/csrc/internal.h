@@ -307,6 +307,8 @@ size_t scan_generic_lds_bytes(int dk, int chunk, bool general = false);
 hipError_t launch_scan_mfma(const ScanArgs &a);
 bool scan_mfma_supports(int dk, int dv, int chunk, int io_dtype);
 size_t scan_mfma_workspace_bytes(int B, int T, int H, int dv);
+// packed batch of N sequences cut along the sequences by the kernels; 0: the batch is not cut
+size_t scan_mfma_packed_workspace_bytes(int N, int total_tokens, int H, int dv);
 // State entering each of nseg sequence segments (seg_tokens a multiple of 64) of a dense bf16 batch with dk = 64:
 // slots [nseg][B*H][64][dv] and the segment decays gamma [nseg-1][B*H][64], fp32 (used by the backward pass); beta: fp32
 // gate values or, with beta_preact, bf16 pre-activations (then not NULL)

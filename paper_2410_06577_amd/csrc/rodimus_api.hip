@@ -44,7 +44,7 @@ int scan_entry(const void *q, const void *k, const void *v, const float *log_alp
                const float *S0, void *o, float *S_T, int B, int T, int H, int dk, int dv, int chunk, int io_dtype,
                void *workspace, size_t workspace_bytes, void *stream, bool packed = false, const int *cu_seqlens = nullptr,
                OutputStage stage = OutputStage{nullptr, nullptr, nullptr, 0}, bool gated = false, const void *z_g = nullptr,
-               const void *z_tau = nullptr, bool general = false, const float *log_beta_t = nullptr)
+               const void *z_tau = nullptr, bool general = false, const float *log_beta_t = nullptr, bool packed_cut = false)
 {
     const int shape = scan_shape_status(B, T, H, dk, dv, chunk, io_dtype);
     if (shape != RODIMUS_OK) return shape;
@@ -89,7 +89,9 @@ int scan_entry(const void *q, const void *k, const void *v, const float *log_alp
 
     // the general transition runs on the any-shape kernel only
     const bool mfma = !general && scan_mfma_supports(dk, dv, chunk, io_dtype);
-    const size_t need = (!packed && mfma) ? scan_mfma_workspace_bytes(B, T, H, dv) : 0;
+    // a packed batch is cut along its sequences only through the entry point that brings a workspace for it
+    const size_t need = !mfma ? 0 : !packed ? scan_mfma_workspace_bytes(B, T, H, dv)
+                                : packed_cut ? scan_mfma_packed_workspace_bytes(B, T, H, dv) : 0;
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return RODIMUS_ERR_WORKSPACE;
     if (need > 0) {
         // the kernels write the first `need` bytes of the workspace while they read the inputs and write the outputs
@@ -101,7 +103,7 @@ int scan_entry(const void *q, const void *k, const void *v, const float *log_alp
     }
 
     ScanArgs a{q, k, v, log_alpha, beta, beta_preact, S0, o, S_T, B, T, H, dk, dv, chunk, io_dtype,
-               packed ? cu_seqlens : nullptr, stage, workspace, workspace_bytes, static_cast<hipStream_t>(stream)};
+               packed ? cu_seqlens : nullptr, stage, need > 0 ? workspace : nullptr, workspace_bytes, static_cast<hipStream_t>(stream)};
     if (gated) { a.log_alpha = nullptr; a.z_g = z_g; a.z_tau = z_tau; }
     if (general) a.log_beta_t = log_beta_t;
     const hipError_t err = mfma ? launch_scan_mfma(a) : launch_scan_generic(a);
@@ -209,6 +211,23 @@ int rodimus_chunk_scan_varlen_fwd(const void *q, const void *k, const void *v, c
     if (beta_kind != RODIMUS_BETA_VALUES && beta_kind != RODIMUS_BETA_PREACTIVATION) return RODIMUS_ERR_DTYPE;
     return scan_entry(q, k, v, log_alpha, beta, beta_kind == RODIMUS_BETA_PREACTIVATION, S0, o, S_T, N, total_tokens, H,
                       dk, dv, chunk, io_dtype, nullptr, 0, stream, true, cu_seqlens);
+}
+
+size_t rodimus_chunk_scan_varlen_workspace_bytes(int N, int total_tokens, int H, int dk, int dv, int chunk, int io_dtype)
+{
+    if (scan_shape_status(N, total_tokens, H, dk, dv, chunk, io_dtype) != RODIMUS_OK) return 0;
+    return scan_mfma_supports(dk, dv, chunk, io_dtype) ? scan_mfma_packed_workspace_bytes(N, total_tokens, H, dv) : 0;
+}
+
+int rodimus_chunk_scan_varlen_fwd_cut(const void *q, const void *k, const void *v, const float *log_alpha, const void *beta,
+                                      int beta_kind, const float *S0, void *o, float *S_T, const int *cu_seqlens, int N,
+                                      int total_tokens, int H, int dk, int dv, int chunk, int io_dtype, void *workspace,
+                                      size_t workspace_bytes, void *stream)
+{
+    if (beta_kind != RODIMUS_BETA_VALUES && beta_kind != RODIMUS_BETA_PREACTIVATION) return RODIMUS_ERR_DTYPE;
+    return scan_entry(q, k, v, log_alpha, beta, beta_kind == RODIMUS_BETA_PREACTIVATION, S0, o, S_T, N, total_tokens, H,
+                      dk, dv, chunk, io_dtype, workspace, workspace_bytes, stream, true, cu_seqlens,
+                      OutputStage{nullptr, nullptr, nullptr, 0}, false, nullptr, nullptr, false, nullptr, true);
 }
 
 int rodimus_chunk_scan_fwd_block(const void *q, const void *k, const void *v, const float *log_alpha, const void *beta,

@@ -790,12 +790,27 @@ __device__ __forceinline__ void state_chunk(const unsigned char *buf, const unsi
 // Workspace of a sequence-split call: `nseg` state slots [seg][B*H][64][dv] fp32 followed by the segment decays
 // [nseg-1][B*H][64] fp32.  Slot 0 receives the initial state, slot s > 0 first the state increment of segment s-1
 // (summary pass), then the state entering segment s (segment_state_scan_kernel), which the main pass reads.
+//
+// Packed batch cut on the device (`packed_cut`): the host knows only the total token count, so it fixes the segment length
+// and an upper bound on the number of segments; sequence b owns max(1, ceil(len_b / seg_tokens)) consecutive slots, counted
+// from the sequences before it.  Slots are [slot][H][64][dv], decays [slot][H][64]; `nseg` is then the slot bound.
 struct SegmentPlan {
     int nseg;              // 1: no split, no workspace
     int seg_tokens;        // tokens per segment, a multiple of 64
     float *slots;
     float *gamma;
+    bool packed_cut;
 };
+
+// Row range of sequence b of a packed batch; every entry is clamped to the tensor so that a corrupt table cannot take an
+// access outside it.
+__device__ __forceinline__ void packed_rows(const int *__restrict__ cu_seqlens, int b, int total_tokens, int &first, int &last)
+{
+    first = min(max(cu_seqlens[b], 0), total_tokens);
+    last = min(max(cu_seqlens[b + 1], first), total_tokens);
+}
+
+__device__ __forceinline__ int packed_segments(int len, int seg_tokens) { return max(1, (len + seg_tokens - 1) / seg_tokens); }
 
 // kSummary = false: the scan proper over this workgroup's segment (blockIdx.z), reading its entering state.
 // kSummary = true : same walk from a zero state without q, scores or outputs; leaves the segment's state
@@ -816,9 +831,37 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, grp = lane >> 4;
     int bh = blockIdx.x, col_tile = blockIdx.y;
-    const int seg = blockIdx.z;
-    const int BH = gridDim.x;
-    if (!kSummary && cu_seqlens == nullptr && gridDim.y == 1 && gridDim.z == 1 && dv > kColTile) {
+    int seg = blockIdx.z;                      // slot of the workspace this segment's entering state sits in
+    int BH = gridDim.x, slot_bh = bh;          // (batch, head) pairs per slot and this workgroup's index among them
+    bool last_seg = seg == plan.nseg - 1;
+    int t_begin = seg * plan.seg_tokens;
+    size_t tok0 = 0;
+    if (plan.packed_cut) {
+        // Flat grid over (slot, head, column tile).  Which sequence the slot belongs to follows from the lengths of the
+        // sequences before it: a short walk (the cut is only made when the batch holds few sequences), the same in every
+        // lane, out of scalar registers.
+        const int col_tiles = dv / kColTile;
+        col_tile = blockIdx.x % col_tiles;
+        const int rest = blockIdx.x / col_tiles, slot = rest / H;
+        int b = -1, before = 0, first = 0, last = 0, count = 0;
+        for (int i = 0; i < total_seqs; ++i) {
+            packed_rows(cu_seqlens, i, total_tokens, first, last);
+            count = packed_segments(last - first, plan.seg_tokens);
+            if (slot < before + count) { b = i; break; }
+            before += count;
+        }
+        if (b < 0) return;                                   // the grid covers the largest possible number of slots
+        const int j = slot - before;                         // segment j of `count` of sequence b
+        last_seg = j == count - 1;
+        // nothing continues from a sequence's last segment; with a valid table the segments fit the slots, a corrupt one
+        // (overlapping sequences) must not reach past them
+        if (kSummary && (last_seg || slot + 1 >= plan.nseg)) return;
+        bh = __builtin_amdgcn_readfirstlane(b * H + rest % H);
+        seg = slot; BH = H; slot_bh = rest % H;
+        t_begin = j * plan.seg_tokens;
+        tok0 = first;
+        T = last - first;
+    } else if (!kSummary && cu_seqlens == nullptr && gridDim.y == 1 && gridDim.z == 1 && dv > kColTile) {
         // Dense batch with more workgroups than compute units, launched flat: workgroups go round-robin over the eight XCDs
         // (each with its own L2), so in every run of 8 * col_tiles workgroups the column tiles of a (batch, head) are 8
         // apart: on the same XCD and started together, they share q, k and the gates in its L2.
@@ -826,8 +869,8 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
         col_tile = (blockIdx.x / 8) % col_tiles;
         bh = (blockIdx.x / (8 * col_tiles)) * 8 + blockIdx.x % 8;
         if (bh >= total_seqs * H) return;                   // the grid is rounded up to whole runs
-    }
-    if (!kSummary && cu_seqlens != nullptr) {
+        slot_bh = bh;
+    } else if (!kSummary && cu_seqlens != nullptr) {
         // Packed batch, launched as a flat grid: the column tiles of one (sequence, head) are neighbours in dispatch order
         // (they read the same q, k and gates while those are in the cache), and the workgroups take the sequences by
         // descending length (small batches).
@@ -836,6 +879,7 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
         const int slot = blockIdx.x / col_tiles, rank = slot / H;
         const int b = sequence_by_length_rank(cu_seqlens, nseq, total_tokens, rank, reinterpret_cast<int *>(lds));   // the dynamic LDS is free until the walk starts
         bh = __builtin_amdgcn_readfirstlane(b * H + slot % H);      // the same in every lane: keeps the row bases in scalar registers
+        slot_bh = bh;
     }
 
     Geometry g;
@@ -849,18 +893,18 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
     g.H = H; g.dv = dv;
     g.h = bh % H; g.j0 = col_tile * kColTile;
     g.tok0 = (size_t)(bh / H) * T;
-    if (cu_seqlens != nullptr) {
-        // packed variable-length batch: sequence bh / H owns the token rows [cu[b], cu[b+1]); the bounds are clamped
-        // to the tensor so that a corrupt table cannot take an access outside it
-        const int first = min(max(cu_seqlens[bh / H], 0), total_tokens);
-        const int last = min(max(cu_seqlens[bh / H + 1], first), total_tokens);
+    if (plan.packed_cut) {
+        g.tok0 = tok0;
+    } else if (cu_seqlens != nullptr) {
+        // packed variable-length batch: sequence bh / H owns the token rows [cu[b], cu[b+1])
+        int first, last;
+        packed_rows(cu_seqlens, bh / H, total_tokens, first, last);
         g.tok0 = first;
         T = last - first;
     }
-    const int t_begin = seg * plan.seg_tokens;
     g.t_end = min(T, t_begin + plan.seg_tokens);
 
-    const int nchunks = (g.t_end - t_begin + kChunk - 1) / kChunk;
+    const int nchunks = max(0, (g.t_end - t_begin + kChunk - 1) / kChunk);
     const size_t slot_elems = (size_t)BH * kK * dv;
 
     // Every role runs nchunks + 2 iterations with one barrier each.  Iteration `it`: the gate wavefronts build chunk `it`,
@@ -918,10 +962,12 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
         const int slab = wave - 4;
         __builtin_amdgcn_s_setprio(PRIO_STATE);
         StateSlab st;
-        const size_t state_base = (size_t)bh * kK * dv + g.j0 + 32 * slab;
+        // offsets of this wavefront's slab in the caller's state tensors and inside a workspace slot
+        const size_t cache_base = (size_t)bh * kK * dv + g.j0 + 32 * slab, slot_base = (size_t)slot_bh * kK * dv + g.j0 + 32 * slab;
         // entering state: zero (summary), the caller's S0 (no split), or this segment's workspace slot.  The state is read
         // once here and written once at the end: streaming accesses
-        const float *S_in = kSummary ? nullptr : (plan.nseg > 1 ? plan.slots + seg * slot_elems : S0);
+        const float *S_in = kSummary ? nullptr
+                                     : (plan.nseg > 1 ? plan.slots + seg * slot_elems + slot_base : (S0 != nullptr ? S0 + cache_base : nullptr));
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
@@ -929,7 +975,7 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
                     st.S[kt][ct][r] = (S_in != nullptr)
-                                          ? __builtin_nontemporal_load(S_in + state_base + (size_t)slab_channel(kt, 4 * grp + r) * dv + slab_column(ct, n))
+                                          ? __builtin_nontemporal_load(S_in + (size_t)slab_channel(kt, 4 * grp + r) * dv + slab_column(ct, n))
                                           : 0.f;
         refresh_operands(st);
         floatx4_t decay[4];       // summary pass: product of the tile decays for this lane's state rows
@@ -949,7 +995,8 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
             __syncthreads();
         }
 
-        float *S_out = kSummary ? plan.slots + (size_t)(seg + 1) * slot_elems : (seg == plan.nseg - 1 ? S_T : nullptr);
+        float *S_out = kSummary ? plan.slots + (size_t)(seg + 1) * slot_elems + slot_base
+                                : (last_seg && S_T != nullptr ? S_T + cache_base : nullptr);
         if (S_out != nullptr) {
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt)
@@ -957,10 +1004,10 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
                 for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
-                        __builtin_nontemporal_store(st.S[kt][ct][r], S_out + state_base + (size_t)slab_channel(kt, 4 * grp + r) * dv + slab_column(ct, n));
+                        __builtin_nontemporal_store(st.S[kt][ct][r], S_out + (size_t)slab_channel(kt, 4 * grp + r) * dv + slab_column(ct, n));
         }
         if (kSummary && col_tile == 0 && slab == 0 && n == 0) {
-            float *gam = plan.gamma + ((size_t)seg * BH + bh) * kK;
+            float *gam = plan.gamma + ((size_t)seg * BH + slot_bh) * kK;
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt) *reinterpret_cast<floatx4_t *>(gam + slab_channel(kt, 4 * grp)) = decay[kt];
         }
@@ -1006,35 +1053,58 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
 
 // Entering state of every segment from the summary pass: slot 0 = S0 (or zero), and for s >= 1
 // slot s <- gamma[s-1] .* slot[s-1] + slot[s] (the increment left there by the summary pass).  One thread per
-// four adjacent state elements; the segments are walked in order.
-__global__ __launch_bounds__(256) void segment_state_scan_kernel(const float *S0, SegmentPlan plan, int dv, size_t quads_per_slot)
+// four adjacent state elements; the segments are walked in order.  With a packed batch cut on the device the thread
+// first finds the slots of its sequence (the first one and how many) from the lengths before it.
+__global__ __launch_bounds__(256) void segment_state_scan_kernel(const float *S0, SegmentPlan plan, int dv, size_t quads_per_slot,
+                                                                 const int *__restrict__ cu_seqlens, int total_seqs, int total_tokens)
 {
     const size_t e4 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e4 >= quads_per_slot) return;
-    const size_t elem = e4 * 4;                           // element index inside a slot: ((bh * 64) + n) * dv + column
-    const size_t row = elem / dv;                         // bh * 64 + n
-    floatx4_t s = (S0 != nullptr) ? *reinterpret_cast<const floatx4_t *>(S0 + elem) : floatx4_t{0.f, 0.f, 0.f, 0.f};
     const size_t slot_elems = quads_per_slot * 4;
-    *reinterpret_cast<floatx4_t *>(plan.slots + elem) = s;
+    size_t elem = e4 * 4;                                 // element index inside a slot: ((bh * 64) + n) * dv + column
+    size_t first_slot = 0;
+    int count = plan.nseg;
+    if (plan.packed_cut) {
+        // here a slot holds the H heads of ONE sequence and e4 runs over [sequence][slot element]
+        const int b = (int)(e4 / quads_per_slot);
+        if (b >= total_seqs) return;
+        elem = (e4 % quads_per_slot) * 4;
+        for (int i = 0; i <= b; ++i) {
+            int first, last;
+            packed_rows(cu_seqlens, i, total_tokens, first, last);
+            count = packed_segments(last - first, plan.seg_tokens);
+            if (i < b) first_slot += count;
+        }
+        if (first_slot >= (size_t)plan.nseg) return;         // only with a corrupt table: stay inside the slots
+        count = min(count, plan.nseg - (int)first_slot);
+        S0 = (S0 != nullptr) ? S0 + (size_t)b * slot_elems : nullptr;
+    } else if (e4 >= quads_per_slot) {
+        return;
+    }
+    const size_t row = elem / dv;                         // bh * 64 + n
+    const size_t rows_per_slot = slot_elems / dv;
+    float *slots = plan.slots + first_slot * slot_elems;
+    const float *gamma = plan.gamma + first_slot * rows_per_slot;
+    floatx4_t s = (S0 != nullptr) ? *reinterpret_cast<const floatx4_t *>(S0 + elem) : floatx4_t{0.f, 0.f, 0.f, 0.f};
+    *reinterpret_cast<floatx4_t *>(slots + elem) = s;
     // eight segments at a time: their increments and decays are requested together, so that the walk costs one memory
     // latency per eight segments and not one per segment
     constexpr int kBatch = 8;
-    for (int s0 = 1; s0 < plan.nseg; s0 += kBatch) {
+    for (int s0 = 1; s0 < count; s0 += kBatch) {
         floatx4_t inc[kBatch];
         float gmm[kBatch];
 #pragma unroll
         for (int i = 0; i < kBatch; ++i) {
-            const int sg = min(s0 + i, plan.nseg - 1);          // past the end: the last segment again, not used
-            inc[i] = *reinterpret_cast<const floatx4_t *>(plan.slots + (size_t)sg * slot_elems + elem);
-            gmm[i] = plan.gamma[(size_t)(sg - 1) * (slot_elems / dv) + row];
+            const int sg = min(s0 + i, count - 1);          // past the end: the last segment again, not used
+            inc[i] = *reinterpret_cast<const floatx4_t *>(slots + (size_t)sg * slot_elems + elem);
+            gmm[i] = gamma[(size_t)(sg - 1) * rows_per_slot + row];
         }
 #pragma unroll
         for (int i = 0; i < kBatch; ++i) {
             const int sg = s0 + i;
-            if (sg < plan.nseg) {
+            if (sg < count) {
                 s[0] = fmaf(gmm[i], s[0], inc[i][0]); s[1] = fmaf(gmm[i], s[1], inc[i][1]);
                 s[2] = fmaf(gmm[i], s[2], inc[i][2]); s[3] = fmaf(gmm[i], s[3], inc[i][3]);
-                *reinterpret_cast<floatx4_t *>(plan.slots + (size_t)sg * slot_elems + elem) = s;
+                *reinterpret_cast<floatx4_t *>(slots + (size_t)sg * slot_elems + elem) = s;
             }
         }
     }
@@ -1061,6 +1131,23 @@ SplitShape choose_split(int B, int T, int H, int dv)
     return sp;
 }
 
+// A packed batch, whose lengths only the device knows, is cut when the caller asks for it: a fixed segment length, and
+// the largest number of segments the batch can then have (every sequence adds at most one partial segment, an empty one
+// holds one slot).  The segment length is the share of one compute unit when all of them work (one round of workgroups:
+// measured against two, four and eight rounds of shorter segments and half a round of longer ones, 405 against 429, 460,
+// 502 and 638 us on eight sequences of 32768 tokens in all), and at least eight chunks.
+SplitShape choose_packed_cut(int N, int total_tokens, int H, int dv)
+{
+    const long long per_slot = (long long)H * (dv / kColTile);
+    SplitShape none{1, ((total_tokens + kChunk - 1) / kChunk) * kChunk};
+    if (N <= 0 || per_slot == 0 || total_tokens < 16 * kChunk) return none;
+    long long seg = ((long long)total_tokens * per_slot / 256 + kChunk - 1) / kChunk * kChunk;
+    if (seg < 8 * kChunk) seg = 8 * kChunk;
+    const long long slots = total_tokens / seg + N;
+    if (slots < 2 || slots * per_slot > 2147483647LL) return none;
+    return SplitShape{(int)slots, (int)seg};
+}
+
 }  // namespace
 
 bool scan_mfma_supports(int dk, int dv, int chunk, int io_dtype)
@@ -1074,6 +1161,13 @@ size_t scan_mfma_workspace_bytes(int B, int T, int H, int dv)
     if (sp.nseg <= 1) return 0;
     const size_t bh = (size_t)B * H;
     return ((size_t)sp.nseg * bh * kK * dv + (size_t)(sp.nseg - 1) * bh * kK) * sizeof(float);
+}
+
+size_t scan_mfma_packed_workspace_bytes(int N, int total_tokens, int H, int dv)
+{
+    const SplitShape sp = choose_packed_cut(N, total_tokens, H, dv);
+    if (sp.nseg <= 1) return 0;
+    return ((size_t)sp.nseg * H * kK * dv + (size_t)sp.nseg * H * kK) * sizeof(float);
 }
 
 namespace {
@@ -1098,12 +1192,15 @@ hipError_t allow_lds()
 template <int kBeta, bool kGated, int kStage>
 hipError_t launch_scan_mfma_typed(const ScanArgs &a)
 {
-    // a packed variable-length batch is never cut into segments (its lengths live in device memory): one segment
-    // that covers any length
-    const SplitShape sp = a.cu_seqlens != nullptr ? SplitShape{1, ((a.T + kChunk - 1) / kChunk) * kChunk}
-                                                  : choose_split(a.B, a.T, a.H, a.dv);
+    // a packed variable-length batch is cut only when the caller brought a workspace for it (its lengths live in device
+    // memory, so the cut is made by the kernels); otherwise one segment that covers any length
+    const bool packed = a.cu_seqlens != nullptr;
+    const bool packed_cut = packed && a.workspace != nullptr && choose_packed_cut(a.B, a.T, a.H, a.dv).nseg > 1;
+    const SplitShape sp = packed_cut ? choose_packed_cut(a.B, a.T, a.H, a.dv)
+                          : packed   ? SplitShape{1, ((a.T + kChunk - 1) / kChunk) * kChunk}
+                                     : choose_split(a.B, a.T, a.H, a.dv);
     const size_t bh = (size_t)a.B * a.H;
-    SegmentPlan plan{sp.nseg, sp.seg_tokens, nullptr, nullptr};
+    SegmentPlan plan{sp.nseg, sp.seg_tokens, nullptr, nullptr, packed_cut};
     hipError_t attr = allow_lds<false, kBeta, kGated, kStage>();
     if (attr == hipSuccess && sp.nseg > 1) attr = allow_lds<true, kBeta, kGated, 0>();
     if (attr != hipSuccess) return attr;
@@ -1111,20 +1208,25 @@ hipError_t launch_scan_mfma_typed(const ScanArgs &a)
     const unsigned col_tiles = (unsigned)(a.dv / kColTile);
     const void *gate_a = kGated ? a.z_g : static_cast<const void *>(a.log_alpha);
     const OutputStage no_stage{nullptr, nullptr, nullptr, 0};
+    // dense cut: (batch, head) x column tile x segment; packed cut: one flat index over (slot, head, column tile)
+    const dim3 cut_grid = packed_cut ? dim3((unsigned)((size_t)sp.nseg * a.H * col_tiles)) : dim3((unsigned)bh, col_tiles, (unsigned)(sp.nseg - 1));
     if (sp.nseg > 1) {
+        const size_t per_slot = (packed_cut ? (size_t)a.H : bh) * kK;        // state rows in a slot
         plan.slots = static_cast<float *>(a.workspace);
-        plan.gamma = plan.slots + (size_t)sp.nseg * bh * kK * a.dv;
-        hipLaunchKernelGGL((scan_mfma_kernel<true, kBeta, kGated, 0>), dim3((unsigned)bh, col_tiles, (unsigned)(sp.nseg - 1)), block,
+        plan.gamma = plan.slots + (size_t)sp.nseg * per_slot * a.dv;
+        hipLaunchKernelGGL((scan_mfma_kernel<true, kBeta, kGated, 0>), cut_grid, block,
                            lds_bytes(false), a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, gate_a,
                            (const bf16_t *)a.z_tau, a.beta, (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, a.T, a.H, a.dv, plan,
-                           (const int *)nullptr, 0, 0, no_stage);
-        const size_t quads = bh * kK * a.dv / 4;
-        hipLaunchKernelGGL(segment_state_scan_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, a.stream, a.S0,
-                           plan, a.dv, quads);
+                           packed_cut ? a.cu_seqlens : (const int *)nullptr, packed_cut ? a.T : 0, packed_cut ? a.B : 0, no_stage);
+        const size_t quads = per_slot * a.dv / 4;                            // per slot; the packed walk has one thread set per sequence
+        const size_t threads = packed_cut ? quads * a.B : quads;
+        hipLaunchKernelGGL(segment_state_scan_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, a.stream, a.S0,
+                           plan, a.dv, quads, a.cu_seqlens, a.B, a.T);
     }
     // dense: (batch, head) x column tile x segment; packed: one flat index (see the kernel)
-    const bool flat_dense = a.cu_seqlens == nullptr && sp.nseg == 1 && col_tiles > 1 && bh * col_tiles > 256;
-    const dim3 grid = a.cu_seqlens != nullptr ? dim3((unsigned)(bh * col_tiles))
+    const bool flat_dense = !packed && sp.nseg == 1 && col_tiles > 1 && bh * col_tiles > 256;
+    const dim3 grid = packed_cut ? cut_grid
+                      : packed   ? dim3((unsigned)(bh * col_tiles))
                       : flat_dense ? dim3((unsigned)((bh + 7) / 8 * 8 * col_tiles)) : dim3((unsigned)bh, col_tiles, (unsigned)sp.nseg);
     hipLaunchKernelGGL((scan_mfma_kernel<false, kBeta, kGated, kStage>), grid, block, lds_bytes(kStage != 0),
                        a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, gate_a, (const bf16_t *)a.z_tau, a.beta, a.S0,
@@ -1157,7 +1259,7 @@ hipError_t launch_segment_states_typed(const void *k, const void *v, const float
                                        hipStream_t stream)
 {
     const size_t bh = (size_t)B * H;
-    SegmentPlan plan{nseg, seg_tokens, slots, gamma};
+    SegmentPlan plan{nseg, seg_tokens, slots, gamma, false};
     const hipError_t attr = allow_lds<true, kBeta, false, 0>();
     if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL((scan_mfma_kernel<true, kBeta, false, 0>), dim3((unsigned)bh, (unsigned)(dv / kColTile), (unsigned)(nseg - 1)),
@@ -1166,7 +1268,8 @@ hipError_t launch_segment_states_typed(const void *k, const void *v, const float
                        (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, T, H, dv, plan, (const int *)nullptr, 0, 0,
                        OutputStage{nullptr, nullptr, nullptr, 0});
     const size_t quads = bh * kK * dv / 4;
-    hipLaunchKernelGGL(segment_state_scan_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, S0, plan, dv, quads);
+    hipLaunchKernelGGL(segment_state_scan_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, S0, plan, dv, quads,
+                       (const int *)nullptr, 0, 0);
     return hipGetLastError();
 }
 

@@ -57,6 +57,10 @@ def lib() -> ctypes.CDLL:
         L.rodimus_decode_step_zbeta.restype = i
         L.rodimus_chunk_scan_varlen_fwd.argtypes = [vp] * 5 + [i] + [vp] * 4 + [i] * 7 + [vp]
         L.rodimus_chunk_scan_varlen_fwd.restype = i
+        L.rodimus_chunk_scan_varlen_fwd_cut.argtypes = [vp] * 5 + [i] + [vp] * 4 + [i] * 7 + [vp, sz, vp]
+        L.rodimus_chunk_scan_varlen_fwd_cut.restype = i
+        L.rodimus_chunk_scan_varlen_workspace_bytes.argtypes = [i] * 7
+        L.rodimus_chunk_scan_varlen_workspace_bytes.restype = sz
         L.rodimus_chunk_scan_bwd.argtypes = [vp] * 14 + [i] * 6 + [vp, sz, vp]
         L.rodimus_chunk_scan_bwd.restype = i
         L.rodimus_chunk_scan_bwd_zbeta.argtypes = L.rodimus_chunk_scan_bwd.argtypes
@@ -583,8 +587,23 @@ def rodimus_chunk_scan_bwd_zbeta(q, k, v, log_alpha, z_beta, S0, d_o, dS_T=None,
                      workspace)
 
 
+def rodimus_chunk_scan_varlen_workspace_bytes(N, total_tokens, H, dk, dv, chunk, io_dtype):
+    """Workspace bytes of ``rodimus_chunk_scan_varlen_fwd_cut`` (0: the batch is not cut along its sequences)."""
+    code = _DTYPES[io_dtype] if isinstance(io_dtype, torch.dtype) else int(io_dtype)
+    return int(lib().rodimus_chunk_scan_varlen_workspace_bytes(int(N), int(total_tokens), int(H), int(dk), int(dv), int(chunk), code))
+
+
+def rodimus_chunk_scan_varlen_fwd_cut(q, k, v, log_alpha, cu_seqlens, beta=None, S0=None, *, z_beta=None, chunk=64, o=None,
+                                      S_T=None, want_state=True, workspace=None):
+    """``rodimus_chunk_scan_varlen_fwd`` for a batch of few long sequences: the kernels cut every sequence into segments that
+    run side by side.  ``workspace``: a uint8 device tensor of ``rodimus_chunk_scan_varlen_workspace_bytes`` bytes
+    (allocated here when missing)."""
+    return rodimus_chunk_scan_varlen_fwd(q, k, v, log_alpha, cu_seqlens, beta, S0, z_beta=z_beta, chunk=chunk, o=o, S_T=S_T,
+                                         want_state=want_state, _cut=True, _workspace=workspace)
+
+
 def rodimus_chunk_scan_varlen_fwd(q, k, v, log_alpha, cu_seqlens, beta=None, S0=None, *, z_beta=None, chunk=64, o=None,
-                                  S_T=None, want_state=True):
+                                  S_T=None, want_state=True, _cut=False, _workspace=None):
     """Chunkwise forward scan over a packed variable-length batch.
 
     q,k,log_alpha [total,H,dk]; v, beta (fp32) or z_beta (dtype of v) [total,H,dv]; cu_seqlens [N+1] int32 on the
@@ -615,6 +634,17 @@ def rodimus_chunk_scan_varlen_fwd(q, k, v, log_alpha, cu_seqlens, beta=None, S0=
         S_T = torch.empty((N, H, dk, dv), dtype=torch.float32, device=dev)
     _require(S_T, "S_T", (N, H, dk, dv), torch.float32, dev)
     gate, kind = (z_beta, 1) if z_beta is not None else (beta, 0)
+    if _cut:
+        need = rodimus_chunk_scan_varlen_workspace_bytes(N, total, H, dk, dv, chunk, io)
+        ws = _workspace
+        if ws is None and need > 0:
+            ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+        with torch.cuda.device(dev):
+            _check(lib().rodimus_chunk_scan_varlen_fwd_cut(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(gate), kind, _ptr(S0),
+                                                           _ptr(o), _ptr(S_T), _ptr(cu_seqlens), N, total, H, dk, dv, int(chunk),
+                                                           _DTYPES[io], _ptr(ws), ws_bytes, _stream(dev)))
+        return o, S_T
     with torch.cuda.device(dev):
         _check(lib().rodimus_chunk_scan_varlen_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(gate), kind, _ptr(S0),
                                                    _ptr(o), _ptr(S_T), _ptr(cu_seqlens), N, total, H, dk, dv, int(chunk),

@@ -35,7 +35,8 @@ def test_every_declared_symbol_is_exported(L):
             "rodimus_chunk_scan_varlen_bwd", "rodimus_chunk_scan_varlen_bwd_workspace_bytes",
             "rodimus_chunk_scan_fwd_noalloc", "rodimus_chunk_scan_fwd_noalloc_scratch_bytes",
             "rodimus_chunk_scan_bwd_gated", "rodimus_chunk_scan_bwd_gated_workspace_bytes",
-            "rodimus_chunk_scan_fwd_gated_block", "rodimus_decode_step_gated_block"} <= declared
+            "rodimus_chunk_scan_fwd_gated_block", "rodimus_decode_step_gated_block",
+            "rodimus_chunk_scan_varlen_fwd_cut", "rodimus_chunk_scan_varlen_workspace_bytes"} <= declared
     for name in declared:
         assert hasattr(L, name), name
 
@@ -289,6 +290,27 @@ def test_gated_calls_validation(L):
     assert scan(B=1, T=32768, H=16, dk=64, dv=256, chunk=64, io=rodimus.BF16, q=0x10000000, k=0x20000000, v=0x30000000,
                 zg=0x40000000, zt=0x50000000, zb=0x60000000, S0=None, o=0x80000000, S_T=None) == E_WS
     assert scan(B=0) == OK and dec(N=0) == OK and scan(T=0, S_T=None) == OK
+
+
+def test_packed_cut_workspace_and_validation(L):
+    L.rodimus_chunk_scan_varlen_workspace_bytes.restype = ctypes.c_size_t
+    need = L.rodimus_chunk_scan_varlen_workspace_bytes(8, 32768, 16, 64, 256, 64, rodimus.BF16)
+    # segments of 32768 * 16 * 2 / 256 = 4096 tokens: at most 8 + 8 slots of [16 heads][64][256] fp32 plus their decays
+    assert need == 16 * 16 * 64 * (256 + 1) * 4
+    assert L.rodimus_chunk_scan_varlen_workspace_bytes(3, 1023, 2, 64, 128, 64, rodimus.BF16) == 0       # too short to cut
+    assert L.rodimus_chunk_scan_varlen_workspace_bytes(3, 9000, 2, 16, 32, 16, rodimus.F32) == 0         # any-shape kernels
+    assert L.rodimus_chunk_scan_varlen_workspace_bytes(3, 9000, 2, 64, 128, 64, rodimus.BF16) == (9000 // 512 + 3) * 2 * 64 * 129 * 4
+    p = lambda x: None if x is None else ctypes.c_void_p(x)
+
+    def call(ws=0x4000000, ws_bytes=1 << 30, kind=0, cu=0x90000, o=0xA00000, total=9000):
+        return L.rodimus_chunk_scan_varlen_fwd_cut(p(0x1000000), p(0x2000000), p(0x3000000), p(0x5000000), p(0x6000000), kind,
+                                                   p(0x7000000), p(o), p(0x8000000), p(cu), 3, total, 2, 64, 128, 64, rodimus.BF16,
+                                                   p(ws), ctypes.c_size_t(ws_bytes), None)
+
+    assert call(ws=None, ws_bytes=0) == E_WS and call(ws_bytes=1000) == E_WS
+    assert call(kind=7) == E_DTYPE and call(cu=None) == E_NULL and call(ws=0x4000008) == E_ALIGN
+    assert call(ws=0xA00000) == E_ALIAS                      # the workspace over the output
+    assert call(ws=0x8000000 - 4096) == E_ALIAS              # ... or reaching into the state cache
 
 
 def test_gated_block_calls_validation(L):
