@@ -7,7 +7,7 @@ import torch
 
 import oracle
 from paper_2410_06577_amd import rodimus, workloads as wl
-from _parity import rel_err, to_dev, tol_for
+from _parity import TOL_BF16, rel_err, to_dev, tol_for
 
 pytestmark = pytest.mark.gpu
 
@@ -64,3 +64,29 @@ def test_decode_steps_chain_from_the_scan(N, H, dk, dv, io):
     y_ref = oracle.block_output(o_ref, st["x_prime"], st["d"], st["z_gate"], "silu")
     tol = tol_for(d["q"].dtype)
     assert rel_err(torch.stack(ys, 1), y_ref) <= tol and rel_err(S, S_ref) <= tol
+
+
+def test_full_size_layer_config():
+    """The layer-shaped configuration at full size (the launch that bench.py times as scan_whole_block), every output element
+    and every final state against the oracle, with a bar per (batch, head) as well."""
+    w = wl.LAYER_1P6B
+    print("gated block layer_1p6b: inputs ...", flush=True)
+    d = wl.make_gated_scan_inputs(w.B, w.T, w.H, w.dk, w.dv, "bf16", seed=17)
+    st = _stage((w.B, w.T, w.H, w.dv), w.H, w.dv, "bf16", 21)
+    g, gs = to_dev(d), to_dev(st)
+    print("gated block layer_1p6b: GPU ...", flush=True)
+    y, S_T = rodimus.rodimus_chunk_scan_fwd_gated_block(g["q"], g["k"], g["v"], g["z_g"], g["z_tau"], g["z_beta"], g["S0"], chunk=w.chunk,
+                                                        x_prime=gs["x_prime"], d=gs["d"], z_gate=gs["z_gate"], gate_act="silu")
+    torch.cuda.synchronize()
+    print("gated block layer_1p6b: oracle ...", flush=True)
+    o_ref, S_ref = oracle.scan_gated(d["q"], d["k"], d["v"], d["z_g"], d["z_tau"], d["z_beta"], d["S0"])
+    y_ref = oracle.block_output(o_ref, st["x_prime"], st["d"], st["z_gate"], "silu")
+    del o_ref
+    ey, es = rel_err(y, y_ref), rel_err(S_T, S_ref)
+    print(f"   y {ey:.2e}  S_T {es:.2e}", flush=True)
+    assert ey <= TOL_BF16 and es <= TOL_BF16
+    gy = y.float().cpu().numpy()
+    for b in range(w.B):
+        for h in range(w.H):
+            ref = y_ref[b, :, h]
+            assert np.abs(gy[b, :, h] - ref).max() <= TOL_BF16 * np.abs(ref).max(), (b, h)
