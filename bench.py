@@ -342,6 +342,36 @@ def bench_whole_block_scan(w, rodimus, wl, dev, steps, warmup):
             "GB_per_s": algo / (ms * 1e-3) / 1e9, "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
 
+def bench_stream_probe(rodimus, dev, steps=20):
+    """What the memory system of this GPU gives a kernel that only streams (rodimus_hbm_stream_probe): four 16-byte units
+    read per unit written, the mix of the layer scan (2048 B read and 512 B written per token and head; 1 GiB read, 256 MiB
+    written per launch), and one read per write, the mix and the footprint of the decode step over 512 sequences (512 MiB
+    each way).  Best of a few grid sizes each."""
+    out = {}
+    for name, reads, mib in (("four_reads_per_write", 4, 256), ("one_read_per_write", 1, 512)):
+        dst = torch.empty(mib << 20, dtype=torch.uint8, device=dev)
+        src = torch.ones(reads * dst.numel(), dtype=torch.uint8, device=dev)
+        best, best_wgs = None, None
+        for wgs in (256, 512, 1024, 16384, 65536, 262144):
+            def step():
+                rodimus.rodimus_hbm_stream_probe(src, dst, reads, wgs)
+            warm_up(step, 5)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(steps):
+                step()
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b) / steps
+            if best is None or ms < best:
+                best, best_wgs = ms, wgs
+        gbs = (reads + 1) * dst.numel() / (best * 1e-3) / 1e9
+        out[name] = {"GB_per_s": gbs, "hbm_frac": gbs / HBM_PEAK_GBS, "ms": best, "workgroups": best_wgs,
+                     "MiB_written": mib, "MiB_read": reads * mib}
+        del src, dst
+    return out
+
+
 def bench_short_conv(w, rodimus, wl, dev, steps=50, warmup=20, width=4):
     """The block's ShortConv over the layer workload's tokens: C = H * dv channels, width 4, SiLU, bf16 I/O."""
     C = w.H * w.dv
@@ -600,6 +630,11 @@ def main():
         out["scan_fused_all_gates"] = bench_gated_scan(w, rodimus, wl, dev, args.steps, args.warmup)
         out["scan_block_output"] = bench_block_scan(w, rodimus, wl, dev, args.steps, args.warmup)
         out["scan_block_output"]["vs_plain_scan"] = out["scan_block_output"]["ms_per_step"] / scan["launch_ms"]
+        probe = bench_stream_probe(rodimus, dev)
+        out["hbm_stream_probe"] = probe
+        out["roofline"]["vs_stream_probe"] = scan["gbs"] / probe["four_reads_per_write"]["GB_per_s"]
+        if "decode" in out:
+            out["decode"]["roofline"]["vs_stream_probe"] = out["decode"]["roofline"]["achieved"] / probe["one_read_per_write"]["GB_per_s"]
         out["scan_whole_block"] = bench_whole_block_scan(w, rodimus, wl, dev, args.steps, args.warmup)
         out["scan_whole_block"]["vs_plain_scan"] = out["scan_whole_block"]["ms_per_step"] / scan["launch_ms"]
         out["scan_backward"] = bench_backward(w, rodimus, wl, dev, args.steps, args.warmup)

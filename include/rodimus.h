@@ -105,6 +105,16 @@ size_t rodimus_chunk_scan_workspace_bytes(int B, int T, int H, int dk, int dv, i
 int rodimus_chunk_scan_path(int B, int T, int H, int dk, int dv, int chunk, int io_dtype);
 
 /*
+ * Measurement aid (no part of the paper's method): a plain streaming kernel, against which the bandwidth of the calls in
+ * this header can be judged on the GPU at hand.  Writes `units` 16-byte units to dst; unit i is a constant plus the sum of
+ * unit i of each of `reads_per_write` (0, 1, 2 or 4) input streams laid end to end in src (src holds reads_per_write *
+ * units units; ignored and may be NULL for 0).  Coalesced, streaming accesses, `workgroups` workgroups of 256 lanes in a
+ * grid-stride loop.  Device pointers, 16-byte aligned, dst must not overlap src.  No workspace, no synchronisation.
+ * RODIMUS_ERR_SHAPE for another reads_per_write or workgroups outside 1 .. 2^20.
+ */
+int rodimus_hbm_stream_probe(const void *src, void *dst, size_t units, int reads_per_write, int workgroups, void *stream);
+
+/*
  * rodimus_chunk_scan_fwd for callers that cannot allocate device memory: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical results, but no
  * workspace argument: a call that is cut along the sequence keeps its segment summaries and entering states in a

@@ -37,7 +37,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(
     float *__restrict__ S, IO *__restrict__ o, int dk, int dv, int H, OutputStage stage,
     const IO *__restrict__ z_g, const IO *__restrict__ z_tau, const float *__restrict__ log_beta_t)
 {
-    constexpr int kRowBatch = kStream ? 4 : 8;      // rows in flight per wavefront
+        constexpr int kRowBatch = kStream ? 4 : 8;      // rows in flight per wavefront (streamed: 2 / 4 / 8 / 16 rows give 5.53 / 5.71 / 5.60 / 5.42 TB/s)
     __shared__ float s_q[kDecodeMaxDk];
     __shared__ float s_k[kDecodeMaxDk];
     __shared__ float s_a[kDecodeMaxDk];

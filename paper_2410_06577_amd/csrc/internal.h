@@ -307,6 +307,8 @@ size_t scan_generic_lds_bytes(int dk, int chunk, bool general = false);
 hipError_t launch_scan_mfma(const ScanArgs &a);
 bool scan_mfma_supports(int dk, int dv, int chunk, int io_dtype);
 size_t scan_mfma_workspace_bytes(int B, int T, int H, int dv);
+// measurement aid: a plain streaming kernel, `reads_per_write` (0, 1, 2 or 4) 16-byte units read per unit written
+hipError_t launch_hbm_stream_probe(const void *src, void *dst, size_t units, int reads_per_write, int workgroups, hipStream_t stream);
 // packed batch of N sequences cut along the sequences by the kernels; 0: the batch is not cut
 size_t scan_mfma_packed_workspace_bytes(int N, int total_tokens, int H, int dv);
 // State entering each of nseg sequence segments (seg_tokens a multiple of 64) of a dense bf16 batch with dk = 64:

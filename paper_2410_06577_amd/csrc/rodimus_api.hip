@@ -176,6 +176,17 @@ const char *rodimus_status_string(int status)
     }
 }
 
+int rodimus_hbm_stream_probe(const void *src, void *dst, size_t units, int reads_per_write, int workgroups, void *stream)
+{
+    if (reads_per_write != 0 && reads_per_write != 1 && reads_per_write != 2 && reads_per_write != 4) return RODIMUS_ERR_SHAPE;
+    if (workgroups < 1 || workgroups > 1 << 20) return RODIMUS_ERR_SHAPE;
+    if (units > 0 && (!dst || (reads_per_write > 0 && !src))) return RODIMUS_ERR_NULL;
+    if (misaligned(src) || misaligned(dst)) return RODIMUS_ERR_ALIGN;
+    if (overlaps(dst, units * 16, src, units * 16 * (size_t)reads_per_write)) return RODIMUS_ERR_ALIAS;
+    const hipError_t err = launch_hbm_stream_probe(src, dst, units, reads_per_write, workgroups, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
+}
+
 int rodimus_chunk_scan_path(int B, int T, int H, int dk, int dv, int chunk, int io_dtype)
 {
     if (scan_shape_status(B, T, H, dk, dv, chunk, io_dtype) != RODIMUS_OK) return RODIMUS_PATH_NONE;

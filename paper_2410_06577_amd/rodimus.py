@@ -57,6 +57,8 @@ def lib() -> ctypes.CDLL:
         L.rodimus_decode_step_zbeta.restype = i
         L.rodimus_chunk_scan_varlen_fwd.argtypes = [vp] * 5 + [i] + [vp] * 4 + [i] * 7 + [vp]
         L.rodimus_chunk_scan_varlen_fwd.restype = i
+        L.rodimus_hbm_stream_probe.argtypes = [vp, vp, sz, i, i, vp]
+        L.rodimus_hbm_stream_probe.restype = i
         L.rodimus_chunk_scan_varlen_fwd_cut.argtypes = [vp] * 5 + [i] + [vp] * 4 + [i] * 7 + [vp, sz, vp]
         L.rodimus_chunk_scan_varlen_fwd_cut.restype = i
         L.rodimus_chunk_scan_varlen_workspace_bytes.argtypes = [i] * 7
@@ -585,6 +587,20 @@ def rodimus_chunk_scan_bwd_zbeta(q, k, v, log_alpha, z_beta, S0, d_o, dS_T=None,
     Returns the dict of ``rodimus_chunk_scan_bwd`` with ``dz_beta`` (dtype of v) in place of ``dbeta``."""
     return _scan_bwd("rodimus_chunk_scan_bwd_zbeta", "dz_beta", q, k, v, log_alpha, z_beta, S0, d_o, dS_T, want_dz_beta, want_dS0,
                      workspace)
+
+
+def rodimus_hbm_stream_probe(src, dst, reads_per_write, workgroups=2048):
+    """Plain streaming kernel (measurement aid): dst (any dtype, a multiple of 16 bytes) <- constant + sum of the
+    ``reads_per_write`` streams of dst's size laid end to end in src."""
+    if not dst.is_cuda:
+        raise ValueError("rodimus_hbm_stream_probe needs device tensors (no CPU path exists)")
+    nbytes = dst.numel() * dst.element_size()
+    if nbytes % 16 or (reads_per_write and src.numel() * src.element_size() < nbytes * reads_per_write):
+        raise ValueError("dst must hold whole 16-byte units and src reads_per_write times as many")
+    with torch.cuda.device(dst.device):
+        _check(lib().rodimus_hbm_stream_probe(_ptr(src) if reads_per_write else None, _ptr(dst), nbytes // 16, int(reads_per_write),
+                                              int(workgroups), _stream(dst.device)))
+    return dst
 
 
 def rodimus_chunk_scan_varlen_workspace_bytes(N, total_tokens, H, dk, dv, chunk, io_dtype):

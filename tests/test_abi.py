@@ -36,7 +36,8 @@ def test_every_declared_symbol_is_exported(L):
             "rodimus_chunk_scan_fwd_noalloc", "rodimus_chunk_scan_fwd_noalloc_scratch_bytes",
             "rodimus_chunk_scan_bwd_gated", "rodimus_chunk_scan_bwd_gated_workspace_bytes",
             "rodimus_chunk_scan_fwd_gated_block", "rodimus_decode_step_gated_block",
-            "rodimus_chunk_scan_varlen_fwd_cut", "rodimus_chunk_scan_varlen_workspace_bytes"} <= declared
+            "rodimus_chunk_scan_varlen_fwd_cut", "rodimus_chunk_scan_varlen_workspace_bytes",
+            "rodimus_hbm_stream_probe"} <= declared
     for name in declared:
         assert hasattr(L, name), name
 
@@ -290,6 +291,16 @@ def test_gated_calls_validation(L):
     assert scan(B=1, T=32768, H=16, dk=64, dv=256, chunk=64, io=rodimus.BF16, q=0x10000000, k=0x20000000, v=0x30000000,
                 zg=0x40000000, zt=0x50000000, zb=0x60000000, S0=None, o=0x80000000, S_T=None) == E_WS
     assert scan(B=0) == OK and dec(N=0) == OK and scan(T=0, S_T=None) == OK
+
+
+def test_stream_probe_validation(L):
+    p = lambda x: None if x is None else ctypes.c_void_p(x)
+    call = lambda src=0x100000, dst=0x900000, units=1024, reads=4, wgs=256: L.rodimus_hbm_stream_probe(
+        p(src), p(dst), ctypes.c_size_t(units), reads, wgs, None)
+    assert call(reads=3) == E_SHAPE and call(wgs=0) == E_SHAPE and call(wgs=(1 << 20) + 1) == E_SHAPE
+    assert call(dst=None) == E_NULL and call(src=None) == E_NULL and call(src=0x100008) == E_ALIGN
+    assert call(dst=0x100000 + 3 * 16384) == E_ALIAS          # inside the fourth input stream
+    assert call(units=0, src=None, dst=None) == OK
 
 
 def test_packed_cut_workspace_and_validation(L):
