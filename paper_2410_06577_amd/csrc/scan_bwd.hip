@@ -25,6 +25,8 @@
 // (q .* A and k ./ A as operands) when the tile's total decay A_16 is at least 2^-80 in every channel concerned, so
 // that 1 / A_i cannot overflow; otherwise (a hard reset or very strong decay inside the tile) they are evaluated pair
 // by pair on the vector ALUs in fp32 from exp(l_t - l_i) <= 1.  The choice is uniform per tile.
+#include <atomic>
+
 #include "internal.h"
 
 namespace rodimus {
@@ -1291,9 +1293,18 @@ hipError_t launch_scan_bwd_typed(const ScanBwdArgs &a)
         segs.S_slots = S_slots;
         segs.G_slots = G_slots;
     }
-    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_bwd_sweeps_kernel<DV, kZBeta>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, DkvLds<DV>::kBytes);
+    // more than the default 64 KB of dynamic LDS: the limit is raised once per kernel instance and device
+    static std::atomic<bool> lds_allowed[64];
+    int device = 0;
+    hipError_t attr = hipGetDevice(&device);
     if (attr != hipSuccess) return attr;
+    if (device < 0 || device >= 64) return hipErrorInvalidDevice;
+    if (!lds_allowed[device].load(std::memory_order_acquire)) {
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_bwd_sweeps_kernel<DV, kZBeta>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, DkvLds<DV>::kBytes);
+        if (attr != hipSuccess) return attr;
+        lds_allowed[device].store(true, std::memory_order_release);
+    }
     hipLaunchKernelGGL((scan_bwd_sweeps_kernel<DV, kZBeta>), dim3(bh, (unsigned)sp.nseg, 2), dim3(BwdShape<DV>::kSweepThreads), DkvLds<DV>::kBytes,
                        a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0,
                        (const bf16_t *)a.d_o, a.dS_T, (bf16_t *)a.dq, (bf16_t *)a.dk, (bf16_t *)a.dv, a.dbeta, a.dS0, qdq, kdk,
