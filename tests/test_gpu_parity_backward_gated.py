@@ -57,6 +57,12 @@ def test_zero_and_tiny_keys_take_the_norm_guard():
     assert np.isfinite(list(errs.values())).all()
 
 
+def test_whole_sequences_at_layer_head_shape():
+    # enough (batch, head) pairs that the call is not cut: the sweeps evaluate the gates themselves while they stage a tile
+    print("gated backward, uncut, layer head shape", flush=True)
+    _check(6, 1024, 16, 256, seed=22, label="uncut")
+
+
 def test_layer_head_shape_full_length():
     # one sequence of the 1.6B-class layer: T = 4096, 16 heads of 64 x 256 (the call is cut along the sequence)
     print("gated backward layer head shape", flush=True)
