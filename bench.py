@@ -436,6 +436,44 @@ def bench_varlen(w, rodimus, wl, dev, steps, warmup, n_seq=64, longest_first=Fal
             "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
 
+def bench_varlen_whole_block(w, rodimus, wl, dev, steps, warmup, n_seq=64):
+    """Packed variable-length prefill of the whole block in one launch (rodimus_chunk_scan_varlen_fwd_gated_block): the length mix
+    of bench_varlen, every gate as a bf16 pre-activation, raw q and k, feed-through and SiLU output gate."""
+    import numpy as np
+    lengths = wl.serving_length_mix(n_seq, w.B * w.T)
+    total = w.B * w.T
+    d = wl.make_gated_scan_inputs(1, total, w.H, w.dk, w.dv, "bf16", s0_std=0.0, seed=17)
+    g = {k: (None if v is None else v[0].to(dev)) for k, v in d.items()}
+    rng = np.random.Generator(np.random.PCG64(21))
+    shape = (total, w.H, w.dv)
+    x_prime = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(torch.bfloat16).to(dev)
+    z_gate = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(torch.bfloat16).to(dev)
+    dw = torch.from_numpy(rng.standard_normal((w.H, w.dv), dtype=np.float32)).to(dev)
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(lengths)]), dtype=torch.int32, device=dev)
+    cache = (0.1 * torch.randn((n_seq, w.H, w.dk, w.dv), generator=torch.Generator().manual_seed(3))).to(dev)
+    o = torch.empty(shape, dtype=torch.bfloat16, device=dev)
+    S_T = torch.empty_like(cache)
+
+    def step():
+        rodimus.rodimus_chunk_scan_varlen_fwd_gated_block(g["q"], g["k"], g["v"], g["z_g"], g["z_tau"], cu, g["z_beta"], cache,
+                                                          x_prime=x_prime, d=dw, z_gate=z_gate, gate_act="silu", o=o, S_T=S_T)
+
+    warm_up(step, warmup)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(steps):
+        step()
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / steps
+    algo = w.token_heads * (4 * 2 * w.dk + 5 * 2 * w.dv) + 2 * n_seq * w.H * w.dk * w.dv * 4
+    return {"entry_point": "rodimus_chunk_scan_varlen_fwd_gated_block",
+            "workload": f"{n_seq} sequences, lengths {min(lengths)}..{max(lengths)} (log-uniform mix), {total} tokens, "
+                        f"H={w.H} dk={w.dk} dv={w.dv}, all gates as pre-activations, feed-through and SiLU gate",
+            "launches_per_call": 1, "ms_per_step": ms, "tokens_per_s": total / (ms * 1e-3), "algorithmic_bytes": algo,
+            "GB_per_s": algo / (ms * 1e-3) / 1e9, "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+
 def bench_backward(w, rodimus, wl, dev, steps, warmup, zbeta=False):
     """Backward pass of the scan over the layer workload (rodimus_chunk_scan_bwd: dq, dk, dv, dlog_alpha, dbeta, dS0; with
     zbeta the form that reads the value gate's bf16 pre-activation and writes its cotangent, rodimus_chunk_scan_bwd_zbeta)."""
@@ -653,6 +691,7 @@ def main():
         lf = bench_varlen(w, rodimus, wl, dev, args.steps, args.warmup, longest_first=True)
         out["serving_prefill_varlen"]["sequences_sorted_longest_first"] = {
             k: lf[k] for k in ("ms_per_step", "tokens_per_s", "GB_per_s", "hbm_frac")}
+        out["serving_prefill_whole_block"] = bench_varlen_whole_block(w, rodimus, wl, dev, args.steps, args.warmup)
         # few long sequences: the packed call lasts as long as its longest sequence unless the kernels cut the sequences
         few = bench_varlen(w, rodimus, wl, dev, args.steps, args.warmup, n_seq=8)
         few_cut = bench_varlen(w, rodimus, wl, dev, args.steps, args.warmup, n_seq=8, cut=True)

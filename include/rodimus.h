@@ -476,6 +476,30 @@ int rodimus_decode_step_gated_block(const void *q, const void *k, const void *v,
                                     int N, int H, int dk, int dv, int io_dtype, void *stream);
 
 /*
+ * rodimus_chunk_scan_fwd_gated_block over a PACKED batch of N sequences of different lengths (serving prefill of the whole
+ * block in one launch; paper Sec. 3.1.2 and 3.1.3 as for the calls it combines): the layouts and the length table of
+ * rodimus_chunk_scan_varlen_fwd, the gates and the output stage of rodimus_chunk_scan_fwd_gated_block.
+ *
+ *   q, k, z_g, z_tau          [total_tokens,H,dk] io_dtype   in
+ *   v, z_beta, x_prime, z_gate [total_tokens,H,dv] io_dtype  in   z_beta, x_prime (with d [H,dv] fp32) and z_gate may each be
+ *                                                                 NULL: no value gate / no feed-through / no output gate
+ *   S0, S_T                   [N,H,dk,dv] fp32               S_T may be S0 (a state cache updated in place)
+ *   cu_seqlens                [N+1] int32, DEVICE memory     as in rodimus_chunk_scan_varlen_fwd (clamped by the kernels)
+ *   workspace                 NULL: one workgroup set per (sequence, head), as rodimus_chunk_scan_varlen_fwd;
+ *                             otherwise rodimus_chunk_scan_varlen_workspace_bytes(...) bytes: the kernels cut the sequences
+ *                             into segments that run side by side, as rodimus_chunk_scan_varlen_fwd_cut (same rule of thumb)
+ *
+ * Shapes, kernel families, alignment, aliasing rules and status codes as for the calls it combines.
+ */
+int rodimus_chunk_scan_varlen_fwd_gated_block(const void *q, const void *k, const void *v,
+                                              const void *z_g, const void *z_tau, const void *z_beta, const float *S0,
+                                              const void *x_prime, const float *d, const void *z_gate, int gate_act,
+                                              void *o, float *S_T,
+                                              const int *cu_seqlens, int N, int total_tokens,
+                                              int H, int dk, int dv, int chunk, int io_dtype,
+                                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The two recurrence calls with the general transition of paper Sec. 3.1.1 (first equation of the section), which gates
  * the state along the value dimension as well:
  *     S_t = (alpha_t^T beta_t) .* S_{t-1} + k_t^T (beta_hat_t .* v_t),   o_t = q_t S_t

@@ -308,6 +308,19 @@ int rodimus_decode_step_gated_block(const void *q, const void *k, const void *v,
                         true, z_g, z_tau);
 }
 
+int rodimus_chunk_scan_varlen_fwd_gated_block(const void *q, const void *k, const void *v, const void *z_g, const void *z_tau,
+                                              const void *z_beta, const float *S0, const void *x_prime, const float *d,
+                                              const void *z_gate, int gate_act, void *o, float *S_T, const int *cu_seqlens, int N,
+                                              int total_tokens, int H, int dk, int dv, int chunk, int io_dtype, void *workspace,
+                                              size_t workspace_bytes, void *stream)
+{
+    if (gate_act != RODIMUS_GATE_SIGMOID && gate_act != RODIMUS_GATE_SILU) return RODIMUS_ERR_DTYPE;
+    // without a workspace the batch is never cut along its sequences
+    return scan_entry(q, k, v, nullptr, z_beta, true, S0, o, S_T, N, total_tokens, H, dk, dv, chunk, io_dtype, workspace,
+                      workspace_bytes, stream, true, cu_seqlens, OutputStage{x_prime, d, z_gate, gate_act}, true, z_g, z_tau, false,
+                      nullptr, workspace != nullptr);
+}
+
 int rodimus_chunk_scan_fwd_general(const void *q, const void *k, const void *v, const float *log_alpha,
                                    const float *log_beta_t, const float *beta, const float *S0, void *o, float *S_T, int B, int T,
                                    int H, int dk, int dv, int chunk, int io_dtype, void *stream)

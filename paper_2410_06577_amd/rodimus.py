@@ -57,6 +57,8 @@ def lib() -> ctypes.CDLL:
         L.rodimus_decode_step_zbeta.restype = i
         L.rodimus_chunk_scan_varlen_fwd.argtypes = [vp] * 5 + [i] + [vp] * 4 + [i] * 7 + [vp]
         L.rodimus_chunk_scan_varlen_fwd.restype = i
+        L.rodimus_chunk_scan_varlen_fwd_gated_block.argtypes = [vp] * 10 + [i] + [vp] * 3 + [i] * 7 + [vp, sz, vp]
+        L.rodimus_chunk_scan_varlen_fwd_gated_block.restype = i
         L.rodimus_hbm_stream_probe.argtypes = [vp, vp, sz, i, i, vp]
         L.rodimus_hbm_stream_probe.restype = i
         L.rodimus_chunk_scan_varlen_fwd_cut.argtypes = [vp] * 5 + [i] + [vp] * 4 + [i] * 7 + [vp, sz, vp]
@@ -601,6 +603,50 @@ def rodimus_hbm_stream_probe(src, dst, reads_per_write, workgroups=2048):
         _check(lib().rodimus_hbm_stream_probe(_ptr(src) if reads_per_write else None, _ptr(dst), nbytes // 16, int(reads_per_write),
                                               int(workgroups), _stream(dst.device)))
     return dst
+
+
+def rodimus_chunk_scan_varlen_fwd_gated_block(q, k, v, z_g, z_tau, cu_seqlens, z_beta=None, S0=None, *, x_prime=None, d=None,
+                                              z_gate=None, gate_act="sigmoid", chunk=64, o=None, S_T=None, want_state=True,
+                                              cut=False, workspace=None):
+    """The whole block around the recurrence over a packed variable-length batch, one launch (three with ``cut``, which lets
+    the kernels cut long sequences into segments that run side by side; the workspace is allocated here when missing).
+    Returns (y [total,H,dv], S_T or None)."""
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_chunk_scan_varlen_fwd_gated_block needs device tensors (no CPU path exists)")
+    total, H, dk = q.shape
+    dv = v.shape[-1]
+    dev, io = q.device, q.dtype
+    N = cu_seqlens.numel() - 1
+    _require(cu_seqlens, "cu_seqlens", (N + 1,), torch.int32, dev)
+    for name, t in (("q", q), ("k", k), ("z_g", z_g), ("z_tau", z_tau)):
+        if t is None:
+            raise ValueError(f"{name} is required")
+        _require(t, name, (total, H, dk), io, dev)
+    for name, t in (("v", v), ("z_beta", z_beta), ("x_prime", x_prime), ("z_gate", z_gate)):
+        _require(t, name, (total, H, dv), io, dev)
+    _require(d, "d", (H, dv), torch.float32, dev)
+    _require(S0, "S0", (N, H, dk, dv), torch.float32, dev)
+    if o is None:
+        o = torch.empty((total, H, dv), dtype=io, device=dev)
+    _require(o, "o", (total, H, dv), io, dev)
+    if S_T is None and want_state:
+        S_T = torch.empty((N, H, dk, dv), dtype=torch.float32, device=dev)
+    _require(S_T, "S_T", (N, H, dk, dv), torch.float32, dev)
+    ws = None
+    if cut or workspace is not None:
+        need = rodimus_chunk_scan_varlen_workspace_bytes(N, total, H, dk, dv, chunk, io)
+        ws = workspace
+        if ws is None and need > 0:
+            ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_chunk_scan_varlen_fwd_gated_block(_ptr(q), _ptr(k), _ptr(v), _ptr(z_g), _ptr(z_tau), _ptr(z_beta), _ptr(S0),
+                                                               _ptr(x_prime), _ptr(d), _ptr(z_gate), _GATE_ACTS[gate_act], _ptr(o),
+                                                               _ptr(S_T), _ptr(cu_seqlens), N, total, H, dk, dv, int(chunk), _DTYPES[io],
+                                                               _ptr(ws), ws_bytes, _stream(dev)))
+    return o, S_T
 
 
 def rodimus_chunk_scan_varlen_workspace_bytes(N, total_tokens, H, dk, dv, chunk, io_dtype):

@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported(L):
             "rodimus_chunk_scan_bwd_gated", "rodimus_chunk_scan_bwd_gated_workspace_bytes",
             "rodimus_chunk_scan_fwd_gated_block", "rodimus_decode_step_gated_block",
             "rodimus_chunk_scan_varlen_fwd_cut", "rodimus_chunk_scan_varlen_workspace_bytes",
-            "rodimus_hbm_stream_probe"} <= declared
+            "rodimus_hbm_stream_probe", "rodimus_chunk_scan_varlen_fwd_gated_block"} <= declared
     for name in declared:
         assert hasattr(L, name), name
 
@@ -322,6 +322,23 @@ def test_packed_cut_workspace_and_validation(L):
     assert call(kind=7) == E_DTYPE and call(cu=None) == E_NULL and call(ws=0x4000008) == E_ALIGN
     assert call(ws=0xA00000) == E_ALIAS                      # the workspace over the output
     assert call(ws=0x8000000 - 4096) == E_ALIAS              # ... or reaching into the state cache
+
+
+def test_packed_gated_block_validation(L):
+    p = lambda x: None if x is None else ctypes.c_void_p(x)
+
+    def call(act=0, ws=None, ws_bytes=0, total=9000, **kw):
+        a = dict(q=0x1000000, k=0x2000000, v=0x3000000, zg=0x4000000, zt=0x5000000, zb=0x6000000, S0=0x7000000, x=0x8000000,
+                 d=0x9000000, z=0xA000000, o=0xB000000, S_T=0xC000000, cu=0xD000000)
+        a.update(kw)
+        return L.rodimus_chunk_scan_varlen_fwd_gated_block(p(a["q"]), p(a["k"]), p(a["v"]), p(a["zg"]), p(a["zt"]), p(a["zb"]), p(a["S0"]),
+                                                           p(a["x"]), p(a["d"]), p(a["z"]), act, p(a["o"]), p(a["S_T"]), p(a["cu"]), 3, total,
+                                                           2, 64, 128, 64, rodimus.BF16, p(ws), ctypes.c_size_t(ws_bytes), None)
+
+    assert call(act=9) == E_DTYPE and call(cu=None) == E_NULL and call(zt=None) == E_NULL and call(d=None) == E_NULL
+    assert call(o=0x8000000) == E_ALIAS and call(S_T=0xA000000) == E_ALIAS and call(z=0xA000004) == E_ALIGN
+    assert call(ws=0xE000000, ws_bytes=1000) == E_WS          # a workspace asks for the cut: it must then be large enough
+    assert call(ws=0xB000000, ws_bytes=1 << 30) == E_ALIAS    # ... and must not lie over the output
 
 
 def test_gated_block_calls_validation(L):
