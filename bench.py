@@ -31,7 +31,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (scaled by a plain copy kernel);
 # taken from the summaries under profiles/ (scan_mfma_kernel_layer_1p6b.md, decode_step_kernel_256x16.md).
-MEASURED_TRAFFIC_BYTES = {"scan_layer_1p6b": 1388.3e6, "decode_256x16": 54.8e6, "decode_512x16": 1094.8e6}   # profiles/*.md
+MEASURED_TRAFFIC_BYTES = {"scan_layer_1p6b": 1384.5e6, "decode_256x16": 547.6e6, "decode_512x16": 1094.8e6}   # profiles/*.md
 
 
 def warm_up(step, launches, min_seconds=0.08):
@@ -649,9 +649,10 @@ def main():
                 "GB_per_s_effective": dec["gbs"], "frac_of_hbm_peak": dec["gbs"] / HBM_PEAK_GBS, "ms_per_step": dec["launch_ms"],
                 "algorithmic_bytes": dec["algo_bytes"], "traffic": MEASURED_TRAFFIC_BYTES["decode_256x16"],
                 "traffic_source": "profiles/decode_step_kernel_256x16.md (counter figure of the profile run)",
-                "note": "256 sequences hold exactly 256 MiB of state, the size of the last-level cache: chained steps find it "
-                        "there (a tenth of the algorithmic bytes reach HBM), so this is a cache rate, not an HBM rate; with "
-                        "other layers running between two steps of a model it would not be reached"},
+                "note": "256 sequences hold exactly 256 MiB of state, the size of the last-level cache: chained steps find part "
+                        "of it there (the same step with streaming accesses takes 96 us; the traffic counters sit in front of "
+                        "that cache and read the full bytes), so this is a cache-assisted rate, not an HBM rate; with other "
+                        "layers running between two steps of a model it would not be reached"},
         }
         if not args.skip_cpu_baseline:
             out["decode"]["cpu_baseline"] = decode_cpu_baseline(dw, wl)

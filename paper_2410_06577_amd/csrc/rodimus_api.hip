@@ -50,7 +50,7 @@ int scan_entry(const void *q, const void *k, const void *v, const float *log_alp
     if (shape != RODIMUS_OK) return shape;
     if (packed && B > 0 && cu_seqlens == nullptr) return RODIMUS_ERR_NULL;
     if (packed && misaligned(cu_seqlens)) return RODIMUS_ERR_ALIGN;
-    if (packed && (long long)B * H * ((dv + 127) / 128) > kMaxGridX) return RODIMUS_ERR_SHAPE;      // the packed scan runs on a flat grid
+    if (packed && ((long long)B * H + 8) * ((dv + 127) / 128) > kMaxGridX) return RODIMUS_ERR_SHAPE;      // the packed scan runs on a flat grid, rounded up to whole runs of eight
     const size_t tokens = packed ? (size_t)T * H : (size_t)B * T * H;
     // the key-side gates: log_alpha (fp32), or in the gated form the two pre-activations (I/O dtype)
     const void *gate_a = gated ? z_g : static_cast<const void *>(log_alpha);

@@ -812,6 +812,16 @@ __device__ __forceinline__ void packed_rows(const int *__restrict__ cu_seqlens, 
 
 __device__ __forceinline__ int packed_segments(int len, int seg_tokens) { return max(1, (len + seg_tokens - 1) / seg_tokens); }
 
+// Flat grids over (pair, column tile), a pair being a (sequence or slot, head): workgroups go round-robin over the eight
+// XCDs (each with its own L2), so in every run of 8 * col_tiles workgroups the column tiles of a pair are 8 apart: on the
+// same XCD and started together, they share q, k and the gates in its L2.  The grid holds whole runs (packed_grid).
+__device__ __forceinline__ void xcd_pair_mapping(unsigned x, int col_tiles, int &pair, int &col_tile)
+{
+    const unsigned group = x / 8;
+    col_tile = (int)(group % (unsigned)col_tiles);
+    pair = (int)((group / (unsigned)col_tiles) * 8 + x % 8);
+}
+
 // kSummary = false: the scan proper over this workgroup's segment (blockIdx.z), reading its entering state.
 // kSummary = true : same walk from a zero state without q, scores or outputs; leaves the segment's state
 //                   increment in slot seg+1 and the segment's total decay in gamma[seg].
@@ -840,9 +850,10 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
         // Flat grid over (slot, head, column tile).  Which sequence the slot belongs to follows from the lengths of the
         // sequences before it: a short walk (the cut is only made when the batch holds few sequences), the same in every
         // lane, out of scalar registers.
-        const int col_tiles = dv / kColTile;
-        col_tile = blockIdx.x % col_tiles;
-        const int rest = blockIdx.x / col_tiles, slot = rest / H;
+        int rest;
+        xcd_pair_mapping(blockIdx.x, dv / kColTile, rest, col_tile);
+        if (rest >= plan.nseg * H) return;                   // the grid is rounded up to whole runs of eight pairs
+        const int slot = rest / H;
         int b = -1, before = 0, first = 0, last = 0, count = 0;
         for (int i = 0; i < total_seqs; ++i) {
             packed_rows(cu_seqlens, i, total_tokens, first, last);
@@ -871,13 +882,14 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
         if (bh >= total_seqs * H) return;                   // the grid is rounded up to whole runs
         slot_bh = bh;
     } else if (!kSummary && cu_seqlens != nullptr) {
-        // Packed batch, launched as a flat grid: the column tiles of one (sequence, head) are neighbours in dispatch order
-        // (they read the same q, k and gates while those are in the cache), and the workgroups take the sequences by
-        // descending length (small batches).
-        const int col_tiles = dv / kColTile, nseq = (int)(gridDim.x / (unsigned)(col_tiles * H));
-        col_tile = blockIdx.x % col_tiles;
-        const int slot = blockIdx.x / col_tiles, rank = slot / H;
-        const int b = sequence_by_length_rank(cu_seqlens, nseq, total_tokens, rank, reinterpret_cast<int *>(lds));   // the dynamic LDS is free until the walk starts
+        // Packed batch, launched as a flat grid: the column tiles of one (sequence, head) start together on one XCD (they
+        // read the same q, k and gates while those are in its L2), and the workgroups take the sequences by descending
+        // length (small batches).
+        int slot;
+        xcd_pair_mapping(blockIdx.x, dv / kColTile, slot, col_tile);
+        if (slot >= total_seqs * H) return;                  // the grid is rounded up to whole runs of eight pairs
+        const int rank = slot / H;
+        const int b = sequence_by_length_rank(cu_seqlens, total_seqs, total_tokens, rank, reinterpret_cast<int *>(lds));   // the dynamic LDS is free until the walk starts
         bh = __builtin_amdgcn_readfirstlane(b * H + slot % H);      // the same in every lane: keeps the row bases in scalar registers
         slot_bh = bh;
     }
@@ -1144,7 +1156,7 @@ SplitShape choose_packed_cut(int N, int total_tokens, int H, int dv)
     long long seg = ((long long)total_tokens * per_slot / 256 + kChunk - 1) / kChunk * kChunk;
     if (seg < 8 * kChunk) seg = 8 * kChunk;
     const long long slots = total_tokens / seg + N;
-    if (slots < 2 || slots * per_slot > 2147483647LL) return none;
+    if (slots < 2 || (slots * H + 8) * (dv / kColTile) > 2147483647LL) return none;      // the flat grid, rounded up to whole runs of eight
     return SplitShape{(int)slots, (int)seg};
 }
 
@@ -1209,7 +1221,8 @@ hipError_t launch_scan_mfma_typed(const ScanArgs &a)
     const void *gate_a = kGated ? a.z_g : static_cast<const void *>(a.log_alpha);
     const OutputStage no_stage{nullptr, nullptr, nullptr, 0};
     // dense cut: (batch, head) x column tile x segment; packed cut: one flat index over (slot, head, column tile)
-    const dim3 cut_grid = packed_cut ? dim3((unsigned)((size_t)sp.nseg * a.H * col_tiles)) : dim3((unsigned)bh, col_tiles, (unsigned)(sp.nseg - 1));
+    const auto packed_grid = [&](size_t pairs) { return dim3((unsigned)((pairs + 7) / 8 * 8 * col_tiles)); };      // see xcd_pair_mapping
+    const dim3 cut_grid = packed_cut ? packed_grid((size_t)sp.nseg * a.H) : dim3((unsigned)bh, col_tiles, (unsigned)(sp.nseg - 1));
     if (sp.nseg > 1) {
         const size_t per_slot = (packed_cut ? (size_t)a.H : bh) * kK;        // state rows in a slot
         plan.slots = static_cast<float *>(a.workspace);
@@ -1226,7 +1239,7 @@ hipError_t launch_scan_mfma_typed(const ScanArgs &a)
     // dense: (batch, head) x column tile x segment; packed: one flat index (see the kernel)
     const bool flat_dense = !packed && sp.nseg == 1 && col_tiles > 1 && bh * col_tiles > 256;
     const dim3 grid = packed_cut ? cut_grid
-                      : packed   ? dim3((unsigned)(bh * col_tiles))
+                      : packed   ? packed_grid(bh)
                       : flat_dense ? dim3((unsigned)((bh + 7) / 8 * 8 * col_tiles)) : dim3((unsigned)bh, col_tiles, (unsigned)sp.nseg);
     hipLaunchKernelGGL((scan_mfma_kernel<false, kBeta, kGated, kStage>), grid, block, lds_bytes(kStage != 0),
                        a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, gate_a, (const bf16_t *)a.z_tau, a.beta, a.S0,
