@@ -255,8 +255,8 @@ int rodimus_chunk_scan_varlen_fwd(const void *q, const void *k, const void *v,
  * total_tokens and hardly on the lengths; which call is faster is the caller's decision (it built cu_seqlens).  A
  * segment has total_tokens * H * (dv / 128) / 256 tokens (the share of one of the 256 compute units), rounded up to a
  * multiple of 64 and at least 512; as a rule this call wins when the longest sequence is longer than about 2.5
- * segments (measured at H = 16, dv = 256, 32768 tokens, segments of 4096: 405 us whatever the lengths, against 340 us
- * uncut when the longest sequence has 8192 tokens, 650 us at 16311 and 1020 us at 25045).
+ * segments (measured at H = 16, dv = 256, 32768 tokens, segments of 4096: 390 us whatever the lengths, against 330 us
+ * uncut when the longest sequence has 8192 tokens, 640 us at 16311 and 1000 us at 25045).
  *
  *   workspace   rodimus_chunk_scan_varlen_workspace_bytes(...) bytes of device memory, 16-byte aligned, contents
  *               undefined before and after; must not overlap any other argument.  The size depends on N and
