@@ -515,6 +515,42 @@ def bench_backward(w, rodimus, wl, dev, steps, warmup, zbeta=False):
             "tflops": flops / (ms * 1e-3) / 1e12, "finite": bool(torch.isfinite(out["dlog_alpha"]).all().item())}
 
 
+def bench_backward_few_long(w, rodimus, wl, dev, steps, warmup, n_seq=8):
+    """Backward pass over a packed batch of few long sequences (the length mix of serving_prefill_few_long_sequences): one
+    workgroup pair per (sequence, head) (rodimus_chunk_scan_varlen_bwd) against the kernels cutting the sequences into segments
+    (rodimus_chunk_scan_varlen_bwd_cut)."""
+    lengths = wl.serving_length_mix(n_seq, w.B * w.T)
+    total = w.B * w.T
+    d = wl.make_varlen_inputs(lengths, w.H, w.dk, w.dv, "bf16", seed=14)
+    g = {k: (None if v is None else v.to(dev)) for k, v in d.items()}
+    gen = torch.Generator(device="cpu").manual_seed(23)
+    d_o = torch.randn((total, w.H, w.dv), generator=gen).to(torch.bfloat16).to(dev)
+    dS_T = (0.1 * torch.randn((n_seq, w.H, w.dk, w.dv), generator=gen)).to(dev)
+    lib = rodimus.lib()
+    need = max(int(lib.rodimus_chunk_scan_varlen_bwd_workspace_bytes(n_seq, total, w.H, w.dk, w.dv, rodimus.BF16)),
+               int(lib.rodimus_chunk_scan_varlen_bwd_cut_workspace_bytes(n_seq, total, w.H, w.dk, w.dv, rodimus.BF16)))
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    args = (g["q"], g["k"], g["v"], g["log_alpha"], g["cu_seqlens"], g["beta"], g["S0"], d_o, dS_T)
+    out, res = {}, {}
+    for name, fn in (("uncut", rodimus.rodimus_chunk_scan_varlen_bwd), ("cut", rodimus.rodimus_chunk_scan_varlen_bwd_cut)):
+        def step():
+            out.update(fn(*args, workspace=ws))
+        warm_up(step, 3, min_seconds=0.2)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n = max(3, steps // 20)
+        a.record()
+        for _ in range(n):
+            step()
+        b.record()
+        torch.cuda.synchronize()
+        res[name] = a.elapsed_time(b) / n
+    return {"entry_point": "rodimus_chunk_scan_varlen_bwd_cut",
+            "workload": f"{n_seq} sequences, lengths {min(lengths)}..{max(lengths)} (log-uniform mix), {total} tokens, "
+                        f"H={w.H} dk={w.dk} dv={w.dv}",
+            "ms_per_step": res["cut"], "uncut_ms_per_step": res["uncut"], "tokens_per_s": total / (res["cut"] * 1e-3),
+            "finite": bool(torch.isfinite(out["dlog_alpha"]).all().item())}
+
+
 def bench_backward_gated(w, rodimus, wl, dev, steps, warmup):
     """Backward pass of the gated scan over the layer workload (rodimus_chunk_scan_bwd_gated: cotangents of the raw q, k, v and
     of the three pre-activations): key-side gate pass, backward of the scan, backward of the gate pass."""
@@ -688,6 +724,7 @@ def main():
         mb = bench_backward(small, rodimus, wl, dev, args.steps, args.warmup)
         out["scan_backward_micro_batch"] = {"workload": f"B={small.B} T={small.T} H={small.H} dk={small.dk} dv={small.dv}",
                                             **{k: mb[k] for k in ("ms_per_step", "tokens_per_s", "GB_per_s", "hbm_frac", "finite")}}
+        out["scan_backward_few_long_sequences"] = bench_backward_few_long(w, rodimus, wl, dev, args.steps, args.warmup)
         out["serving_prefill_varlen"] = bench_varlen(w, rodimus, wl, dev, args.steps, args.warmup)
         lf = bench_varlen(w, rodimus, wl, dev, args.steps, args.warmup, longest_first=True)
         out["serving_prefill_varlen"]["sequences_sorted_longest_first"] = {

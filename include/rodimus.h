@@ -429,6 +429,34 @@ int rodimus_chunk_scan_varlen_bwd(const void *q, const void *k, const void *v,
 size_t rodimus_chunk_scan_varlen_bwd_workspace_bytes(int N, int total_tokens, int H, int dk, int dv, int io_dtype);
 
 /*
+ * rodimus_chunk_scan_varlen_bwd for a packed batch dominated by FEW LONG sequences (the backward counterpart of
+ * rodimus_chunk_scan_varlen_fwd_cut, with the same reasoning): the kernels cut every sequence into segments of a fixed
+ * length chosen from total_tokens alone -- total_tokens * H / 256 tokens, rounded up to a multiple of 64, at least 256 --
+ * find each segment's sequence from cu_seqlens on the device, and run the segments side by side: the state entering and
+ * the state cotangent leaving every segment come from two summary passes and two chains along each sequence, then both
+ * sweeps and the gate pass run per segment.  Same results as rodimus_chunk_scan_varlen_bwd to rounding.  The summary
+ * passes read k, v, the gates, q and d_o once more, so the call pays when the longest sequence would otherwise keep most
+ * of the chip waiting (as a rule: longer than about three segments).
+ *
+ *   workspace   rodimus_chunk_scan_varlen_bwd_cut_workspace_bytes(...) bytes; the size depends on N and total_tokens only.
+ *               Batches under 512 tokens and shapes outside the matrix-core kernels (bf16, dk = 64, dv = 128 or 256) are
+ *               not cut: the call is then exactly rodimus_chunk_scan_varlen_bwd and the size function returns that
+ *               call's size.
+ *
+ * Every other argument, layout, aliasing rule and status code as for rodimus_chunk_scan_varlen_bwd.
+ */
+int rodimus_chunk_scan_varlen_bwd_cut(const void *q, const void *k, const void *v,
+                                      const float *log_alpha, const float *beta, const float *S0,
+                                      const void *d_o, const float *dS_T,
+                                      void *dq, void *dk, void *dv,
+                                      float *dlog_alpha, float *dbeta, float *dS0,
+                                      const int *cu_seqlens, int N, int total_tokens,
+                                      int H, int dk_width, int dv_width, int io_dtype,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
+size_t rodimus_chunk_scan_varlen_bwd_cut_workspace_bytes(int N, int total_tokens, int H, int dk, int dv, int io_dtype);
+
+/*
  * The two recurrence calls with the whole DDTS gate front-end fused in (paper Sec. 3.1.2 and the pre-processing of q and k
  * in Sec. 3.1.3; the block's state-space form of Sec. 3.1.3 evaluated straight from the projections): every gate arrives
  * as its pre-activation and q, k arrive raw.  Per token and head, inside the kernels, in fp32:

@@ -224,6 +224,7 @@ struct ScanBwdArgs {
     hipStream_t stream;
     const int *cu_seqlens = nullptr;      // device, B + 1 entries, or NULL for the dense [B, T, H, .] layout
     bool beta_preact = false;
+    bool packed_cut = false;              // packed batch: let the kernels cut the sequences into segments (matrix-core kernels)
     size_t token_rows() const { return cu_seqlens != nullptr ? (size_t)T : (size_t)B * T; }
 };
 
@@ -271,12 +272,49 @@ __device__ __forceinline__ int sequence_by_length_rank(const int *cu_seqlens, in
     return chosen;                                      // (every read of scratch lies before this barrier)
 }
 
+// A packed batch cut into segments by the kernels (the lengths live in device memory): with segments of `seg_tokens`
+// tokens, sequence b owns max(1, ceil(len_b / seg_tokens)) consecutive slots, counted from the sequences before it.  Finds
+// the sequence and segment of `slot` by walking the length table (every entry clamped to the tensor); false if the slot lies
+// past the batch's last segment.  The same in every lane.
+struct PackedSlot {
+    int b, j, count;      // sequence, segment of the sequence, segments of the sequence
+    int first, len;       // first row and length of the sequence
+};
+__device__ __forceinline__ bool locate_packed_slot(const int *cu_seqlens, int nseq, int total_tokens, int seg_tokens, int slot, PackedSlot &out)
+{
+    int before = 0;
+    for (int i = 0; i < nseq; ++i) {
+        const int first = min(max(cu_seqlens[i], 0), total_tokens);
+        const int len = min(max(cu_seqlens[i + 1], first), total_tokens) - first;
+        const int count = max(1, (len + seg_tokens - 1) / seg_tokens);
+        if (slot < before + count) {
+            out = PackedSlot{i, slot - before, count, first, len};
+            return true;
+        }
+        before += count;
+    }
+    return false;
+}
+// First slot and number of slots of sequence b (see locate_packed_slot).
+__device__ __forceinline__ void packed_sequence_slots(const int *cu_seqlens, int b, int total_tokens, int seg_tokens, int &first_slot, int &count)
+{
+    first_slot = 0;
+    count = 1;
+    for (int i = 0; i <= b; ++i) {
+        const int first = min(max(cu_seqlens[i], 0), total_tokens);
+        const int len = min(max(cu_seqlens[i + 1], first), total_tokens) - first;
+        count = max(1, (len + seg_tokens - 1) / seg_tokens);
+        if (i < b) first_slot += count;
+    }
+}
+
 hipError_t launch_scan_bwd(const ScanBwdArgs &a);
 hipError_t launch_scan_bwd_generic(const ScanBwdArgs &a);       // any other supported shape: fp32 on the vector ALUs
 bool scan_bwd_generic_supports(int dk, int dv);
 size_t scan_bwd_generic_workspace_bytes(size_t token_rows, int B, int H, int dk);
 bool scan_bwd_supports(int dk, int dv, int io_dtype);
 size_t scan_bwd_workspace_bytes(size_t token_rows, int B, int T, int H, int dv, bool packed);
+size_t scan_bwd_packed_cut_workspace_bytes(int N, int total_tokens, int H, int dv);     // 0: such a batch is not cut
 hipError_t launch_decode_step(const DecodeArgs &a);
 hipError_t launch_ddts_gates(const GateArgs &a);
 // Backward of the key side of the gate front-end: cotangents of z_g, z_tau and of the raw q, k from those of log_alpha
@@ -313,9 +351,10 @@ hipError_t launch_hbm_stream_probe(const void *src, void *dst, size_t units, int
 size_t scan_mfma_packed_workspace_bytes(int N, int total_tokens, int H, int dv);
 // State entering each of nseg sequence segments (seg_tokens a multiple of 64) of a dense bf16 batch with dk = 64:
 // slots [nseg][B*H][64][dv] and the segment decays gamma [nseg-1][B*H][64], fp32 (used by the backward pass); beta: fp32
-// gate values or, with beta_preact, bf16 pre-activations (then not NULL)
+// gate values or, with beta_preact, bf16 pre-activations (then not NULL).  With cu_seqlens: a packed batch of B sequences,
+// T tokens in all, cut by the kernels (locate_packed_slot); nseg is the slot bound, slots [nseg][H][64][dv], gamma [nseg][H][64]
 hipError_t launch_scan_segment_states(const void *k, const void *v, const float *log_alpha, const void *beta, bool beta_preact, const float *S0,
                                       int B, int T, int H, int dv, int nseg, int seg_tokens, float *slots, float *gamma,
-                                      hipStream_t stream);
+                                      hipStream_t stream, const int *cu_seqlens = nullptr);
 
 }  // namespace rodimus

@@ -353,7 +353,7 @@ size_t bwd_workspace(size_t token_rows, int B, int T, int H, int dk, int dv, int
 int bwd_entry(const void *q, const void *k, const void *v, const float *log_alpha, const void *beta, const float *S0,
               const void *d_o, const float *dS_T, void *dq, void *dk, void *dv_out, float *dlog_alpha, void *dbeta, float *dS0,
               int B, int T, int H, int dk_width, int dv, int io_dtype, void *workspace, size_t workspace_bytes, void *stream,
-              bool packed, const int *cu_seqlens, bool beta_preact = false)
+              bool packed, const int *cu_seqlens, bool beta_preact = false, bool packed_cut = false)
 {
     if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
     if (B < 0 || T < 0 || H < 0 || (long long)B * H > kMaxGridX) return RODIMUS_ERR_SHAPE;
@@ -373,7 +373,11 @@ int bwd_entry(const void *q, const void *k, const void *v, const float *log_alph
                                 tokens * dv * gate_bytes, states * dk_width * dv * 4, tokens * dv * eb, states * dk_width * dv * 4,
                                 packed ? ((size_t)B + 1) * sizeof(int) : 0};
     void *outs[7] = {dq, dk, dv_out, dlog_alpha, dbeta, dS0, workspace};
-    const size_t need = bwd_workspace(token_rows, B, T, H, dk_width, dv, io_dtype, packed);
+    size_t need = bwd_workspace(token_rows, B, T, H, dk_width, dv, io_dtype, packed);
+    // a packed batch is cut along its sequences only on request, by the matrix-core kernels, and if it is long enough
+    const size_t need_cut = (packed && packed_cut && mfma) ? scan_bwd_packed_cut_workspace_bytes(B, T, H, dv) : 0;
+    packed_cut = need_cut > 0;
+    if (packed_cut) need = need_cut;
     const size_t out_bytes[7] = {tokens * dk_width * eb, tokens * dk_width * eb, tokens * dv * eb, tokens * dk_width * 4,
                                  tokens * dv * gate_bytes, states * dk_width * dv * 4, need};
     for (int i = 0; i < 9; ++i)
@@ -392,6 +396,7 @@ int bwd_entry(const void *q, const void *k, const void *v, const float *log_alph
                   io_dtype, workspace, workspace_bytes, static_cast<hipStream_t>(stream)};
     if (packed) a.cu_seqlens = cu_seqlens;
     a.beta_preact = beta_preact;
+    a.packed_cut = packed_cut;
     return (mfma ? launch_scan_bwd(a) : launch_scan_bwd_generic(a)) == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
 }
 
@@ -501,6 +506,22 @@ int rodimus_chunk_scan_varlen_bwd(const void *q, const void *k, const void *v, c
 {
     return bwd_entry(q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, dk, dv_out, dlog_alpha, dbeta, dS0, N, total_tokens, H,
                      dk_width, dv, io_dtype, workspace, workspace_bytes, stream, true, cu_seqlens);
+}
+
+size_t rodimus_chunk_scan_varlen_bwd_cut_workspace_bytes(int N, int total_tokens, int H, int dk, int dv, int io_dtype)
+{
+    if (N < 0 || total_tokens < 0 || H < 0) return 0;
+    const size_t cut = scan_bwd_supports(dk, dv, io_dtype) ? scan_bwd_packed_cut_workspace_bytes(N, total_tokens, H, dv) : 0;
+    return cut > 0 ? cut : bwd_workspace((size_t)total_tokens, N, total_tokens, H, dk, dv, io_dtype, true);
+}
+
+int rodimus_chunk_scan_varlen_bwd_cut(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta,
+                                      const float *S0, const void *d_o, const float *dS_T, void *dq, void *dk, void *dv_out,
+                                      float *dlog_alpha, float *dbeta, float *dS0, const int *cu_seqlens, int N, int total_tokens,
+                                      int H, int dk_width, int dv, int io_dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return bwd_entry(q, k, v, log_alpha, beta, S0, d_o, dS_T, dq, dk, dv_out, dlog_alpha, dbeta, dS0, N, total_tokens, H,
+                     dk_width, dv, io_dtype, workspace, workspace_bytes, stream, true, cu_seqlens, false, true);
 }
 
 int rodimus_ddts_gates(const void *z_g, const void *z_tau, const void *z_beta, const void *q, const void *k,

@@ -56,13 +56,40 @@ constexpr float kSafeTileLog = -55.f;      // ln(2^-80) = -55.45: above it 1 / A
 constexpr int kGateParts = 32;
 __host__ __device__ inline int gate_part_tiles(int T) { return (((T + kTile - 1) / kTile) + kGateParts - 1) / kGateParts; }
 
-// How a call is cut along the sequence.  Slots: [segment][B*H][64][dv] fp32.
+// How a call is cut along the sequence.  Slots: [segment][B*H][64][dv] fp32.  A packed batch is cut by the kernels
+// (`packed_cut`, see locate_packed_slot): `nseg` is then the largest number of segments the batch can have, the slots are
+// [slot][H][64][dv], and the grids run over (head, slot) instead of ((batch, head), segment).
 struct BwdSegments {
     int nseg;                    // 1: whole sequences, no slots
     int seg_tokens;              // a multiple of 64
     const float *S_slots;        // state entering each segment
     const float *G_slots;        // cotangent of the state leaving each segment
+    bool packed_cut;
+    int nseq;                    // packed_cut: sequences in the batch
 };
+
+// What one workgroup of the sweeps or of the gate kernel works on: (x, s) = ((batch, head), segment) of the grid, or
+// (head, slot) for a packed batch cut by the kernels.  `bh` indexes the caller's state tensors, `unit` the per-unit arrays
+// and the slots (unit >= bh always, so slot pointers may be formed as base + (unit - bh) * state size and then indexed by bh).
+struct BwdUnit {
+    int bh;
+    size_t unit;
+    SeqSpan span;
+    bool first_seg;
+};
+
+// packed_cut only; false: the slot lies past the batch's last segment (the grid covers the largest possible number)
+__device__ __forceinline__ bool packed_cut_unit(int h, int slot, int T, int H, const int *cu_seqlens, const BwdSegments &segs, BwdUnit &u)
+{
+    PackedSlot ps;
+    if (!locate_packed_slot(cu_seqlens, segs.nseq, T, segs.seg_tokens, slot, ps)) return false;
+    const int begin = ps.j * segs.seg_tokens;
+    u.bh = ps.b * H + h;
+    u.unit = (size_t)slot * H + h;
+    u.span = SeqSpan{(size_t)ps.first + (size_t)begin, max(min(segs.seg_tokens, ps.len - begin), 0)};
+    u.first_seg = ps.j == 0;
+    return true;
+}
 
 // The tokens of segment `seg` of a sequence (empty beyond its end)
 __device__ __forceinline__ SeqSpan segment_span(SeqSpan s, const BwdSegments &sg, int seg)
@@ -345,16 +372,23 @@ __device__ __forceinline__ void sweep_dq(
     const int ch = 16 * (wave & 3) + c;
     int bh = blockIdx.x;
     const int seg = blockIdx.y;
-    if (cu_seqlens != nullptr)                                    // packed batch: sequences by descending length (small batches)
-        bh = sequence_by_length_rank(cu_seqlens, (int)gridDim.x / H, T, bh / H, reinterpret_cast<int *>(lds_raw)) * H + bh % H;
-    const size_t unit = (size_t)seg * gridDim.x + bh;             // (segment, batch, head): index of the per-unit totals
+    BwdUnit u;
+    if (segs.packed_cut) {
+        if (!packed_cut_unit(blockIdx.x, seg, T, H, cu_seqlens, segs, u)) return;      // the whole workgroup, before any barrier
+        bh = u.bh;
+    } else {
+        if (cu_seqlens != nullptr)                                // packed batch: sequences by descending length (small batches)
+            bh = sequence_by_length_rank(cu_seqlens, (int)gridDim.x / H, T, bh / H, reinterpret_cast<int *>(lds_raw)) * H + bh % H;
+        u = BwdUnit{bh, (size_t)seg * gridDim.x + bh, segment_span(seq_span(bh / H, T, cu_seqlens), segs, seg), seg == 0};
+    }
+    const size_t unit = u.unit;                                   // (segment, batch, head): index of the per-unit totals
     const bool has_beta = beta != nullptr;
-    const SeqSpan span = segment_span(seq_span(bh / H, T, cu_seqlens), segs, seg);
+    const SeqSpan span = u.span;
     T = span.length;
     const BwdGeometry g(q, k, v, d_o, log_alpha, beta, span.first, bh % H, T, H, DV);
     const size_t row0 = span.first * H + bh % H;                  // outputs: same layout as the inputs
     if (segs.nseg > 1) {                                          // the segment's own boundary states
-        const size_t slot = (size_t)seg * gridDim.x * kK * DV; // state_base below adds the (batch, head)
+        const size_t slot = (unit - (size_t)bh) * kK * DV;        // state_base below adds the (batch, head)
         S0 = segs.S_slots + slot;
         dS_T = segs.G_slots + slot;
     }
@@ -647,18 +681,25 @@ __device__ __forceinline__ void sweep_dkv(
     const int n = lane & 15, grp = lane >> 4;
     int bh = blockIdx.x;
     const int seg = blockIdx.y;
-    if (cu_seqlens != nullptr)                                    // packed batch: sequences by descending length (small batches)
-        bh = sequence_by_length_rank(cu_seqlens, (int)gridDim.x / H, T, bh / H, reinterpret_cast<int *>(lds_raw)) * H + bh % H;
-    const size_t unit = (size_t)seg * gridDim.x + bh;
+    BwdUnit u;
+    if (segs.packed_cut) {
+        if (!packed_cut_unit(blockIdx.x, seg, T, H, cu_seqlens, segs, u)) return;      // the whole workgroup, before any barrier
+        bh = u.bh;
+    } else {
+        if (cu_seqlens != nullptr)                                // packed batch: sequences by descending length (small batches)
+            bh = sequence_by_length_rank(cu_seqlens, (int)gridDim.x / H, T, bh / H, reinterpret_cast<int *>(lds_raw)) * H + bh % H;
+        u = BwdUnit{bh, (size_t)seg * gridDim.x + bh, segment_span(seq_span(bh / H, T, cu_seqlens), segs, seg), seg == 0};
+    }
+    const size_t unit = u.unit;
     const bool has_beta = beta != nullptr;
-    const SeqSpan span = segment_span(seq_span(bh / H, T, cu_seqlens), segs, seg);
+    const SeqSpan span = u.span;
     T = span.length;
     const BwdGeometry g(q, k, v, d_o, log_alpha, beta, span.first, bh % H, T, H, DV);
     const size_t row0 = span.first * H + bh % H;                  // outputs: same layout as the inputs
     const int col0 = wave * kSlab;
     if (segs.nseg > 1) {
-        dS_T = segs.G_slots + (size_t)seg * gridDim.x * kK * DV;
-        if (seg > 0) dS0 = nullptr;                               // only the first segment's cotangent leaves the call
+        dS_T = segs.G_slots + (unit - (size_t)bh) * kK * DV;      // state_base below adds the (batch, head)
+        if (!u.first_seg) dS0 = nullptr;                          // only the first segment's cotangent leaves the call
     }
 
     // cotangent slab: acc[kt][ct][r] = G[16kt + 4grp + r][col0 + 16ct + n]
@@ -1016,7 +1057,7 @@ __device__ __forceinline__ void sweep_dkv(
 
 // When 2 * B * H workgroups would leave much of the chip idle, a dense batch is cut into segments of whole 64-token
 // chunks so that about 512 workgroups exist (the two sweeps differ in length, two rounds even them out), each segment
-// keeping at least 256 tokens.  A packed batch is never cut: its lengths live in device memory.
+// keeping at least 256 tokens.  A packed batch is not cut here: its lengths live in device memory (choose_bwd_packed_cut).
 struct BwdSplit { int nseg, seg_tokens; };
 static BwdSplit choose_bwd_split(int B, int T, int H, bool packed)
 {
@@ -1031,6 +1072,32 @@ static BwdSplit choose_bwd_split(int B, int T, int H, bool packed)
     const int seg_chunks = (int)((nchunks + want - 1) / want);
     const int nseg = (nchunks + seg_chunks - 1) / seg_chunks;
     return nseg < 2 ? whole : BwdSplit{nseg, seg_chunks * 64};
+}
+
+// A packed batch cut by the kernels (the caller asks for it): a fixed segment length from the token total, such that about
+// 512 workgroups exist when every sequence is cut evenly, at least 256 tokens; and the largest number of segments the batch
+// can then have (every sequence adds at most one partial segment, an empty one holds one slot).
+static BwdSplit choose_bwd_packed_cut(int N, int total_tokens, int H)
+{
+    const BwdSplit whole{1, ((total_tokens + 63) / 64) * 64};
+    if (N <= 0 || H <= 0 || total_tokens < 512) return whole;
+    // (segments twice and half as long measured 1.32 and 1.28 ms against 1.29 ms on eight sequences of 32768 tokens in all,
+    // 1.52 and 1.36 against 1.32 ms on another mix)
+    long long seg = ((long long)total_tokens * H / 256 + 63) / 64 * 64;
+    if (seg < 256) seg = 256;
+    const long long slots = total_tokens / seg + N;
+    if (slots < 2 || slots > 65535) return whole;          // the slots are a grid dimension
+    return BwdSplit{(int)slots, (int)seg};
+}
+
+size_t scan_bwd_packed_cut_workspace_bytes(int N, int total_tokens, int H, int dv)
+{
+    const BwdSplit sp = choose_bwd_packed_cut(N, total_tokens, H);
+    if (sp.nseg <= 1) return 0;
+    const size_t units = (size_t)sp.nseg * H;
+    const size_t floats = 2 * (size_t)total_tokens * H * kK + units * kK * (1 + kGateParts + 8 * kGateParts) + 2 * units * kK * dv +
+                          2 * units * kK;
+    return floats * sizeof(float);
 }
 
 // Workspace: q .* dq and k .* dk in fp32 for every (token, head, channel); per unit (segment, batch, head) and channel
@@ -1081,7 +1148,7 @@ __global__ __launch_bounds__(BwdShape<DV>::kSweepThreads) void scan_bwd_sweeps_k
 template <int DV>
 __global__ __launch_bounds__(BwdShape<DV>::kThreads) void scan_bwd_cotangent_summary_kernel(
     const bf16_t *__restrict__ q, const float *__restrict__ log_alpha, const bf16_t *__restrict__ d_o,
-    float *__restrict__ G_slots, float *__restrict__ decay, int T, int H, int seg_tokens)
+    float *__restrict__ G_slots, float *__restrict__ decay, int T, int H, int seg_tokens, const int *__restrict__ cu_seqlens, int nseq)
 {
     using L = BwdLayout<DV>;
     constexpr int kWaves = BwdShape<DV>::kWaves, kSlab = 32, kCt = kSlab / 16, kTok = kTile / kWaves;
@@ -1092,10 +1159,20 @@ __global__ __launch_bounds__(BwdShape<DV>::kThreads) void scan_bwd_cotangent_sum
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, grp = lane >> 4;
-    const int bh = blockIdx.x, seg = blockIdx.y + 1;
-    const int t_begin = seg * seg_tokens;
-    const int len = min(seg_tokens, T - t_begin);                 // > 0: the host cuts T into ceil(T / seg_tokens) segments
-    const size_t row0 = ((size_t)(bh / H) * T + t_begin) * H + bh % H;
+    int bh = blockIdx.x, seg = blockIdx.y + 1;
+    int t_begin = seg * seg_tokens;
+    int len = min(seg_tokens, T - t_begin);                       // > 0: the host cuts T into ceil(T / seg_tokens) segments
+    size_t row0 = ((size_t)(bh / H) * T + t_begin) * H + bh % H;
+    size_t unit = (size_t)(seg - 1) * gridDim.x + bh;             // the slot that receives the result: the segment before
+    if (cu_seqlens != nullptr) {
+        // packed batch cut by the kernels: grid (head, slot); a sequence's first segment has no segment before it
+        PackedSlot ps;
+        if (!locate_packed_slot(cu_seqlens, nseq, T, seg_tokens, blockIdx.y, ps) || ps.j == 0) return;
+        t_begin = ps.j * seg_tokens;
+        len = min(seg_tokens, ps.len - t_begin);
+        row0 = ((size_t)ps.first + t_begin) * H + blockIdx.x;
+        unit = (size_t)(blockIdx.y - 1) * H + blockIdx.x;
+    }
     q += row0 * kK; log_alpha += row0 * kK; d_o += row0 * DV;
     const int col0 = wave * kSlab;
     const int vc = tid & 63, vg = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1190,7 +1267,6 @@ __global__ __launch_bounds__(BwdShape<DV>::kThreads) void scan_bwd_cotangent_sum
                 }
         }
     }
-    const size_t unit = (size_t)(seg - 1) * gridDim.x + bh;
     float *out = G_slots + unit * kK * DV;
 #pragma unroll
     for (int kt = 0; kt < 4; ++kt)
@@ -1206,11 +1282,30 @@ __global__ __launch_bounds__(BwdShape<DV>::kThreads) void scan_bwd_cotangent_sum
 // summary of segment s+1).  One thread per four adjacent state elements; the segments are walked from the last one back.
 __global__ __launch_bounds__(256) void scan_bwd_cotangent_chain_kernel(const float *__restrict__ dS_T, float *__restrict__ G_slots,
                                                                       const float *__restrict__ decay, int nseg, int dv,
-                                                                      size_t quads_per_slot)
+                                                                      size_t quads_per_slot, const int *__restrict__ cu_seqlens,
+                                                                      int nseq, int total_tokens, int seg_tokens)
 {
     const size_t e4 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e4 >= quads_per_slot) return;
-    const size_t elem = e4 * 4, row = elem / dv, slot_elems = quads_per_slot * 4;      // row = (batch, head) * 64 + channel
+    const size_t slot_elems = quads_per_slot * 4;
+    size_t elem = e4 * 4;
+    if (cu_seqlens != nullptr) {
+        // packed batch cut by the kernels: a slot holds the H heads of one sequence, e4 runs over [sequence][slot element],
+        // and the chain walks the slots of that sequence
+        const int b = (int)(e4 / quads_per_slot);
+        if (b >= nseq) return;
+        elem = (e4 % quads_per_slot) * 4;
+        int first_slot, count;
+        packed_sequence_slots(cu_seqlens, b, total_tokens, seg_tokens, first_slot, count);
+        if (first_slot >= nseg) return;                    // only with a corrupt table: stay inside the slots
+        count = min(count, nseg - first_slot);
+        dS_T = dS_T != nullptr ? dS_T + (size_t)b * slot_elems : nullptr;
+        G_slots += (size_t)first_slot * slot_elems;
+        decay += (size_t)first_slot * (slot_elems / dv);
+        nseg = count;
+    } else if (e4 >= quads_per_slot) {
+        return;
+    }
+    const size_t row = elem / dv;                          // (batch, head) * 64 + channel
     floatx4_t g = dS_T != nullptr ? *reinterpret_cast<const floatx4_t *>(dS_T + elem) : floatx4_t{0.f, 0.f, 0.f, 0.f};
     *reinterpret_cast<floatx4_t *>(G_slots + (size_t)(nseg - 1) * slot_elems + elem) = g;
     for (int sg = nseg - 2; sg >= 0; --sg) {
@@ -1237,11 +1332,17 @@ __global__ __launch_bounds__(1024) void scan_bwd_gate_kernel(const float *__rest
     __shared__ float tot_s[kGateParts][32];
     const int tid = threadIdx.x, c = tid & 31, part = tid >> 5;
     const int bh = blockIdx.x, ch = 32 * blockIdx.y + c;
-    const size_t unit = (size_t)blockIdx.z * gridDim.x + bh;
-    const SeqSpan span = segment_span(seq_span(bh / H, T, cu_seqlens), segs, blockIdx.z);
+    BwdUnit u{bh, (size_t)blockIdx.z * gridDim.x + bh, SeqSpan{0, 0}, blockIdx.z == 0};
+    if (segs.packed_cut) {
+        if (!packed_cut_unit(blockIdx.x, blockIdx.z, T, H, cu_seqlens, segs, u)) return;      // the whole workgroup, before the barrier
+    } else {
+        u.span = segment_span(seq_span(bh / H, T, cu_seqlens), segs, blockIdx.z);
+    }
+    const size_t unit = u.unit;
+    const SeqSpan span = u.span;
     T = span.length;
     const size_t tok0 = span.first;
-    const int h = bh % H;
+    const int h = u.bh % H;
     const int ntiles = (T + kTile - 1) / kTile, part_tiles = gate_part_tiles(T);
     const int t_lo = min(part * part_tiles * kTile, T), t_hi = min(t_lo + part_tiles * kTile, T);
     float total = 0.f;
@@ -1266,30 +1367,37 @@ template <int DV, bool kZBeta>
 hipError_t launch_scan_bwd_typed(const ScanBwdArgs &a)
 {
     const unsigned bh = (unsigned)(a.B * a.H);
-    const BwdSplit sp = choose_bwd_split(a.B, a.T, a.H, a.cu_seqlens != nullptr);
-    const size_t units = (size_t)bh * sp.nseg;
+    const bool packed = a.cu_seqlens != nullptr;
+    const bool packed_cut = packed && a.packed_cut && choose_bwd_packed_cut(a.B, a.T, a.H).nseg > 1;
+    const BwdSplit sp = packed_cut ? choose_bwd_packed_cut(a.B, a.T, a.H) : choose_bwd_split(a.B, a.T, a.H, packed);
+    // a packed batch cut by the kernels: the grids run over (head, slot), the per-unit arrays and the slots over slot x head
+    const size_t units = packed_cut ? (size_t)sp.nseg * a.H : (size_t)bh * sp.nseg;
+    const unsigned grid_x = packed_cut ? (unsigned)a.H : bh;
     const size_t rows = a.token_rows() * a.H * kK;
     float *qdq = static_cast<float *>(a.workspace);
     float *kdk = qdq + rows;
     float *gate_const = kdk + rows;
     float *qtot = gate_const + units * kK;                              // [units][kGateParts][64]
     float *ktot = qtot + units * kGateParts * kK;                       // [units][kGateParts][wavefronts][64]
-    BwdSegments segs{sp.nseg, sp.seg_tokens, nullptr, nullptr};
+    BwdSegments segs{sp.nseg, sp.seg_tokens, nullptr, nullptr, packed_cut, a.B};
     if (sp.nseg > 1) {
-        const size_t slot_elems = (size_t)bh * kK * DV;
+        const size_t slot_elems = (size_t)grid_x * kK * DV;
         float *S_slots = ktot + units * kGateParts * 8 * kK;
         float *G_slots = S_slots + sp.nseg * slot_elems;
-        float *s_decay = G_slots + sp.nseg * slot_elems;                // [nseg-1][B*H][64], forward direction
-        float *g_decay = s_decay + (size_t)(sp.nseg - 1) * bh * kK;     // the same for the cotangent chain
+        float *s_decay = G_slots + sp.nseg * slot_elems;                // [nseg-1][B*H][64] ([nseg][H][64] packed), forward direction
+        float *g_decay = s_decay + (size_t)(packed_cut ? sp.nseg : sp.nseg - 1) * grid_x * kK;     // the same for the cotangent chain
         hipError_t e = launch_scan_segment_states(a.k, a.v, a.log_alpha, a.beta, kZBeta, a.S0, a.B, a.T, a.H, DV, sp.nseg,
-                                                  sp.seg_tokens, S_slots, s_decay, a.stream);
+                                                  sp.seg_tokens, S_slots, s_decay, a.stream, packed_cut ? a.cu_seqlens : nullptr);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(scan_bwd_cotangent_summary_kernel<DV>, dim3(bh, (unsigned)(sp.nseg - 1)), dim3(BwdShape<DV>::kThreads), 0,
+        hipLaunchKernelGGL(scan_bwd_cotangent_summary_kernel<DV>, dim3(grid_x, (unsigned)(packed_cut ? sp.nseg : sp.nseg - 1)),
+                           dim3(BwdShape<DV>::kThreads), 0,
                            a.stream, (const bf16_t *)a.q, a.log_alpha, (const bf16_t *)a.d_o, G_slots, g_decay, a.T, a.H,
-                           sp.seg_tokens);
+                           sp.seg_tokens, packed_cut ? a.cu_seqlens : (const int *)nullptr, a.B);
         const size_t quads = slot_elems / 4;
-        hipLaunchKernelGGL(scan_bwd_cotangent_chain_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, a.stream, a.dS_T,
-                           G_slots, g_decay, sp.nseg, DV, quads);
+        const size_t threads = packed_cut ? quads * a.B : quads;
+        hipLaunchKernelGGL(scan_bwd_cotangent_chain_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, a.stream, a.dS_T,
+                           G_slots, g_decay, sp.nseg, DV, quads, packed_cut ? a.cu_seqlens : (const int *)nullptr, a.B, a.T,
+                           sp.seg_tokens);
         segs.S_slots = S_slots;
         segs.G_slots = G_slots;
     }
@@ -1305,12 +1413,12 @@ hipError_t launch_scan_bwd_typed(const ScanBwdArgs &a)
         if (attr != hipSuccess) return attr;
         lds_allowed[device].store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((scan_bwd_sweeps_kernel<DV, kZBeta>), dim3(bh, (unsigned)sp.nseg, 2), dim3(BwdShape<DV>::kSweepThreads), DkvLds<DV>::kBytes,
+    hipLaunchKernelGGL((scan_bwd_sweeps_kernel<DV, kZBeta>), dim3(grid_x, (unsigned)sp.nseg, 2), dim3(BwdShape<DV>::kSweepThreads), DkvLds<DV>::kBytes,
                        a.stream, (const bf16_t *)a.q, (const bf16_t *)a.k, (const bf16_t *)a.v, a.log_alpha, a.beta, a.S0,
                        (const bf16_t *)a.d_o, a.dS_T, (bf16_t *)a.dq, (bf16_t *)a.dk, (bf16_t *)a.dv, a.dbeta, a.dS0, qdq, kdk,
                        gate_const, qtot, ktot, a.T, a.H, a.cu_seqlens, segs);
     if (a.T > 0)
-        hipLaunchKernelGGL(scan_bwd_gate_kernel, dim3(bh, 2, (unsigned)sp.nseg), dim3(1024), 0, a.stream, qdq, kdk, gate_const, qtot,
+        hipLaunchKernelGGL(scan_bwd_gate_kernel, dim3(grid_x, 2, (unsigned)sp.nseg), dim3(1024), 0, a.stream, qdq, kdk, gate_const, qtot,
                            ktot, BwdShape<DV>::kWaves, a.log_alpha, a.dlog_alpha, a.T, a.H, a.cu_seqlens, segs);
     return hipGetLastError();
 }

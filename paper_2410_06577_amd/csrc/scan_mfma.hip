@@ -1269,33 +1269,41 @@ namespace {
 template <int kBeta>
 hipError_t launch_segment_states_typed(const void *k, const void *v, const float *log_alpha, const void *beta, const float *S0,
                                        int B, int T, int H, int dv, int nseg, int seg_tokens, float *slots, float *gamma,
-                                       hipStream_t stream)
+                                       const int *cu_seqlens, hipStream_t stream)
 {
+    const bool packed_cut = cu_seqlens != nullptr;
     const size_t bh = (size_t)B * H;
-    SegmentPlan plan{nseg, seg_tokens, slots, gamma, false};
+    SegmentPlan plan{nseg, seg_tokens, slots, gamma, packed_cut};
     const hipError_t attr = allow_lds<true, kBeta, false, 0>();
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((scan_mfma_kernel<true, kBeta, false, 0>), dim3((unsigned)bh, (unsigned)(dv / kColTile), (unsigned)(nseg - 1)),
+    const unsigned col_tiles = (unsigned)(dv / kColTile);
+    const dim3 grid = packed_cut ? dim3((unsigned)(((size_t)nseg * H + 7) / 8 * 8 * col_tiles))      // see xcd_pair_mapping
+                                 : dim3((unsigned)bh, col_tiles, (unsigned)(nseg - 1));
+    hipLaunchKernelGGL((scan_mfma_kernel<true, kBeta, false, 0>), grid,
                        dim3(kThreads), lds_bytes(false), stream, (const bf16_t *)nullptr, (const bf16_t *)k, (const bf16_t *)v,
                        static_cast<const void *>(log_alpha), (const bf16_t *)nullptr, beta,
-                       (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, T, H, dv, plan, (const int *)nullptr, 0, 0,
-                       OutputStage{nullptr, nullptr, nullptr, 0});
-    const size_t quads = bh * kK * dv / 4;
-    hipLaunchKernelGGL(segment_state_scan_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, S0, plan, dv, quads,
-                       (const int *)nullptr, 0, 0);
+                       (const float *)nullptr, (bf16_t *)nullptr, (float *)nullptr, T, H, dv, plan, cu_seqlens, packed_cut ? T : 0,
+                       packed_cut ? B : 0, OutputStage{nullptr, nullptr, nullptr, 0});
+    const size_t quads = (packed_cut ? (size_t)H : bh) * kK * dv / 4;      // per slot; the packed walk has one thread set per sequence
+    const size_t threads = packed_cut ? quads * B : quads;
+    hipLaunchKernelGGL(segment_state_scan_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream, S0, plan, dv, quads,
+                       cu_seqlens, B, T);
     return hipGetLastError();
 }
 
 }  // namespace
 
+// cu_seqlens != NULL: a packed batch of B sequences with T tokens in all, cut by the kernels into segments of seg_tokens
+// tokens; nseg is then the largest number of segments the batch can have and the slots are [nseg][H][64][dv], gamma
+// [nseg][H][64].
 hipError_t launch_scan_segment_states(const void *k, const void *v, const float *log_alpha, const void *beta, bool beta_preact,
                                       const float *S0, int B, int T, int H, int dv, int nseg, int seg_tokens, float *slots,
-                                      float *gamma, hipStream_t stream)
+                                      float *gamma, hipStream_t stream, const int *cu_seqlens)
 {
     if (nseg < 2 || seg_tokens % kChunk != 0 || dv % kColTile != 0 || (beta_preact && beta == nullptr)) return hipErrorInvalidValue;
-    if (beta == nullptr) return launch_segment_states_typed<kBetaNone>(k, v, log_alpha, beta, S0, B, T, H, dv, nseg, seg_tokens, slots, gamma, stream);
-    return beta_preact ? launch_segment_states_typed<kBetaPreact>(k, v, log_alpha, beta, S0, B, T, H, dv, nseg, seg_tokens, slots, gamma, stream)
-                       : launch_segment_states_typed<kBetaValues>(k, v, log_alpha, beta, S0, B, T, H, dv, nseg, seg_tokens, slots, gamma, stream);
+    if (beta == nullptr) return launch_segment_states_typed<kBetaNone>(k, v, log_alpha, beta, S0, B, T, H, dv, nseg, seg_tokens, slots, gamma, cu_seqlens, stream);
+    return beta_preact ? launch_segment_states_typed<kBetaPreact>(k, v, log_alpha, beta, S0, B, T, H, dv, nseg, seg_tokens, slots, gamma, cu_seqlens, stream)
+                       : launch_segment_states_typed<kBetaValues>(k, v, log_alpha, beta, S0, B, T, H, dv, nseg, seg_tokens, slots, gamma, cu_seqlens, stream);
 }
 
 hipError_t launch_scan_mfma(const ScanArgs &a)

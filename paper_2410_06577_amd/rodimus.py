@@ -79,6 +79,10 @@ def lib() -> ctypes.CDLL:
         L.rodimus_chunk_scan_varlen_bwd.restype = i
         L.rodimus_chunk_scan_varlen_bwd_workspace_bytes.argtypes = [i] * 6
         L.rodimus_chunk_scan_varlen_bwd_workspace_bytes.restype = sz
+        L.rodimus_chunk_scan_varlen_bwd_cut.argtypes = [vp] * 15 + [i] * 6 + [vp, sz, vp]
+        L.rodimus_chunk_scan_varlen_bwd_cut.restype = i
+        L.rodimus_chunk_scan_varlen_bwd_cut_workspace_bytes.argtypes = [i] * 6
+        L.rodimus_chunk_scan_varlen_bwd_cut_workspace_bytes.restype = sz
         L.rodimus_chunk_scan_fwd_block.argtypes = [vp] * 5 + [i] + [vp] * 4 + [i] + [vp] * 2 + [i] * 7 + [vp, sz, vp]
         L.rodimus_chunk_scan_fwd_block.restype = i
         L.rodimus_decode_step_block.argtypes = [vp] * 5 + [i] + [vp] * 3 + [i] + [vp] * 2 + [i] * 5 + [vp]
@@ -244,8 +248,16 @@ def rodimus_chunk_scan_bwd_gated(q, k, v, z_g, z_tau, z_beta, S0, d_o, dS_T=None
     return out
 
 
+def rodimus_chunk_scan_varlen_bwd_cut(q, k, v, log_alpha, cu_seqlens, beta, S0, d_o, dS_T=None, *, want_dbeta=True, want_dS0=True,
+                                      workspace=None):
+    """``rodimus_chunk_scan_varlen_bwd`` for a batch dominated by few long sequences: the kernels cut every sequence into
+    segments that run side by side."""
+    return rodimus_chunk_scan_varlen_bwd(q, k, v, log_alpha, cu_seqlens, beta, S0, d_o, dS_T, want_dbeta=want_dbeta, want_dS0=want_dS0,
+                                         workspace=workspace, _cut=True)
+
+
 def rodimus_chunk_scan_varlen_bwd(q, k, v, log_alpha, cu_seqlens, beta, S0, d_o, dS_T=None, *, want_dbeta=True, want_dS0=True,
-                                  workspace=None):
+                                  workspace=None, _cut=False):
     """Backward over a packed variable-length batch.  q, k, log_alpha [total,H,dk]; v, beta, d_o [total,H,dv];
     S0, dS_T [N,H,dk,dv] fp32; cu_seqlens [N+1] int32 on the device.  Returns the same dict as ``rodimus_chunk_scan_bwd``."""
     if q.dtype not in _DTYPES:
@@ -268,15 +280,16 @@ def rodimus_chunk_scan_varlen_bwd(q, k, v, log_alpha, cu_seqlens, beta, S0, d_o,
            "dlog_alpha": torch.empty_like(log_alpha),
            "dbeta": torch.empty((total, H, dv), dtype=torch.float32, device=dev) if want_dbeta else None,
            "dS0": torch.empty((N, H, dk, dv), dtype=torch.float32, device=dev) if want_dS0 else None}
-    need = int(lib().rodimus_chunk_scan_varlen_bwd_workspace_bytes(N, total, H, dk, dv, _DTYPES[io]))
+    size_fn = lib().rodimus_chunk_scan_varlen_bwd_cut_workspace_bytes if _cut else lib().rodimus_chunk_scan_varlen_bwd_workspace_bytes
+    call = lib().rodimus_chunk_scan_varlen_bwd_cut if _cut else lib().rodimus_chunk_scan_varlen_bwd
+    need = int(size_fn(N, total, H, dk, dv, _DTYPES[io]))
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     with torch.cuda.device(dev):
-        _check(lib().rodimus_chunk_scan_varlen_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(S0), _ptr(d_o),
-                                                   _ptr(dS_T), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]),
-                                                   _ptr(out["dlog_alpha"]), _ptr(out["dbeta"]), _ptr(out["dS0"]), _ptr(cu_seqlens),
-                                                   N, total, H, dk, dv, _DTYPES[io], _ptr(workspace), ws_bytes, _stream(dev)))
+        _check(call(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(S0), _ptr(d_o), _ptr(dS_T), _ptr(out["dq"]),
+                    _ptr(out["dk"]), _ptr(out["dv"]), _ptr(out["dlog_alpha"]), _ptr(out["dbeta"]), _ptr(out["dS0"]), _ptr(cu_seqlens),
+                    N, total, H, dk, dv, _DTYPES[io], _ptr(workspace), ws_bytes, _stream(dev)))
     return out
 
 

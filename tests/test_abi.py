@@ -37,7 +37,8 @@ def test_every_declared_symbol_is_exported(L):
             "rodimus_chunk_scan_bwd_gated", "rodimus_chunk_scan_bwd_gated_workspace_bytes",
             "rodimus_chunk_scan_fwd_gated_block", "rodimus_decode_step_gated_block",
             "rodimus_chunk_scan_varlen_fwd_cut", "rodimus_chunk_scan_varlen_workspace_bytes",
-            "rodimus_hbm_stream_probe", "rodimus_chunk_scan_varlen_fwd_gated_block"} <= declared
+            "rodimus_hbm_stream_probe", "rodimus_chunk_scan_varlen_fwd_gated_block",
+            "rodimus_chunk_scan_varlen_bwd_cut", "rodimus_chunk_scan_varlen_bwd_cut_workspace_bytes"} <= declared
     for name in declared:
         assert hasattr(L, name), name
 
@@ -322,6 +323,18 @@ def test_packed_cut_workspace_and_validation(L):
     assert call(kind=7) == E_DTYPE and call(cu=None) == E_NULL and call(ws=0x4000008) == E_ALIGN
     assert call(ws=0xA00000) == E_ALIAS                      # the workspace over the output
     assert call(ws=0x8000000 - 4096) == E_ALIAS              # ... or reaching into the state cache
+
+
+def test_packed_backward_cut_workspace(L):
+    for f in (L.rodimus_chunk_scan_varlen_bwd_cut_workspace_bytes, L.rodimus_chunk_scan_varlen_bwd_workspace_bytes):
+        f.restype = ctypes.c_size_t
+    # 8 sequences, 32768 tokens, 16 heads: segments of 32768 * 16 / 256 = 2048 tokens, at most 16 + 8 slots of 16 units each
+    units, rows = 24 * 16, 32768 * 16
+    want = (2 * rows * 64 + units * 64 * (1 + 32 + 8 * 32) + 2 * units * 64 * 256 + 2 * units * 64) * 4
+    assert L.rodimus_chunk_scan_varlen_bwd_cut_workspace_bytes(8, 32768, 16, 64, 256, rodimus.BF16) == want
+    # too short, or a shape of the token-by-token kernels: the uncut call's size
+    for args in ((3, 500, 2, 64, 128, rodimus.BF16), (3, 5000, 2, 16, 32, rodimus.F32)):
+        assert L.rodimus_chunk_scan_varlen_bwd_cut_workspace_bytes(*args) == L.rodimus_chunk_scan_varlen_bwd_workspace_bytes(*args)
 
 
 def test_packed_gated_block_validation(L):
