@@ -792,8 +792,8 @@ __device__ __forceinline__ void state_chunk(const unsigned char *buf, const unsi
 // (summary pass), then the state entering segment s (segment_state_scan_kernel), which the main pass reads.
 //
 // Packed batch cut on the device (`packed_cut`): the host knows only the total token count, so it fixes the segment length
-// and an upper bound on the number of segments; sequence b owns max(1, ceil(len_b / seg_tokens)) consecutive slots, counted
-// from the sequences before it.  Slots are [slot][H][64][dv], decays [slot][H][64]; `nseg` is then the slot bound.
+// and an upper bound on the number of segments; every sequence owns consecutive slots, counted from the sequences before it
+// (locate_packed_slot).  Slots are [slot][H][64][dv], decays [slot][H][64]; `nseg` is then the slot bound.
 struct SegmentPlan {
     int nseg;              // 1: no split, no workspace
     int seg_tokens;        // tokens per segment, a multiple of 64
@@ -809,8 +809,6 @@ __device__ __forceinline__ void packed_rows(const int *__restrict__ cu_seqlens, 
     first = min(max(cu_seqlens[b], 0), total_tokens);
     last = min(max(cu_seqlens[b + 1], first), total_tokens);
 }
-
-__device__ __forceinline__ int packed_segments(int len, int seg_tokens) { return max(1, (len + seg_tokens - 1) / seg_tokens); }
 
 // Flat grids over (pair, column tile), a pair being a (sequence or slot, head): workgroups go round-robin over the eight
 // XCDs (each with its own L2), so in every run of 8 * col_tiles workgroups the column tiles of a pair are 8 apart: on the
@@ -854,24 +852,17 @@ __global__ __launch_bounds__(kThreads) void scan_mfma_kernel(
         xcd_pair_mapping(blockIdx.x, dv / kColTile, rest, col_tile);
         if (rest >= plan.nseg * H) return;                   // the grid is rounded up to whole runs of eight pairs
         const int slot = rest / H;
-        int b = -1, before = 0, first = 0, last = 0, count = 0;
-        for (int i = 0; i < total_seqs; ++i) {
-            packed_rows(cu_seqlens, i, total_tokens, first, last);
-            count = packed_segments(last - first, plan.seg_tokens);
-            if (slot < before + count) { b = i; break; }
-            before += count;
-        }
-        if (b < 0) return;                                   // the grid covers the largest possible number of slots
-        const int j = slot - before;                         // segment j of `count` of sequence b
-        last_seg = j == count - 1;
+        PackedSlot ps;
+        if (!locate_packed_slot(cu_seqlens, total_seqs, total_tokens, plan.seg_tokens, slot, ps)) return;      // the grid covers the largest possible number of slots
+        last_seg = ps.j == ps.count - 1;
         // nothing continues from a sequence's last segment; with a valid table the segments fit the slots, a corrupt one
         // (overlapping sequences) must not reach past them
         if (kSummary && (last_seg || slot + 1 >= plan.nseg)) return;
-        bh = __builtin_amdgcn_readfirstlane(b * H + rest % H);
+        bh = __builtin_amdgcn_readfirstlane(ps.b * H + rest % H);
         seg = slot; BH = H; slot_bh = rest % H;
-        t_begin = j * plan.seg_tokens;
-        tok0 = first;
-        T = last - first;
+        t_begin = ps.j * plan.seg_tokens;
+        tok0 = ps.first;
+        T = ps.len;
     } else if (!kSummary && cu_seqlens == nullptr && gridDim.y == 1 && gridDim.z == 1 && dv > kColTile) {
         // Dense batch with more workgroups than compute units, launched flat: workgroups go round-robin over the eight XCDs
         // (each with its own L2), so in every run of 8 * col_tiles workgroups the column tiles of a (batch, head) are 8
@@ -1080,12 +1071,9 @@ __global__ __launch_bounds__(256) void segment_state_scan_kernel(const float *S0
         const int b = (int)(e4 / quads_per_slot);
         if (b >= total_seqs) return;
         elem = (e4 % quads_per_slot) * 4;
-        for (int i = 0; i <= b; ++i) {
-            int first, last;
-            packed_rows(cu_seqlens, i, total_tokens, first, last);
-            count = packed_segments(last - first, plan.seg_tokens);
-            if (i < b) first_slot += count;
-        }
+        int first;
+        packed_sequence_slots(cu_seqlens, b, total_tokens, plan.seg_tokens, first, count);
+        first_slot = (size_t)first;
         if (first_slot >= (size_t)plan.nseg) return;         // only with a corrupt table: stay inside the slots
         count = min(count, plan.nseg - (int)first_slot);
         S0 = (S0 != nullptr) ? S0 + (size_t)b * slot_elems : nullptr;
