@@ -106,3 +106,42 @@ def test_captured_backward_pass_replays_like_the_eager_call():
         for name, ref in eager.items():
             assert torch.equal(out[name], ref), (replay, name)
         assert torch.equal(o, o_eager) and torch.equal(S_T, S_eager), replay
+
+
+def test_captured_packed_whole_block_with_the_device_side_cut_replays_like_the_eager_call():
+    """A serving prefill in one graph: the whole block over a packed batch, the sequences cut into segments by the kernels
+    (summary pass, chain, main pass), the state cache updated in place."""
+    lengths, H, dv = [1800, 300, 0, 2100], 2, 256
+    total, N = sum(lengths), len(lengths)
+    d = wl.make_gated_scan_inputs(1, total, H, 64, dv, "bf16", s0_std=0.0, seed=5)
+    g = {k: (None if v is None else v[0].cuda()) for k, v in d.items()}
+    gen = torch.Generator(device="cpu").manual_seed(9)
+    x_prime = torch.randn((total, H, dv), generator=gen).to(torch.bfloat16).cuda()
+    z_gate = torch.randn((total, H, dv), generator=gen).to(torch.bfloat16).cuda()
+    d_w = torch.randn((H, dv), generator=gen).cuda()
+    cache0 = (0.1 * torch.randn((N, H, 64, dv), generator=gen)).cuda()
+    cu = torch.tensor([0, 1800, 2100, 2100, 4200], dtype=torch.int32, device="cuda")
+    need = rodimus.rodimus_chunk_scan_varlen_workspace_bytes(N, total, H, 64, dv, 64, torch.bfloat16)
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+
+    def run(cache, y):
+        rodimus.rodimus_chunk_scan_varlen_fwd_gated_block(g["q"], g["k"], g["v"], g["z_g"], g["z_tau"], cu, g["z_beta"], cache,
+                                                          x_prime=x_prime, d=d_w, z_gate=z_gate, gate_act="silu", o=y, S_T=cache,
+                                                          workspace=ws)
+
+    cache_eager, y_eager = cache0.clone(), torch.empty((total, H, dv), dtype=torch.bfloat16, device="cuda")
+    run(cache_eager, y_eager)
+    torch.cuda.synchronize()
+    cache, y = cache0.clone(), torch.empty_like(y_eager)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run(cache, y)
+    for replay in range(3):
+        cache.copy_(cache0)
+        y.fill_(0)
+        ws.fill_(0x5A)                         # stale workspace contents must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_eager) and torch.equal(cache, cache_eager), replay
