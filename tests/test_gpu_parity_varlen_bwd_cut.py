@@ -103,3 +103,27 @@ def test_corrupt_length_table_stays_inside_the_tensors_and_the_workspace():
                                                   workspace=ws[:need])
         torch.cuda.synchronize()
         assert torch.all(ws[need:] == 0x5A), table
+
+
+def test_few_long_sequences_full_size():
+    """The workload bench.py times as scan_backward_few_long_sequences: eight sequences with a log-uniform length mix, 32768
+    tokens in all, at the layer's head shape; every sequence against the backward oracle."""
+    lengths, H, dv = wl.serving_length_mix(8, 32768), 16, 256
+    print(f"varlen bwd cut full size: {lengths}", flush=True)
+    d = wl.make_varlen_inputs(lengths, H, 64, dv, "bf16", seed=14)
+    d_o, dS_T = _cotangents(lengths, H, dv, 81)
+    g = to_dev(d)
+    out = rodimus.rodimus_chunk_scan_varlen_bwd_cut(g["q"], g["k"], g["v"], g["log_alpha"], g["cu_seqlens"], g["beta"], g["S0"],
+                                                    d_o.cuda(), dS_T.cuda())
+    torch.cuda.synchronize()
+    host = {name: out[name].float().cpu() for name in NAMES}
+    start = 0
+    for b, n in enumerate(lengths):
+        sl = slice(start, start + n)
+        ref = oracle.scan_bwd(d["q"][sl][None], d["k"][sl][None], d["v"][sl][None], d["log_alpha"][sl][None],
+                              d["beta"][sl][None], d["S0"][b][None], d_o[sl][None], dS_T[b][None])
+        errs = {name: rel_err(host[name][sl][None], ref[name]) for name in NAMES}
+        errs["dS0"] = rel_err(out["dS0"][b][None], ref["dS0"])
+        print(f"   sequence {b} ({n} tokens): " + "  ".join(f"{k} {v:.2e}" for k, v in errs.items()), flush=True)
+        assert max(errs.values()) <= TOL_BF16, (b, n, errs)
+        start += n
