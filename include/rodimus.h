@@ -407,6 +407,28 @@ int rodimus_chunk_scan_bwd_gated(const void *q, const void *k, const void *v,
 size_t rodimus_chunk_scan_bwd_gated_workspace_bytes(int B, int T, int H, int dk, int dv, int io_dtype);
 
 /*
+ * rodimus_chunk_scan_bwd_gated over a PACKED batch of N sequences of different lengths (training on packed batches straight
+ * from the projections; the backward of rodimus_chunk_scan_varlen_fwd_gated_block without its output stage): the same
+ * chain rule and the same three steps, with the layouts and the length table of rodimus_chunk_scan_varlen_bwd:
+ *
+ *   token tensors [total_tokens,H,.], S0, dS_T, dS0 [N,H,dk,dv], cu_seqlens [N+1] int32 in DEVICE memory (clamped by the
+ *   kernels); cut != 0: the scan backward in the middle lets the kernels cut the sequences into segments, as
+ *   rodimus_chunk_scan_varlen_bwd_cut (for batches dominated by few long sequences);
+ *   workspace: rodimus_chunk_scan_varlen_bwd_gated_workspace_bytes(..., cut) bytes.
+ *
+ * Shapes, alignment, aliasing rules and status codes as for rodimus_chunk_scan_bwd_gated.
+ */
+int rodimus_chunk_scan_varlen_bwd_gated(const void *q, const void *k, const void *v,
+                                        const void *z_g, const void *z_tau, const void *z_beta,
+                                        const float *S0, const void *d_o, const float *dS_T,
+                                        void *dq, void *dk, void *dv_out, void *dz_g, void *dz_tau, void *dz_beta, float *dS0,
+                                        const int *cu_seqlens, int N, int total_tokens,
+                                        int H, int dk_width, int dv, int io_dtype, int cut,
+                                        void *workspace, size_t workspace_bytes, void *stream);
+
+size_t rodimus_chunk_scan_varlen_bwd_gated_workspace_bytes(int N, int total_tokens, int H, int dk, int dv, int io_dtype, int cut);
+
+/*
  * Backward pass over a packed batch of sequences of different lengths (training on packed sequences; the backward of
  * rodimus_chunk_scan_varlen_fwd with the value gate given as values): exactly rodimus_chunk_scan_bwd applied to every
  * sequence, with the layouts of rodimus_chunk_scan_varlen_fwd:

@@ -440,38 +440,43 @@ int rodimus_chunk_scan_bwd_zbeta(const void *q, const void *k, const void *v, co
 // folded k pass through the caller's dq and dk buffers, which the last kernel updates in place.
 static size_t gated_bwd_front_bytes(size_t tokens, int dk, int io_dtype) { return tokens * dk * (4 + 2 * elem_bytes(io_dtype) + 4); }
 
-size_t rodimus_chunk_scan_bwd_gated_workspace_bytes(int B, int T, int H, int dk, int dv, int io_dtype)
+// workspace of the scan backward inside the gated backward: dense, packed, or packed and cut by the kernels
+static size_t gated_bwd_inner_bytes(int B, int T, int H, int dk, int dv, int io_dtype, bool packed, bool packed_cut)
 {
-    if (B < 0 || T < 0 || H < 0 || !scan_bwd_supports(dk, dv, io_dtype)) return 0;
-    return gated_bwd_front_bytes((size_t)B * T * H, dk, io_dtype) + bwd_workspace((size_t)B * T, B, T, H, dk, dv, io_dtype, false);
+    if (!packed) return bwd_workspace((size_t)B * T, B, T, H, dk, dv, io_dtype, false);
+    const size_t cut = packed_cut ? scan_bwd_packed_cut_workspace_bytes(B, T, H, dv) : 0;
+    return cut > 0 ? cut : bwd_workspace((size_t)T, B, T, H, dk, dv, io_dtype, true);
 }
 
-int rodimus_chunk_scan_bwd_gated(const void *q, const void *k, const void *v, const void *z_g, const void *z_tau, const void *z_beta,
-                                 const float *S0, const void *d_o, const float *dS_T, void *dq, void *dk, void *dv_out, void *dz_g,
-                                 void *dz_tau, void *dz_beta, float *dS0, int B, int T, int H, int dk_width, int dv, int io_dtype,
-                                 void *workspace, size_t workspace_bytes, void *stream)
+// Dense: B sequences of T tokens.  Packed: B sequences, T tokens in all, lengths in cu_seqlens (device).
+static int bwd_gated_entry(const void *q, const void *k, const void *v, const void *z_g, const void *z_tau, const void *z_beta,
+                           const float *S0, const void *d_o, const float *dS_T, void *dq, void *dk, void *dv_out, void *dz_g,
+                           void *dz_tau, void *dz_beta, float *dS0, int B, int T, int H, int dk_width, int dv, int io_dtype,
+                           void *workspace, size_t workspace_bytes, void *stream, bool packed, const int *cu_seqlens, bool packed_cut)
 {
     if (io_dtype != RODIMUS_F32 && io_dtype != RODIMUS_BF16) return RODIMUS_ERR_DTYPE;
     if (B < 0 || T < 0 || H < 0 || (long long)B * H > kMaxGridX || (long long)T * H > kMaxGridX) return RODIMUS_ERR_SHAPE;
     if (!scan_bwd_supports(dk_width, dv, io_dtype)) return RODIMUS_ERR_SHAPE;       // matrix-core shapes only
-    const size_t tokens = (size_t)B * T * H;
+    const size_t tokens = packed ? (size_t)T * H : (size_t)B * T * H;
     if (tokens == 0) return bwd_entry(q, k, v, nullptr, z_beta, S0, d_o, dS_T, dq, dk, dv_out, nullptr, dz_beta, dS0, B, T, H, dk_width,
-                                      dv, io_dtype, workspace, workspace_bytes, stream, false, nullptr, z_beta != nullptr);
+                                      dv, io_dtype, workspace, workspace_bytes, stream, packed, cu_seqlens, z_beta != nullptr);
     if (!q || !k || !v || !z_g || !z_tau || !d_o || !dq || !dk || !dv_out || !dz_g || !dz_tau) return RODIMUS_ERR_NULL;
     if (z_beta == nullptr && dz_beta != nullptr) return RODIMUS_ERR_NULL;
     if (misaligned(z_g) || misaligned(z_tau) || misaligned(dz_g) || misaligned(dz_tau) || misaligned(workspace)) return RODIMUS_ERR_ALIGN;
     const size_t eb = elem_bytes(io_dtype), key_bytes = tokens * dk_width * eb;
     const size_t front = gated_bwd_front_bytes(tokens, dk_width, io_dtype);
-    const size_t need = front + bwd_workspace((size_t)B * T, B, T, H, dk_width, dv, io_dtype, false);
+    const size_t need = front + gated_bwd_inner_bytes(B, T, H, dk_width, dv, io_dtype, packed, packed_cut);
     if (workspace == nullptr || workspace_bytes < need) return RODIMUS_ERR_WORKSPACE;
     // the two extra inputs and outputs against everything else (the call below checks the rest, workspace included)
-    const void *others[16] = {q, k, v, z_beta, S0, d_o, dS_T, dq, dk, dv_out, dz_beta, dS0, workspace, z_g, z_tau, nullptr};
+    const void *others[16] = {q, k, v, z_beta, S0, d_o, dS_T, dq, dk, dv_out, dz_beta, dS0, workspace, z_g, z_tau,
+                              packed ? cu_seqlens : nullptr};
     const size_t state_bytes = (size_t)B * H * dk_width * dv * 4, val_bytes = tokens * dv * eb;
     const size_t other_bytes[16] = {key_bytes, key_bytes, val_bytes, val_bytes, state_bytes, val_bytes, state_bytes, key_bytes, key_bytes,
-                                    val_bytes, val_bytes, state_bytes, need, key_bytes, key_bytes, 0};
+                                    val_bytes, val_bytes, state_bytes, need, key_bytes, key_bytes,
+                                    packed ? ((size_t)B + 1) * sizeof(int) : 0};
     void *extra_out[2] = {dz_g, dz_tau};
     for (int o = 0; o < 2; ++o)
-        for (int i = 0; i < 15; ++i)
+        for (int i = 0; i < 16; ++i)
             if (overlaps(extra_out[o], key_bytes, others[i], other_bytes[i])) return RODIMUS_ERR_ALIAS;
     if (overlaps(dz_g, key_bytes, dz_tau, key_bytes)) return RODIMUS_ERR_ALIAS;
     const void *extra_in[2] = {z_g, z_tau};
@@ -492,11 +497,45 @@ int rodimus_chunk_scan_bwd_gated(const void *q, const void *k, const void *v, co
                 static_cast<hipStream_t>(stream)};
     if (launch_ddts_gates(ga) != hipSuccess) return RODIMUS_ERR_LAUNCH;
     const int inner = bwd_entry(q_hat, k_hat, v, log_alpha, z_beta, S0, d_o, dS_T, dq, dk, dv_out, dlog_alpha, dz_beta, dS0, B, T, H,
-                                dk_width, dv, io_dtype, inner_ws, workspace_bytes - front, stream, false, nullptr, z_beta != nullptr);
+                                dk_width, dv, io_dtype, inner_ws, workspace_bytes - front, stream, packed, cu_seqlens, z_beta != nullptr,
+                                packed_cut);
     if (inner != RODIMUS_OK) return inner;
     GateBwdArgs gb{z_g, z_tau, k, dq, dk, dlog_alpha, dz_g, dz_tau, dq, dk, (long long)tokens, dk_width, io_dtype,
                    static_cast<hipStream_t>(stream)};
     return launch_ddts_gates_bwd(gb) == hipSuccess ? RODIMUS_OK : RODIMUS_ERR_LAUNCH;
+}
+
+size_t rodimus_chunk_scan_bwd_gated_workspace_bytes(int B, int T, int H, int dk, int dv, int io_dtype)
+{
+    if (B < 0 || T < 0 || H < 0 || !scan_bwd_supports(dk, dv, io_dtype)) return 0;
+    return gated_bwd_front_bytes((size_t)B * T * H, dk, io_dtype) + gated_bwd_inner_bytes(B, T, H, dk, dv, io_dtype, false, false);
+}
+
+int rodimus_chunk_scan_bwd_gated(const void *q, const void *k, const void *v, const void *z_g, const void *z_tau, const void *z_beta,
+                                 const float *S0, const void *d_o, const float *dS_T, void *dq, void *dk, void *dv_out, void *dz_g,
+                                 void *dz_tau, void *dz_beta, float *dS0, int B, int T, int H, int dk_width, int dv, int io_dtype,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    return bwd_gated_entry(q, k, v, z_g, z_tau, z_beta, S0, d_o, dS_T, dq, dk, dv_out, dz_g, dz_tau, dz_beta, dS0, B, T, H, dk_width, dv,
+                           io_dtype, workspace, workspace_bytes, stream, false, nullptr, false);
+}
+
+size_t rodimus_chunk_scan_varlen_bwd_gated_workspace_bytes(int N, int total_tokens, int H, int dk, int dv, int io_dtype, int cut)
+{
+    if (N < 0 || total_tokens < 0 || H < 0 || !scan_bwd_supports(dk, dv, io_dtype)) return 0;
+    return gated_bwd_front_bytes((size_t)total_tokens * H, dk, io_dtype) +
+           gated_bwd_inner_bytes(N, total_tokens, H, dk, dv, io_dtype, true, cut != 0);
+}
+
+int rodimus_chunk_scan_varlen_bwd_gated(const void *q, const void *k, const void *v, const void *z_g, const void *z_tau,
+                                        const void *z_beta, const float *S0, const void *d_o, const float *dS_T, void *dq, void *dk,
+                                        void *dv_out, void *dz_g, void *dz_tau, void *dz_beta, float *dS0, const int *cu_seqlens, int N,
+                                        int total_tokens, int H, int dk_width, int dv, int io_dtype, int cut, void *workspace,
+                                        size_t workspace_bytes, void *stream)
+{
+    if (N > 0 && cu_seqlens == nullptr) return RODIMUS_ERR_NULL;
+    return bwd_gated_entry(q, k, v, z_g, z_tau, z_beta, S0, d_o, dS_T, dq, dk, dv_out, dz_g, dz_tau, dz_beta, dS0, N, total_tokens, H,
+                           dk_width, dv, io_dtype, workspace, workspace_bytes, stream, true, cu_seqlens, cut != 0);
 }
 
 int rodimus_chunk_scan_varlen_bwd(const void *q, const void *k, const void *v, const float *log_alpha, const float *beta,

@@ -73,6 +73,10 @@ def lib() -> ctypes.CDLL:
         L.rodimus_chunk_scan_bwd_gated.restype = i
         L.rodimus_chunk_scan_bwd_gated_workspace_bytes.argtypes = [i] * 6
         L.rodimus_chunk_scan_bwd_gated_workspace_bytes.restype = sz
+        L.rodimus_chunk_scan_varlen_bwd_gated.argtypes = [vp] * 17 + [i] * 7 + [vp, sz, vp]
+        L.rodimus_chunk_scan_varlen_bwd_gated.restype = i
+        L.rodimus_chunk_scan_varlen_bwd_gated_workspace_bytes.argtypes = [i] * 7
+        L.rodimus_chunk_scan_varlen_bwd_gated_workspace_bytes.restype = sz
         L.rodimus_chunk_scan_bwd_workspace_bytes.argtypes = [i] * 6
         L.rodimus_chunk_scan_bwd_workspace_bytes.restype = sz
         L.rodimus_chunk_scan_varlen_bwd.argtypes = [vp] * 15 + [i] * 6 + [vp, sz, vp]
@@ -245,6 +249,41 @@ def rodimus_chunk_scan_bwd_gated(q, k, v, z_g, z_tau, z_beta, S0, d_o, dS_T=None
                                                   _ptr(dS_T), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]), _ptr(out["dz_g"]),
                                                   _ptr(out["dz_tau"]), _ptr(out["dz_beta"]), _ptr(out["dS0"]), B, T, H, dk, dv,
                                                   _DTYPES[io], _ptr(workspace), ws_bytes, _stream(dev)))
+    return out
+
+
+def rodimus_chunk_scan_varlen_bwd_gated(q, k, v, z_g, z_tau, z_beta, cu_seqlens, S0, d_o, dS_T=None, *, cut=False, want_dS0=True,
+                                        workspace=None):
+    """``rodimus_chunk_scan_bwd_gated`` over a packed variable-length batch (token tensors [total,H,.], states [N,H,dk,dv],
+    cu_seqlens [N+1] int32 on the device); ``cut``: the kernels cut long sequences into segments that run side by side."""
+    if q.dtype not in _DTYPES:
+        raise ValueError(f"q: unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("rodimus_chunk_scan_varlen_bwd_gated needs device tensors (no CPU path exists)")
+    total, H, dk = q.shape
+    dv = v.shape[-1]
+    dev, io = q.device, q.dtype
+    N = cu_seqlens.numel() - 1
+    _require(cu_seqlens, "cu_seqlens", (N + 1,), torch.int32, dev)
+    for name, t in (("k", k), ("z_g", z_g), ("z_tau", z_tau)):
+        _require(t, name, (total, H, dk), io, dev)
+    for name, t in (("v", v), ("z_beta", z_beta), ("d_o", d_o)):
+        _require(t, name, (total, H, dv), io, dev)
+    _require(S0, "S0", (N, H, dk, dv), torch.float32, dev)
+    _require(dS_T, "dS_T", (N, H, dk, dv), torch.float32, dev)
+    out = {"dq": torch.empty_like(q), "dk": torch.empty_like(k), "dv": torch.empty_like(v), "dz_g": torch.empty_like(q),
+           "dz_tau": torch.empty_like(q), "dz_beta": torch.empty_like(v) if z_beta is not None else None,
+           "dS0": torch.empty((N, H, dk, dv), dtype=torch.float32, device=dev) if want_dS0 else None}
+    need = int(lib().rodimus_chunk_scan_varlen_bwd_gated_workspace_bytes(N, total, H, dk, dv, _DTYPES[io], int(bool(cut))))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        _check(lib().rodimus_chunk_scan_varlen_bwd_gated(_ptr(q), _ptr(k), _ptr(v), _ptr(z_g), _ptr(z_tau), _ptr(z_beta), _ptr(S0),
+                                                         _ptr(d_o), _ptr(dS_T), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]),
+                                                         _ptr(out["dz_g"]), _ptr(out["dz_tau"]), _ptr(out["dz_beta"]), _ptr(out["dS0"]),
+                                                         _ptr(cu_seqlens), N, total, H, dk, dv, _DTYPES[io], int(bool(cut)),
+                                                         _ptr(workspace), ws_bytes, _stream(dev)))
     return out
 
 

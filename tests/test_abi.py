@@ -38,7 +38,8 @@ def test_every_declared_symbol_is_exported(L):
             "rodimus_chunk_scan_fwd_gated_block", "rodimus_decode_step_gated_block",
             "rodimus_chunk_scan_varlen_fwd_cut", "rodimus_chunk_scan_varlen_workspace_bytes",
             "rodimus_hbm_stream_probe", "rodimus_chunk_scan_varlen_fwd_gated_block",
-            "rodimus_chunk_scan_varlen_bwd_cut", "rodimus_chunk_scan_varlen_bwd_cut_workspace_bytes"} <= declared
+            "rodimus_chunk_scan_varlen_bwd_cut", "rodimus_chunk_scan_varlen_bwd_cut_workspace_bytes",
+            "rodimus_chunk_scan_varlen_bwd_gated", "rodimus_chunk_scan_varlen_bwd_gated_workspace_bytes"} <= declared
     for name in declared:
         assert hasattr(L, name), name
 
@@ -335,6 +336,33 @@ def test_packed_backward_cut_workspace(L):
     # too short, or a shape of the token-by-token kernels: the uncut call's size
     for args in ((3, 500, 2, 64, 128, rodimus.BF16), (3, 5000, 2, 16, 32, rodimus.F32)):
         assert L.rodimus_chunk_scan_varlen_bwd_cut_workspace_bytes(*args) == L.rodimus_chunk_scan_varlen_bwd_workspace_bytes(*args)
+
+
+def test_packed_gated_backward_workspace_and_validation(L):
+    size = L.rodimus_chunk_scan_varlen_bwd_gated_workspace_bytes
+    size.restype = ctypes.c_size_t
+    L.rodimus_chunk_scan_varlen_bwd_workspace_bytes.restype = ctypes.c_size_t
+    L.rodimus_chunk_scan_varlen_bwd_cut_workspace_bytes.restype = ctypes.c_size_t
+    N, total, H, dv = 3, 5000, 2, 128
+    front = total * H * 64 * (4 + 2 * 2 + 4)         # log_alpha fp32, prepared q and k bf16, dlog_alpha fp32
+    assert size(N, total, H, 64, dv, rodimus.BF16, 0) == front + L.rodimus_chunk_scan_varlen_bwd_workspace_bytes(N, total, H, 64, dv, rodimus.BF16)
+    assert size(N, total, H, 64, dv, rodimus.BF16, 1) == front + L.rodimus_chunk_scan_varlen_bwd_cut_workspace_bytes(N, total, H, 64, dv, rodimus.BF16)
+    assert size(N, total, H, 16, 32, rodimus.F32, 0) == 0          # matrix-core shapes only
+    p = lambda x: None if x is None else ctypes.c_void_p(x)
+    G = 0x10000000
+
+    def call(ws_bytes=1 << 30, cu=18 * G, **kw):
+        a = dict(q=G, k=2 * G, v=3 * G, zg=4 * G, zt=5 * G, zb=6 * G, S0=7 * G, do=8 * G, dS=9 * G, dq=10 * G, dk=11 * G, dv=12 * G,
+                 dzg=13 * G, dzt=14 * G, dzb=15 * G, dS0=16 * G, ws=17 * G)
+        a.update(kw)
+        return L.rodimus_chunk_scan_varlen_bwd_gated(*(p(a[n]) for n in ("q", "k", "v", "zg", "zt", "zb", "S0", "do", "dS", "dq", "dk", "dv",
+                                                                          "dzg", "dzt", "dzb", "dS0")), p(cu), N, total, H, 64, dv, rodimus.BF16,
+                                                     1, p(a["ws"]), ctypes.c_size_t(ws_bytes), None)
+
+    assert call(cu=None) == E_NULL and call(zt=None) == E_NULL and call(dzg=None) == E_NULL
+    assert call(ws_bytes=1000) == E_WS and call(ws=None) == E_WS
+    assert call(dzg=4 * G) == E_ALIAS and call(dzt=13 * G) == E_ALIAS and call(dzg=18 * G) == E_ALIAS       # over z_g, over dz_g, over cu_seqlens
+    assert call(zg=4 * G + 8) == E_ALIGN
 
 
 def test_packed_gated_block_validation(L):
