@@ -26,6 +26,8 @@ def _cotangents(lengths, H, dv, seed):
     ([512, 256, 257], 1, 128),           # lengths on and one past a segment boundary
     ([2100], 3, 128),                    # one sequence
     ([1, 1, 900, 1], 2, 128),
+    ([500, 12], 1, 128),                 # exactly the smallest batch that is cut (512 tokens): two segments of 256
+    ([255, 1, 256, 257], 2, 256),        # lengths around a segment
 ])
 def test_cut_matches_the_oracle_per_sequence(lengths, H, dv):
     print(f"varlen bwd cut {lengths} H{H} dv{dv}", flush=True)

@@ -25,6 +25,8 @@ def _run_cut(inp, gate, **kw):
     ([1024, 512, 513], 1, 128, "z_beta", True),       # lengths on and one past a segment boundary
     ([5000], 3, 128, "none", False),                  # one sequence, zero initial state, no value gate
     ([1, 1, 3000, 1], 2, 128, "beta", True),
+    ([1000, 24], 1, 128, "beta", True),               # exactly the smallest batch that is cut (1024 tokens): two segments of 512
+    ([511, 1, 512], 2, 256, "z_beta", True),          # a sequence one token short of a segment, one of exactly a segment
 ])
 def test_cut_matches_the_oracle_per_sequence(lengths, H, dv, gate, s0):
     print(f"varlen cut {lengths} H{H} dv{dv} {gate}", flush=True)
