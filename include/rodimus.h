@@ -261,8 +261,8 @@ int rodimus_chunk_scan_varlen_fwd(const void *q, const void *k, const void *v,
  *   workspace   rodimus_chunk_scan_varlen_workspace_bytes(...) bytes of device memory, 16-byte aligned, contents
  *               undefined before and after; must not overlap any other argument.  The size depends on N and
  *               total_tokens only (the largest number of segments the batch can have); 0 = this batch is not cut
- *               (under 1024 tokens in all, or a shape the matrix-core kernels do not take) and the call is then
- *               exactly rodimus_chunk_scan_varlen_fwd; workspace may be NULL.
+ *               (under 1024 tokens in all, more than 256 sequences, or a shape the matrix-core kernels do not take)
+ *               and the call is then exactly rodimus_chunk_scan_varlen_fwd; workspace may be NULL.
  *
  * Every other argument, layout, aliasing rule and status code as for rodimus_chunk_scan_varlen_fwd (S_T may be S0);
  * RODIMUS_ERR_WORKSPACE if the workspace is missing or too small, RODIMUS_ERR_ALIAS if it overlaps another argument.
@@ -461,8 +461,8 @@ size_t rodimus_chunk_scan_varlen_bwd_workspace_bytes(int N, int total_tokens, in
  * of the chip waiting (as a rule: longer than about three segments).
  *
  *   workspace   rodimus_chunk_scan_varlen_bwd_cut_workspace_bytes(...) bytes; the size depends on N and total_tokens only.
- *               Batches under 512 tokens and shapes outside the matrix-core kernels (bf16, dk = 64, dv = 128 or 256) are
- *               not cut: the call is then exactly rodimus_chunk_scan_varlen_bwd and the size function returns that
+ *               Batches under 512 tokens or of more than 256 sequences and shapes outside the matrix-core kernels (bf16,
+ *               dk = 64, dv = 128 or 256) are not cut: the call is then exactly rodimus_chunk_scan_varlen_bwd and the size function returns that
  *               call's size.
  *
  * Every other argument, layout, aliasing rule and status code as for rodimus_chunk_scan_varlen_bwd.

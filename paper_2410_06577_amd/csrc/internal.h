@@ -276,6 +276,7 @@ __device__ __forceinline__ int sequence_by_length_rank(const int *cu_seqlens, in
 // tokens, sequence b owns max(1, ceil(len_b / seg_tokens)) consecutive slots, counted from the sequences before it.  Finds
 // the sequence and segment of `slot` by walking the length table (every entry clamped to the tensor); false if the slot lies
 // past the batch's last segment.  The same in every lane.
+constexpr int kMaxCutSequences = 256;      // larger packed batches are not cut (they hold enough sequences to fill the chip)
 struct PackedSlot {
     int b, j, count;      // sequence, segment of the sequence, segments of the sequence
     int first, len;       // first row and length of the sequence

@@ -1080,7 +1080,8 @@ static BwdSplit choose_bwd_split(int B, int T, int H, bool packed)
 static BwdSplit choose_bwd_packed_cut(int N, int total_tokens, int H)
 {
     const BwdSplit whole{1, ((total_tokens + 63) / 64) * 64};
-    if (N <= 0 || H <= 0 || total_tokens < 512) return whole;
+    // every workgroup finds its slot by walking the length table: kept to batches where that walk is short
+    if (N <= 0 || N > kMaxCutSequences || H <= 0 || total_tokens < 512) return whole;
     // (segments twice and half as long measured 1.32 and 1.28 ms against 1.29 ms on eight sequences of 32768 tokens in all,
     // 1.52 and 1.36 against 1.32 ms on another mix)
     long long seg = ((long long)total_tokens * H / 256 + 63) / 64 * 64;

@@ -1140,7 +1140,8 @@ SplitShape choose_packed_cut(int N, int total_tokens, int H, int dv)
 {
     const long long per_slot = (long long)H * (dv / kColTile);
     SplitShape none{1, ((total_tokens + kChunk - 1) / kChunk) * kChunk};
-    if (N <= 0 || per_slot == 0 || total_tokens < 16 * kChunk) return none;
+    // every workgroup finds its slot by walking the length table: kept to batches where that walk is short
+    if (N <= 0 || N > kMaxCutSequences || per_slot == 0 || total_tokens < 16 * kChunk) return none;
     long long seg = ((long long)total_tokens * per_slot / 256 + kChunk - 1) / kChunk * kChunk;
     if (seg < 8 * kChunk) seg = 8 * kChunk;
     const long long slots = total_tokens / seg + N;

@@ -311,6 +311,8 @@ def test_packed_cut_workspace_and_validation(L):
     # segments of 32768 * 16 * 2 / 256 = 4096 tokens: at most 8 + 8 slots of [16 heads][64][256] fp32 plus their decays
     assert need == 16 * 16 * 64 * (256 + 1) * 4
     assert L.rodimus_chunk_scan_varlen_workspace_bytes(3, 1023, 2, 64, 128, 64, rodimus.BF16) == 0       # too short to cut
+    assert L.rodimus_chunk_scan_varlen_workspace_bytes(256, 90000, 2, 64, 128, 64, rodimus.BF16) > 0
+    assert L.rodimus_chunk_scan_varlen_workspace_bytes(257, 90000, 2, 64, 128, 64, rodimus.BF16) == 0    # too many sequences: the slot walk
     assert L.rodimus_chunk_scan_varlen_workspace_bytes(3, 9000, 2, 16, 32, 16, rodimus.F32) == 0         # any-shape kernels
     assert L.rodimus_chunk_scan_varlen_workspace_bytes(3, 9000, 2, 64, 128, 64, rodimus.BF16) == (9000 // 512 + 3) * 2 * 64 * 129 * 4
     p = lambda x: None if x is None else ctypes.c_void_p(x)
